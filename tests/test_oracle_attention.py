@@ -1,0 +1,96 @@
+"""Pins for the oracle's attention: the textbook float64 softmax attention of a
+library, invariants (rows of the map sum to one, key order is irrelevant, one key
+returns its value) and the dense statement of the sparse-query layer."""
+import numpy as np
+import torch
+
+from paper_2211_02048_amd import inputs
+
+
+def test_attention_equals_library_float64(oracle):
+    g = torch.Generator().manual_seed(1)
+    Nq, T, heads, d = 7, 19, 3, 5
+    q = torch.randn(Nq, heads, d, dtype=torch.float64, generator=g)
+    k = torch.randn(T, heads, d, dtype=torch.float64, generator=g)
+    v = torch.randn(T, heads, d, dtype=torch.float64, generator=g)
+    scale = 0.37
+    s = torch.einsum("qhd,thd->hqt", q, k) * scale
+    want = torch.einsum("hqt,thd->qhd", torch.softmax(s, dim=-1), v).numpy()
+    got = oracle.attention(q.numpy(), k.numpy(), v.numpy(), scale)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+
+
+def test_attention_invariants(oracle):
+    rng = np.random.default_rng(2)
+    Nq, T, heads, d = 5, 33, 2, 8
+    q = rng.standard_normal((Nq, heads, d)) * 3
+    k = rng.standard_normal((T, heads, d)) * 3
+    v = rng.standard_normal((T, heads, d))
+    o = oracle.attention(q, k, v, 0.5)
+    # rows of the attention map sum to one: constant values pass through
+    ones = oracle.attention(q, k, np.ones_like(v), 0.5)
+    np.testing.assert_allclose(ones, 1.0, rtol=0, atol=1e-14)
+    # permuting the keys (with their values) changes nothing
+    perm = rng.permutation(T)
+    np.testing.assert_allclose(oracle.attention(q, k[perm], v[perm], 0.5), o, rtol=0, atol=1e-13)
+    # a single key returns its value row whatever the query
+    o1 = oracle.attention(q, k[:1], v[:1], 0.5)
+    assert np.array_equal(o1, np.broadcast_to(v[:1], o1.shape))
+    # heads are independent: changing head 1's keys leaves head 0 untouched
+    k2 = k.copy()
+    k2[:, 1] += 1.0
+    assert np.array_equal(oracle.attention(q, k2, v, 0.5)[:, 0], o[:, 0])
+    # large logits do not overflow (max subtraction)
+    big = oracle.attention(q * 1e3, k, v, 1.0)
+    assert np.isfinite(big).all()
+    # scale multiplies the logits: scale*q == q with scale folded in
+    np.testing.assert_allclose(oracle.attention(q * 0.5, k, v, 1.0), o, rtol=1e-12, atol=1e-13)
+
+
+def test_sige_attention_layer_all_active_is_full_attention(oracle):
+    """Fig. "sige-attention": with every token block active the layer is the vanilla
+    self-attention layer; with a subset, active tokens get the full-attention value
+    on the edited input and the rest keep the cached output."""
+    g = torch.Generator().manual_seed(4)
+    H, W, C, heads = 8, 8, 6, 2
+    d = C // heads
+    x = torch.randn(H, W, C, dtype=torch.float64, generator=g)
+    ws = [torch.randn(C, C, 1, 1, dtype=torch.float64, generator=g) * 0.4 for _ in range(4)]
+    bs = [torch.randn(C, dtype=torch.float64, generator=g) * 0.1 for _ in range(4)]
+    scale = d ** -0.5
+
+    def vanilla(xx):
+        t = xx.reshape(H * W, C)
+        q, k, v = [(t @ ws[i][:, :, 0, 0].T + bs[i]).reshape(H * W, heads, d) for i in range(3)]
+        s = torch.einsum("qhd,thd->hqt", q, k) * scale
+        a = torch.einsum("hqt,thd->qhd", torch.softmax(s, -1), v).reshape(H * W, C)
+        return (a @ ws[3][:, :, 0, 0].T + bs[3]).reshape(H, W, C).numpy()
+
+    npw = [w.numpy() for w in ws]
+    npb = [b.numpy() for b in bs]
+    all_blocks = np.array([(y, xx) for y in range(0, H, 4) for xx in range(0, W, 4)], np.int32)
+    cache = np.full((H, W, C), 123.0)
+    got = oracle.sige_attention_layer(x.numpy(), cache, all_blocks, 4, 4, *npw, *npb, heads, scale)
+    np.testing.assert_allclose(got, vanilla(x), rtol=1e-11, atol=1e-12)
+    # edit one block; K/V caches from the original input
+    x_e = x.clone()
+    x_e[4:8, 0:4] += torch.randn(4, 4, C, dtype=torch.float64, generator=g)
+    t = x.reshape(H * W, C)
+    k_cache = (t @ ws[1][:, :, 0, 0].T + bs[1]).reshape(H, W, C).numpy()
+    v_cache = (t @ ws[2][:, :, 0, 0].T + bs[2]).reshape(H, W, C).numpy()
+    out_cache = vanilla(x)
+    blocks = np.array([(4, 0)], np.int32)
+    got = oracle.sige_attention_layer(x_e.numpy(), out_cache, blocks, 4, 4, *npw, *npb, heads,
+                                      scale, k_cache, v_cache)
+    full = vanilla(x_e)
+    np.testing.assert_allclose(got[4:8, 0:4], full[4:8, 0:4], rtol=1e-11, atol=1e-12)
+    keep = np.ones((H, W), bool)
+    keep[4:8, 0:4] = False
+    assert np.array_equal(got[keep], out_cache[keep])
+    assert np.abs(full[keep] - out_cache[keep]).max() > 1e-6  # the accepted approximation is real
+
+
+def test_attention_case_generator_shapes():
+    c = inputs.attention_case(5, T=64, heads=2, d=40, n_q=16, dtype="bf16")
+    assert c["q"].shape == (16, 2, 40) and c["k"].shape == (64, 2, 40)
+    assert c["q"].dtype == torch.bfloat16
