@@ -1,0 +1,168 @@
+/*
+ * sige.h - C ABI of the MI355X (gfx950) library for spatially sparse inference:
+ * the cached-activation block-sparse convolution and the sparse-query attention
+ * of "Efficient Spatially Sparse Inference for Conditional GANs and Diffusion
+ * Models" (Sec. 3.1-3.2, Fig. "method", Fig. "pipeline" (b), Fig. "sige-attention").
+ *
+ * Conventions shared by every entry point
+ *  - Tensors are batch 1, NHWC: an activation is [H][W][C] with C fastest.  Where
+ *    a pixel stride `ld` (in elements, >= C) is given, the tensor may be a channel
+ *    slice of a wider buffer; C*size and ld*size must be multiples of 16 bytes
+ *    and base pointers 16-byte aligned unless a function says otherwise.
+ *  - ALL pointers are DEVICE pointers owned by the caller, except `sige_geom*`
+ *    (host) and where marked host.  The library allocates nothing, keeps no
+ *    state between calls and only enqueues work on the HIP stream passed as
+ *    `void* stream` (a hipStream_t; NULL = the default stream).  No call
+ *    synchronises.
+ *  - Return value: SIGE_OK or an error code; argument errors are detected on the
+ *    host before anything is enqueued.  sige_last_error() gives a thread-local
+ *    message for the last failing call.
+ *  - Block lists: int32 [max_blocks][2] = (y0, x0), the top-left OUTPUT pixel of an
+ *    active block, zero-based (App. A, Fig. "scatter-gather"), row-major ascending.
+ *    `count` is a device int32 holding the true number of active blocks; kernels
+ *    use min(*count, max_blocks).  A host `n_blocks >= 0` sizes the launch exactly
+ *    and replaces *count (count may then be NULL); n_blocks = -1 launches for
+ *    max_blocks and lets surplus workgroups exit on *count.
+ */
+#ifndef SIGE_H
+#define SIGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SIGE_OK = 0,
+    SIGE_ERR_INVALID_ARG = 1, /* NULL where required, non-positive size, inconsistent geometry */
+    SIGE_ERR_UNSUPPORTED = 2, /* a shape the kernels do not cover (never a silent fallback)     */
+    SIGE_ERR_CAPACITY = 3,    /* host n_blocks > max_blocks, or a size beyond a stated maximum  */
+    SIGE_ERR_HIP = 4          /* a HIP launch failed; message holds hipGetErrorString           */
+} sige_status;
+
+typedef enum { SIGE_F32 = 0, SIGE_F16 = 1, SIGE_BF16 = 2 } sige_dtype;
+typedef enum { SIGE_ACT_NONE = 0, SIGE_ACT_SILU = 1, SIGE_ACT_RELU = 2 } sige_act;
+
+/* Geometry of one wrapped convolution (host struct).  The output is cut into
+ * block_h x block_w blocks anchored at (0,0); edge blocks may be partial.  The
+ * input tile of a block is tile = (block-1)*stride + k pixels per side and starts
+ * at (y0*stride - pad, x0*stride - pad): for 3x3 / stride 1 neighbouring tiles
+ * overlap by 2 (Fig. "method").  Required: H_out == (H_in + 2*pad - k)/stride + 1. */
+typedef struct {
+    int32_t H_in, W_in;       /* spatial size the convolution reads               */
+    int32_t H_out, W_out;     /* spatial size it writes                           */
+    int32_t block_h, block_w; /* output block                                     */
+    int32_t k, stride, pad;   /* square kernel (odd), stride >= 1, zero padding   */
+} sige_geom;
+
+/* Sec. 3.1 "Structured sparsity" + Sec. 3.2 "Tiling-based sparse convolution":
+ * difference mask -> downsample -> dilate -> ordered list of active blocks.
+ *
+ * Mask source, exactly one of:
+ *   (a_orig, a_edit): two [Hm][Wm][C] tensors of dtype dt (contiguous, ld == C);
+ *       pixel marked iff for any channel !(|a_edit - a_orig| <= tau), evaluated in
+ *       fp32 (NaN counts as changed).  The mask is written to mask_out, which is
+ *       then REQUIRED (u8 [Hm][Wm]) and doubles as the hand-over between kernels.
+ *       Fast path needs C*size % 16 == 0; other C run a scalar kernel.
+ *   mask_in: a ready u8 [Hm][Wm] mask (non-zero = marked); mask_out is ignored.
+ * The mask is max-pooled by 2^pool_log2 per side (a chain of 2x2 / stride-2
+ * ceil-mode pools) and must then have size g->H_in x g->W_in; it is dilated by
+ * `dilate` pixels (square window, clipped).  A block is active iff its input tile,
+ * clipped to the image, contains a marked pixel of that mask.
+ * Outputs: indices [max_blocks][2] (rows beyond the count are left untouched; never
+ * more than max_blocks rows are written) and *count = the true number of active
+ * blocks, even when it exceeds max_blocks.  The block grid may hold at most
+ * 131072 blocks (SIGE_ERR_CAPACITY beyond).                                       */
+int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt,
+                     int32_t Hm, int32_t Wm, int32_t C, float tau,
+                     const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
+                     const sige_geom* g, uint8_t* mask_out,
+                     int32_t* indices, int32_t max_blocks, int32_t* count, void* stream);
+
+/* Fig. "method" Gather, with Sec. 3.2 "Pre-computing normalization parameters" and
+ * "Kernel fusion" folded in:
+ *   tiles[n][i][j][c] = act(scale[c] * x[y][x][c] + shift[c]),
+ *   (y, x) = (y0*stride - pad + i, x0*stride - pad + j), and literally 0 where (y, x)
+ *   lies outside g->H_in x g->W_in (padding applies to the activated tensor).
+ * x is [H_in >> up][W_in >> up] pixels of x_ld elements; up = 1 reads a nearest-
+ * neighbour x2 up-sampled view (source pixel = (y >> 1, x >> 1)), up = 0 reads x
+ * itself.  scale/shift: fp32 [C], both NULL = identity.  Arithmetic in fp32, one
+ * rounding to dt.  tiles: [max_blocks][tile_h][tile_w][C] contiguous; only the
+ * first min(count, max_blocks) tiles are written.                                 */
+int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
+                const sige_geom* g, const int32_t* indices, const int32_t* count,
+                int32_t max_blocks, int32_t n_blocks,
+                const float* scale, const float* shift, sige_act act,
+                void* tiles, void* stream);
+
+/* Fig. "method": the convolution F_l applied to the stacked tiles (valid, i.e. no
+ * padding inside a tile), with bias (Fig. "pipeline" (b)):
+ *   out[n][py][px][o] = bias[o] + sum_{ky,kx,c} W[o][c][ky][kx] *
+ *                       tiles[n][py*stride+ky][px*stride+kx][c].
+ * An implicit GEMM on the matrix cores with fp32 accumulation, one rounding to dt.
+ * packed_weight comes from sige_pack_weight for the same (dt, Cout, Cin, k); bias
+ * fp32 [Cout] or NULL.  Cin must be a multiple of 16 (f16/bf16) or 8 (f32).
+ * out_tiles: [max_blocks][block_h][block_w][Cout] contiguous.                     */
+int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+              const void* packed_weight, const float* bias,
+              const int32_t* count, int32_t max_blocks, int32_t n_blocks,
+              void* out_tiles, void* stream);
+
+/* Fig. "pipeline" (b) Scatter: y holds the cached F_l(A_orig) on entry and is updated
+ * in place; for every active block and every in-image pixel of it
+ *   y[y0+i][x0+j][o] = out_tiles[n][i][j][o] (+ residual_tiles[n][i][j][o])
+ *                                            (+ residual[y0+i][x0+j][o]);
+ * all other elements of y are left untouched.  Sums are taken in fp32 and rounded
+ * once.  residual_tiles ([max_blocks][block_h][block_w][Cout]) and residual (a full
+ * [H_out][W_out] tensor with pixel stride res_ld) may each be NULL.  Blocks are
+ * disjoint, so the stores never race.  y has pixel stride y_ld.                    */
+int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32_t Cout,
+                 const int32_t* indices, const int32_t* count, int32_t max_blocks, int32_t n_blocks,
+                 const void* residual_tiles, const void* residual, int32_t res_ld,
+                 void* y, int32_t y_ld, void* stream);
+
+/* Fig. "sige-attention" / Sec. 3.2 "Extension to attention layers": attention for the
+ * edited query tokens only, against all T keys and values (the caches with the
+ * edited tokens already overwritten):
+ *   o[i][h][:] = sum_t softmax_t(scale * q[i][h][:] . k[t][h][:]) * v[t][h][:].
+ * q, o: [Nq][heads][d] with row strides q_ld / o_ld elements; k, v: [T][heads][d]
+ * with row stride kv_ld (a row = one token, heads*d contiguous elements inside it).
+ * dt is f16 or bf16; d % 8 == 0, d <= 256; strides multiples of 8 elements.
+ * Streaming (online) softmax in fp32 on the matrix cores.  Nq is a host value;
+ * Nq == 0 enqueues nothing.
+ * workspace: optional device scratch for splitting the keys over several workgroups
+ * when Nq is small; sige_sparse_attn_workspace_bytes gives the size that allows it.
+ * NULL (or too small) runs without key splitting.                                 */
+int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, const void* v, int32_t kv_ld,
+                     sige_dtype dt, int32_t Nq, int32_t T, int32_t heads, int32_t d, float scale,
+                     void* o, int32_t o_ld, void* workspace, size_t workspace_bytes, void* stream);
+size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_t heads, int32_t d);
+
+/* ---- helpers beside the path --------------------------------------------------- */
+
+/* Re-lays an OIHW weight tensor (device, dtype dt, [Cout][Cin][k][k]) into the
+ * matrix-core fragment order sige_conv reads; done once per layer.                */
+size_t sige_packed_weight_bytes(sige_dtype dt, int32_t Cout, int32_t Cin, int32_t k);
+int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout, int32_t Cin, int32_t k,
+                     void* packed, void* stream);
+
+/* Sec. 3.2 "Pre-computing normalization parameters": group statistics of a full
+ * [H][W][C] tensor (pixel stride x_ld) from the pre-computation pass, folded into
+ * the per-channel Scale+Shift the gather applies:
+ *   scale[c] = gamma[c] / sqrt(var_g + eps), shift[c] = beta[c] - mean_g * scale[c],
+ * mean_g and the biased var_g taken over H*W*(C/groups) elements.  mean, var:
+ * fp32 [groups] outputs (also used as accumulators); gamma, beta, scale, shift:
+ * fp32 [C]; gamma/beta NULL = 1/0.  C % groups == 0.                              */
+int sige_gn_stats(const void* x, sige_dtype dt, int32_t H, int32_t W, int32_t C, int32_t x_ld,
+                  int32_t groups, const float* gamma, const float* beta, float eps,
+                  float* mean, float* var, float* scale, float* shift, void* stream);
+
+const char* sige_last_error(void);
+int sige_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIGE_H */

@@ -187,11 +187,33 @@ def conv2d(z, w_oihw, bias, stride: int = 1, pad: int = 0, pixels=None) -> np.nd
     return y
 
 
+def round_storage(a, storage: str) -> np.ndarray:
+    """Round-to-nearest-even of float64 values to a storage type ("f32", "f16", "bf16"),
+    returned as float64; half types are reached through single precision, the type the
+    element-wise work is done in.  Fig. "method": the gathered blocks are a stored tensor
+    of the model's dtype that the convolution then reads."""
+    a = _f64(a)
+    if storage == "f32":
+        return a.astype(np.float32).astype(np.float64)
+    if storage == "f16":
+        return a.astype(np.float32).astype(np.float16).astype(np.float64)
+    if storage == "bf16":
+        bits = a.astype(np.float32).view(np.uint32)
+        bits = (bits + np.uint32(0x7FFF) + ((bits >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+        return bits.view(np.float32).astype(np.float64)
+    raise ValueError(storage)
+
+
 def dense_layer(x, w_oihw, bias, stride=1, pad=0, scale=None, shift=None, act=ACT_NONE,
-                pixels=None) -> np.ndarray:
+                pixels=None, storage=None) -> np.ndarray:
     """One wrapped layer on a whole tensor: Scale+Shift (cached statistics),
-    nonlinearity, then the convolution; padding is applied to the activated tensor."""
-    z = scale_shift_act(x, scale, shift, act) if (scale is not None or act != ACT_NONE) else _f64(x)
+    nonlinearity, then the convolution; padding is applied to the activated tensor.
+    storage: when given, the activated tensor (what Gather hands to the convolution)
+    is rounded once to that storage type, as a stored tensor of the model would be."""
+    fused = scale is not None or act != ACT_NONE
+    z = scale_shift_act(x, scale, shift, act) if fused else _f64(x)
+    if fused and storage is not None:
+        z = round_storage(z, storage)
     return conv2d(z, w_oihw, bias, stride, pad, pixels)
 
 
@@ -209,10 +231,10 @@ def select_blocks(y_new, y_cache, blocks, bh, bw) -> np.ndarray:
 
 
 def sige_layer(x_edit, y_cache, blocks, bh, bw, w_oihw, bias, stride=1, pad=0, scale=None,
-               shift=None, act=ACT_NONE) -> np.ndarray:
+               shift=None, act=ACT_NONE, storage=None) -> np.ndarray:
     """Fig. "pipeline" (b), written densely: compute the layer on the whole edited
     input, keep the new values on active blocks and the cache elsewhere."""
-    y = dense_layer(x_edit, w_oihw, bias, stride, pad, scale, shift, act)
+    y = dense_layer(x_edit, w_oihw, bias, stride, pad, scale, shift, act, storage=storage)
     return select_blocks(y, y_cache, blocks, bh, bw)
 
 

@@ -1,0 +1,195 @@
+"""Thin ctypes binding of libsige_hip.so: the same entry points as include/sige.h.
+
+Argument marshalling only.  Tensors are torch CUDA tensors used purely as device
+memory; every call enqueues on torch's current stream and returns at once.  There
+is no fallback: if the library has not been built, or a call is refused, a
+:class:`SigeError` is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsige_hip.so")
+
+SIGE_F32, SIGE_F16, SIGE_BF16 = 0, 1, 2
+ACT_NONE, ACT_SILU, ACT_RELU = 0, 1, 2
+_DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF16}
+STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
+          4: "SIGE_ERR_HIP"}
+
+EXPORTS = ["sige_reduce_mask", "sige_gather", "sige_conv", "sige_scatter", "sige_sparse_attn",
+           "sige_sparse_attn_workspace_bytes", "sige_packed_weight_bytes", "sige_pack_weight",
+           "sige_gn_stats", "sige_last_error", "sige_version"]
+
+
+class SigeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class Geom(ctypes.Structure):
+    """Mirror of sige_geom."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("H_in", "W_in", "H_out", "W_out", "block_h", "block_w", "k", "stride", "pad")]
+
+    @property
+    def tile_h(self):
+        return (self.block_h - 1) * self.stride + self.k
+
+    @property
+    def tile_w(self):
+        return (self.block_w - 1) * self.stride + self.k
+
+    @property
+    def grid_blocks(self):
+        return -(-self.H_out // self.block_h) * -(-self.W_out // self.block_w)
+
+
+def geom(H_in, W_in, block, k=3, stride=1, pad=None) -> Geom:
+    pad = k // 2 if pad is None else pad
+    bh, bw = (block, block) if isinstance(block, int) else block
+    return Geom(H_in, W_in, (H_in + 2 * pad - k) // stride + 1, (W_in + 2 * pad - k) // stride + 1,
+                bh, bw, k, stride, pad)
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the HIP library; raises if it has not been built (no CPU fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SigeError(-1, f"{LIB_PATH} is missing: run `python -m paper_2211_02048_amd.build` "
+                                "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(LIB_PATH)
+        L.sige_last_error.restype = ctypes.c_char_p
+        L.sige_packed_weight_bytes.restype = ctypes.c_size_t
+        L.sige_sparse_attn_workspace_bytes.restype = ctypes.c_size_t
+        vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+        gp = ctypes.POINTER(Geom)
+        L.sige_reduce_mask.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp]
+        L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
+        L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
+        L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
+        L.sige_sparse_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
+        L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sige_packed_weight_bytes.argtypes = [i32, i32, i32, i32]
+        L.sige_pack_weight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.sige_gn_stats.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SigeError(rc, lib().sige_last_error().decode())
+
+
+def sige_reduce_mask(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None,
+                     mask_out=None, pool_log2=0, dilate=0, max_blocks=None):
+    """Difference mask -> pooled, dilated mask -> ordered active-block list (device)."""
+    if a_orig is not None:
+        Hm, Wm, C = a_orig.shape
+        dt = _DT[a_orig.dtype]
+    else:
+        Hm, Wm = mask_in.shape
+        C, dt = 0, SIGE_F32
+    mb = indices.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_reduce_mask(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2,
+                                  dilate, ctypes.byref(g), _ptr(mask_out), _ptr(indices), mb, _ptr(count),
+                                  _stream()))
+
+
+def sige_gather(x, g: Geom, indices, count, tiles, *, n_blocks=-1, scale=None, shift=None, act=ACT_NONE,
+                up=0, C=None, x_ld=None, max_blocks=None):
+    """tiles[n] = act(scale * x[tile n] + shift), zero outside the image."""
+    C = x.shape[-1] if C is None else C
+    x_ld = x.stride(-2) if x_ld is None else x_ld
+    mb = tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_gather(_ptr(x), _DT[x.dtype], C, x_ld, up, ctypes.byref(g), _ptr(indices), _ptr(count),
+                             mb, n_blocks, _ptr(scale), _ptr(shift), act, _ptr(tiles), _stream()))
+
+
+def sige_conv(tiles, g: Geom, Cin, Cout, packed_weight, bias, count, out_tiles, *, n_blocks=-1,
+              max_blocks=None):
+    """out_tiles[n] = valid conv of tiles[n] with the packed weight, plus bias."""
+    mb = tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_conv(_ptr(tiles), _DT[tiles.dtype], ctypes.byref(g), Cin, Cout, _ptr(packed_weight),
+                           _ptr(bias), _ptr(count), mb, n_blocks, _ptr(out_tiles), _stream()))
+
+
+def sige_scatter(out_tiles, g: Geom, indices, count, y, *, n_blocks=-1, residual_tiles=None, residual=None,
+                 Cout=None, y_ld=None, res_ld=None, max_blocks=None):
+    """y[block n] = out_tiles[n] (+ residual_tiles[n]) (+ residual[block n]); y is updated in place."""
+    Cout = out_tiles.shape[-1] if Cout is None else Cout
+    y_ld = y.stride(-2) if y_ld is None else y_ld
+    if residual is not None and res_ld is None:
+        res_ld = residual.stride(-2)
+    mb = out_tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_scatter(_ptr(out_tiles), _DT[out_tiles.dtype], ctypes.byref(g), Cout, _ptr(indices),
+                              _ptr(count), mb, n_blocks, _ptr(residual_tiles), _ptr(residual), res_ld or 0,
+                              _ptr(y), y_ld, _stream()))
+
+
+def sige_sparse_attn_workspace_bytes(Nq, T, heads, d) -> int:
+    return int(lib().sige_sparse_attn_workspace_bytes(Nq, T, heads, d))
+
+
+def sige_sparse_attn(q, k, v, o, scale, *, Nq=None, workspace=None, heads=None, d=None, q_ld=None,
+                     kv_ld=None, o_ld=None):
+    """o[i, h] = softmax(scale * q[i, h] . k[:, h]) v[:, h] for the Nq edited query tokens."""
+    heads = q.shape[1] if heads is None else heads
+    d = q.shape[2] if d is None else d
+    Nq = q.shape[0] if Nq is None else Nq
+    T = k.shape[0]
+    q_ld = q.stride(0) if q_ld is None else q_ld
+    kv_ld = k.stride(0) if kv_ld is None else kv_ld
+    o_ld = o.stride(0) if o_ld is None else o_ld
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sige_sparse_attn(_ptr(q), q_ld, _ptr(k), _ptr(v), kv_ld, _DT[q.dtype], Nq, T, heads, d,
+                                  scale, _ptr(o), o_ld, _ptr(workspace), wsb, _stream()))
+
+
+def sige_packed_weight_bytes(dtype, Cout, Cin, k) -> int:
+    return int(lib().sige_packed_weight_bytes(_DT[dtype], Cout, Cin, k))
+
+
+def sige_pack_weight(w_oihw):
+    """Returns the weight re-laid for sige_conv (a new device buffer owned by the caller)."""
+    Cout, Cin, k, _ = w_oihw.shape
+    nbytes = sige_packed_weight_bytes(w_oihw.dtype, Cout, Cin, k)
+    if nbytes == 0:
+        raise SigeError(2, f"sige_pack_weight: unsupported shape {tuple(w_oihw.shape)} for {w_oihw.dtype}")
+    packed = torch.empty(nbytes // w_oihw.element_size(), dtype=w_oihw.dtype, device=w_oihw.device)
+    w = w_oihw.contiguous()
+    _check(lib().sige_pack_weight(_ptr(w), _DT[w.dtype], Cout, Cin, k, _ptr(packed), _stream()))
+    return packed
+
+
+def sige_gn_stats(x, groups, mean, var, *, gamma=None, beta=None, eps=1e-5, scale=None, shift=None,
+                  C=None, x_ld=None):
+    """Group mean / biased variance of a full tensor and the folded per-channel scale / shift."""
+    H, W = x.shape[0], x.shape[1]
+    C = x.shape[2] if C is None else C
+    x_ld = x.stride(1) if x_ld is None else x_ld
+    _check(lib().sige_gn_stats(_ptr(x), _DT[x.dtype], H, W, C, x_ld, groups, _ptr(gamma), _ptr(beta), eps,
+                               _ptr(mean), _ptr(var), _ptr(scale), _ptr(shift), _stream()))
+
+
+def sige_version() -> int:
+    return int(lib().sige_version())

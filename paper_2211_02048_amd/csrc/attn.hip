@@ -1,0 +1,323 @@
+// sige_sparse_attn: attention for the edited query tokens only, against all cached
+// keys and values (Sec. 3.2 "Extension to attention layers", Fig. "sige-attention"):
+// the attention map is Nq x T instead of T x T.
+//
+// One wave owns 32 queries of one head and streams the keys in chunks of 32.  All
+// products run transposed so that everything belonging to a query stays in one lane
+// (pair): S^T = K Q^T leaves a query's 32 logits in the registers of lanes l and
+// l+32, the online softmax needs a single cross-lane exchange, the probabilities
+// feed the second MFMA (O^T = V^T P^T) straight from registers because the
+// contraction index may be permuted freely as long as V^T is read with the same
+// permutation, and the running rescale of O^T is lane-local.  K and V chunks are
+// staged in LDS once per workgroup (4 waves = 128 queries); V is transposed on the
+// way in, with an XOR swizzle on 4-key groups to keep the 2-byte stores off the same
+// banks.  When few queries are active the key range is split over workgroups and a
+// second small kernel merges the partial (max, sum, O) triples.
+#include "common.h"
+
+namespace sige {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <typename T> struct Mma16;
+template <> struct Mma16<f16> {
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        union { uint4 u; f16x8 v; } x, y;
+        x.u = a; y.u = b;
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(x.v, y.v, c, 0, 0, 0);
+    }
+};
+template <> struct Mma16<bf16> {
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        union { uint4 u; bf16x8 v; } x, y;
+        x.u = a; y.u = b;
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, y.v, c, 0, 0, 0);
+    }
+};
+
+struct AttnArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    float* ws;       // partials [split][head][Nq][d + 2] when splits > 1
+    int q_ld, kv_ld, o_ld;
+    int Nq, T, heads, d;
+    int splits, chunks_per_split;
+    float scale_log2e;
+};
+
+constexpr int KCH = 32;          // keys per chunk
+constexpr int VT_STRIDE = 72;    // bytes per row of the transposed V chunk (32 keys * 2 B + 8 pad)
+
+template <typename T, int DT>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
+{
+    constexpr int DKMAX = 2 * DT;  // 16-wide steps over d for S^T
+    extern __shared__ uint4 lds4[];
+    char* lds = reinterpret_cast<char*>(lds4);
+    const int d = a.d;
+    const int k_stride = d * 2 + 16;               // bytes per staged K row
+    char* ks = lds;                                // [KCH][k_stride]
+    char* vt = lds + KCH * k_stride;               // [DT*32][VT_STRIDE]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int head = blockIdx.y;
+    const int qi = (blockIdx.x * 4 + wave) * 32 + l32;
+    const bool q_ok = qi < a.Nq;
+    const int dk = (d + 15) / 16;
+    const int dvec = d / 8;                        // 16-byte vectors per row
+
+    const int chunks_total = (a.T + KCH - 1) / KCH;
+    const int c_begin = blockIdx.z * a.chunks_per_split;
+    const int c_end = min(c_begin + a.chunks_per_split, chunks_total);
+
+    // Q fragments (B operand of S^T = K Q^T): 8 consecutive d values of this lane's query
+    uint4 qf[DKMAX];
+#pragma unroll
+    for (int s = 0; s < DKMAX; ++s) {
+        const int dd = 16 * s + 8 * half;
+        qf[s] = make_uint4(0, 0, 0, 0);
+        if (q_ok && dd < d)
+            qf[s] = *(const uint4*)((const char*)a.q + ((long)qi * a.q_ld + head * d + dd) * 2);
+    }
+    // rows d .. DT*32 of V^T never receive data: zero them once
+    for (int j = tid; j < (DT * 32 - d) * (VT_STRIDE / 4); j += 256)
+        *(uint32_t*)(vt + d * VT_STRIDE + j * 4) = 0u;
+
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[nt][r] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    for (int c = c_begin; c < c_end; ++c) {
+        const int t0 = c * KCH;
+        __syncthreads();  // previous chunk fully consumed
+        for (int j = tid; j < KCH * dvec; j += 256) {
+            const int key = j / dvec, dv = j - key * dvec;
+            uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
+            if (t0 + key < a.T) {
+                const long off = ((long)(t0 + key) * a.kv_ld + head * d + dv * 8) * 2;
+                kv = *(const uint4*)((const char*)a.k + off);
+                vv = *(const uint4*)((const char*)a.v + off);
+            }
+            *(uint4*)(ks + key * k_stride + dv * 16) = kv;
+            // transpose V: element e of this vector is row dv*8+e; 4-key group index is swizzled by dv
+            const int col = ((((key >> 2) ^ (dv & 7)) << 2) | (key & 3)) * 2;
+            union { uint4 u; uint16_t h[8]; } x;
+            x.u = vv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) *(uint16_t*)(vt + (dv * 8 + e) * VT_STRIDE + col) = x.h[e];
+        }
+        __syncthreads();
+
+        // S^T chunk: rows = keys, cols = queries
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < DKMAX; ++s) {
+            if (s < dk) {
+                const int dd = 16 * s + 8 * half;
+                uint4 kf = make_uint4(0, 0, 0, 0);
+                if (dd < d) kf = *(const uint4*)(ks + l32 * k_stride + dd * 2);
+                Mma16<T>::run(kf, qf[s], sacc);
+            }
+        }
+        // online softmax; this lane holds keys 8*(r/4) + 4*half + r%4 of its query
+        float mx = m_run;
+        float sv[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = t0 + 8 * (r >> 2) + 4 * half + (r & 3);
+            sv[r] = key < a.T ? sacc[r] * a.scale_log2e : -INFINITY;
+            mx = fmaxf(mx, sv[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float alpha = exp2f(m_run - mx);  // first chunk: exp2(-inf) = 0
+        float lsum = 0.0f;
+        float pv[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            pv[r] = exp2f(sv[r] - mx);
+            lsum += pv[r];
+        }
+        l_run = l_run * alpha + lsum;
+        m_run = mx;
+#pragma unroll
+        for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[nt][r] *= alpha;
+
+        // O^T += V^T P^T, two steps of 16 keys; step s uses registers 8s..8s+7
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            union { uint4 u; T h[8]; } pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf.h[e] = from_f32<T>(pv[8 * s + e]);
+#pragma unroll
+            for (int nt = 0; nt < DT; ++nt) {
+                const int row = nt * 32 + l32;
+                const int sw = (row >> 3) & 7;
+                const int g_lo = (4 * s + half) ^ sw, g_hi = (4 * s + 2 + half) ^ sw;
+                const uint2 lo = *(const uint2*)(vt + row * VT_STRIDE + g_lo * 8);
+                const uint2 hi = *(const uint2*)(vt + row * VT_STRIDE + g_hi * 8);
+                Mma16<T>::run(make_uint4(lo.x, lo.y, hi.x, hi.y), pf.u, oacc[nt]);
+            }
+        }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (!q_ok) return;
+    if (a.splits == 1) {
+        const float inv = 1.0f / l_tot;
+#pragma unroll
+        for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dd = nt * 32 + 8 * rq + 4 * half;
+                if (dd < d) {
+                    union { uint2 u; T h[4]; } x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x.h[e] = from_f32<T>(oacc[nt][4 * rq + e] * inv);
+                    *(uint2*)((char*)a.o + ((long)qi * a.o_ld + head * d + dd) * 2) = x.u;
+                }
+            }
+    } else {
+        float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 2);
+        if (half == 0) { w[d] = m_run; w[d + 1] = l_tot; }
+#pragma unroll
+        for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dd = nt * 32 + 8 * rq + 4 * half;
+                if (dd < d) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[dd + e] = oacc[nt][4 * rq + e];
+                }
+            }
+    }
+}
+
+// Merge of the per-split partials: one thread per (query, head, d element).
+template <typename T>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int d = a.d;
+    if (i >= (long)a.Nq * a.heads * d) return;
+    const int dd = (int)(i % d);
+    const int head = (int)((i / d) % a.heads);
+    const int qi = (int)(i / ((long)d * a.heads));
+    float m = -INFINITY;
+    for (int s = 0; s < a.splits; ++s)
+        m = fmaxf(m, a.ws[(((long)s * a.heads + head) * a.Nq + qi) * (d + 2) + d]);
+    float num = 0.0f, den = 0.0f;
+    for (int s = 0; s < a.splits; ++s) {
+        const float* w = a.ws + (((long)s * a.heads + head) * a.Nq + qi) * (d + 2);
+        const float f = exp2f(w[d] - m);
+        num += w[dd] * f;
+        den += w[d + 1] * f;
+    }
+    ((T*)a.o)[(long)qi * a.o_ld + head * d + dd] = from_f32<T>(num / den);
+}
+
+// Number of key splits: enough workgroups to fill the chip, at least 8 chunks each.
+static int pick_splits(int Nq, int T, int heads)
+{
+    const long base = (long)heads * ((Nq + 127) / 128);
+    const int chunks = (T + KCH - 1) / KCH;
+    long want = (512 + base - 1) / base;
+    long cap = chunks / 8;
+    if (want > cap) want = cap;
+    if (want > 64) want = 64;
+    if (want < 1) want = 1;
+    const int per = (int)((chunks + want - 1) / want);
+    return (chunks + per - 1) / per;
+}
+
+template <typename T, int DT>
+static int launch_attn_dt(const AttnArgs& a, hipStream_t st)
+{
+    const size_t lds = (size_t)KCH * (a.d * 2 + 16) + (size_t)DT * 32 * VT_STRIDE;
+    dim3 grid((a.Nq + 127) / 128, a.heads, a.splits);
+    hipLaunchKernelGGL((attn_kernel<T, DT>), grid, dim3(256), lds, st, a);
+    SIGE_LAUNCH_CHECK("sige_sparse_attn");
+    if (a.splits > 1) {
+        const long n = (long)a.Nq * a.heads * a.d;
+        hipLaunchKernelGGL((attn_merge_kernel<T>), dim3((int)((n + 255) / 256)), dim3(256), 0, st, a);
+        SIGE_LAUNCH_CHECK("sige_sparse_attn(merge)");
+    }
+    return SIGE_OK;
+}
+
+template <typename T>
+static int launch_attn(const AttnArgs& a, hipStream_t st)
+{
+    const int dt = (a.d + 31) / 32;
+    switch (dt) {
+    case 1: return launch_attn_dt<T, 1>(a, st);
+    case 2: return launch_attn_dt<T, 2>(a, st);
+    case 3: return launch_attn_dt<T, 3>(a, st);
+    case 4: return launch_attn_dt<T, 4>(a, st);
+    case 5: return launch_attn_dt<T, 5>(a, st);
+    case 6: return launch_attn_dt<T, 6>(a, st);
+    default: return launch_attn_dt<T, 8>(a, st);
+    }
+}
+
+}  // namespace sige
+
+using namespace sige;
+
+extern "C" size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_t heads, int32_t d)
+{
+    if (Nq <= 0 || T <= 0 || heads <= 0 || d <= 0) return 0;
+    const int splits = pick_splits(Nq, T, heads);
+    if (splits <= 1) return 0;
+    return (size_t)splits * heads * Nq * (d + 2) * sizeof(float);
+}
+
+extern "C" int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, const void* v, int32_t kv_ld,
+                                sige_dtype dt, int32_t Nq, int32_t T, int32_t heads, int32_t d,
+                                float scale, void* o, int32_t o_ld, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    const char* who = "sige_sparse_attn";
+    SIGE_REQUIRE(Nq >= 0 && T > 0 && heads > 0 && d > 0, SIGE_ERR_INVALID_ARG,
+                 "%s: need Nq >= 0, T > 0, heads > 0, d > 0", who);
+    SIGE_REQUIRE(dt == SIGE_F16 || dt == SIGE_BF16, SIGE_ERR_UNSUPPORTED, "%s: dtype must be f16 or bf16", who);
+    SIGE_REQUIRE(d % 8 == 0 && d <= 256, SIGE_ERR_UNSUPPORTED, "%s: d must be a multiple of 8 and <= 256", who);
+    SIGE_REQUIRE(heads <= 65535, SIGE_ERR_UNSUPPORTED, "%s: too many heads", who);
+    if (Nq == 0) return SIGE_OK;
+    SIGE_REQUIRE(q && k && v && o, SIGE_ERR_INVALID_ARG, "%s: q, k, v and o are required", who);
+    SIGE_REQUIRE(q_ld >= heads * d && kv_ld >= heads * d && o_ld >= heads * d, SIGE_ERR_INVALID_ARG,
+                 "%s: row strides must be >= heads*d", who);
+    SIGE_REQUIRE(q_ld % 8 == 0 && kv_ld % 8 == 0 && o_ld % 8 == 0, SIGE_ERR_UNSUPPORTED,
+                 "%s: row strides must be multiples of 8 elements", who);
+    SIGE_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o), SIGE_ERR_UNSUPPORTED,
+                 "%s: pointers must be 16-byte aligned", who);
+    AttnArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.ws = (float*)workspace;
+    a.q_ld = q_ld; a.kv_ld = kv_ld; a.o_ld = o_ld;
+    a.Nq = Nq; a.T = T; a.heads = heads; a.d = d;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    const int chunks = (T + KCH - 1) / KCH;
+    int splits = pick_splits(Nq, T, heads);
+    if (splits > 1 && (workspace == nullptr ||
+                       workspace_bytes < (size_t)splits * heads * Nq * (d + 2) * sizeof(float) ||
+                       (reinterpret_cast<uintptr_t>(workspace) & 3u)))
+        splits = 1;
+    a.chunks_per_split = (chunks + splits - 1) / splits;
+    a.splits = (chunks + a.chunks_per_split - 1) / a.chunks_per_split;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == SIGE_F16 ? launch_attn<f16>(a, st) : launch_attn<bf16>(a, st);
+}

@@ -1,0 +1,117 @@
+// Internal helpers of the gfx950 library: error reporting, argument checks,
+// storage-type traits and 16-byte vector access.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "sige.h"
+
+namespace sige {
+
+typedef _Float16 f16;
+typedef __bf16 bf16;
+
+int fail(int code, const char* fmt, ...);  // records a thread-local message, returns code
+void clear_error();
+
+#define SIGE_REQUIRE(cond, code, ...)                 \
+    do {                                              \
+        if (!(cond)) return sige::fail(code, __VA_ARGS__); \
+    } while (0)
+
+#define SIGE_LAUNCH_CHECK(name)                                                          \
+    do {                                                                                 \
+        hipError_t e_ = hipGetLastError();                                               \
+        if (e_ != hipSuccess)                                                            \
+            return sige::fail(SIGE_ERR_HIP, "%s: launch failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+inline size_t dtype_size(sige_dtype dt) { return dt == SIGE_F32 ? 4 : 2; }
+inline bool dtype_ok(sige_dtype dt) { return dt == SIGE_F32 || dt == SIGE_F16 || dt == SIGE_BF16; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks shared by every call that takes a geometry; fills tile sizes.
+int check_geom(const sige_geom* g, const char* who, int* tile_h, int* tile_w);
+// Resolves (count, max_blocks, n_blocks) into the number of blocks to launch for.
+int check_blocks(const int32_t* count, int32_t max_blocks, int32_t n_blocks, const char* who,
+                 int* launch_blocks);
+
+// ---- device side ---------------------------------------------------------------
+
+template <typename T> struct Vec16;                    // a 16-byte vector of T
+template <> struct Vec16<float> { static constexpr int N = 4; };
+template <> struct Vec16<f16> { static constexpr int N = 8; };
+template <> struct Vec16<bf16> { static constexpr int N = 8; };
+
+template <typename T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }
+
+// Unpack a 16-byte vector into floats / pack floats back with one rounding each.
+template <typename T> __device__ __forceinline__ void unpack(const uint4& u, float* f);
+template <> __device__ __forceinline__ void unpack<float>(const uint4& u, float* f)
+{
+    f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
+    f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
+}
+template <> __device__ __forceinline__ void unpack<f16>(const uint4& u, float* f)
+{
+    union { uint4 v; f16 h[8]; } c; c.v = u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)c.h[i];
+}
+template <> __device__ __forceinline__ void unpack<bf16>(const uint4& u, float* f)
+{
+    // bf16 -> fp32 is a 16-bit shift, exact
+    f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
+    f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+    f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
+    f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+template <typename T> __device__ __forceinline__ uint4 pack(const float* f);
+template <> __device__ __forceinline__ uint4 pack<float>(const float* f)
+{
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                      __float_as_uint(f[3]));
+}
+template <> __device__ __forceinline__ uint4 pack<f16>(const float* f)
+{
+    union { uint4 v; f16 h[8]; } c;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c.h[i] = (f16)f[i];
+    return c.v;
+}
+template <> __device__ __forceinline__ uint4 pack<bf16>(const float* f)
+{
+    union { uint4 v; bf16 h[8]; } c;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c.h[i] = (bf16)f[i];
+    return c.v;
+}
+
+// Streaming (non-temporal) 16-byte load: data that is read exactly once.
+__device__ __forceinline__ uint4 load_stream(const uint4* p)
+{
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ float apply_act(float v, int act)
+{
+    if (act == SIGE_ACT_SILU) return v / (1.0f + __expf(-v));
+    if (act == SIGE_ACT_RELU) return v > 0.0f ? v : 0.0f;
+    return v;
+}
+
+// Number of blocks a kernel may touch: the host value when given, else the device count.
+__device__ __forceinline__ int effective_blocks(const int32_t* count, int max_blocks, int n_host)
+{
+    if (n_host >= 0) return n_host;
+    int c = *count;
+    return c < max_blocks ? c : max_blocks;
+}
+
+}  // namespace sige

@@ -1,0 +1,340 @@
+// sige_conv: the convolution F_l on the stacked active tiles (Fig. "method"), with bias
+// (Fig. "pipeline" (b)), as an implicit GEMM on the gfx950 matrix cores:
+//     M = pixels of the active blocks, N = Cout, K = k*k*Cin.
+//
+// A workgroup (4 waves) owns an M x N patch: a row band of one block (or several
+// whole small blocks) times a slab of output channels.  The input rows it needs
+// (band + halo) are staged once per channel chunk into LDS and reused by all k*k
+// taps; the A operand of each MFMA is a 16-byte LDS read at
+// pixel(py*stride+ky, px*stride+kx), the B operand a 16-byte read of weights that
+// sige_pack_weight has laid out in fragment order (L2 resident, shared by every
+// workgroup).  fp32 accumulation, bias as the accumulator's start value, one
+// rounding to the storage type at the store.
+#include "common.h"
+
+#include <stdlib.h>
+
+#include <algorithm>
+
+namespace sige {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// One 16-byte A fragment and one 16-byte B fragment per lane advance K by KSTEP channels.
+template <typename T> struct Mma;
+template <> struct Mma<f16> {
+    static constexpr int KSTEP = 16;
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        union { uint4 u; f16x8 v; } x, y;
+        x.u = a; y.u = b;
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(x.v, y.v, c, 0, 0, 0);
+    }
+};
+template <> struct Mma<bf16> {
+    static constexpr int KSTEP = 16;
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        union { uint4 u; bf16x8 v; } x, y;
+        x.u = a; y.u = b;
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, y.v, c, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {
+    static constexpr int KSTEP = 8;  // lane half h holds channels 4h..4h+3 of the step
+    static __device__ __forceinline__ void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+struct ConvArgs {
+    const void* tiles;
+    const void* w;
+    const float* bias;
+    void* out;
+    const int32_t* count;
+    int th, tw, bh, bw, k, stride, Cin, Cout;
+    int max_blocks, n_host;
+    int G;      // whole blocks per workgroup (1 when a block is split into row bands)
+    int rows;   // output rows of a block handled by one workgroup
+    int trows;  // tile rows staged: (rows-1)*stride + k
+    int Cc;     // channels staged per pass (multiple of KSTEP)
+    int ps;     // LDS pixel stride in bytes: Cc*size + 16 (the pad spreads pixels over banks)
+};
+
+// Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
+// holds output channel nt*32 + l%32 and the l/32-th half of the step's channels.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ w, int Cout, int Cin,
+                                                          int k, long n_elems, T* __restrict__ packed)
+{
+    constexpr int N = Vec16<T>::N, KS = Mma<T>::KSTEP;
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_elems) return;
+    const int e = (int)(i % N);
+    const int lane = (int)((i / N) % 64);
+    long r = i / (N * 64);
+    const int kc = (int)(r % (Cin / KS));
+    r /= (Cin / KS);
+    const int tap = (int)(r % (k * k));
+    const int nt = (int)(r / (k * k));
+    const int o = nt * 32 + (lane & 31);
+    const int c = kc * KS + (lane >> 5) * N + e;
+    const int ky = tap / k, kx = tap - ky * k;
+    packed[i] = o < Cout ? w[(((long)o * Cin + c) * k + ky) * k + kx] : from_f32<T>(0.0f);
+}
+
+template <typename T, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
+{
+    static_assert(WM * WN == 4, "four waves per workgroup");
+    constexpr int KS = Mma<T>::KSTEP;
+    constexpr int S = (int)sizeof(T);
+    extern __shared__ uint4 lds4[];
+    char* lds = reinterpret_cast<char*>(lds4);
+
+    const int n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
+    const int g0 = blockIdx.z * a.G;
+    if (g0 >= n_eff) return;
+    const int band = blockIdx.y;
+    const int band_row0 = band * a.rows;                      // first output row of the band
+    const int band_rows = min(a.rows, a.bh - band_row0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int pb = a.rows * a.bw;                             // M rows one block contributes
+    const int trow0 = band_row0 * a.stride;                   // first staged tile row
+
+    // LDS byte offset of this lane's A row for each of its M tiles (clamped to a valid pixel)
+    int a_base[TM];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int m = (wm * TM + tm) * 32 + l32;
+        int g = m / pb, p = m - g * pb;
+        int py = p / a.bw, px = p - py * a.bw;
+        if (g >= a.G || py >= band_rows) { g = 0; py = 0; px = 0; }
+        a_base[tm] = ((g * a.trows + py * a.stride) * a.tw + px * a.stride) * a.ps + half * 16;
+    }
+    const int nt0 = (blockIdx.x * WN + wn) * TN;              // first 32-wide Cout tile of this wave
+    const int kk = a.k * a.k, kcs = a.Cin / KS;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int o = (nt0 + tn) * 32 + l32;
+        const float b = (a.bias && o < a.Cout) ? a.bias[o] : 0.0f;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = b;
+    }
+
+    const uint4* __restrict__ wp = (const uint4*)a.w;
+    const char* __restrict__ tiles = (const char*)a.tiles;
+    const int npix = a.G * a.trows * a.tw;
+    const int ntn_total = (a.Cout + 31) / 32;
+
+    for (int c0 = 0; c0 < a.Cin; c0 += a.Cc) {
+        const int cc = min(a.Cc, a.Cin - c0);
+        const int vpc = cc * S / 16;                          // 16-byte vectors per staged pixel
+        if (c0) __syncthreads();
+        for (int j = tid; j < npix * vpc; j += 256) {
+            const int q = j / vpc, v = j - q * vpc;
+            const int g = q / (a.trows * a.tw), rem = q - g * (a.trows * a.tw);
+            const int r = rem / a.tw, x = rem - r * a.tw;
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (g0 + g < n_eff && trow0 + r < a.th)
+                val = *(const uint4*)(tiles + ((((long)(g0 + g) * a.th + trow0 + r) * a.tw + x) * a.Cin + c0) * S + v * 16);
+            *(uint4*)(lds + q * a.ps + v * 16) = val;
+        }
+        __syncthreads();
+        for (int tap = 0; tap < kk; ++tap) {
+            const int ky = tap / a.k, kx = tap - ky * a.k;
+            const int tap_off = (ky * a.tw + kx) * a.ps;
+            for (int kc = 0; kc < cc / KS; ++kc) {
+                uint4 af[TM], bf[TN];
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int nt = min(nt0 + tn, ntn_total - 1);
+                    bf[tn] = wp[(((long)nt * kk + tap) * kcs + (c0 / KS + kc)) * 64 + lane];
+                }
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    af[tm] = *(const uint4*)(lds + a_base[tm] + tap_off + kc * (KS * S));
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], bf[tn], acc[tm][tn]);
+            }
+        }
+    }
+
+    // epilogue: lane holds column l32 of each tile, rows 8*(r/4) + 4*half + r%4
+    T* __restrict__ out = (T*)a.out;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            const int g = m / pb, p = m - g * pb;
+            const int py = p / a.bw, px = p - py * a.bw;
+            if (g >= a.G || py >= band_rows || g0 + g >= n_eff) continue;
+            const long base = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int o = (nt0 + tn) * 32 + l32;
+                if (o < a.Cout) out[base + o] = from_f32<T>(acc[tm][tn][r]);
+            }
+        }
+    }
+}
+
+struct ConvPlan {
+    int cfg;  // 0: 128x128, 1: 128x64, 2: 64x64 (M x N per workgroup)
+    int G, rows, trows, Cc, ps, bands, slabs, groups;
+    size_t lds;
+};
+
+static const int kCfgM[3] = {128, 128, 64};
+static const int kCfgN[3] = {128, 64, 64};
+
+// Chooses the workgroup shape and the staged channel chunk for one call.
+static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, size_t s, int kstep,
+                      int nblocks, ConvPlan* best)
+{
+    const char* force = getenv("SIGE_CONV_CFG");
+    double best_score = -1.0;
+    for (int cfg = 0; cfg < 3; ++cfg) {
+        if (force && atoi(force) != cfg) continue;
+        const int M = kCfgM[cfg], Nn = kCfgN[cfg];
+        if (g->block_w > M) continue;
+        ConvPlan p;
+        p.cfg = cfg;
+        const int pbfull = g->block_h * g->block_w;
+        if (pbfull <= M) { p.G = M / pbfull; p.rows = g->block_h; }
+        else { p.G = 1; p.rows = M / g->block_w; }
+        p.bands = (g->block_h + p.rows - 1) / p.rows;
+        p.trows = (p.rows - 1) * g->stride + g->k;
+        p.slabs = (Cout + Nn - 1) / Nn;
+        p.groups = (nblocks + p.G - 1) / p.G;
+        // largest channel chunk whose staged tile fits 64 KiB (up to 160 KiB for the smallest chunk)
+        const long npix = (long)p.G * p.trows * tw;
+        int Cc = Cin;
+        while (Cc > kstep && npix * (Cc * s + 16) > 64 * 1024) Cc = ((Cc / 2 + kstep - 1) / kstep) * kstep;
+        p.Cc = Cc;
+        p.ps = (int)(Cc * s + 16);
+        p.lds = (size_t)npix * p.ps;
+        if (p.lds > 160 * 1024) continue;
+        const double util = (double)(p.G * (p.G > 1 ? pbfull : std::min(p.rows, (int)g->block_h) * g->block_w)) / M;
+        const long wgs = (long)p.groups * p.bands * p.slabs;
+        const double fill = wgs >= 512 ? 1.0 : (double)wgs / 512.0;
+        const double bonus = cfg == 0 ? 1.0 : cfg == 1 ? 0.9 : 0.75;
+        const double nuse = (double)Cout / (p.slabs * Nn);
+        const double score = util * fill * bonus * nuse;
+        if (score > best_score) { best_score = score; *best = p; }
+    }
+    return best_score >= 0.0;
+}
+
+template <typename T, int TM, int TN, int WM, int WN>
+static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
+{
+    auto kern = conv_kernel<T, TM, TN, WM, WN>;
+    if (p.lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)p.lds);
+        SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_conv: cannot reserve %zu bytes of LDS: %s", p.lds,
+                     hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(kern, dim3(p.slabs, p.bands, p.groups), dim3(256), p.lds, st, a);
+    SIGE_LAUNCH_CHECK("sige_conv");
+    return SIGE_OK;
+}
+
+template <typename T>
+static int launch_conv(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
+{
+    switch (p.cfg) {
+    case 0: return launch_cfg<T, 2, 2, 2, 2>(a, p, st);
+    case 1: return launch_cfg<T, 2, 1, 2, 2>(a, p, st);
+    default: return launch_cfg<T, 1, 1, 2, 2>(a, p, st);
+    }
+}
+
+}  // namespace sige
+
+using namespace sige;
+
+extern "C" size_t sige_packed_weight_bytes(sige_dtype dt, int32_t Cout, int32_t Cin, int32_t k)
+{
+    if (!dtype_ok(dt) || Cout <= 0 || Cin <= 0 || k <= 0) return 0;
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    if (Cin % ks) return 0;
+    return (size_t)((Cout + 31) / 32) * k * k * (Cin / ks) * 64 * 16;
+}
+
+extern "C" int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout, int32_t Cin, int32_t k,
+                                void* packed, void* stream)
+{
+    clear_error();
+    const char* who = "sige_pack_weight";
+    SIGE_REQUIRE(w_oihw && packed, SIGE_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cout > 0 && Cin > 0 && k > 0 && (k & 1), SIGE_ERR_INVALID_ARG, "%s: bad shape", who);
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
+    const size_t bytes = sige_packed_weight_bytes(dt, Cout, Cin, k);
+    const long n = (long)(bytes / dtype_size(dt));
+    const long blocks = (n + 255) / 256;
+    SIGE_REQUIRE(blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "%s: weight too large", who);
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == SIGE_F32)
+        hipLaunchKernelGGL((pack_weight_kernel<float>), dim3((int)blocks), dim3(256), 0, st, (const float*)w_oihw, Cout, Cin, k, n, (float*)packed);
+    else if (dt == SIGE_F16)
+        hipLaunchKernelGGL((pack_weight_kernel<f16>), dim3((int)blocks), dim3(256), 0, st, (const f16*)w_oihw, Cout, Cin, k, n, (f16*)packed);
+    else
+        hipLaunchKernelGGL((pack_weight_kernel<bf16>), dim3((int)blocks), dim3(256), 0, st, (const bf16*)w_oihw, Cout, Cin, k, n, (bf16*)packed);
+    SIGE_LAUNCH_CHECK(who);
+    return SIGE_OK;
+}
+
+extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                         const void* packed_weight, const float* bias, const int32_t* count,
+                         int32_t max_blocks, int32_t n_blocks, void* out_tiles, void* stream)
+{
+    clear_error();
+    const char* who = "sige_conv";
+    int th, tw, nl;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(tiles && packed_weight && out_tiles, SIGE_ERR_INVALID_ARG,
+                 "%s: tiles, packed_weight and out_tiles are required", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cin > 0 && Cout > 0, SIGE_ERR_INVALID_ARG, "%s: Cin and Cout must be positive", who);
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
+    SIGE_REQUIRE(aligned16(tiles) && aligned16(packed_weight), SIGE_ERR_UNSUPPORTED,
+                 "%s: tiles and packed_weight must be 16-byte aligned", who);
+    if (nl == 0) return SIGE_OK;
+    ConvPlan p;
+    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, &p), SIGE_ERR_UNSUPPORTED,
+                 "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who, g->block_h, g->block_w,
+                 g->k, g->stride, Cin);
+    SIGE_REQUIRE(p.groups <= 65535 && p.bands <= 65535, SIGE_ERR_UNSUPPORTED, "%s: too many blocks per launch", who);
+    ConvArgs a;
+    a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
+    a.th = th; a.tw = tw; a.bh = g->block_h; a.bw = g->block_w; a.k = g->k; a.stride = g->stride;
+    a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
+    a.G = p.G; a.rows = p.rows; a.trows = p.trows; a.Cc = p.Cc; a.ps = p.ps;
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == SIGE_F32) return launch_conv<float>(a, p, st);
+    if (dt == SIGE_F16) return launch_conv<f16>(a, p, st);
+    return launch_conv<bf16>(a, p, st);
+}

@@ -1,0 +1,246 @@
+// sige_gather / sige_scatter (Fig. "method", Fig. "pipeline" (b)) with the cached-
+// statistics Scale+Shift and the nonlinearity fused into the gather (Sec. 3.2
+// "Pre-computing normalization parameters", "Kernel fusion").
+//
+// Both are pure HBM streams.  A tile row is one contiguous run of tile_w*C elements
+// on either side, so every lane moves one 16-byte vector and a wave covers whole
+// 1 KiB runs; the grid is (row groups) x (blocks), which keeps hundreds of
+// workgroups in flight even when only a handful of blocks are active.
+#include "common.h"
+
+namespace sige {
+
+struct GatherArgs {
+    const void* x;
+    void* tiles;
+    const int32_t* indices;
+    const int32_t* count;
+    const float* scale;
+    const float* shift;
+    int Hin, Win, ld_vec, V;  // V = 16-byte vectors per pixel, ld_vec = pixel stride in vectors
+    int th, tw, stride, pad, up;
+    int max_blocks, n_host, act, rows_per_wg;
+};
+
+// FIXED_CG: blockDim.x is a multiple of V, so a thread keeps one channel group and
+// holds its scale/shift in registers.
+template <typename T, bool FUSED, bool FIXED_CG>
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
+{
+    constexpr int N = Vec16<T>::N;
+    const int n = blockIdx.y;
+    if (n >= effective_blocks(a.count, a.max_blocks, a.n_host)) return;
+    const int iy0 = a.indices[2 * n] * a.stride - a.pad, ix0 = a.indices[2 * n + 1] * a.stride - a.pad;
+    const int r0 = blockIdx.x * a.rows_per_wg;
+    const int r1 = min(r0 + a.rows_per_wg, a.th);
+    const int row_vecs = a.tw * a.V;
+    const int total = (r1 - r0) * row_vecs;
+    const uint4* __restrict__ src = (const uint4*)a.x;
+    uint4* __restrict__ dst = (uint4*)a.tiles + ((long)n * a.th + r0) * row_vecs;
+    const int Ws = a.Win >> a.up;
+
+    float sc[N], sh[N];
+    if (FUSED && FIXED_CG) {
+        const int cg = threadIdx.x % a.V;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            sc[i] = a.scale ? a.scale[cg * N + i] : 1.0f;
+            sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
+        }
+    }
+    for (int j = threadIdx.x; j < total; j += 256) {
+        const int r = j / row_vecs, jr = j - r * row_vecs;
+        const int px = jr / a.V, cg = jr - px * a.V;
+        const int iy = iy0 + r0 + r, ix = ix0 + px;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) {
+            v = src[((long)(iy >> a.up) * Ws + (ix >> a.up)) * a.ld_vec + cg];
+            if (FUSED) {
+                float f[N];
+                unpack<T>(v, f);
+                if (!FIXED_CG) {
+#pragma unroll
+                    for (int i = 0; i < N; ++i) {
+                        sc[i] = a.scale ? a.scale[cg * N + i] : 1.0f;
+                        sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < N; ++i) f[i] = apply_act(fmaf(sc[i], f[i], sh[i]), a.act);
+                v = pack<T>(f);
+            }
+        }
+        dst[j] = v;
+    }
+}
+
+struct ScatterArgs {
+    const void* out_tiles;
+    const void* res_tiles;
+    const void* res_full;
+    void* y;
+    const int32_t* indices;
+    const int32_t* count;
+    int Hout, Wout, V, y_ld_vec, res_ld_vec;
+    int bh, bw;
+    int max_blocks, n_host, rows_per_wg;
+};
+
+template <typename T, bool ADD>
+__global__ __launch_bounds__(256) void scatter_kernel(ScatterArgs a)
+{
+    constexpr int N = Vec16<T>::N;
+    const int n = blockIdx.y;
+    if (n >= effective_blocks(a.count, a.max_blocks, a.n_host)) return;
+    const int y0 = a.indices[2 * n], x0 = a.indices[2 * n + 1];
+    if (y0 < 0 || x0 < 0 || y0 >= a.Hout || x0 >= a.Wout) return;  // never store outside y
+    const int r0 = blockIdx.x * a.rows_per_wg;
+    const int r1 = min(min(r0 + a.rows_per_wg, a.bh), a.Hout - y0);  // clip rows at the bottom edge
+    if (r1 <= r0) return;
+    const int cols = min(a.bw, a.Wout - x0);                         // clip columns at the right edge
+    const int row_vecs = cols * a.V;
+    const int total = (r1 - r0) * row_vecs;
+    const uint4* __restrict__ src = (const uint4*)a.out_tiles;
+    const uint4* __restrict__ rt = (const uint4*)a.res_tiles;
+    const uint4* __restrict__ rf = (const uint4*)a.res_full;
+    uint4* __restrict__ dst = (uint4*)a.y;
+    for (int j = threadIdx.x; j < total; j += 256) {
+        const int r = j / row_vecs, jr = j - r * row_vecs;
+        const int px = jr / a.V, cg = jr - px * a.V;
+        const long t = (((long)n * a.bh + r0 + r) * a.bw + px) * a.V + cg;
+        const long pix = (long)(y0 + r0 + r) * a.Wout + x0 + px;
+        uint4 v = src[t];
+        if (ADD) {
+            float f[N], g[N];
+            unpack<T>(v, f);
+            if (rt) {
+                unpack<T>(rt[t], g);
+#pragma unroll
+                for (int i = 0; i < N; ++i) f[i] += g[i];
+            }
+            if (rf) {
+                unpack<T>(rf[pix * a.res_ld_vec + cg], g);
+#pragma unroll
+                for (int i = 0; i < N; ++i) f[i] += g[i];
+            }
+            v = pack<T>(f);
+        }
+        dst[pix * a.y_ld_vec + cg] = v;
+    }
+}
+
+// Rows per workgroup: aim for at least ~2048 workgroups in total (8 per CU) while
+// giving each one at least ~16 KiB to move.
+static int pick_rows(int rows, size_t row_bytes, int blocks)
+{
+    int rpw = (int)((16384 + row_bytes - 1) / row_bytes);
+    if (rpw < 1) rpw = 1;
+    while (rpw > 1 && (long)blocks * ((rows + rpw - 1) / rpw) < 2048) --rpw;
+    return rpw > rows ? rows : rpw;
+}
+
+template <typename T>
+static void launch_gather(const GatherArgs& a, dim3 grid, bool fused, hipStream_t st)
+{
+    const bool fixed = (256 % a.V) == 0;
+    if (!fused)
+        hipLaunchKernelGGL((gather_kernel<T, false, true>), grid, dim3(256), 0, st, a);
+    else if (fixed)
+        hipLaunchKernelGGL((gather_kernel<T, true, true>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((gather_kernel<T, true, false>), grid, dim3(256), 0, st, a);
+}
+
+template <typename T>
+static void launch_scatter(const ScatterArgs& a, dim3 grid, hipStream_t st)
+{
+    if (a.res_tiles || a.res_full)
+        hipLaunchKernelGGL((scatter_kernel<T, true>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((scatter_kernel<T, false>), grid, dim3(256), 0, st, a);
+}
+
+}  // namespace sige
+
+using namespace sige;
+
+extern "C" int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
+                           const sige_geom* g, const int32_t* indices, const int32_t* count,
+                           int32_t max_blocks, int32_t n_blocks, const float* scale,
+                           const float* shift, sige_act act, void* tiles, void* stream)
+{
+    clear_error();
+    const char* who = "sige_gather";
+    int th, tw, nl;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(x && indices && tiles, SIGE_ERR_INVALID_ARG, "%s: x, indices and tiles are required", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(C > 0 && x_ld >= C, SIGE_ERR_INVALID_ARG, "%s: need C > 0 and x_ld >= C", who);
+    SIGE_REQUIRE((scale == nullptr) == (shift == nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: scale and shift must be given together", who);
+    SIGE_REQUIRE(act == SIGE_ACT_NONE || act == SIGE_ACT_SILU || act == SIGE_ACT_RELU, SIGE_ERR_INVALID_ARG,
+                 "%s: unknown activation %d", who, (int)act);
+    SIGE_REQUIRE(up == 0 || up == 1, SIGE_ERR_INVALID_ARG, "%s: up must be 0 or 1", who);
+    SIGE_REQUIRE(up == 0 || (g->H_in % 2 == 0 && g->W_in % 2 == 0), SIGE_ERR_INVALID_ARG,
+                 "%s: up-sampled input size must be even", who);
+    const size_t s = dtype_size(dt);
+    SIGE_REQUIRE((C * s) % 16 == 0 && (x_ld * s) % 16 == 0, SIGE_ERR_UNSUPPORTED,
+                 "%s: C and x_ld must be multiples of %zu elements (16 bytes)", who, 16 / s);
+    SIGE_REQUIRE(aligned16(x) && aligned16(tiles), SIGE_ERR_UNSUPPORTED, "%s: pointers must be 16-byte aligned", who);
+    if (nl == 0) return SIGE_OK;
+    GatherArgs a;
+    a.x = x; a.tiles = tiles; a.indices = indices; a.count = count; a.scale = scale; a.shift = shift;
+    a.Hin = g->H_in; a.Win = g->W_in; a.V = (int)(C * s / 16); a.ld_vec = (int)(x_ld * s / 16);
+    a.th = th; a.tw = tw; a.stride = g->stride; a.pad = g->pad; a.up = up;
+    a.max_blocks = max_blocks; a.n_host = n_blocks; a.act = (int)act;
+    a.rows_per_wg = pick_rows(th, (size_t)tw * C * s, nl);
+    const bool fused = scale != nullptr || act != SIGE_ACT_NONE;
+    dim3 grid((th + a.rows_per_wg - 1) / a.rows_per_wg, nl);
+    SIGE_REQUIRE(nl <= 65535, SIGE_ERR_UNSUPPORTED, "%s: more than 65535 blocks per launch", who);
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == SIGE_F32) launch_gather<float>(a, grid, fused, st);
+    else if (dt == SIGE_F16) launch_gather<f16>(a, grid, fused, st);
+    else launch_gather<bf16>(a, grid, fused, st);
+    SIGE_LAUNCH_CHECK(who);
+    return SIGE_OK;
+}
+
+extern "C" int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32_t Cout,
+                            const int32_t* indices, const int32_t* count, int32_t max_blocks,
+                            int32_t n_blocks, const void* residual_tiles, const void* residual,
+                            int32_t res_ld, void* y, int32_t y_ld, void* stream)
+{
+    clear_error();
+    const char* who = "sige_scatter";
+    int nl;
+    if (int rc = check_geom(g, who, nullptr, nullptr)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(out_tiles && indices && y, SIGE_ERR_INVALID_ARG, "%s: out_tiles, indices and y are required", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cout > 0 && y_ld >= Cout, SIGE_ERR_INVALID_ARG, "%s: need Cout > 0 and y_ld >= Cout", who);
+    SIGE_REQUIRE(residual == nullptr || res_ld >= Cout, SIGE_ERR_INVALID_ARG, "%s: res_ld must be >= Cout", who);
+    const size_t s = dtype_size(dt);
+    SIGE_REQUIRE((Cout * s) % 16 == 0 && (y_ld * s) % 16 == 0 && (residual == nullptr || (res_ld * s) % 16 == 0),
+                 SIGE_ERR_UNSUPPORTED, "%s: Cout and pixel strides must be multiples of %zu elements (16 bytes)",
+                 who, 16 / s);
+    SIGE_REQUIRE(aligned16(out_tiles) && aligned16(y) && aligned16(residual_tiles) && aligned16(residual),
+                 SIGE_ERR_UNSUPPORTED, "%s: pointers must be 16-byte aligned", who);
+    SIGE_REQUIRE(nl <= 65535, SIGE_ERR_UNSUPPORTED, "%s: more than 65535 blocks per launch", who);
+    if (nl == 0) return SIGE_OK;
+    ScatterArgs a;
+    a.out_tiles = out_tiles; a.res_tiles = residual_tiles; a.res_full = residual; a.y = y;
+    a.indices = indices; a.count = count;
+    a.Hout = g->H_out; a.Wout = g->W_out; a.V = (int)(Cout * s / 16);
+    a.y_ld_vec = (int)(y_ld * s / 16); a.res_ld_vec = residual ? (int)(res_ld * s / 16) : 0;
+    a.bh = g->block_h; a.bw = g->block_w;
+    a.max_blocks = max_blocks; a.n_host = n_blocks;
+    a.rows_per_wg = pick_rows(g->block_h, (size_t)g->block_w * Cout * s, nl);
+    dim3 grid((g->block_h + a.rows_per_wg - 1) / a.rows_per_wg, nl);
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == SIGE_F32) launch_scatter<float>(a, grid, st);
+    else if (dt == SIGE_F16) launch_scatter<f16>(a, grid, st);
+    else launch_scatter<bf16>(a, grid, st);
+    SIGE_LAUNCH_CHECK(who);
+    return SIGE_OK;
+}

@@ -1,0 +1,135 @@
+// sige_gn_stats: group statistics of a full tensor, folded into the per-channel
+// Scale+Shift that replaces the normalisation layer once the statistics of the
+// original activation are cached (Sec. 3.2 "Pre-computing normalization parameters").
+// Used by the pre-computation pass only: the sparse pass never touches full tensors.
+//
+// Pass 1 streams the tensor once, fully coalesced (every lane keeps one 16-byte
+// channel group and walks down the pixels), reduces per-group sums of x and x^2 in
+// LDS and adds them to the fp32 accumulators; pass 2 (one workgroup) turns the sums
+// into mean / biased variance and the folded scale and shift.
+#include "common.h"
+
+namespace sige {
+
+__global__ void gn_zero_kernel(float* mean, float* var, int groups)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < groups) { mean[i] = 0.0f; var[i] = 0.0f; }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gn_sum_kernel(const uint4* __restrict__ x, long n_pix, int V,
+                                                     int ld_vec, int cg, int groups,
+                                                     float* __restrict__ sum, float* __restrict__ sumsq)
+{
+    constexpr int N = Vec16<T>::N;
+    extern __shared__ float red[];  // [2][groups]
+    for (int i = threadIdx.x; i < 2 * groups; i += 256) red[i] = 0.0f;
+    __syncthreads();
+    const bool fixed = (256 % V) == 0;
+    if (fixed) {
+        const int cgv = threadIdx.x % V, ppi = 256 / V;  // pixels per workgroup step
+        float s[N], q[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) { s[i] = 0.0f; q[i] = 0.0f; }
+        for (long p = (long)blockIdx.x * ppi + threadIdx.x / V; p < n_pix; p += (long)gridDim.x * ppi) {
+            float f[N];
+            unpack<T>(x[p * ld_vec + cgv], f);
+#pragma unroll
+            for (int i = 0; i < N; ++i) { s[i] += f[i]; q[i] = fmaf(f[i], f[i], q[i]); }
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int g = (cgv * N + i) / cg;
+            atomicAdd(&red[g], s[i]);
+            atomicAdd(&red[groups + g], q[i]);
+        }
+    } else {
+        const long n_vec = n_pix * V;
+        for (long j = (long)blockIdx.x * 256 + threadIdx.x; j < n_vec; j += (long)gridDim.x * 256) {
+            const long p = j / V;
+            const int cgv = (int)(j - p * V);
+            float f[N];
+            unpack<T>(x[p * ld_vec + cgv], f);
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                const int g = (cgv * N + i) / cg;
+                atomicAdd(&red[g], f[i]);
+                atomicAdd(&red[groups + g], f[i] * f[i]);
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < groups; i += 256) {
+        atomicAdd(&sum[i], red[i]);
+        atomicAdd(&sumsq[i], red[groups + i]);
+    }
+}
+
+__global__ __launch_bounds__(256) void gn_fold_kernel(float* mean, float* var, float n, int C, int cg,
+                                                      int groups, const float* gamma, const float* beta,
+                                                      float eps, float* scale, float* shift)
+{
+    extern __shared__ float st[];  // [2][groups]: mean, var
+    for (int g = threadIdx.x; g < groups; g += 256) {
+        const float mu = mean[g] / n;
+        const float v = fmaxf(var[g] / n - mu * mu, 0.0f);
+        st[g] = mu;
+        st[groups + g] = v;
+    }
+    __syncthreads();
+    for (int g = threadIdx.x; g < groups; g += 256) { mean[g] = st[g]; var[g] = st[groups + g]; }
+    if (scale) {
+        for (int c = threadIdx.x; c < C; c += 256) {
+            const int g = c / cg;
+            const float sc = (gamma ? gamma[c] : 1.0f) * rsqrtf(st[groups + g] + eps);
+            scale[c] = sc;
+            shift[c] = (beta ? beta[c] : 0.0f) - st[g] * sc;
+        }
+    }
+}
+
+template <typename T>
+static void launch_sum(const void* x, long n_pix, int V, int ld_vec, int cg, int groups, float* mean,
+                       float* var, hipStream_t st)
+{
+    long want = (n_pix * V + 256L * 8 - 1) / (256L * 8);
+    int grid = (int)(want < 1 ? 1 : want > 2048 ? 2048 : want);
+    hipLaunchKernelGGL((gn_sum_kernel<T>), dim3(grid), dim3(256), 2 * groups * sizeof(float), st,
+                       (const uint4*)x, n_pix, V, ld_vec, cg, groups, mean, var);
+}
+
+}  // namespace sige
+
+using namespace sige;
+
+extern "C" int sige_gn_stats(const void* x, sige_dtype dt, int32_t H, int32_t W, int32_t C, int32_t x_ld,
+                             int32_t groups, const float* gamma, const float* beta, float eps,
+                             float* mean, float* var, float* scale, float* shift, void* stream)
+{
+    clear_error();
+    const char* who = "sige_gn_stats";
+    SIGE_REQUIRE(x && mean && var, SIGE_ERR_INVALID_ARG, "%s: x, mean and var are required", who);
+    SIGE_REQUIRE((scale == nullptr) == (shift == nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: scale and shift must be given together", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(H > 0 && W > 0 && C > 0 && groups > 0 && x_ld >= C, SIGE_ERR_INVALID_ARG, "%s: bad shape", who);
+    SIGE_REQUIRE(C % groups == 0, SIGE_ERR_INVALID_ARG, "%s: C must be divisible by groups", who);
+    SIGE_REQUIRE(groups <= 4096, SIGE_ERR_UNSUPPORTED, "%s: at most 4096 groups", who);
+    const size_t s = dtype_size(dt);
+    SIGE_REQUIRE((C * s) % 16 == 0 && (x_ld * s) % 16 == 0 && aligned16(x), SIGE_ERR_UNSUPPORTED,
+                 "%s: C and x_ld must be multiples of %zu elements and x 16-byte aligned", who, 16 / s);
+    hipStream_t st = (hipStream_t)stream;
+    const long n_pix = (long)H * W;
+    const int V = (int)(C * s / 16), ld_vec = (int)(x_ld * s / 16), cg = C / groups;
+    hipLaunchKernelGGL(gn_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, mean, var, groups);
+    SIGE_LAUNCH_CHECK("sige_gn_stats(zero)");
+    if (dt == SIGE_F32) launch_sum<float>(x, n_pix, V, ld_vec, cg, groups, mean, var, st);
+    else if (dt == SIGE_F16) launch_sum<f16>(x, n_pix, V, ld_vec, cg, groups, mean, var, st);
+    else launch_sum<bf16>(x, n_pix, V, ld_vec, cg, groups, mean, var, st);
+    SIGE_LAUNCH_CHECK("sige_gn_stats(sum)");
+    hipLaunchKernelGGL(gn_fold_kernel, dim3(1), dim3(256), 2 * groups * sizeof(float), st, mean, var,
+                       (float)n_pix * (float)cg, C, cg, groups, gamma, beta, eps, scale, shift);
+    SIGE_LAUNCH_CHECK("sige_gn_stats(fold)");
+    return SIGE_OK;
+}

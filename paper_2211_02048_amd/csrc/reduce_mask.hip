@@ -1,0 +1,269 @@
+// sige_reduce_mask: difference mask (Sec. 3.1 "Structured sparsity"), per-scale
+// downsample + dilate and reduction to the ordered active-block list (Sec. 3.2
+// "Tiling-based sparse convolution", Fig. "method").
+//
+// Kernel 1 streams both activations once (the only HBM-sized traffic here): each
+// lane owns one 16-byte vector, the lanes of one pixel vote with a wave ballot and
+// the first lanes of the wave store one mask byte per pixel.
+// Kernel 2 is a single workgroup: every wave tests whole blocks against the pooled,
+// dilated mask and leaves one flag per block in LDS; an ordered ballot/popcount
+// prefix sum then compacts the flags into the row-major index list.
+#include "common.h"
+
+namespace sige {
+
+template <typename T>
+__device__ __forceinline__ bool vec_differs(const uint4& o, const uint4& e, float tau)
+{
+    float fo[Vec16<T>::N], fe[Vec16<T>::N];
+    unpack<T>(o, fo);
+    unpack<T>(e, fe);
+    bool any = false;
+#pragma unroll
+    for (int i = 0; i < Vec16<T>::N; ++i) any |= !(fabsf(fe[i] - fo[i]) <= tau);
+    return any;
+}
+
+// V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
+template <typename T, int U>
+__global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ a_o,
+                                                      const uint4* __restrict__ a_e, long n_vec,
+                                                      int log2v, float tau, long n_pix,
+                                                      uint8_t* __restrict__ mask)
+{
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const long n_waves = (long)gridDim.x * (blockDim.x >> 6);
+    const int V = 1 << log2v;
+    const int ppw = 64 >> log2v;  // pixels per wave step
+    const unsigned long long gmask = V == 64 ? ~0ull : ((1ull << V) - 1ull);
+    for (long base = wave * (64L * U); base < n_vec; base += n_waves * (64L * U)) {
+        uint4 o[U], e[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            long idx = base + u * 64 + lane;
+            if (idx < n_vec) {
+                o[u] = load_stream(a_o + idx);
+                e[u] = load_stream(a_e + idx);
+            } else {
+                o[u] = make_uint4(0, 0, 0, 0);
+                e[u] = o[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            unsigned long long b = __ballot(vec_differs<T>(o[u], e[u], tau));
+            long pix = ((base + u * 64) >> log2v) + lane;
+            if (lane < ppw && pix < n_pix) mask[pix] = ((b >> (lane << log2v)) & gmask) ? 1 : 0;
+        }
+    }
+}
+
+// Any number of vectors per pixel: one wave per pixel.
+template <typename T>
+__global__ __launch_bounds__(256) void diff_mask_wave(const uint4* __restrict__ a_o,
+                                                      const uint4* __restrict__ a_e, int V, float tau,
+                                                      long n_pix, uint8_t* __restrict__ mask)
+{
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const long n_waves = (long)gridDim.x * (blockDim.x >> 6);
+    for (long pix = wave; pix < n_pix; pix += n_waves) {
+        bool any = false;
+        for (int j = lane; j < V; j += 64)
+            any |= vec_differs<T>(a_o[pix * V + j], a_e[pix * V + j], tau);
+        unsigned long long b = __ballot(any);
+        if (lane == 0) mask[pix] = b ? 1 : 0;
+    }
+}
+
+// Channel counts whose pixel is not a whole number of 16-byte vectors: one thread per pixel.
+template <typename T>
+__global__ __launch_bounds__(256) void diff_mask_scalar(const T* __restrict__ a_o,
+                                                        const T* __restrict__ a_e, int C, float tau,
+                                                        long n_pix, uint8_t* __restrict__ mask)
+{
+    long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= n_pix) return;
+    bool any = false;
+    for (int c = 0; c < C; ++c)
+        any |= !(fabsf(to_f32(a_e[pix * C + c]) - to_f32(a_o[pix * C + c])) <= tau);
+    mask[pix] = any ? 1 : 0;
+}
+
+struct ListArgs {
+    const uint8_t* mask;
+    int Hm, Wm, pool_log2, dilate;
+    int Hin, Win, bh, bw, stride, pad, th, tw;
+    int nby, nbx;
+    int32_t* indices;
+    int max_blocks;
+    int32_t* count;
+    int words;  // 1: pooled windows may be read as aligned 32-bit words
+};
+
+__global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
+{
+    extern __shared__ uint8_t flags[];
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nb = a.nby * a.nbx;
+    const int p = a.pool_log2;
+
+    for (int blk = w; blk < nb; blk += 16) {
+        const int by = blk / a.nbx, bx = blk - by * a.nbx;
+        // input tile of the block, clipped to the image, then grown by the dilation radius
+        int fy0 = by * a.bh * a.stride - a.pad, fx0 = bx * a.bw * a.stride - a.pad;
+        int fy1 = min(fy0 + a.th, a.Hin), fx1 = min(fx0 + a.tw, a.Win);
+        fy0 = max(fy0, 0);
+        fx0 = max(fx0, 0);
+        const int ry0 = max(fy0 - a.dilate, 0), ry1 = min(fy1 + a.dilate, a.Hin);
+        const int rx0 = max(fx0 - a.dilate, 0), rx1 = min(fx1 + a.dilate, a.Win);
+        const int ncols = rx1 - rx0, n = (ry1 - ry0) * ncols;
+        bool any = false;
+        for (int e = lane; e < n; e += 64) {
+            const int y = ry0 + e / ncols, x = rx0 + e % ncols;
+            if (p == 0) {
+                any |= a.mask[(long)y * a.Wm + x] != 0;
+            } else {
+                const int sy1 = min((y + 1) << p, a.Hm), sx0 = x << p, sx1 = min((x + 1) << p, a.Wm);
+                for (int sy = y << p; sy < sy1; ++sy) {
+                    if (a.words) {
+                        const uint32_t* row = reinterpret_cast<const uint32_t*>(a.mask + (long)sy * a.Wm);
+                        for (int sx = sx0 >> 2; sx < (sx1 >> 2); ++sx) any |= row[sx] != 0;
+                    } else {
+                        for (int sx = sx0; sx < sx1; ++sx) any |= a.mask[(long)sy * a.Wm + sx] != 0;
+                    }
+                }
+            }
+        }
+        unsigned long long b = __ballot(any);
+        if (lane == 0) flags[blk] = b ? 1 : 0;
+    }
+    __syncthreads();
+
+    // ordered compaction: blocks are visited in row-major order, 1024 at a time
+    int base = 0;
+    for (int c0 = 0; c0 < nb; c0 += 1024) {
+        const int blk = c0 + tid;
+        const int f = blk < nb ? flags[blk] : 0;
+        const unsigned long long b = __ballot(f);
+        const int pre = __popcll(b & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[w] = __popcll(b);
+        __syncthreads();
+        int off = base, total = 0;
+        for (int i = 0; i < 16; ++i) {
+            const int t = wave_tot[i];
+            if (i < w) off += t;
+            total += t;
+        }
+        if (f) {
+            const int slot = off + pre;
+            if (slot < a.max_blocks) {
+                const int by = blk / a.nbx;
+                a.indices[2 * slot] = by * a.bh;
+                a.indices[2 * slot + 1] = (blk - by * a.nbx) * a.bw;
+            }
+        }
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) *a.count = base;
+}
+
+template <typename T>
+static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, int C, float tau,
+                       uint8_t* mask, hipStream_t st)
+{
+    const long n_pix = (long)Hm * Wm;
+    const size_t bytes = (size_t)C * sizeof(T);
+    if (bytes % 16 == 0 && aligned16(a_orig) && aligned16(a_edit)) {
+        const int V = (int)(bytes / 16);
+        const long n_vec = n_pix * V;
+        if (V <= 64 && (V & (V - 1)) == 0) {
+            int log2v = 0;
+            while ((1 << log2v) < V) ++log2v;
+            constexpr int U = 4;
+            long steps = (n_vec + 256L * U - 1) / (256L * U);
+            int grid = (int)(steps < 4096 ? steps : 4096);
+            hipLaunchKernelGGL((diff_mask_pow2<T, U>), dim3(grid), dim3(256), 0, st,
+                               (const uint4*)a_orig, (const uint4*)a_edit, n_vec, log2v, tau, n_pix, mask);
+        } else {
+            long blocks = (n_pix + 3) / 4;
+            int grid = (int)(blocks < 8192 ? blocks : 8192);
+            hipLaunchKernelGGL((diff_mask_wave<T>), dim3(grid), dim3(256), 0, st, (const uint4*)a_orig,
+                               (const uint4*)a_edit, V, tau, n_pix, mask);
+        }
+    } else {
+        long blocks = (n_pix + 255) / 256;
+        SIGE_REQUIRE(blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "sige_reduce_mask: mask too large");
+        hipLaunchKernelGGL((diff_mask_scalar<T>), dim3((int)blocks), dim3(256), 0, st, (const T*)a_orig,
+                           (const T*)a_edit, C, tau, n_pix, mask);
+    }
+    SIGE_LAUNCH_CHECK("sige_reduce_mask(diff)");
+    return SIGE_OK;
+}
+
+}  // namespace sige
+
+using namespace sige;
+
+extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
+                                int32_t Wm, int32_t C, float tau, const uint8_t* mask_in,
+                                int32_t pool_log2, int32_t dilate, const sige_geom* g,
+                                uint8_t* mask_out, int32_t* indices, int32_t max_blocks,
+                                int32_t* count, void* stream)
+{
+    clear_error();
+    const char* who = "sige_reduce_mask";
+    int th, tw;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    const bool diff_mode = a_orig != nullptr || a_edit != nullptr;
+    SIGE_REQUIRE(diff_mode != (mask_in != nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: give either (a_orig, a_edit) or mask_in, not both and not neither", who);
+    SIGE_REQUIRE(Hm > 0 && Wm > 0, SIGE_ERR_INVALID_ARG, "%s: mask size must be positive", who);
+    SIGE_REQUIRE(pool_log2 >= 0 && pool_log2 <= 12 && dilate >= 0, SIGE_ERR_INVALID_ARG,
+                 "%s: pool_log2 must be in [0, 12] and dilate >= 0", who);
+    const int ps = 1 << pool_log2;
+    SIGE_REQUIRE((Hm + ps - 1) / ps == g->H_in && (Wm + ps - 1) / ps == g->W_in, SIGE_ERR_INVALID_ARG,
+                 "%s: pooled mask %dx%d does not match the conv input %dx%d", who, (Hm + ps - 1) / ps,
+                 (Wm + ps - 1) / ps, g->H_in, g->W_in);
+    SIGE_REQUIRE(indices != nullptr && count != nullptr, SIGE_ERR_INVALID_ARG,
+                 "%s: indices and count are required", who);
+    SIGE_REQUIRE(max_blocks >= 0, SIGE_ERR_INVALID_ARG, "%s: max_blocks is negative", who);
+    const long nby = (g->H_out + g->block_h - 1) / g->block_h, nbx = (g->W_out + g->block_w - 1) / g->block_w;
+    SIGE_REQUIRE(nby * nbx <= 131072, SIGE_ERR_CAPACITY,
+                 "%s: block grid %ldx%ld exceeds 131072 blocks", who, nby, nbx);
+    hipStream_t st = (hipStream_t)stream;
+    const uint8_t* mask = mask_in;
+    if (diff_mode) {
+        SIGE_REQUIRE(a_orig && a_edit, SIGE_ERR_INVALID_ARG, "%s: a_orig and a_edit are both required", who);
+        SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+        SIGE_REQUIRE(C > 0, SIGE_ERR_INVALID_ARG, "%s: C must be positive", who);
+        SIGE_REQUIRE(mask_out != nullptr, SIGE_ERR_INVALID_ARG,
+                     "%s: mask_out is required when the mask is computed from activations", who);
+        int rc = dt == SIGE_F32   ? launch_diff<float>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, st)
+                 : dt == SIGE_F16 ? launch_diff<f16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, st)
+                                  : launch_diff<bf16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, st);
+        if (rc) return rc;
+        mask = mask_out;
+    }
+    ListArgs a;
+    a.mask = mask;
+    a.Hm = Hm; a.Wm = Wm; a.pool_log2 = pool_log2; a.dilate = dilate;
+    a.Hin = g->H_in; a.Win = g->W_in; a.bh = g->block_h; a.bw = g->block_w;
+    a.stride = g->stride; a.pad = g->pad; a.th = th; a.tw = tw;
+    a.nby = (int)nby; a.nbx = (int)nbx;
+    a.indices = indices; a.max_blocks = max_blocks; a.count = count;
+    a.words = (pool_log2 >= 2 && Wm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & 3u) == 0) ? 1 : 0;
+    const size_t lds = ((size_t)(nby * nbx) + 15) & ~(size_t)15;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)block_list_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "%s: cannot reserve %zu bytes of LDS: %s", who, lds,
+                     hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(block_list_kernel, dim3(1), dim3(1024), lds, st, a);
+    SIGE_LAUNCH_CHECK("sige_reduce_mask(list)");
+    return SIGE_OK;
+}

@@ -1,0 +1,102 @@
+"""Orchestration of the library calls for one wrapped convolution (Fig. "method"):
+reduce -> gather -> conv -> scatter.  No arithmetic happens here; the class only owns
+device buffers (packed weight, block list, tile workspaces) and issues the C-ABI calls
+in order on torch's current stream.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import api
+
+
+class Workspace:
+    """Tile buffers shared by layers that run one after another on one stream."""
+
+    def __init__(self, device):
+        self.device = device
+        self._buf = {}
+
+    def get(self, name: str, numel: int, dtype) -> torch.Tensor:
+        key = (name, dtype)
+        b = self._buf.get(key)
+        if b is None or b.numel() < numel:
+            b = torch.empty(max(numel, 1), dtype=dtype, device=self.device)
+            self._buf[key] = b
+        return b[:numel]
+
+
+class BlockList:
+    """Device-side ordered list of active blocks for one (resolution, block, kernel)."""
+
+    def __init__(self, g: api.Geom, device, max_blocks=None):
+        self.g = g
+        self.max_blocks = g.grid_blocks if max_blocks is None else max_blocks
+        self.indices = torch.zeros((max(self.max_blocks, 1), 2), dtype=torch.int32, device=device)
+        self.count = torch.zeros(1, dtype=torch.int32, device=device)
+        self.n_host = -1
+
+    def reduce(self, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None, mask_out=None, pool_log2=0,
+               dilate=0):
+        api.sige_reduce_mask(self.g, self.indices, self.count, a_orig=a_orig, a_edit=a_edit, tau=tau,
+                             mask_in=mask_in, mask_out=mask_out, pool_log2=pool_log2, dilate=dilate,
+                             max_blocks=self.max_blocks)
+        self.n_host = -1
+
+    def all_active(self):
+        """Every block of the grid, row-major: the dense / pre-computation pass."""
+        g = self.g
+        ys = torch.arange(0, g.H_out, g.block_h, dtype=torch.int32)
+        xs = torch.arange(0, g.W_out, g.block_w, dtype=torch.int32)
+        idx = torch.stack(torch.meshgrid(ys, xs, indexing="ij"), dim=-1).reshape(-1, 2)
+        n = idx.shape[0]
+        assert n <= self.max_blocks
+        self.indices[:n].copy_(idx)
+        self.count.fill_(n)
+        self.n_host = n
+        return self
+
+    def sync_count(self) -> int:
+        """One device->host readback of the block count (once per edit and list)."""
+        n = int(self.count.item())
+        if n > self.max_blocks:
+            raise api.SigeError(3, f"{n} active blocks exceed max_blocks={self.max_blocks}")
+        self.n_host = n
+        return n
+
+
+class SigeConv:
+    """One convolution wrapped for sparse update: packed weight + geometry."""
+
+    def __init__(self, w_oihw: torch.Tensor, bias, H_in: int, W_in: int, block, stride: int = 1,
+                 pad=None, up: int = 0):
+        self.Cout, self.Cin, k, _ = w_oihw.shape
+        self.g = api.geom(H_in, W_in, block, k, stride, pad)
+        self.dtype = w_oihw.dtype
+        self.device = w_oihw.device
+        self.packed = api.sige_pack_weight(w_oihw)
+        self.bias = None if bias is None else bias.to(self.device, torch.float32).contiguous()
+        self.up = up
+
+    def tiles_numel(self, n):
+        return n * self.g.tile_h * self.g.tile_w * self.Cin
+
+    def out_numel(self, n):
+        return n * self.g.block_h * self.g.block_w * self.Cout
+
+    def forward(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None,
+                act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t"):
+        """gather(x) -> conv -> scatter into y (in place).  Returns the output tiles."""
+        g, n = self.g, blocks.n_host
+        cap = blocks.max_blocks if n < 0 else max(n, 1)
+        tiles = ws.get("tiles", self.tiles_numel(cap), self.dtype)
+        out_tiles = ws.get("out_" + tag, self.out_numel(cap), self.dtype)
+        api.sige_gather(x, g, blocks.indices, blocks.count, tiles, n_blocks=n, scale=scale, shift=shift,
+                        act=act, up=self.up, C=self.Cin, max_blocks=cap)
+        api.sige_conv(tiles, g, self.Cin, self.Cout, self.packed, self.bias, blocks.count, out_tiles,
+                      n_blocks=n, max_blocks=cap)
+        if scatter:
+            api.sige_scatter(out_tiles, g, blocks.indices, blocks.count, y, n_blocks=n,
+                             residual_tiles=residual_tiles, residual=residual, Cout=self.Cout,
+                             max_blocks=cap)
+        return out_tiles

@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the public header declares, and refuses bad arguments synchronously with the
+documented codes (nothing is enqueued on those paths)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2211_02048_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x10000)  # never dereferenced: every call below fails validation first
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(api.LIB_PATH):
+        from paper_2211_02048_amd import build
+        build.build()
+    return api.lib()
+
+
+def test_exports_match_header(L):
+    hdr = open(os.path.join(ROOT, "include", "sige.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(sige_[a-z0-9_]+)\s*\(", hdr)))
+    assert declared == sorted(api.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.sige_version() >= 1
+
+
+def good_geom():
+    return api.geom(64, 64, 6, 3, 1, 1)
+
+
+def err(L):
+    return L.sige_last_error().decode()
+
+
+def test_geometry_errors(L):
+    g = good_geom()
+    g.block_h = 0
+    assert L.sige_gather(FAKE, 0, 64, 64, 0, ctypes.byref(g), FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 1
+    assert "block" in err(L)
+    g = good_geom()
+    g.k = 2
+    assert L.sige_conv(FAKE, 0, ctypes.byref(g), 64, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 1
+    assert "odd" in err(L)
+    g = good_geom()
+    g.H_out = 63
+    assert L.sige_scatter(FAKE, 0, ctypes.byref(g), 64, FAKE, FAKE, 8, -1, None, None, 0, FAKE, 64, None) == 1
+    assert L.sige_gather(FAKE, 0, 64, 64, 0, None, FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 1
+
+
+def test_pointer_and_capacity_errors(L):
+    g = good_geom()
+    gp = ctypes.byref(g)
+    # required pointer missing
+    assert L.sige_gather(None, 0, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 1
+    # host n_blocks beyond the capacity
+    assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, 9, None, None, 0, FAKE, None) == 3
+    assert "exceeds" in err(L)
+    assert L.sige_conv(FAKE, 0, gp, 64, 64, FAKE, None, FAKE, 8, 9, FAKE, None) == 3
+    assert L.sige_scatter(FAKE, 0, gp, 64, FAKE, FAKE, 8, 9, None, None, 0, FAKE, 64, None) == 3
+    # neither a host count nor a device count
+    assert L.sige_conv(FAKE, 0, gp, 64, 64, FAKE, None, None, 8, -1, FAKE, None) == 1
+    # channel counts the vector kernels do not cover are refused, never silently handled
+    assert L.sige_gather(FAKE, 0, 3, 3, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 2
+    assert L.sige_conv(FAKE, 1, gp, 24, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
+    assert L.sige_conv(FAKE, 0, gp, 4, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
+    # scale without shift
+    assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, -1, FAKE, None, 0, FAKE, None) == 1
+    # unknown dtype
+    assert L.sige_gather(FAKE, 7, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 1
+    # zero blocks on the host: accepted, nothing to do
+    assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, 0, None, None, 0, FAKE, None) == 0
+    assert err(L) == ""
+
+
+def test_reduce_mask_errors(L):
+    g = good_geom()
+    gp = ctypes.byref(g)
+    f = ctypes.c_float(1e-6)
+    # both sources / neither source
+    assert L.sige_reduce_mask(FAKE, FAKE, 0, 64, 64, 64, f, FAKE, 0, 0, gp, FAKE, FAKE, 121, FAKE, None) == 1
+    assert L.sige_reduce_mask(None, None, 0, 64, 64, 64, f, None, 0, 0, gp, FAKE, FAKE, 121, FAKE, None) == 1
+    assert "either" in err(L)
+    # activation mode needs mask_out
+    assert L.sige_reduce_mask(FAKE, FAKE, 0, 64, 64, 64, f, None, 0, 0, gp, None, FAKE, 121, FAKE, None) == 1
+    # pooled mask size must match the conv input
+    assert L.sige_reduce_mask(None, None, 0, 100, 64, 0, f, FAKE, 0, 0, gp, None, FAKE, 121, FAKE, None) == 1
+    # block grid beyond the stated maximum
+    big = api.geom(2048, 2048, 4, 1, 1, 0)
+    assert L.sige_reduce_mask(None, None, 0, 2048, 2048, 0, f, FAKE, 0, 0, ctypes.byref(big), None, FAKE, 8,
+                              FAKE, None) == 3
+
+
+def test_attention_and_helper_errors(L):
+    f = ctypes.c_float(0.1)
+    assert L.sige_sparse_attn(FAKE, 320, FAKE, FAKE, 320, 0, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 2
+    assert L.sige_sparse_attn(FAKE, 320, FAKE, FAKE, 320, 2, 16, 64, 8, 36, f, FAKE, 320, None, 0, None) == 2
+    assert L.sige_sparse_attn(FAKE, 100, FAKE, FAKE, 320, 2, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1
+    assert L.sige_sparse_attn(None, 320, FAKE, FAKE, 320, 2, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1
+    assert L.sige_sparse_attn(None, 320, None, None, 320, 2, 0, 64, 8, 40, f, None, 320, None, 0, None) == 0
+    assert L.sige_packed_weight_bytes(1, 128, 128, 3) == 128 * 128 * 9 * 2
+    assert L.sige_packed_weight_bytes(0, 3, 64, 3) == 32 * 64 * 9 * 4  # Cout padded to 32
+    assert L.sige_packed_weight_bytes(1, 128, 24, 3) == 0
+    assert L.sige_pack_weight(FAKE, 1, 128, 24, 3, FAKE, None) == 2
+    assert L.sige_gn_stats(FAKE, 1, 16, 16, 30, 32, 4, None, None, f, FAKE, FAKE, None, None, None) == 1
+    assert L.sige_sparse_attn_workspace_bytes(16384, 4096, 8, 40) == 0     # enough queries: no split
+    assert L.sige_sparse_attn_workspace_bytes(64, 4096, 8, 40) > 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(api, "_lib", None)
+    monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(api.SigeError):
+        api.sige_version()

@@ -1,0 +1,479 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by
+element.  Masks, block lists and pure copies bit-exact; floating results within
+1e-4 (fp32) / 1e-2 (fp16, bf16) of the oracle, relative to max(|ref|, rms(ref))."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import assert_close, assert_mostly_close, dev, expected_tiles, f64, outside_blocks_mask
+from paper_2211_02048_amd import api, inputs
+from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
+
+pytestmark = pytest.mark.gpu
+DT = inputs.DTYPES
+
+
+def run_reduce(g, *, a_orig=None, a_edit=None, tau=0.0, mask=None, pool_log2=0, dilate=0, max_blocks=None):
+    bl = BlockList(g, "cuda", max_blocks)
+    bl.indices.fill_(-7)
+    mask_out = None
+    if a_orig is not None:
+        mask_out = torch.full(a_orig.shape[:2], 9, dtype=torch.uint8, device="cuda")
+    bl.reduce(a_orig=a_orig, a_edit=a_edit, tau=tau, mask_in=mask, mask_out=mask_out, pool_log2=pool_log2,
+              dilate=dilate)
+    torch.cuda.synchronize()
+    return bl, mask_out
+
+
+# ------------------------------------------------------------------ a1-a3: mask and block list
+
+@pytest.mark.parametrize("seed", range(1001, 1021))
+def test_reduce_mask_config1_bit_exact(oracle, seed):
+    cfg = inputs.config1(seed=seed)
+    g = api.geom(64, 64, cfg["block"], 3, 1, 1)
+    bl, mask = run_reduce(g, a_orig=dev(cfg["a_orig"]), a_edit=dev(cfg["a_edit"]), tau=cfg["tau"])
+    want_mask = oracle.diff_mask(cfg["a_orig"].numpy(), cfg["a_edit"].numpy(), cfg["tau"])
+    want = oracle.active_blocks(want_mask, 64, 64, 6, 6, 3, 1, 1)
+    assert np.array_equal(mask.cpu().numpy(), want_mask)
+    n = int(bl.count.item())
+    assert n == len(want) and 0 < n < 121
+    assert np.array_equal(bl.indices[:n].cpu().numpy(), want)
+    assert (bl.indices[n:] == -7).all()  # rows beyond the count are untouched
+
+
+@pytest.mark.parametrize("dtype,C", [("f16", 128), ("bf16", 320), ("f32", 3), ("f16", 8), ("f32", 256),
+                                     ("bf16", 512), ("f16", 24)])
+def test_diff_mask_channel_paths(oracle, dtype, C):
+    rng = np.random.default_rng(C)
+    H, W = 37, 53
+    a = torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(DT[dtype])
+    e = a.clone()
+    ys, xs = rng.integers(0, H, 40), rng.integers(0, W, 40)
+    cs = rng.integers(0, C, 40)
+    for y, x, c in zip(ys, xs, cs):
+        e[y, x, c] = e[y, x, c] + 1.0
+    e[0, 0, C - 1] = float("nan")
+    e[H - 1, W - 1, 0] = e[H - 1, W - 1, 0] + 2.0
+    g = api.geom(H, W, 5, 3, 1, 1)
+    for tau in (0.0, 1e-6, 1.5):
+        bl, mask = run_reduce(g, a_orig=dev(a), a_edit=dev(e), tau=tau)
+        want_mask = oracle.diff_mask(a.float().numpy(), e.float().numpy(), tau)
+        assert np.array_equal(mask.cpu().numpy(), want_mask), (dtype, C, tau)
+        want = oracle.active_blocks(want_mask, H, W, 5, 5, 3, 1, 1)
+        n = int(bl.count.item())
+        assert n == len(want) and np.array_equal(bl.indices[:n].cpu().numpy(), want)
+
+
+def test_block_list_pool_dilate_geometries(oracle):
+    rng = np.random.default_rng(42)
+    cases = 0
+    for Hm, Wm in [(100, 76), (64, 64), (33, 47), (256, 256)]:
+        for pool in (0, 1, 2, 3):
+            Hin, Win = -(-Hm // (1 << pool)), -(-Wm // (1 << pool))
+            for (k, s, p) in [(3, 1, 1), (1, 1, 0), (3, 2, 1)]:
+                for b in (4, 6, 16):
+                    for r in (0, 1, 5):
+                        if Hin + 2 * p < k or Win + 2 * p < k:
+                            continue
+                        m = (rng.random((Hm, Wm)) < rng.choice([0.0005, 0.005, 0.05])).astype(np.uint8)
+                        g = api.geom(Hin, Win, b, k, s, p)
+                        bl, _ = run_reduce(g, mask=torch.from_numpy(m).cuda(), pool_log2=pool, dilate=r)
+                        lv = oracle.level_mask(m, pool, r)
+                        want = oracle.active_blocks(lv, g.H_out, g.W_out, b, b, k, s, p)
+                        n = int(bl.count.item())
+                        assert n == len(want), (Hm, Wm, pool, k, s, b, r)
+                        assert np.array_equal(bl.indices[:n].cpu().numpy(), want)
+                        cases += 1
+    assert cases > 300
+
+
+def test_block_list_degenerate_and_overflow(oracle):
+    H = W = 50
+    g = api.geom(H, W, 6, 3, 1, 1)
+    empty = torch.zeros((H, W), dtype=torch.uint8, device="cuda")
+    bl, _ = run_reduce(g, mask=empty)
+    assert int(bl.count.item()) == 0 and (bl.indices == -7).all()
+    full = torch.ones((H, W), dtype=torch.uint8, device="cuda")
+    bl, _ = run_reduce(g, mask=full)
+    want = np.array([(y, x) for y in range(0, H, 6) for x in range(0, W, 6)], np.int32)
+    assert int(bl.count.item()) == 81 and np.array_equal(bl.indices.cpu().numpy(), want)
+    # capacity smaller than the number of active blocks: true count, first rows only, no overrun
+    bl, _ = run_reduce(g, mask=full, max_blocks=10)
+    assert int(bl.count.item()) == 81
+    assert np.array_equal(bl.indices.cpu().numpy(), want[:10])
+    with pytest.raises(api.SigeError):
+        bl.sync_count()
+    # a grid larger than one compaction pass (1024 blocks per pass)
+    Hb = 300
+    gb = api.geom(Hb, Hb, 4, 1, 1, 0)
+    m = (np.random.default_rng(0).random((Hb, Hb)) < 0.01).astype(np.uint8)
+    bl, _ = run_reduce(gb, mask=torch.from_numpy(m).cuda())
+    want = oracle.active_blocks(m, Hb, Hb, 4, 4, 1, 1, 0)
+    assert gb.grid_blocks == 5625 and int(bl.count.item()) == len(want)
+    assert np.array_equal(bl.indices[:len(want)].cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------ a4 / a6: gather and scatter
+
+def random_blocks(rng, g, n):
+    ids = rng.choice(g.grid_blocks, size=min(n, g.grid_blocks), replace=False)
+    ids.sort()
+    nbx = -(-g.W_out // g.block_w)
+    return np.array([((i // nbx) * g.block_h, (i % nbx) * g.block_w) for i in ids], np.int32)
+
+
+@pytest.mark.parametrize("dtype,C,H,W,b,k,s", [
+    ("f32", 64, 64, 64, 6, 3, 1), ("f16", 128, 70, 90, 16, 3, 1), ("bf16", 320, 33, 31, 4, 1, 1),
+    ("f16", 64, 64, 48, 8, 3, 2), ("f32", 8, 20, 20, 6, 5, 1), ("f16", 24, 41, 29, 6, 3, 1)])
+def test_gather_unfused_bit_exact_and_fused(oracle, dtype, C, H, W, b, k, s):
+    rng = np.random.default_rng(C + H)
+    td = DT[dtype]
+    g = api.geom(H, W, b, k, s, k // 2)
+    x = torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(td)
+    blocks = random_blocks(rng, g, 13)
+    # make sure corner blocks (zero padding on two sides, partial blocks) are included
+    nby, nbx = -(-g.H_out // b), -(-g.W_out // b)
+    corners = np.array([(0, 0), ((nby - 1) * b, (nbx - 1) * b)], np.int32)
+    blocks = np.unique(np.concatenate([blocks, corners]), axis=0)
+    n = len(blocks)
+    idx = torch.from_numpy(blocks).cuda()
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    th, tw = g.tile_h, g.tile_w
+    tiles = torch.full((n + 2, th, tw, C), 3.0, dtype=td, device="cuda")
+    api.sige_gather(dev(x), g, idx, cnt, tiles, n_blocks=n)
+    want = expected_tiles(oracle, f64(x), blocks, th, tw, s, k // 2, None, None, 0)
+    assert np.array_equal(f64(tiles[:n]), want)
+    assert (tiles[n:] == 3.0).all()  # tiles beyond the count are untouched
+    # device-side count (launch sized by capacity) gives the same bytes
+    tiles2 = torch.full((n + 2, th, tw, C), 3.0, dtype=td, device="cuda")
+    api.sige_gather(dev(x), g, idx, cnt, tiles2, n_blocks=-1)
+    assert torch.equal(tiles, tiles2)
+    # fused Scale+Shift + SiLU / ReLU
+    scale = torch.from_numpy(rng.uniform(0.5, 1.5, C).astype(np.float32))
+    shift = torch.from_numpy(rng.uniform(-0.5, 0.5, C).astype(np.float32))
+    for act in (api.ACT_SILU, api.ACT_RELU, api.ACT_NONE):
+        api.sige_gather(dev(x), g, idx, cnt, tiles, n_blocks=n, scale=dev(scale), shift=dev(shift), act=act)
+        want = expected_tiles(oracle, f64(x), blocks, th, tw, s, k // 2, f64(scale), f64(shift), act)
+        assert_close(tiles[:n], want, td, f"gather act={act}")
+        # padding is exactly zero (not act(shift))
+        assert (f64(tiles[:n])[want == 0.0] == 0.0).all()
+    api.sige_gather(dev(x), g, idx, cnt, tiles, n_blocks=n, act=api.ACT_SILU)  # activation without scale
+    want = expected_tiles(oracle, f64(x), blocks, th, tw, s, k // 2, None, None, api.ACT_SILU)
+    assert_close(tiles[:n], want, td, "gather silu only")
+
+
+def test_gather_strided_source_and_upsample(oracle):
+    rng = np.random.default_rng(5)
+    td = torch.float16
+    H, W, C, LD = 24, 32, 32, 96
+    buf = torch.from_numpy(rng.standard_normal((H, W, LD)).astype(np.float32)).to(td).cuda()
+    x = buf[:, :, 32:64]  # channel slice of a wider buffer
+    g = api.geom(H, W, 8, 3, 1, 1)
+    blocks = random_blocks(rng, g, 5)
+    idx = torch.from_numpy(blocks).cuda()
+    cnt = torch.tensor([len(blocks)], dtype=torch.int32, device="cuda")
+    tiles = torch.zeros((len(blocks), 10, 10, C), dtype=td, device="cuda")
+    api.sige_gather(x, g, idx, cnt, tiles, n_blocks=len(blocks), C=C, x_ld=LD)
+    want = expected_tiles(oracle, f64(x), blocks, 10, 10, 1, 1, None, None, 0)
+    assert np.array_equal(f64(tiles), want)
+    # nearest-neighbour x2 up-sampling folded into the gather address
+    src = torch.from_numpy(rng.standard_normal((H // 2, W // 2, C)).astype(np.float32)).to(td).cuda()
+    api.sige_gather(src, g, idx, cnt, tiles, n_blocks=len(blocks), up=1)
+    up = f64(src).repeat(2, axis=0).repeat(2, axis=1)
+    want = expected_tiles(oracle, up, blocks, 10, 10, 1, 1, None, None, 0)
+    assert np.array_equal(f64(tiles), want)
+
+
+@pytest.mark.parametrize("dtype,C,H,W,b", [("f32", 64, 64, 64, 6), ("f16", 128, 70, 90, 16),
+                                           ("bf16", 256, 33, 31, 4), ("f16", 8, 19, 23, 5)])
+def test_scatter_bit_exact_and_untouched_outside(oracle, dtype, C, H, W, b):
+    rng = np.random.default_rng(H * W)
+    td = DT[dtype]
+    g = api.geom(H, W, b, 3, 1, 1)
+    blocks = random_blocks(rng, g, 11)
+    nby, nbx = -(-H // b), -(-W // b)
+    blocks = np.unique(np.concatenate([blocks, np.array([((nby - 1) * b, (nbx - 1) * b)], np.int32)]), axis=0)
+    n = len(blocks)
+    idx = torch.from_numpy(blocks).cuda()
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    out_tiles = torch.from_numpy(rng.standard_normal((n + 1, b, b, C)).astype(np.float32)).to(td).cuda()
+    cache = torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(td).cuda()
+    y = cache.clone()
+    api.sige_scatter(out_tiles, g, idx, cnt, y, n_blocks=n)
+    # Fig. "pipeline" (b): active blocks replaced, everything else is the cache bit for bit
+    new_full = np.zeros((H, W, C))
+    ot = f64(out_tiles)
+    for i, (y0, x0) in enumerate(blocks):
+        hh, ww = min(b, H - y0), min(b, W - x0)
+        new_full[y0:y0 + hh, x0:x0 + ww] = ot[i, :hh, :ww]
+    want = oracle.select_blocks(new_full, f64(cache), blocks, b, b)
+    assert np.array_equal(f64(y), want)
+    # zero blocks: nothing changes
+    y2 = cache.clone()
+    zero = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.sige_scatter(out_tiles, g, idx, zero, y2, n_blocks=-1)
+    api.sige_scatter(out_tiles, g, idx, zero, y2, n_blocks=0)
+    assert torch.equal(y2, cache)
+    # residual tiles + full residual are added in fp32 and rounded once
+    res_t = torch.from_numpy(rng.standard_normal((n + 1, b, b, C)).astype(np.float32)).to(td).cuda()
+    res_f = torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(td).cuda()
+    y3 = cache.clone()
+    api.sige_scatter(out_tiles, g, idx, cnt, y3, n_blocks=-1, residual_tiles=res_t, residual=res_f)
+    rt = f64(res_t)
+    for i, (y0, x0) in enumerate(blocks):
+        hh, ww = min(b, H - y0), min(b, W - x0)
+        new_full[y0:y0 + hh, x0:x0 + ww] = ot[i, :hh, :ww] + rt[i, :hh, :ww] + f64(res_f)[y0:y0 + hh, x0:x0 + ww]
+    want = oracle.select_blocks(new_full, f64(cache), blocks, b, b)
+    assert_close(y3, want, td, "scatter+residual", tol=1e-6 if td == torch.float32 else 2e-3)
+    out = outside_blocks_mask(blocks, b, b, H, W)
+    assert torch.equal(y3[torch.from_numpy(out).cuda()], cache[torch.from_numpy(out).cuda()])
+
+
+# ------------------------------------------------------------------ a5: convolution on tiles
+
+@pytest.mark.parametrize("dtype,Cin,Cout,b,k,s,n", [
+    ("f32", 64, 64, 6, 3, 1, 9), ("f16", 128, 128, 16, 3, 1, 5), ("f16", 128, 256, 16, 1, 1, 5),
+    ("bf16", 320, 320, 4, 1, 1, 7), ("f16", 64, 128, 8, 3, 2, 6), ("f32", 8, 3, 6, 3, 1, 4),
+    ("bf16", 48, 40, 5, 3, 1, 11), ("f16", 16, 100, 32, 3, 1, 2), ("f16", 256, 64, 16, 3, 1, 3)])
+def test_conv_on_tiles(oracle, dtype, Cin, Cout, b, k, s, n):
+    rng = np.random.default_rng(Cin * 7 + Cout)
+    td = DT[dtype]
+    g = api.geom(64 * s, 64 * s, b, k, s, k // 2)
+    th, tw = g.tile_h, g.tile_w
+    tiles = torch.from_numpy(rng.standard_normal((n, th, tw, Cin)).astype(np.float32)).to(td)
+    w, bias = inputs.conv_params(rng, Cout, Cin, k, td)
+    want = np.stack([oracle.conv2d(f64(tiles[i]), f64(w), f64(bias), s, 0) for i in range(n)])
+    assert want.shape == (n, b, b, Cout)
+    packed = api.sige_pack_weight(dev(w))
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    prev = os.environ.pop("SIGE_CONV_CFG", None)
+    try:
+        for cfg in (None, "0", "1", "2"):
+            if cfg is None:
+                os.environ.pop("SIGE_CONV_CFG", None)
+            else:
+                os.environ["SIGE_CONV_CFG"] = cfg
+            if cfg is not None and b > (128 if cfg in ("0", "1") else 64):
+                continue
+            out = torch.full((n + 1, b, b, Cout), 5.0, dtype=td, device="cuda")
+            api.sige_conv(dev(tiles), g, Cin, Cout, packed, dev(bias), cnt, out, n_blocks=n, max_blocks=n)
+            assert_close(out[:n], want, td, f"conv cfg={cfg}")
+            assert (out[n:] == 5.0).all()
+            out2 = torch.full((n + 1, b, b, Cout), 5.0, dtype=td, device="cuda")
+            big = torch.cat([dev(tiles), torch.zeros((3, th, tw, Cin), dtype=td, device="cuda")])
+            api.sige_conv(big, g, Cin, Cout, packed, None, cnt, out2, n_blocks=-1, max_blocks=n + 1)
+            want_nb = want - f64(bias)[None, None, None, :]
+            assert_close(out2[:n], want_nb, td, f"conv no-bias device-count cfg={cfg}")
+            assert (out2[n:] == 5.0).all()
+    finally:
+        os.environ.pop("SIGE_CONV_CFG", None)
+        if prev is not None:
+            os.environ["SIGE_CONV_CFG"] = prev
+
+
+# ------------------------------------------------------------------ the whole layer
+
+def sparse_layer(cfg, *, fused, shortcut=False, device_count=False, cache=None):
+    """reduce -> gather -> conv -> scatter through the library; returns (y, blocks, extras)."""
+    td = DT[cfg["dtype"]]
+    H, W = cfg["H"], cfg["W"]
+    conv = SigeConv(dev(cfg["w"]), cfg["bias"], H, W, cfg["block"], cfg["stride"], cfg["pad"])
+    ws = Workspace("cuda")
+    bl = BlockList(conv.g, "cuda")
+    mask_out = torch.zeros((H, W), dtype=torch.uint8, device="cuda")
+    a_o, a_e = dev(cfg["a_orig"]), dev(cfg["a_edit"])
+    bl.reduce(a_orig=a_o, a_edit=a_e, tau=cfg["tau"], mask_out=mask_out, dilate=cfg["dilate"])
+    if not device_count:
+        bl.sync_count()
+    y = dev(cache).clone()
+    scale = shift = None
+    act = api.ACT_NONE
+    if fused:
+        mean = torch.zeros(cfg["groups"], device="cuda")
+        var = torch.zeros(cfg["groups"], device="cuda")
+        scale = torch.zeros(cfg["Cin"], device="cuda")
+        shift = torch.zeros(cfg["Cin"], device="cuda")
+        # statistics of the ORIGINAL activation (Sec. 3.2 "Pre-computing normalization parameters")
+        api.sige_gn_stats(a_o, cfg["groups"], mean, var, gamma=dev(cfg["gamma"]), beta=dev(cfg["beta"]),
+                          eps=cfg["eps"], scale=scale, shift=shift)
+        act = api.ACT_SILU
+    conv.forward(a_e, y, bl, ws, scale=scale, shift=shift, act=act)
+    torch.cuda.synchronize()
+    n = int(bl.count.item())
+    return y, bl.indices[:n].cpu().numpy(), mask_out.cpu().numpy()
+
+
+@pytest.mark.parametrize("seed", [1001, 1002, 1003, 1004])
+@pytest.mark.parametrize("device_count", [False, True])
+def test_layer_config1(oracle, seed, device_count):
+    cfg = inputs.config1(seed=seed)
+    a_o, a_e, w, b = f64(cfg["a_orig"]), f64(cfg["a_edit"]), f64(cfg["w"]), f64(cfg["bias"])
+    cache64 = oracle.conv2d(a_o, w, b, 1, 1)
+    cache = torch.from_numpy(cache64).to(torch.float32)
+    y, blocks, mask = sparse_layer(cfg, fused=False, device_count=device_count, cache=cache)
+    want_blocks = oracle.active_blocks(oracle.diff_mask(cfg["a_orig"].numpy(), cfg["a_edit"].numpy(), cfg["tau"]),
+                                       64, 64, 6, 6, 3, 1, 1)
+    assert np.array_equal(blocks, want_blocks)
+    want = oracle.sige_layer(a_e, f64(cache), blocks, 6, 6, w, b, 1, 1)
+    assert_close(y, want, torch.float32, "config1 layer")
+    # with the true difference mask the sparse result is the dense layer on the edited input
+    assert_close(y, oracle.conv2d(a_e, w, b, 1, 1), torch.float32, "config1 == dense")
+    out = torch.from_numpy(outside_blocks_mask(blocks, 6, 6, 64, 64)).cuda()
+    assert torch.equal(y[out], cache.cuda()[out])  # outside the active blocks: the cache, bit for bit
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_layer_config2_small_fused(oracle, dtype):
+    cfg = inputs.config2(seed=7, H=96, W=80, C=64, Cs=128, area_frac=0.02, dtype=dtype, axes=(3.0, 8.0))
+    td = DT[dtype]
+    a_o, a_e = f64(cfg["a_orig"]), f64(cfg["a_edit"])
+    w, b = f64(cfg["w"]), f64(cfg["bias"])
+    mean, var = oracle.gn_stats(a_o, cfg["groups"])
+    scale, shift = oracle.fold_gn(f64(cfg["gamma"]), f64(cfg["beta"]), mean, var, cfg["eps"])
+    cache64 = oracle.dense_layer(a_o, w, b, 1, 1, scale, shift, oracle.ACT_SILU)
+    cache = torch.from_numpy(cache64).to(td)
+    y, blocks, mask = sparse_layer(cfg, fused=True, cache=cache)
+    m = oracle.diff_mask(cfg["a_orig"].float().numpy(), cfg["a_edit"].float().numpy(), cfg["tau"])
+    assert np.array_equal(mask, m)
+    assert np.array_equal(blocks, oracle.active_blocks(m, 96, 80, 16, 16, 3, 1, 1))
+    # element-wise bar against the oracle whose gathered (activated) tensor is a stored tensor of
+    # the layer's dtype; and against the oracle with no intermediate rounding at all
+    want = oracle.sige_layer(a_e, f64(cache), blocks, 16, 16, w, b, 1, 1, scale, shift, oracle.ACT_SILU,
+                             storage=dtype)
+    assert_close(y, want, td, "config2 small")
+    want = oracle.sige_layer(a_e, f64(cache), blocks, 16, 16, w, b, 1, 1, scale, shift, oracle.ACT_SILU)
+    assert_mostly_close(y, want, td, "config2 small vs unrounded oracle")
+    out = torch.from_numpy(outside_blocks_mask(blocks, 16, 16, 96, 80)).cuda()
+    assert torch.equal(y[out], cache.cuda()[out])
+    # the statistics really are the cached ones: with statistics of the EDITED tensor the oracle differs
+    mean_e, var_e = oracle.gn_stats(a_e, cfg["groups"])
+    assert np.abs(mean_e - mean).max() > 0
+
+
+def test_layer_config2_shortcut_and_residual(oracle):
+    """1x1 shortcut conv on the same mask (its own k=1 list) and a ResBlock-style tail:
+    scatter(main + shortcut tiles)."""
+    cfg = inputs.config2(seed=11, H=64, W=64, C=64, Cs=64, area_frac=0.03, dtype="f16", axes=(3.0, 8.0))
+    td = torch.float16
+    a_o, a_e = f64(cfg["a_orig"]), f64(cfg["a_edit"])
+    ws_, bs_ = f64(cfg["w_s"]), f64(cfg["bias_s"])
+    m = oracle.diff_mask(cfg["a_orig"].float().numpy(), cfg["a_edit"].float().numpy(), 0.0)
+    # shortcut alone, with its own list
+    sc = SigeConv(dev(cfg["w_s"]), cfg["bias_s"], 64, 64, 16, 1, 0)
+    bl1 = BlockList(sc.g, "cuda")
+    bl1.reduce(mask_in=torch.from_numpy(m).cuda())
+    n1 = bl1.sync_count()
+    want1 = oracle.active_blocks(m, 64, 64, 16, 16, 1, 1, 0)
+    assert n1 == len(want1) and np.array_equal(bl1.indices[:n1].cpu().numpy(), want1)
+    cache_s = torch.from_numpy(oracle.conv2d(a_o, ws_, bs_, 1, 0)).to(td)
+    y = dev(cache_s).clone()
+    wsp = Workspace("cuda")
+    sc.forward(dev(cfg["a_edit"]), y, bl1, wsp)
+    want = oracle.sige_layer(a_e, f64(cache_s), want1, 16, 16, ws_, bs_, 1, 0)
+    assert_close(y, want, td, "shortcut 1x1")
+    assert_close(y, oracle.conv2d(a_e, ws_, bs_, 1, 0), td, "shortcut == dense")
+    # main 3x3 + shortcut on the 3x3 list, summed in the scatter
+    main = SigeConv(dev(cfg["w"]), cfg["bias"], 64, 64, 16, 1, 1)
+    bl3 = BlockList(main.g, "cuda")
+    bl3.reduce(mask_in=torch.from_numpy(m).cuda())
+    bl3.sync_count()
+    blocks3 = bl3.indices[:bl3.n_host].cpu().numpy()
+    sc3 = SigeConv(dev(cfg["w_s"]), cfg["bias_s"], 64, 64, 16, 1, 0)
+    w, b = f64(cfg["w"]), f64(cfg["bias"])
+    dense_sum = lambda a: oracle.conv2d(a, w, b, 1, 1) + oracle.conv2d(a, ws_, bs_, 1, 0)
+    cache_sum = torch.from_numpy(dense_sum(a_o)).to(td)
+    y = dev(cache_sum).clone()
+    res_tiles = sc3.forward(dev(cfg["a_edit"]), None, bl3, wsp, scatter=False, tag="s")
+    main.forward(dev(cfg["a_edit"]), y, bl3, wsp, residual_tiles=res_tiles, tag="m")
+    want = oracle.select_blocks(dense_sum(a_e), f64(cache_sum), blocks3, 16, 16)
+    assert_close(y, want, td, "main + shortcut")
+
+
+def test_layer_all_active_equals_dense_and_zero_blocks(oracle):
+    cfg = inputs.config2(seed=3, H=40, W=56, C=32, Cs=32, area_frac=0.05, dtype="f16", axes=(2.0, 5.0))
+    td = torch.float16
+    conv = SigeConv(dev(cfg["w"]), cfg["bias"], 40, 56, 16, 1, 1)
+    ws = Workspace("cuda")
+    bl = BlockList(conv.g, "cuda").all_active()
+    y = torch.full((40, 56, 32), float("nan"), dtype=td, device="cuda")  # every element must be written
+    conv.forward(dev(cfg["a_edit"]), y, bl, ws)
+    want = oracle.conv2d(f64(cfg["a_edit"]), f64(cfg["w"]), f64(cfg["bias"]), 1, 1)
+    assert_close(y, want, td, "all active == dense")
+    # no active block: y untouched bitwise, through both count paths
+    poison = torch.from_numpy(np.random.default_rng(1).standard_normal((40, 56, 32)).astype(np.float32)).to(td).cuda()
+    y = poison.clone()
+    bl.reduce(mask_in=torch.zeros((40, 56), dtype=torch.uint8, device="cuda"))
+    conv.forward(dev(cfg["a_edit"]), y, bl, ws)
+    bl.sync_count()
+    conv.forward(dev(cfg["a_edit"]), y, bl, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, poison)
+
+
+def test_layer_stride2_and_upsample(oracle):
+    rng = np.random.default_rng(21)
+    td = torch.float16
+    H, W, C = 64, 48, 32
+    mask = inputs.blob_mask(rng, H, W, 60, 2, (2.0, 5.0))
+    a_o, a_e = inputs.edited_pair(rng, H, W, C, mask, 1.0, td)
+    w, b = inputs.conv_params(rng, 64, C, 3, td)
+    # stride-2 down-sampling conv
+    conv = SigeConv(dev(w), b, H, W, 8, 2, 1)
+    bl = BlockList(conv.g, "cuda")
+    bl.reduce(mask_in=torch.from_numpy(mask).cuda())
+    n = bl.sync_count()
+    want_blocks = oracle.active_blocks(mask, 32, 24, 8, 8, 3, 2, 1)
+    assert np.array_equal(bl.indices[:n].cpu().numpy(), want_blocks) and 0 < n < 12
+    cache = torch.from_numpy(oracle.conv2d(f64(a_o), f64(w), f64(b), 2, 1)).to(td)
+    y = dev(cache).clone()
+    conv.forward(dev(a_e), y, bl, Workspace("cuda"))
+    assert_close(y, oracle.conv2d(f64(a_e), f64(w), f64(b), 2, 1), td, "stride 2 == dense")
+    # nearest x2 up-sampling followed by a 3x3 conv, mask taken at the output resolution
+    up_o = f64(a_o).repeat(2, axis=0).repeat(2, axis=1)
+    up_e = f64(a_e).repeat(2, axis=0).repeat(2, axis=1)
+    mask_up = mask.repeat(2, axis=0).repeat(2, axis=1)
+    convu = SigeConv(dev(w), b, 2 * H, 2 * W, 16, 1, 1, up=1)
+    blu = BlockList(convu.g, "cuda")
+    blu.reduce(mask_in=torch.from_numpy(mask_up).cuda())
+    blu.sync_count()
+    cache = torch.from_numpy(oracle.conv2d(up_o, f64(w), f64(b), 1, 1)).to(td)
+    y = dev(cache).clone()
+    convu.forward(dev(a_e), y, blu, Workspace("cuda"))
+    assert_close(y, oracle.conv2d(up_e, f64(w), f64(b), 1, 1), td, "upsample+conv == dense")
+
+
+def test_layer_config2_full_size_sampled(oracle):
+    """BASELINE config 2 at full size (256x256x128 fp16, 16x16 blocks, ~1 % blobs), in the launch
+    configuration the benchmark times; the oracle evaluates sampled output pixels one by one.
+    The cache is an arbitrary seeded tensor: what must hold is 'dense layer on active blocks,
+    cache bit for bit elsewhere'."""
+    cfg = inputs.config2()
+    td = torch.float16
+    H = W = 256
+    a_o, a_e = f64(cfg["a_orig"]), f64(cfg["a_edit"])
+    mean, var = oracle.gn_stats(a_o, 32)
+    scale, shift = oracle.fold_gn(f64(cfg["gamma"]), f64(cfg["beta"]), mean, var, cfg["eps"])
+    rng = np.random.default_rng(99)
+    cache = torch.from_numpy(rng.standard_normal((H, W, 128)).astype(np.float32)).to(td)
+    y, blocks, mask = sparse_layer(cfg, fused=True, cache=cache)
+    m = oracle.diff_mask(cfg["a_orig"].float().numpy(), cfg["a_edit"].float().numpy(), 0.0)
+    assert np.array_equal(mask, m) and abs(int(m.sum()) - 655) <= 33
+    want_blocks = oracle.active_blocks(m, H, W, 16, 16, 3, 1, 1)
+    assert np.array_equal(blocks, want_blocks) and 3 <= len(blocks) <= 40
+    out = outside_blocks_mask(blocks, 16, 16, H, W)
+    out_t = torch.from_numpy(out).cuda()
+    assert torch.equal(y[out_t], cache.cuda()[out_t])
+    # sampled pixels inside active blocks (corners, edges and random interior points of each block)
+    px = []
+    for (y0, x0) in blocks:
+        px += [(y0, x0), (y0 + 15, x0 + 15), (y0, x0 + 15), (y0 + 15, x0)]
+        px += [(y0 + int(rng.integers(16)), x0 + int(rng.integers(16))) for _ in range(12)]
+    px = np.array(px, np.int32)
+    got = y[torch.from_numpy(px[:, 0]).long().cuda(), torch.from_numpy(px[:, 1]).long().cuda()]
+    want = oracle.dense_layer(a_e, f64(cfg["w"]), f64(cfg["bias"]), 1, 1, scale, shift, oracle.ACT_SILU, pixels=px,
+                              storage="f16")
+    assert_close(got, want, td, "config2 full size (sampled)")
+    want = oracle.dense_layer(a_e, f64(cfg["w"]), f64(cfg["bias"]), 1, 1, scale, shift, oracle.ACT_SILU, pixels=px)
+    assert_mostly_close(got, want, td, "config2 full size (sampled) vs unrounded oracle")

@@ -130,3 +130,24 @@ def test_select_blocks_clips_and_keeps_cache(oracle):
     want[0:4, 0:4] = 1
     want[4:5, 4:7] = 1
     assert np.array_equal(out[:, :, 0], want) and np.array_equal(out[:, :, 1], want)
+
+
+def test_round_storage_equals_library_casts(oracle):
+    rng = np.random.default_rng(13)
+    a = np.concatenate([rng.standard_normal(20000) * 3, rng.standard_normal(2000) * 1e-3,
+                        # exact ties between neighbouring bf16 / f16 values round to even
+                        np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11,
+                                  -(2.0 + 2.0 ** -7), 0.0, -0.0, 65504.0, 3.3895e38])])
+    t = torch.from_numpy(a)
+    for name, td in (("bf16", torch.bfloat16), ("f16", torch.float16), ("f32", torch.float32)):
+        want = t.to(torch.float32).to(td).to(torch.float64).numpy()
+        got = oracle.round_storage(a, name)
+        assert np.array_equal(got, want), name
+    # the hook changes the layer only through the rounded activation
+    x = rng.standard_normal((5, 5, 4))
+    w = rng.standard_normal((3, 4, 3, 3))
+    sc, sh = np.ones(4), np.zeros(4)
+    y1 = oracle.dense_layer(x, w, None, 1, 1, sc, sh, oracle.ACT_SILU, storage="bf16")
+    z = oracle.round_storage(oracle.scale_shift_act(x, sc, sh, oracle.ACT_SILU), "bf16")
+    assert np.array_equal(y1, oracle.conv2d(z, w, None, 1, 1))
+    assert np.array_equal(oracle.dense_layer(x, w, None, 1, 1, storage="bf16"), oracle.conv2d(x, w, None, 1, 1))
