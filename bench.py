@@ -1,0 +1,328 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse layer hot path on one MI355X.
+
+A step is one pass of the whole path over BASELINE config 2 (256x256x128 fp16, ~1 % blob
+edit, 16x16 blocks): difference mask + block lists (3x3 and 1x1), then
+gather(GN+SiLU) -> conv3x3 -> scatter and gather -> conv1x1 -> scatter, inputs resident in
+HBM.  `value` is the algorithmic bytes of one step divided by its wall time.  The line also
+carries the roofline of the dominant kernel (measured live with events on the launch stream),
+the CPU oracle timed on the host cores, and supplements: per-call times, gather/scatter
+bandwidth on a 1024x1024x128 tensor with 20 % of the blocks active, dense-equivalent conv
+throughput, and sparse-query attention.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-supplement", action="store_true", help="only the headline step")
+    return ap.parse_args()
+
+
+def time_calls(fn, iters, warm=20):
+    """Average duration of fn() in microseconds, HIP events on the current stream."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters
+
+
+class Layer2:
+    """Config 2 on the device: caches from a first all-active pass, then the sparse step."""
+
+    def __init__(self, cfg, device="cuda"):
+        import torch
+        from paper_2211_02048_amd import api
+        from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
+        self.api, self.cfg = api, cfg
+        H, W, C, Cs = cfg["H"], cfg["W"], cfg["Cin"], cfg["Cs"]
+        self.a_o, self.a_e = cfg["a_orig"].to(device), cfg["a_edit"].to(device)
+        self.main = SigeConv(cfg["w"].to(device), cfg["bias"], H, W, cfg["block"], 1, 1)
+        self.short = SigeConv(cfg["w_s"].to(device), cfg["bias_s"], H, W, cfg["block"], 1, 0)
+        self.ws = Workspace(device)
+        self.bl3 = BlockList(self.main.g, device)
+        self.bl1 = BlockList(self.short.g, device)
+        self.mask = torch.zeros((H, W), dtype=torch.uint8, device=device)
+        G = cfg["groups"]
+        self.mean, self.var = torch.zeros(G, device=device), torch.zeros(G, device=device)
+        self.scale, self.shift = torch.zeros(C, device=device), torch.zeros(C, device=device)
+        # pre-computation pass on the original input: statistics and F(A_orig) for both convs
+        api.sige_gn_stats(self.a_o, G, self.mean, self.var, gamma=cfg["gamma"].to(device),
+                          beta=cfg["beta"].to(device), eps=cfg["eps"], scale=self.scale, shift=self.shift)
+        self.y_main = torch.empty((H, W, C), dtype=self.a_o.dtype, device=device)
+        self.y_short = torch.empty((H, W, Cs), dtype=self.a_o.dtype, device=device)
+        full3, full1 = BlockList(self.main.g, device).all_active(), BlockList(self.short.g, device).all_active()
+        self.main.forward(self.a_o, self.y_main, full3, self.ws, scale=self.scale, shift=self.shift,
+                          act=api.ACT_SILU)
+        self.short.forward(self.a_o, self.y_short, full1, self.ws)
+        torch.cuda.synchronize()
+
+    def reduce(self):
+        c = self.cfg
+        self.bl3.reduce(a_orig=self.a_o, a_edit=self.a_e, tau=c["tau"], mask_out=self.mask, dilate=c["dilate"])
+        self.bl1.reduce(mask_in=self.mask, dilate=c["dilate"])
+
+    def layer(self):
+        api = self.api
+        self.main.forward(self.a_e, self.y_main, self.bl3, self.ws, scale=self.scale, shift=self.shift,
+                          act=api.ACT_SILU)
+        self.short.forward(self.a_e, self.y_short, self.bl1, self.ws)
+
+    def step(self):
+        self.reduce()
+        self.bl3.sync_count()   # the one readback per edit and list that sizes the launches
+        self.bl1.sync_count()
+        self.layer()
+
+    def bytes_per_step(self, n3, n1):
+        c = self.cfg
+        s, C, Cs, b = 2, c["Cin"], c["Cs"], c["block"]
+        t = b + 2
+        diff = 2 * c["H"] * c["W"] * C * s + c["H"] * c["W"]
+        lists = 2 * c["H"] * c["W"] + 8 * (n3 + n1) + 8
+        main = n3 * (2 * t * t * C * s + 2 * b * b * C * s + t * t * C * s + b * b * C * s) + 9 * C * C * s
+        short = n1 * (2 * b * b * C * s + 2 * b * b * Cs * s + b * b * C * s + b * b * Cs * s) + C * Cs * s
+        return diff + lists + main + short, diff
+
+    def flops_per_step(self, n3, n1):
+        c = self.cfg
+        b = c["block"]
+        return 2 * b * b * (n3 * 9 * c["Cin"] * c["Cout"] + n1 * c["Cin"] * c["Cs"])
+
+
+def cpu_baseline(cfg, n_bytes):
+    """The oracle as it stands, timed on the host cores: the whole config-2 step (difference
+    mask, block lists, dense GN+SiLU+3x3 layer, dense 1x1 layer, block selection), repeated
+    until about 10 s have passed."""
+    import numpy as np
+    import torch
+
+    import oracle
+    f64 = lambda t: t.to(torch.float64).numpy()
+    a_o32, a_e32 = cfg["a_orig"].float().numpy(), cfg["a_edit"].float().numpy()
+    a_o, a_e = f64(cfg["a_orig"]), f64(cfg["a_edit"])
+    w, b, ws, bs = f64(cfg["w"]), f64(cfg["bias"]), f64(cfg["w_s"]), f64(cfg["bias_s"])
+    mean, var = oracle.gn_stats(a_o, cfg["groups"])
+    scale, shift = oracle.fold_gn(f64(cfg["gamma"]), f64(cfg["beta"]), mean, var, cfg["eps"])
+    H, W, blk = cfg["H"], cfg["W"], cfg["block"]
+    cache3 = np.zeros((H, W, cfg["Cout"]))
+    cache1 = np.zeros((H, W, cfg["Cs"]))
+    cores = oracle.get_max_threads()
+    times = []
+    t_all = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        m = oracle.diff_mask(a_o32, a_e32, cfg["tau"])
+        b3 = oracle.active_blocks(m, H, W, blk, blk, 3, 1, 1)
+        b1 = oracle.active_blocks(m, H, W, blk, blk, 1, 1, 0)
+        oracle.sige_layer(a_e, cache3, b3, blk, blk, w, b, 1, 1, scale, shift, oracle.ACT_SILU)
+        oracle.sige_layer(a_e, cache1, b1, blk, blk, ws, bs, 1, 0)
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > 10.0 or len(times) >= 10:
+            break
+    t = float(np.median(times))
+    return {"value": n_bytes / t / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"whole config-2 step (dense GN+SiLU+3x3 and 1x1 layers on the edited input, then "
+                      f"block selection), median of {len(times)} runs", "s_per_step": t}
+
+
+def supplement(L, dtype_name):
+    """Per-call times at config 2 and bandwidth / throughput points in regimes where they show."""
+    import numpy as np
+    import torch
+    from paper_2211_02048_amd import api, inputs
+    from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
+    out = {}
+    c = L.cfg
+    n3, n1 = L.bl3.n_host, L.bl1.n_host
+    # ---- per-call times at config 2 (exact host block count)
+    g3, ws = L.main.g, L.ws
+    tiles = ws.get("tiles", L.main.tiles_numel(max(n3, 1)), L.a_e.dtype)
+    ot = ws.get("out_t", L.main.out_numel(max(n3, 1)), L.a_e.dtype)
+    per = {}
+    per["reduce_mask_diff_us"] = time_calls(lambda: L.bl3.reduce(a_orig=L.a_o, a_edit=L.a_e, tau=c["tau"],
+                                                                 mask_out=L.mask), 200)
+    per["reduce_mask_list_us"] = time_calls(lambda: L.bl1.reduce(mask_in=L.mask), 200)
+    L.bl3.n_host, L.bl1.n_host = n3, n1
+    per["gather_fused_us"] = time_calls(lambda: api.sige_gather(L.a_e, g3, L.bl3.indices, L.bl3.count, tiles,
+                                                                n_blocks=n3, scale=L.scale, shift=L.shift,
+                                                                act=api.ACT_SILU, max_blocks=max(n3, 1)), 200)
+    per["conv3x3_us"] = time_calls(lambda: api.sige_conv(tiles, g3, c["Cin"], c["Cout"], L.main.packed, L.main.bias,
+                                                         L.bl3.count, ot, n_blocks=n3, max_blocks=max(n3, 1)), 200)
+    per["scatter_us"] = time_calls(lambda: api.sige_scatter(ot, g3, L.bl3.indices, L.bl3.count, L.y_main,
+                                                            n_blocks=n3, Cout=c["Cout"], max_blocks=max(n3, 1)), 200)
+    per["layer_only_us"] = time_calls(L.layer, 200)
+    out["config2_calls"] = {k: round(v, 2) for k, v in per.items()}
+    out["config2_calls"]["n_blocks_3x3"] = n3
+    out["config2_calls"]["n_blocks_1x1"] = n1
+
+    # ---- dense comparator: the same kernels with every block active
+    full3 = BlockList(g3, "cuda").all_active()
+    full1 = BlockList(L.short.g, "cuda").all_active()
+    y3, y1 = torch.empty_like(L.y_main), torch.empty_like(L.y_short)
+
+    def dense():
+        L.main.forward(L.a_e, y3, full3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU)
+        L.short.forward(L.a_e, y1, full1, ws)
+    dense_us = time_calls(dense, 50, 5)
+    nfull = g3.grid_blocks
+    tl = ws.get("tiles", L.main.tiles_numel(nfull), L.a_e.dtype)
+    of = ws.get("out_t", L.main.out_numel(nfull), L.a_e.dtype)
+    api.sige_gather(L.a_e, g3, full3.indices, full3.count, tl, n_blocks=nfull, scale=L.scale, shift=L.shift,
+                    act=api.ACT_SILU, max_blocks=nfull)
+    conv_us = time_calls(lambda: api.sige_conv(tl, g3, c["Cin"], c["Cout"], L.main.packed, L.main.bias, full3.count,
+                                               of, n_blocks=nfull, max_blocks=nfull), 50, 5)
+    fl = 2.0 * c["H"] * c["W"] * 9 * c["Cin"] * c["Cout"]
+    out["dense_all_active"] = {"layer_us": round(dense_us, 1), "conv3x3_us": round(conv_us, 1),
+                               "conv3x3_tflops": round(fl / conv_us / 1e6, 1),
+                               "conv3x3_frac_mfma_peak": round(fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS[dtype_name], 4),
+                               "sparse_layer_speedup": round(dense_us / per["layer_only_us"], 2)}
+
+    # ---- bandwidth regime: 1024x1024x128 fp16 (256 MiB per tensor), 20 % of the 4096 blocks active
+    H2 = 1024
+    C = c["Cin"]
+    rng = np.random.Generator(np.random.PCG64(2002))
+    x = torch.randn((H2, H2, C), dtype=torch.float16, device="cuda")
+    x2 = x.clone()
+    m = inputs.blob_mask(rng, H2, H2, int(0.16 * H2 * H2), 12, (40.0, 120.0), tol=0.1)
+    big = SigeConv(c["w"].cuda(), c["bias"], H2, H2, 16, 1, 1)
+    bl = BlockList(big.g, "cuda")
+    md = torch.from_numpy(m).cuda()
+    bl.reduce(mask_in=md)
+    nb = bl.sync_count()
+    t2 = torch.empty(big.tiles_numel(nb), dtype=torch.float16, device="cuda")
+    o2 = torch.empty(big.out_numel(nb), dtype=torch.float16, device="cuda")
+    y2 = torch.empty((H2, H2, C), dtype=torch.float16, device="cuda")
+    sc, sh = L.scale, L.shift
+    g_us = time_calls(lambda: api.sige_gather(x, big.g, bl.indices, bl.count, t2, n_blocks=nb, scale=sc, shift=sh,
+                                              act=api.ACT_SILU, max_blocks=nb), 30, 3)
+    gp_us = time_calls(lambda: api.sige_gather(x, big.g, bl.indices, bl.count, t2, n_blocks=nb, max_blocks=nb),
+                       30, 3)
+    s_us = time_calls(lambda: api.sige_scatter(o2, big.g, bl.indices, bl.count, y2, n_blocks=nb, Cout=C,
+                                               max_blocks=nb), 30, 3)
+    c_us = time_calls(lambda: api.sige_conv(t2, big.g, C, C, big.packed, big.bias, bl.count, o2, n_blocks=nb,
+                                            max_blocks=nb), 10, 2)
+    mask_o = torch.zeros((H2, H2), dtype=torch.uint8, device="cuda")
+    d_us = time_calls(lambda: api.sige_reduce_mask(big.g, bl.indices, bl.count, a_orig=x, a_edit=x2, tau=0.0,
+                                                   mask_out=mask_o), 20, 2)
+    gb = nb * 2 * 18 * 18 * C * 2
+    sb = nb * 2 * 16 * 16 * C * 2
+    db = 2 * H2 * H2 * C * 2 + H2 * H2
+    cf = 2.0 * nb * 256 * 9 * C * C
+    out["bandwidth_1024x1024x128"] = {
+        "active_blocks": nb, "of_blocks": big.g.grid_blocks,
+        "gather_fused_us": round(g_us, 1), "gather_fused_GBs": round(gb / g_us / 1e3, 1),
+        "gather_fused_frac_hbm_peak": round(gb / g_us / 1e3 / HBM_PEAK_GBS, 4),
+        "gather_plain_GBs": round(gb / gp_us / 1e3, 1),
+        "scatter_us": round(s_us, 1), "scatter_GBs": round(sb / s_us / 1e3, 1),
+        "scatter_frac_hbm_peak": round(sb / s_us / 1e3 / HBM_PEAK_GBS, 4),
+        "diff_mask_us": round(d_us, 1), "diff_mask_GBs": round(db / d_us / 1e3, 1),
+        "diff_mask_frac_hbm_peak": round(db / d_us / 1e3 / HBM_PEAK_GBS, 4),
+        "conv3x3_us": round(c_us, 1), "conv3x3_tflops": round(cf / c_us / 1e6, 1),
+        "conv3x3_frac_mfma_peak": round(cf / c_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 4)}
+    del x, x2, t2, o2, y2
+
+    # ---- sparse-query attention at the Stable-Diffusion 64x64 level (bf16, 8 heads x 40)
+    att = {}
+    T, heads, d = 4096, 8, 40
+    for frac, nq in (("1pct", 96), ("5pct", 400), ("20pct", 1200), ("dense", 4096)):
+        cs = inputs.attention_case(7, T, heads, d, nq, "bf16")
+        q, k, v = cs["q"].cuda(), cs["k"].cuda(), cs["v"].cuda()
+        o = torch.empty_like(q)
+        nbytes = api.sige_sparse_attn_workspace_bytes(nq, T, heads, d)
+        wsb = torch.empty(max(nbytes // 4, 1), dtype=torch.float32, device="cuda") if nbytes else None
+        us = time_calls(lambda: api.sige_sparse_attn(q, k, v, o, cs["scale"], workspace=wsb), 50, 5)
+        att[frac] = {"n_q": nq, "us": round(us, 1), "tflops": round(4.0 * nq * T * heads * d / us / 1e6, 2)}
+    out["sparse_attention_T4096_h8_d40_bf16"] = att
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures one MI355X; --gpus {args.gpus} is not supported "
+              "(one GPU per box, no collectives in this path)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2211_02048_amd import api, inputs
+    api.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = inputs.config2()
+    L = Layer2(cfg)
+
+    for _ in range(args.warmup):
+        L.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        L.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    n3, n1 = L.bl3.n_host, L.bl1.n_host
+    n_bytes, diff_bytes = L.bytes_per_step(n3, n1)
+
+    # dominant kernel: the difference-mask stream (both activations read once).  Rotate over
+    # distinct buffer pairs (> 256 MB in total) so that the Infinity Cache cannot serve them.
+    pairs = [(L.a_o.clone(), L.a_e.clone()) for _ in range(10)]
+    it = [0]
+
+    def diff_cold():
+        a, e = pairs[it[0] % len(pairs)]
+        it[0] += 1
+        L.bl3.reduce(a_orig=a, a_edit=e, tau=cfg["tau"], mask_out=L.mask)
+    both_us = time_calls(diff_cold, 200)
+    list_us = time_calls(lambda: L.bl3.reduce(mask_in=L.mask), 200)
+    diff_us = max(both_us - list_us, 1e-3)
+    L.bl3.n_host = n3
+    roof = {"bound": "hbm", "kernel": "diff_mask_pow2 (sige_reduce_mask, activation mode)",
+            "achieved": round(diff_bytes / diff_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(diff_bytes / diff_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+            "bytes_per_launch": diff_bytes, "avg_launch_us": round(diff_us, 2),
+            "note": "duration = (reduce_mask with activations) - (reduce_mask from a ready mask), events on the "
+                    "launch stream, inputs rotated over 10 buffer pairs (335 MB)"}
+    del pairs
+
+    res = {"metric": "sparse-conv gather/scatter GB/s", "value": round(n_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": "BASELINE config 2: GN(32, cached stats)+SiLU+3x3 conv 128->128 and 1x1 shortcut "
+                                  "128->256, 256x256 fp16, ~1% blob edit, 16x16 blocks; step = diff mask + block "
+                                  "lists + gather/conv/scatter for both convs",
+                      "active_blocks_3x3": n3, "active_blocks_1x1": n1, "grid_blocks": L.main.g.grid_blocks,
+                      "algorithmic_bytes_per_step": n_bytes, "mfma_flop_per_step": L.flops_per_step(n3, n1)},
+           "roofline": roof}
+    if not args.no_supplement:
+        res["supplement"] = supplement(L, "f16")
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(cfg, n_bytes)
+    else:
+        res["cpu_baseline"] = None
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

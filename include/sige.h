@@ -74,12 +74,19 @@ typedef struct {
  * Outputs: indices [max_blocks][2] (rows beyond the count are left untouched; never
  * more than max_blocks rows are written) and *count = the true number of active
  * blocks, even when it exceeds max_blocks.  The block grid may hold at most
- * 131072 blocks (SIGE_ERR_CAPACITY beyond).                                       */
+ * 131072 blocks (SIGE_ERR_CAPACITY beyond).
+ * workspace: optional device scratch of sige_reduce_mask_workspace_bytes(g) bytes,
+ * 4-byte aligned, whose first 4 bytes the caller zeroes ONCE before the first use (every
+ * call leaves them zero again); it lets the block tests run on many workgroups.  Calls
+ * that share a workspace must not overlap.  NULL (or too small): one workgroup does all
+ * the work - same results, slower on large grids.                                  */
 int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt,
                      int32_t Hm, int32_t Wm, int32_t C, float tau,
                      const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
                      const sige_geom* g, uint8_t* mask_out,
-                     int32_t* indices, int32_t max_blocks, int32_t* count, void* stream);
+                     int32_t* indices, int32_t max_blocks, int32_t* count,
+                     void* workspace, size_t workspace_bytes, void* stream);
+size_t sige_reduce_mask_workspace_bytes(const sige_geom* g);
 
 /* Fig. "method" Gather, with Sec. 3.2 "Pre-computing normalization parameters" and
  * "Kernel fusion" folded in:

@@ -22,7 +22,7 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_gather", "sige_conv", "sige_scatter", "sige_sparse_attn",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_gather", "sige_conv", "sige_scatter", "sige_sparse_attn",
            "sige_sparse_attn_workspace_bytes", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -74,7 +74,10 @@ def lib() -> ctypes.CDLL:
         L.sige_sparse_attn_workspace_bytes.restype = ctypes.c_size_t
         vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
         gp = ctypes.POINTER(Geom)
-        L.sige_reduce_mask.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp]
+        L.sige_reduce_mask.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp, sz,
+                                       vp]
+        L.sige_reduce_mask_workspace_bytes.restype = ctypes.c_size_t
+        L.sige_reduce_mask_workspace_bytes.argtypes = [gp]
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
         L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
@@ -100,8 +103,12 @@ def _check(rc: int):
         raise SigeError(rc, lib().sige_last_error().decode())
 
 
+def sige_reduce_mask_workspace_bytes(g: Geom) -> int:
+    return int(lib().sige_reduce_mask_workspace_bytes(ctypes.byref(g)))
+
+
 def sige_reduce_mask(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None,
-                     mask_out=None, pool_log2=0, dilate=0, max_blocks=None):
+                     mask_out=None, pool_log2=0, dilate=0, max_blocks=None, workspace=None):
     """Difference mask -> pooled, dilated mask -> ordered active-block list (device)."""
     if a_orig is not None:
         Hm, Wm, C = a_orig.shape
@@ -112,7 +119,8 @@ def sige_reduce_mask(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0
     mb = indices.shape[0] if max_blocks is None else max_blocks
     _check(lib().sige_reduce_mask(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2,
                                   dilate, ctypes.byref(g), _ptr(mask_out), _ptr(indices), mb, _ptr(count),
-                                  _stream()))
+                                  _ptr(workspace), 0 if workspace is None else workspace.numel() *
+                                  workspace.element_size(), _stream()))
 
 
 def sige_gather(x, g: Geom, indices, count, tiles, *, n_blocks=-1, scale=None, shift=None, act=ACT_NONE,

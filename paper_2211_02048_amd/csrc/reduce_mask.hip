@@ -102,57 +102,57 @@ struct ListArgs {
     int words;  // 1: pooled windows may be read as aligned 32-bit words
 };
 
-__global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
+// True iff the input tile of block blk (clipped to the image, grown by the dilation radius)
+// holds a marked pixel of the pooled mask.  Evaluated by one whole wave.
+__device__ __forceinline__ bool block_is_active(const ListArgs& a, int blk, int lane)
 {
-    extern __shared__ uint8_t flags[];
-    __shared__ int wave_tot[16];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int nb = a.nby * a.nbx;
     const int p = a.pool_log2;
-
-    for (int blk = w; blk < nb; blk += 16) {
-        const int by = blk / a.nbx, bx = blk - by * a.nbx;
-        // input tile of the block, clipped to the image, then grown by the dilation radius
-        int fy0 = by * a.bh * a.stride - a.pad, fx0 = bx * a.bw * a.stride - a.pad;
-        int fy1 = min(fy0 + a.th, a.Hin), fx1 = min(fx0 + a.tw, a.Win);
-        fy0 = max(fy0, 0);
-        fx0 = max(fx0, 0);
-        const int ry0 = max(fy0 - a.dilate, 0), ry1 = min(fy1 + a.dilate, a.Hin);
-        const int rx0 = max(fx0 - a.dilate, 0), rx1 = min(fx1 + a.dilate, a.Win);
-        const int ncols = rx1 - rx0, n = (ry1 - ry0) * ncols;
-        bool any = false;
-        for (int e = lane; e < n; e += 64) {
-            const int y = ry0 + e / ncols, x = rx0 + e % ncols;
-            if (p == 0) {
-                any |= a.mask[(long)y * a.Wm + x] != 0;
-            } else {
-                const int sy1 = min((y + 1) << p, a.Hm), sx0 = x << p, sx1 = min((x + 1) << p, a.Wm);
-                for (int sy = y << p; sy < sy1; ++sy) {
-                    if (a.words) {
-                        const uint32_t* row = reinterpret_cast<const uint32_t*>(a.mask + (long)sy * a.Wm);
-                        for (int sx = sx0 >> 2; sx < (sx1 >> 2); ++sx) any |= row[sx] != 0;
-                    } else {
-                        for (int sx = sx0; sx < sx1; ++sx) any |= a.mask[(long)sy * a.Wm + sx] != 0;
-                    }
+    const int by = blk / a.nbx, bx = blk - by * a.nbx;
+    int fy0 = by * a.bh * a.stride - a.pad, fx0 = bx * a.bw * a.stride - a.pad;
+    int fy1 = min(fy0 + a.th, a.Hin), fx1 = min(fx0 + a.tw, a.Win);
+    fy0 = max(fy0, 0);
+    fx0 = max(fx0, 0);
+    const int ry0 = max(fy0 - a.dilate, 0), ry1 = min(fy1 + a.dilate, a.Hin);
+    const int rx0 = max(fx0 - a.dilate, 0), rx1 = min(fx1 + a.dilate, a.Win);
+    const int ncols = rx1 - rx0, n = (ry1 - ry0) * ncols;
+    bool any = false;
+    for (int e = lane; e < n; e += 64) {
+        const int y = ry0 + e / ncols, x = rx0 + e % ncols;
+        if (p == 0) {
+            any |= a.mask[(long)y * a.Wm + x] != 0;
+        } else {
+            const int sy1 = min((y + 1) << p, a.Hm), sx0 = x << p, sx1 = min((x + 1) << p, a.Wm);
+            for (int sy = y << p; sy < sy1; ++sy) {
+                if (a.words) {
+                    const uint32_t* row = reinterpret_cast<const uint32_t*>(a.mask + (long)sy * a.Wm);
+                    for (int sx = sx0 >> 2; sx < (sx1 >> 2); ++sx) any |= row[sx] != 0;
+                } else {
+                    for (int sx = sx0; sx < sx1; ++sx) any |= a.mask[(long)sy * a.Wm + sx] != 0;
                 }
             }
         }
-        unsigned long long b = __ballot(any);
-        if (lane == 0) flags[blk] = b ? 1 : 0;
     }
-    __syncthreads();
+    return __ballot(any) != 0ull;
+}
 
-    // ordered compaction: blocks are visited in row-major order, 1024 at a time
+// Ordered compaction of nb flags by one workgroup of NT threads: blocks are visited in
+// row-major order, NT at a time; ballot + popcount give the position inside a wave, the wave
+// totals are scanned through LDS.
+template <int NT>
+__device__ __forceinline__ void compact_flags(const ListArgs& a, const uint8_t* flags, int nb, int* wave_tot)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     int base = 0;
-    for (int c0 = 0; c0 < nb; c0 += 1024) {
+    for (int c0 = 0; c0 < nb; c0 += NT) {
         const int blk = c0 + tid;
-        const int f = blk < nb ? flags[blk] : 0;
+        const int f = blk < nb ? ((const volatile uint8_t*)flags)[blk] : 0;
         const unsigned long long b = __ballot(f);
         const int pre = __popcll(b & ((1ull << lane) - 1ull));
         if (lane == 0) wave_tot[w] = __popcll(b);
         __syncthreads();
         int off = base, total = 0;
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < NW; ++i) {
             const int t = wave_tot[i];
             if (i < w) off += t;
             total += t;
@@ -169,6 +169,45 @@ __global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
         __syncthreads();
     }
     if (tid == 0) *a.count = base;
+}
+
+// Without a workspace: one workgroup tests every block (flags in LDS) and compacts.
+__global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
+{
+    extern __shared__ uint8_t flags[];
+    __shared__ int wave_tot[16];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int nb = a.nby * a.nbx;
+    for (int blk = w; blk < nb; blk += 16) {
+        const bool f = block_is_active(a, blk, lane);
+        if (lane == 0) flags[blk] = f ? 1 : 0;
+    }
+    __syncthreads();
+    compact_flags<1024>(a, flags, nb, wave_tot);
+}
+
+// With a workspace: one wave per block over many workgroups; flags go to global memory and
+// the workgroup that takes the last ticket compacts them.  Every workgroup reaches the
+// ticket exactly once and nobody waits, so the grid always drains.  The ticket is left at 0.
+__global__ __launch_bounds__(256) void block_list_ws_kernel(ListArgs a, uint8_t* flags, unsigned int* ticket)
+{
+    __shared__ int wave_tot[4];
+    __shared__ int is_last;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int nb = a.nby * a.nbx;
+    const int blk = blockIdx.x * 4 + w;
+    if (blk < nb) {
+        const bool f = block_is_active(a, blk, lane);
+        if (lane == 0) flags[blk] = f ? 1 : 0;
+    }
+    __threadfence();   // flags visible device-wide before the ticket is taken
+    __syncthreads();
+    if (threadIdx.x == 0) is_last = atomicAdd(ticket, 1u) == gridDim.x - 1;
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    compact_flags<256>(a, (const uint8_t*)flags, nb, wave_tot);
+    if (threadIdx.x == 0) *ticket = 0u;
 }
 
 template <typename T>
@@ -208,11 +247,18 @@ static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, i
 
 using namespace sige;
 
+extern "C" size_t sige_reduce_mask_workspace_bytes(const sige_geom* g)
+{
+    if (g == nullptr || g->block_h <= 0 || g->block_w <= 0 || g->H_out <= 0 || g->W_out <= 0) return 0;
+    const size_t nb = (size_t)((g->H_out + g->block_h - 1) / g->block_h) * ((g->W_out + g->block_w - 1) / g->block_w);
+    return 16 + ((nb + 15) & ~(size_t)15);
+}
+
 extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
                                 int32_t Wm, int32_t C, float tau, const uint8_t* mask_in,
                                 int32_t pool_log2, int32_t dilate, const sige_geom* g,
                                 uint8_t* mask_out, int32_t* indices, int32_t max_blocks,
-                                int32_t* count, void* stream)
+                                int32_t* count, void* workspace, size_t workspace_bytes, void* stream)
 {
     clear_error();
     const char* who = "sige_reduce_mask";
@@ -257,6 +303,15 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     a.indices = indices; a.max_blocks = max_blocks; a.count = count;
     a.words = (pool_log2 >= 2 && Wm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & 3u) == 0) ? 1 : 0;
     const size_t lds = ((size_t)(nby * nbx) + 15) & ~(size_t)15;
+    if (workspace != nullptr && workspace_bytes >= sige_reduce_mask_workspace_bytes(g) &&
+        (reinterpret_cast<uintptr_t>(workspace) & 3u) == 0) {
+        unsigned int* ticket = (unsigned int*)workspace;
+        uint8_t* flags = (uint8_t*)workspace + 16;
+        const int grid = (int)((nby * nbx + 3) / 4);
+        hipLaunchKernelGGL(block_list_ws_kernel, dim3(grid), dim3(256), 0, st, a, flags, ticket);
+        SIGE_LAUNCH_CHECK("sige_reduce_mask(list)");
+        return SIGE_OK;
+    }
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)block_list_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -29,18 +29,21 @@ class Workspace:
 class BlockList:
     """Device-side ordered list of active blocks for one (resolution, block, kernel)."""
 
-    def __init__(self, g: api.Geom, device, max_blocks=None):
+    def __init__(self, g: api.Geom, device, max_blocks=None, use_workspace=True):
         self.g = g
         self.max_blocks = g.grid_blocks if max_blocks is None else max_blocks
         self.indices = torch.zeros((max(self.max_blocks, 1), 2), dtype=torch.int32, device=device)
         self.count = torch.zeros(1, dtype=torch.int32, device=device)
         self.n_host = -1
+        # scratch for the multi-workgroup block test; its ticket word starts (and stays) zero
+        self.scratch = torch.zeros(api.sige_reduce_mask_workspace_bytes(g), dtype=torch.uint8,
+                                   device=device) if use_workspace else None
 
     def reduce(self, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None, mask_out=None, pool_log2=0,
                dilate=0):
         api.sige_reduce_mask(self.g, self.indices, self.count, a_orig=a_orig, a_edit=a_edit, tau=tau,
                              mask_in=mask_in, mask_out=mask_out, pool_log2=pool_log2, dilate=dilate,
-                             max_blocks=self.max_blocks)
+                             max_blocks=self.max_blocks, workspace=self.scratch)
         self.n_host = -1
 
     def all_active(self):

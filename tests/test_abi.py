@@ -84,17 +84,18 @@ def test_reduce_mask_errors(L):
     gp = ctypes.byref(g)
     f = ctypes.c_float(1e-6)
     # both sources / neither source
-    assert L.sige_reduce_mask(FAKE, FAKE, 0, 64, 64, 64, f, FAKE, 0, 0, gp, FAKE, FAKE, 121, FAKE, None) == 1
-    assert L.sige_reduce_mask(None, None, 0, 64, 64, 64, f, None, 0, 0, gp, FAKE, FAKE, 121, FAKE, None) == 1
+    assert L.sige_reduce_mask(FAKE, FAKE, 0, 64, 64, 64, f, FAKE, 0, 0, gp, FAKE, FAKE, 121, FAKE, None, 0, None) == 1
+    assert L.sige_reduce_mask(None, None, 0, 64, 64, 64, f, None, 0, 0, gp, FAKE, FAKE, 121, FAKE, None, 0, None) == 1
     assert "either" in err(L)
     # activation mode needs mask_out
-    assert L.sige_reduce_mask(FAKE, FAKE, 0, 64, 64, 64, f, None, 0, 0, gp, None, FAKE, 121, FAKE, None) == 1
+    assert L.sige_reduce_mask(FAKE, FAKE, 0, 64, 64, 64, f, None, 0, 0, gp, None, FAKE, 121, FAKE, None, 0, None) == 1
     # pooled mask size must match the conv input
-    assert L.sige_reduce_mask(None, None, 0, 100, 64, 0, f, FAKE, 0, 0, gp, None, FAKE, 121, FAKE, None) == 1
+    assert L.sige_reduce_mask(None, None, 0, 100, 64, 0, f, FAKE, 0, 0, gp, None, FAKE, 121, FAKE, None, 0, None) == 1
     # block grid beyond the stated maximum
     big = api.geom(2048, 2048, 4, 1, 1, 0)
     assert L.sige_reduce_mask(None, None, 0, 2048, 2048, 0, f, FAKE, 0, 0, ctypes.byref(big), None, FAKE, 8,
-                              FAKE, None) == 3
+                              FAKE, None, 0, None) == 3
+    assert L.sige_reduce_mask_workspace_bytes(gp) == 16 + 128  # 121 flags rounded up to 16, plus the ticket
 
 
 def test_attention_and_helper_errors(L):

@@ -15,8 +15,9 @@ pytestmark = pytest.mark.gpu
 DT = inputs.DTYPES
 
 
-def run_reduce(g, *, a_orig=None, a_edit=None, tau=0.0, mask=None, pool_log2=0, dilate=0, max_blocks=None):
-    bl = BlockList(g, "cuda", max_blocks)
+def run_reduce(g, *, a_orig=None, a_edit=None, tau=0.0, mask=None, pool_log2=0, dilate=0, max_blocks=None,
+               use_workspace=True):
+    bl = BlockList(g, "cuda", max_blocks, use_workspace)
     bl.indices.fill_(-7)
     mask_out = None
     if a_orig is not None:
@@ -79,7 +80,8 @@ def test_block_list_pool_dilate_geometries(oracle):
                             continue
                         m = (rng.random((Hm, Wm)) < rng.choice([0.0005, 0.005, 0.05])).astype(np.uint8)
                         g = api.geom(Hin, Win, b, k, s, p)
-                        bl, _ = run_reduce(g, mask=torch.from_numpy(m).cuda(), pool_log2=pool, dilate=r)
+                        bl, _ = run_reduce(g, mask=torch.from_numpy(m).cuda(), pool_log2=pool, dilate=r,
+                                           use_workspace=(cases % 2 == 0))  # both kernels, alternating
                         lv = oracle.level_mask(m, pool, r)
                         want = oracle.active_blocks(lv, g.H_out, g.W_out, b, b, k, s, p)
                         n = int(bl.count.item())
@@ -105,14 +107,23 @@ def test_block_list_degenerate_and_overflow(oracle):
     assert np.array_equal(bl.indices.cpu().numpy(), want[:10])
     with pytest.raises(api.SigeError):
         bl.sync_count()
-    # a grid larger than one compaction pass (1024 blocks per pass)
+    # a grid larger than one compaction pass, with and without the workspace; the workspace
+    # is reused by back-to-back calls (its ticket returns to zero each time)
     Hb = 300
     gb = api.geom(Hb, Hb, 4, 1, 1, 0)
     m = (np.random.default_rng(0).random((Hb, Hb)) < 0.01).astype(np.uint8)
-    bl, _ = run_reduce(gb, mask=torch.from_numpy(m).cuda())
     want = oracle.active_blocks(m, Hb, Hb, 4, 4, 1, 1, 0)
-    assert gb.grid_blocks == 5625 and int(bl.count.item()) == len(want)
-    assert np.array_equal(bl.indices[:len(want)].cpu().numpy(), want)
+    for use_ws in (True, False):
+        bl, _ = run_reduce(gb, mask=torch.from_numpy(m).cuda(), use_workspace=use_ws)
+        assert gb.grid_blocks == 5625 and int(bl.count.item()) == len(want)
+        assert np.array_equal(bl.indices[:len(want)].cpu().numpy(), want)
+        for rep in range(3):
+            bl.indices.fill_(-7)
+            bl.reduce(mask_in=torch.from_numpy(m).cuda())
+            assert int(bl.count.item()) == len(want)
+            assert np.array_equal(bl.indices[:len(want)].cpu().numpy(), want)
+        if use_ws:
+            assert int(bl.scratch[:4].view(torch.int32).item()) == 0
 
 
 # ------------------------------------------------------------------ a4 / a6: gather and scatter
