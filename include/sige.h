@@ -76,10 +76,10 @@ typedef struct {
  * blocks, even when it exceeds max_blocks.  The block grid may hold at most
  * 131072 blocks (SIGE_ERR_CAPACITY beyond).
  * workspace: optional device scratch of sige_reduce_mask_workspace_bytes(g) bytes,
- * 4-byte aligned, whose first 4 bytes the caller zeroes ONCE before the first use (every
- * call leaves them zero again); it lets the block tests run on many workgroups.  Calls
- * that share a workspace must not overlap.  NULL (or too small): one workgroup does all
- * the work - same results, slower on large grids.                                  */
+ * 16-byte aligned, which the caller zeroes ONCE before the first use (every call leaves
+ * it zero again); with it the marked pixels set per-block flags in parallel.  Calls that
+ * share a workspace must not overlap.  NULL (or too small): one workgroup tests every
+ * block - same results, slower on large grids.                                     */
 int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt,
                      int32_t Hm, int32_t Wm, int32_t C, float tau,
                      const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,

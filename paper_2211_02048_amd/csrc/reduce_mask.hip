@@ -5,9 +5,13 @@
 // Kernel 1 streams both activations once (the only HBM-sized traffic here): each
 // lane owns one 16-byte vector, the lanes of one pixel vote with a wave ballot and
 // the first lanes of the wave store one mask byte per pixel.
-// Kernel 2 is a single workgroup: every wave tests whole blocks against the pooled,
-// dilated mask and leaves one flag per block in LDS; an ordered ballot/popcount
-// prefix sum then compacts the flags into the row-major index list.
+// With a caller workspace the block test is turned around: instead of every block
+// scanning its tile, every MARKED pixel sets the flag of the (few) blocks whose
+// dilated tile contains it - done by the difference kernel itself, or by a vectorised
+// scan of a ready mask - and one small workgroup compacts the flags into the row-major
+// list with an ordered ballot/popcount prefix sum and clears them for the next call.
+// Without a workspace a single workgroup tests every block against the pooled, dilated
+// mask (flags in LDS) and compacts.
 #include "common.h"
 
 namespace sige {
@@ -24,12 +28,37 @@ __device__ __forceinline__ bool vec_differs(const uint4& o, const uint4& e, floa
     return any;
 }
 
+struct MarkArgs {
+    uint8_t* flags;  // one byte per block of the grid, all zero on entry; NULL = do not mark
+    int Wm, pool_log2, dilate;
+    int sy, sx;      // block pitch in input pixels: block * stride
+    int th, tw, pad, nby, nbx;
+};
+
+// Sets the flag of every block whose input tile, grown by the dilation radius, contains the
+// pooled position of the marked source pixel `pix`.  In input coordinates block b covers
+// [b*s - pad - r, b*s - pad + tile + r); clipping to the image never excludes an in-image pixel.
+__device__ __forceinline__ void mark_blocks(const MarkArgs& m, long pix)
+{
+    const int y = (int)(pix / m.Wm) >> m.pool_log2, x = (int)(pix % m.Wm) >> m.pool_log2;
+    const int ylo = y - m.dilate - m.th + m.pad, xlo = x - m.dilate - m.tw + m.pad;
+    // first block with b*s > lo  (floor division that is correct for negative lo)
+    int by0 = (ylo >= 0 ? ylo / m.sy : -((-ylo + m.sy - 1) / m.sy)) + 1;
+    int bx0 = (xlo >= 0 ? xlo / m.sx : -((-xlo + m.sx - 1) / m.sx)) + 1;
+    const int by1 = min((y + m.dilate + m.pad) / m.sy, m.nby - 1);
+    const int bx1 = min((x + m.dilate + m.pad) / m.sx, m.nbx - 1);
+    by0 = max(by0, 0);
+    bx0 = max(bx0, 0);
+    for (int by = by0; by <= by1; ++by)
+        for (int bx = bx0; bx <= bx1; ++bx) m.flags[by * m.nbx + bx] = 1;
+}
+
 // V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
 template <typename T, int U>
 __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ a_o,
                                                       const uint4* __restrict__ a_e, long n_vec,
                                                       int log2v, float tau, long n_pix,
-                                                      uint8_t* __restrict__ mask)
+                                                      uint8_t* __restrict__ mask, MarkArgs mk)
 {
     const int lane = threadIdx.x & 63;
     const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -54,7 +83,11 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
         for (int u = 0; u < U; ++u) {
             unsigned long long b = __ballot(vec_differs<T>(o[u], e[u], tau));
             long pix = ((base + u * 64) >> log2v) + lane;
-            if (lane < ppw && pix < n_pix) mask[pix] = ((b >> (lane << log2v)) & gmask) ? 1 : 0;
+            if (lane < ppw && pix < n_pix) {
+                const bool marked = ((b >> (lane << log2v)) & gmask) != 0ull;
+                mask[pix] = marked ? 1 : 0;
+                if (marked && mk.flags) mark_blocks(mk, pix);
+            }
         }
     }
 }
@@ -146,7 +179,7 @@ __device__ __forceinline__ void compact_flags(const ListArgs& a, const uint8_t* 
     int base = 0;
     for (int c0 = 0; c0 < nb; c0 += NT) {
         const int blk = c0 + tid;
-        const int f = blk < nb ? ((const volatile uint8_t*)flags)[blk] : 0;
+        const int f = blk < nb ? flags[blk] : 0;
         const unsigned long long b = __ballot(f);
         const int pre = __popcll(b & ((1ull << lane) - 1ull));
         if (lane == 0) wave_tot[w] = __popcll(b);
@@ -171,6 +204,39 @@ __device__ __forceinline__ void compact_flags(const ListArgs& a, const uint8_t* 
     if (tid == 0) *a.count = base;
 }
 
+// Ready mask -> block flags: every lane reads 16 mask bytes and marks for the non-zero ones.
+__global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __restrict__ mask, long n_pix,
+                                                             int vec_ok, MarkArgs mk)
+{
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long p0 = t * 16;
+    if (p0 >= n_pix) return;
+    if (vec_ok && p0 + 16 <= n_pix) {
+        const uint4 v = *reinterpret_cast<const uint4*>(mask + p0);
+        if ((v.x | v.y | v.z | v.w) == 0u) return;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (w[i] == 0u) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((w[i] >> (8 * j)) & 0xffu) mark_blocks(mk, p0 + 4 * i + j);
+        }
+    } else {
+        for (long p = p0; p < min(p0 + 16, n_pix); ++p)
+            if (mask[p]) mark_blocks(mk, p);
+    }
+}
+
+// Flags (global) -> ordered list; the flags are cleared again for the next call.
+__global__ __launch_bounds__(1024) void compact_ws_kernel(ListArgs a, uint8_t* flags)
+{
+    __shared__ int wave_tot[16];
+    const int nb = a.nby * a.nbx;
+    compact_flags<1024>(a, flags, nb, wave_tot);
+    for (int i = threadIdx.x; i < nb; i += 1024) flags[i] = 0;
+}
+
 // Without a workspace: one workgroup tests every block (flags in LDS) and compacts.
 __global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
 {
@@ -186,34 +252,11 @@ __global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
     compact_flags<1024>(a, flags, nb, wave_tot);
 }
 
-// With a workspace: one wave per block over many workgroups; flags go to global memory and
-// the workgroup that takes the last ticket compacts them.  Every workgroup reaches the
-// ticket exactly once and nobody waits, so the grid always drains.  The ticket is left at 0.
-__global__ __launch_bounds__(256) void block_list_ws_kernel(ListArgs a, uint8_t* flags, unsigned int* ticket)
-{
-    __shared__ int wave_tot[4];
-    __shared__ int is_last;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int nb = a.nby * a.nbx;
-    const int blk = blockIdx.x * 4 + w;
-    if (blk < nb) {
-        const bool f = block_is_active(a, blk, lane);
-        if (lane == 0) flags[blk] = f ? 1 : 0;
-    }
-    __threadfence();   // flags visible device-wide before the ticket is taken
-    __syncthreads();
-    if (threadIdx.x == 0) is_last = atomicAdd(ticket, 1u) == gridDim.x - 1;
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-    compact_flags<256>(a, (const uint8_t*)flags, nb, wave_tot);
-    if (threadIdx.x == 0) *ticket = 0u;
-}
-
 template <typename T>
 static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, int C, float tau,
-                       uint8_t* mask, hipStream_t st)
+                       uint8_t* mask, const MarkArgs& mk, bool* marked, hipStream_t st)
 {
+    *marked = false;
     const long n_pix = (long)Hm * Wm;
     const size_t bytes = (size_t)C * sizeof(T);
     if (bytes % 16 == 0 && aligned16(a_orig) && aligned16(a_edit)) {
@@ -226,7 +269,8 @@ static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, i
             long steps = (n_vec + 256L * U - 1) / (256L * U);
             int grid = (int)(steps < 4096 ? steps : 4096);
             hipLaunchKernelGGL((diff_mask_pow2<T, U>), dim3(grid), dim3(256), 0, st,
-                               (const uint4*)a_orig, (const uint4*)a_edit, n_vec, log2v, tau, n_pix, mask);
+                               (const uint4*)a_orig, (const uint4*)a_edit, n_vec, log2v, tau, n_pix, mask, mk);
+            *marked = mk.flags != nullptr;
         } else {
             long blocks = (n_pix + 3) / 4;
             int grid = (int)(blocks < 8192 ? blocks : 8192);
@@ -251,7 +295,7 @@ extern "C" size_t sige_reduce_mask_workspace_bytes(const sige_geom* g)
 {
     if (g == nullptr || g->block_h <= 0 || g->block_w <= 0 || g->H_out <= 0 || g->W_out <= 0) return 0;
     const size_t nb = (size_t)((g->H_out + g->block_h - 1) / g->block_h) * ((g->W_out + g->block_w - 1) / g->block_w);
-    return 16 + ((nb + 15) & ~(size_t)15);
+    return (nb + 15) & ~(size_t)15;
 }
 
 extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
@@ -282,15 +326,23 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
                  "%s: block grid %ldx%ld exceeds 131072 blocks", who, nby, nbx);
     hipStream_t st = (hipStream_t)stream;
     const uint8_t* mask = mask_in;
+    const bool use_ws = workspace != nullptr && workspace_bytes >= sige_reduce_mask_workspace_bytes(g) &&
+                        (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
+    MarkArgs mk;
+    mk.flags = use_ws ? (uint8_t*)workspace : nullptr;
+    mk.Wm = Wm; mk.pool_log2 = pool_log2; mk.dilate = dilate;
+    mk.sy = g->block_h * g->stride; mk.sx = g->block_w * g->stride;
+    mk.th = th; mk.tw = tw; mk.pad = g->pad; mk.nby = (int)nby; mk.nbx = (int)nbx;
+    bool marked = false;
     if (diff_mode) {
         SIGE_REQUIRE(a_orig && a_edit, SIGE_ERR_INVALID_ARG, "%s: a_orig and a_edit are both required", who);
         SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
         SIGE_REQUIRE(C > 0, SIGE_ERR_INVALID_ARG, "%s: C must be positive", who);
         SIGE_REQUIRE(mask_out != nullptr, SIGE_ERR_INVALID_ARG,
                      "%s: mask_out is required when the mask is computed from activations", who);
-        int rc = dt == SIGE_F32   ? launch_diff<float>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, st)
-                 : dt == SIGE_F16 ? launch_diff<f16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, st)
-                                  : launch_diff<bf16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, st);
+        int rc = dt == SIGE_F32   ? launch_diff<float>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, mk, &marked, st)
+                 : dt == SIGE_F16 ? launch_diff<f16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, mk, &marked, st)
+                                  : launch_diff<bf16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, mk, &marked, st);
         if (rc) return rc;
         mask = mask_out;
     }
@@ -303,13 +355,17 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     a.indices = indices; a.max_blocks = max_blocks; a.count = count;
     a.words = (pool_log2 >= 2 && Wm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & 3u) == 0) ? 1 : 0;
     const size_t lds = ((size_t)(nby * nbx) + 15) & ~(size_t)15;
-    if (workspace != nullptr && workspace_bytes >= sige_reduce_mask_workspace_bytes(g) &&
-        (reinterpret_cast<uintptr_t>(workspace) & 3u) == 0) {
-        unsigned int* ticket = (unsigned int*)workspace;
-        uint8_t* flags = (uint8_t*)workspace + 16;
-        const int grid = (int)((nby * nbx + 3) / 4);
-        hipLaunchKernelGGL(block_list_ws_kernel, dim3(grid), dim3(256), 0, st, a, flags, ticket);
-        SIGE_LAUNCH_CHECK("sige_reduce_mask(list)");
+    if (use_ws) {
+        if (!marked) {
+            const long n_pix = (long)Hm * Wm;
+            const long threads = (n_pix + 15) / 16;
+            const int vec_ok = (reinterpret_cast<uintptr_t>(mask) & 15u) == 0;
+            hipLaunchKernelGGL(mark_from_mask_kernel, dim3((int)((threads + 255) / 256)), dim3(256), 0, st, mask,
+                               n_pix, vec_ok, mk);
+            SIGE_LAUNCH_CHECK("sige_reduce_mask(mark)");
+        }
+        hipLaunchKernelGGL(compact_ws_kernel, dim3(1), dim3(1024), 0, st, a, mk.flags);
+        SIGE_LAUNCH_CHECK("sige_reduce_mask(compact)");
         return SIGE_OK;
     }
     if (lds > 48 * 1024) {

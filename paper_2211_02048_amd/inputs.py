@@ -143,3 +143,164 @@ def token_mask(seed: int, Ht: int, Wt: int, area_frac: float, n_blobs: int = 3) 
     s = min(Ht, Wt) / 64.0
     return blob_mask(rng, Ht, Wt, max(1, int(round(area_frac * Ht * Wt))), n_blobs,
                      (2.0 * s + 0.5, 6.0 * s + 0.5), tol=0.15)
+
+
+# ----------------------------------------------------------------------------------------
+# Synthetic DDPM-style UNet denoiser (BASELINE config 3).  The topology is plain data: a list
+# of operations over named buffers, consumed by the HIP harness and, separately, by the CPU
+# oracle.  Views are (buffer, first channel, channels); buffers are NHWC [res, res, Ctot].
+# ----------------------------------------------------------------------------------------
+
+def unet_topology(res: int = 256, in_ch: int = 3, channels=(128, 128, 256, 256, 512, 512),
+                  attn_res=(16,), heads: int = 4, in_pad: int = 16):
+    """Returns (buffers, ops).  conv-in; per level two ResBlocks (GN+SiLU+3x3 twice, 1x1 shortcut
+    iff the channel count changes) and a stride-2 3x3 conv; two ResBlocks in the middle; on the way
+    up per level two ResBlocks on concat(h, skip) and nearest-x2 + 3x3 conv; self-attention after
+    every ResBlock at the listed resolutions; GN+SiLU+3x3 conv-out.  Skips are the outputs of the
+    down-path ResBlocks, consumed in reverse order."""
+    bufs, ops = {}, []
+    nl = len(channels)
+    R = [res >> i for i in range(nl)]
+
+    def buf(name, r, c):
+        bufs[name] = (r, r, c)
+        return name
+
+    def conv(name, x, y, lvl_in, k=3, stride=1, up=0, gn=True, act=True, residual=None, shortcut=None,
+             scatter=True):
+        ops.append(dict(kind="conv", name=name, x=x, y=y, level=lvl_in, k=k, stride=stride, up=up, gn=gn,
+                        act=act, residual=residual, shortcut=shortcut, scatter=scatter))
+
+    def resblock(name, x, y, lvl):
+        cin, cout = x[2], y[2]
+        h1 = (buf(name + ".h1", R[lvl], cout), 0, cout)
+        conv(name + ".conv1", x, h1, lvl)
+        if cin != cout:
+            conv(name + ".short", x, None, lvl, k=1, gn=False, act=False, scatter=False)
+            conv(name + ".conv2", h1, y, lvl, shortcut=name + ".short")
+        else:
+            conv(name + ".conv2", h1, y, lvl, residual=x)
+
+    def attn(name, x, y, lvl):
+        c = x[2]
+        ops.append(dict(kind="attn", name=name, x=x, y=y, level=lvl, heads=heads, C=c))
+
+    img = (buf("image", res, in_pad), 0, in_pad)   # the 3 image channels, zero padded to in_pad
+    h = (buf("in", res, channels[0]), 0, channels[0])
+    conv("conv_in", img, h, 0, gn=False, act=False)
+    skips = []
+    # each down ResBlock writes straight into the first... second half of the concat buffer that the
+    # matching up ResBlock reads (its own slot), so the concat is never materialised
+    for l in range(nl):
+        c = channels[l]
+        for i in range(2):
+            # the up ResBlock that consumes this skip reads concat(h_up, skip): h_up has the channel
+            # count of the tensor arriving there (see the up path below)
+            slot = f"cat{l}.{i}"
+            skips.append((l, i, slot))
+    # channel count of the tensor entering each up ResBlock
+    up_in = {}
+    hc = channels[-1]
+    for l in reversed(range(nl)):
+        for j in range(2):
+            i = 1 - j                       # skips are consumed in reverse order
+            up_in[(l, i)] = hc
+            hc = channels[l]
+        # the up-conv keeps the channel count
+    for l in range(nl):
+        c = channels[l]
+        for i in range(2):
+            slot = f"cat{l}.{i}"
+            ctot = up_in[(l, i)] + c
+            buf(slot, R[l], ctot)
+            y = (slot, up_in[(l, i)], c)
+            resblock(f"down{l}.{i}", h, y, l)
+            h = y
+            if R[l] in attn_res:
+                # attention output replaces the skip in place (reads and writes the same view)
+                attn(f"down{l}.{i}.attn", h, h, l)
+        if l + 1 < nl:
+            hn = (buf(f"down{l}.ds", R[l + 1], c), 0, c)
+            conv(f"down{l}.downsample", h, hn, l, stride=2, gn=False, act=False)
+            h = hn
+    c = channels[-1]
+    m1 = (buf("mid.0", R[-1], c), 0, c)
+    resblock("mid.0", h, m1, nl - 1)
+    # mid.1 writes into the h half of the first concat buffer of the up path
+    first = f"cat{nl - 1}.1"
+    h = (first, 0, up_in[(nl - 1, 1)])
+    resblock("mid.1", m1, h, nl - 1)
+    for l in reversed(range(nl)):
+        c = channels[l]
+        for j in range(2):
+            i = 1 - j
+            slot = f"cat{l}.{i}"
+            x = (slot, 0, bufs[slot][2])
+            # destination: the h half of the next concat buffer, or a plain buffer before an up-conv
+            if j == 0:
+                nxt = f"cat{l}.0"
+                y = (nxt, 0, up_in[(l, 0)])
+            else:
+                y = (buf(f"up{l}.out", R[l], c), 0, c)
+            resblock(f"up{l}.{j}", x, y, l)
+            h = y
+            if R[l] in attn_res:
+                attn(f"up{l}.{j}.attn", h, h, l)
+        if l > 0:
+            nxt = f"cat{l - 1}.1"
+            y = (nxt, 0, up_in[(l - 1, 1)])
+            conv(f"up{l}.upsample", h, y, l, up=1, gn=False, act=False)   # input level l, output l-1
+            h = y
+    out = (buf("out", res, in_pad), 0, in_pad)
+    conv("conv_out", h, out, 0)
+    return bufs, ops
+
+
+def unet_params(seed: int, ops, dtype: str = "f16", groups: int = 32, in_ch: int = 3, in_pad: int = 16):
+    """Random-init parameters for every op: W ~ N(0, 1/fan_in), bias ~ N(0, 0.01) (a fixed time
+    embedding is thought of as folded into the biases), gamma ~ N(1, 0.1), beta ~ N(0, 0.1)."""
+    rng = _rng(seed)
+    td = DTYPES[dtype]
+    P = {}
+
+    def gn(name, c):
+        P[name + ".gamma"] = torch.from_numpy((1.0 + math.sqrt(0.1) * rng.standard_normal(c)).astype(np.float32))
+        P[name + ".beta"] = torch.from_numpy((math.sqrt(0.1) * rng.standard_normal(c)).astype(np.float32))
+
+    for op in ops:
+        n = op["name"]
+        if op["kind"] == "conv":
+            cin = op["x"][2]
+            cout = op["y"][2] if op["y"] is not None else None
+            if cout is None:   # shortcut conv: output channels of the ResBlock
+                cout = next(o["y"][2] for o in ops if o.get("shortcut") == n)
+            w, b = conv_params(rng, cout, cin, op["k"], td)
+            if n == "conv_in":    # padded input channels carry zeros; keep their weights zero too
+                w[:, in_ch:] = 0
+            if n == "conv_out":   # padded output channels produce exactly zero
+                w[in_ch:] = 0
+                b[in_ch:] = 0
+            P[n + ".w"], P[n + ".b"] = w, b
+            if op["gn"]:
+                gn(n, cin)
+        else:
+            c = op["C"]
+            gn(n, c)
+            for part in ("q", "k", "v", "o"):
+                w, b = conv_params(rng, c, c, 1, td)
+                P[f"{n}.{part}.w"], P[f"{n}.{part}.b"] = w, b
+    return P
+
+
+def unet_images(seed: int, res: int, area_frac: float, dtype: str = "f16", in_ch: int = 3, in_pad: int = 16,
+                n_blobs: int = 3):
+    """Original and edited input image (N(0,1), zero padded to in_pad channels) and the image-level
+    difference mask: blobs covering about area_frac, inside which all channels get N(0,1) noise."""
+    rng = _rng(seed)
+    td = DTYPES[dtype]
+    s = res / 256.0
+    mask = blob_mask(rng, res, res, max(1, int(round(area_frac * res * res))), n_blobs,
+                     (5.0 * s + 0.5, 12.0 * s + 0.5), tol=0.1)
+    a_o, a_e = edited_pair(rng, res, res, in_ch, mask, 1.0, td)
+    pad = torch.zeros((res, res, in_pad - in_ch), dtype=td)
+    return torch.cat([a_o, pad], 2).contiguous(), torch.cat([a_e, pad], 2).contiguous(), mask

@@ -35,7 +35,7 @@ class BlockList:
         self.indices = torch.zeros((max(self.max_blocks, 1), 2), dtype=torch.int32, device=device)
         self.count = torch.zeros(1, dtype=torch.int32, device=device)
         self.n_host = -1
-        # scratch for the multi-workgroup block test; its ticket word starts (and stays) zero
+        # per-block flag scratch for the reduction; starts zero and every call leaves it zero
         self.scratch = torch.zeros(api.sige_reduce_mask_workspace_bytes(g), dtype=torch.uint8,
                                    device=device) if use_workspace else None
 

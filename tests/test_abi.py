@@ -95,7 +95,7 @@ def test_reduce_mask_errors(L):
     big = api.geom(2048, 2048, 4, 1, 1, 0)
     assert L.sige_reduce_mask(None, None, 0, 2048, 2048, 0, f, FAKE, 0, 0, ctypes.byref(big), None, FAKE, 8,
                               FAKE, None, 0, None) == 3
-    assert L.sige_reduce_mask_workspace_bytes(gp) == 16 + 128  # 121 flags rounded up to 16, plus the ticket
+    assert L.sige_reduce_mask_workspace_bytes(gp) == 128  # 121 block flags rounded up to 16
 
 
 def test_attention_and_helper_errors(L):
