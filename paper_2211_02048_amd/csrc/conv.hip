@@ -91,12 +91,18 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
     packed[i] = o < Cout ? w[(((long)o * Cin + c) * k + ky) * k + kx] : from_f32<T>(0.0f);
 }
 
-template <typename T, int TM, int TN, int WM, int WN>
+// TM x TN: 32x32 MFMA tiles per wave; WM x WN x WK = 4 waves over M, N and K (waves that split K
+// take different channel ranges of every tap and are summed through LDS at the end); KC = K steps
+// per staged channel chunk.  The weight fragments of the next tap are fetched into registers
+// while the current tap is multiplied, so the global-memory latency is paid once per tap.
+template <typename T, int TM, int TN, int WM, int WN, int WK, int KC>
 __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 {
-    static_assert(WM * WN == 4, "four waves per workgroup");
+    static_assert(WM * WN * WK == 4, "four waves per workgroup");
+    static_assert(KC % WK == 0, "waves that split K take whole K steps");
     constexpr int KS = Mma<T>::KSTEP;
     constexpr int S = (int)sizeof(T);
+    constexpr int KW = KC / WK;                               // K steps per wave and tap
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
 
@@ -107,7 +113,8 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     const int band_row0 = band * a.rows;                      // first output row of the band
     const int band_rows = min(a.rows, a.bh - band_row0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave - wm * WN;
+    const int wk = wave % WK, wmn = wave / WK;
+    const int wm = wmn / WN, wn = wmn - wm * WN;
     const int half = lane >> 5, l32 = lane & 31;
     const int pb = a.rows * a.bw;                             // M rows one block contributes
     const int trow0 = band_row0 * a.stride;                   // first staged tile row
@@ -120,33 +127,45 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
         int g = m / pb, p = m - g * pb;
         int py = p / a.bw, px = p - py * a.bw;
         if (g >= a.G || py >= band_rows) { g = 0; py = 0; px = 0; }
-        a_base[tm] = ((g * a.trows + py * a.stride) * a.tw + px * a.stride) * a.ps + half * 16;
+        a_base[tm] = ((g * a.trows + py * a.stride) * a.tw + px * a.stride) * a.ps + half * 16 +
+                     wk * KW * (KS * S);
     }
     const int nt0 = (blockIdx.x * WN + wn) * TN;              // first 32-wide Cout tile of this wave
     const int kk = a.k * a.k, kcs = a.Cin / KS;
+    const int ntn_total = (a.Cout + 31) / 32;
 
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int o = (nt0 + tn) * 32 + l32;
-        const float b = (a.bias && o < a.Cout) ? a.bias[o] : 0.0f;
+        const float b = (a.bias && o < a.Cout && wk == 0) ? a.bias[o] : 0.0f;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = b;
     }
 
-    const uint4* __restrict__ wp = (const uint4*)a.w;
+    // weight fragment pointers of this wave's Cout tiles (at tap 0, this wave's first K step)
+    const uint4* __restrict__ wp[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int nt = min(nt0 + tn, ntn_total - 1);
+        wp[tn] = (const uint4*)a.w + ((long)nt * kk * kcs + wk * KW) * 64 + lane;
+    }
     const char* __restrict__ tiles = (const char*)a.tiles;
     const int npix = a.G * a.trows * a.tw;
-    const int ntn_total = (a.Cout + 31) / 32;
+    constexpr int VPC = KC * KS * S / 16;                     // 16-byte vectors per staged pixel
 
-    for (int c0 = 0; c0 < a.Cin; c0 += a.Cc) {
-        const int cc = min(a.Cc, a.Cin - c0);
-        const int vpc = cc * S / 16;                          // 16-byte vectors per staged pixel
+    uint4 bcur[KW][TN], bnxt[KW][TN];
+#pragma unroll
+    for (int kc = 0; kc < KW; ++kc)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) bcur[kc][tn] = wp[tn][(long)kc * 64];
+
+    for (int c0 = 0; c0 < a.Cin; c0 += KC * KS) {
         if (c0) __syncthreads();
-        for (int j = tid; j < npix * vpc; j += 256) {
-            const int q = j / vpc, v = j - q * vpc;
+        for (int j = tid; j < npix * VPC; j += 256) {
+            const int q = j / VPC, v = j - q * VPC;
             const int g = q / (a.trows * a.tw), rem = q - g * (a.trows * a.tw);
             const int r = rem / a.tw, x = rem - r * a.tw;
             uint4 val = make_uint4(0, 0, 0, 0);
@@ -155,29 +174,70 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
             *(uint4*)(lds + q * a.ps + v * 16) = val;
         }
         __syncthreads();
+        const int kc0 = c0 / KS;
         for (int tap = 0; tap < kk; ++tap) {
+            // prefetch the next tap's fragments (or the first tap of the next channel chunk)
+            int ntap = tap + 1, nkc0 = kc0;
+            if (ntap == kk) { ntap = 0; nkc0 = kc0 + KC; }
+            if (nkc0 < kcs) {
+#pragma unroll
+                for (int kc = 0; kc < KW; ++kc)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        bnxt[kc][tn] = wp[tn][((long)ntap * kcs + nkc0 + kc) * 64];
+            }
             const int ky = tap / a.k, kx = tap - ky * a.k;
             const int tap_off = (ky * a.tw + kx) * a.ps;
-            for (int kc = 0; kc < cc / KS; ++kc) {
-                uint4 af[TM], bf[TN];
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const int nt = min(nt0 + tn, ntn_total - 1);
-                    bf[tn] = wp[(((long)nt * kk + tap) * kcs + (c0 / KS + kc)) * 64 + lane];
-                }
+            for (int kc = 0; kc < KW; ++kc) {
+                uint4 af[TM];
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
                     af[tm] = *(const uint4*)(lds + a_base[tm] + tap_off + kc * (KS * S));
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], bf[tn], acc[tm][tn]);
+                    for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], bcur[kc][tn], acc[tm][tn]);
             }
+#pragma unroll
+            for (int kc = 0; kc < KW; ++kc)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) bcur[kc][tn] = bnxt[kc][tn];
         }
     }
 
-    // epilogue: lane holds column l32 of each tile, rows 8*(r/4) + 4*half + r%4
     T* __restrict__ out = (T*)a.out;
+    if (WK > 1) {
+        // sum the K-split partials through LDS, then store with consecutive lanes on consecutive
+        // output channels
+        constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+        float* red = reinterpret_cast<float*>(lds);           // [WK][BM][BN + 1]
+        __syncthreads();
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int nn = (wn * TN + tn) * 32 + l32;
+                    red[(wk * BM + m) * (BN + 1) + nn] = acc[tm][tn][r];
+                }
+        __syncthreads();
+        for (int e = tid; e < BM * BN; e += 256) {
+            const int m = e / BN, nn = e - m * BN;
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < WK; ++w) v += red[(w * BM + m) * (BN + 1) + nn];
+            const int g = m / pb, p = m - g * pb;
+            const int py = p / a.bw, px = p - py * a.bw;
+            const int o = blockIdx.x * BN + nn;
+            if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
+            out[(((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o] = from_f32<T>(v);
+        }
+        return;
+    }
+    // epilogue: lane holds column l32 of each tile, rows 8*(r/4) + 4*half + r%4
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
@@ -197,13 +257,15 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 }
 
 struct ConvPlan {
-    int cfg;  // 0: 128x128, 1: 128x64, 2: 64x64 (M x N per workgroup)
+    int cfg;  // index into kCfg
+    int kc;   // K steps per staged channel chunk: 8, 4 or 1
     int G, rows, trows, Cc, ps, bands, slabs, groups;
     size_t lds;
 };
 
-static const int kCfgM[3] = {128, 128, 64};
-static const int kCfgN[3] = {128, 64, 64};
+// M x N per workgroup and whether the four waves split K
+struct CfgShape { int M, N, WK; };
+static const CfgShape kCfg[4] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}};
 
 // Chooses the workgroup shape and the staged channel chunk for one call.
 static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, size_t s, int kstep,
@@ -211,9 +273,9 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
 {
     const char* force = getenv("SIGE_CONV_CFG");
     double best_score = -1.0;
-    for (int cfg = 0; cfg < 3; ++cfg) {
+    for (int cfg = 0; cfg < 4; ++cfg) {
         if (force && atoi(force) != cfg) continue;
-        const int M = kCfgM[cfg], Nn = kCfgN[cfg];
+        const int M = kCfg[cfg].M, Nn = kCfg[cfg].N, WK = kCfg[cfg].WK;
         if (g->block_w > M) continue;
         ConvPlan p;
         p.cfg = cfg;
@@ -224,18 +286,23 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         p.trows = (p.rows - 1) * g->stride + g->k;
         p.slabs = (Cout + Nn - 1) / Nn;
         p.groups = (nblocks + p.G - 1) / p.G;
-        // largest channel chunk whose staged tile fits 64 KiB (up to 160 KiB for the smallest chunk)
         const long npix = (long)p.G * p.trows * tw;
-        int Cc = Cin;
-        while (Cc > kstep && npix * (Cc * s + 16) > 64 * 1024) Cc = ((Cc / 2 + kstep - 1) / kstep) * kstep;
-        p.Cc = Cc;
-        p.ps = (int)(Cc * s + 16);
-        p.lds = (size_t)npix * p.ps;
-        if (p.lds > 160 * 1024) continue;
-        const double util = (double)(p.G * (p.G > 1 ? pbfull : std::min(p.rows, (int)g->block_h) * g->block_w)) / M;
+        // K steps per chunk: the largest of 8 / 4 / 1 that divides Cin and whose staged tile fits
+        p.kc = 0;
+        for (int kc : {8, 4, 1}) {
+            if (kc % WK || Cin % (kc * kstep)) continue;
+            size_t lds = (size_t)npix * (kc * kstep * s + 16);
+            if (WK > 1) lds = std::max(lds, (size_t)WK * M * (Nn + 1) * sizeof(float));
+            if (lds <= (kc == 1 || (kc == 4 && WK == 4) ? 160u : 64u) * 1024u) { p.kc = kc; p.lds = lds; break; }
+        }
+        if (p.kc == 0) continue;
+        p.Cc = p.kc * kstep;
+        p.ps = (int)(p.Cc * s + 16);
+        const double util = (double)(p.G > 1 ? std::min(p.G, nblocks) * pbfull
+                                             : std::min(p.rows, (int)g->block_h) * g->block_w) / M;
         const long wgs = (long)p.groups * p.bands * p.slabs;
         const double fill = wgs >= 512 ? 1.0 : (double)wgs / 512.0;
-        const double bonus = cfg == 0 ? 1.0 : cfg == 1 ? 0.9 : 0.75;
+        const double bonus = cfg == 0 ? 1.0 : cfg == 1 ? 0.9 : cfg == 2 ? 0.75 : 0.7;
         const double nuse = (double)Cout / (p.slabs * Nn);
         const double score = util * fill * bonus * nuse;
         if (score > best_score) { best_score = score; *best = p; }
@@ -243,10 +310,10 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     return best_score >= 0.0;
 }
 
-template <typename T, int TM, int TN, int WM, int WN>
+template <typename T, int TM, int TN, int WM, int WN, int WK, int KC>
 static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
-    auto kern = conv_kernel<T, TM, TN, WM, WN>;
+    auto kern = conv_kernel<T, TM, TN, WM, WN, WK, KC>;
     if (p.lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)p.lds);
@@ -258,13 +325,26 @@ static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
     return SIGE_OK;
 }
 
+template <typename T, int KC>
+static int launch_kc(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
+{
+    switch (p.cfg) {
+    case 0: return launch_cfg<T, 2, 2, 2, 2, 1, KC>(a, p, st);
+    case 1: return launch_cfg<T, 2, 1, 2, 2, 1, KC>(a, p, st);
+    case 2: return launch_cfg<T, 1, 1, 2, 2, 1, KC>(a, p, st);
+    default:
+        if constexpr (KC % 4 == 0) return launch_cfg<T, 2, 1, 1, 1, 4, KC>(a, p, st);
+        return fail(SIGE_ERR_UNSUPPORTED, "sige_conv: internal: K-split shape without a K-split chunk");
+    }
+}
+
 template <typename T>
 static int launch_conv(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
-    switch (p.cfg) {
-    case 0: return launch_cfg<T, 2, 2, 2, 2>(a, p, st);
-    case 1: return launch_cfg<T, 2, 1, 2, 2>(a, p, st);
-    default: return launch_cfg<T, 1, 1, 2, 2>(a, p, st);
+    switch (p.kc) {
+    case 8: return launch_kc<T, 8>(a, p, st);
+    case 4: return launch_kc<T, 4>(a, p, st);
+    default: return launch_kc<T, 1>(a, p, st);
     }
 }
 
