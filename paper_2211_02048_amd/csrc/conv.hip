@@ -93,9 +93,9 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 
 // TM x TN: 32x32 MFMA tiles per wave; WM x WN x WK = 4 waves over M, N and K (waves that split K
 // take different channel ranges of every tap and are summed through LDS at the end); KC = K steps
-// per staged channel chunk.  The weight fragments of the next tap are fetched into registers
-// while the current tap is multiplied, so the global-memory latency is paid once per tap.
-template <typename T, int TM, int TN, int WM, int WN, int WK, int KC>
+// per staged channel chunk; KK = k*k when it is 9 or 1 (taps unrolled), 0 for any other kernel size.  Weight fragments are fetched into a register ring several taps ahead
+// of the MFMAs that use them (deepest for the K-split shape, whose layers are weight-bound).
+template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
 __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 {
     static_assert(WM * WN * WK == 4, "four waves per workgroup");
@@ -156,14 +156,25 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     const int npix = a.G * a.trows * a.tw;
     constexpr int VPC = KC * KS * S / 16;                     // 16-byte vectors per staged pixel
 
-    uint4 bcur[KW][TN], bnxt[KW][TN];
+    // Weight fragments run P taps ahead of the MFMAs in a register ring.  The taps of one channel
+    // chunk are unrolled into straight-line code (KK = k*k known at compile time), so every ring
+    // slot is a fixed register and the hardware's in-order load counter lets the oldest slot be
+    // awaited while the younger loads stay in flight.  P divides KK; a prefetch that would run past
+    // the last chunk re-reads the last chunk instead of branching.
+    constexpr int P = KK == 0 ? 1 : (KW * TN <= 2 ? KK : (KW * TN <= 8 && KK % 3 == 0) ? 3 : 1);
+    const int nch = a.Cin / (KC * KS);
+    const int ntaps = KK ? KK : kk;
+    uint4 bq[P][KW][TN];
+    auto fetch = [&](uint4 (&slot)[KW][TN], int chunk, int tp) {
+        chunk = min(chunk, nch - 1);
 #pragma unroll
-    for (int kc = 0; kc < KW; ++kc)
+        for (int kc = 0; kc < KW; ++kc)
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) bcur[kc][tn] = wp[tn][(long)kc * 64];
-
-    for (int c0 = 0; c0 < a.Cin; c0 += KC * KS) {
-        if (c0) __syncthreads();
+            for (int tn = 0; tn < TN; ++tn) slot[kc][tn] = wp[tn][((long)tp * kcs + chunk * KC + kc) * 64];
+    };
+    auto stage = [&](int chunk) {
+        const int c0 = chunk * (KC * KS);
+        if (chunk) __syncthreads();
         for (int j = tid; j < npix * VPC; j += 256) {
             const int q = j / VPC, v = j - q * VPC;
             const int g = q / (a.trows * a.tw), rem = q - g * (a.trows * a.tw);
@@ -174,35 +185,47 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
             *(uint4*)(lds + q * a.ps + v * 16) = val;
         }
         __syncthreads();
-        const int kc0 = c0 / KS;
-        for (int tap = 0; tap < kk; ++tap) {
-            // prefetch the next tap's fragments (or the first tap of the next channel chunk)
-            int ntap = tap + 1, nkc0 = kc0;
-            if (ntap == kk) { ntap = 0; nkc0 = kc0 + KC; }
-            if (nkc0 < kcs) {
+    };
+    auto multiply = [&](const uint4 (&b)[KW][TN], int tp) {
+        const int ky = tp / a.k, kx = tp - ky * a.k;
+        const int tap_off = (ky * a.tw + kx) * a.ps;
+#pragma unroll
+        for (int kc = 0; kc < KW; ++kc) {
+            uint4 af[TM];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                af[tm] = *(const uint4*)(lds + a_base[tm] + tap_off + kc * (KS * S));
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], b[kc][tn], acc[tm][tn]);
+        }
+    };
+
+    if constexpr (KK > 0) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) fetch(bq[p], 0, p);
+        for (int chunk = 0; chunk < nch; ++chunk) {
+            stage(chunk);
+#pragma unroll
+            for (int tp = 0; tp < KK; ++tp) {
+                uint4 bc[KW][TN];
 #pragma unroll
                 for (int kc = 0; kc < KW; ++kc)
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        bnxt[kc][tn] = wp[tn][((long)ntap * kcs + nkc0 + kc) * 64];
+                    for (int tn = 0; tn < TN; ++tn) bc[kc][tn] = bq[tp % P][kc][tn];
+                fetch(bq[tp % P], tp + P < KK ? chunk : chunk + 1, (tp + P) % KK);
+                multiply(bc, tp);
             }
-            const int ky = tap / a.k, kx = tap - ky * a.k;
-            const int tap_off = (ky * a.tw + kx) * a.ps;
-#pragma unroll
-            for (int kc = 0; kc < KW; ++kc) {
-                uint4 af[TM];
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-                    af[tm] = *(const uint4*)(lds + a_base[tm] + tap_off + kc * (KS * S));
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], bcur[kc][tn], acc[tm][tn]);
+        }
+    } else {
+        for (int chunk = 0; chunk < nch; ++chunk) {
+            stage(chunk);
+#pragma nounroll
+            for (int tp = 0; tp < ntaps; ++tp) {
+                fetch(bq[0], chunk, tp);
+                multiply(bq[0], tp);
             }
-#pragma unroll
-            for (int kc = 0; kc < KW; ++kc)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) bcur[kc][tn] = bnxt[kc][tn];
         }
     }
 
@@ -310,10 +333,10 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     return best_score >= 0.0;
 }
 
-template <typename T, int TM, int TN, int WM, int WN, int WK, int KC>
+template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
 static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
-    auto kern = conv_kernel<T, TM, TN, WM, WN, WK, KC>;
+    auto kern = conv_kernel<T, TM, TN, WM, WN, WK, KC, KK>;
     if (p.lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)p.lds);
@@ -325,26 +348,36 @@ static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
     return SIGE_OK;
 }
 
-template <typename T, int KC>
+template <typename T, int KC, int KK>
 static int launch_kc(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
     switch (p.cfg) {
-    case 0: return launch_cfg<T, 2, 2, 2, 2, 1, KC>(a, p, st);
-    case 1: return launch_cfg<T, 2, 1, 2, 2, 1, KC>(a, p, st);
-    case 2: return launch_cfg<T, 1, 1, 2, 2, 1, KC>(a, p, st);
+    case 0: return launch_cfg<T, 2, 2, 2, 2, 1, KC, KK>(a, p, st);
+    case 1: return launch_cfg<T, 2, 1, 2, 2, 1, KC, KK>(a, p, st);
+    case 2: return launch_cfg<T, 1, 1, 2, 2, 1, KC, KK>(a, p, st);
     default:
-        if constexpr (KC % 4 == 0) return launch_cfg<T, 2, 1, 1, 1, 4, KC>(a, p, st);
+        if constexpr (KC % 4 == 0) return launch_cfg<T, 2, 1, 1, 1, 4, KC, KK>(a, p, st);
         return fail(SIGE_ERR_UNSUPPORTED, "sige_conv: internal: K-split shape without a K-split chunk");
+    }
+}
+
+template <typename T, int KK>
+static int launch_kk(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
+{
+    switch (p.kc) {
+    case 8: return launch_kc<T, 8, KK>(a, p, st);
+    case 4: return launch_kc<T, 4, KK>(a, p, st);
+    default: return launch_kc<T, 1, KK>(a, p, st);
     }
 }
 
 template <typename T>
 static int launch_conv(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
-    switch (p.kc) {
-    case 8: return launch_kc<T, 8>(a, p, st);
-    case 4: return launch_kc<T, 4>(a, p, st);
-    default: return launch_kc<T, 1>(a, p, st);
+    switch (a.k) {
+    case 3: return launch_kk<T, 9>(a, p, st);
+    case 1: return launch_kk<T, 1>(a, p, st);
+    default: return launch_kk<T, 0>(a, p, st);
     }
 }
 
