@@ -130,6 +130,25 @@ int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32
                  const void* residual_tiles, const void* residual, int32_t res_ld,
                  void* y, int32_t y_ld, void* stream);
 
+/* Sec. 3.2 "Kernel fusion" taken to its end on this hardware: Gather (with Scale+Shift and
+ * the nonlinearity), the convolution and Scatter (with the residual additions) in ONE
+ * kernel.  The input tile of each active block is gathered from x straight into LDS,
+ * multiplied on the matrix cores, and the result goes straight into y - the stacked tiles
+ * never touch HBM.  Arguments as in sige_gather / sige_conv / sige_scatter; results are
+ * bit-identical to calling those three in sequence (the convolution result is rounded to dt
+ * before the residuals are added, as a stored tile would be).  Exactly one of
+ *   y         - scatter into the cached output, in place (residuals allowed), or
+ *   out_tiles - keep the output tiles [max_blocks][block_h][block_w][Cout] (a shortcut
+ *               branch whose tiles a later call adds as residual_tiles)
+ * must be given.  x and y must not overlap (a tile's halo belongs to other blocks).     */
+int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
+                    const sige_geom* g, const int32_t* indices, const int32_t* count,
+                    int32_t max_blocks, int32_t n_blocks,
+                    const float* scale, const float* shift, sige_act act,
+                    int32_t Cout, const void* packed_weight, const float* bias,
+                    const void* residual_tiles, const void* residual, int32_t res_ld,
+                    void* y, int32_t y_ld, void* out_tiles, void* stream);
+
 /* Fig. "sige-attention" / Sec. 3.2 "Extension to attention layers": attention for the
  * edited query tokens only, against all T keys and values (the caches with the
  * edited tokens already overwritten):

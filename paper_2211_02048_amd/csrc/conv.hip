@@ -67,6 +67,16 @@ struct ConvArgs {
     int trows;  // tile rows staged: (rows-1)*stride + k
     int Cc;     // channels staged per pass (multiple of KSTEP)
     int ps;     // LDS pixel stride in bytes: Cc*size + 16 (the pad spreads pixels over banks)
+    // fused mode (x != nullptr): tiles are gathered from x on the way into LDS and the output is
+    // scattered into y (or stored as tiles when y == nullptr)
+    const void* x;
+    const int32_t* indices;
+    const float* scale;
+    const float* shift;
+    const void* res_tiles;
+    const void* res_full;
+    void* y;
+    int Hin, Win, x_ld, up, pad, act, Hout, Wout, y_ld, res_ld;
 };
 
 // Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
@@ -172,16 +182,47 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) slot[kc][tn] = wp[tn][((long)tp * kcs + chunk * KC + kc) * 64];
     };
+    const bool fused = a.x != nullptr;
+    const bool fuse_math = fused && (a.scale != nullptr || a.act != SIGE_ACT_NONE);
     auto stage = [&](int chunk) {
+        constexpr int N = Vec16<T>::N;
         const int c0 = chunk * (KC * KS);
         if (chunk) __syncthreads();
+        // 256 is a multiple of VPC, so a thread keeps one 16-byte channel group of the chunk
+        float sc[N], sh[N];
+        if (fuse_math) {
+            const int cbase = c0 + (tid % VPC) * N;
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                sc[i] = a.scale ? a.scale[cbase + i] : 1.0f;
+                sh[i] = a.scale ? a.shift[cbase + i] : 0.0f;
+            }
+        }
         for (int j = tid; j < npix * VPC; j += 256) {
             const int q = j / VPC, v = j - q * VPC;
             const int g = q / (a.trows * a.tw), rem = q - g * (a.trows * a.tw);
             const int r = rem / a.tw, x = rem - r * a.tw;
             uint4 val = make_uint4(0, 0, 0, 0);
-            if (g0 + g < n_eff && trow0 + r < a.th)
-                val = *(const uint4*)(tiles + ((((long)(g0 + g) * a.th + trow0 + r) * a.tw + x) * a.Cin + c0) * S + v * 16);
+            if (g0 + g < n_eff && trow0 + r < a.th) {
+                if (!fused) {
+                    val = *(const uint4*)(tiles + ((((long)(g0 + g) * a.th + trow0 + r) * a.tw + x) * a.Cin + c0) * S + v * 16);
+                } else {
+                    // the gather: input pixel of tile position (trow0 + r, x) of block g0 + g
+                    const int iy = a.indices[2 * (g0 + g)] * a.stride - a.pad + trow0 + r;
+                    const int ix = a.indices[2 * (g0 + g) + 1] * a.stride - a.pad + x;
+                    if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) {
+                        val = *(const uint4*)((const char*)a.x +
+                                              (((long)(iy >> a.up) * (a.Win >> a.up) + (ix >> a.up)) * a.x_ld + c0) * S + v * 16);
+                        if (fuse_math) {
+                            float f[N];
+                            unpack<T>(val, f);
+#pragma unroll
+                            for (int i = 0; i < N; ++i) f[i] = apply_act(fmaf(sc[i], f[i], sh[i]), a.act);
+                            val = pack<T>(f);   // padding never takes this branch: it stays literally zero
+                        }
+                    }
+                }
+            }
             *(uint4*)(lds + q * a.ps + v * 16) = val;
         }
         __syncthreads();
@@ -230,6 +271,27 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     }
 
     T* __restrict__ out = (T*)a.out;
+    // One output element: row m of this workgroup's patch, output channel o, fp32 value v (bias
+    // included).  Plain mode stores the tile element; fused mode rounds it to the storage type as
+    // a stored tile would be, adds the residuals in fp32 and scatters it into y (clipped).
+    auto emit = [&](int m, int o, float v) {
+        const int g = m / pb, p = m - g * pb;
+        const int py = p / a.bw, px = p - py * a.bw;
+        if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) return;
+        const long t = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o;
+        if (!fused || a.y == nullptr) { out[t] = from_f32<T>(v); return; }
+        const int oy = a.indices[2 * (g0 + g)] + band_row0 + py, ox = a.indices[2 * (g0 + g) + 1] + px;
+        if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) return;
+        const long pix = (long)oy * a.Wout + ox;
+        T r = from_f32<T>(v);
+        if (a.res_tiles || a.res_full) {
+            float f = to_f32(r);
+            if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t]);
+            if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o]);
+            r = from_f32<T>(f);
+        }
+        ((T*)a.y)[pix * a.y_ld + o] = r;
+    };
     if (WK > 1) {
         // sum the K-split partials through LDS, then store with consecutive lanes on consecutive
         // output channels
@@ -252,11 +314,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
             float v = 0.0f;
 #pragma unroll
             for (int w = 0; w < WK; ++w) v += red[(w * BM + m) * (BN + 1) + nn];
-            const int g = m / pb, p = m - g * pb;
-            const int py = p / a.bw, px = p - py * a.bw;
-            const int o = blockIdx.x * BN + nn;
-            if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
-            out[(((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o] = from_f32<T>(v);
+            emit(m, blockIdx.x * BN + nn, v);
         }
         return;
     }
@@ -266,15 +324,8 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            const int g = m / pb, p = m - g * pb;
-            const int py = p / a.bw, px = p - py * a.bw;
-            if (g >= a.G || py >= band_rows || g0 + g >= n_eff) continue;
-            const long base = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout;
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int o = (nt0 + tn) * 32 + l32;
-                if (o < a.Cout) out[base + o] = from_f32<T>(acc[tm][tn][r]);
-            }
+            for (int tn = 0; tn < TN; ++tn) emit(m, (nt0 + tn) * 32 + l32, acc[tm][tn][r]);
         }
     }
 }
@@ -298,6 +349,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     double best_score = -1.0;
     for (int cfg = 0; cfg < 4; ++cfg) {
         if (force && atoi(force) != cfg) continue;
+        if (g->k != 1 && g->k != 3 && cfg != 2) continue;   // only the plain 64x64 shape is built for other k
         const int M = kCfg[cfg].M, Nn = kCfg[cfg].N, WK = kCfg[cfg].WK;
         if (g->block_w > M) continue;
         ConvPlan p;
@@ -314,6 +366,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         p.kc = 0;
         for (int kc : {8, 4, 1}) {
             if (kc % WK || Cin % (kc * kstep)) continue;
+            if (g->k != 1 && g->k != 3 && kc != 1) continue;
             size_t lds = (size_t)npix * (kc * kstep * s + 16);
             if (WK > 1) lds = std::max(lds, (size_t)WK * M * (Nn + 1) * sizeof(float));
             if (lds <= (kc == 1 || (kc == 4 && WK == 4) ? 160u : 64u) * 1024u) { p.kc = kc; p.lds = lds; break; }
@@ -377,7 +430,7 @@ static int launch_conv(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
     switch (a.k) {
     case 3: return launch_kk<T, 9>(a, p, st);
     case 1: return launch_kk<T, 1>(a, p, st);
-    default: return launch_kk<T, 0>(a, p, st);
+    default: return launch_cfg<T, 1, 1, 2, 2, 1, 1, 0>(a, p, st);   // other kernel sizes: one plain shape
     }
 }
 
@@ -418,6 +471,25 @@ extern "C" int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout,
     return SIGE_OK;
 }
 
+// Shared by sige_conv and sige_fused_conv: plan, fill the arguments, launch.
+static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, int tw, int Cin, int Cout,
+                    int max_blocks, int n_blocks, int nl, ConvArgs& a, void* stream)
+{
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    ConvPlan p;
+    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, &p), SIGE_ERR_UNSUPPORTED,
+                 "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who, g->block_h, g->block_w,
+                 g->k, g->stride, Cin);
+    SIGE_REQUIRE(p.groups <= 65535 && p.bands <= 65535, SIGE_ERR_UNSUPPORTED, "%s: too many blocks per launch", who);
+    a.th = th; a.tw = tw; a.bh = g->block_h; a.bw = g->block_w; a.k = g->k; a.stride = g->stride;
+    a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
+    a.G = p.G; a.rows = p.rows; a.trows = p.trows; a.Cc = p.Cc; a.ps = p.ps;
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == SIGE_F32) return launch_conv<float>(a, p, st);
+    if (dt == SIGE_F16) return launch_conv<f16>(a, p, st);
+    return launch_conv<bf16>(a, p, st);
+}
+
 extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
                          const void* packed_weight, const float* bias, const int32_t* count,
                          int32_t max_blocks, int32_t n_blocks, void* out_tiles, void* stream)
@@ -436,18 +508,50 @@ extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, i
     SIGE_REQUIRE(aligned16(tiles) && aligned16(packed_weight), SIGE_ERR_UNSUPPORTED,
                  "%s: tiles and packed_weight must be 16-byte aligned", who);
     if (nl == 0) return SIGE_OK;
-    ConvPlan p;
-    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, &p), SIGE_ERR_UNSUPPORTED,
-                 "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who, g->block_h, g->block_w,
-                 g->k, g->stride, Cin);
-    SIGE_REQUIRE(p.groups <= 65535 && p.bands <= 65535, SIGE_ERR_UNSUPPORTED, "%s: too many blocks per launch", who);
-    ConvArgs a;
+    ConvArgs a = {};
     a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
-    a.th = th; a.tw = tw; a.bh = g->block_h; a.bw = g->block_w; a.k = g->k; a.stride = g->stride;
-    a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
-    a.G = p.G; a.rows = p.rows; a.trows = p.trows; a.Cc = p.Cc; a.ps = p.ps;
-    hipStream_t st = (hipStream_t)stream;
-    if (dt == SIGE_F32) return launch_conv<float>(a, p, st);
-    if (dt == SIGE_F16) return launch_conv<f16>(a, p, st);
-    return launch_conv<bf16>(a, p, st);
+    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, stream);
+}
+
+extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
+                               const sige_geom* g, const int32_t* indices, const int32_t* count,
+                               int32_t max_blocks, int32_t n_blocks, const float* scale, const float* shift,
+                               sige_act act, int32_t Cout, const void* packed_weight, const float* bias,
+                               const void* residual_tiles, const void* residual, int32_t res_ld, void* y,
+                               int32_t y_ld, void* out_tiles, void* stream)
+{
+    clear_error();
+    const char* who = "sige_fused_conv";
+    int th, tw, nl;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(x && indices && packed_weight, SIGE_ERR_INVALID_ARG, "%s: x, indices and packed_weight are required", who);
+    SIGE_REQUIRE((y != nullptr) != (out_tiles != nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: give either y (scatter) or out_tiles (keep the tiles), not both and not neither", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cin > 0 && Cout > 0 && x_ld >= Cin, SIGE_ERR_INVALID_ARG, "%s: need Cin, Cout > 0 and x_ld >= Cin", who);
+    SIGE_REQUIRE(y == nullptr || y_ld >= Cout, SIGE_ERR_INVALID_ARG, "%s: y_ld must be >= Cout", who);
+    SIGE_REQUIRE(residual == nullptr || res_ld >= Cout, SIGE_ERR_INVALID_ARG, "%s: res_ld must be >= Cout", who);
+    SIGE_REQUIRE(y != nullptr || (residual_tiles == nullptr && residual == nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: residuals are added by the scatter; they need y", who);
+    SIGE_REQUIRE((scale == nullptr) == (shift == nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: scale and shift must be given together", who);
+    SIGE_REQUIRE(act == SIGE_ACT_NONE || act == SIGE_ACT_SILU || act == SIGE_ACT_RELU, SIGE_ERR_INVALID_ARG,
+                 "%s: unknown activation %d", who, (int)act);
+    SIGE_REQUIRE(up == 0 || up == 1, SIGE_ERR_INVALID_ARG, "%s: up must be 0 or 1", who);
+    SIGE_REQUIRE(up == 0 || (g->H_in % 2 == 0 && g->W_in % 2 == 0), SIGE_ERR_INVALID_ARG,
+                 "%s: up-sampled input size must be even", who);
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    const size_t s = dtype_size(dt);
+    SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
+    SIGE_REQUIRE((x_ld * s) % 16 == 0 && aligned16(x) && aligned16(packed_weight), SIGE_ERR_UNSUPPORTED,
+                 "%s: x and packed_weight must be 16-byte aligned and x_ld a multiple of %zu elements", who, 16 / s);
+    if (nl == 0) return SIGE_OK;
+    ConvArgs a = {};
+    a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
+    a.x = x; a.indices = indices; a.scale = scale; a.shift = shift;
+    a.res_tiles = residual_tiles; a.res_full = residual; a.y = y;
+    a.Hin = g->H_in; a.Win = g->W_in; a.x_ld = x_ld; a.up = up; a.pad = g->pad; a.act = (int)act;
+    a.Hout = g->H_out; a.Wout = g->W_out; a.y_ld = y_ld; a.res_ld = res_ld;
+    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, stream);
 }

@@ -88,10 +88,18 @@ class SigeConv:
         return n * self.g.block_h * self.g.block_w * self.Cout
 
     def forward(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None,
-                act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t"):
-        """gather(x) -> conv -> scatter into y (in place).  Returns the output tiles."""
+                act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False):
+        """gather(x) -> conv -> scatter into y (in place), as three calls or as the one fused call.
+        Returns the output tiles (None when the fused call scattered them directly)."""
         g, n = self.g, blocks.n_host
         cap = blocks.max_blocks if n < 0 else max(n, 1)
+        if fused:
+            out_tiles = None if scatter else ws.get("out_" + tag, self.out_numel(cap), self.dtype)
+            api.sige_fused_conv(x, g, blocks.indices, blocks.count, self.Cin, self.Cout, self.packed, self.bias,
+                                y=y if scatter else None, out_tiles=out_tiles, n_blocks=n, max_blocks=cap,
+                                scale=scale, shift=shift, act=act, up=self.up, residual_tiles=residual_tiles,
+                                residual=residual)
+            return out_tiles
         tiles = ws.get("tiles", self.tiles_numel(cap), self.dtype)
         out_tiles = ws.get("out_" + tag, self.out_numel(cap), self.dtype)
         api.sige_gather(x, g, blocks.indices, blocks.count, tiles, n_blocks=n, scale=scale, shift=shift,

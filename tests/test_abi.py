@@ -70,6 +70,17 @@ def test_pointer_and_capacity_errors(L):
     assert L.sige_gather(FAKE, 0, 3, 3, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 2
     assert L.sige_conv(FAKE, 1, gp, 24, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
     assert L.sige_conv(FAKE, 0, gp, 4, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
+    # fused call: exactly one destination
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             FAKE, 64, FAKE, None) == 1
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             None, 0, None, None) == 1
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, FAKE, None, 0,
+                             None, 0, FAKE, None) == 1       # residuals need y
+    assert L.sige_fused_conv(FAKE, 1, 24, 24, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             FAKE, 64, None, None) == 2
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, 9, None, None, 0, 64, FAKE, None, None, None, 0,
+                             FAKE, 64, None, None) == 3
     # scale without shift
     assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, -1, FAKE, None, 0, FAKE, None) == 1
     # unknown dtype

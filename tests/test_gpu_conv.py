@@ -316,7 +316,11 @@ def sparse_layer(cfg, *, fused, shortcut=False, device_count=False, cache=None):
                           eps=cfg["eps"], scale=scale, shift=shift)
         act = api.ACT_SILU
     conv.forward(a_e, y, bl, ws, scale=scale, shift=shift, act=act)
+    # the fused call (gather -> LDS -> MFMA -> scatter in one kernel) must give the same bits
+    y_f = dev(cache).clone()
+    conv.forward(a_e, y_f, bl, ws, scale=scale, shift=shift, act=act, fused=True)
     torch.cuda.synchronize()
+    assert torch.equal(y, y_f), "fused call differs from gather + conv + scatter"
     n = int(bl.count.item())
     return y, bl.indices[:n].cpu().numpy(), mask_out.cpu().numpy()
 
@@ -405,6 +409,17 @@ def test_layer_config2_shortcut_and_residual(oracle):
     main.forward(dev(cfg["a_edit"]), y, bl3, wsp, residual_tiles=res_tiles, tag="m")
     want = oracle.select_blocks(dense_sum(a_e), f64(cache_sum), blocks3, 16, 16)
     assert_close(y, want, td, "main + shortcut")
+    y_f = dev(cache_sum).clone()
+    res_f = sc3.forward(dev(cfg["a_edit"]), None, bl3, wsp, scatter=False, tag="sf", fused=True)
+    assert torch.equal(res_f, res_tiles)
+    full_res = dev(cfg["a_orig"])[:, :, :64].contiguous()
+    main.forward(dev(cfg["a_edit"]), y_f, bl3, wsp, residual_tiles=res_f, tag="mf", fused=True)
+    assert torch.equal(y_f, y)
+    # both residual kinds at once, three calls vs fused
+    y1, y2 = dev(cache_sum).clone(), dev(cache_sum).clone()
+    main.forward(dev(cfg["a_edit"]), y1, bl3, wsp, residual_tiles=res_tiles, residual=full_res, tag="m")
+    main.forward(dev(cfg["a_edit"]), y2, bl3, wsp, residual_tiles=res_f, residual=full_res, tag="mf", fused=True)
+    assert torch.equal(y1, y2)
 
 
 def test_layer_all_active_equals_dense_and_zero_blocks(oracle):
@@ -417,13 +432,18 @@ def test_layer_all_active_equals_dense_and_zero_blocks(oracle):
     conv.forward(dev(cfg["a_edit"]), y, bl, ws)
     want = oracle.conv2d(f64(cfg["a_edit"]), f64(cfg["w"]), f64(cfg["bias"]), 1, 1)
     assert_close(y, want, td, "all active == dense")
+    y_f = torch.full((40, 56, 32), float("nan"), dtype=td, device="cuda")
+    conv.forward(dev(cfg["a_edit"]), y_f, bl, ws, fused=True)
+    assert torch.equal(y, y_f)
     # no active block: y untouched bitwise, through both count paths
     poison = torch.from_numpy(np.random.default_rng(1).standard_normal((40, 56, 32)).astype(np.float32)).to(td).cuda()
     y = poison.clone()
     bl.reduce(mask_in=torch.zeros((40, 56), dtype=torch.uint8, device="cuda"))
     conv.forward(dev(cfg["a_edit"]), y, bl, ws)
+    conv.forward(dev(cfg["a_edit"]), y, bl, ws, fused=True)
     bl.sync_count()
     conv.forward(dev(cfg["a_edit"]), y, bl, ws)
+    conv.forward(dev(cfg["a_edit"]), y, bl, ws, fused=True)
     torch.cuda.synchronize()
     assert torch.equal(y, poison)
 
@@ -446,6 +466,9 @@ def test_layer_stride2_and_upsample(oracle):
     y = dev(cache).clone()
     conv.forward(dev(a_e), y, bl, Workspace("cuda"))
     assert_close(y, oracle.conv2d(f64(a_e), f64(w), f64(b), 2, 1), td, "stride 2 == dense")
+    y_f = dev(cache).clone()
+    conv.forward(dev(a_e), y_f, bl, Workspace("cuda"), fused=True)
+    assert torch.equal(y, y_f)
     # nearest x2 up-sampling followed by a 3x3 conv, mask taken at the output resolution
     up_o = f64(a_o).repeat(2, axis=0).repeat(2, axis=1)
     up_e = f64(a_e).repeat(2, axis=0).repeat(2, axis=1)
@@ -458,6 +481,9 @@ def test_layer_stride2_and_upsample(oracle):
     y = dev(cache).clone()
     convu.forward(dev(a_e), y, blu, Workspace("cuda"))
     assert_close(y, oracle.conv2d(up_e, f64(w), f64(b), 1, 1), td, "upsample+conv == dense")
+    y_f = dev(cache).clone()
+    convu.forward(dev(a_e), y_f, blu, Workspace("cuda"), fused=True)
+    assert torch.equal(y, y_f)
 
 
 def test_layer_config2_full_size_sampled(oracle):

@@ -88,6 +88,16 @@ def test_unet_precompute_and_sparse_step(setup):
     assert checked >= 20
     # the edit really changed the output, and only moderately many blocks were touched
     assert not torch.equal(net.B["out"], gpu_cache["out"])
+    # the three-call path (gather, conv, scatter) and the fused call give the same bits
+    three_calls = {n: b.clone() for n, b in net.B.items()}
+    net.fused = True
+    for n in gpu_cache:
+        net.B[n].copy_(gpu_cache[n])
+    net.step(s["img_e"].cuda())
+    torch.cuda.synchronize()
+    net.fused = False
+    for n in three_calls:
+        assert torch.equal(net.B[n], three_calls[n]), ("fused vs three calls", n)
 
 
 def test_unet_zero_edit_and_graph_replay(setup):
