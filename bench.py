@@ -1,14 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the block-sparse layer hot path on one MI355X.
 
-A step is one pass of the whole path over BASELINE config 2 (256x256x128 fp16, ~1 % blob
-edit, 16x16 blocks): difference mask + block lists (3x3 and 1x1), then
-gather(GN+SiLU) -> conv3x3 -> scatter and gather -> conv1x1 -> scatter, inputs resident in
-HBM.  `value` is the algorithmic bytes of one step divided by its wall time.  The line also
-carries the roofline of the dominant kernel (measured live with events on the launch stream),
-the CPU oracle timed on the host cores, and supplements: per-call times, gather/scatter
-bandwidth on a 1024x1024x128 tensor with 20 % of the blocks active, dense-equivalent conv
-throughput, and sparse-query attention.
+A step is one pass of the whole path over BASELINE config 2 (256x256x128 fp16, ~1 % blob edit,
+16x16 blocks): difference mask + block lists (3x3 and 1x1 geometry), then gather(GN+SiLU) ->
+conv3x3 -> scatter and gather -> conv1x1 -> scatter, inputs resident in HBM, replayed as one HIP
+graph (block counts stay on the device).  `value` is the algorithmic bytes of one step divided by
+its wall time.  The line also carries
+  roofline      - the kernel that takes longest in the step (the 3x3 convolution: MFMA bound),
+  roofline_hbm  - the step's HBM-bound kernel (the difference-mask stream),
+both timed live with events on the launch stream, the CPU oracle timed on the host cores, and
+`supplement`: per-call times, gather / scatter / difference-mask bandwidth on a 1024x1024x128
+tensor with every block active (footprint far beyond the 256 MB Infinity Cache), convolution
+throughput with every block active, sparse-query attention, and the synthetic DDPM-style UNet
+step (BASELINE config 3) sparse at ~1.2 % and 15.5 % edit versus dense.
 """
 import argparse
 import json
@@ -29,8 +33,18 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--no-supplement", action="store_true", help="only the headline step")
+    ap.add_argument("--no-supplement", action="store_true", help="only the headline step and rooflines")
+    ap.add_argument("--no-unet", action="store_true", help="skip the UNet step in the supplement")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="gather, conv, scatter as three kernels per convolution instead of the fused one")
     return ap.parse_args()
+
+
+def next_pow2(n):
+    p = 1
+    while p < n:
+        p *= 2
+    return p
 
 
 def time_calls(fn, iters, warm=20):
@@ -48,24 +62,17 @@ def time_calls(fn, iters, warm=20):
     return e0.elapsed_time(e1) * 1e3 / iters
 
 
-def next_pow2(n):
-    p = 1
-    while p < n:
-        p *= 2
-    return p
-
-
 class Layer2:
-    """Config 2 on the device: caches from a first all-active pass, then the sparse step.
-    The step is captured once in a HIP graph: every kernel takes the block count from device
-    memory and the launches are sized by a capacity chosen after the first reduction of an edit,
-    so a replay needs no host round trip."""
+    """Config 2 on the device: caches from a first all-active pass, then the sparse step.  The step
+    is captured once in a HIP graph: every kernel takes the block count from device memory and the
+    launches are sized by a capacity chosen after the first reduction of an edit, so a replay needs
+    no host round trip."""
 
-    def __init__(self, cfg, device="cuda"):
+    def __init__(self, cfg, fused, device="cuda"):
         import torch
         from paper_2211_02048_amd import api
         from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
-        self.api, self.cfg = api, cfg
+        self.api, self.cfg, self.fused = api, cfg, fused
         H, W, C, Cs = cfg["H"], cfg["W"], cfg["Cin"], cfg["Cs"]
         self.a_o, self.a_e = cfg["a_orig"].to(device), cfg["a_edit"].to(device)
         self.main = SigeConv(cfg["w"].to(device), cfg["bias"], H, W, cfg["block"], 1, 1)
@@ -96,8 +103,8 @@ class Layer2:
     def layer(self):
         api = self.api
         self.main.forward(self.a_e, self.y_main, self.bl3, self.ws, scale=self.scale, shift=self.shift,
-                          act=api.ACT_SILU)
-        self.short.forward(self.a_e, self.y_short, self.bl1, self.ws)
+                          act=api.ACT_SILU, fused=self.fused)
+        self.short.forward(self.a_e, self.y_short, self.bl1, self.ws, fused=self.fused)
 
     def step_eager(self):
         self.reduce()
@@ -141,8 +148,12 @@ class Layer2:
         t = b + 2
         diff = 2 * c["H"] * c["W"] * C * s + c["H"] * c["W"]
         lists = 2 * c["H"] * c["W"] + 8 * (n3 + n1) + 8
-        main = n3 * (2 * t * t * C * s + 2 * b * b * C * s + t * t * C * s + b * b * C * s) + 9 * C * C * s
-        short = n1 * (2 * b * b * C * s + 2 * b * b * Cs * s + b * b * C * s + b * b * Cs * s) + C * Cs * s
+        if self.fused:   # tile read once, output block written once
+            main = n3 * (t * t * C * s + b * b * C * s) + 9 * C * C * s
+            short = n1 * (b * b * C * s + b * b * Cs * s) + C * Cs * s
+        else:            # gather r+w, conv r+w, scatter r+w
+            main = n3 * (2 * t * t * C * s + 2 * b * b * C * s + t * t * C * s + b * b * C * s) + 9 * C * C * s
+            short = n1 * (2 * b * b * C * s + 2 * b * b * Cs * s + b * b * C * s + b * b * Cs * s) + C * Cs * s
         return diff + lists + main + short, diff
 
     def flops_per_step(self, n3, n1):
@@ -182,40 +193,42 @@ def cpu_baseline(cfg, n_bytes):
         if time.perf_counter() - t_all > 10.0 or len(times) >= 10:
             break
     t = float(np.median(times))
-    return {"value": n_bytes / t / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+    return {"value": round(n_bytes / t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": f"whole config-2 step (dense GN+SiLU+3x3 and 1x1 layers on the edited input, then "
-                      f"block selection), median of {len(times)} runs", "s_per_step": t}
+                      f"block selection), median of {len(times)} runs", "s_per_step": round(t, 4)}
 
 
-def supplement(L, dtype_name):
+def supplement(L, with_unet):
     """Per-call times at config 2 and bandwidth / throughput points in regimes where they show."""
-    import numpy as np
     import torch
     from paper_2211_02048_amd import api, inputs
-    from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
+    from paper_2211_02048_amd.layers import BlockList, SigeConv
     out = {}
     c = L.cfg
     n3, n1 = L.bl3.n_host, L.bl1.n_host
-    # ---- per-call times at config 2 (exact host block count)
+    # ---- per-call times at config 2 (exact host block count, eager launches)
     g3, ws = L.main.g, L.ws
     tiles = ws.get("tiles", L.main.tiles_numel(max(n3, 1)), L.a_e.dtype)
     ot = ws.get("out_t", L.main.out_numel(max(n3, 1)), L.a_e.dtype)
     per = {}
-    per["reduce_mask_diff_us"] = time_calls(lambda: L.bl3.reduce(a_orig=L.a_o, a_edit=L.a_e, tau=c["tau"],
-                                                                 mask_out=L.mask), 200)
-    per["reduce_mask_list_us"] = time_calls(lambda: L.bl1.reduce(mask_in=L.mask), 200)
+    per["reduce_mask_from_activations_us"] = time_calls(
+        lambda: L.bl3.reduce(a_orig=L.a_o, a_edit=L.a_e, tau=c["tau"], mask_out=L.mask), 200)
+    per["reduce_mask_from_mask_us"] = time_calls(lambda: L.bl1.reduce(mask_in=L.mask), 200)
     L.bl3.n_host, L.bl1.n_host = n3, n1
-    per["gather_fused_us"] = time_calls(lambda: api.sige_gather(L.a_e, g3, L.bl3.indices, L.bl3.count, tiles,
-                                                                n_blocks=n3, scale=L.scale, shift=L.shift,
-                                                                act=api.ACT_SILU, max_blocks=max(n3, 1)), 200)
-    per["conv3x3_us"] = time_calls(lambda: api.sige_conv(tiles, g3, c["Cin"], c["Cout"], L.main.packed, L.main.bias,
-                                                         L.bl3.count, ot, n_blocks=n3, max_blocks=max(n3, 1)), 200)
-    per["scatter_us"] = time_calls(lambda: api.sige_scatter(ot, g3, L.bl3.indices, L.bl3.count, L.y_main,
-                                                            n_blocks=n3, Cout=c["Cout"], max_blocks=max(n3, 1)), 200)
-    per["layer_only_us"] = time_calls(L.layer, 200)
-    out["config2_calls"] = {k: round(v, 2) for k, v in per.items()}
-    out["config2_calls"]["n_blocks_3x3"] = n3
-    out["config2_calls"]["n_blocks_1x1"] = n1
+    per["gather_fused_gn_silu_us"] = time_calls(
+        lambda: api.sige_gather(L.a_e, g3, L.bl3.indices, L.bl3.count, tiles, n_blocks=n3, scale=L.scale,
+                                shift=L.shift, act=api.ACT_SILU, max_blocks=max(n3, 1)), 200)
+    per["conv3x3_us"] = time_calls(
+        lambda: api.sige_conv(tiles, g3, c["Cin"], c["Cout"], L.main.packed, L.main.bias, L.bl3.count, ot,
+                              n_blocks=n3, max_blocks=max(n3, 1)), 200)
+    per["scatter_us"] = time_calls(
+        lambda: api.sige_scatter(ot, g3, L.bl3.indices, L.bl3.count, L.y_main, n_blocks=n3, Cout=c["Cout"],
+                                 max_blocks=max(n3, 1)), 200)
+    per["fused_conv3x3_us"] = time_calls(
+        lambda: L.main.forward(L.a_e, L.y_main, L.bl3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU,
+                               fused=True), 200)
+    out["config2_calls_eager"] = {k: round(v, 2) for k, v in per.items()}
+    out["config2_calls_eager"]["note"] = "eager single calls include the host launch path (a few us each)"
 
     # ---- dense comparator: the same kernels with every block active
     full3 = BlockList(g3, "cuda").all_active()
@@ -223,9 +236,14 @@ def supplement(L, dtype_name):
     y3, y1 = torch.empty_like(L.y_main), torch.empty_like(L.y_short)
 
     def dense():
-        L.main.forward(L.a_e, y3, full3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU)
-        L.short.forward(L.a_e, y1, full1, ws)
+        L.main.forward(L.a_e, y3, full3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=L.fused)
+        L.short.forward(L.a_e, y1, full1, ws, fused=L.fused)
+
+    def sparse():
+        L.main.forward(L.a_e, L.y_main, L.bl3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=L.fused)
+        L.short.forward(L.a_e, L.y_short, L.bl1, ws, fused=L.fused)
     dense_us = time_calls(dense, 50, 5)
+    sparse_us = time_calls(sparse, 200, 5)
     nfull = g3.grid_blocks
     tl = ws.get("tiles", L.main.tiles_numel(nfull), L.a_e.dtype)
     of = ws.get("out_t", L.main.out_numel(nfull), L.a_e.dtype)
@@ -234,52 +252,48 @@ def supplement(L, dtype_name):
     conv_us = time_calls(lambda: api.sige_conv(tl, g3, c["Cin"], c["Cout"], L.main.packed, L.main.bias, full3.count,
                                                of, n_blocks=nfull, max_blocks=nfull), 50, 5)
     fl = 2.0 * c["H"] * c["W"] * 9 * c["Cin"] * c["Cout"]
-    out["dense_all_active"] = {"layer_us": round(dense_us, 1), "conv3x3_us": round(conv_us, 1),
-                               "conv3x3_tflops": round(fl / conv_us / 1e6, 1),
-                               "conv3x3_frac_mfma_peak": round(fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS[dtype_name], 4),
-                               "sparse_layer_speedup": round(dense_us / per["layer_only_us"], 2)}
+    out["config2_all_blocks_active"] = {
+        "both_convs_us": round(dense_us, 1), "both_convs_sparse_us": round(sparse_us, 1),
+        "sparse_over_dense_speedup": round(dense_us / sparse_us, 2),
+        "conv3x3_us": round(conv_us, 1), "conv3x3_tflops": round(fl / conv_us / 1e6, 1),
+        "conv3x3_frac_mfma_peak": round(fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 4)}
 
-    # ---- bandwidth regime: 1024x1024x128 fp16 (256 MiB per tensor), 20 % of the 4096 blocks active
+    # ---- bandwidth regime: 1024x1024x128 fp16 (256 MiB per tensor), all 4096 blocks active
     H2 = 1024
     C = c["Cin"]
-    rng = np.random.Generator(np.random.PCG64(2002))
     x = torch.randn((H2, H2, C), dtype=torch.float16, device="cuda")
     x2 = x.clone()
-    m = inputs.blob_mask(rng, H2, H2, int(0.16 * H2 * H2), 12, (40.0, 120.0), tol=0.1)
     big = SigeConv(c["w"].cuda(), c["bias"], H2, H2, 16, 1, 1)
-    bl = BlockList(big.g, "cuda")
-    md = torch.from_numpy(m).cuda()
-    bl.reduce(mask_in=md)
-    nb = bl.sync_count()
+    bl = BlockList(big.g, "cuda").all_active()
+    nb = bl.n_host
     t2 = torch.empty(big.tiles_numel(nb), dtype=torch.float16, device="cuda")
     o2 = torch.empty(big.out_numel(nb), dtype=torch.float16, device="cuda")
     y2 = torch.empty((H2, H2, C), dtype=torch.float16, device="cuda")
     sc, sh = L.scale, L.shift
     g_us = time_calls(lambda: api.sige_gather(x, big.g, bl.indices, bl.count, t2, n_blocks=nb, scale=sc, shift=sh,
-                                              act=api.ACT_SILU, max_blocks=nb), 30, 3)
+                                              act=api.ACT_SILU, max_blocks=nb), 20, 3)
     gp_us = time_calls(lambda: api.sige_gather(x, big.g, bl.indices, bl.count, t2, n_blocks=nb, max_blocks=nb),
-                       30, 3)
+                       20, 3)
     s_us = time_calls(lambda: api.sige_scatter(o2, big.g, bl.indices, bl.count, y2, n_blocks=nb, Cout=C,
-                                               max_blocks=nb), 30, 3)
+                                               max_blocks=nb), 20, 3)
     c_us = time_calls(lambda: api.sige_conv(t2, big.g, C, C, big.packed, big.bias, bl.count, o2, n_blocks=nb,
                                             max_blocks=nb), 10, 2)
     mask_o = torch.zeros((H2, H2), dtype=torch.uint8, device="cuda")
-    d_us = time_calls(lambda: bl.reduce(a_orig=x, a_edit=x2, tau=0.0, mask_out=mask_o), 20, 2)
-    l_us = time_calls(lambda: bl.reduce(mask_in=md), 20, 2)
-    d_us = max(d_us - l_us, 1e-3)
-    bl.n_host = nb
+    d_us = time_calls(lambda: api.sige_reduce_mask(big.g, None, None, a_orig=x, a_edit=x2, tau=0.0,
+                                                   mask_out=mask_o), 20, 2)
     gb = nb * 2 * 18 * 18 * C * 2
     sb = nb * 2 * 16 * 16 * C * 2
     db = 2 * H2 * H2 * C * 2 + H2 * H2
     cf = 2.0 * nb * 256 * 9 * C * C
-    out["bandwidth_1024x1024x128"] = {
-        "active_blocks": nb, "of_blocks": big.g.grid_blocks,
-        "gather_fused_us": round(g_us, 1), "gather_fused_GBs": round(gb / g_us / 1e3, 1),
-        "gather_fused_frac_hbm_peak": round(gb / g_us / 1e3 / HBM_PEAK_GBS, 4),
-        "gather_plain_GBs": round(gb / gp_us / 1e3, 1),
+    out["bandwidth_1024x1024x128_all_blocks"] = {
+        "active_blocks": nb,
+        "gather_plain_us": round(gp_us, 1), "gather_plain_GBs": round(gb / gp_us / 1e3, 1),
+        "gather_plain_frac_hbm_peak": round(gb / gp_us / 1e3 / HBM_PEAK_GBS, 4),
+        "gather_fused_gn_silu_us": round(g_us, 1), "gather_fused_gn_silu_GBs": round(gb / g_us / 1e3, 1),
+        "gather_fused_gn_silu_frac_hbm_peak": round(gb / g_us / 1e3 / HBM_PEAK_GBS, 4),
         "scatter_us": round(s_us, 1), "scatter_GBs": round(sb / s_us / 1e3, 1),
         "scatter_frac_hbm_peak": round(sb / s_us / 1e3 / HBM_PEAK_GBS, 4),
-        "block_list_us": round(l_us, 1), "diff_mask_us": round(d_us, 1), "diff_mask_GBs": round(db / d_us / 1e3, 1),
+        "diff_mask_us": round(d_us, 1), "diff_mask_GBs": round(db / d_us / 1e3, 1),
         "diff_mask_frac_hbm_peak": round(db / d_us / 1e3 / HBM_PEAK_GBS, 4),
         "conv3x3_us": round(c_us, 1), "conv3x3_tflops": round(cf / c_us / 1e6, 1),
         "conv3x3_frac_mfma_peak": round(cf / c_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 4)}
@@ -288,7 +302,7 @@ def supplement(L, dtype_name):
     # ---- sparse-query attention at the Stable-Diffusion 64x64 level (bf16, 8 heads x 40)
     att = {}
     T, heads, d = 4096, 8, 40
-    for frac, nq in (("1pct", 96), ("5pct", 400), ("20pct", 1200), ("dense", 4096)):
+    for frac, nq in (("1pct", 96), ("5pct", 400), ("20pct", 1200), ("all_queries", 4096)):
         cs = inputs.attention_case(7, T, heads, d, nq, "bf16")
         q, k, v = cs["q"].cuda(), cs["k"].cuda(), cs["v"].cuda()
         o = torch.empty_like(q)
@@ -296,7 +310,44 @@ def supplement(L, dtype_name):
         wsb = torch.empty(max(nbytes // 4, 1), dtype=torch.float32, device="cuda") if nbytes else None
         us = time_calls(lambda: api.sige_sparse_attn(q, k, v, o, cs["scale"], workspace=wsb), 50, 5)
         att[frac] = {"n_q": nq, "us": round(us, 1), "tflops": round(4.0 * nq * T * heads * d / us / 1e6, 2)}
+    att["all_over_1pct_speedup"] = round(att["all_queries"]["us"] / att["1pct"]["us"], 2)
     out["sparse_attention_T4096_h8_d40_bf16"] = att
+
+    # ---- the synthetic DDPM-style UNet step (BASELINE config 3)
+    if with_unet:
+        from paper_2211_02048_amd.unet import SigeUNet
+        net = SigeUNet()
+        un = {"config": "256x256x3, channels 128/128/256/256/512/512, 2 ResBlocks per level, attention at "
+                        "16x16, fp16, 16x16 blocks, dilation 1, sparse layers at resolution >= 64",
+              "dense_gmacs": round(net.macs() / 1e9, 1)}
+        for name, frac in (("edit_1.2pct", 0.012), ("edit_15.5pct", 0.155)):
+            io, ie, mask = inputs.unet_images(1003, 256, frac)
+            io, ie = io.cuda(), ie.cuda()
+            md = torch.from_numpy(mask).cuda()
+            net.precompute(io)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                net.precompute(io)
+            torch.cuda.synchronize()
+            dense_ms = (time.perf_counter() - t0) / 10 * 1e3
+            counts = net.set_edit(md, exact=False)
+            g = net.capture(ie)
+            for _ in range(5):
+                g.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(50):
+                g.replay()
+            torch.cuda.synchronize()
+            sparse_ms = (time.perf_counter() - t0) / 50 * 1e3
+            un[name] = {"edited_px": int(mask.sum()), "dense_step_ms": round(dense_ms, 3),
+                        "sparse_step_ms": round(sparse_ms, 3), "speedup": round(dense_ms / sparse_ms, 2),
+                        "sparse_gmacs": round(net.macs(counts) / 1e9, 1),
+                        "macs_reduction": round(net.macs() / net.macs(counts), 2)}
+        un["note"] = ("dense = the same kernels with every block active and group statistics computed on the "
+                      "fly; sparse = one HIP graph replay, cached statistics, device-side block counts")
+        out["unet_step_config3"] = un
     return out
 
 
@@ -312,7 +363,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = inputs.config2()
-    L = Layer2(cfg)
+    L = Layer2(cfg, fused=not args.three_calls)
     n3, n1 = L.capture()
 
     for _ in range(args.warmup):
@@ -329,25 +380,42 @@ def main():
     eager_us = time_calls(L.step_eager, 100)
     L.bl3.sync_count(), L.bl1.sync_count()
 
-    # dominant kernel: the difference-mask stream (both activations read once).  Rotate over
-    # distinct buffer pairs (> 256 MB in total) so that the Infinity Cache cannot serve them.
+    # roofline 1: the longest kernel of the step, the 3x3 convolution on the active blocks
+    if L.fused:
+        conv_call = lambda: L.main.forward(L.a_e, L.y_main, L.bl3, L.ws, scale=L.scale, shift=L.shift,
+                                           act=api.ACT_SILU, fused=True)
+    else:
+        tl = L.ws.get("tiles", L.main.tiles_numel(n3), L.a_e.dtype)
+        ot = L.ws.get("out_main", L.main.out_numel(n3), L.a_e.dtype)
+        conv_call = lambda: api.sige_conv(tl, L.main.g, cfg["Cin"], cfg["Cout"], L.main.packed, L.main.bias,
+                                          L.bl3.count, ot, n_blocks=n3, max_blocks=n3)
+    conv_us = time_calls(conv_call, 300)
+    conv_fl = 2.0 * n3 * cfg["block"] ** 2 * 9 * cfg["Cin"] * cfg["Cout"]
+    roof = {"bound": "mfma", "kernel": "conv_kernel (sige_fused_conv)" if L.fused else "conv_kernel (sige_conv)",
+            "achieved": round(conv_fl / conv_us / 1e6, 2), "peak": MFMA_PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
+            "frac": round(conv_fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 5), "traffic": None,
+            "flop_per_launch": conv_fl, "avg_launch_us": round(conv_us, 2),
+            "note": f"{n3} active 16x16 blocks, 3x3, 128->128, fp16: {conv_fl / 1e9:.2f} GFLOP per launch - far too "
+                    "little work to fill 256 CUs; the supplement has the same kernel with every block active"}
+
+    # roofline 2: the HBM-bound kernel, the difference-mask stream (both activations read once).
+    # Rotated over distinct buffer pairs (> 256 MB in total) so that the Infinity Cache cannot serve them.
     pairs = [(L.a_o.clone(), L.a_e.clone()) for _ in range(10)]
     it = [0]
 
     def diff_cold():
         a, e = pairs[it[0] % len(pairs)]
         it[0] += 1
-        L.bl3.reduce(a_orig=a, a_edit=e, tau=cfg["tau"], mask_out=L.mask)
-    both_us = time_calls(diff_cold, 200)
-    list_us = time_calls(lambda: L.bl3.reduce(mask_in=L.mask), 200)
-    diff_us = max(both_us - list_us, 1e-3)
-    L.bl3.n_host = n3
-    roof = {"bound": "hbm", "kernel": "diff_mask_pow2 (sige_reduce_mask, activation mode)",
-            "achieved": round(diff_bytes / diff_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(diff_bytes / diff_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
-            "bytes_per_launch": diff_bytes, "avg_launch_us": round(diff_us, 2),
-            "note": "duration = (reduce_mask with activations) - (reduce_mask from a ready mask), events on the "
-                    "launch stream, inputs rotated over 10 buffer pairs (335 MB)"}
+        api.sige_reduce_mask(L.main.g, None, None, a_orig=a, a_edit=e, tau=cfg["tau"], mask_out=L.mask)
+    diff_us = time_calls(diff_cold, 300)
+    diff_warm_us = time_calls(lambda: api.sige_reduce_mask(L.main.g, None, None, a_orig=L.a_o, a_edit=L.a_e,
+                                                           tau=cfg["tau"], mask_out=L.mask), 300)
+    roof_hbm = {"bound": "hbm", "kernel": "diff_mask_pow2 (sige_reduce_mask, mask only)",
+                "achieved": round(diff_bytes / diff_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(diff_bytes / diff_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": diff_bytes, "avg_launch_us": round(diff_us, 2),
+                "same_buffers_every_launch_us": round(diff_warm_us, 2),
+                "note": "inputs rotated over 10 buffer pairs (335 MB); back-to-back launches, events on the stream"}
     del pairs
 
     res = {"metric": "sparse-conv gather/scatter GB/s", "value": round(n_bytes / (ms_per_step * 1e-3) / 1e9, 2),
@@ -357,17 +425,15 @@ def main():
            "config": {"workload": "BASELINE config 2: GN(32, cached stats)+SiLU+3x3 conv 128->128 and 1x1 shortcut "
                                   "128->256, 256x256 fp16, ~1% blob edit, 16x16 blocks; step = diff mask + block "
                                   "lists + gather/conv/scatter for both convs",
-                      "launch": f"one HIP graph per step, device-side block counts, capacity {L.capacity} blocks",
+                      "launch": f"one HIP graph per step, device-side block counts, capacity {L.capacity} blocks, "
+                                + ("fused gather-conv-scatter kernel" if L.fused else "gather, conv, scatter kernels"),
                       "eager_step_ms_with_count_readback": round(eager_us / 1e3, 4),
                       "active_blocks_3x3": n3, "active_blocks_1x1": n1, "grid_blocks": L.main.g.grid_blocks,
                       "algorithmic_bytes_per_step": n_bytes, "mfma_flop_per_step": L.flops_per_step(n3, n1)},
-           "roofline": roof}
+           "roofline": roof, "roofline_hbm": roof_hbm}
     if not args.no_supplement:
-        res["supplement"] = supplement(L, "f16")
-    if not args.no_cpu:
-        res["cpu_baseline"] = cpu_baseline(cfg, n_bytes)
-    else:
-        res["cpu_baseline"] = None
+        res["supplement"] = supplement(L, not args.no_unet)
+    res["cpu_baseline"] = None if args.no_cpu else cpu_baseline(cfg, n_bytes)
     print(json.dumps(res))
 
 

@@ -71,6 +71,8 @@ typedef struct {
  * ceil-mode pools) and must then have size g->H_in x g->W_in; it is dilated by
  * `dilate` pixels (square window, clipped).  A block is active iff its input tile,
  * clipped to the image, contains a marked pixel of that mask.
+ * With activations as the source, indices and count may both be NULL: only mask_out is
+ * produced.
  * Outputs: indices [max_blocks][2] (rows beyond the count are left untouched; never
  * more than max_blocks rows are written) and *count = the true number of active
  * blocks, even when it exceeds max_blocks.  The block grid may hold at most

@@ -118,7 +118,7 @@ def sige_reduce_mask(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0
     else:
         Hm, Wm = mask_in.shape
         C, dt = 0, SIGE_F32
-    mb = indices.shape[0] if max_blocks is None else max_blocks
+    mb = (indices.shape[0] if indices is not None else 0) if max_blocks is None else max_blocks
     _check(lib().sige_reduce_mask(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2,
                                   dilate, ctypes.byref(g), _ptr(mask_out), _ptr(indices), mb, _ptr(count),
                                   _ptr(workspace), 0 if workspace is None else workspace.numel() *

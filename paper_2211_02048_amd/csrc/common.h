@@ -99,9 +99,13 @@ __device__ __forceinline__ uint4 load_stream(const uint4* p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// SiLU as v * rcp(1 + exp2(-v * log2 e)): two hardware transcendentals (about 1 ulp each) and no
+// full-precision division, so that the fused gather stays bandwidth bound.  exp2 overflows to
+// +inf for very negative v, whose reciprocal is 0: the result is -0, as it should be.
 __device__ __forceinline__ float apply_act(float v, int act)
 {
-    if (act == SIGE_ACT_SILU) return v / (1.0f + __expf(-v));
+    if (act == SIGE_ACT_SILU)
+        return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f));
     if (act == SIGE_ACT_RELU) return v > 0.0f ? v : 0.0f;
     return v;
 }

@@ -48,9 +48,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
             sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
         }
     }
-    for (int j = threadIdx.x; j < total; j += 256) {
-        const int r = j / row_vecs, jr = j - r * row_vecs;
-        const int px = jr / a.V, cg = jr - px * a.V;
+    auto move = [&](int r, int px, int cg) {
         const int iy = iy0 + r0 + r, ix = ix0 + px;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) {
@@ -70,7 +68,28 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
                 v = pack<T>(f);
             }
         }
-        dst[j] = v;
+        dst[(r * a.tw + px) * a.V + cg] = v;
+    };
+    if (FIXED_CG) {
+        // a thread keeps its channel group and walks over the pixels of the row group without
+        // dividing: 256 / V pixels further each time
+        const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
+        const int step_r = ppi / a.tw, step_x = ppi - step_r * a.tw;
+        int p = threadIdx.x / a.V;
+        int r = p / a.tw, px = p - r * a.tw;
+        const int nrows = r1 - r0;
+        while (r < nrows) {
+            move(r, px, cg);
+            px += step_x;
+            r += step_r;
+            if (px >= a.tw) { px -= a.tw; ++r; }
+        }
+    } else {
+        for (int j = threadIdx.x; j < total; j += 256) {
+            const int r = j / row_vecs, jr = j - r * row_vecs;
+            const int px = jr / a.V;
+            move(r, px, jr - px * a.V);
+        }
     }
 }
 
@@ -104,9 +123,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(ScatterArgs a)
     const uint4* __restrict__ rt = (const uint4*)a.res_tiles;
     const uint4* __restrict__ rf = (const uint4*)a.res_full;
     uint4* __restrict__ dst = (uint4*)a.y;
-    for (int j = threadIdx.x; j < total; j += 256) {
-        const int r = j / row_vecs, jr = j - r * row_vecs;
-        const int px = jr / a.V, cg = jr - px * a.V;
+    auto move = [&](int r, int px, int cg) {
         const long t = (((long)n * a.bh + r0 + r) * a.bw + px) * a.V + cg;
         const long pix = (long)(y0 + r0 + r) * a.Wout + x0 + px;
         uint4 v = src[t];
@@ -126,6 +143,26 @@ __global__ __launch_bounds__(256) void scatter_kernel(ScatterArgs a)
             v = pack<T>(f);
         }
         dst[pix * a.y_ld_vec + cg] = v;
+    };
+    if (256 % a.V == 0) {
+        // division-free walk: a thread keeps its channel group, 256 / V pixels further each time
+        const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
+        const int step_r = ppi / cols, step_x = ppi - step_r * cols;
+        int p = threadIdx.x / a.V;
+        int r = p / cols, px = p - r * cols;
+        const int nrows = r1 - r0;
+        while (r < nrows) {
+            move(r, px, cg);
+            px += step_x;
+            r += step_r;
+            if (px >= cols) { px -= cols; ++r; }
+        }
+    } else {
+        for (int j = threadIdx.x; j < total; j += 256) {
+            const int r = j / row_vecs, jr = j - r * row_vecs;
+            const int px = jr / a.V;
+            move(r, px, jr - px * a.V);
+        }
     }
 }
 

@@ -38,9 +38,9 @@ struct MarkArgs {
 // Sets the flag of every block whose input tile, grown by the dilation radius, contains the
 // pooled position of the marked source pixel `pix`.  In input coordinates block b covers
 // [b*s - pad - r, b*s - pad + tile + r); clipping to the image never excludes an in-image pixel.
-__device__ __forceinline__ void mark_blocks(const MarkArgs& m, long pix)
+__device__ __forceinline__ void mark_blocks(const MarkArgs& m, int py, int px)
 {
-    const int y = (int)(pix / m.Wm) >> m.pool_log2, x = (int)(pix % m.Wm) >> m.pool_log2;
+    const int y = py >> m.pool_log2, x = px >> m.pool_log2;
     const int ylo = y - m.dilate - m.th + m.pad, xlo = x - m.dilate - m.tw + m.pad;
     // first block with b*s > lo  (floor division that is correct for negative lo)
     int by0 = (ylo >= 0 ? ylo / m.sy : -((-ylo + m.sy - 1) / m.sy)) + 1;
@@ -49,8 +49,14 @@ __device__ __forceinline__ void mark_blocks(const MarkArgs& m, long pix)
     const int bx1 = min((x + m.dilate + m.pad) / m.sx, m.nbx - 1);
     by0 = max(by0, 0);
     bx0 = max(bx0, 0);
+    // Many pixels hit the same few flags: look before storing, so that a flag's cache line is
+    // written a handful of times instead of once per marked pixel (the race is benign: every
+    // writer stores 1).
     for (int by = by0; by <= by1; ++by)
-        for (int bx = bx0; bx <= bx1; ++bx) m.flags[by * m.nbx + bx] = 1;
+        for (int bx = bx0; bx <= bx1; ++bx) {
+            volatile uint8_t* f = m.flags + by * m.nbx + bx;
+            if (*f == 0) *f = 1;
+        }
 }
 
 // V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
@@ -86,7 +92,10 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
             if (lane < ppw && pix < n_pix) {
                 const bool marked = ((b >> (lane << log2v)) & gmask) != 0ull;
                 mask[pix] = marked ? 1 : 0;
-                if (marked && mk.flags) mark_blocks(mk, pix);
+                if (marked && mk.flags) {
+                    const int py = (int)pix / mk.Wm;          // the host checked that pixels fit 31 bits
+                    mark_blocks(mk, py, (int)pix - py * mk.Wm);
+                }
             }
         }
     }
@@ -204,27 +213,24 @@ __device__ __forceinline__ void compact_flags(const ListArgs& a, const uint8_t* 
     if (tid == 0) *a.count = base;
 }
 
-// Ready mask -> block flags: every lane reads 16 mask bytes and marks for the non-zero ones.
-__global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __restrict__ mask, long n_pix,
-                                                             int vec_ok, MarkArgs mk)
+// Ready mask -> block flags: every lane reads 4 mask bytes of one row and marks for the non-zero
+// ones (32-bit index arithmetic only; the few marked pixels are spread over many lanes).
+__global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __restrict__ mask, int Hm,
+                                                             int words_per_row, int aligned, MarkArgs mk)
 {
-    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long p0 = t * 16;
-    if (p0 >= n_pix) return;
-    if (vec_ok && p0 + 16 <= n_pix) {
-        const uint4 v = *reinterpret_cast<const uint4*>(mask + p0);
-        if ((v.x | v.y | v.z | v.w) == 0u) return;
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= Hm * words_per_row) return;
+    const int y = t / words_per_row, x0 = (t - y * words_per_row) * 4;
+    const uint8_t* row = mask + (long)y * mk.Wm;
+    if (aligned && x0 + 4 <= mk.Wm) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(row + x0);
+        if (w == 0u) return;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (w[i] == 0u) continue;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((w[i] >> (8 * j)) & 0xffu) mark_blocks(mk, p0 + 4 * i + j);
-        }
+        for (int j = 0; j < 4; ++j)
+            if ((w >> (8 * j)) & 0xffu) mark_blocks(mk, y, x0 + j);
     } else {
-        for (long p = p0; p < min(p0 + 16, n_pix); ++p)
-            if (mask[p]) mark_blocks(mk, p);
+        for (int x = x0; x < min(x0 + 4, mk.Wm); ++x)
+            if (row[x]) mark_blocks(mk, y, x);
     }
 }
 
@@ -312,14 +318,16 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     SIGE_REQUIRE(diff_mode != (mask_in != nullptr), SIGE_ERR_INVALID_ARG,
                  "%s: give either (a_orig, a_edit) or mask_in, not both and not neither", who);
     SIGE_REQUIRE(Hm > 0 && Wm > 0, SIGE_ERR_INVALID_ARG, "%s: mask size must be positive", who);
+    SIGE_REQUIRE((long)Hm * Wm < (1L << 31), SIGE_ERR_UNSUPPORTED, "%s: mask larger than 2^31 pixels", who);
     SIGE_REQUIRE(pool_log2 >= 0 && pool_log2 <= 12 && dilate >= 0, SIGE_ERR_INVALID_ARG,
                  "%s: pool_log2 must be in [0, 12] and dilate >= 0", who);
     const int ps = 1 << pool_log2;
     SIGE_REQUIRE((Hm + ps - 1) / ps == g->H_in && (Wm + ps - 1) / ps == g->W_in, SIGE_ERR_INVALID_ARG,
                  "%s: pooled mask %dx%d does not match the conv input %dx%d", who, (Hm + ps - 1) / ps,
                  (Wm + ps - 1) / ps, g->H_in, g->W_in);
-    SIGE_REQUIRE(indices != nullptr && count != nullptr, SIGE_ERR_INVALID_ARG,
-                 "%s: indices and count are required", who);
+    const bool mask_only = diff_mode && indices == nullptr && count == nullptr;
+    SIGE_REQUIRE(mask_only || (indices != nullptr && count != nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: indices and count are required (both NULL only to get just the difference mask)", who);
     SIGE_REQUIRE(max_blocks >= 0, SIGE_ERR_INVALID_ARG, "%s: max_blocks is negative", who);
     const long nby = (g->H_out + g->block_h - 1) / g->block_h, nbx = (g->W_out + g->block_w - 1) / g->block_w;
     SIGE_REQUIRE(nby * nbx <= 131072, SIGE_ERR_CAPACITY,
@@ -333,6 +341,7 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     mk.Wm = Wm; mk.pool_log2 = pool_log2; mk.dilate = dilate;
     mk.sy = g->block_h * g->stride; mk.sx = g->block_w * g->stride;
     mk.th = th; mk.tw = tw; mk.pad = g->pad; mk.nby = (int)nby; mk.nbx = (int)nbx;
+    if (mask_only) mk.flags = nullptr;
     bool marked = false;
     if (diff_mode) {
         SIGE_REQUIRE(a_orig && a_edit, SIGE_ERR_INVALID_ARG, "%s: a_orig and a_edit are both required", who);
@@ -345,6 +354,7 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
                                   : launch_diff<bf16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, mk, &marked, st);
         if (rc) return rc;
         mask = mask_out;
+        if (mask_only) return SIGE_OK;
     }
     ListArgs a;
     a.mask = mask;
@@ -357,11 +367,11 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     const size_t lds = ((size_t)(nby * nbx) + 15) & ~(size_t)15;
     if (use_ws) {
         if (!marked) {
-            const long n_pix = (long)Hm * Wm;
-            const long threads = (n_pix + 15) / 16;
-            const int vec_ok = (reinterpret_cast<uintptr_t>(mask) & 15u) == 0;
+            const int wpr = (Wm + 3) / 4;
+            const long threads = (long)Hm * wpr;
+            const int aligned = (reinterpret_cast<uintptr_t>(mask) & 3u) == 0 && Wm % 4 == 0;
             hipLaunchKernelGGL(mark_from_mask_kernel, dim3((int)((threads + 255) / 256)), dim3(256), 0, st, mask,
-                               n_pix, vec_ok, mk);
+                               Hm, wpr, aligned, mk);
             SIGE_LAUNCH_CHECK("sige_reduce_mask(mark)");
         }
         hipLaunchKernelGGL(compact_ws_kernel, dim3(1), dim3(1024), 0, st, a, mk.flags);
