@@ -23,6 +23,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs of `bench.py --probe`: FETCH_SIZE
+# scaled by 2.0, WRITE_SIZE by 1.0, the factors a plain 128 MiB copy gives; see profiles/hbm_traffic_pmc.md)
+PMC_TRAFFIC_DIFF_MASK_CONFIG2 = 16437 * 2 * 1024 + int(64.5 * 1024)
+PMC_TRAFFIC_FUSED_CONV_CONFIG2 = 2306 * 2 * 1024 + 576 * 1024
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
 
@@ -35,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-supplement", action="store_true", help="only the headline step and rooflines")
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet step in the supplement")
+    ap.add_argument("--probe", action="store_true",
+                    help="launch each kernel of interest a few times and exit (for rocprofv3 --pmc runs)")
     ap.add_argument("--three-calls", action="store_true",
                     help="gather, conv, scatter as three kernels per convolution instead of the fused one")
     return ap.parse_args()
@@ -60,6 +66,26 @@ def time_calls(fn, iters, warm=20):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) * 1e3 / iters
+
+
+def time_graphed(fn, per_graph=20, replays=15):
+    """Average duration of one fn() in microseconds with the host launch path taken out: per_graph
+    calls are captured in a HIP graph (launched back to back by the GPU's command processor) and the
+    replays are timed with events on the stream."""
+    import torch
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for _ in range(3):
+            fn()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(per_graph):
+            fn()
+    torch.cuda.synchronize()
+    return time_calls(g.replay, replays, 3) / per_graph
 
 
 class Layer2:
@@ -351,8 +377,55 @@ def supplement(L, with_unet):
     return out
 
 
+def probe():
+    """A short, fixed sequence of launches for counter collection: a plain device copy of known size
+    (the yardstick FETCH_SIZE / WRITE_SIZE are scaled by), then the kernels the rooflines quote."""
+    import torch
+    from paper_2211_02048_amd import api, inputs
+    from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
+    cfg = inputs.config2()
+    L = Layer2(cfg, fused=True)
+    n3, n1 = L.capture()
+    src = torch.randn(64 * 1024 * 1024, dtype=torch.float16, device="cuda")   # 128 MiB
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)                                   # yardstick 1 (runtime's copy kernel): 128 MiB each way
+    for _ in range(3):
+        torch.neg(src, out=dst)                          # yardstick 2 (16-byte vector loads): 128 MiB each way
+    for _ in range(3):
+        api.sige_reduce_mask(L.main.g, None, None, a_orig=L.a_o, a_edit=L.a_e, tau=cfg["tau"], mask_out=L.mask)
+    L.bl3.sync_count(), L.bl1.sync_count()
+    for _ in range(3):
+        L.main.forward(L.a_e, L.y_main, L.bl3, L.ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=True)
+    for _ in range(3):
+        L.main.forward(L.a_e, L.y_main, L.bl3, L.ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=False)
+    H2, C = 1024, cfg["Cin"]
+    x = torch.randn((H2, H2, C), dtype=torch.float16, device="cuda")
+    x2 = x.clone()
+    big = SigeConv(cfg["w"].cuda(), cfg["bias"], H2, H2, 16, 1, 1)
+    bl = BlockList(big.g, "cuda").all_active()
+    nb = bl.n_host
+    t2 = torch.empty(big.tiles_numel(nb), dtype=torch.float16, device="cuda")
+    o2 = torch.empty(big.out_numel(nb), dtype=torch.float16, device="cuda")
+    y2 = torch.empty((H2, H2, C), dtype=torch.float16, device="cuda")
+    mask_o = torch.zeros((H2, H2), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        api.sige_reduce_mask(big.g, None, None, a_orig=x, a_edit=x2, tau=0.0, mask_out=mask_o)
+        api.sige_gather(x, big.g, bl.indices, bl.count, t2, n_blocks=nb, max_blocks=nb)
+        api.sige_gather(x, big.g, bl.indices, bl.count, t2, n_blocks=nb, scale=L.scale, shift=L.shift,
+                        act=api.ACT_SILU, max_blocks=nb)
+        api.sige_conv(t2, big.g, C, C, big.packed, big.bias, bl.count, o2, n_blocks=nb, max_blocks=nb)
+        api.sige_scatter(o2, big.g, bl.indices, bl.count, y2, n_blocks=nb, Cout=C, max_blocks=nb)
+    torch.cuda.synchronize()
+    print(json.dumps({"probe": "done", "copy_bytes_each_way": src.numel() * 2, "active_blocks_config2": n3,
+                      "blocks_1024": nb}))
+
+
 def main():
     args = parse()
+    if args.probe:
+        probe()
+        return
     if args.gpus != 1:
         print(f"bench.py: this build measures one MI355X; --gpus {args.gpus} is not supported "
               "(one GPU per box, no collectives in this path)", file=sys.stderr)
@@ -389,12 +462,14 @@ def main():
         ot = L.ws.get("out_main", L.main.out_numel(n3), L.a_e.dtype)
         conv_call = lambda: api.sige_conv(tl, L.main.g, cfg["Cin"], cfg["Cout"], L.main.packed, L.main.bias,
                                           L.bl3.count, ot, n_blocks=n3, max_blocks=n3)
-    conv_us = time_calls(conv_call, 300)
+    conv_us = time_graphed(conv_call)
     conv_fl = 2.0 * n3 * cfg["block"] ** 2 * 9 * cfg["Cin"] * cfg["Cout"]
     roof = {"bound": "mfma", "kernel": "conv_kernel (sige_fused_conv)" if L.fused else "conv_kernel (sige_conv)",
             "achieved": round(conv_fl / conv_us / 1e6, 2), "peak": MFMA_PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
-            "frac": round(conv_fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 5), "traffic": None,
+            "frac": round(conv_fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 5),
+            "traffic": PMC_TRAFFIC_FUSED_CONV_CONFIG2 if L.fused else None,
             "flop_per_launch": conv_fl, "avg_launch_us": round(conv_us, 2),
+            "timing": "20 launches per HIP graph, replays timed with events on the stream",
             "note": f"{n3} active 16x16 blocks, 3x3, 128->128, fp16: {conv_fl / 1e9:.2f} GFLOP per launch - far too "
                     "little work to fill 256 CUs; the supplement has the same kernel with every block active"}
 
@@ -407,15 +482,17 @@ def main():
         a, e = pairs[it[0] % len(pairs)]
         it[0] += 1
         api.sige_reduce_mask(L.main.g, None, None, a_orig=a, a_edit=e, tau=cfg["tau"], mask_out=L.mask)
-    diff_us = time_calls(diff_cold, 300)
-    diff_warm_us = time_calls(lambda: api.sige_reduce_mask(L.main.g, None, None, a_orig=L.a_o, a_edit=L.a_e,
-                                                           tau=cfg["tau"], mask_out=L.mask), 300)
+    diff_us = time_graphed(diff_cold, per_graph=20)   # 20 launches per graph = two passes over the 10 pairs
+    diff_warm_us = time_graphed(lambda: api.sige_reduce_mask(L.main.g, None, None, a_orig=L.a_o, a_edit=L.a_e,
+                                                             tau=cfg["tau"], mask_out=L.mask))
     roof_hbm = {"bound": "hbm", "kernel": "diff_mask_pow2 (sige_reduce_mask, mask only)",
                 "achieved": round(diff_bytes / diff_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(diff_bytes / diff_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(diff_bytes / diff_us / 1e3 / HBM_PEAK_GBS, 4),
+                "traffic": PMC_TRAFFIC_DIFF_MASK_CONFIG2,
                 "bytes_per_launch": diff_bytes, "avg_launch_us": round(diff_us, 2),
                 "same_buffers_every_launch_us": round(diff_warm_us, 2),
-                "note": "inputs rotated over 10 buffer pairs (335 MB); back-to-back launches, events on the stream"}
+                "note": "inputs rotated over 10 buffer pairs (335 MB); 20 launches per HIP graph, replays timed with "
+                        "events on the stream"}
     del pairs
 
     res = {"metric": "sparse-conv gather/scatter GB/s", "value": round(n_bytes / (ms_per_step * 1e-3) / 1e9, 2),
