@@ -110,6 +110,11 @@ __device__ __forceinline__ float apply_act(float v, int act)
     return v;
 }
 
+__device__ __forceinline__ bool aligned16_dev(const void* p)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
 // Number of blocks a kernel may touch: the host value when given, else the device count.
 __device__ __forceinline__ int effective_blocks(const int32_t* count, int max_blocks, int n_host)
 {

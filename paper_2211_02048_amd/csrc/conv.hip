@@ -144,15 +144,18 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     const int kk = a.k * a.k, kcs = a.Cin / KS;
     const int ntn_total = (a.Cout + 31) / 32;
 
+    // The bias is fetched now and added when the accumulators leave the registers, so that its
+    // load latency hides behind the whole K loop instead of delaying the first MFMA.
     f32x16 acc[TM][TN];
+    float bias_v[TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int o = (nt0 + tn) * 32 + l32;
-        const float b = (a.bias && o < a.Cout && wk == 0) ? a.bias[o] : 0.0f;
+        bias_v[tn] = (a.bias && o < a.Cout && wk == 0) ? a.bias[o] : 0.0f;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = b;
+            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.0f;
     }
 
     // weight fragment pointers of this wave's Cout tiles (at tap 0, this wave's first K step)
@@ -270,62 +273,91 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
         }
     }
 
+    // ---- epilogue.  The accumulators go through LDS (the staged tile is no longer needed) so that
+    // every thread then owns 8 consecutive output channels of one pixel: residual reads and output
+    // writes are 16-byte vectors and a pixel's channels leave in one coalesced run.
+    constexpr int N = Vec16<T>::N;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr int RS = BN + 4;                                // fp32 row stride: pad keeps 16-byte alignment
+    float* red = reinterpret_cast<float*>(lds);               // [WK][BM][RS]
+    __syncthreads();
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                const int nn = (wn * TN + tn) * 32 + l32;
+                red[(wk * BM + m) * RS + nn] = acc[tm][tn][r] + bias_v[tn];
+            }
+    __syncthreads();
+    // One run of V consecutive channels starting at o of row m of this workgroup's patch; vals are
+    // fp32 sums (bias included).  Plain mode stores the tile elements; fused mode rounds them to
+    // the storage type as a stored tile would be, adds the residuals in fp32 and scatters into y.
+    const bool vec_ok = (a.Cout % N == 0) && aligned16_dev(a.out) &&
+                        (!fused || a.y == nullptr ||
+                         (a.y_ld % N == 0 && aligned16_dev(a.y) && (!a.res_tiles || aligned16_dev(a.res_tiles)) &&
+                          (!a.res_full || (a.res_ld % N == 0 && aligned16_dev(a.res_full)))));
     T* __restrict__ out = (T*)a.out;
-    // One output element: row m of this workgroup's patch, output channel o, fp32 value v (bias
-    // included).  Plain mode stores the tile element; fused mode rounds it to the storage type as
-    // a stored tile would be, adds the residuals in fp32 and scatters it into y (clipped).
-    auto emit = [&](int m, int o, float v) {
+    for (int e = tid; e < BM * (BN / N); e += 256) {
+        const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
+        const int o = blockIdx.x * BN + nn;
         const int g = m / pb, p = m - g * pb;
         const int py = p / a.bw, px = p - py * a.bw;
-        if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) return;
+        if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
+        float v[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            v[i] = 0.0f;
+#pragma unroll
+            for (int w = 0; w < WK; ++w) v[i] += red[(w * BM + m) * RS + nn + i];
+        }
         const long t = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o;
-        if (!fused || a.y == nullptr) { out[t] = from_f32<T>(v); return; }
-        const int oy = a.indices[2 * (g0 + g)] + band_row0 + py, ox = a.indices[2 * (g0 + g) + 1] + px;
-        if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) return;
-        const long pix = (long)oy * a.Wout + ox;
-        T r = from_f32<T>(v);
-        if (a.res_tiles || a.res_full) {
-            float f = to_f32(r);
-            if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t]);
-            if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o]);
-            r = from_f32<T>(f);
+        const bool to_y = fused && a.y != nullptr;
+        long pix = 0;
+        if (to_y) {
+            const int oy = a.indices[2 * (g0 + g)] + band_row0 + py, ox = a.indices[2 * (g0 + g) + 1] + px;
+            if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) continue;
+            pix = (long)oy * a.Wout + ox;
         }
-        ((T*)a.y)[pix * a.y_ld + o] = r;
-    };
-    if (WK > 1) {
-        // sum the K-split partials through LDS, then store with consecutive lanes on consecutive
-        // output channels
-        constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-        float* red = reinterpret_cast<float*>(lds);           // [WK][BM][BN + 1]
-        __syncthreads();
+        if (vec_ok && o + N <= a.Cout) {
+            uint4 r = pack<T>(v);
+            if (to_y) {
+                if (a.res_tiles || a.res_full) {
+                    float f[N], q[N];
+                    unpack<T>(r, f);
+                    if (a.res_tiles) {
+                        unpack<T>(*(const uint4*)((const T*)a.res_tiles + t), q);
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+                        for (int i = 0; i < N; ++i) f[i] += q[i];
+                    }
+                    if (a.res_full) {
+                        unpack<T>(*(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const int nn = (wn * TN + tn) * 32 + l32;
-                    red[(wk * BM + m) * (BN + 1) + nn] = acc[tm][tn][r];
+                        for (int i = 0; i < N; ++i) f[i] += q[i];
+                    }
+                    r = pack<T>(f);
                 }
-        __syncthreads();
-        for (int e = tid; e < BM * BN; e += 256) {
-            const int m = e / BN, nn = e - m * BN;
-            float v = 0.0f;
-#pragma unroll
-            for (int w = 0; w < WK; ++w) v += red[(w * BM + m) * (BN + 1) + nn];
-            emit(m, blockIdx.x * BN + nn, v);
-        }
-        return;
-    }
-    // epilogue: lane holds column l32 of each tile, rows 8*(r/4) + 4*half + r%4
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) emit(m, (nt0 + tn) * 32 + l32, acc[tm][tn][r]);
+                *(uint4*)((T*)a.y + pix * a.y_ld + o) = r;
+            } else {
+                *(uint4*)(out + t) = r;
+            }
+        } else {
+            for (int i = 0; i < N && o + i < a.Cout; ++i) {
+                T r = from_f32<T>(v[i]);
+                if (to_y) {
+                    if (a.res_tiles || a.res_full) {
+                        float f = to_f32(r);
+                        if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t + i]);
+                        if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o + i]);
+                        r = from_f32<T>(f);
+                    }
+                    ((T*)a.y)[pix * a.y_ld + o + i] = r;
+                } else {
+                    out[t + i] = r;
+                }
+            }
         }
     }
 }
@@ -364,12 +396,14 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         const long npix = (long)p.G * p.trows * tw;
         // K steps per chunk: the largest of 8 / 4 / 1 that divides Cin and whose staged tile fits
         p.kc = 0;
+        const char* force_kc = getenv("SIGE_CONV_KC");   // tuning aid: fix the K steps per chunk
         for (int kc : {8, 4, 1}) {
+            if (force_kc && atoi(force_kc) != kc) continue;
             if (kc % WK || Cin % (kc * kstep)) continue;
             if (g->k != 1 && g->k != 3 && kc != 1) continue;
             size_t lds = (size_t)npix * (kc * kstep * s + 16);
-            if (WK > 1) lds = std::max(lds, (size_t)WK * M * (Nn + 1) * sizeof(float));
-            if (lds <= (kc == 1 || (kc == 4 && WK == 4) ? 160u : 64u) * 1024u) { p.kc = kc; p.lds = lds; break; }
+            lds = std::max(lds, (size_t)WK * M * (Nn + 4) * sizeof(float));   // the epilogue's staging
+            if (lds <= (kc == 1 || (kc == 4 && WK == 4) ? 160u : 80u) * 1024u) { p.kc = kc; p.lds = lds; break; }
         }
         if (p.kc == 0) continue;
         p.Cc = p.kc * kstep;
