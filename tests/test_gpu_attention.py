@@ -125,3 +125,67 @@ def test_gn_stats_and_fold(oracle, dtype, H, W, C, G, ld):
     np.testing.assert_allclose(f64(var), wv, rtol=2e-5)
     np.testing.assert_allclose(f64(scale), ws, rtol=2e-5)
     np.testing.assert_allclose(f64(shift), wsh, rtol=0, atol=5e-5)
+
+
+def test_sige_attention_layer_sparse_queries(oracle):
+    """Fig. "sige-attention" end to end through the library: gather the active 4x4 token blocks, run
+    the Q, K, V 1x1 convolutions on them, scatter ONLY K and V into the cached K/V, attend with the
+    gathered queries against all cached keys/values, run the Out convolution on the attended tiles
+    and scatter it into the cached output.  Compared with the oracle's dense statement of the layer."""
+    from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
+    rng = np.random.default_rng(77)
+    td, dtype = torch.bfloat16, "bf16"
+    H = W = 32
+    C, heads = 128, 4
+    d = C // heads
+    scale = 1.0 / math.sqrt(d)
+    mask = inputs.token_mask(9, H, W, 0.04)
+    x_o, x_e = inputs.edited_pair(rng, H, W, C, mask, 1.0, td)
+    ws_, bs_ = zip(*[inputs.conv_params(rng, C, C, 1, td) for _ in range(4)])
+    w64 = [f64(w) for w in ws_]
+    b64 = [f64(b) for b in bs_]
+    # caches from the original input, computed by the oracle and rounded to the storage type
+    xo64 = f64(x_o)
+    k_cache = torch.from_numpy(oracle.conv2d(xo64, w64[1], b64[1])).to(td)
+    v_cache = torch.from_numpy(oracle.conv2d(xo64, w64[2], b64[2])).to(td)
+    all_blocks = np.array([(y, x) for y in range(0, H, 4) for x in range(0, W, 4)], np.int32)
+    out_cache64 = oracle.sige_attention_layer(xo64, np.zeros((H, W, C)), all_blocks, 4, 4, *w64, *b64, heads, scale)
+    out_cache = torch.from_numpy(out_cache64).to(td)
+
+    convs = [SigeConv(dev(w), b, H, W, 4, 1, 0) for w, b in zip(ws_, bs_)]
+    wsp = Workspace("cuda")
+    bl = BlockList(convs[0].g, "cuda")
+    bl.reduce(mask_in=torch.from_numpy(mask).cuda())
+    n = bl.sync_count()
+    blocks = bl.indices[:n].cpu().numpy()
+    assert np.array_equal(blocks, oracle.active_blocks(mask, H, W, 4, 4, 1, 1, 0)) and 0 < n < 24
+    xe = dev(x_e)
+    kc, vc, oc = dev(k_cache).clone(), dev(v_cache).clone(), dev(out_cache).clone()
+    q_tiles = convs[0].forward(xe, None, bl, wsp, scatter=False, tag="q").clone()
+    convs[1].forward(xe, kc, bl, wsp, tag="k")          # K and V of the edited tokens overwrite the caches
+    convs[2].forward(xe, vc, bl, wsp, tag="v")
+    nq = n * 16
+    att = torch.zeros((nq, heads, d), dtype=td, device="cuda")
+    nb = api.sige_sparse_attn_workspace_bytes(nq, H * W, heads, d)
+    wsb = torch.empty(max(nb // 4, 1), dtype=torch.float32, device="cuda") if nb else None
+    api.sige_sparse_attn(q_tiles.view(nq, heads, d), kc.view(H * W, heads, d), vc.view(H * W, heads, d), att, scale,
+                         workspace=wsb)
+    # the Out convolution reads the attended tokens as tiles [n, 4, 4, C] and scatters into the cache
+    out_tiles = wsp.get("out_o", convs[3].out_numel(n), td)
+    api.sige_conv(att.view(n, 4, 4, C), convs[3].g, C, C, convs[3].packed, convs[3].bias, bl.count, out_tiles,
+                  n_blocks=n, max_blocks=n)
+    api.sige_scatter(out_tiles, convs[3].g, bl.indices, bl.count, oc, n_blocks=n, Cout=C, max_blocks=n)
+    torch.cuda.synchronize()
+
+    want = oracle.sige_attention_layer(f64(x_e), f64(out_cache), blocks, 4, 4, *w64, *b64, heads, scale,
+                                       f64(k_cache), f64(v_cache))
+    act = np.zeros((H, W), bool)
+    for y0, x0 in blocks:
+        act[y0:y0 + 4, x0:x0 + 4] = True
+    a_t = torch.from_numpy(act).cuda()
+    assert torch.equal(oc[~a_t], dev(out_cache)[~a_t])      # unedited tokens keep the cached output
+    # stored intermediates (q, k, v, attended values) are rounded to bf16 on the way: 2e-2 on the chain
+    assert_close(oc[a_t], want[act], td, "SIGE attention layer (active tokens)", tol=2e-2)
+    # K/V caches: edited tokens overwritten, the rest bit-identical
+    assert torch.equal(kc[~a_t], dev(k_cache)[~a_t]) and torch.equal(vc[~a_t], dev(v_cache)[~a_t])
+    assert_close(kc[a_t], oracle.conv2d(f64(x_e), w64[1], b64[1])[act], td, "K overwrite")

@@ -519,3 +519,34 @@ def test_layer_config2_full_size_sampled(oracle):
     assert_close(got, want, td, "config2 full size (sampled)")
     want = oracle.dense_layer(a_e, f64(cfg["w"]), f64(cfg["bias"]), 1, 1, scale, shift, oracle.ACT_SILU, pixels=px)
     assert_mostly_close(got, want, td, "config2 full size (sampled) vs unrounded oracle")
+
+
+def test_sequential_edits_incremental_cache(oracle):
+    """Sec. 4.2 "Sequential edits", incremental pre-computation: after each edit the sparse pass has
+    updated the cache in place, and the next edit is reduced against the previous edited input.  With
+    true difference masks the cache equals the dense layer on the current input after every edit."""
+    rng = np.random.default_rng(31)
+    td = torch.float16
+    H, W, C = 80, 64, 32
+    w, b = inputs.conv_params(rng, C, C, 3, td)
+    cur = torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(td)
+    conv = SigeConv(dev(w), b, H, W, 16, 1, 1)
+    ws = Workspace("cuda")
+    bl = BlockList(conv.g, "cuda")
+    y = torch.from_numpy(oracle.conv2d(f64(cur), f64(w), f64(b), 1, 1)).to(td).cuda()
+    mask_out = torch.zeros((H, W), dtype=torch.uint8, device="cuda")
+    touched = 0
+    for edit in range(5):
+        m = inputs.blob_mask(rng, H, W, 40 + 30 * edit, 2, (2.0, 5.0), tol=0.2)
+        nxt = torch.where(torch.from_numpy(m.astype(bool))[:, :, None],
+                          cur + torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(td), cur)
+        bl.reduce(a_orig=dev(cur), a_edit=dev(nxt), tau=0.0, mask_out=mask_out)
+        n = bl.sync_count()
+        want_m = oracle.diff_mask(cur.float().numpy(), nxt.float().numpy(), 0.0)
+        assert np.array_equal(mask_out.cpu().numpy(), want_m)
+        assert np.array_equal(bl.indices[:n].cpu().numpy(), oracle.active_blocks(want_m, H, W, 16, 16, 3, 1, 1))
+        conv.forward(dev(nxt), y, bl, ws, fused=(edit % 2 == 1))
+        touched += n
+        assert_close(y, oracle.conv2d(f64(nxt), f64(w), f64(b), 1, 1), td, f"cache after edit {edit}")
+        cur = nxt
+    assert 5 <= touched < 5 * conv.g.grid_blocks
