@@ -284,6 +284,50 @@ def supplement(L, with_unet):
         "conv3x3_us": round(conv_us, 1), "conv3x3_tflops": round(fl / conv_us / 1e6, 1),
         "conv3x3_frac_mfma_peak": round(fl / conv_us / 1e6 / MFMA_PEAK_TFLOPS["f16"], 4)}
 
+    # ---- latency against edited area (Sec. 4.2 "Large edits"): both convs of config 2 on blob masks
+    import numpy as np
+    rng = np.random.Generator(np.random.PCG64(2002))
+    sweep = []
+    for frac in (0.01, 0.05, 0.15, 0.30, 0.50, 0.75):
+        m = inputs.blob_mask(rng, c["H"], c["W"], int(frac * c["H"] * c["W"]), 3 + int(20 * frac),
+                             (5.0, 12.0), tol=0.1)
+        md = torch.from_numpy(m).cuda()
+        b3, b1 = BlockList(g3, "cuda"), BlockList(L.short.g, "cuda")
+        b3.reduce(mask_in=md)
+        b1.reduce(mask_in=md)
+        k3, k1 = b3.sync_count(), b1.sync_count()
+
+        def run():
+            L.main.forward(L.a_e, y3, b3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=L.fused)
+            L.short.forward(L.a_e, y1, b1, ws, fused=L.fused)
+        us = time_graphed(run, per_graph=10, replays=10)
+        sweep.append({"edited_area": frac, "active_blocks_3x3": k3, "active_blocks_1x1": k1,
+                      "both_convs_us": round(us, 1)})
+    dense_g = time_graphed(dense, per_graph=10, replays=10)
+    out["config2_latency_vs_edited_area"] = {"points": sweep, "all_blocks_active_us": round(dense_g, 1),
+                                             "note": "graph-batched launches; break-even against the all-active "
+                                                     "launch is where both_convs_us crosses all_blocks_active_us "
+                                                     "(the paper reports 65-75 % on RTX 3090, Sec. 4.2)"}
+
+    # ---- config 1 (3x3, 64->64, 64x64, fp32, 6x6 blocks, ~5 % rectangle): whole step
+    c1 = inputs.config1()
+    conv1 = SigeConv(c1["w"].cuda(), c1["bias"], 64, 64, 6, 1, 1)
+    bl1c = BlockList(conv1.g, "cuda")
+    ao1, ae1 = c1["a_orig"].cuda(), c1["a_edit"].cuda()
+    m1 = torch.zeros((64, 64), dtype=torch.uint8, device="cuda")
+    y1c = torch.zeros((64, 64, 64), dtype=torch.float32, device="cuda")
+    bl1c.reduce(a_orig=ao1, a_edit=ae1, tau=c1["tau"], mask_out=m1)
+    n1c = bl1c.sync_count()
+    bl1c.n_host = -1
+    bl1c.max_blocks = max(8, next_pow2(n1c))
+
+    def step1():
+        bl1c.reduce(a_orig=ao1, a_edit=ae1, tau=c1["tau"], mask_out=m1)
+        bl1c.n_host = -1
+        conv1.forward(ae1, y1c, bl1c, ws, fused=L.fused)
+    out["config1_fp32_step"] = {"active_blocks": n1c, "of_blocks": conv1.g.grid_blocks,
+                                "step_us": round(time_graphed(step1, per_graph=10, replays=10), 1)}
+
     # ---- bandwidth regime: 1024x1024x128 fp16 (256 MiB per tensor), all 4096 blocks active
     H2 = 1024
     C = c["Cin"]
