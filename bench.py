@@ -122,9 +122,11 @@ class Layer2:
         torch.cuda.synchronize()
 
     def reduce(self):
+        # one pass over both activations marks the blocks of both geometries (3x3 and 1x1 tiles)
+        from paper_2211_02048_amd.layers import BlockList
         c = self.cfg
-        self.bl3.reduce(a_orig=self.a_o, a_edit=self.a_e, tau=c["tau"], mask_out=self.mask, dilate=c["dilate"])
-        self.bl1.reduce(mask_in=self.mask, dilate=c["dilate"])
+        BlockList.reduce_together([self.bl3, self.bl1], a_orig=self.a_o, a_edit=self.a_e, tau=c["tau"],
+                                  mask_out=self.mask, dilate=c["dilate"])
 
     def layer(self):
         api = self.api
@@ -173,7 +175,7 @@ class Layer2:
         s, C, Cs, b = 2, c["Cin"], c["Cs"], c["block"]
         t = b + 2
         diff = 2 * c["H"] * c["W"] * C * s + c["H"] * c["W"]
-        lists = 2 * c["H"] * c["W"] + 8 * (n3 + n1) + 8
+        lists = 8 * (n3 + n1) + 8      # the mask is written by the difference pass and not read again
         if self.fused:   # tile read once, output block written once
             main = n3 * (t * t * C * s + b * b * C * s) + 9 * C * C * s
             short = n1 * (b * b * C * s + b * b * Cs * s) + C * Cs * s

@@ -90,6 +90,30 @@ int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt,
                      void* workspace, size_t workspace_bytes, void* stream);
 size_t sige_reduce_mask_workspace_bytes(const sige_geom* g);
 
+/* One list of sige_reduce_mask_lists: a layer geometry, where its list goes, and its own
+ * flag workspace (required here; zeroed once by the caller, left zero by every call). */
+typedef struct {
+    sige_geom g;
+    int32_t*  indices;          /* device [max_blocks][2]                          */
+    int32_t   max_blocks;
+    int32_t*  count;            /* device, one int32                               */
+    void*     workspace;        /* device, sige_reduce_mask_workspace_bytes(&g)    */
+    size_t    workspace_bytes;
+} sige_block_list;
+
+/* Sec. 3.2 "Tiling-based sparse convolution" for several layers at once: the layers of one
+ * resolution (a 3x3 convolution and its 1x1 shortcut, a stride-2 convolution) share the
+ * difference mask but have their own tiles, hence their own lists.  Same mask sources,
+ * pooling, dilation and results as n_lists calls of sige_reduce_mask with the same
+ * arguments; the activations are streamed once and every marked pixel sets the flags of
+ * all lists.  lists is a HOST array of 1..4 entries whose geometries all have the pooled
+ * mask's size as H_in x W_in; the workspaces must be distinct.                        */
+int sige_reduce_mask_lists(const void* a_orig, const void* a_edit, sige_dtype dt,
+                           int32_t Hm, int32_t Wm, int32_t C, float tau,
+                           const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
+                           const sige_block_list* lists, int32_t n_lists,
+                           uint8_t* mask_out, void* stream);
+
 /* Fig. "method" Gather, with Sec. 3.2 "Pre-computing normalization parameters" and
  * "Kernel fusion" folded in:
  *   tiles[n][i][j][c] = act(scale[c] * x[y][x][c] + shift[c]),

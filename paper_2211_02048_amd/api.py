@@ -22,7 +22,7 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_gather", "sige_conv", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_conv", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
            "sige_sparse_attn_workspace_bytes", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -51,6 +51,12 @@ class Geom(ctypes.Structure):
         return -(-self.H_out // self.block_h) * -(-self.W_out // self.block_w)
 
 
+class BlockListDesc(ctypes.Structure):
+    """Mirror of sige_block_list."""
+    _fields_ = [("g", Geom), ("indices", ctypes.c_void_p), ("max_blocks", ctypes.c_int32),
+                ("count", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
 def geom(H_in, W_in, block, k=3, stride=1, pad=None) -> Geom:
     pad = k // 2 if pad is None else pad
     bh, bw = (block, block) if isinstance(block, int) else block
@@ -76,6 +82,8 @@ def lib() -> ctypes.CDLL:
         gp = ctypes.POINTER(Geom)
         L.sige_reduce_mask.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp, sz,
                                        vp]
+        L.sige_reduce_mask_lists.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32,
+                                             ctypes.POINTER(BlockListDesc), i32, vp, vp]
         L.sige_reduce_mask_workspace_bytes.restype = ctypes.c_size_t
         L.sige_reduce_mask_workspace_bytes.argtypes = [gp]
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
@@ -123,6 +131,26 @@ def sige_reduce_mask(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0
                                   dilate, ctypes.byref(g), _ptr(mask_out), _ptr(indices), mb, _ptr(count),
                                   _ptr(workspace), 0 if workspace is None else workspace.numel() *
                                   workspace.element_size(), _stream()))
+
+
+def sige_reduce_mask_lists(lists, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None, mask_out=None,
+                           pool_log2=0, dilate=0):
+    """One mask, several layer geometries: lists = [(g, indices, count, max_blocks, workspace), ...]."""
+    if a_orig is not None:
+        Hm, Wm, C = a_orig.shape
+        dt = _DT[a_orig.dtype]
+    else:
+        Hm, Wm = mask_in.shape
+        C, dt = 0, SIGE_F32
+    arr = (BlockListDesc * max(len(lists), 1))()
+    for d, (g, indices, count, mb, ws) in zip(arr, lists):
+        d.g = g
+        d.indices, d.count = indices.data_ptr(), count.data_ptr()
+        d.max_blocks = indices.shape[0] if mb is None else mb
+        d.workspace = None if ws is None else ws.data_ptr()
+        d.workspace_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().sige_reduce_mask_lists(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2,
+                                        dilate, arr, len(lists), _ptr(mask_out), _stream()))
 
 
 def sige_gather(x, g: Geom, indices, count, tiles, *, n_blocks=-1, scale=None, shift=None, act=ACT_NONE,

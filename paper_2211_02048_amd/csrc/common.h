@@ -123,4 +123,18 @@ __device__ __forceinline__ int effective_blocks(const int32_t* count, int max_bl
     return c < max_blocks ? c : max_blocks;
 }
 
+// Number of blocks and the origin of block n, fetched together: the count and the index row are
+// independent loads, so they are issued back to back and awaited once instead of one after the
+// other (row n exists whenever n < max_blocks, whatever the count says).  The empty asm pins the
+// loads above the early exit that depends on the count.
+__device__ __forceinline__ int blocks_and_origin(const int32_t* count, int max_blocks, int n_host,
+                                                 const int32_t* indices, int n, int& y0, int& x0)
+{
+    y0 = indices[2 * n];
+    x0 = indices[2 * n + 1];
+    int n_eff = effective_blocks(count, max_blocks, n_host);
+    asm volatile("" : "+v"(y0), "+v"(x0), "+v"(n_eff));
+    return n_eff;
+}
+
 }  // namespace sige

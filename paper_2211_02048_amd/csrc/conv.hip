@@ -105,6 +105,8 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 // take different channel ranges of every tap and are summed through LDS at the end); KC = K steps
 // per staged channel chunk; KK = k*k when it is 9 or 1 (taps unrolled), 0 for any other kernel size.  Weight fragments are fetched into a register ring several taps ahead
 // of the MFMAs that use them (deepest for the K-split shape, whose layers are weight-bound).
+constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks in a 256-row patch)
+
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
 __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 {
@@ -116,9 +118,23 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
 
-    const int n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
+    // Fused mode: the origins of this workgroup's blocks go to LDS once.  Their loads and the
+    // load of the count are independent and are issued together (row n exists for n < max_blocks).
+    __shared__ int org[2 * MAX_G];
     const int g0 = blockIdx.z * a.G;
+    int oy = 0, ox = 0;
+    if (a.indices != nullptr && threadIdx.x < a.G) {
+        const int n = min(g0 + (int)threadIdx.x, a.max_blocks - 1);
+        oy = a.indices[2 * n];
+        ox = a.indices[2 * n + 1];
+    }
+    int n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
+    asm volatile("" : "+v"(oy), "+v"(ox), "+v"(n_eff));
     if (g0 >= n_eff) return;
+    if (a.indices != nullptr) {
+        if (threadIdx.x < a.G) { org[2 * threadIdx.x] = oy; org[2 * threadIdx.x + 1] = ox; }
+        __syncthreads();
+    }
     const int band = blockIdx.y;
     const int band_row0 = band * a.rows;                      // first output row of the band
     const int band_rows = min(a.rows, a.bh - band_row0);
@@ -211,8 +227,8 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
                     val = *(const uint4*)(tiles + ((((long)(g0 + g) * a.th + trow0 + r) * a.tw + x) * a.Cin + c0) * S + v * 16);
                 } else {
                     // the gather: input pixel of tile position (trow0 + r, x) of block g0 + g
-                    const int iy = a.indices[2 * (g0 + g)] * a.stride - a.pad + trow0 + r;
-                    const int ix = a.indices[2 * (g0 + g) + 1] * a.stride - a.pad + x;
+                    const int iy = org[2 * g] * a.stride - a.pad + trow0 + r;
+                    const int ix = org[2 * g + 1] * a.stride - a.pad + x;
                     if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) {
                         val = *(const uint4*)((const char*)a.x +
                                               (((long)(iy >> a.up) * (a.Win >> a.up) + (ix >> a.up)) * a.x_ld + c0) * S + v * 16);
@@ -317,7 +333,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
         const bool to_y = fused && a.y != nullptr;
         long pix = 0;
         if (to_y) {
-            const int oy = a.indices[2 * (g0 + g)] + band_row0 + py, ox = a.indices[2 * (g0 + g) + 1] + px;
+            const int oy = org[2 * g] + band_row0 + py, ox = org[2 * g + 1] + px;
             if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) continue;
             pix = (long)oy * a.Wout + ox;
         }

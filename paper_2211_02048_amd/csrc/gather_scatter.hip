@@ -29,8 +29,9 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
 {
     constexpr int N = Vec16<T>::N;
     const int n = blockIdx.y;
-    if (n >= effective_blocks(a.count, a.max_blocks, a.n_host)) return;
-    const int iy0 = a.indices[2 * n] * a.stride - a.pad, ix0 = a.indices[2 * n + 1] * a.stride - a.pad;
+    int by0, bx0;
+    if (n >= blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, by0, bx0)) return;
+    const int iy0 = by0 * a.stride - a.pad, ix0 = bx0 * a.stride - a.pad;
     const int r0 = blockIdx.x * a.rows_per_wg;
     const int r1 = min(r0 + a.rows_per_wg, a.th);
     const int row_vecs = a.tw * a.V;
@@ -110,8 +111,8 @@ __global__ __launch_bounds__(256) void scatter_kernel(ScatterArgs a)
 {
     constexpr int N = Vec16<T>::N;
     const int n = blockIdx.y;
-    if (n >= effective_blocks(a.count, a.max_blocks, a.n_host)) return;
-    const int y0 = a.indices[2 * n], x0 = a.indices[2 * n + 1];
+    int y0, x0;
+    if (n >= blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, y0, x0)) return;
     if (y0 < 0 || x0 < 0 || y0 >= a.Hout || x0 >= a.Wout) return;  // never store outside y
     const int r0 = blockIdx.x * a.rows_per_wg;
     const int r1 = min(min(r0 + a.rows_per_wg, a.bh), a.Hout - y0);  // clip rows at the bottom edge

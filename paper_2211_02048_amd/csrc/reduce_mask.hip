@@ -35,6 +35,13 @@ struct MarkArgs {
     int th, tw, pad, nby, nbx;
 };
 
+// The lists one call builds from the same pooled mask (one per layer geometry at that resolution).
+constexpr int MAX_LISTS = 4;
+struct MarkSet {
+    int n;           // 0 = do not mark
+    MarkArgs m[MAX_LISTS];
+};
+
 // Sets the flag of every block whose input tile, grown by the dilation radius, contains the
 // pooled position of the marked source pixel `pix`.  In input coordinates block b covers
 // [b*s - pad - r, b*s - pad + tile + r); clipping to the image never excludes an in-image pixel.
@@ -64,7 +71,7 @@ template <typename T, int U>
 __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ a_o,
                                                       const uint4* __restrict__ a_e, long n_vec,
                                                       int log2v, float tau, long n_pix,
-                                                      uint8_t* __restrict__ mask, MarkArgs mk)
+                                                      uint8_t* __restrict__ mask, MarkSet mk)
 {
     const int lane = threadIdx.x & 63;
     const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -92,9 +99,10 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
             if (lane < ppw && pix < n_pix) {
                 const bool marked = ((b >> (lane << log2v)) & gmask) != 0ull;
                 mask[pix] = marked ? 1 : 0;
-                if (marked && mk.flags) {
-                    const int py = (int)pix / mk.Wm;          // the host checked that pixels fit 31 bits
-                    mark_blocks(mk, py, (int)pix - py * mk.Wm);
+                if (marked && mk.n) {
+                    const int py = (int)pix / mk.m[0].Wm;     // the host checked that pixels fit 31 bits
+                    const int px = (int)pix - py * mk.m[0].Wm;
+                    for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], py, px);
                 }
             }
         }
@@ -216,28 +224,39 @@ __device__ __forceinline__ void compact_flags(const ListArgs& a, const uint8_t* 
 // Ready mask -> block flags: every lane reads 4 mask bytes of one row and marks for the non-zero
 // ones (32-bit index arithmetic only; the few marked pixels are spread over many lanes).
 __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __restrict__ mask, int Hm,
-                                                             int words_per_row, int aligned, MarkArgs mk)
+                                                             int words_per_row, int aligned, MarkSet mk)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= Hm * words_per_row) return;
+    const int Wm = mk.m[0].Wm;
     const int y = t / words_per_row, x0 = (t - y * words_per_row) * 4;
-    const uint8_t* row = mask + (long)y * mk.Wm;
-    if (aligned && x0 + 4 <= mk.Wm) {
+    const uint8_t* row = mask + (long)y * Wm;
+    if (aligned && x0 + 4 <= Wm) {
         const uint32_t w = *reinterpret_cast<const uint32_t*>(row + x0);
         if (w == 0u) return;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if ((w >> (8 * j)) & 0xffu) mark_blocks(mk, y, x0 + j);
+            if ((w >> (8 * j)) & 0xffu)
+                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], y, x0 + j);
     } else {
-        for (int x = x0; x < min(x0 + 4, mk.Wm); ++x)
-            if (row[x]) mark_blocks(mk, y, x);
+        for (int x = x0; x < min(x0 + 4, Wm); ++x)
+            if (row[x])
+                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], y, x);
     }
 }
 
-// Flags (global) -> ordered list; the flags are cleared again for the next call.
-__global__ __launch_bounds__(1024) void compact_ws_kernel(ListArgs a, uint8_t* flags)
+struct ListSet {
+    ListArgs a[MAX_LISTS];
+    uint8_t* flags[MAX_LISTS];
+};
+
+// Flags (global) -> ordered list, one workgroup per list; the flags are cleared again for the
+// next call.
+__global__ __launch_bounds__(1024) void compact_ws_kernel(ListSet s)
 {
     __shared__ int wave_tot[16];
+    const ListArgs& a = s.a[blockIdx.x];
+    uint8_t* flags = s.flags[blockIdx.x];
     const int nb = a.nby * a.nbx;
     compact_flags<1024>(a, flags, nb, wave_tot);
     for (int i = threadIdx.x; i < nb; i += 1024) flags[i] = 0;
@@ -260,7 +279,7 @@ __global__ __launch_bounds__(1024) void block_list_kernel(ListArgs a)
 
 template <typename T>
 static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, int C, float tau,
-                       uint8_t* mask, const MarkArgs& mk, bool* marked, hipStream_t st)
+                       uint8_t* mask, const MarkSet& mk, bool* marked, hipStream_t st)
 {
     *marked = false;
     const long n_pix = (long)Hm * Wm;
@@ -276,7 +295,7 @@ static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, i
             int grid = (int)(steps < 4096 ? steps : 4096);
             hipLaunchKernelGGL((diff_mask_pow2<T, U>), dim3(grid), dim3(256), 0, st,
                                (const uint4*)a_orig, (const uint4*)a_edit, n_vec, log2v, tau, n_pix, mask, mk);
-            *marked = mk.flags != nullptr;
+            *marked = mk.n != 0;
         } else {
             long blocks = (n_pix + 3) / 4;
             int grid = (int)(blocks < 8192 ? blocks : 8192);
@@ -304,16 +323,13 @@ extern "C" size_t sige_reduce_mask_workspace_bytes(const sige_geom* g)
     return (nb + 15) & ~(size_t)15;
 }
 
-extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
-                                int32_t Wm, int32_t C, float tau, const uint8_t* mask_in,
-                                int32_t pool_log2, int32_t dilate, const sige_geom* g,
-                                uint8_t* mask_out, int32_t* indices, int32_t max_blocks,
-                                int32_t* count, void* workspace, size_t workspace_bytes, void* stream)
+// Shared by both entry points: n lists (n >= 1; n == 0 only for the mask-only mode) built from one
+// mask.  With n == 1 a missing workspace falls back to the single-workgroup block test.
+static int reduce_lists(const char* who, const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
+                        int32_t Wm, int32_t C, float tau, const uint8_t* mask_in, int32_t pool_log2,
+                        int32_t dilate, const sige_block_list* lists, int n, const sige_geom* g_mask_only,
+                        uint8_t* mask_out, void* stream)
 {
-    clear_error();
-    const char* who = "sige_reduce_mask";
-    int th, tw;
-    if (int rc = check_geom(g, who, &th, &tw)) return rc;
     const bool diff_mode = a_orig != nullptr || a_edit != nullptr;
     SIGE_REQUIRE(diff_mode != (mask_in != nullptr), SIGE_ERR_INVALID_ARG,
                  "%s: give either (a_orig, a_edit) or mask_in, not both and not neither", who);
@@ -322,26 +338,56 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     SIGE_REQUIRE(pool_log2 >= 0 && pool_log2 <= 12 && dilate >= 0, SIGE_ERR_INVALID_ARG,
                  "%s: pool_log2 must be in [0, 12] and dilate >= 0", who);
     const int ps = 1 << pool_log2;
-    SIGE_REQUIRE((Hm + ps - 1) / ps == g->H_in && (Wm + ps - 1) / ps == g->W_in, SIGE_ERR_INVALID_ARG,
-                 "%s: pooled mask %dx%d does not match the conv input %dx%d", who, (Hm + ps - 1) / ps,
-                 (Wm + ps - 1) / ps, g->H_in, g->W_in);
-    const bool mask_only = diff_mode && indices == nullptr && count == nullptr;
-    SIGE_REQUIRE(mask_only || (indices != nullptr && count != nullptr), SIGE_ERR_INVALID_ARG,
-                 "%s: indices and count are required (both NULL only to get just the difference mask)", who);
-    SIGE_REQUIRE(max_blocks >= 0, SIGE_ERR_INVALID_ARG, "%s: max_blocks is negative", who);
-    const long nby = (g->H_out + g->block_h - 1) / g->block_h, nbx = (g->W_out + g->block_w - 1) / g->block_w;
-    SIGE_REQUIRE(nby * nbx <= 131072, SIGE_ERR_CAPACITY,
-                 "%s: block grid %ldx%ld exceeds 131072 blocks", who, nby, nbx);
+    const int Hp = (Hm + ps - 1) / ps, Wp = (Wm + ps - 1) / ps;
     hipStream_t st = (hipStream_t)stream;
+    MarkSet mk;
+    mk.n = 0;
+    ListSet ls;
+    bool all_ws = n > 0;
+    for (int i = 0; i < n; ++i) {
+        const sige_block_list& L = lists[i];
+        const sige_geom* g = &L.g;
+        int th, tw;
+        if (int rc = check_geom(g, who, &th, &tw)) return rc;
+        SIGE_REQUIRE(Hp == g->H_in && Wp == g->W_in, SIGE_ERR_INVALID_ARG,
+                     "%s: pooled mask %dx%d does not match the conv input %dx%d", who, Hp, Wp, g->H_in, g->W_in);
+        SIGE_REQUIRE(L.indices != nullptr && L.count != nullptr, SIGE_ERR_INVALID_ARG,
+                     "%s: indices and count are required (both NULL only to get just the difference mask)", who);
+        SIGE_REQUIRE(L.max_blocks >= 0, SIGE_ERR_INVALID_ARG, "%s: max_blocks is negative", who);
+        const long nby = (g->H_out + g->block_h - 1) / g->block_h, nbx = (g->W_out + g->block_w - 1) / g->block_w;
+        SIGE_REQUIRE(nby * nbx <= 131072, SIGE_ERR_CAPACITY, "%s: block grid %ldx%ld exceeds 131072 blocks", who,
+                     nby, nbx);
+        const bool ws = L.workspace != nullptr && L.workspace_bytes >= sige_reduce_mask_workspace_bytes(g) &&
+                        (reinterpret_cast<uintptr_t>(L.workspace) & 15u) == 0;
+        all_ws = all_ws && ws;
+        for (int j = 0; j < i; ++j)
+            SIGE_REQUIRE(!ws || lists[j].workspace != L.workspace, SIGE_ERR_INVALID_ARG,
+                         "%s: lists %d and %d share a workspace", who, j, i);
+        MarkArgs& m = mk.m[i];
+        m.flags = (uint8_t*)L.workspace;
+        m.Wm = Wm; m.pool_log2 = pool_log2; m.dilate = dilate;
+        m.sy = g->block_h * g->stride; m.sx = g->block_w * g->stride;
+        m.th = th; m.tw = tw; m.pad = g->pad; m.nby = (int)nby; m.nbx = (int)nbx;
+        ListArgs& a = ls.a[i];
+        a.Hm = Hm; a.Wm = Wm; a.pool_log2 = pool_log2; a.dilate = dilate;
+        a.Hin = g->H_in; a.Win = g->W_in; a.bh = g->block_h; a.bw = g->block_w;
+        a.stride = g->stride; a.pad = g->pad; a.th = th; a.tw = tw;
+        a.nby = (int)nby; a.nbx = (int)nbx;
+        a.indices = L.indices; a.max_blocks = L.max_blocks; a.count = L.count;
+        ls.flags[i] = (uint8_t*)L.workspace;
+    }
+    SIGE_REQUIRE(n <= 1 || all_ws, SIGE_ERR_INVALID_ARG,
+                 "%s: every list needs its own zeroed, 16-byte aligned workspace of "
+                 "sige_reduce_mask_workspace_bytes(g) bytes", who);
+    if (n == 0) {   // mask only: the geometry only has to match the pooled size
+        int th, tw;
+        if (int rc = check_geom(g_mask_only, who, &th, &tw)) return rc;
+        SIGE_REQUIRE(Hp == g_mask_only->H_in && Wp == g_mask_only->W_in, SIGE_ERR_INVALID_ARG,
+                     "%s: pooled mask %dx%d does not match the conv input %dx%d", who, Hp, Wp,
+                     g_mask_only->H_in, g_mask_only->W_in);
+    }
+    if (all_ws) mk.n = n;
     const uint8_t* mask = mask_in;
-    const bool use_ws = workspace != nullptr && workspace_bytes >= sige_reduce_mask_workspace_bytes(g) &&
-                        (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
-    MarkArgs mk;
-    mk.flags = use_ws ? (uint8_t*)workspace : nullptr;
-    mk.Wm = Wm; mk.pool_log2 = pool_log2; mk.dilate = dilate;
-    mk.sy = g->block_h * g->stride; mk.sx = g->block_w * g->stride;
-    mk.th = th; mk.tw = tw; mk.pad = g->pad; mk.nby = (int)nby; mk.nbx = (int)nbx;
-    if (mask_only) mk.flags = nullptr;
     bool marked = false;
     if (diff_mode) {
         SIGE_REQUIRE(a_orig && a_edit, SIGE_ERR_INVALID_ARG, "%s: a_orig and a_edit are both required", who);
@@ -354,18 +400,11 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
                                   : launch_diff<bf16>(a_orig, a_edit, Hm, Wm, C, tau, mask_out, mk, &marked, st);
         if (rc) return rc;
         mask = mask_out;
-        if (mask_only) return SIGE_OK;
+        if (n == 0) return SIGE_OK;
     }
-    ListArgs a;
-    a.mask = mask;
-    a.Hm = Hm; a.Wm = Wm; a.pool_log2 = pool_log2; a.dilate = dilate;
-    a.Hin = g->H_in; a.Win = g->W_in; a.bh = g->block_h; a.bw = g->block_w;
-    a.stride = g->stride; a.pad = g->pad; a.th = th; a.tw = tw;
-    a.nby = (int)nby; a.nbx = (int)nbx;
-    a.indices = indices; a.max_blocks = max_blocks; a.count = count;
-    a.words = (pool_log2 >= 2 && Wm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & 3u) == 0) ? 1 : 0;
-    const size_t lds = ((size_t)(nby * nbx) + 15) & ~(size_t)15;
-    if (use_ws) {
+    const int words = (pool_log2 >= 2 && Wm % 4 == 0 && (reinterpret_cast<uintptr_t>(mask) & 3u) == 0) ? 1 : 0;
+    for (int i = 0; i < n; ++i) { ls.a[i].mask = mask; ls.a[i].words = words; }
+    if (all_ws) {
         if (!marked) {
             const int wpr = (Wm + 3) / 4;
             const long threads = (long)Hm * wpr;
@@ -374,10 +413,12 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
                                Hm, wpr, aligned, mk);
             SIGE_LAUNCH_CHECK("sige_reduce_mask(mark)");
         }
-        hipLaunchKernelGGL(compact_ws_kernel, dim3(1), dim3(1024), 0, st, a, mk.flags);
+        hipLaunchKernelGGL(compact_ws_kernel, dim3(n), dim3(1024), 0, st, ls);
         SIGE_LAUNCH_CHECK("sige_reduce_mask(compact)");
         return SIGE_OK;
     }
+    const ListArgs& a = ls.a[0];
+    const size_t lds = ((size_t)(a.nby * a.nbx) + 15) & ~(size_t)15;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)block_list_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -387,4 +428,39 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     hipLaunchKernelGGL(block_list_kernel, dim3(1), dim3(1024), lds, st, a);
     SIGE_LAUNCH_CHECK("sige_reduce_mask(list)");
     return SIGE_OK;
+}
+
+extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
+                                int32_t Wm, int32_t C, float tau, const uint8_t* mask_in,
+                                int32_t pool_log2, int32_t dilate, const sige_geom* g,
+                                uint8_t* mask_out, int32_t* indices, int32_t max_blocks,
+                                int32_t* count, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    const char* who = "sige_reduce_mask";
+    SIGE_REQUIRE(g != nullptr, SIGE_ERR_INVALID_ARG, "%s: geometry is NULL", who);
+    const bool diff_mode = a_orig != nullptr || a_edit != nullptr;
+    if (diff_mode && indices == nullptr && count == nullptr)
+        return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, nullptr, 0, g,
+                            mask_out, stream);
+    sige_block_list L;
+    L.g = *g; L.indices = indices; L.max_blocks = max_blocks; L.count = count;
+    L.workspace = workspace; L.workspace_bytes = workspace_bytes;
+    return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, &L, 1, nullptr,
+                        mask_out, stream);
+}
+
+extern "C" int sige_reduce_mask_lists(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
+                                      int32_t Wm, int32_t C, float tau, const uint8_t* mask_in,
+                                      int32_t pool_log2, int32_t dilate, const sige_block_list* lists,
+                                      int32_t n_lists, uint8_t* mask_out, void* stream)
+{
+    clear_error();
+    const char* who = "sige_reduce_mask_lists";
+    SIGE_REQUIRE(lists != nullptr && n_lists >= 1 && n_lists <= MAX_LISTS, SIGE_ERR_INVALID_ARG,
+                 "%s: between 1 and %d lists per call", who, MAX_LISTS);
+    for (int i = 0; i < n_lists; ++i)
+        SIGE_REQUIRE(lists[i].workspace != nullptr, SIGE_ERR_INVALID_ARG, "%s: list %d has no workspace", who, i);
+    return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, lists, n_lists,
+                        nullptr, mask_out, stream);
 }

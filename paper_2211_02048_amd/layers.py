@@ -46,6 +46,16 @@ class BlockList:
                              max_blocks=self.max_blocks, workspace=self.scratch)
         self.n_host = -1
 
+    @staticmethod
+    def reduce_together(lists, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None, mask_out=None,
+                        pool_log2=0, dilate=0):
+        """One call for the lists of several layer geometries at one resolution (same mask)."""
+        api.sige_reduce_mask_lists([(b.g, b.indices, b.count, b.max_blocks, b.scratch) for b in lists],
+                                   a_orig=a_orig, a_edit=a_edit, tau=tau, mask_in=mask_in, mask_out=mask_out,
+                                   pool_log2=pool_log2, dilate=dilate)
+        for b in lists:
+            b.n_host = -1
+
     def all_active(self):
         """Every block of the grid, row-major: the dense / pre-computation pass."""
         g = self.g

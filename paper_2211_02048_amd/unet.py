@@ -94,10 +94,14 @@ class SigeUNet:
         exact=False keeps the counts on the device and sizes launches by a capacity (power of two
         above the count), which is what a captured graph needs."""
         used = {id(L["list"][1]): L["list"][1] for L in self.layers.values() if L["sparse"]}
+        by_res = {}
         for bl in used.values():
-            pool = int(math.log2(self.res // bl.g.H_in))
             bl.max_blocks = bl.indices.shape[0]
-            bl.reduce(mask_in=mask_image, pool_log2=pool, dilate=self.dilate)
+            by_res.setdefault(bl.g.H_in, []).append(bl)
+        for H_in, group in by_res.items():       # one call per resolution: its geometries share the mask
+            pool = int(math.log2(self.res // H_in))
+            for i in range(0, len(group), 4):
+                BlockList.reduce_together(group[i:i + 4], mask_in=mask_image, pool_log2=pool, dilate=self.dilate)
         counts = {}
         for bl in used.values():
             n = bl.sync_count()

@@ -126,6 +126,60 @@ def test_block_list_degenerate_and_overflow(oracle):
             assert not bl.scratch.any()  # the flags are left cleared
 
 
+@pytest.mark.parametrize("mode", ["activations", "mask"])
+@pytest.mark.parametrize("pool_log2,dilate", [(0, 0), (0, 1), (1, 1), (2, 2)])
+def test_reduce_mask_lists_one_pass_several_geometries(oracle, mode, pool_log2, dilate):
+    """Four layer geometries of one resolution from one pass: every list bit-exact against the oracle
+    (hence equal to four separate calls); flags left clean; capacity clipping per list."""
+    rng = np.random.default_rng(77 + 10 * pool_log2 + dilate)
+    Hm, Wm, C = 90, 122, 64
+    H, W = -(-Hm // (1 << pool_log2)), -(-Wm // (1 << pool_log2))
+    geoms = [api.geom(H, W, 8, 3, 1, 1), api.geom(H, W, 8, 1, 1, 0), api.geom(H, W, 4, 3, 2, 1),
+             api.geom(H, W, (6, 5), 5, 1, 2)]
+    m = inputs.blob_mask(rng, Hm, Wm, int(0.03 * Hm * Wm)).astype(np.float32)
+    a_o = rng.standard_normal((Hm, Wm, C)).astype(np.float32)
+    a_e = a_o + m[:, :, None] * rng.standard_normal((Hm, Wm, C)).astype(np.float32)
+    lists = [BlockList(g, "cuda", max_blocks=(2 if i == 1 else None)) for i, g in enumerate(geoms)]
+    for b in lists:
+        b.indices.fill_(-7)
+    for rep in range(2):      # the second call reuses the workspaces the first one left zero
+        if mode == "activations":
+            mask_out = torch.full((Hm, Wm), 9, dtype=torch.uint8, device="cuda")
+            BlockList.reduce_together(lists, a_orig=dev(torch.from_numpy(a_o).half()),
+                                      a_edit=dev(torch.from_numpy(a_e).half()), tau=0.0, mask_out=mask_out,
+                                      pool_log2=pool_log2, dilate=dilate)
+            want_mask = oracle.diff_mask(torch.from_numpy(a_o).half().double().numpy(),
+                                         torch.from_numpy(a_e).half().double().numpy(), 0.0)
+            assert np.array_equal(mask_out.cpu().numpy(), want_mask)
+        else:
+            want_mask = m.astype(np.uint8)
+            BlockList.reduce_together(lists, mask_in=torch.from_numpy(want_mask).cuda(), pool_log2=pool_log2,
+                                      dilate=dilate)
+        torch.cuda.synchronize()
+        lvl = oracle.level_mask(want_mask, pool_log2, dilate)
+        for i, (b, g) in enumerate(zip(lists, geoms)):
+            want = oracle.active_blocks(lvl, g.H_out, g.W_out, g.block_h, g.block_w, g.k, g.stride, g.pad)
+            n = int(b.count.item())
+            assert n == len(want) and n > 0, (i, n, len(want))
+            keep = min(n, b.max_blocks)
+            assert np.array_equal(b.indices[:keep].cpu().numpy(), want[:keep]), i
+            assert (b.indices[keep:] == -7).all()
+            assert not b.scratch.any()
+    assert int(lists[1].count.item()) > 2        # the clipped list really was clipped
+    # error paths: shared workspace, missing workspace, too many lists
+    with pytest.raises(api.SigeError):
+        api.sige_reduce_mask_lists([(geoms[0], lists[0].indices, lists[0].count, None, lists[0].scratch),
+                                    (geoms[0], lists[1].indices, lists[1].count, None, lists[0].scratch)],
+                                   mask_in=torch.from_numpy(want_mask).cuda(), pool_log2=pool_log2, dilate=dilate)
+    with pytest.raises(api.SigeError):
+        api.sige_reduce_mask_lists([(geoms[0], lists[0].indices, lists[0].count, None, None)],
+                                   mask_in=torch.from_numpy(want_mask).cuda(), pool_log2=pool_log2, dilate=dilate)
+    with pytest.raises(api.SigeError):
+        api.sige_reduce_mask_lists([(g, b.indices, b.count, None, b.scratch) for g, b in zip(geoms, lists)] +
+                                   [(geoms[0], lists[0].indices, lists[0].count, None, lists[0].scratch)],
+                                   mask_in=torch.from_numpy(want_mask).cuda(), pool_log2=pool_log2, dilate=dilate)
+
+
 # ------------------------------------------------------------------ a4 / a6: gather and scatter
 
 def random_blocks(rng, g, n):
