@@ -137,11 +137,22 @@ int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t u
  * An implicit GEMM on the matrix cores with fp32 accumulation, one rounding to dt.
  * packed_weight comes from sige_pack_weight for the same (dt, Cout, Cin, k); bias
  * fp32 [Cout] or NULL.  Cin must be a multiple of 16 (f16/bf16) or 8 (f32).
- * out_tiles: [max_blocks][block_h][block_w][Cout] contiguous.                     */
+ * out_tiles: [max_blocks][block_h][block_w][Cout] contiguous.
+ * workspace: optional device scratch (16-byte aligned, any contents, no state kept between
+ * calls; sige_conv_workspace_bytes gives the size that allows every split).  With it a call
+ * that has few active blocks but many input channels (the low-resolution layers of a UNet)
+ * is cut along K over more workgroups, which leave fp32 partial sums there; a second kernel
+ * adds them in a fixed order.  Results are deterministic for a given workspace size; with
+ * and without a workspace they may differ in the last bit of the fp32 sum.  Calls that
+ * share a workspace must not overlap.  NULL: never split.                            */
 int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
               const void* packed_weight, const float* bias,
               const int32_t* count, int32_t max_blocks, int32_t n_blocks,
-              void* out_tiles, void* stream);
+              void* out_tiles, void* workspace, size_t workspace_bytes, void* stream);
+/* Bytes of workspace with which sige_conv / sige_fused_conv can split K as far as they would
+ * for any number of blocks up to max_blocks (0 when they never split this layer).    */
+size_t sige_conv_workspace_bytes(sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                                 int32_t max_blocks);
 
 /* Fig. "pipeline" (b) Scatter: y holds the cached F_l(A_orig) on entry and is updated
  * in place; for every active block and every in-image pixel of it
@@ -166,14 +177,18 @@ int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32
  *   y         - scatter into the cached output, in place (residuals allowed), or
  *   out_tiles - keep the output tiles [max_blocks][block_h][block_w][Cout] (a shortcut
  *               branch whose tiles a later call adds as residual_tiles)
- * must be given.  x and y must not overlap (a tile's halo belongs to other blocks).     */
+ * must be given.  x and y must not overlap (a tile's halo belongs to other blocks).
+ * workspace: as for sige_conv (the reduction kernel then also adds the residuals and
+ * scatters); bit-identity with the three calls holds when sige_conv gets a workspace of
+ * the same size.                                                                      */
 int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
                     const sige_geom* g, const int32_t* indices, const int32_t* count,
                     int32_t max_blocks, int32_t n_blocks,
                     const float* scale, const float* shift, sige_act act,
                     int32_t Cout, const void* packed_weight, const float* bias,
                     const void* residual_tiles, const void* residual, int32_t res_ld,
-                    void* y, int32_t y_ld, void* out_tiles, void* stream);
+                    void* y, int32_t y_ld, void* out_tiles,
+                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* Fig. "sige-attention" / Sec. 3.2 "Extension to attention layers": attention for the
  * edited query tokens only, against all T keys and values (the caches with the

@@ -22,7 +22,7 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_conv", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_conv", "sige_conv_workspace_bytes", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
            "sige_sparse_attn_workspace_bytes", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -87,9 +87,11 @@ def lib() -> ctypes.CDLL:
         L.sige_reduce_mask_workspace_bytes.restype = ctypes.c_size_t
         L.sige_reduce_mask_workspace_bytes.argtypes = [gp]
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
-        L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
+        L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+        L.sige_conv_workspace_bytes.restype = ctypes.c_size_t
+        L.sige_conv_workspace_bytes.argtypes = [i32, gp, i32, i32, i32]
         L.sige_fused_conv.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp,
-                                      i32, vp, i32, vp, vp]
+                                      i32, vp, i32, vp, vp, sz, vp]
         L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
         L.sige_sparse_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
         L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
@@ -163,12 +165,21 @@ def sige_gather(x, g: Geom, indices, count, tiles, *, n_blocks=-1, scale=None, s
                              mb, n_blocks, _ptr(scale), _ptr(shift), act, _ptr(tiles), _stream()))
 
 
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def sige_conv_workspace_bytes(dtype, g: Geom, Cin, Cout, max_blocks) -> int:
+    return int(lib().sige_conv_workspace_bytes(_DT[dtype], ctypes.byref(g), Cin, Cout, max_blocks))
+
+
 def sige_conv(tiles, g: Geom, Cin, Cout, packed_weight, bias, count, out_tiles, *, n_blocks=-1,
-              max_blocks=None):
+              max_blocks=None, workspace=None):
     """out_tiles[n] = valid conv of tiles[n] with the packed weight, plus bias."""
     mb = tiles.shape[0] if max_blocks is None else max_blocks
     _check(lib().sige_conv(_ptr(tiles), _DT[tiles.dtype], ctypes.byref(g), Cin, Cout, _ptr(packed_weight),
-                           _ptr(bias), _ptr(count), mb, n_blocks, _ptr(out_tiles), _stream()))
+                           _ptr(bias), _ptr(count), mb, n_blocks, _ptr(out_tiles), _ptr(workspace),
+                           _nbytes(workspace), _stream()))
 
 
 def sige_scatter(out_tiles, g: Geom, indices, count, y, *, n_blocks=-1, residual_tiles=None, residual=None,
@@ -186,7 +197,7 @@ def sige_scatter(out_tiles, g: Geom, indices, count, y, *, n_blocks=-1, residual
 
 def sige_fused_conv(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, *, y=None, out_tiles=None,
                     n_blocks=-1, max_blocks=None, scale=None, shift=None, act=ACT_NONE, up=0, x_ld=None,
-                    residual_tiles=None, residual=None, res_ld=None, y_ld=None):
+                    residual_tiles=None, residual=None, res_ld=None, y_ld=None, workspace=None):
     """gather -> conv -> scatter in one kernel; y is updated in place (or out_tiles receives the tiles)."""
     x_ld = x.stride(-2) if x_ld is None else x_ld
     if y is not None and y_ld is None:
@@ -197,7 +208,7 @@ def sige_fused_conv(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, 
     _check(lib().sige_fused_conv(_ptr(x), _DT[x.dtype], Cin, x_ld, up, ctypes.byref(g), _ptr(indices), _ptr(count),
                                  mb, n_blocks, _ptr(scale), _ptr(shift), act, Cout, _ptr(packed_weight), _ptr(bias),
                                  _ptr(residual_tiles), _ptr(residual), res_ld or 0, _ptr(y), y_ld or 0,
-                                 _ptr(out_tiles), _stream()))
+                                 _ptr(out_tiles), _ptr(workspace), _nbytes(workspace), _stream()))
 
 
 def sige_sparse_attn_workspace_bytes(Nq, T, heads, d) -> int:

@@ -99,15 +99,30 @@ __device__ __forceinline__ uint4 load_stream(const uint4* p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// f[i] = act(sc[i] * f[i] + sh[i]) for the N elements of one vector.  The activation is chosen once
+// per vector, not per element, so that the N independent chains sit in one basic block and overlap.
 // SiLU as v * rcp(1 + exp2(-v * log2 e)): two hardware transcendentals (about 1 ulp each) and no
 // full-precision division, so that the fused gather stays bandwidth bound.  exp2 overflows to
 // +inf for very negative v, whose reciprocal is 0: the result is -0, as it should be.
-__device__ __forceinline__ float apply_act(float v, int act)
+template <int N>
+__device__ __forceinline__ void scale_shift_act(float (&f)[N], const float (&sc)[N], const float (&sh)[N], int act)
 {
-    if (act == SIGE_ACT_SILU)
-        return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f));
-    if (act == SIGE_ACT_RELU) return v > 0.0f ? v : 0.0f;
-    return v;
+    if (act == SIGE_ACT_SILU) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const float v = fmaf(sc[i], f[i], sh[i]);
+            f[i] = v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f));
+        }
+    } else if (act == SIGE_ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const float v = fmaf(sc[i], f[i], sh[i]);
+            f[i] = v > 0.0f ? v : 0.0f;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) f[i] = fmaf(sc[i], f[i], sh[i]);
+    }
 }
 
 __device__ __forceinline__ bool aligned16_dev(const void* p)

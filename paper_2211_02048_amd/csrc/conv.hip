@@ -77,6 +77,12 @@ struct ConvArgs {
     const void* res_full;
     void* y;
     int Hin, Win, x_ld, up, pad, act, Hout, Wout, y_ld, res_ld;
+    // K split over workgroups (ksplit > 1): workgroup (band, split) multiplies only its share of
+    // the channel chunks and stores fp32 partial sums, partial[split][tile element]; a second
+    // kernel adds the shares in a fixed order and finishes the output
+    float* partial;
+    long partial_stride;
+    int ksplit, bands;
 };
 
 // Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
@@ -105,6 +111,67 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 // take different channel ranges of every tap and are summed through LDS at the end); KC = K steps
 // per staged channel chunk; KK = k*k when it is 9 or 1 (taps unrolled), 0 for any other kernel size.  Weight fragments are fetched into a register ring several taps ahead
 // of the MFMAs that use them (deepest for the K-split shape, whose layers are weight-bound).
+// Finishes one run of N consecutive output channels starting at o: v holds the fp32 sums (bias
+// included), t the element's index in the stacked output tiles, pix the pixel of y it belongs to.
+// Plain mode stores the tile elements; fused mode rounds them to the storage type as a stored
+// tile would be, adds the residuals in fp32 and stores into y.
+template <typename T>
+__device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_ok, long t, long pix, int o,
+                                         float (&v)[Vec16<T>::N])
+{
+    constexpr int N = Vec16<T>::N;
+    T* __restrict__ out = (T*)a.out;
+    if (vec_ok && o + N <= a.Cout) {
+        uint4 r = pack<T>(v);
+        if (to_y) {
+            if (a.res_tiles || a.res_full) {
+                float f[N], q[N];
+                unpack<T>(r, f);
+                if (a.res_tiles) {
+                    unpack<T>(*(const uint4*)((const T*)a.res_tiles + t), q);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) f[i] += q[i];
+                }
+                if (a.res_full) {
+                    unpack<T>(*(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) f[i] += q[i];
+                }
+                r = pack<T>(f);
+            }
+            *(uint4*)((T*)a.y + pix * a.y_ld + o) = r;
+        } else {
+            *(uint4*)(out + t) = r;
+        }
+    } else {
+        for (int i = 0; i < N && o + i < a.Cout; ++i) {
+            T r = from_f32<T>(v[i]);
+            if (to_y) {
+                if (a.res_tiles || a.res_full) {
+                    float f = to_f32(r);
+                    if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t + i]);
+                    if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o + i]);
+                    r = from_f32<T>(f);
+                }
+                ((T*)a.y)[pix * a.y_ld + o + i] = r;
+            } else {
+                out[t + i] = r;
+            }
+        }
+    }
+}
+
+// Whether the 16-byte paths of emit_run may be taken for this call.
+template <typename T>
+__device__ __forceinline__ bool emit_vec_ok(const ConvArgs& a, bool fused)
+{
+    constexpr int N = Vec16<T>::N;
+    return (a.Cout % N == 0) && aligned16_dev(a.out) &&
+           (!fused || a.y == nullptr ||
+            (a.y_ld % N == 0 && aligned16_dev(a.y) && (!a.res_tiles || aligned16_dev(a.res_tiles)) &&
+             (!a.res_full || (a.res_ld % N == 0 && aligned16_dev(a.res_full)))));
+}
+
 constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks in a 256-row patch)
 
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
@@ -135,7 +202,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
         if (threadIdx.x < a.G) { org[2 * threadIdx.x] = oy; org[2 * threadIdx.x + 1] = ox; }
         __syncthreads();
     }
-    const int band = blockIdx.y;
+    const int split = blockIdx.y / a.bands, band = blockIdx.y - split * a.bands;
     const int band_row0 = band * a.rows;                      // first output row of the band
     const int band_rows = min(a.rows, a.bh - band_row0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -167,7 +234,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int o = (nt0 + tn) * 32 + l32;
-        bias_v[tn] = (a.bias && o < a.Cout && wk == 0) ? a.bias[o] : 0.0f;
+        bias_v[tn] = (a.bias && o < a.Cout && wk == 0 && a.partial == nullptr) ? a.bias[o] : 0.0f;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -192,6 +259,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     // the last chunk re-reads the last chunk instead of branching.
     constexpr int P = KK == 0 ? 1 : (KW * TN <= 2 ? KK : (KW * TN <= 8 && KK % 3 == 0) ? 3 : 1);
     const int nch = a.Cin / (KC * KS);
+    const int ch0 = split * nch / a.ksplit, ch1 = (split + 1) * nch / a.ksplit;   // this workgroup's chunks
     const int ntaps = KK ? KK : kk;
     uint4 bq[P][KW][TN];
     auto fetch = [&](uint4 (&slot)[KW][TN], int chunk, int tp) {
@@ -203,46 +271,77 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     };
     const bool fused = a.x != nullptr;
     const bool fuse_math = fused && (a.scale != nullptr || a.act != SIGE_ACT_NONE);
+    // Staging of one channel chunk.  256 is a multiple of VPC, so a thread keeps one 16-byte channel
+    // group and walks over the pixels 256 / VPC at a time without dividing.  Each batch of U vectors
+    // is loaded before any of them is used (addresses are clamped into the source, so the loads are
+    // unconditional and overlap; what lies outside becomes zero afterwards).
+    constexpr int U = TM * TN <= 2 ? 8 : 4;
+    constexpr int PPI = 256 / VPC;                            // pixels covered by one step of the walk
+    const int sv = tid % VPC;
+    int sq0 = tid / VPC, sg0, sr0, sx0;                       // first pixel of this thread: index, block, row, column
+    {
+        const int per = a.trows * a.tw;
+        sg0 = sq0 / per;
+        const int rem = sq0 - sg0 * per;
+        sr0 = rem / a.tw;
+        sx0 = rem - sr0 * a.tw;
+    }
     auto stage = [&](int chunk) {
         constexpr int N = Vec16<T>::N;
         const int c0 = chunk * (KC * KS);
-        if (chunk) __syncthreads();
-        // 256 is a multiple of VPC, so a thread keeps one 16-byte channel group of the chunk
+        if (chunk != ch0) __syncthreads();
         float sc[N], sh[N];
         if (fuse_math) {
-            const int cbase = c0 + (tid % VPC) * N;
+            const int cbase = c0 + sv * N;
 #pragma unroll
             for (int i = 0; i < N; ++i) {
                 sc[i] = a.scale ? a.scale[cbase + i] : 1.0f;
                 sh[i] = a.scale ? a.shift[cbase + i] : 0.0f;
             }
         }
-        for (int j = tid; j < npix * VPC; j += 256) {
-            const int q = j / VPC, v = j - q * VPC;
-            const int g = q / (a.trows * a.tw), rem = q - g * (a.trows * a.tw);
-            const int r = rem / a.tw, x = rem - r * a.tw;
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (g0 + g < n_eff && trow0 + r < a.th) {
+        int q = sq0, g = sg0, r = sr0, x = sx0;
+        const int Ws = a.Win >> a.up;
+        while (q < npix) {
+            uint4 val[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool in = q + u * PPI < npix;
+                const int gb = min(g0 + g, n_eff - 1), tr = min(trow0 + r, a.th - 1);
+                ok[u] = in && g0 + g < n_eff && trow0 + r < a.th;
+                const char* src;
                 if (!fused) {
-                    val = *(const uint4*)(tiles + ((((long)(g0 + g) * a.th + trow0 + r) * a.tw + x) * a.Cin + c0) * S + v * 16);
+                    src = tiles + ((((long)gb * a.th + tr) * a.tw + x) * a.Cin + c0) * S + sv * 16;
                 } else {
                     // the gather: input pixel of tile position (trow0 + r, x) of block g0 + g
-                    const int iy = org[2 * g] * a.stride - a.pad + trow0 + r;
-                    const int ix = org[2 * g + 1] * a.stride - a.pad + x;
-                    if (iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win) {
-                        val = *(const uint4*)((const char*)a.x +
-                                              (((long)(iy >> a.up) * (a.Win >> a.up) + (ix >> a.up)) * a.x_ld + c0) * S + v * 16);
-                        if (fuse_math) {
-                            float f[N];
-                            unpack<T>(val, f);
+                    const int gl = min(g, a.G - 1);
+                    const int iy = org[2 * gl] * a.stride - a.pad + tr;
+                    const int ix = org[2 * gl + 1] * a.stride - a.pad + x;
+                    ok[u] = ok[u] && iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win;
+                    const int cy = min(max(iy, 0), a.Hin - 1) >> a.up, cx = min(max(ix, 0), a.Win - 1) >> a.up;
+                    src = (const char*)a.x + (((long)cy * Ws + cx) * a.x_ld + c0) * S + sv * 16;
+                }
+                val[u] = *(const uint4*)src;
+                x += PPI;
+                while (x >= a.tw) { x -= a.tw; ++r; }
+                while (r >= a.trows) { r -= a.trows; ++g; }
+            }
 #pragma unroll
-                            for (int i = 0; i < N; ++i) f[i] = apply_act(fmaf(sc[i], f[i], sh[i]), a.act);
-                            val = pack<T>(f);   // padding never takes this branch: it stays literally zero
-                        }
+            for (int u = 0; u < U; ++u) {
+                if (q + u * PPI >= npix) break;
+                uint4 w = make_uint4(0, 0, 0, 0);   // padding and inactive rows stay literally zero
+                if (ok[u]) {
+                    w = val[u];
+                    if (fuse_math) {
+                        float f[N];
+                        unpack<T>(w, f);
+                        scale_shift_act<N>(f, sc, sh, a.act);
+                        w = pack<T>(f);
                     }
                 }
+                *(uint4*)(lds + (q + u * PPI) * a.ps + sv * 16) = w;
             }
-            *(uint4*)(lds + q * a.ps + v * 16) = val;
+            q += U * PPI;
         }
         __syncthreads();
     };
@@ -264,8 +363,8 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 
     if constexpr (KK > 0) {
 #pragma unroll
-        for (int p = 0; p < P; ++p) fetch(bq[p], 0, p);
-        for (int chunk = 0; chunk < nch; ++chunk) {
+        for (int p = 0; p < P; ++p) fetch(bq[p], ch0, p);
+        for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
 #pragma unroll
             for (int tp = 0; tp < KK; ++tp) {
@@ -279,7 +378,7 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
             }
         }
     } else {
-        for (int chunk = 0; chunk < nch; ++chunk) {
+        for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
 #pragma nounroll
             for (int tp = 0; tp < ntaps; ++tp) {
@@ -308,14 +407,8 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
                 red[(wk * BM + m) * RS + nn] = acc[tm][tn][r] + bias_v[tn];
             }
     __syncthreads();
-    // One run of V consecutive channels starting at o of row m of this workgroup's patch; vals are
-    // fp32 sums (bias included).  Plain mode stores the tile elements; fused mode rounds them to
-    // the storage type as a stored tile would be, adds the residuals in fp32 and scatters into y.
-    const bool vec_ok = (a.Cout % N == 0) && aligned16_dev(a.out) &&
-                        (!fused || a.y == nullptr ||
-                         (a.y_ld % N == 0 && aligned16_dev(a.y) && (!a.res_tiles || aligned16_dev(a.res_tiles)) &&
-                          (!a.res_full || (a.res_ld % N == 0 && aligned16_dev(a.res_full)))));
-    T* __restrict__ out = (T*)a.out;
+    const bool vec_ok = emit_vec_ok<T>(a, fused);
+    const bool to_y = fused && a.y != nullptr;
     for (int e = tid; e < BM * (BN / N); e += 256) {
         const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
         const int o = blockIdx.x * BN + nn;
@@ -330,58 +423,95 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
             for (int w = 0; w < WK; ++w) v[i] += red[(w * BM + m) * RS + nn + i];
         }
         const long t = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o;
-        const bool to_y = fused && a.y != nullptr;
+        if (a.partial != nullptr) {          // this workgroup's share of K, unrounded, for the reduction kernel
+            float* __restrict__ dst = a.partial + split * a.partial_stride + t;
+            if ((a.Cout & 3) == 0 && o + N <= a.Cout) {
+#pragma unroll
+                for (int i = 0; i < N; i += 4) *(float4*)(dst + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+            } else {
+                for (int i = 0; i < N && o + i < a.Cout; ++i) dst[i] = v[i];
+            }
+            continue;
+        }
         long pix = 0;
         if (to_y) {
             const int oy = org[2 * g] + band_row0 + py, ox = org[2 * g + 1] + px;
             if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) continue;
             pix = (long)oy * a.Wout + ox;
         }
-        if (vec_ok && o + N <= a.Cout) {
-            uint4 r = pack<T>(v);
-            if (to_y) {
-                if (a.res_tiles || a.res_full) {
-                    float f[N], q[N];
-                    unpack<T>(r, f);
-                    if (a.res_tiles) {
-                        unpack<T>(*(const uint4*)((const T*)a.res_tiles + t), q);
+        emit_run<T>(a, to_y, vec_ok, t, pix, o, v);
+    }
+}
+
+// Second kernel of a K-split call: adds the workgroups' shares in a fixed order, then the bias, and
+// finishes every run of output channels exactly as the unsplit epilogue does.
+template <typename T>
+__global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_runs)
+{
+    constexpr int N = Vec16<T>::N;
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n_runs) return;
+    const int runs = (a.Cout + N - 1) / N;
+    const long row = e / runs;
+    const int o = (int)(e - row * runs) * N;
+    const int pb = a.bh * a.bw;
+    const int n = (int)(row / pb), p = (int)(row - (long)n * pb);
+    const int py = p / a.bw, px = p - py * a.bw;
+    const bool fused = a.x != nullptr;
+    const bool to_y = fused && a.y != nullptr;
+    int y0 = 0, x0 = 0, n_eff;
+    if (to_y) n_eff = blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, y0, x0);
+    else n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
+    if (n >= n_eff) return;
+    const long t = row * a.Cout + o;
+    float v[N];
+    const bool vec4 = (a.Cout & 3) == 0 && o + N <= a.Cout;
 #pragma unroll
-                        for (int i = 0; i < N; ++i) f[i] += q[i];
-                    }
-                    if (a.res_full) {
-                        unpack<T>(*(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
+    for (int i = 0; i < N; ++i) v[i] = 0.0f;
+    if (vec4) {
+        // four shares are in flight at a time; they are still added in the order of the split index
+        for (int s0 = 0; s0 < a.ksplit; s0 += 4) {
+            float4 q[4][N / 4];
 #pragma unroll
-                        for (int i = 0; i < N; ++i) f[i] += q[i];
-                    }
-                    r = pack<T>(f);
-                }
-                *(uint4*)((T*)a.y + pix * a.y_ld + o) = r;
-            } else {
-                *(uint4*)(out + t) = r;
+            for (int j = 0; j < 4; ++j) {
+                const float* __restrict__ src = a.partial + min(s0 + j, a.ksplit - 1) * a.partial_stride + t;
+#pragma unroll
+                for (int i = 0; i < N / 4; ++i) q[j][i] = *(const float4*)(src + 4 * i);
             }
-        } else {
-            for (int i = 0; i < N && o + i < a.Cout; ++i) {
-                T r = from_f32<T>(v[i]);
-                if (to_y) {
-                    if (a.res_tiles || a.res_full) {
-                        float f = to_f32(r);
-                        if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t + i]);
-                        if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o + i]);
-                        r = from_f32<T>(f);
-                    }
-                    ((T*)a.y)[pix * a.y_ld + o + i] = r;
-                } else {
-                    out[t + i] = r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (s0 + j >= a.ksplit) break;
+#pragma unroll
+                for (int i = 0; i < N / 4; ++i) {
+                    v[4 * i] += q[j][i].x; v[4 * i + 1] += q[j][i].y;
+                    v[4 * i + 2] += q[j][i].z; v[4 * i + 3] += q[j][i].w;
                 }
             }
         }
+    } else {
+        for (int s = 0; s < a.ksplit; ++s) {
+            const float* __restrict__ src = a.partial + s * a.partial_stride + t;
+            for (int i = 0; i < N && o + i < a.Cout; ++i) v[i] += src[i];
+        }
     }
+    if (a.bias)
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            if (o + i < a.Cout) v[i] += a.bias[o + i];
+    long pix = 0;
+    if (to_y) {
+        const int oy = y0 + py, ox = x0 + px;
+        if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) return;
+        pix = (long)oy * a.Wout + ox;
+    }
+    emit_run<T>(a, to_y, emit_vec_ok<T>(a, fused), t, pix, o, v);
 }
 
 struct ConvPlan {
     int cfg;  // index into kCfg
     int kc;   // K steps per staged channel chunk: 8, 4 or 1
     int G, rows, trows, Cc, ps, bands, slabs, groups;
+    int ksplit;   // workgroups that share one output patch along K (1 = no split)
     size_t lds;
 };
 
@@ -389,12 +519,22 @@ struct ConvPlan {
 struct CfgShape { int M, N, WK; };
 static const CfgShape kCfg[4] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}};
 
-// Chooses the workgroup shape and the staged channel chunk for one call.
+// Chooses the workgroup shape and the staged channel chunk for one call, then - when the caller
+// gave a workspace (partial_elems = fp32 elements it holds) and the call has few workgroups but a
+// long K - how many workgroups share one output patch along K.
 static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, size_t s, int kstep,
-                      int nblocks, ConvPlan* best)
+                      int nblocks, size_t partial_elems, ConvPlan* best)
 {
     const char* force = getenv("SIGE_CONV_CFG");
+    const char* force_kc = getenv("SIGE_CONV_KC");   // tuning aids: fix the shape / the K steps per chunk
     double best_score = -1.0;
+    auto lds_bytes = [&](int cfg, long npix, int kc) {
+        size_t lds = (size_t)npix * (kc * kstep * s + 16);
+        return std::max(lds, (size_t)kCfg[cfg].WK * kCfg[cfg].M * (kCfg[cfg].N + 4) * sizeof(float));   // the epilogue's staging
+    };
+    auto lds_fits = [&](int cfg, size_t lds, int kc) {
+        return lds <= (kc == 1 || (kc == 4 && kCfg[cfg].WK == 4) ? 160u : 80u) * 1024u;
+    };
     for (int cfg = 0; cfg < 4; ++cfg) {
         if (force && atoi(force) != cfg) continue;
         if (g->k != 1 && g->k != 3 && cfg != 2) continue;   // only the plain 64x64 shape is built for other k
@@ -402,6 +542,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         if (g->block_w > M) continue;
         ConvPlan p;
         p.cfg = cfg;
+        p.ksplit = 1;
         const int pbfull = g->block_h * g->block_w;
         if (pbfull <= M) { p.G = M / pbfull; p.rows = g->block_h; }
         else { p.G = 1; p.rows = M / g->block_w; }
@@ -412,14 +553,12 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         const long npix = (long)p.G * p.trows * tw;
         // K steps per chunk: the largest of 8 / 4 / 1 that divides Cin and whose staged tile fits
         p.kc = 0;
-        const char* force_kc = getenv("SIGE_CONV_KC");   // tuning aid: fix the K steps per chunk
         for (int kc : {8, 4, 1}) {
             if (force_kc && atoi(force_kc) != kc) continue;
             if (kc % WK || Cin % (kc * kstep)) continue;
             if (g->k != 1 && g->k != 3 && kc != 1) continue;
-            size_t lds = (size_t)npix * (kc * kstep * s + 16);
-            lds = std::max(lds, (size_t)WK * M * (Nn + 4) * sizeof(float));   // the epilogue's staging
-            if (lds <= (kc == 1 || (kc == 4 && WK == 4) ? 160u : 80u) * 1024u) { p.kc = kc; p.lds = lds; break; }
+            const size_t lds = lds_bytes(cfg, npix, kc);
+            if (lds_fits(cfg, lds, kc)) { p.kc = kc; p.lds = lds; break; }
         }
         if (p.kc == 0) continue;
         p.Cc = p.kc * kstep;
@@ -433,7 +572,38 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         const double score = util * fill * bonus * nuse;
         if (score > best_score) { best_score = score; *best = p; }
     }
-    return best_score >= 0.0;
+    if (best_score < 0.0) return false;
+    // K split over workgroups.  A workgroup walks through its channel chunks one after the other and
+    // each costs a staging round trip (a few microseconds), so a call with at most one workgroup per
+    // compute unit and at least three full chunks is cut along K (up to four workgroups per compute
+    // unit; with fewer chunks the second kernel costs more than it saves); smaller chunks when that
+    // is what it takes to reach 256 workgroups.
+    ConvPlan& p = *best;
+    const char* force_split = getenv("SIGE_CONV_SPLIT");
+    const long wgs = (long)p.groups * p.bands * p.slabs;
+    const size_t per_split = (size_t)nblocks * g->block_h * g->block_w * Cout;
+    const int max_by_ws = per_split ? (int)std::min<size_t>(partial_elems / per_split, 64) : 0;
+    if (max_by_ws >= 2 && (g->k == 1 || g->k == 3) && p.kc >= 4) {
+        const int WK = kCfg[p.cfg].WK;
+        int kc = p.kc;
+        if (kc == 8 && wgs * (Cin / (8 * kstep)) < 256 && 4 % WK == 0 && !force_kc) kc = 4;
+        const int nch = Cin / (kc * kstep);
+        int S = 1;
+        if (wgs <= 256 && Cin >= 3 * 8 * kstep) S = (int)std::min<long>(nch, (1024 + wgs - 1) / wgs);
+        if (force_split) S = std::min(atoi(force_split), nch);
+        S = std::max(1, std::min(S, max_by_ws));
+        if (S > 1) {
+            if (kc != p.kc) {
+                const long npix = (long)p.G * p.trows * tw;
+                p.kc = kc;
+                p.lds = lds_bytes(p.cfg, npix, kc);
+                p.Cc = kc * kstep;
+                p.ps = (int)(p.Cc * s + 16);
+            }
+            p.ksplit = S;
+        }
+    }
+    return true;
 }
 
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
@@ -446,7 +616,7 @@ static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
         SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_conv: cannot reserve %zu bytes of LDS: %s", p.lds,
                      hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(kern, dim3(p.slabs, p.bands, p.groups), dim3(256), p.lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(p.slabs, p.bands * p.ksplit, p.groups), dim3(256), p.lds, st, a);
     SIGE_LAUNCH_CHECK("sige_conv");
     return SIGE_OK;
 }
@@ -521,28 +691,66 @@ extern "C" int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout,
     return SIGE_OK;
 }
 
+template <typename T>
+static int launch_reduce(const ConvArgs& a, int nl, hipStream_t st)
+{
+    const long n_runs = (long)nl * a.bh * a.bw * ((a.Cout + Vec16<T>::N - 1) / Vec16<T>::N);
+    const long blocks = (n_runs + 255) / 256;
+    SIGE_REQUIRE(blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "sige_conv: too many output elements for the K-split reduction");
+    hipLaunchKernelGGL((conv_reduce_kernel<T>), dim3((int)blocks), dim3(256), 0, st, a, n_runs);
+    SIGE_LAUNCH_CHECK("sige_conv(reduce)");
+    return SIGE_OK;
+}
+
 // Shared by sige_conv and sige_fused_conv: plan, fill the arguments, launch.
 static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, int tw, int Cin, int Cout,
-                    int max_blocks, int n_blocks, int nl, ConvArgs& a, void* stream)
+                    int max_blocks, int n_blocks, int nl, ConvArgs& a, void* workspace, size_t workspace_bytes,
+                    void* stream)
 {
     const int ks = dt == SIGE_F32 ? 8 : 16;
     ConvPlan p;
-    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, &p), SIGE_ERR_UNSUPPORTED,
-                 "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who, g->block_h, g->block_w,
-                 g->k, g->stride, Cin);
-    SIGE_REQUIRE(p.groups <= 65535 && p.bands <= 65535, SIGE_ERR_UNSUPPORTED, "%s: too many blocks per launch", who);
+    const bool ws_ok = workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
+    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok ? workspace_bytes / sizeof(float) : 0, &p),
+                 SIGE_ERR_UNSUPPORTED, "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who,
+                 g->block_h, g->block_w, g->k, g->stride, Cin);
+    SIGE_REQUIRE(p.groups <= 65535 && p.bands * p.ksplit <= 65535, SIGE_ERR_UNSUPPORTED,
+                 "%s: too many blocks per launch", who);
     a.th = th; a.tw = tw; a.bh = g->block_h; a.bw = g->block_w; a.k = g->k; a.stride = g->stride;
     a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
     a.G = p.G; a.rows = p.rows; a.trows = p.trows; a.Cc = p.Cc; a.ps = p.ps;
+    a.bands = p.bands; a.ksplit = p.ksplit;
+    a.partial = p.ksplit > 1 ? (float*)workspace : nullptr;
+    a.partial_stride = (long)nl * g->block_h * g->block_w * Cout;
     hipStream_t st = (hipStream_t)stream;
-    if (dt == SIGE_F32) return launch_conv<float>(a, p, st);
-    if (dt == SIGE_F16) return launch_conv<f16>(a, p, st);
-    return launch_conv<bf16>(a, p, st);
+    int rc = dt == SIGE_F32 ? launch_conv<float>(a, p, st)
+             : dt == SIGE_F16 ? launch_conv<f16>(a, p, st) : launch_conv<bf16>(a, p, st);
+    if (rc || p.ksplit == 1) return rc;
+    return dt == SIGE_F32 ? launch_reduce<float>(a, nl, st)
+           : dt == SIGE_F16 ? launch_reduce<f16>(a, nl, st) : launch_reduce<bf16>(a, nl, st);
+}
+
+extern "C" size_t sige_conv_workspace_bytes(sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                                            int32_t max_blocks)
+{
+    int th, tw;
+    if (!dtype_ok(dt) || Cin <= 0 || Cout <= 0 || max_blocks <= 0 || check_geom(g, "sige_conv_workspace_bytes", &th, &tw))
+        return 0;
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    if (Cin % ks) return 0;
+    size_t need = 0;
+    for (int nl = 1; nl <= max_blocks; ++nl) {
+        ConvPlan p;
+        if (!plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, (size_t)1 << 40, &p)) return 0;
+        if (p.ksplit > 1) need = std::max(need, (size_t)p.ksplit * nl * g->block_h * g->block_w * Cout * sizeof(float));
+        else if ((long)p.groups * p.bands * p.slabs > 256) break;   // more blocks only add workgroups
+    }
+    return need;
 }
 
 extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
                          const void* packed_weight, const float* bias, const int32_t* count,
-                         int32_t max_blocks, int32_t n_blocks, void* out_tiles, void* stream)
+                         int32_t max_blocks, int32_t n_blocks, void* out_tiles, void* workspace,
+                         size_t workspace_bytes, void* stream)
 {
     clear_error();
     const char* who = "sige_conv";
@@ -560,7 +768,7 @@ extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, i
     if (nl == 0) return SIGE_OK;
     ConvArgs a = {};
     a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
-    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, stream);
+    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
 }
 
 extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
@@ -568,7 +776,8 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
                                int32_t max_blocks, int32_t n_blocks, const float* scale, const float* shift,
                                sige_act act, int32_t Cout, const void* packed_weight, const float* bias,
                                const void* residual_tiles, const void* residual, int32_t res_ld, void* y,
-                               int32_t y_ld, void* out_tiles, void* stream)
+                               int32_t y_ld, void* out_tiles, void* workspace, size_t workspace_bytes,
+                               void* stream)
 {
     clear_error();
     const char* who = "sige_fused_conv";
@@ -603,5 +812,5 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
     a.res_tiles = residual_tiles; a.res_full = residual; a.y = y;
     a.Hin = g->H_in; a.Win = g->W_in; a.x_ld = x_ld; a.up = up; a.pad = g->pad; a.act = (int)act;
     a.Hout = g->H_out; a.Wout = g->W_out; a.y_ld = y_ld; a.res_ld = res_ld;
-    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, stream);
+    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
 }

@@ -64,8 +64,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
                         sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
                     }
                 }
-#pragma unroll
-                for (int i = 0; i < N; ++i) f[i] = apply_act(fmaf(sc[i], f[i], sh[i]), a.act);
+                scale_shift_act<N>(f, sc, sh, a.act);
                 v = pack<T>(f);
             }
         }

@@ -90,6 +90,7 @@ class SigeConv:
         self.packed = api.sige_pack_weight(w_oihw)
         self.bias = None if bias is None else bias.to(self.device, torch.float32).contiguous()
         self.up = up
+        self._split_bytes = {}     # capacity -> workspace bytes that allow every K split
 
     def tiles_numel(self, n):
         return n * self.g.tile_h * self.g.tile_w * self.Cin
@@ -98,24 +99,32 @@ class SigeConv:
         return n * self.g.block_h * self.g.block_w * self.Cout
 
     def forward(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None,
-                act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False):
+                act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False,
+                split_k=True):
         """gather(x) -> conv -> scatter into y (in place), as three calls or as the one fused call.
         Returns the output tiles (None when the fused call scattered them directly)."""
         g, n = self.g, blocks.n_host
         cap = blocks.max_blocks if n < 0 else max(n, 1)
+        split = None
+        if split_k:
+            nb = self._split_bytes.get(cap)
+            if nb is None:
+                nb = self._split_bytes[cap] = api.sige_conv_workspace_bytes(self.dtype, g, self.Cin, self.Cout, cap)
+            if nb:
+                split = ws.get("split_k", nb // 4, torch.float32)
         if fused:
             out_tiles = None if scatter else ws.get("out_" + tag, self.out_numel(cap), self.dtype)
             api.sige_fused_conv(x, g, blocks.indices, blocks.count, self.Cin, self.Cout, self.packed, self.bias,
                                 y=y if scatter else None, out_tiles=out_tiles, n_blocks=n, max_blocks=cap,
                                 scale=scale, shift=shift, act=act, up=self.up, residual_tiles=residual_tiles,
-                                residual=residual)
+                                residual=residual, workspace=split)
             return out_tiles
         tiles = ws.get("tiles", self.tiles_numel(cap), self.dtype)
         out_tiles = ws.get("out_" + tag, self.out_numel(cap), self.dtype)
         api.sige_gather(x, g, blocks.indices, blocks.count, tiles, n_blocks=n, scale=scale, shift=shift,
                         act=act, up=self.up, C=self.Cin, max_blocks=cap)
         api.sige_conv(tiles, g, self.Cin, self.Cout, self.packed, self.bias, blocks.count, out_tiles,
-                      n_blocks=n, max_blocks=cap)
+                      n_blocks=n, max_blocks=cap, workspace=split)
         if scatter:
             api.sige_scatter(out_tiles, g, blocks.indices, blocks.count, y, n_blocks=n,
                              residual_tiles=residual_tiles, residual=residual, Cout=self.Cout,

@@ -31,7 +31,7 @@ def _next_pow2(n: int) -> int:
 class SigeUNet:
     def __init__(self, res=256, channels=(128, 128, 256, 256, 512, 512), attn_res=(16,), heads=4,
                  dtype="f16", seed=1003, device="cuda", block=16, groups=32, eps=1e-5, dilate=1,
-                 min_sparse_res=64, params=None, fused=False):
+                 min_sparse_res=64, params=None, fused=True):
         self.res, self.device, self.td = res, device, inputs.DTYPES[dtype]
         self.block, self.groups, self.eps, self.dilate, self.min_sparse_res = block, groups, eps, dilate, min_sparse_res
         self.bufs_shape, self.ops = inputs.unet_topology(res, 3, channels, attn_res, heads)
@@ -41,7 +41,9 @@ class SigeUNet:
         self.lists = {}        # (H_in, k, stride) -> [all-active list, sparse list]
         self.layers = {}
         self.graph = None
-        self.fused = fused       # True: one fused gather-conv-scatter call per convolution instead of three
+        # True: one fused gather-conv-scatter call per convolution instead of three; "lowres": only
+        # for the layers below min_sparse_res (all blocks active, few of them, many channels)
+        self.fused = fused
         f32 = lambda t: t.to(device, torch.float32).contiguous()
         for op in self.ops:
             n, C = op["name"], op["x"][2]
@@ -116,6 +118,7 @@ class SigeUNet:
         shortcut_tiles = {}
         for n, L in self.layers.items():
             op = L["op"]
+            fused = self.fused is True or (self.fused == "lowres" and not L["sparse"])
             bl = L["list"][0 if (dense or not L["sparse"]) else 1]
             x = self.view(op["x"])
             scale = shift = None
@@ -128,23 +131,23 @@ class SigeUNet:
                 act = api.ACT_SILU if op["act"] else api.ACT_NONE
                 if not op["scatter"]:
                     shortcut_tiles[n] = L["conv"].forward(x, None, bl, self.ws, scatter=False, tag="short",
-                                                          fused=self.fused)
+                                                          fused=fused)
                     continue
                 res_t = shortcut_tiles.get(op["shortcut"]) if op["shortcut"] else None
                 res_f = self.view(op["residual"]) if op["residual"] is not None else None
                 L["conv"].forward(x, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift, act=act,
-                                  residual_tiles=res_t, residual=res_f, tag="main", fused=self.fused)
+                                  residual_tiles=res_t, residual=res_f, tag="main", fused=fused)
             else:
                 C, heads = op["C"], op["heads"]
                 T = x.shape[0] * x.shape[1]
                 L["qkv"].forward(x, L["qkv_buf"], bl, self.ws, scale=scale, shift=shift, tag="main",
-                                 fused=self.fused)
+                                 fused=fused)
                 qkv = L["qkv_buf"].view(T, 3 * C)
                 api.sige_sparse_attn(qkv[:, :C], qkv[:, C:2 * C], qkv[:, 2 * C:], L["att_buf"].view(T, C),
                                      1.0 / math.sqrt(C // heads), Nq=T, workspace=L["att_ws"], heads=heads,
                                      d=C // heads, q_ld=3 * C, kv_ld=3 * C, o_ld=C)
                 L["proj"].forward(L["att_buf"], self.view(op["y"]), bl, self.ws, residual=x, tag="main",
-                                  fused=self.fused)
+                                  fused=fused)
         return self.B["out"]
 
     def precompute(self, image):

@@ -46,7 +46,7 @@ def test_geometry_errors(L):
     assert "block" in err(L)
     g = good_geom()
     g.k = 2
-    assert L.sige_conv(FAKE, 0, ctypes.byref(g), 64, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 1
+    assert L.sige_conv(FAKE, 0, ctypes.byref(g), 64, 64, FAKE, None, FAKE, 8, -1, FAKE, None, 0, None) == 1
     assert "odd" in err(L)
     g = good_geom()
     g.H_out = 63
@@ -62,25 +62,25 @@ def test_pointer_and_capacity_errors(L):
     # host n_blocks beyond the capacity
     assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, 9, None, None, 0, FAKE, None) == 3
     assert "exceeds" in err(L)
-    assert L.sige_conv(FAKE, 0, gp, 64, 64, FAKE, None, FAKE, 8, 9, FAKE, None) == 3
+    assert L.sige_conv(FAKE, 0, gp, 64, 64, FAKE, None, FAKE, 8, 9, FAKE, None, 0, None) == 3
     assert L.sige_scatter(FAKE, 0, gp, 64, FAKE, FAKE, 8, 9, None, None, 0, FAKE, 64, None) == 3
     # neither a host count nor a device count
-    assert L.sige_conv(FAKE, 0, gp, 64, 64, FAKE, None, None, 8, -1, FAKE, None) == 1
+    assert L.sige_conv(FAKE, 0, gp, 64, 64, FAKE, None, None, 8, -1, FAKE, None, 0, None) == 1
     # channel counts the vector kernels do not cover are refused, never silently handled
     assert L.sige_gather(FAKE, 0, 3, 3, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, FAKE, None) == 2
-    assert L.sige_conv(FAKE, 1, gp, 24, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
-    assert L.sige_conv(FAKE, 0, gp, 4, 64, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
+    assert L.sige_conv(FAKE, 1, gp, 24, 64, FAKE, None, FAKE, 8, -1, FAKE, None, 0, None) == 2
+    assert L.sige_conv(FAKE, 0, gp, 4, 64, FAKE, None, FAKE, 8, -1, FAKE, None, 0, None) == 2
     # fused call: exactly one destination
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
-                             FAKE, 64, FAKE, None) == 1
+                             FAKE, 64, FAKE, None, 0, None) == 1
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
-                             None, 0, None, None) == 1
+                             None, 0, None, None, 0, None) == 1
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, FAKE, None, 0,
-                             None, 0, FAKE, None) == 1       # residuals need y
+                             None, 0, FAKE, None, 0, None) == 1       # residuals need y
     assert L.sige_fused_conv(FAKE, 1, 24, 24, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
-                             FAKE, 64, None, None) == 2
+                             FAKE, 64, None, None, 0, None) == 2
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, 9, None, None, 0, 64, FAKE, None, None, None, 0,
-                             FAKE, 64, None, None) == 3
+                             FAKE, 64, None, None, 0, None) == 3
     # scale without shift
     assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, -1, FAKE, None, 0, FAKE, None) == 1
     # unknown dtype

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import assert_close, assert_mostly_close, dev, expected_tiles, f64, outside_blocks_mask
+from helpers import assert_close, assert_mostly_close, dev, expected_tiles, f64, outside_blocks_mask, round_to
 from paper_2211_02048_amd import api, inputs
 from paper_2211_02048_amd.layers import BlockList, SigeConv, Workspace
 
@@ -341,6 +341,61 @@ def test_conv_on_tiles(oracle, dtype, Cin, Cout, b, k, s, n):
         os.environ.pop("SIGE_CONV_CFG", None)
         if prev is not None:
             os.environ["SIGE_CONV_CFG"] = prev
+
+
+@pytest.mark.parametrize("dtype,Cin,Cout,res,b,k", [
+    ("f16", 512, 96, 8, 8, 3), ("bf16", 384, 136, 16, 16, 3), ("f32", 192, 32, 8, 8, 3),
+    ("f16", 384, 64, 8, 4, 1), ("f16", 512, 33, 12, 8, 3)])
+def test_conv_k_split_over_workgroups(oracle, dtype, Cin, Cout, res, b, k):
+    """Few blocks, many input channels: with a workspace the call is cut along K over several
+    workgroups and a second kernel adds the shares.  Against the oracle; the workspace is poisoned
+    (no state is assumed); three calls and the fused call agree bit for bit; residuals included."""
+    rng = np.random.default_rng(Cin + Cout + res)
+    td = DT[dtype]
+    x = torch.from_numpy(rng.standard_normal((res, res, Cin)).astype(np.float32)).to(td)
+    w, bias = inputs.conv_params(rng, Cout, Cin, k, td)
+    resid = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td)
+    conv = SigeConv(dev(w), bias, res, res, b, 1, k // 2)
+    g = conv.g
+    nb = api.sige_conv_workspace_bytes(td, g, Cin, Cout, g.grid_blocks)
+    assert nb > 0 and nb % 4 == 0, "this shape is meant to split"
+    ws = Workspace("cuda")
+    ws.get("split_k", nb // 4, torch.float32).fill_(float("nan"))
+    bl = BlockList(g, "cuda").all_active()
+    want = oracle.conv2d(f64(x), f64(w), f64(bias), 1, k // 2)
+    three_calls = Cout % 8 == 0      # the scatter call needs 16-byte channel runs; the fused call does not
+    for device_count in (False, True):
+        bl.n_host = -1 if device_count else g.grid_blocks
+        y_f = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+        conv.forward(dev(x), y_f, bl, ws, residual=dev(resid), fused=True)
+        if three_calls:
+            y = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+            conv.forward(dev(x), y, bl, ws, residual=dev(resid))
+            assert torch.equal(y, y_f), "fused call differs from gather + conv + scatter under a K split"
+        # the convolution result is a stored tensor (rounded once) before the residual is added
+        assert_close(y_f, round_to(want, td) + f64(resid), td, "k-split + residual")
+    # without a workspace: the unsplit kernel; same values up to the rounding order of the fp32 sum
+    y_n = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+    conv.forward(dev(x), y_n, bl, ws, split_k=False, fused=True)
+    y_s = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+    conv.forward(dev(x), y_s, bl, ws, fused=True)
+    assert_close(y_n, want, td, "unsplit")
+    assert_close(y_s, want, td, "k-split")
+    # a partial list: only some blocks active, the rest of y untouched
+    if g.grid_blocks >= 2:
+        blp = BlockList(g, "cuda")
+        m = np.zeros((res, res), np.uint8)
+        m[0, 0] = 1
+        blp.reduce(mask_in=torch.from_numpy(m).cuda())
+        n = blp.sync_count()
+        assert 0 < n < g.grid_blocks
+        cache = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td)
+        y = dev(cache).clone()
+        conv.forward(dev(x), y, blp, ws, fused=not three_calls)
+        blocks = blp.indices[:n].cpu().numpy()
+        assert_close(y, oracle.select_blocks(want, f64(cache), blocks, b, b), td, "k-split sparse")
+        out = torch.from_numpy(outside_blocks_mask(blocks, b, b, res, res)).cuda()
+        assert torch.equal(y[out], dev(cache)[out])
 
 
 # ------------------------------------------------------------------ the whole layer
