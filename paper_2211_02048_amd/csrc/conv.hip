@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
     packed[i] = o < Cout ? w[(((long)o * Cin + c) * k + ky) * k + kx] : from_f32<T>(0.0f);
 }
 
-// TM x TN: 32x32 MFMA tiles per wave; WM x WN x WK = 4 waves over M, N and K (waves that split K
+// TM x TN: 32x32 MFMA tiles per wave; WM x WN x WK = 4 (or 8) waves over M, N and K (waves that split K
 // take different channel ranges of every tap and are summed through LDS at the end); KC = K steps
 // per staged channel chunk; KK = k*k when it is 9 or 1 (taps unrolled), 0 for any other kernel size.  Weight fragments are fetched into a register ring several taps ahead
 // of the MFMAs that use them (deepest for the K-split shape, whose layers are weight-bound).
@@ -172,12 +172,22 @@ __device__ __forceinline__ bool emit_vec_ok(const ConvArgs& a, bool fused)
              (!a.res_full || (a.res_ld % N == 0 && aligned16_dev(a.res_full)))));
 }
 
+// Largest divisor of the number of steps that does not exceed the limit.
+constexpr int ring_depth(int steps, int limit)
+{
+    int d = 1;
+    for (int i = 1; i <= limit && i <= steps; ++i)
+        if (steps % i == 0) d = i;
+    return d;
+}
+
 constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks in a 256-row patch)
 
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
-__global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
+__global__ __launch_bounds__(64 * WM * WN * WK) void conv_kernel(ConvArgs a)
 {
-    static_assert(WM * WN * WK == 4, "four waves per workgroup");
+    constexpr int NT = 64 * WM * WN * WK;                     // threads per workgroup
+    static_assert(NT == 256 || NT == 512, "four or eight waves per workgroup");
     static_assert(KC % WK == 0, "waves that split K take whole K steps");
     constexpr int KS = Mma<T>::KSTEP;
     constexpr int S = (int)sizeof(T);
@@ -252,31 +262,32 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     const int npix = a.G * a.trows * a.tw;
     constexpr int VPC = KC * KS * S / 16;                     // 16-byte vectors per staged pixel
 
-    // Weight fragments run P taps ahead of the MFMAs in a register ring.  The taps of one channel
-    // chunk are unrolled into straight-line code (KK = k*k known at compile time), so every ring
-    // slot is a fixed register and the hardware's in-order load counter lets the oldest slot be
-    // awaited while the younger loads stay in flight.  P divides KK; a prefetch that would run past
-    // the last chunk re-reads the last chunk instead of branching.
-    constexpr int P = KK == 0 ? 1 : (KW * TN <= 2 ? KK : (KW * TN <= 8 && KK % 3 == 0) ? 3 : 1);
+    // Weight fragments run D steps ahead of the MFMAs in a register ring (a step = one K step of one
+    // tap: TM x TN MFMAs).  The steps of one channel chunk are unrolled into straight-line code (KK =
+    // k*k known at compile time), so every ring slot is a fixed register and the hardware's in-order
+    // load counter lets the oldest slot be awaited while the younger loads stay in flight.  D divides
+    // the steps of a chunk; a prefetch that would run past the last chunk re-reads the last chunk
+    // instead of branching.  Small rings for the big shapes (registers), the whole chunk for the
+    // K-split shape, whose calls are latency bound.
+    constexpr int STEPS = KK > 0 ? KK * KW : 1;
+    constexpr int D = KK == 0 ? 1 : ring_depth(STEPS, TN == 1 ? 18 : 8);
     const int nch = a.Cin / (KC * KS);
     const int ch0 = split * nch / a.ksplit, ch1 = (split + 1) * nch / a.ksplit;   // this workgroup's chunks
     const int ntaps = KK ? KK : kk;
-    uint4 bq[P][KW][TN];
-    auto fetch = [&](uint4 (&slot)[KW][TN], int chunk, int tp) {
+    uint4 ring[D][TN];
+    auto fetch = [&](uint4 (&slot)[TN], int chunk, int tp, int kc) {
         chunk = min(chunk, nch - 1);
 #pragma unroll
-        for (int kc = 0; kc < KW; ++kc)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) slot[kc][tn] = wp[tn][((long)tp * kcs + chunk * KC + kc) * 64];
+        for (int tn = 0; tn < TN; ++tn) slot[tn] = wp[tn][((long)tp * kcs + chunk * KC + kc) * 64];
     };
     const bool fused = a.x != nullptr;
     const bool fuse_math = fused && (a.scale != nullptr || a.act != SIGE_ACT_NONE);
-    // Staging of one channel chunk.  256 is a multiple of VPC, so a thread keeps one 16-byte channel
-    // group and walks over the pixels 256 / VPC at a time without dividing.  Each batch of U vectors
+    // Staging of one channel chunk.  NT is a multiple of VPC, so a thread keeps one 16-byte channel
+    // group and walks over the pixels NT / VPC at a time without dividing.  Each batch of U vectors
     // is loaded before any of them is used (addresses are clamped into the source, so the loads are
     // unconditional and overlap; what lies outside becomes zero afterwards).
     constexpr int U = TM * TN <= 2 ? 8 : 4;
-    constexpr int PPI = 256 / VPC;                            // pixels covered by one step of the walk
+    constexpr int PPI = NT / VPC;                             // pixels covered by one step of the walk
     const int sv = tid % VPC;
     int sq0 = tid / VPC, sg0, sr0, sx0;                       // first pixel of this thread: index, block, row, column
     {
@@ -329,62 +340,65 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (q + u * PPI >= npix) break;
-                uint4 w = make_uint4(0, 0, 0, 0);   // padding and inactive rows stay literally zero
-                if (ok[u]) {
-                    w = val[u];
-                    if (fuse_math) {
-                        float f[N];
-                        unpack<T>(w, f);
-                        scale_shift_act<N>(f, sc, sh, a.act);
-                        w = pack<T>(f);
-                    }
+                // computed for every vector, selected afterwards: no branch between the vectors of a
+                // batch, so their chains interleave; padding and inactive rows stay literally zero
+                uint4 w = val[u];
+                if (fuse_math) {
+                    float f[N];
+                    unpack<T>(w, f);
+                    scale_shift_act<N>(f, sc, sh, a.act);
+                    w = pack<T>(f);
                 }
+                if (!ok[u]) w = make_uint4(0, 0, 0, 0);
                 *(uint4*)(lds + (q + u * PPI) * a.ps + sv * 16) = w;
             }
             q += U * PPI;
         }
         __syncthreads();
     };
-    auto multiply = [&](const uint4 (&b)[KW][TN], int tp) {
+    auto load_a = [&](uint4 (&af)[TM], int tp, int kc) {
         const int ky = tp / a.k, kx = tp - ky * a.k;
-        const int tap_off = (ky * a.tw + kx) * a.ps;
+        const int off = (ky * a.tw + kx) * a.ps + kc * (KS * S);
 #pragma unroll
-        for (int kc = 0; kc < KW; ++kc) {
-            uint4 af[TM];
+        for (int tm = 0; tm < TM; ++tm) af[tm] = *(const uint4*)(lds + a_base[tm] + off);
+    };
+    auto multiply = [&](const uint4 (&af)[TM], const uint4 (&b)[TN]) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                af[tm] = *(const uint4*)(lds + a_base[tm] + tap_off + kc * (KS * S));
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], b[kc][tn], acc[tm][tn]);
-        }
+            for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], b[tn], acc[tm][tn]);
     };
 
     if constexpr (KK > 0) {
 #pragma unroll
-        for (int p = 0; p < P; ++p) fetch(bq[p], ch0, p);
+        for (int d = 0; d < D; ++d) fetch(ring[d], ch0, d / KW, d % KW);
         for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
+            uint4 af[2][TM];                                  // this step's rows and the next step's
+            load_a(af[0], 0, 0);
 #pragma unroll
-            for (int tp = 0; tp < KK; ++tp) {
-                uint4 bc[KW][TN];
-#pragma unroll
-                for (int kc = 0; kc < KW; ++kc)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) bc[kc][tn] = bq[tp % P][kc][tn];
-                fetch(bq[tp % P], tp + P < KK ? chunk : chunk + 1, (tp + P) % KK);
-                multiply(bc, tp);
+            for (int st = 0; st < STEPS; ++st) {
+                if (st + 1 < STEPS) load_a(af[(st + 1) & 1], (st + 1) / KW, (st + 1) % KW);
+                multiply(af[st & 1], ring[st % D]);
+                const int nx = (st + D) % STEPS;              // the step that takes over this slot
+                fetch(ring[st % D], st + D < STEPS ? chunk : chunk + 1, nx / KW, nx % KW);
+                // nothing moves across a step boundary: left alone, the scheduler sinks every prefetch
+                // down to its first use to save registers and the ring collapses
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     } else {
         for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
 #pragma nounroll
-            for (int tp = 0; tp < ntaps; ++tp) {
-                fetch(bq[0], chunk, tp);
-                multiply(bq[0], tp);
-            }
+            for (int tp = 0; tp < ntaps; ++tp)
+#pragma unroll
+                for (int kc = 0; kc < KW; ++kc) {
+                    uint4 af[TM];
+                    fetch(ring[0], chunk, tp, kc);
+                    load_a(af, tp, kc);
+                    multiply(af, ring[0]);
+                }
         }
     }
 
@@ -395,51 +409,53 @@ __global__ __launch_bounds__(256) void conv_kernel(ConvArgs a)
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int RS = BN + 4;                                // fp32 row stride: pad keeps 16-byte alignment
     float* red = reinterpret_cast<float*>(lds);               // [WK][BM][RS]
-    __syncthreads();
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                const int nn = (wn * TN + tn) * 32 + l32;
-                red[(wk * BM + m) * RS + nn] = acc[tm][tn][r] + bias_v[tn];
-            }
-    __syncthreads();
     const bool vec_ok = emit_vec_ok<T>(a, fused);
     const bool to_y = fused && a.y != nullptr;
-    for (int e = tid; e < BM * (BN / N); e += 256) {
-        const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
-        const int o = blockIdx.x * BN + nn;
-        const int g = m / pb, p = m - g * pb;
-        const int py = p / a.bw, px = p - py * a.bw;
-        if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
-        float v[N];
+    {
+        __syncthreads();
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            v[i] = 0.0f;
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int w = 0; w < WK; ++w) v[i] += red[(w * BM + m) * RS + nn + i];
-        }
-        const long t = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o;
-        if (a.partial != nullptr) {          // this workgroup's share of K, unrounded, for the reduction kernel
-            float* __restrict__ dst = a.partial + split * a.partial_stride + t;
-            if ((a.Cout & 3) == 0 && o + N <= a.Cout) {
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                for (int i = 0; i < N; i += 4) *(float4*)(dst + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
-            } else {
-                for (int i = 0; i < N && o + i < a.Cout; ++i) dst[i] = v[i];
+                for (int r = 0; r < 16; ++r) {
+                    const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int nn = (wn * TN + tn) * 32 + l32;
+                    red[(wk * BM + m) * RS + nn] = acc[tm][tn][r] + bias_v[tn];
+                }
+        __syncthreads();
+        for (int e = tid; e < BM * (BN / N); e += NT) {
+            const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;   // row of the workgroup's patch
+            const int o = blockIdx.x * BN + nn;
+            const int g = m / pb, p = m - g * pb;
+            const int py = p / a.bw, px = p - py * a.bw;
+            if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
+            float v[N];
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                v[i] = 0.0f;
+#pragma unroll
+                for (int w = 0; w < WK; ++w) v[i] += red[(w * BM + m) * RS + nn + i];
             }
-            continue;
+            const long t = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout + o;
+            if (a.partial != nullptr) {      // this workgroup's share of K, unrounded, for the reduction kernel
+                float* __restrict__ dst = a.partial + split * a.partial_stride + t;
+                if ((a.Cout & 3) == 0 && o + N <= a.Cout) {
+#pragma unroll
+                    for (int i = 0; i < N; i += 4) *(float4*)(dst + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+                } else {
+                    for (int i = 0; i < N && o + i < a.Cout; ++i) dst[i] = v[i];
+                }
+                continue;
+            }
+            long pix = 0;
+            if (to_y) {
+                const int oy = org[2 * g] + band_row0 + py, ox = org[2 * g + 1] + px;
+                if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) continue;
+                pix = (long)oy * a.Wout + ox;
+            }
+            emit_run<T>(a, to_y, vec_ok, t, pix, o, v);
         }
-        long pix = 0;
-        if (to_y) {
-            const int oy = org[2 * g] + band_row0 + py, ox = org[2 * g + 1] + px;
-            if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) continue;
-            pix = (long)oy * a.Wout + ox;
-        }
-        emit_run<T>(a, to_y, vec_ok, t, pix, o, v);
     }
 }
 
@@ -517,7 +533,8 @@ struct ConvPlan {
 
 // M x N per workgroup and whether the four waves split K
 struct CfgShape { int M, N, WK; };
-static const CfgShape kCfg[4] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}};
+constexpr int kNumCfg = 4;
+static const CfgShape kCfg[kNumCfg] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}};
 
 // Chooses the workgroup shape and the staged channel chunk for one call, then - when the caller
 // gave a workspace (partial_elems = fp32 elements it holds) and the call has few workgroups but a
@@ -535,7 +552,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     auto lds_fits = [&](int cfg, size_t lds, int kc) {
         return lds <= (kc == 1 || (kc == 4 && kCfg[cfg].WK == 4) ? 160u : 80u) * 1024u;
     };
-    for (int cfg = 0; cfg < 4; ++cfg) {
+    for (int cfg = 0; cfg < kNumCfg; ++cfg) {
         if (force && atoi(force) != cfg) continue;
         if (g->k != 1 && g->k != 3 && cfg != 2) continue;   // only the plain 64x64 shape is built for other k
         const int M = kCfg[cfg].M, Nn = kCfg[cfg].N, WK = kCfg[cfg].WK;
@@ -616,7 +633,7 @@ static int launch_cfg(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
         SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_conv: cannot reserve %zu bytes of LDS: %s", p.lds,
                      hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(kern, dim3(p.slabs, p.bands * p.ksplit, p.groups), dim3(256), p.lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(p.slabs, p.bands * p.ksplit, p.groups), dim3(64 * WM * WN * WK), p.lds, st, a);
     SIGE_LAUNCH_CHECK("sige_conv");
     return SIGE_OK;
 }

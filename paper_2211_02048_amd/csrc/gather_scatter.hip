@@ -145,17 +145,54 @@ __global__ __launch_bounds__(256) void scatter_kernel(ScatterArgs a)
         dst[pix * a.y_ld_vec + cg] = v;
     };
     if (256 % a.V == 0) {
-        // division-free walk: a thread keeps its channel group, 256 / V pixels further each time
+        // division-free walk: a thread keeps its channel group, 256 / V pixels further each time;
+        // the tile vectors (and residuals) of U pixels are loaded before any is stored
+        constexpr int U = 4;
         const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
         const int step_r = ppi / cols, step_x = ppi - step_r * cols;
         int p = threadIdx.x / a.V;
         int r = p / cols, px = p - r * cols;
         const int nrows = r1 - r0;
         while (r < nrows) {
-            move(r, px, cg);
-            px += step_x;
-            r += step_r;
-            if (px >= cols) { px -= cols; ++r; }
+            uint4 v[U], q1[U], q2[U];
+            long pix[U];
+            bool in[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                in[u] = r < nrows;
+                const int rr = in[u] ? r : 0, pp = in[u] ? px : 0;     // a valid element when past the end
+                const long t = (((long)n * a.bh + r0 + rr) * a.bw + pp) * a.V + cg;
+                pix[u] = (long)(y0 + r0 + rr) * a.Wout + x0 + pp;
+                v[u] = src[t];
+                if (ADD) {
+                    if (rt) q1[u] = rt[t];
+                    if (rf) q2[u] = rf[pix[u] * a.res_ld_vec + cg];
+                }
+                px += step_x;
+                r += step_r;
+                if (px >= cols) { px -= cols; ++r; }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (!in[u]) break;
+                uint4 w = v[u];
+                if (ADD) {
+                    float f[N], g[N];
+                    unpack<T>(w, f);
+                    if (rt) {
+                        unpack<T>(q1[u], g);
+#pragma unroll
+                        for (int i = 0; i < N; ++i) f[i] += g[i];
+                    }
+                    if (rf) {
+                        unpack<T>(q2[u], g);
+#pragma unroll
+                        for (int i = 0; i < N; ++i) f[i] += g[i];
+                    }
+                    w = pack<T>(f);
+                }
+                dst[pix[u] * a.y_ld_vec + cg] = w;
+            }
         }
     } else {
         for (int j = threadIdx.x; j < total; j += 256) {
