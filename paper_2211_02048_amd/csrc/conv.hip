@@ -10,6 +10,8 @@
 // sige_pack_weight has laid out in fragment order (L2 resident, shared by every
 // workgroup).  fp32 accumulation, bias as the accumulator's start value, one
 // rounding to the storage type at the store.
+#include <type_traits>
+
 #include "common.h"
 
 #include <stdlib.h>
@@ -184,7 +186,7 @@ constexpr int ring_depth(int steps, int limit)
 constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks in a 256-row patch)
 
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
-__global__ __launch_bounds__(64 * WM * WN * WK) void conv_kernel(ConvArgs a)
+__global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
 {
     constexpr int NT = 64 * WM * WN * WK;                     // threads per workgroup
     static_assert(NT == 256 || NT == 512, "four or eight waves per workgroup");
@@ -286,23 +288,33 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_kernel(ConvArgs a)
     // group and walks over the pixels NT / VPC at a time without dividing.  Each batch of U vectors
     // is loaded before any of them is used (addresses are clamped into the source, so the loads are
     // unconditional and overlap; what lies outside becomes zero afterwards).
-    constexpr int U = TM * TN <= 2 ? 8 : 4;
+    constexpr int U = TM * TN >= 4 ? 6 : 8;                   // fewer where the accumulators leave fewer registers
     constexpr int PPI = NT / VPC;                             // pixels covered by one step of the walk
     const int sv = tid % VPC;
     int sq0 = tid / VPC, sg0, sr0, sx0;                       // first pixel of this thread: index, block, row, column
+    int step_g, step_r, step_x;                               // PPI pixels further, in the same mixed radix
     {
         const int per = a.trows * a.tw;
         sg0 = sq0 / per;
-        const int rem = sq0 - sg0 * per;
+        int rem = sq0 - sg0 * per;
         sr0 = rem / a.tw;
         sx0 = rem - sr0 * a.tw;
+        step_g = PPI / per;
+        rem = PPI - step_g * per;
+        step_r = rem / a.tw;
+        step_x = rem - step_r * a.tw;
     }
-    auto stage = [&](int chunk) {
+    const int Ws = a.Win >> a.up;
+    const int rmax = a.th - 1 - trow0;                        // last staged row that exists in the tile
+    // FUSED: gather from x instead of reading stored tiles; SINGLE: one block per workgroup, whose
+    // origin is then fixed.  Both are decided once per call, outside the per-vector code.
+    auto stage_as = [&](int chunk, auto fused_c, auto single_c) {
+        constexpr bool FUSED = decltype(fused_c)::value, SINGLE = decltype(single_c)::value;
         constexpr int N = Vec16<T>::N;
         const int c0 = chunk * (KC * KS);
         if (chunk != ch0) __syncthreads();
         float sc[N], sh[N];
-        if (fuse_math) {
+        if (FUSED && fuse_math) {
             const int cbase = c0 + sv * N;
 #pragma unroll
             for (int i = 0; i < N; ++i) {
@@ -310,32 +322,47 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_kernel(ConvArgs a)
                 sh[i] = a.scale ? a.shift[cbase + i] : 0.0f;
             }
         }
+        // this thread's 16 bytes of pixel 0 of the source; pixels are then a 32-bit index away
+        const char* const src0 = (FUSED ? (const char*)a.x : tiles) + (long)c0 * S + sv * 16;
+        const int px_bytes = (FUSED ? a.x_ld : a.Cin) * S;
         int q = sq0, g = sg0, r = sr0, x = sx0;
-        const int Ws = a.Win >> a.up;
+        int gc = -1, oyb = 0, oxb = 0, tb = 0;                 // block the cached origin belongs to
+        auto origin = [&](int gg) {
+            gc = gg;
+            if (FUSED) {
+                const int gl = min(gg, a.G - 1);
+                oyb = org[2 * gl] * a.stride - a.pad + trow0;
+                oxb = org[2 * gl + 1] * a.stride - a.pad;
+            } else {
+                tb = (min(g0 + gg, n_eff - 1) * a.th + trow0) * a.tw;
+            }
+        };
+        if (SINGLE) origin(0);
         while (q < npix) {
             uint4 val[U];
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const bool in = q + u * PPI < npix;
-                const int gb = min(g0 + g, n_eff - 1), tr = min(trow0 + r, a.th - 1);
-                ok[u] = in && g0 + g < n_eff && trow0 + r < a.th;
-                const char* src;
-                if (!fused) {
-                    src = tiles + ((((long)gb * a.th + tr) * a.tw + x) * a.Cin + c0) * S + sv * 16;
+                if (!SINGLE && g != gc) origin(g);
+                ok[u] = q + u * PPI < npix && r <= rmax && (SINGLE || g0 + g < n_eff);
+                const int rr = min(r, rmax);
+                int pix;
+                if (!FUSED) {
+                    pix = tb + rr * a.tw + x;
                 } else {
                     // the gather: input pixel of tile position (trow0 + r, x) of block g0 + g
-                    const int gl = min(g, a.G - 1);
-                    const int iy = org[2 * gl] * a.stride - a.pad + tr;
-                    const int ix = org[2 * gl + 1] * a.stride - a.pad + x;
+                    const int iy = oyb + rr, ix = oxb + x;
                     ok[u] = ok[u] && iy >= 0 && iy < a.Hin && ix >= 0 && ix < a.Win;
-                    const int cy = min(max(iy, 0), a.Hin - 1) >> a.up, cx = min(max(ix, 0), a.Win - 1) >> a.up;
-                    src = (const char*)a.x + (((long)cy * Ws + cx) * a.x_ld + c0) * S + sv * 16;
+                    pix = (min(max(iy, 0), a.Hin - 1) >> a.up) * Ws + (min(max(ix, 0), a.Win - 1) >> a.up);
                 }
-                val[u] = *(const uint4*)src;
-                x += PPI;
-                while (x >= a.tw) { x -= a.tw; ++r; }
-                while (r >= a.trows) { r -= a.trows; ++g; }
+                val[u] = *(const uint4*)(src0 + (long)pix * px_bytes);
+                x += step_x;
+                r += step_r;
+                if (x >= a.tw) { x -= a.tw; ++r; }
+                if (!SINGLE) {
+                    g += step_g;
+                    if (r >= a.trows) { r -= a.trows; ++g; }
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -343,7 +370,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_kernel(ConvArgs a)
                 // computed for every vector, selected afterwards: no branch between the vectors of a
                 // batch, so their chains interleave; padding and inactive rows stay literally zero
                 uint4 w = val[u];
-                if (fuse_math) {
+                if (FUSED && fuse_math) {
                     float f[N];
                     unpack<T>(w, f);
                     scale_shift_act<N>(f, sc, sh, a.act);
@@ -355,6 +382,17 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void conv_kernel(ConvArgs a)
             q += U * PPI;
         }
         __syncthreads();
+    };
+    auto stage = [&](int chunk) {
+        using yes = std::true_type;
+        using no = std::false_type;
+        if (fused) {
+            if (a.G == 1) stage_as(chunk, yes{}, yes{});
+            else stage_as(chunk, yes{}, no{});
+        } else {
+            if (a.G == 1) stage_as(chunk, no{}, yes{});
+            else stage_as(chunk, no{}, no{});
+        }
     };
     auto load_a = [&](uint4 (&af)[TM], int tp, int kc) {
         const int ky = tp / a.k, kx = tp - ky * a.k;
