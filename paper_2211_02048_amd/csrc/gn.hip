@@ -17,46 +17,100 @@ __global__ void gn_zero_kernel(float* mean, float* var, int groups)
     if (i < groups) { mean[i] = 0.0f; var[i] = 0.0f; }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void gn_sum_kernel(const uint4* __restrict__ x, long n_pix, int V,
-                                                     int ld_vec, int cg, int groups,
-                                                     float* __restrict__ sum, float* __restrict__ sumsq)
+// Adds one lane's per-channel sums (channels cgv*N .. cgv*N+N-1) to the per-group sums in LDS,
+// combining the channels of one group in registers first where the group size allows.
+template <int N>
+__device__ __forceinline__ void add_to_groups(float* red, int groups, int cgv, int cg, const float (&s)[N],
+                                              const float (&q)[N])
 {
-    constexpr int N = Vec16<T>::N;
-    extern __shared__ float red[];  // [2][groups]
-    for (int i = threadIdx.x; i < 2 * groups; i += 256) red[i] = 0.0f;
-    __syncthreads();
-    const bool fixed = (256 % V) == 0;
-    if (fixed) {
-        const int cgv = threadIdx.x % V, ppi = 256 / V;  // pixels per workgroup step
-        float s[N], q[N];
+    if (cg % N == 0) {                       // the vector lies inside one group
+        float st = 0.0f, qt = 0.0f;
 #pragma unroll
-        for (int i = 0; i < N; ++i) { s[i] = 0.0f; q[i] = 0.0f; }
-        for (long p = (long)blockIdx.x * ppi + threadIdx.x / V; p < n_pix; p += (long)gridDim.x * ppi) {
-            float f[N];
-            unpack<T>(x[p * ld_vec + cgv], f);
+        for (int i = 0; i < N; ++i) { st += s[i]; qt += q[i]; }
+        const int g = cgv * N / cg;
+        atomicAdd(&red[g], st);
+        atomicAdd(&red[groups + g], qt);
+    } else if (N % cg == 0) {                // the vector holds N / cg whole groups
+        float st = 0.0f, qt = 0.0f;
 #pragma unroll
-            for (int i = 0; i < N; ++i) { s[i] += f[i]; q[i] = fmaf(f[i], f[i], q[i]); }
+        for (int i = 0; i < N; ++i) {
+            st += s[i];
+            qt += q[i];
+            if ((i + 1) % cg == 0) {
+                const int g = (cgv * N + i) / cg;
+                atomicAdd(&red[g], st);
+                atomicAdd(&red[groups + g], qt);
+                st = 0.0f;
+                qt = 0.0f;
+            }
         }
+    } else {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int g = (cgv * N + i) / cg;
             atomicAdd(&red[g], s[i]);
             atomicAdd(&red[groups + g], q[i]);
         }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gn_sum_kernel(const uint4* __restrict__ x, long n_pix, int V,
+                                                     int ld_vec, int cg, int groups,
+                                                     float* __restrict__ sum, float* __restrict__ sumsq)
+{
+    constexpr int N = Vec16<T>::N;
+    constexpr int U = 4;            // loads in flight per lane
+    extern __shared__ float red[];  // [2][groups]
+    for (int i = threadIdx.x; i < 2 * groups; i += 256) red[i] = 0.0f;
+    __syncthreads();
+    // Up to 256 vectors per pixel: the first (256 / V) * V threads each keep one channel group and
+    // walk down the pixels (the rest idle, none when V divides 256).
+    if (V <= 256) {
+        const int cgv = threadIdx.x % V, ppi = 256 / V;  // pixels per workgroup step
+        const bool active = threadIdx.x < ppi * V;
+        float s[N], q[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) { s[i] = 0.0f; q[i] = 0.0f; }
+        const long stride = (long)gridDim.x * ppi;
+        for (long p = (long)blockIdx.x * ppi + threadIdx.x / V; active && p < n_pix; p += U * stride) {
+            uint4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long pp = p + u * stride;
+                v[u] = pp < n_pix ? x[pp * ld_vec + cgv] : make_uint4(0, 0, 0, 0);   // zeros add nothing
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float f[N];
+                unpack<T>(v[u], f);
+#pragma unroll
+                for (int i = 0; i < N; ++i) { s[i] += f[i]; q[i] = fmaf(f[i], f[i], q[i]); }
+            }
+        }
+        // lanes of a wave that hold the same channel group are V apart: when V is a power of two below
+        // 64, fold them onto the first V lanes, which then add to LDS
+        if (V < 64 && (V & (V - 1)) == 0) {
+            for (int off = V; off < 64; off <<= 1)
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    s[i] += __shfl_xor(s[i], off);
+                    q[i] += __shfl_xor(q[i], off);
+                }
+            if ((threadIdx.x & 63) < V) add_to_groups<N>(red, groups, cgv, cg, s, q);
+        } else if (active) {
+            add_to_groups<N>(red, groups, cgv, cg, s, q);
+        }
     } else {
         const long n_vec = n_pix * V;
         for (long j = (long)blockIdx.x * 256 + threadIdx.x; j < n_vec; j += (long)gridDim.x * 256) {
             const long p = j / V;
             const int cgv = (int)(j - p * V);
-            float f[N];
+            float f[N], q[N];
             unpack<T>(x[p * ld_vec + cgv], f);
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int g = (cgv * N + i) / cg;
-                atomicAdd(&red[g], f[i]);
-                atomicAdd(&red[groups + g], f[i] * f[i]);
-            }
+            for (int i = 0; i < N; ++i) q[i] = f[i] * f[i];
+            add_to_groups<N>(red, groups, cgv, cg, f, q);
         }
     }
     __syncthreads();
@@ -93,8 +147,10 @@ template <typename T>
 static void launch_sum(const void* x, long n_pix, int V, int ld_vec, int cg, int groups, float* mean,
                        float* var, hipStream_t st)
 {
+    // at most two workgroups per compute unit: every workgroup ends with one atomic per group and
+    // statistic on the same few addresses, and each lane keeps four loads in flight
     long want = (n_pix * V + 256L * 8 - 1) / (256L * 8);
-    int grid = (int)(want < 1 ? 1 : want > 2048 ? 2048 : want);
+    int grid = (int)(want < 1 ? 1 : want > 512 ? 512 : want);
     hipLaunchKernelGGL((gn_sum_kernel<T>), dim3(grid), dim3(256), 2 * groups * sizeof(float), st,
                        (const uint4*)x, n_pix, V, ld_vec, cg, groups, mean, var);
 }
