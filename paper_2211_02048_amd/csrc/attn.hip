@@ -2,7 +2,10 @@
 // keys and values (Sec. 3.2 "Extension to attention layers", Fig. "sige-attention"):
 // the attention map is Nq x T instead of T x T.
 //
-// One wave owns 32 queries of one head and streams the keys in chunks of 32.  All
+// One wave owns 32 queries of one head and streams the keys in chunks of 32 * KT
+// (64 keys for head sizes up to 96, 32 beyond; small heads keep two waves per SIMD resident);
+// the next chunk's K and V rows travel from HBM to registers while the current one is
+// multiplied.  All
 // products run transposed so that everything belonging to a query stays in one lane
 // (pair): S^T = K Q^T leaves a query's 32 logits in the registers of lanes l and
 // l+32, the online softmax needs a single cross-lane exchange, the probabilities
@@ -51,13 +54,18 @@ struct AttnArgs {
     float scale_log2e;
 };
 
-constexpr int KCH = 32;          // keys per chunk
-constexpr int VT_STRIDE = 72;    // bytes per row of the transposed V chunk (32 keys * 2 B + 8 pad)
+// 32-key tiles per chunk, by head size (DT = 32-wide tiles over d)
+constexpr int key_tiles(int DT) { return DT <= 3 ? 2 : 1; }
+static int keys_per_chunk(int d) { return 32 * key_tiles((d + 31) / 32); }
 
 template <typename T, int DT>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
+__global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
 {
-    constexpr int DKMAX = 2 * DT;  // 16-wide steps over d for S^T
+    constexpr int KT = key_tiles(DT);
+    constexpr int KCH = 32 * KT;                   // keys per chunk
+    constexpr int VT_STRIDE = KCH * 2 + 8;         // bytes per row of the transposed V chunk (pad 8)
+    constexpr int DKMAX = 2 * DT;                  // 16-wide steps over d for S^T
+    constexpr int NV = (KT * DT + 1) / 2;          // K (and V) vectors a thread stages per chunk, at most
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
     const int d = a.d;
@@ -90,6 +98,48 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
     for (int j = tid; j < (DT * 32 - d) * (VT_STRIDE / 4); j += 256)
         *(uint32_t*)(vt + d * VT_STRIDE + j * 4) = 0u;
 
+    // The vectors of a chunk this thread stages: (key, 16-byte group of d), the same for every chunk.
+    int skey[NV], sdv[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int j = tid + u * 256;
+        skey[u] = j < KCH * dvec ? j / dvec : -1;
+        sdv[u] = j < KCH * dvec ? j - skey[u] * dvec : 0;
+    }
+    uint4 kreg[NV], vreg[NV];
+    // HBM -> registers; keys past the end read the last key's row (a valid address) and are zeroed
+    // when they are written to LDS
+    auto fetch = [&](int c) {
+        const int t0 = c * KCH;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            if (skey[u] < 0) continue;
+            const long off = ((long)min(t0 + skey[u], a.T - 1) * a.kv_ld + head * d + sdv[u] * 8) * 2;
+            kreg[u] = *(const uint4*)((const char*)a.k + off);
+            vreg[u] = *(const uint4*)((const char*)a.v + off);
+        }
+    };
+    // registers -> LDS: K rows as they are, V transposed
+    auto commit = [&](int c) {
+        const int t0 = c * KCH;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            if (skey[u] < 0) continue;
+            const int key = skey[u], dv = sdv[u];
+            const bool in = t0 + key < a.T;
+            const uint4 kv = in ? kreg[u] : make_uint4(0, 0, 0, 0);
+            const uint4 vv = in ? vreg[u] : make_uint4(0, 0, 0, 0);
+            *(uint4*)(ks + key * k_stride + dv * 16) = kv;
+            // element e of this vector is row dv*8+e of V^T; the index of the 4-key group is swizzled
+            // by dv in its low three bits
+            const int col = ((((key >> 2) ^ (dv & 7)) << 2) | (key & 3)) * 2;
+            union { uint4 u4; uint16_t h[8]; } x;
+            x.u4 = vv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) *(uint16_t*)(vt + (dv * 8 + e) * VT_STRIDE + col) = x.h[e];
+        }
+    };
+
     f32x16 oacc[DT];
 #pragma unroll
     for (int nt = 0; nt < DT; ++nt)
@@ -97,58 +147,51 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
         for (int r = 0; r < 16; ++r) oacc[nt][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
+    if (c_begin < c_end) fetch(c_begin);
     for (int c = c_begin; c < c_end; ++c) {
         const int t0 = c * KCH;
         __syncthreads();  // previous chunk fully consumed
-        for (int j = tid; j < KCH * dvec; j += 256) {
-            const int key = j / dvec, dv = j - key * dvec;
-            uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
-            if (t0 + key < a.T) {
-                const long off = ((long)(t0 + key) * a.kv_ld + head * d + dv * 8) * 2;
-                kv = *(const uint4*)((const char*)a.k + off);
-                vv = *(const uint4*)((const char*)a.v + off);
-            }
-            *(uint4*)(ks + key * k_stride + dv * 16) = kv;
-            // transpose V: element e of this vector is row dv*8+e; 4-key group index is swizzled by dv
-            const int col = ((((key >> 2) ^ (dv & 7)) << 2) | (key & 3)) * 2;
-            union { uint4 u; uint16_t h[8]; } x;
-            x.u = vv;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) *(uint16_t*)(vt + (dv * 8 + e) * VT_STRIDE + col) = x.h[e];
-        }
+        commit(c);
         __syncthreads();
+        if (c + 1 < c_end) fetch(c + 1);          // in flight while this chunk is multiplied
+        __builtin_amdgcn_sched_barrier(0);        // (kept above the MFMAs: the scheduler would sink the loads)
 
-        // S^T chunk: rows = keys, cols = queries
-        f32x16 sacc;
+        // S^T chunk: rows = keys (KT tiles of 32), cols = queries
+        f32x16 sacc[KT];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
+        for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
-        for (int s = 0; s < DKMAX; ++s) {
-            if (s < dk) {
-                const int dd = 16 * s + 8 * half;
-                uint4 kf = make_uint4(0, 0, 0, 0);
-                if (dd < d) kf = *(const uint4*)(ks + l32 * k_stride + dd * 2);
-                Mma16<T>::run(kf, qf[s], sacc);
+            for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < DKMAX; ++s) {
+                if (s < dk) {
+                    const int dd = 16 * s + 8 * half;
+                    uint4 kf = make_uint4(0, 0, 0, 0);
+                    if (dd < d) kf = *(const uint4*)(ks + (kt * 32 + l32) * k_stride + dd * 2);
+                    Mma16<T>::run(kf, qf[s], sacc[kt]);
+                }
             }
         }
-        // online softmax; this lane holds keys 8*(r/4) + 4*half + r%4 of its query
+        // online softmax; of tile kt this lane holds keys 8*(r/4) + 4*half + r%4 of its query
         float mx = m_run;
-        float sv[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = t0 + 8 * (r >> 2) + 4 * half + (r & 3);
-            sv[r] = key < a.T ? sacc[r] * a.scale_log2e : -INFINITY;
-            mx = fmaxf(mx, sv[r]);
-        }
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = t0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                sacc[kt][r] = key < a.T ? sacc[kt][r] * a.scale_log2e : -INFINITY;
+                mx = fmaxf(mx, sacc[kt][r]);
+            }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float alpha = exp2f(m_run - mx);  // first chunk: exp2(-inf) = 0
         float lsum = 0.0f;
-        float pv[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            pv[r] = exp2f(sv[r] - mx);
-            lsum += pv[r];
-        }
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                sacc[kt][r] = exp2f(sacc[kt][r] - mx);
+                lsum += sacc[kt][r];
+            }
         l_run = l_run * alpha + lsum;
         m_run = mx;
 #pragma unroll
@@ -156,22 +199,24 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[nt][r] *= alpha;
 
-        // O^T += V^T P^T, two steps of 16 keys; step s uses registers 8s..8s+7
+        // O^T += V^T P^T, two steps of 16 keys per tile; step s uses registers 8s..8s+7
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            union { uint4 u; T h[8]; } pf;
+        for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf.h[e] = from_f32<T>(pv[8 * s + e]);
+            for (int s = 0; s < 2; ++s) {
+                union { uint4 u; T h[8]; } pf;
 #pragma unroll
-            for (int nt = 0; nt < DT; ++nt) {
-                const int row = nt * 32 + l32;
-                const int sw = (row >> 3) & 7;
-                const int g_lo = (4 * s + half) ^ sw, g_hi = (4 * s + 2 + half) ^ sw;
-                const uint2 lo = *(const uint2*)(vt + row * VT_STRIDE + g_lo * 8);
-                const uint2 hi = *(const uint2*)(vt + row * VT_STRIDE + g_hi * 8);
-                Mma16<T>::run(make_uint4(lo.x, lo.y, hi.x, hi.y), pf.u, oacc[nt]);
+                for (int e = 0; e < 8; ++e) pf.h[e] = from_f32<T>(sacc[kt][8 * s + e]);
+#pragma unroll
+                for (int nt = 0; nt < DT; ++nt) {
+                    const int row = nt * 32 + l32;
+                    const int sw = (row >> 3) & 7;
+                    const int g_lo = kt * 8 + ((4 * s + half) ^ sw), g_hi = kt * 8 + ((4 * s + 2 + half) ^ sw);
+                    const uint2 lo = *(const uint2*)(vt + row * VT_STRIDE + g_lo * 8);
+                    const uint2 hi = *(const uint2*)(vt + row * VT_STRIDE + g_hi * 8);
+                    Mma16<T>::run(make_uint4(lo.x, lo.y, hi.x, hi.y), pf.u, oacc[nt]);
+                }
             }
-        }
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -216,26 +261,51 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     const int dd = (int)(i % d);
     const int head = (int)((i / d) % a.heads);
     const int qi = (int)(i / ((long)d * a.heads));
-    float m = -INFINITY;
-    for (int s = 0; s < a.splits; ++s)
-        m = fmaxf(m, a.ws[(((long)s * a.heads + head) * a.Nq + qi) * (d + 2) + d]);
-    float num = 0.0f, den = 0.0f;
-    for (int s = 0; s < a.splits; ++s) {
-        const float* w = a.ws + (((long)s * a.heads + head) * a.Nq + qi) * (d + 2);
-        const float f = exp2f(w[d] - m);
-        num += w[dd] * f;
-        den += w[d + 1] * f;
+    // One pass, sixteen splits fetched at a time (their loads are independent): the running maximum
+    // rescales what has been summed so far, as inside the attention kernel; the order of the sums is
+    // that of the split index.
+    constexpr int B = 16;
+    const long sstride = (long)a.heads * a.Nq * (d + 2);
+    const float* w0 = a.ws + ((long)head * a.Nq + qi) * (d + 2);
+    float m = -INFINITY, num = 0.0f, den = 0.0f;
+    for (int s0 = 0; s0 < a.splits; s0 += B) {
+        float mx[B], val[B], dn[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const float* w = w0 + min(s0 + j, a.splits - 1) * sstride;
+            mx[j] = w[d];
+            val[j] = w[dd];
+            dn[j] = w[d + 1];
+        }
+        float mb = m;
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            if (s0 + j < a.splits) mb = fmaxf(mb, mx[j]);
+        const float r = exp2f(m - mb);       // 0 on the first batch (m = -inf), when nothing is summed yet
+        num *= r;
+        den *= r;
+        m = mb;
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            if (s0 + j >= a.splits) break;
+            const float f = exp2f(mx[j] - m);
+            num += val[j] * f;
+            den += dn[j] * f;
+        }
     }
     ((T*)a.o)[(long)qi * a.o_ld + head * d + dd] = from_f32<T>(num / den);
 }
 
-// Number of key splits: enough workgroups to fill the chip, at least 8 chunks each.
-static int pick_splits(int Nq, int T, int heads)
+// Number of key splits: a workgroup walks through its key chunks one after the other and each costs
+// a staging round trip, so few queries are spread over up to four workgroups per compute unit, at
+// least 2 chunks each.
+static int pick_splits(int Nq, int T, int heads, int d)
 {
+    const int KCH = keys_per_chunk(d);
     const long base = (long)heads * ((Nq + 127) / 128);
     const int chunks = (T + KCH - 1) / KCH;
-    long want = (512 + base - 1) / base;
-    long cap = chunks / 8;
+    long want = (1024 + base - 1) / base;
+    long cap = chunks / 2;
     if (want > cap) want = cap;
     if (want > 64) want = 64;
     if (want < 1) want = 1;
@@ -246,9 +316,16 @@ static int pick_splits(int Nq, int T, int heads)
 template <typename T, int DT>
 static int launch_attn_dt(const AttnArgs& a, hipStream_t st)
 {
-    const size_t lds = (size_t)KCH * (a.d * 2 + 16) + (size_t)DT * 32 * VT_STRIDE;
+    constexpr int KCH = 32 * key_tiles(DT);
+    const size_t lds = (size_t)KCH * (a.d * 2 + 16) + (size_t)DT * 32 * (KCH * 2 + 8);
     dim3 grid((a.Nq + 127) / 128, a.heads, a.splits);
-    hipLaunchKernelGGL((attn_kernel<T, DT>), grid, dim3(256), lds, st, a);
+    auto kern = attn_kernel<T, DT>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_sparse_attn: cannot reserve %zu bytes of LDS: %s", lds,
+                     hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
     SIGE_LAUNCH_CHECK("sige_sparse_attn");
     if (a.splits > 1) {
         const long n = (long)a.Nq * a.heads * a.d;
@@ -280,7 +357,7 @@ using namespace sige;
 extern "C" size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_t heads, int32_t d)
 {
     if (Nq <= 0 || T <= 0 || heads <= 0 || d <= 0) return 0;
-    const int splits = pick_splits(Nq, T, heads);
+    const int splits = pick_splits(Nq, T, heads, d);
     if (splits <= 1) return 0;
     return (size_t)splits * heads * Nq * (d + 2) * sizeof(float);
 }
@@ -310,8 +387,9 @@ extern "C" int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, cons
     a.q_ld = q_ld; a.kv_ld = kv_ld; a.o_ld = o_ld;
     a.Nq = Nq; a.T = T; a.heads = heads; a.d = d;
     a.scale_log2e = scale * 1.4426950408889634f;
+    const int KCH = keys_per_chunk(d);
     const int chunks = (T + KCH - 1) / KCH;
-    int splits = pick_splits(Nq, T, heads);
+    int splits = pick_splits(Nq, T, heads, d);
     if (splits > 1 && (workspace == nullptr ||
                        workspace_bytes < (size_t)splits * heads * Nq * (d + 2) * sizeof(float) ||
                        (reinterpret_cast<uintptr_t>(workspace) & 3u)))

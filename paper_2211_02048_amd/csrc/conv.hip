@@ -117,9 +117,11 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 // included), t the element's index in the stacked output tiles, pix the pixel of y it belongs to.
 // Plain mode stores the tile elements; fused mode rounds them to the storage type as a stored
 // tile would be, adds the residuals in fp32 and stores into y.
+// early != nullptr: the two residual vectors were fetched by the caller ahead of time (early[0] the
+// tile residual, early[1] the full-tensor one), for the 16-byte path only.
 template <typename T>
 __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_ok, long t, long pix, int o,
-                                         float (&v)[Vec16<T>::N])
+                                         float (&v)[Vec16<T>::N], const uint4* early = nullptr)
 {
     constexpr int N = Vec16<T>::N;
     T* __restrict__ out = (T*)a.out;
@@ -130,12 +132,12 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
                 float f[N], q[N];
                 unpack<T>(r, f);
                 if (a.res_tiles) {
-                    unpack<T>(*(const uint4*)((const T*)a.res_tiles + t), q);
+                    unpack<T>(early ? early[0] : *(const uint4*)((const T*)a.res_tiles + t), q);
 #pragma unroll
                     for (int i = 0; i < N; ++i) f[i] += q[i];
                 }
                 if (a.res_full) {
-                    unpack<T>(*(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
+                    unpack<T>(early ? early[1] : *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
 #pragma unroll
                     for (int i = 0; i < N; ++i) f[i] += q[i];
                 }
@@ -518,10 +520,28 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     else n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
     if (n >= n_eff) return;
     const long t = row * a.Cout + o;
-    float v[N];
+    long pix = 0;
+    if (to_y) {
+        const int oy = y0 + py, ox = x0 + px;
+        if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) return;
+        pix = (long)oy * a.Wout + ox;
+    }
+    // the residual vectors do not depend on the sums: fetch them first so that they travel together
+    // with the shares
+    const bool vec_ok = emit_vec_ok<T>(a, fused);
+    const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
+    uint4 early[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    if (early_ok) {
+        if (a.res_tiles) early[0] = *(const uint4*)((const T*)a.res_tiles + t);
+        if (a.res_full) early[1] = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+    }
+    float v[N], bv[N];
     const bool vec4 = (a.Cout & 3) == 0 && o + N <= a.Cout;
 #pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = 0.0f;
+    for (int i = 0; i < N; ++i) {
+        v[i] = 0.0f;
+        bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
+    }
     if (vec4) {
         // four shares are in flight at a time; they are still added in the order of the split index
         for (int s0 = 0; s0 < a.ksplit; s0 += 4) {
@@ -548,17 +568,9 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
             for (int i = 0; i < N && o + i < a.Cout; ++i) v[i] += src[i];
         }
     }
-    if (a.bias)
 #pragma unroll
-        for (int i = 0; i < N; ++i)
-            if (o + i < a.Cout) v[i] += a.bias[o + i];
-    long pix = 0;
-    if (to_y) {
-        const int oy = y0 + py, ox = x0 + px;
-        if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) return;
-        pix = (long)oy * a.Wout + ox;
-    }
-    emit_run<T>(a, to_y, emit_vec_ok<T>(a, fused), t, pix, o, v);
+    for (int i = 0; i < N; ++i) v[i] += bv[i];
+    emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok ? early : nullptr);
 }
 
 struct ConvPlan {
