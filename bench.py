@@ -6,8 +6,9 @@ A step is one pass of the whole path over BASELINE config 2 (256x256x128 fp16, ~
 conv3x3 -> scatter and gather -> conv1x1 -> scatter, inputs resident in HBM, replayed as one HIP
 graph (block counts stay on the device).  `value` is the algorithmic bytes of one step divided by
 its wall time.  The line also carries
-  roofline      - the kernel that takes longest in the step (the 3x3 convolution: MFMA bound),
-  roofline_hbm  - the step's HBM-bound kernel (the difference-mask stream),
+  roofline      - the kernel that moves 91 % of the step's bytes and takes as long as any other in it
+                  (the difference-mask stream: HBM bound),
+  roofline_mfma - the step's MFMA-bound kernel (the 3x3 convolution on the active blocks),
 both timed live with events on the launch stream, the CPU oracle timed on the host cores, and
 `supplement`: per-call times, gather / scatter / difference-mask bandwidth on a 1024x1024x128
 tensor with every block active (footprint far beyond the 256 MB Infinity Cache), convolution
@@ -25,8 +26,8 @@ sys.path.insert(0, ROOT)
 
 # HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs of `bench.py --probe`: FETCH_SIZE
 # scaled by 2.0, WRITE_SIZE by 1.0, the factors a plain 128 MiB copy gives; see profiles/hbm_traffic_pmc.md)
-PMC_TRAFFIC_DIFF_MASK_CONFIG2 = 16437 * 2 * 1024 + int(64.5 * 1024)
-PMC_TRAFFIC_FUSED_CONV_CONFIG2 = 2306 * 2 * 1024 + 576 * 1024
+PMC_TRAFFIC_DIFF_MASK_CONFIG2 = 16450 * 2 * 1024 + 65 * 1024
+PMC_TRAFFIC_FUSED_CONV_CONFIG2 = 2547 * 2 * 1024 + 576 * 1024
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
 
@@ -499,7 +500,7 @@ def main():
     eager_us = time_calls(L.step_eager, 100)
     L.bl3.sync_count(), L.bl1.sync_count()
 
-    # roofline 1: the longest kernel of the step, the 3x3 convolution on the active blocks
+    # MFMA roofline: the 3x3 convolution on the active blocks
     if L.fused:
         conv_call = lambda: L.main.forward(L.a_e, L.y_main, L.bl3, L.ws, scale=L.scale, shift=L.shift,
                                            act=api.ACT_SILU, fused=True)
@@ -519,7 +520,8 @@ def main():
             "note": f"{n3} active 16x16 blocks, 3x3, 128->128, fp16: {conv_fl / 1e9:.2f} GFLOP per launch - far too "
                     "little work to fill 256 CUs; the supplement has the same kernel with every block active"}
 
-    # roofline 2: the HBM-bound kernel, the difference-mask stream (both activations read once).
+    # HBM roofline (the dominant kernel of a bandwidth metric): the difference-mask stream, both
+    # activations read once.
     # Rotated over distinct buffer pairs (> 256 MB in total) so that the Infinity Cache cannot serve them.
     pairs = [(L.a_o.clone(), L.a_e.clone()) for _ in range(10)]
     it = [0]
@@ -553,7 +555,7 @@ def main():
                       "eager_step_ms_with_count_readback": round(eager_us / 1e3, 4),
                       "active_blocks_3x3": n3, "active_blocks_1x1": n1, "grid_blocks": L.main.g.grid_blocks,
                       "algorithmic_bytes_per_step": n_bytes, "mfma_flop_per_step": L.flops_per_step(n3, n1)},
-           "roofline": roof, "roofline_hbm": roof_hbm}
+           "roofline": roof_hbm, "roofline_mfma": roof}
     if not args.no_supplement:
         res["supplement"] = supplement(L, not args.no_unet)
     res["cpu_baseline"] = None if args.no_cpu else cpu_baseline(cfg, n_bytes)
