@@ -123,7 +123,9 @@ int sige_reduce_mask_lists(const void* a_orig, const void* a_edit, sige_dtype dt
  * neighbour x2 up-sampled view (source pixel = (y >> 1, x >> 1)), up = 0 reads x
  * itself.  scale/shift: fp32 [C], both NULL = identity.  Arithmetic in fp32, one
  * rounding to dt.  tiles: [max_blocks][tile_h][tile_w][C] contiguous; only the
- * first min(count, max_blocks) tiles are written.                                 */
+ * first min(count, max_blocks) tiles are written.  Here and in every call below that
+ * takes a block list: indices holds max_blocks rows, all readable (the kernels fetch
+ * row n together with the count; rows beyond the count may hold anything).          */
 int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
                 const sige_geom* g, const int32_t* indices, const int32_t* count,
                 int32_t max_blocks, int32_t n_blocks,
