@@ -56,14 +56,10 @@ __device__ __forceinline__ void mark_blocks(const MarkArgs& m, int py, int px)
     const int bx1 = min((x + m.dilate + m.pad) / m.sx, m.nbx - 1);
     by0 = max(by0, 0);
     bx0 = max(bx0, 0);
-    // Many pixels hit the same few flags: look before storing, so that a flag's cache line is
-    // written a handful of times instead of once per marked pixel (the race is benign: every
-    // writer stores 1).
+    // Plain stores (the race is benign: every writer stores 1).  Looking at the flag first would
+    // save stores but puts a dependent global load on the path of every marking lane.
     for (int by = by0; by <= by1; ++by)
-        for (int bx = bx0; bx <= bx1; ++bx) {
-            volatile uint8_t* f = m.flags + by * m.nbx + bx;
-            if (*f == 0) *f = 1;
-        }
+        for (int bx = bx0; bx <= bx1; ++bx) m.flags[by * m.nbx + bx] = 1;
 }
 
 // V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
