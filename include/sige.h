@@ -209,6 +209,31 @@ int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, const void* v, 
                      void* o, int32_t o_ld, void* workspace, size_t workspace_bytes, void* stream);
 size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_t heads, int32_t d);
 
+/* Sec. 3.2 "Extension to attention layers" (Fig. "sige-attention"): between Gather and
+ * Scatter an attention block sees only the tokens of the active blocks, so its token-wise
+ * layers run on the stacked tiles, one row per token: x is [n_rows][C] with row stride x_ld,
+ * y likewise.  Rows: n_rows >= 0 from the host, or -1 = min(*count * rows_per_count,
+ * max_rows) read on the device (count = the block count, rows_per_count = tokens per
+ * block).  C * size and the strides must be multiples of 16 bytes.  x == y is allowed
+ * for sige_token_norm (a wave reads its whole row before it writes).
+ *
+ * sige_token_norm: per-token layer normalisation over the C channels,
+ *   y[r][c] = (x[r][c] - mean_r) / sqrt(var_r + eps) * gamma[c] + beta[c],
+ * mean and biased variance of row r in fp32 (two passes over registers), gamma / beta
+ * fp32 [C] or NULL (1 / 0).  At most 8 KiB per token.
+ * sige_geglu: the gated GELU of a feed-forward layer, x is [n_rows][2C],
+ *   y[r][c] = x[r][c] * gelu(x[r][C + c]),  gelu(g) = g/2 * (1 + erf(g / sqrt 2)).
+ * (Layer norm and the gated feed-forward are the latent-diffusion transformer block's
+ * operators; the paper applies the engine to that model, Sec. 4.1, without describing
+ * the block.)                                                                        */
+int sige_token_norm(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, const int32_t* count,
+                    int32_t rows_per_count, int32_t max_rows, int32_t n_rows,
+                    const float* gamma, const float* beta, float eps,
+                    void* y, int32_t y_ld, void* stream);
+int sige_geglu(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, const int32_t* count,
+               int32_t rows_per_count, int32_t max_rows, int32_t n_rows,
+               void* y, int32_t y_ld, void* stream);
+
 /* ---- helpers beside the path --------------------------------------------------- */
 
 /* Re-lays an OIHW weight tensor (device, dtype dt, [Cout][Cin][k][k]) into the

@@ -247,6 +247,34 @@ def pipeline_a(x_orig, x_edit, y_cache, blocks, bh, bw, w_oihw, stride=1, pad=0)
     return select_blocks(d, zero, blocks, bh, bw) + _f64(y_cache)
 
 
+# ---------------------------------------------------------------- token-wise layers
+
+def layer_norm(x, gamma=None, beta=None, eps: float = 1e-5) -> np.ndarray:
+    """Per-token layer normalisation over the last axis (biased variance), the textbook
+    operator of a transformer block; the token-wise layers between Gather and Scatter of
+    an attention block (Sec. 3.2 "Extension to attention layers") use it."""
+    x = _f64(x)
+    mean = x.mean(axis=-1, keepdims=True)
+    var = ((x - mean) ** 2).mean(axis=-1, keepdims=True)
+    y = (x - mean) / np.sqrt(var + eps)
+    if gamma is not None:
+        y = y * _f64(gamma)
+    if beta is not None:
+        y = y + _f64(beta)
+    return y
+
+
+def geglu(x) -> np.ndarray:
+    """Gated GELU of a feed-forward layer: x[..., :C] * gelu(x[..., C:]) with the exact
+    gelu(g) = g/2 * (1 + erf(g / sqrt 2))."""
+    from math import erf, sqrt
+    x = _f64(x)
+    C = x.shape[-1] // 2
+    g = x[..., C:]
+    phi = 0.5 * (1.0 + np.vectorize(erf)(g / sqrt(2.0)))
+    return x[..., :C] * g * phi
+
+
 # ---------------------------------------------------------------- attention
 
 def attention(q, k, v, scale: float) -> np.ndarray:

@@ -23,7 +23,7 @@ STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3:
           4: "SIGE_ERR_HIP"}
 
 EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_conv", "sige_conv_workspace_bytes", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
-           "sige_sparse_attn_workspace_bytes", "sige_packed_weight_bytes", "sige_pack_weight",
+           "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
 
@@ -97,6 +97,8 @@ def lib() -> ctypes.CDLL:
         L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.sige_packed_weight_bytes.argtypes = [i32, i32, i32, i32]
         L.sige_pack_weight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.sige_token_norm.argtypes = [vp, i32, i32, i32, vp, i32, i32, i32, vp, vp, f32, vp, i32, vp]
+        L.sige_geglu.argtypes = [vp, i32, i32, i32, vp, i32, i32, i32, vp, i32, vp]
         L.sige_gn_stats.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
@@ -209,6 +211,24 @@ def sige_fused_conv(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, 
                                  mb, n_blocks, _ptr(scale), _ptr(shift), act, Cout, _ptr(packed_weight), _ptr(bias),
                                  _ptr(residual_tiles), _ptr(residual), res_ld or 0, _ptr(y), y_ld or 0,
                                  _ptr(out_tiles), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def sige_token_norm(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_rows=None, gamma=None, beta=None,
+                    eps=1e-5, x_ld=None, y_ld=None):
+    """y[r] = layer_norm(x[r]) * gamma + beta for the token rows of stacked tiles (x, y: [rows, >=C])."""
+    x2, y2 = x.reshape(-1, x.shape[-1]), y.reshape(-1, y.shape[-1])
+    mr = x2.shape[0] if max_rows is None else max_rows
+    _check(lib().sige_token_norm(_ptr(x), _DT[x.dtype], C, x2.stride(0) if x_ld is None else x_ld, _ptr(count),
+                                 rows_per_count, mr, n_rows, _ptr(gamma), _ptr(beta), eps, _ptr(y),
+                                 y2.stride(0) if y_ld is None else y_ld, _stream()))
+
+
+def sige_geglu(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_rows=None, x_ld=None, y_ld=None):
+    """y[r, c] = x[r, c] * gelu(x[r, C + c]) for the token rows of stacked tiles."""
+    x2, y2 = x.reshape(-1, x.shape[-1]), y.reshape(-1, y.shape[-1])
+    mr = x2.shape[0] if max_rows is None else max_rows
+    _check(lib().sige_geglu(_ptr(x), _DT[x.dtype], C, x2.stride(0) if x_ld is None else x_ld, _ptr(count),
+                            rows_per_count, mr, n_rows, _ptr(y), y2.stride(0) if y_ld is None else y_ld, _stream()))
 
 
 def sige_sparse_attn_workspace_bytes(Nq, T, heads, d) -> int:

@@ -197,3 +197,49 @@ def test_sige_attention_layer_sparse_queries(oracle):
     # K/V caches: edited tokens overwritten, the rest bit-identical
     assert torch.equal(kc[~a_t], dev(k_cache)[~a_t]) and torch.equal(vc[~a_t], dev(v_cache)[~a_t])
     assert_close(kc[a_t], oracle.conv2d(f64(x_e), w64[1], b64[1])[act], td, "K overwrite")
+
+
+@pytest.mark.parametrize("dtype,C,rows", [("bf16", 320, 37), ("f16", 1280, 70), ("f32", 64, 9), ("bf16", 2560, 5),
+                                          ("f16", 8, 130)])
+def test_token_norm_and_geglu(oracle, dtype, C, rows):
+    """Token-wise layers on stacked tiles: layer norm over channels and the gated GELU, against the
+    oracle; host row count and device count (count * tokens per block), rows beyond untouched, wider
+    row strides, in-place normalisation."""
+    rng = np.random.default_rng(C + rows)
+    td = DT[dtype]
+    ld = C + (16 if dtype == "f32" else 32)
+    buf = torch.from_numpy((rng.standard_normal((rows + 4, ld)) * 2.0 + 0.5).astype(np.float32)).to(td).cuda()
+    x = buf[:, :C]
+    gamma = torch.from_numpy(rng.uniform(0.5, 1.5, C).astype(np.float32))
+    beta = torch.from_numpy(rng.uniform(-0.5, 0.5, C).astype(np.float32))
+    want = oracle.layer_norm(f64(x[:rows]), f64(gamma), f64(beta), 1e-5)
+    y = torch.full((rows + 4, C), 7.0, dtype=td, device="cuda")
+    api.sige_token_norm(x, y, C, n_rows=rows, gamma=dev(gamma), beta=dev(beta), eps=1e-5, x_ld=ld)
+    assert_close(y[:rows], want, td, "token norm")
+    assert (y[rows:] == 7.0).all()
+    # device-side count: rows = count * rows_per_count, capped by max_rows
+    if rows % 5 == 0:
+        cnt = torch.tensor([rows // 5], dtype=torch.int32, device="cuda")
+        y2 = torch.full((rows + 4, C), 7.0, dtype=td, device="cuda")
+        api.sige_token_norm(x, y2, C, n_rows=-1, count=cnt, rows_per_count=5, max_rows=rows + 4, gamma=dev(gamma),
+                            beta=dev(beta), eps=1e-5, x_ld=ld)
+        assert torch.equal(y2, y)
+        cnt.fill_(1000)
+        api.sige_token_norm(x, y2, C, n_rows=-1, count=cnt, rows_per_count=5, max_rows=rows, gamma=dev(gamma),
+                            beta=dev(beta), eps=1e-5, x_ld=ld)
+        assert torch.equal(y2, y)          # capped at max_rows
+    # in place, no affine part
+    z = x[:rows].contiguous()
+    api.sige_token_norm(z, z, C, n_rows=rows, eps=1e-5)
+    assert_close(z, oracle.layer_norm(f64(x[:rows]), eps=1e-5), td, "token norm in place")
+    # gated GELU: input rows of 2*Ch channels
+    if C % 2 == 0 and (C // 2) * (4 if dtype == "f32" else 2) % 16 == 0:
+        Ch = C // 2
+        o = torch.full((rows + 4, Ch), 7.0, dtype=td, device="cuda")
+        api.sige_geglu(x, o, Ch, n_rows=rows, x_ld=ld)
+        assert_close(o[:rows], oracle.geglu(f64(x[:rows])), td, "geglu")
+        assert (o[rows:] == 7.0).all()
+    with pytest.raises(api.SigeError):
+        api.sige_token_norm(x, y, C, n_rows=rows + 100, x_ld=ld)          # more rows than max_rows
+    with pytest.raises(api.SigeError):
+        api.sige_token_norm(x, y, C, n_rows=-1, x_ld=ld)                  # no count

@@ -94,3 +94,32 @@ def test_attention_case_generator_shapes():
     c = inputs.attention_case(5, T=64, heads=2, d=40, n_q=16, dtype="bf16")
     assert c["q"].shape == (16, 2, 40) and c["k"].shape == (64, 2, 40)
     assert c["q"].dtype == torch.bfloat16
+
+
+def test_token_layers_equal_library_float64_and_invariants(oracle):
+    """Pins for the token-wise layers of a transformer block: the library's float64 layer_norm and
+    gelu, plus what the definitions fix (zero mean / unit variance rows, shift invariance, the gate
+    closed forms gelu(0) = 0, gelu(g) -> g for large g, gelu(g) - gelu(-g) = g)."""
+    g = torch.Generator().manual_seed(4)
+    x = torch.randn(9, 24, dtype=torch.float64, generator=g) * 2.5 + 0.7
+    gamma = torch.rand(24, dtype=torch.float64, generator=g) + 0.5
+    beta = torch.randn(24, dtype=torch.float64, generator=g)
+    want = torch.nn.functional.layer_norm(x, (24,), gamma, beta, 1e-5).numpy()
+    np.testing.assert_allclose(oracle.layer_norm(x.numpy(), gamma.numpy(), beta.numpy(), 1e-5), want,
+                               rtol=1e-12, atol=1e-13)
+    y = oracle.layer_norm(x.numpy(), eps=0.0)
+    np.testing.assert_allclose(y.mean(axis=-1), 0.0, atol=1e-13)
+    np.testing.assert_allclose((y * y).mean(axis=-1), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(oracle.layer_norm(x.numpy() + 11.0, eps=0.0), y, atol=1e-11)   # shift invariance
+    # a transposed operand (normalising over tokens instead of channels) must not pass
+    assert not np.allclose(oracle.layer_norm(x.numpy().T, eps=0.0).T, y)
+    u = torch.randn(9, 16, dtype=torch.float64, generator=g) * 2
+    want = (u[:, :8] * torch.nn.functional.gelu(u[:, 8:])).numpy()
+    np.testing.assert_allclose(oracle.geglu(u.numpy()), want, rtol=1e-12, atol=1e-13)
+    one = np.ones((1, 4))
+    assert np.array_equal(oracle.geglu(np.concatenate([one, 0 * one], -1)), 0 * one)
+    np.testing.assert_allclose(oracle.geglu(np.concatenate([one, 40.0 * one], -1)), 40.0 * one, rtol=1e-15)
+    gp, gm = oracle.geglu(np.concatenate([one, 1.3 * one], -1)), oracle.geglu(np.concatenate([one, -1.3 * one], -1))
+    np.testing.assert_allclose(gp - gm, 1.3 * one, rtol=1e-14)      # gelu(g) - gelu(-g) = g
+    # swapping value and gate halves must not pass
+    assert not np.allclose(oracle.geglu(u.numpy()[:, ::-1].copy())[:, ::-1], want)
