@@ -37,6 +37,70 @@ def all_blocks(Hout, Wout, b):
     return np.array([(y, x) for y in range(0, Hout, b) for x in range(0, Wout, b)], np.int32)
 
 
+def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate, block, min_sparse_res,
+                       groups, eps):
+    """A latent-diffusion style transformer block under the method (Sec. 3.2 "Extension to attention
+    layers", Fig. "sige-attention"), written densely: every stage is computed for all tokens from the
+    current tensors and kept only on the tokens of the active blocks; the self-attention keys and
+    values are caches whose active tokens are overwritten before the attention runs.  Stages: group
+    norm (cached statistics) + 1x1 in; layer norm + self-attention + residual; layer norm +
+    cross-attention over the text embeddings + residual; layer norm + gated-GELU feed-forward +
+    residual; 1x1 out + the block's input.  Every stored tensor is rounded once to the storage type."""
+    n, C, heads = op["name"], op["C"], op["heads"]
+    d = C // heads
+    r = x.shape[0]
+    T = r * r
+    b = min(block, r)
+    lin = lambda z, part: so.conv2d(z, _p64(P, f"{n}.{part}.w"), _p64(P, f"{n}.{part}.b"))
+    ln = lambda z, part: so.layer_norm(z, _p64(P, f"{n}.{part}.gamma"), _p64(P, f"{n}.{part}.beta"), 1e-5)
+    if dense:
+        mean, var = so.gn_stats(x, groups)
+        stats[n] = so.fold_gn(_p64(P, n + ".gamma"), _p64(P, n + ".beta"), mean, var, eps)
+        for name in ("h0", "h1", "h2", "h3"):
+            B[f"{n}.{name}"] = np.zeros((r, r, C))
+        B[f"{n}.kv"] = np.zeros((r, r, 2 * C))
+    if dense or r < min_sparse_res:
+        blocks = all_blocks(r, r, b)
+    else:   # the tokens that changed are the output blocks of the 3x3 convolution before this block
+        lvl_mask = int(np.log2(mask.shape[0] // r))
+        blocks = level_blocks(mask, lvl_mask, dilate, r, r, b, 3, 1, 1)
+    used_blocks[n] = blocks
+    keep = lambda new, name: B.__setitem__(name, so.select_blocks(new, B[name], blocks, b, b))
+    scale, shift = stats[n]
+    x_in = x.copy()
+    keep(rnd(lin(rnd(so.scale_shift_act(x, scale, shift, so.ACT_NONE)), "in")), f"{n}.h0")
+    h0 = B[f"{n}.h0"]
+    # self-attention
+    tn = rnd(ln(h0, "ln1"))
+    q = rnd(lin(tn, "q1"))
+    kv = np.concatenate([rnd(lin(tn, "k1")), rnd(lin(tn, "v1"))], axis=2)
+    keep(kv, f"{n}.kv")
+    kv = B[f"{n}.kv"]
+    a = rnd(so.attention(q.reshape(T, heads, d), kv[:, :, :C].reshape(T, heads, d),
+                         kv[:, :, C:].reshape(T, heads, d), 1.0 / np.sqrt(d))).reshape(r, r, C)
+    keep(rnd(rnd(lin(a, "o1")) + h0), f"{n}.h1")
+    h1 = B[f"{n}.h1"]
+    # cross-attention over the text embeddings
+    ctx = _p64(P, "ctx")[None]                       # [1, n_ctx, d_ctx] as a one-row image
+    kc, vc = rnd(lin(ctx, "k2"))[0], rnd(lin(ctx, "v2"))[0]
+    tn = rnd(ln(h1, "ln2"))
+    q = rnd(lin(tn, "q2"))
+    nc = kc.shape[0]
+    a = rnd(so.attention(q.reshape(T, heads, d), kc.reshape(nc, heads, d), vc.reshape(nc, heads, d),
+                         1.0 / np.sqrt(d))).reshape(r, r, C)
+    keep(rnd(rnd(lin(a, "o2")) + h1), f"{n}.h2")
+    h2 = B[f"{n}.h2"]
+    # gated-GELU feed-forward
+    tn = rnd(ln(h2, "ln3"))
+    u = rnd(lin(tn, "ff1"))
+    gg = rnd(so.geglu(u))
+    keep(rnd(rnd(lin(gg, "ff2")) + h2), f"{n}.h3")
+    h3 = B[f"{n}.h3"]
+    y = rnd(rnd(lin(h3, "out")) + x_in)
+    yv = _view(B, op["y"])
+    yv[...] = so.select_blocks(y, yv, blocks, b, b)
+
+
 def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float = 1e-5, block: int = 16,
               cache=None, stats=None, mask=None, dilate: int = 1, min_sparse_res: int = 64):
     """One forward pass.  cache is None: dense pass on the original image, returns (buffers, stats).
@@ -85,6 +149,9 @@ def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float
                                       1 if k == 1 else pad)
             used_blocks[n] = blocks
             yv[...] = so.select_blocks(y, yv, blocks, b, b)
+        elif op["kind"] == "xfmr":
+            _transformer_block(op, B, P, x, rnd, dense, stats_out, used_blocks, mask, dilate, block,
+                               min_sparse_res, groups, eps)
         else:  # self-attention block: GN -> q, k, v (1x1) -> attention -> proj (1x1) -> + x
             C, heads = op["C"], op["heads"]
             d = C // heads

@@ -152,12 +152,15 @@ def token_mask(seed: int, Ht: int, Wt: int, area_frac: float, n_blobs: int = 3) 
 # ----------------------------------------------------------------------------------------
 
 def unet_topology(res: int = 256, in_ch: int = 3, channels=(128, 128, 256, 256, 512, 512),
-                  attn_res=(16,), heads: int = 4, in_pad: int = 16):
+                  attn_res=(16,), heads: int = 4, in_pad: int = 16, attn_kind: str = "attn", ctx=(77, 768)):
     """Returns (buffers, ops).  conv-in; per level two ResBlocks (GN+SiLU+3x3 twice, 1x1 shortcut
     iff the channel count changes) and a stride-2 3x3 conv; two ResBlocks in the middle; on the way
     up per level two ResBlocks on concat(h, skip) and nearest-x2 + 3x3 conv; self-attention after
     every ResBlock at the listed resolutions; GN+SiLU+3x3 conv-out.  Skips are the outputs of the
-    down-path ResBlocks, consumed in reverse order."""
+    down-path ResBlocks, consumed in reverse order.  attn_kind "attn": a plain self-attention block
+    (GN, q/k/v, attention, projection, residual); "xfmr": a latent-diffusion style transformer block
+    (GN + 1x1 in; layer norm + self-attention; layer norm + cross-attention over ctx = (tokens, width)
+    text embeddings; layer norm + gated-GELU feed-forward; 1x1 out + residual)."""
     bufs, ops = {}, []
     nl = len(channels)
     R = [res >> i for i in range(nl)]
@@ -183,7 +186,10 @@ def unet_topology(res: int = 256, in_ch: int = 3, channels=(128, 128, 256, 256, 
 
     def attn(name, x, y, lvl):
         c = x[2]
-        ops.append(dict(kind="attn", name=name, x=x, y=y, level=lvl, heads=heads, C=c))
+        op = dict(kind=attn_kind, name=name, x=x, y=y, level=lvl, heads=heads, C=c)
+        if attn_kind == "xfmr":
+            op.update(n_ctx=ctx[0], d_ctx=ctx[1])
+        ops.append(op)
 
     img = (buf("image", res, in_pad), 0, in_pad)   # the 3 image channels, zero padded to in_pad
     h = (buf("in", res, channels[0]), 0, channels[0])
@@ -283,12 +289,24 @@ def unet_params(seed: int, ops, dtype: str = "f16", groups: int = 32, in_ch: int
             P[n + ".w"], P[n + ".b"] = w, b
             if op["gn"]:
                 gn(n, cin)
-        else:
+        elif op["kind"] == "attn":
             c = op["C"]
             gn(n, c)
             for part in ("q", "k", "v", "o"):
                 w, b = conv_params(rng, c, c, 1, td)
                 P[f"{n}.{part}.w"], P[f"{n}.{part}.b"] = w, b
+        else:   # transformer block
+            c, dc = op["C"], op["d_ctx"]
+            gn(n, c)
+            for ln in ("ln1", "ln2", "ln3"):
+                gn(f"{n}.{ln}", c)
+            shapes = {"in": (c, c), "q1": (c, c), "k1": (c, c), "v1": (c, c), "o1": (c, c), "q2": (c, c),
+                      "k2": (c, dc), "v2": (c, dc), "o2": (c, c), "ff1": (8 * c, c), "ff2": (c, 4 * c), "out": (c, c)}
+            for part, (co, ci) in shapes.items():
+                w, b = conv_params(rng, co, ci, 1, td)
+                P[f"{n}.{part}.w"], P[f"{n}.{part}.b"] = w, b
+            if "ctx" not in P:   # the text embeddings: one set for the whole network
+                P["ctx"] = torch.from_numpy(rng.standard_normal((op["n_ctx"], dc)).astype(np.float32)).to(td)
     return P
 
 

@@ -31,11 +31,12 @@ def _next_pow2(n: int) -> int:
 class SigeUNet:
     def __init__(self, res=256, channels=(128, 128, 256, 256, 512, 512), attn_res=(16,), heads=4,
                  dtype="f16", seed=1003, device="cuda", block=16, groups=32, eps=1e-5, dilate=1,
-                 min_sparse_res=64, params=None, fused=True):
+                 min_sparse_res=64, params=None, fused=True, in_ch=3, attn_kind="attn", ctx=(77, 768)):
         self.res, self.device, self.td = res, device, inputs.DTYPES[dtype]
         self.block, self.groups, self.eps, self.dilate, self.min_sparse_res = block, groups, eps, dilate, min_sparse_res
-        self.bufs_shape, self.ops = inputs.unet_topology(res, 3, channels, attn_res, heads)
-        P = params if params is not None else inputs.unet_params(seed, self.ops, dtype, groups)
+        self.bufs_shape, self.ops = inputs.unet_topology(res, in_ch, channels, attn_res, heads, attn_kind=attn_kind,
+                                                         ctx=ctx)
+        P = params if params is not None else inputs.unet_params(seed, self.ops, dtype, groups, in_ch=in_ch)
         self.B = {n: torch.zeros(s, dtype=self.td, device=device) for n, s in self.bufs_shape.items()}
         self.ws = Workspace(device)
         self.lists = {}        # (H_in, k, stride) -> [all-active list, sparse list]
@@ -57,6 +58,27 @@ class SigeUNet:
                                      up=op["up"])
                 kk = 3 if op["k"] == 1 else op["k"]          # a 1x1 shortcut runs on its ResBlock's 3x3 list
                 L["list"] = self._lists(Hin, kk, op["stride"], b)
+            elif op["kind"] == "xfmr":
+                b = min(block, r_in)
+                assert r_in % b == 0, "token blocks must tile the map exactly"
+                Cx, nc, dc = op["C"], op["n_ctx"], op["d_ctx"]
+                lin = lambda part: SigeConv(P[f"{n}.{part}.w"].to(device), P[f"{n}.{part}.b"], r_in, r_in, b, 1, 0)
+                for part in ("in", "q1", "o1", "q2", "o2", "ff1", "ff2", "out"):
+                    L[part] = lin(part)
+                L["kv1"] = SigeConv(torch.cat([P[f"{n}.k1.w"], P[f"{n}.v1.w"]], 0).to(device),
+                                    torch.cat([P[f"{n}.k1.b"], P[f"{n}.v1.b"]], 0), r_in, r_in, b, 1, 0)
+                # keys and values of the text embeddings: a 1 x n_ctx "image", one block
+                L["kv2"] = SigeConv(torch.cat([P[f"{n}.k2.w"], P[f"{n}.v2.w"]], 0).to(device),
+                                    torch.cat([P[f"{n}.k2.b"], P[f"{n}.v2.b"]], 0), 1, nc, (1, nc), 1, 0)
+                L["ctx"] = P["ctx"].to(device).contiguous()
+                L["kc"] = torch.zeros((nc, 2 * Cx), dtype=self.td, device=device)
+                for part in ("ln1", "ln2", "ln3"):
+                    L[part + ".g"], L[part + ".b"] = f32(P[f"{n}.{part}.gamma"]), f32(P[f"{n}.{part}.beta"])
+                for name in ("h0", "h1", "h2", "h3"):
+                    L[name] = torch.zeros((r_in, r_in, Cx), dtype=self.td, device=device)
+                L["kv"] = torch.zeros((r_in, r_in, 2 * Cx), dtype=self.td, device=device)
+                L["g1"] = L["in"].g
+                L["list"] = self._lists(r_in, 3, 1, b)
             else:
                 b = min(block, r_in)
                 wqkv = torch.cat([P[f"{n}.{p}.w"] for p in "qkv"], 0).to(device)
@@ -70,7 +92,7 @@ class SigeUNet:
                 nb = api.sige_sparse_attn_workspace_bytes(T, T, op["heads"], C // op["heads"])
                 L["att_ws"] = torch.zeros(max(nb // 4, 1), dtype=torch.float32, device=device) if nb else None
                 assert not L["sparse"], "attention is wrapped at all-active resolutions only"
-            if op["kind"] == "attn" or op["gn"]:
+            if op["kind"] in ("attn", "xfmr") or op["gn"]:
                 L["gamma"], L["beta"] = f32(P[n + ".gamma"]), f32(P[n + ".beta"])
                 L["mean"] = torch.zeros(groups, device=device)
                 L["var"] = torch.zeros(groups, device=device)
@@ -137,6 +159,8 @@ class SigeUNet:
                 res_f = self.view(op["residual"]) if op["residual"] is not None else None
                 L["conv"].forward(x, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift, act=act,
                                   residual_tiles=res_t, residual=res_f, tag="main", fused=fused)
+            elif op["kind"] == "xfmr":
+                self._transformer(L, x, self.view(op["y"]), bl, dense, scale, shift)
             else:
                 C, heads = op["C"], op["heads"]
                 T = x.shape[0] * x.shape[1]
@@ -149,6 +173,79 @@ class SigeUNet:
                 L["proj"].forward(L["att_buf"], self.view(op["y"]), bl, self.ws, residual=x, tag="main",
                                   fused=fused)
         return self.B["out"]
+
+    def _transformer(self, L, x, y, bl, dense, scale, shift):
+        """A transformer block on the tokens of the active blocks (Fig. "sige-attention"): gather,
+        token-wise layers and 1x1 convolutions on the stacked tiles, keys and values scattered into
+        their caches, attention for the gathered queries only, result scattered back with the
+        residual.  Needs the block count on the host (it sizes the attention call)."""
+        op = L["op"]
+        C, heads, g1, ws = op["C"], op["heads"], L["g1"], self.ws
+        d = C // heads
+        nb = bl.n_host
+        assert nb >= 0, "transformer blocks need exact block counts (set_edit(exact=True))"
+        if nb == 0:
+            return
+        idx, cnt = bl.indices, bl.count
+        tpb = g1.block_h * g1.block_w
+        rows, T = nb * tpb, g1.H_in * g1.W_in
+        sm = 1.0 / math.sqrt(d)
+
+        def tiles(tag, ch):
+            return ws.get(tag, rows * ch, self.td).view(nb, g1.block_h, g1.block_w, ch)
+
+        def conv(layer, src, tag):
+            out = tiles(tag, layer.Cout)
+            nbytes = api.sige_conv_workspace_bytes(self.td, layer.g, layer.Cin, layer.Cout, nb)
+            split = ws.get("split_k", nbytes // 4, torch.float32) if nbytes else None
+            api.sige_conv(src, layer.g, layer.Cin, layer.Cout, layer.packed, layer.bias, cnt, out, n_blocks=nb,
+                          max_blocks=nb, workspace=split)
+            return out
+
+        def normed(src_full, part):
+            t = tiles("x_t", C)
+            api.sige_gather(src_full, g1, idx, cnt, t, n_blocks=nb, max_blocks=nb)
+            tn = tiles("x_n", C)
+            api.sige_token_norm(t, tn, C, n_rows=rows, gamma=L[part + ".g"], beta=L[part + ".b"], eps=1e-5)
+            return tn
+
+        def attend(q, k, v, Tk, kv_ld):
+            o = tiles("x_o", C)
+            nbytes = api.sige_sparse_attn_workspace_bytes(rows, Tk, heads, d)
+            aws = ws.get("attn_ws", nbytes // 4, torch.float32) if nbytes else None
+            api.sige_sparse_attn(q.view(rows, C), k, v, o.view(rows, C), sm, Nq=rows, workspace=aws, heads=heads,
+                                 d=d, q_ld=C, kv_ld=kv_ld, o_ld=C)
+            return o
+
+        def back(out_tiles, dst, residual):
+            api.sige_scatter(out_tiles, g1, idx, cnt, dst, n_blocks=nb, residual=residual, Cout=C, max_blocks=nb)
+
+        if dense:   # keys and values of the text embeddings do not depend on the image
+            one = torch.ones(1, dtype=torch.int32, device=self.device)
+            kv2 = L["kv2"]
+            api.sige_conv(L["ctx"].view(1, 1, -1, kv2.Cin), kv2.g, kv2.Cin, kv2.Cout, kv2.packed, kv2.bias, one,
+                          L["kc"].view(1, 1, -1, 2 * C), n_blocks=1, max_blocks=1)
+        L["in"].forward(x, L["h0"], bl, ws, scale=scale, shift=shift, fused=True)
+        # self-attention: only the active tokens' queries; their keys and values go into the caches first
+        tn = normed(L["h0"], "ln1")
+        q = conv(L["q1"], tn, "x_q")
+        kv = conv(L["kv1"], tn, "x_kv")
+        api.sige_scatter(kv, g1, idx, cnt, L["kv"], n_blocks=nb, Cout=2 * C, max_blocks=nb)
+        kvc = L["kv"].view(T, 2 * C)
+        o = attend(q, kvc[:, :C], kvc[:, C:], T, 2 * C)
+        back(conv(L["o1"], o, "x_p"), L["h1"], L["h0"])
+        # cross-attention over the text embeddings
+        tn = normed(L["h1"], "ln2")
+        q = conv(L["q2"], tn, "x_q")
+        o = attend(q, L["kc"][:, :C], L["kc"][:, C:], L["kc"].shape[0], 2 * C)
+        back(conv(L["o2"], o, "x_p"), L["h2"], L["h1"])
+        # gated-GELU feed-forward
+        tn = normed(L["h2"], "ln3")
+        u = conv(L["ff1"], tn, "x_u")
+        gg = tiles("x_g", 4 * C)
+        api.sige_geglu(u, gg, 4 * C, n_rows=rows)
+        back(conv(L["ff2"], gg, "x_p"), L["h3"], L["h2"])
+        L["out"].forward(L["h3"], y, bl, ws, residual=x, fused=True)
 
     def precompute(self, image):
         """Dense pass on the original image: fills every cache and the normalisation statistics."""
@@ -178,9 +275,17 @@ class SigeUNet:
         total = 0
         for n, L in self.layers.items():
             op = L["op"]
-            if op["kind"] != "conv":
+            if op["kind"] == "attn":
                 C, r = op["C"], self.bufs_shape[op["x"][0]][0]
                 total += r * r * C * C * 4 + 2 * (r * r) ** 2 * C
+                continue
+            if op["kind"] == "xfmr":   # linear layers + both attention maps, on the active tokens only
+                C, r, nc = op["C"], self.bufs_shape[op["x"][0]][0], op["n_ctx"]
+                g1 = L["g1"]
+                ntok = r * r
+                if counts is not None and L["sparse"]:
+                    ntok = counts[(g1.H_in, 3, 1)] * g1.block_h * g1.block_w
+                total += ntok * C * C * (2 + 4 + 2 + 12) + 2 * ntok * (r * r) * C + 2 * ntok * nc * C
                 continue
             c = L["conv"]
             g = c.g
