@@ -12,8 +12,9 @@ its wall time.  The line also carries
 both timed live with events on the launch stream, the CPU oracle timed on the host cores, and
 `supplement`: per-call times, gather / scatter / difference-mask bandwidth on a 1024x1024x128
 tensor with every block active (footprint far beyond the 256 MB Infinity Cache), convolution
-throughput with every block active, sparse-query attention, and the synthetic DDPM-style UNet
-step (BASELINE config 3) sparse at ~1.2 % and 15.5 % edit versus dense.
+throughput with every block active, sparse-query attention, the synthetic DDPM-style UNet step
+(BASELINE config 3) sparse at ~1.2 % and 15.5 % edit versus dense, and the synthetic latent-diffusion
+style UNet step (BASELINE config 4) at 1 / 5 / 20 % edit versus dense.
 """
 import argparse
 import json
@@ -421,6 +422,48 @@ def supplement(L, with_unet):
         un["note"] = ("dense = the same kernels with every block active and group statistics computed on the "
                       "fly; sparse = one HIP graph replay, cached statistics, device-side block counts")
         out["unet_step_config3"] = un
+        del net
+        torch.cuda.empty_cache()
+
+        # ---- the synthetic latent-diffusion style UNet step (BASELINE config 4)
+        net = SigeUNet(64, (320, 640, 1280, 1280), (64, 32, 16), 8, dtype="bf16", seed=1004, block=8, dilate=1,
+                       min_sparse_res=16, in_ch=4, attn_kind="xfmr", ctx=(77, 768))
+        sd = {"config": "64x64x4 latent, channels 320/640/1280/1280, 2 ResBlocks per level each followed by a "
+                        "transformer block (self-attention 8 heads of 40/80/160, cross-attention over 77x768 text "
+                        "embeddings, gated-GELU feed-forward) at 64/32/16, bf16, 8x8 blocks, dilation 1, sparse "
+                        "layers at resolution >= 16",
+              "dense_gmacs": round(net.macs() / 1e9, 1)}
+        for name, frac in (("edit_1pct", 0.01), ("edit_5pct", 0.05), ("edit_20pct", 0.20)):
+            io, ie, mask = inputs.unet_images(1004, 64, frac, "bf16", in_ch=4)
+            io, ie = io.cuda(), ie.cuda()
+            md = torch.from_numpy(mask).cuda()
+            net.precompute(io)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                net.precompute(io)
+            torch.cuda.synchronize()
+            dense_ms = (time.perf_counter() - t0) / 5 * 1e3
+            counts = net.set_edit(md, exact=True)      # the attention calls are sized by the host counts
+            g = net.capture(ie)
+            for _ in range(3):
+                g.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                g.replay()
+            torch.cuda.synchronize()
+            sparse_ms = (time.perf_counter() - t0) / 20 * 1e3
+            b0 = net.layers["down0.0.attn"]["list"][1]
+            sd[name] = {"edited_latent_px": int(mask.sum()),
+                        "active_tokens_64x64": b0.n_host * b0.g.block_h * b0.g.block_w,
+                        "dense_step_ms": round(dense_ms, 3), "sparse_step_ms": round(sparse_ms, 3),
+                        "speedup": round(dense_ms / sparse_ms, 2), "sparse_gmacs": round(net.macs(counts) / 1e9, 1),
+                        "macs_reduction": round(net.macs() / net.macs(counts), 2)}
+        sd["note"] = ("dense = the same kernels with every block active (all queries) and group statistics computed "
+                      "on the fly; sparse = one HIP graph replay with the block counts of the edit baked in; only "
+                      "the active tokens' queries are recomputed, keys and values overwritten in their caches")
+        out["unet_step_config4"] = sd
     return out
 
 
