@@ -43,7 +43,8 @@ typedef enum {
 } sige_status;
 
 typedef enum { SIGE_F32 = 0, SIGE_F16 = 1, SIGE_BF16 = 2 } sige_dtype;
-typedef enum { SIGE_ACT_NONE = 0, SIGE_ACT_SILU = 1, SIGE_ACT_RELU = 2 } sige_act;
+typedef enum { SIGE_ACT_NONE = 0, SIGE_ACT_SILU = 1, SIGE_ACT_RELU = 2,
+               SIGE_ACT_LEAKY_RELU = 3 /* slope 0.2 for negative inputs */ } sige_act;
 
 /* Geometry of one wrapped convolution (host struct).  The output is cut into
  * block_h x block_w blocks anchored at (0,0); edge blocks may be partial.  The
@@ -131,6 +132,22 @@ int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t u
                 int32_t max_blocks, int32_t n_blocks,
                 const float* scale, const float* shift, sige_act act,
                 void* tiles, void* stream);
+
+/* The gather of a spatially-adaptive normalisation layer (the conditional-GAN generator of
+ * Sec. 4.1 "Models"; Sec. 3.2 "Pre-computing normalization parameters": the instance-norm
+ * statistics of the original activation are cached and folded into scale / shift, fp32 [C]):
+ *   tiles[n][i][j][c] = act((scale[c] * x[y][x][c] + shift[c]) * (1 + gamma[y][x][c]) + beta[y][x][c]),
+ * zero outside the image.  mod is the per-pixel modulation tensor [H_in][W_in] with pixel
+ * stride mod_ld elements, gamma in channels 0..C-1 and beta in channels C..2C-1 (the output of
+ * the modulation convolutions, itself updated sparsely); it lives at the resolution the
+ * convolution reads, also when up = 1 (x is then the half-resolution tensor).  Everything
+ * else as in sige_gather; scale / shift NULL = identity.                              */
+int sige_gather_modulated(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
+                          const sige_geom* g, const int32_t* indices, const int32_t* count,
+                          int32_t max_blocks, int32_t n_blocks,
+                          const float* scale, const float* shift,
+                          const void* mod, int32_t mod_ld, sige_act act,
+                          void* tiles, void* stream);
 
 /* Fig. "method": the convolution F_l applied to the stacked tiles (valid, i.e. no
  * padding inside a tile), with bias (Fig. "pipeline" (b)):

@@ -127,6 +127,7 @@ void oracle_scale_shift_act(const double *x, int H, int W, int C, const double *
             if (scale) v = scale[c] * v + shift[c];
             if (act == 1) v = v / (1.0 + exp(-v));
             else if (act == 2) v = v > 0.0 ? v : 0.0;
+            else if (act == 3) v = v > 0.0 ? v : 0.2 * v;   /* leaky ReLU, slope 0.2 */
             z[p * C + c] = v;
         }
 }

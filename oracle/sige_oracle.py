@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sige_oracle.c")
 _SO = os.path.join(_HERE, "libsige_oracle.so")
 
-ACT_NONE, ACT_SILU, ACT_RELU = 0, 1, 2
+ACT_NONE, ACT_SILU, ACT_RELU, ACT_LEAKY_RELU = 0, 1, 2, 3
 
 
 def build(force: bool = False) -> str:
@@ -155,6 +155,28 @@ def scale_shift_act(x, scale, shift, act: int) -> np.ndarray:
     _L().oracle_scale_shift_act(_p(x, ctypes.c_double), H, W, C, _p(sc, ctypes.c_double),
                                 _p(sh, ctypes.c_double), int(act), _p(z, ctypes.c_double))
     return z
+
+
+def activation(v, act: int) -> np.ndarray:
+    v = _f64(v)
+    if act == ACT_SILU:
+        return v / (1.0 + np.exp(-v))
+    if act == ACT_RELU:
+        return np.maximum(v, 0.0)
+    if act == ACT_LEAKY_RELU:
+        return np.where(v > 0.0, v, 0.2 * v)
+    return v
+
+
+def modulate(x, scale, shift, gamma_map, beta_map, act: int) -> np.ndarray:
+    """A spatially-adaptive normalisation layer with cached statistics (the conditional-GAN
+    generator of Sec. 4.1; Sec. 3.2 "Pre-computing normalization parameters"): the instance-norm
+    statistics of the original activation are folded into per-channel scale / shift, the
+    per-pixel gamma and beta come from the label map:  act((scale x + shift)(1 + gamma) + beta)."""
+    n = _f64(x)
+    if scale is not None:
+        n = n * _f64(scale) + _f64(shift)
+    return activation(n * (1.0 + _f64(gamma_map)) + _f64(beta_map), act)
 
 
 # ---------------------------------------------------------------- convolution

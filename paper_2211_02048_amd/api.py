@@ -17,12 +17,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsige_hip.so")
 
 SIGE_F32, SIGE_F16, SIGE_BF16 = 0, 1, 2
-ACT_NONE, ACT_SILU, ACT_RELU = 0, 1, 2
+ACT_NONE, ACT_SILU, ACT_RELU, ACT_LEAKY_RELU = 0, 1, 2, 3
 _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF16}
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_conv", "sige_conv_workspace_bytes", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -87,6 +87,7 @@ def lib() -> ctypes.CDLL:
         L.sige_reduce_mask_workspace_bytes.restype = ctypes.c_size_t
         L.sige_reduce_mask_workspace_bytes.argtypes = [gp]
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
+        L.sige_gather_modulated.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
         L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]
         L.sige_conv_workspace_bytes.restype = ctypes.c_size_t
         L.sige_conv_workspace_bytes.argtypes = [i32, gp, i32, i32, i32]
@@ -165,6 +166,18 @@ def sige_gather(x, g: Geom, indices, count, tiles, *, n_blocks=-1, scale=None, s
     mb = tiles.shape[0] if max_blocks is None else max_blocks
     _check(lib().sige_gather(_ptr(x), _DT[x.dtype], C, x_ld, up, ctypes.byref(g), _ptr(indices), _ptr(count),
                              mb, n_blocks, _ptr(scale), _ptr(shift), act, _ptr(tiles), _stream()))
+
+
+def sige_gather_modulated(x, g: Geom, indices, count, tiles, mod, *, n_blocks=-1, scale=None, shift=None,
+                          act=ACT_NONE, up=0, C=None, x_ld=None, mod_ld=None, max_blocks=None):
+    """tiles[n] = act((scale * x + shift) * (1 + gamma) + beta) with per-pixel gamma | beta in mod [H, W, >=2C]."""
+    C = x.shape[-1] if C is None else C
+    x_ld = x.stride(-2) if x_ld is None else x_ld
+    mod_ld = mod.stride(-2) if mod_ld is None else mod_ld
+    mb = tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_gather_modulated(_ptr(x), _DT[x.dtype], C, x_ld, up, ctypes.byref(g), _ptr(indices), _ptr(count),
+                                       mb, n_blocks, _ptr(scale), _ptr(shift), _ptr(mod), mod_ld, act, _ptr(tiles),
+                                       _stream()))
 
 
 def _nbytes(t):

@@ -119,11 +119,28 @@ __device__ __forceinline__ void scale_shift_act(float (&f)[N], const float (&sc)
             const float v = fmaf(sc[i], f[i], sh[i]);
             f[i] = v > 0.0f ? v : 0.0f;
         }
+    } else if (act == SIGE_ACT_LEAKY_RELU) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const float v = fmaf(sc[i], f[i], sh[i]);
+            f[i] = v > 0.0f ? v : 0.2f * v;
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < N; ++i) f[i] = fmaf(sc[i], f[i], sh[i]);
     }
 }
+
+// A single activation (used where the value is not a plain scale-shift result).
+__device__ __forceinline__ float activate(float v, int act)
+{
+    if (act == SIGE_ACT_SILU) return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f));
+    if (act == SIGE_ACT_RELU) return v > 0.0f ? v : 0.0f;
+    if (act == SIGE_ACT_LEAKY_RELU) return v > 0.0f ? v : 0.2f * v;
+    return v;
+}
+
+inline bool act_ok(int act) { return act >= SIGE_ACT_NONE && act <= SIGE_ACT_LEAKY_RELU; }
 
 __device__ __forceinline__ bool aligned16_dev(const void* p)
 {

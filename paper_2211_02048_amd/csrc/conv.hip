@@ -862,8 +862,7 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
                  "%s: residuals are added by the scatter; they need y", who);
     SIGE_REQUIRE((scale == nullptr) == (shift == nullptr), SIGE_ERR_INVALID_ARG,
                  "%s: scale and shift must be given together", who);
-    SIGE_REQUIRE(act == SIGE_ACT_NONE || act == SIGE_ACT_SILU || act == SIGE_ACT_RELU, SIGE_ERR_INVALID_ARG,
-                 "%s: unknown activation %d", who, (int)act);
+    SIGE_REQUIRE(act_ok((int)act), SIGE_ERR_INVALID_ARG, "%s: unknown activation %d", who, (int)act);
     SIGE_REQUIRE(up == 0 || up == 1, SIGE_ERR_INVALID_ARG, "%s: up must be 0 or 1", who);
     SIGE_REQUIRE(up == 0 || (g->H_in % 2 == 0 && g->W_in % 2 == 0), SIGE_ERR_INVALID_ARG,
                  "%s: up-sampled input size must be even", who);

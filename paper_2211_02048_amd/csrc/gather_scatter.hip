@@ -17,6 +17,8 @@ struct GatherArgs {
     const int32_t* count;
     const float* scale;
     const float* shift;
+    const void* mod;          // per-pixel modulation [Hin][Win][gamma C | beta C], or NULL
+    int mod_ld_vec;
     int Hin, Win, ld_vec, V;  // V = 16-byte vectors per pixel, ld_vec = pixel stride in vectors
     int th, tw, stride, pad, up;
     int max_blocks, n_host, act, rows_per_wg;
@@ -64,7 +66,20 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
                         sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
                     }
                 }
-                scale_shift_act<N>(f, sc, sh, a.act);
+                if (a.mod == nullptr) {
+                    scale_shift_act<N>(f, sc, sh, a.act);
+                } else {
+                    // spatially-adaptive: (scale * x + shift) * (1 + gamma) + beta, then the activation
+                    const uint4* __restrict__ m = (const uint4*)a.mod + ((long)iy * a.Win + ix) * a.mod_ld_vec;
+                    float gm[N], bt[N];
+                    unpack<T>(m[cg], gm);
+                    unpack<T>(m[a.V + cg], bt);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) {
+                        const float n = fmaf(sc[i], f[i], sh[i]);
+                        f[i] = activate(fmaf(n, gm[i], n) + bt[i], a.act);
+                    }
+                }
                 v = pack<T>(f);
             }
         }
@@ -239,13 +254,11 @@ static void launch_scatter(const ScatterArgs& a, dim3 grid, hipStream_t st)
 
 using namespace sige;
 
-extern "C" int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
-                           const sige_geom* g, const int32_t* indices, const int32_t* count,
-                           int32_t max_blocks, int32_t n_blocks, const float* scale,
-                           const float* shift, sige_act act, void* tiles, void* stream)
+static int run_gather(const char* who, const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
+                      const sige_geom* g, const int32_t* indices, const int32_t* count,
+                      int32_t max_blocks, int32_t n_blocks, const float* scale, const float* shift,
+                      const void* mod, int32_t mod_ld, sige_act act, void* tiles, void* stream)
 {
-    clear_error();
-    const char* who = "sige_gather";
     int th, tw, nl;
     if (int rc = check_geom(g, who, &th, &tw)) return rc;
     if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
@@ -254,8 +267,7 @@ extern "C" int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld
     SIGE_REQUIRE(C > 0 && x_ld >= C, SIGE_ERR_INVALID_ARG, "%s: need C > 0 and x_ld >= C", who);
     SIGE_REQUIRE((scale == nullptr) == (shift == nullptr), SIGE_ERR_INVALID_ARG,
                  "%s: scale and shift must be given together", who);
-    SIGE_REQUIRE(act == SIGE_ACT_NONE || act == SIGE_ACT_SILU || act == SIGE_ACT_RELU, SIGE_ERR_INVALID_ARG,
-                 "%s: unknown activation %d", who, (int)act);
+    SIGE_REQUIRE(act_ok((int)act), SIGE_ERR_INVALID_ARG, "%s: unknown activation %d", who, (int)act);
     SIGE_REQUIRE(up == 0 || up == 1, SIGE_ERR_INVALID_ARG, "%s: up must be 0 or 1", who);
     SIGE_REQUIRE(up == 0 || (g->H_in % 2 == 0 && g->W_in % 2 == 0), SIGE_ERR_INVALID_ARG,
                  "%s: up-sampled input size must be even", who);
@@ -269,7 +281,12 @@ extern "C" int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld
     a.Hin = g->H_in; a.Win = g->W_in; a.V = (int)(C * s / 16); a.ld_vec = (int)(x_ld * s / 16);
     a.th = th; a.tw = tw; a.stride = g->stride; a.pad = g->pad; a.up = up;
     a.max_blocks = max_blocks; a.n_host = n_blocks; a.act = (int)act;
-    const bool fused = scale != nullptr || act != SIGE_ACT_NONE;
+    a.mod = mod; a.mod_ld_vec = (int)(mod_ld * s / 16);
+    if (mod != nullptr)
+        SIGE_REQUIRE(mod_ld >= 2 * C && (mod_ld * s) % 16 == 0 && aligned16(mod), SIGE_ERR_UNSUPPORTED,
+                     "%s: mod must be 16-byte aligned with a pixel stride >= 2C that is a multiple of %zu elements",
+                     who, 16 / s);
+    const bool fused = scale != nullptr || act != SIGE_ACT_NONE || mod != nullptr;
     a.rows_per_wg = pick_rows(th, (size_t)tw * C * s, nl, fused ? 40960 : 8192);
     dim3 grid((th + a.rows_per_wg - 1) / a.rows_per_wg, nl);
     SIGE_REQUIRE(nl <= 65535, SIGE_ERR_UNSUPPORTED, "%s: more than 65535 blocks per launch", who);
@@ -279,6 +296,28 @@ extern "C" int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld
     else launch_gather<bf16>(a, grid, fused, st);
     SIGE_LAUNCH_CHECK(who);
     return SIGE_OK;
+}
+
+extern "C" int sige_gather(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
+                           const sige_geom* g, const int32_t* indices, const int32_t* count,
+                           int32_t max_blocks, int32_t n_blocks, const float* scale,
+                           const float* shift, sige_act act, void* tiles, void* stream)
+{
+    clear_error();
+    return run_gather("sige_gather", x, dt, C, x_ld, up, g, indices, count, max_blocks, n_blocks, scale, shift,
+                      nullptr, 0, act, tiles, stream);
+}
+
+extern "C" int sige_gather_modulated(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, int32_t up,
+                                     const sige_geom* g, const int32_t* indices, const int32_t* count,
+                                     int32_t max_blocks, int32_t n_blocks, const float* scale,
+                                     const float* shift, const void* mod, int32_t mod_ld, sige_act act,
+                                     void* tiles, void* stream)
+{
+    clear_error();
+    SIGE_REQUIRE(mod != nullptr, SIGE_ERR_INVALID_ARG, "sige_gather_modulated: mod is required");
+    return run_gather("sige_gather_modulated", x, dt, C, x_ld, up, g, indices, count, max_blocks, n_blocks, scale,
+                      shift, mod, mod_ld, act, tiles, stream);
 }
 
 extern "C" int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32_t Cout,

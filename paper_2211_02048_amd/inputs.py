@@ -322,3 +322,134 @@ def unet_images(seed: int, res: int, area_frac: float, dtype: str = "f16", in_ch
     a_o, a_e = edited_pair(rng, res, res, in_ch, mask, 1.0, td)
     pad = torch.zeros((res, res, in_pad - in_ch), dtype=td)
     return torch.cat([a_o, pad], 2).contiguous(), torch.cat([a_e, pad], 2).contiguous(), mask
+
+
+# ----------------------------------------------------------------------------------------
+# Synthetic SPADE-style conditional generator (BASELINE config 5): a constant start tensor,
+# seven spatially-adaptive residual blocks with nearest x2 up-sampling in between, modulation
+# computed from a one-hot label map.  Again plain data: buffers (H, W, C) and a list of ops.
+#   up   : y = nearest x2 of x
+#   conv : y = conv(act(mod(x))) (+ residual / shortcut tiles); "spade" names the label map, the
+#          two modulation convolutions' buffers and whether the instance-norm statistics of x are
+#          cached from the pre-computation pass (Sec. 4.1: only above 16x32) or recomputed
+# ----------------------------------------------------------------------------------------
+
+def spade_topology(out_hw=(256, 512), start_hw=(8, 16), channels=(1024, 1024, 1024, 512, 256, 128, 64),
+                   n_labels: int = 35, label_pad: int = 48, hidden: int = 128, out_pad: int = 16,
+                   stats_cached_above=(16, 32)):
+    """Blocks: head at the start size; middle 0 (after x2) and middle 1; then four blocks each after
+    x2 (7 blocks, 5 up-samplings: start * 32 = output).  A block fin -> fout: main branch
+    spade+leaky+3x3 (fin -> fmid), spade+leaky+3x3 (fmid -> fout); shortcut spade+1x1 (no
+    activation) iff fin != fout, else identity.  Every spade layer has its own 3x3 label
+    convolution (labels -> hidden, ReLU) and 3x3 modulation convolution (hidden -> gamma | beta)."""
+    bufs, ops = {}, []
+    ups = (0, 1, 0, 1, 1, 1, 1)
+    assert len(channels) == 7 and start_hw[0] * 32 == out_hw[0] and start_hw[1] * 32 == out_hw[1]
+
+    def buf(name, hw, c):
+        bufs[name] = (hw[0], hw[1], c)
+        return name
+
+    def spade_conv(name, x, y, hw, cin, cout, k, act, residual=None, shortcut=None, scatter=True):
+        seg = f"seg{hw[0]}"
+        if seg not in bufs:
+            buf(seg, hw, label_pad)
+        actv = buf(name + ".actv", hw, hidden)
+        mod = buf(name + ".mod", hw, 2 * cin)
+        cached = hw[0] > stats_cached_above[0]
+        ops.append(dict(kind="conv", name=name + ".shared", x=seg, y=actv, hw=hw, cin=label_pad, cout=hidden, k=3,
+                        act=None, spade=None, residual=None, shortcut=None, scatter=True))
+        ops.append(dict(kind="conv", name=name + ".gb", x=actv, y=mod, hw=hw, cin=hidden, cout=2 * cin, k=3,
+                        act="relu", spade=None, residual=None, shortcut=None, scatter=True))
+        ops.append(dict(kind="conv", name=name, x=x, y=y, hw=hw, cin=cin, cout=cout, k=k, act=act,
+                        spade=dict(mod=mod, cached=cached), residual=residual, shortcut=shortcut, scatter=scatter))
+
+    hw = tuple(start_hw)
+    x = buf("z", hw, channels[0])
+    cin = channels[0]
+    for i, cout in enumerate(channels):
+        name = f"block{i}"
+        if ups[i]:
+            hw = (hw[0] * 2, hw[1] * 2)
+            xu = buf(name + ".in", hw, cin)
+            ops.append(dict(kind="up", name=name + ".up", x=x, y=xu, hw=hw, cin=cin))
+            x = xu
+        fmid = min(cin, cout)
+        h = buf(name + ".h", hw, fmid)
+        y = buf(name + ".out", hw, cout)
+        spade_conv(name + ".conv0", x, h, hw, cin, fmid, 3, "leaky")
+        if cin != cout:
+            spade_conv(name + ".short", x, None, hw, cin, cout, 1, None, scatter=False)
+            spade_conv(name + ".conv1", h, y, hw, fmid, cout, 3, "leaky", shortcut=name + ".short")
+        else:
+            spade_conv(name + ".conv1", h, y, hw, fmid, cout, 3, "leaky", residual=x)
+        x, cin = y, cout
+    out = buf("out", hw, out_pad)
+    ops.append(dict(kind="conv", name="conv_img", x=x, y=out, hw=hw, cin=cin, cout=out_pad, k=3, act="leaky",
+                    spade=None, residual=None, shortcut=None, scatter=True))
+    return bufs, ops
+
+
+def spade_params(seed: int, bufs, ops, dtype: str = "f16", out_ch: int = 3, n_labels: int = 35):
+    """W ~ N(0, 1/fan_in), bias ~ N(0, 0.01) (none on the 1x1 shortcuts); the modulation
+    convolutions are scaled down (x 0.25) so that 1 + gamma stays near one; the constant start
+    tensor ~ N(0,1); label-map weights of the padded label channels are zero."""
+    rng = _rng(seed)
+    td = DTYPES[dtype]
+    P = {}
+    for op in ops:
+        if op["kind"] != "conv":
+            continue
+        n = op["name"]
+        w, b = conv_params(rng, op["cout"], op["cin"], op["k"], td)
+        if n.endswith(".shared"):
+            w[:, n_labels:] = 0
+        if n.endswith(".gb"):
+            w, b = (w.float() * 0.25).to(td), b * 0.25
+        if n.endswith(".short"):
+            b = torch.zeros_like(b)
+        if n == "conv_img":
+            w[out_ch:] = 0
+            b[out_ch:] = 0
+        P[n + ".w"], P[n + ".b"] = w, b
+    zs = bufs["z"]
+    P["z"] = _t(rng.standard_normal(zs, dtype=np.float32), td)
+    return P
+
+
+def label_map(seed: int, H: int, W: int, n_labels: int = 35, n_regions: int = 40) -> np.ndarray:
+    """A piecewise-constant label map: nearest-seed (Voronoi) regions with random classes."""
+    rng = _rng(seed)
+    cy, cx = rng.uniform(0, H, n_regions), rng.uniform(0, W, n_regions)
+    cls = rng.integers(0, n_labels, n_regions)
+    yy, xx = np.mgrid[0:H, 0:W]
+    d = (yy[None] - cy[:, None, None]) ** 2 + (xx[None] - cx[:, None, None]) ** 2
+    return cls[np.argmin(d, axis=0)].astype(np.int32)
+
+
+def relabel(seed: int, labels: np.ndarray, area_frac: float, n_labels: int = 35, n_blobs: int = 3) -> np.ndarray:
+    """An edit: inside a few elliptical blobs covering about area_frac every pixel gets one new class
+    different from the class most common there (so that labels really change)."""
+    rng = _rng(seed)
+    H, W = labels.shape
+    s = H / 256.0
+    m = blob_mask(rng, H, W, max(1, int(round(area_frac * H * W))), n_blobs, (5.0 * s + 0.5, 12.0 * s + 0.5), tol=0.1)
+    out = labels.copy()
+    common = np.bincount(labels[m.astype(bool)], minlength=n_labels).argmax()
+    new = int((common + 1 + rng.integers(0, n_labels - 1)) % n_labels)
+    out[m.astype(bool)] = new
+    return out
+
+
+def one_hot_pyramid(labels: np.ndarray, sizes, n_labels: int, label_pad: int, dtype: str = "f16"):
+    """The label map at every listed (H, W) by nearest subsampling, one-hot, zero-padded to label_pad."""
+    td = DTYPES[dtype]
+    H, W = labels.shape
+    out = {}
+    for (h, w) in sizes:
+        sy, sx = H // h, W // w
+        sub = labels[::sy, ::sx][:h, :w]
+        oh = np.zeros((h, w, label_pad), dtype=np.float32)
+        oh[np.arange(h)[:, None], np.arange(w)[None, :], sub] = 1.0
+        out[(h, w)] = torch.from_numpy(oh).to(td).contiguous()
+    return out

@@ -100,8 +100,9 @@ class SigeConv:
 
     def forward(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None,
                 act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False,
-                split_k=True):
-        """gather(x) -> conv -> scatter into y (in place), as three calls or as the one fused call.
+                split_k=True, mod=None):
+        """gather(x) -> conv -> scatter into y (in place), as three calls or as the one fused call
+        (a modulated gather, mod given, always runs as three calls).
         Returns the output tiles (None when the fused call scattered them directly)."""
         g, n = self.g, blocks.n_host
         cap = blocks.max_blocks if n < 0 else max(n, 1)
@@ -112,7 +113,7 @@ class SigeConv:
                 nb = self._split_bytes[cap] = api.sige_conv_workspace_bytes(self.dtype, g, self.Cin, self.Cout, cap)
             if nb:
                 split = ws.get("split_k", nb // 4, torch.float32)
-        if fused:
+        if fused and mod is None:
             out_tiles = None if scatter else ws.get("out_" + tag, self.out_numel(cap), self.dtype)
             api.sige_fused_conv(x, g, blocks.indices, blocks.count, self.Cin, self.Cout, self.packed, self.bias,
                                 y=y if scatter else None, out_tiles=out_tiles, n_blocks=n, max_blocks=cap,
@@ -121,8 +122,12 @@ class SigeConv:
             return out_tiles
         tiles = ws.get("tiles", self.tiles_numel(cap), self.dtype)
         out_tiles = ws.get("out_" + tag, self.out_numel(cap), self.dtype)
-        api.sige_gather(x, g, blocks.indices, blocks.count, tiles, n_blocks=n, scale=scale, shift=shift,
-                        act=act, up=self.up, C=self.Cin, max_blocks=cap)
+        if mod is None:
+            api.sige_gather(x, g, blocks.indices, blocks.count, tiles, n_blocks=n, scale=scale, shift=shift,
+                            act=act, up=self.up, C=self.Cin, max_blocks=cap)
+        else:   # spatially-adaptive normalisation: per-pixel gamma | beta beside the cached statistics
+            api.sige_gather_modulated(x, g, blocks.indices, blocks.count, tiles, mod, n_blocks=n, scale=scale,
+                                      shift=shift, act=act, up=self.up, C=self.Cin, max_blocks=cap)
         api.sige_conv(tiles, g, self.Cin, self.Cout, self.packed, self.bias, blocks.count, out_tiles,
                       n_blocks=n, max_blocks=cap, workspace=split)
         if scatter:

@@ -659,3 +659,41 @@ def test_sequential_edits_incremental_cache(oracle):
         assert_close(y, oracle.conv2d(f64(nxt), f64(w), f64(b), 1, 1), td, f"cache after edit {edit}")
         cur = nxt
     assert 5 <= touched < 5 * conv.g.grid_blocks
+
+
+@pytest.mark.parametrize("dtype,C,H,W,b,up,act", [("f16", 64, 40, 56, 16, 0, "leaky"), ("f32", 32, 24, 24, 6, 1, "none"),
+                                                  ("bf16", 128, 32, 64, 8, 1, "leaky"), ("f16", 24, 20, 20, 5, 0, "relu")])
+def test_gather_modulated(oracle, dtype, C, H, W, b, up, act):
+    """Gather of a spatially-adaptive normalisation layer: per-channel scale/shift (cached statistics),
+    per-pixel gamma | beta from a modulation tensor with a wider pixel stride, the activation, zero
+    padding after everything; also through the x2 up-sampled view."""
+    rng = np.random.default_rng(C + H + up)
+    td = DT[dtype]
+    code = {"none": (api.ACT_NONE, oracle.ACT_NONE), "relu": (api.ACT_RELU, oracle.ACT_RELU),
+            "leaky": (api.ACT_LEAKY_RELU, oracle.ACT_LEAKY_RELU)}[act]
+    hs, wsrc = (H >> up), (W >> up)
+    x = torch.from_numpy(rng.standard_normal((hs, wsrc, C)).astype(np.float32)).to(td)
+    ld = 2 * C + (8 if dtype != "f32" else 4)
+    modbuf = torch.from_numpy((rng.standard_normal((H, W, ld)) * 0.4).astype(np.float32)).to(td)
+    scale = torch.from_numpy(rng.uniform(0.5, 1.5, C).astype(np.float32))
+    shift = torch.from_numpy(rng.uniform(-0.5, 0.5, C).astype(np.float32))
+    g = api.geom(H, W, b, 3, 1, 1)
+    blocks = random_blocks(rng, g, 7)
+    n = len(blocks)
+    idx = torch.from_numpy(blocks).cuda()
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    tiles = torch.full((n + 1, g.tile_h, g.tile_w, C), 5.0, dtype=td, device="cuda")
+    api.sige_gather_modulated(dev(x), g, idx, cnt, tiles, dev(modbuf), n_blocks=n, scale=dev(scale), shift=dev(shift),
+                              act=code[0], up=up, C=C, max_blocks=n)
+    xin = f64(x).repeat(2, axis=0).repeat(2, axis=1) if up else f64(x)
+    z = oracle.modulate(xin, f64(scale), f64(shift), f64(modbuf[:, :, :C]), f64(modbuf[:, :, C:2 * C]), code[1])
+    want = expected_tiles(oracle, z, blocks, g.tile_h, g.tile_w, 1, 1, None, None, 0)   # z is already activated
+    assert_close(tiles[:n], want, td, "modulated gather")
+    assert (tiles[n:] == 5.0).all()
+    # padding is zero after modulation and activation (beta would otherwise leak into it)
+    pad_rows = [i for i, (y0, x0) in enumerate(blocks) if y0 == 0]
+    if pad_rows:
+        assert (tiles[pad_rows[0], 0] == 0).all()
+    with pytest.raises(api.SigeError):
+        api.sige_gather_modulated(dev(x), g, idx, cnt, tiles, dev(modbuf[:, :, :C]).contiguous(), n_blocks=n, C=C,
+                                  up=up, max_blocks=n)          # modulation tensor narrower than 2C

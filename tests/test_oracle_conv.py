@@ -151,3 +151,30 @@ def test_round_storage_equals_library_casts(oracle):
     z = oracle.round_storage(oracle.scale_shift_act(x, sc, sh, oracle.ACT_SILU), "bf16")
     assert np.array_equal(y1, oracle.conv2d(z, w, None, 1, 1))
     assert np.array_equal(oracle.dense_layer(x, w, None, 1, 1, storage="bf16"), oracle.conv2d(x, w, None, 1, 1))
+
+
+def test_modulation_and_leaky_relu_against_library(oracle):
+    """Pins for the spatially-adaptive normalisation statement: the library's float64 instance norm,
+    (1 + gamma) scaling and leaky ReLU; special cases gamma = beta = 0 (plain scale-shift-act) and
+    scale/shift None (modulation of the raw tensor); the sign of the slope."""
+    import torch
+    g = torch.Generator().manual_seed(7)
+    H, W, C = 6, 9, 5
+    x = torch.randn(1, C, H, W, dtype=torch.float64, generator=g) * 1.7 + 0.3
+    gam = torch.randn(1, C, H, W, dtype=torch.float64, generator=g) * 0.3
+    bet = torch.randn(1, C, H, W, dtype=torch.float64, generator=g) * 0.3
+    want = torch.nn.functional.leaky_relu(torch.nn.functional.instance_norm(x, eps=1e-5) * (1 + gam) + bet, 0.2)
+    nhwc = lambda t: t[0].permute(1, 2, 0).contiguous().numpy()
+    from oracle import spade as osp
+    scale, shift = osp.instance_stats(nhwc(x), 1e-5)
+    got = oracle.modulate(nhwc(x), scale, shift, nhwc(gam), nhwc(bet), oracle.ACT_LEAKY_RELU)
+    np.testing.assert_allclose(got, nhwc(want), rtol=1e-12, atol=1e-13)
+    zero = np.zeros((H, W, C))
+    np.testing.assert_allclose(oracle.modulate(nhwc(x), scale, shift, zero, zero, oracle.ACT_LEAKY_RELU),
+                               oracle.scale_shift_act(nhwc(x), scale, shift, oracle.ACT_LEAKY_RELU), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(oracle.modulate(nhwc(x), None, None, nhwc(gam), nhwc(bet), oracle.ACT_NONE),
+                               nhwc(x) * (1 + nhwc(gam)) + nhwc(bet), rtol=0, atol=1e-15)
+    v = np.array([[[-2.0, 3.0]]])
+    assert np.array_equal(oracle.scale_shift_act(v, None, None, oracle.ACT_LEAKY_RELU), np.array([[[-0.4, 3.0]]]))
+    # swapping gamma and beta must not pass
+    assert not np.allclose(oracle.modulate(nhwc(x), scale, shift, nhwc(bet), nhwc(gam), oracle.ACT_LEAKY_RELU), nhwc(want))
