@@ -8,8 +8,11 @@
 // taps; the A operand of each MFMA is a 16-byte LDS read at
 // pixel(py*stride+ky, px*stride+kx), the B operand a 16-byte read of weights that
 // sige_pack_weight has laid out in fragment order (L2 resident, shared by every
-// workgroup).  fp32 accumulation, bias as the accumulator's start value, one
-// rounding to the storage type at the store.
+// workgroup), prefetched through a register ring.  fp32 accumulation, bias added when
+// the accumulators leave the registers, one rounding to the storage type at the store.
+// sige_fused_conv is the same kernel with the gather folded into the staging and the
+// scatter into the epilogue; with a workspace, calls with few workgroups and a long K are
+// cut along K and finished by conv_reduce_kernel.
 #include <type_traits>
 
 #include "common.h"
@@ -109,10 +112,6 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
     packed[i] = o < Cout ? w[(((long)o * Cin + c) * k + ky) * k + kx] : from_f32<T>(0.0f);
 }
 
-// TM x TN: 32x32 MFMA tiles per wave; WM x WN x WK = 4 (or 8) waves over M, N and K (waves that split K
-// take different channel ranges of every tap and are summed through LDS at the end); KC = K steps
-// per staged channel chunk; KK = k*k when it is 9 or 1 (taps unrolled), 0 for any other kernel size.  Weight fragments are fetched into a register ring several taps ahead
-// of the MFMAs that use them (deepest for the K-split shape, whose layers are weight-bound).
 // Finishes one run of N consecutive output channels starting at o: v holds the fp32 sums (bias
 // included), t the element's index in the stacked output tiles, pix the pixel of y it belongs to.
 // Plain mode stores the tile elements; fused mode rounds them to the storage type as a stored
@@ -187,6 +186,11 @@ constexpr int ring_depth(int steps, int limit)
 
 constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks in a 256-row patch)
 
+// TM x TN: 32x32 MFMA tiles per wave; WM x WN x WK = 4 (or 8) waves over M, N and K (waves that
+// split K take different channel ranges of every tap and are summed through LDS at the end); KC =
+// K steps per staged channel chunk; KK = k*k when it is 9 or 1 (the steps of a chunk are then
+// unrolled), 0 for any other kernel size.  Two waves per SIMD are enforced: with fewer the MFMA
+// phase has nothing to overlap its LDS and L2 latencies with.
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
 __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
 {
