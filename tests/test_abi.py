@@ -125,6 +125,41 @@ def test_attention_and_helper_errors(L):
     assert L.sige_sparse_attn_workspace_bytes(64, 4096, 8, 40) > 0
 
 
+def test_token_layer_modulated_gather_and_list_errors(L):
+    f = ctypes.c_float(1e-5)
+    g = good_geom()
+    gp = ctypes.byref(g)
+    # token-wise layers: row protocol and alignment
+    assert L.sige_token_norm(FAKE, 1, 320, 320, None, 0, 64, 65, None, None, f, FAKE, 320, None) == 3   # n_rows > max_rows
+    assert L.sige_token_norm(FAKE, 1, 320, 320, None, 0, 64, -1, None, None, f, FAKE, 320, None) == 1   # -1 without count
+    assert L.sige_token_norm(FAKE, 1, 324, 324, None, 0, 64, 8, None, None, f, FAKE, 324, None) == 2    # C not 16-byte
+    assert L.sige_token_norm(FAKE, 1, 8192, 8192, None, 0, 64, 8, None, None, f, FAKE, 8192, None) == 2  # > 8 KiB/token
+    assert L.sige_token_norm(FAKE, 1, 320, 320, None, 0, 64, 0, None, None, f, FAKE, 320, None) == 0    # nothing to do
+    assert L.sige_geglu(FAKE, 1, 320, 320, None, 0, 64, 8, FAKE, 320, None) == 1                        # x rows hold 2C
+    assert L.sige_geglu(None, 1, 320, 640, None, 0, 64, 8, FAKE, 320, None) == 1
+    # modulated gather: the modulation tensor is required and holds gamma | beta
+    assert L.sige_gather_modulated(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, None, 0, 3, FAKE, None) == 1
+    assert L.sige_gather_modulated(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, FAKE, 64, 3, FAKE, None) == 2
+    assert L.sige_gather_modulated(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, FAKE, 128, 4, FAKE, None) == 1
+    # several lists per call: 1..4 lists, each with a workspace of its own
+    lst = (api.BlockListDesc * 5)()
+    for d in lst:
+        d.g = g
+        d.indices, d.count, d.max_blocks = 0x10000, 0x10000, 121
+        d.workspace, d.workspace_bytes = 0x20000, 128
+    fz = ctypes.c_float(0.0)
+    assert L.sige_reduce_mask_lists(None, None, 0, 64, 64, 0, fz, FAKE, 0, 0, lst, 5, None, None) == 1
+    assert L.sige_reduce_mask_lists(None, None, 0, 64, 64, 0, fz, FAKE, 0, 0, lst, 0, None, None) == 1
+    assert L.sige_reduce_mask_lists(None, None, 0, 64, 64, 0, fz, FAKE, 0, 0, lst, 2, None, None) == 1   # shared workspace
+    assert "share" in err(L)
+    lst[1].workspace = None
+    assert L.sige_reduce_mask_lists(None, None, 0, 64, 64, 0, fz, FAKE, 0, 0, lst, 2, None, None) == 1   # no workspace
+    # convolution workspace query: a layer that never splits, one that does
+    assert L.sige_conv_workspace_bytes(1, gp, 64, 64, 121) == 0
+    small = api.geom(8, 8, 8, 3, 1, 1)
+    assert L.sige_conv_workspace_bytes(1, ctypes.byref(small), 512, 512, 1) > 0
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(api, "_lib", None)
     monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "missing.so"))
