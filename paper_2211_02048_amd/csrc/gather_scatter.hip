@@ -232,9 +232,13 @@ static int pick_rows(int rows, size_t row_bytes, int blocks, size_t target)
 template <typename T>
 static void launch_gather(const GatherArgs& a, dim3 grid, bool fused, hipStream_t st)
 {
+    // the fixed-channel-group walk needs a whole number of pixels per 256 threads (V > 256 would
+    // never advance)
     const bool fixed = (256 % a.V) == 0;
-    if (!fused)
+    if (!fused && fixed)
         hipLaunchKernelGGL((gather_kernel<T, false, true>), grid, dim3(256), 0, st, a);
+    else if (!fused)
+        hipLaunchKernelGGL((gather_kernel<T, false, false>), grid, dim3(256), 0, st, a);
     else if (fixed)
         hipLaunchKernelGGL((gather_kernel<T, true, true>), grid, dim3(256), 0, st, a);
     else
