@@ -27,6 +27,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // One 16-byte A fragment and one 16-byte B fragment per lane advance K by KSTEP channels.
 template <typename T> struct Mma;
@@ -418,12 +419,19 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
         for (int d = 0; d < D; ++d) fetch(ring[d], ch0, d / KW, d % KW);
         for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
-            uint4 af[2][TM];                                  // this step's rows and the next step's
-            load_a(af[0], 0, 0);
+            // A rows run AD steps ahead of their MFMAs: one step where a step holds four MFMAs or
+            // more, two where it holds fewer and would not cover the LDS latency.  The barrier after
+            // the loads keeps them in front of this step's MFMAs (the scheduler otherwise issues them
+            // behind, and every step then waits for its own rows).
+            constexpr int AD = TM * TN >= 4 ? 1 : (STEPS > 2 ? 2 : 1);
+            uint4 af[AD + 1][TM];
+#pragma unroll
+            for (int i = 0; i < AD; ++i) load_a(af[i], i / KW, i % KW);
 #pragma unroll
             for (int st = 0; st < STEPS; ++st) {
-                if (st + 1 < STEPS) load_a(af[(st + 1) & 1], (st + 1) / KW, (st + 1) % KW);
-                multiply(af[st & 1], ring[st % D]);
+                if (st + AD < STEPS) load_a(af[(st + AD) % (AD + 1)], (st + AD) / KW, (st + AD) % KW);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(af[st % (AD + 1)], ring[st % D]);
                 const int nx = (st + D) % STEPS;              // the step that takes over this slot
                 fetch(ring[st % D], st + D < STEPS ? chunk : chunk + 1, nx / KW, nx % KW);
                 // nothing moves across a step boundary: left alone, the scheduler sinks every prefetch
@@ -575,6 +583,204 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
 #pragma unroll
     for (int i = 0; i < N; ++i) v[i] += bv[i];
     emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok ? early : nullptr);
+}
+
+// ---- 1x1 convolutions with few rows ------------------------------------------------------------
+// A 1x1, stride-1 convolution on the stacked pixels of the active blocks is a matrix product with
+// few rows (M = active pixels) and a long K; no input pixel is used by two taps, so a tile staged
+// for the whole workgroup buys nothing.  One workgroup owns 64 rows x 32*TN output channels and its
+// W waves split K: each streams its share of the rows' channels and of the packed weight into
+// registers, P pairs of K steps ahead of the MFMAs, and the waves' sums meet in LDS, where they are
+// added in wave order.  No second kernel, no workspace.
+//
+// Four neighbouring lanes fetch the 64 bytes that two K steps take from one row (a load instruction
+// covers 16 rows, one request per row).  That is not the MFMA operand layout, so each pair of steps
+// passes through a buffer in LDS that belongs to the wave alone: written as loaded, read back as
+// operands, no workgroup barrier involved.
+template <typename T, int W, int P, int TN>
+__global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
+{
+    constexpr int KS = Mma<T>::KSTEP, S = (int)sizeof(T), N = Vec16<T>::N;
+    constexpr int TM = 2, BM = 32 * TM, BN = 32 * TN, RS = BN + 4;
+    constexpr int AROW = 80;                                  // bytes per row in the wave's buffer: 64 + pad
+    constexpr int ABUF = BM * AROW;                           // one pair of K steps of 64 rows
+    static_assert(2 * KS * S == 64, "two K steps of one row are 64 bytes");
+    extern __shared__ uint4 lds4[];
+    char* lds = reinterpret_cast<char*>(lds4);
+    float* red = reinterpret_cast<float*>(lds4);              // [W][BM][RS], after the K loop
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int pb = a.bh * a.bw;
+    const int r0 = blockIdx.y * BM;
+    const bool fused = a.x != nullptr;
+    const int kcs = a.Cin / KS, np = kcs / 2;                 // K steps, pairs of K steps
+    const int q0 = wave * np / W, q1 = (wave + 1) * np / W;   // this wave's pairs
+    const int ntn_total = (a.Cout + 31) / 32;
+
+    // The weight fragments do not depend on the block list: their first loads go out before it is
+    // read.  A fetch past the wave's share still happens, so that the loads in flight stay a fixed
+    // number, but every lane then reads the same 16 bytes: one request instead of a kilobyte.
+    const u32x4* const idle = (const u32x4*)a.w;
+    const u32x4* __restrict__ wp[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+        wp[tn] = (const u32x4*)a.w + (long)min((int)blockIdx.x * TN + tn, ntn_total - 1) * kcs * 64 + lane;
+    u32x4 ra[P][4], rb[P][TN][2];
+    auto fetch_b = [&](int st, int q) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const u32x4* src = q < q1 ? wp[tn] + (long)(2 * q) * 64 : idle;
+            rb[st][tn][0] = src[0];
+            rb[st][tn][1] = src[q < q1 ? 64 : 0];
+        }
+    };
+#pragma unroll
+    for (int st = 0; st < P; ++st) fetch_b(st, q0 + st);
+
+    // rows this lane loads from: row 16*i + lane/4 of the patch, i = 0..3, clamped to rows that exist;
+    // in fused mode the block origins are fetched together with the count (row n exists for
+    // n < max_blocks)
+    int oy[4], ox[4], rr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        rr[i] = r0 + 16 * i + (lane >> 2);
+        oy[i] = ox[i] = 0;
+        if (fused) {
+            const int n = min(rr[i] / pb, a.max_blocks - 1);
+            oy[i] = a.indices[2 * n];
+            ox[i] = a.indices[2 * n + 1];
+        }
+    }
+    int n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
+    asm volatile("" : "+v"(oy[0]), "+v"(ox[0]), "+v"(oy[1]), "+v"(ox[1]), "+v"(oy[2]), "+v"(ox[2]), "+v"(oy[3]),
+                 "+v"(ox[3]), "+v"(n_eff));
+    const int rows = n_eff * pb;
+    if (r0 >= rows) return;
+    // the epilogue needs the origin of every row's block again: waves 0..3 hold those of rows
+    // 16*wave + lane/4 (the i = wave entry of what they just fetched)
+    __shared__ int org[2 * BM];
+    if (fused && wave < 4 && (lane & 3) == 0) {
+        int yy = oy[0], xx = ox[0];
+        if (wave == 1) { yy = oy[1]; xx = ox[1]; }
+        if (wave == 2) { yy = oy[2]; xx = ox[2]; }
+        if (wave == 3) { yy = oy[3]; xx = ox[3]; }
+        org[2 * (16 * wave + (lane >> 2))] = yy;
+        org[2 * (16 * wave + (lane >> 2)) + 1] = xx;
+    }
+    const char* __restrict__ rp[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = min(rr[i], rows - 1);
+        long pixel = r;
+        long ld = a.Cin;
+        if (fused) {
+            const int n = r / pb, p = r - n * pb;
+            const int py = p / a.bw, px = p - py * a.bw;
+            // the origin fetched above belongs to row rr; a clamped row reads the last block's
+            const int y0 = r == rr[i] ? oy[i] : a.indices[2 * n];
+            const int x0 = r == rr[i] ? ox[i] : a.indices[2 * n + 1];
+            pixel = (long)min(y0 + py, a.Hin - 1) * a.Win + min(x0 + px, a.Win - 1);
+            ld = a.x_ld;
+        }
+        rp[i] = (fused ? (const char*)a.x : (const char*)a.tiles) + pixel * ld * S + (lane & 3) * 16;
+    }
+    auto fetch_a = [&](int st, int q) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            ra[st][i] = *(q < q1 ? (const u32x4*)(rp[i] + (long)q * 64) : idle);
+    };
+#pragma unroll
+    for (int st = 0; st < P; ++st) fetch_a(st, q0 + st);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.0f;
+
+    char* const abuf = lds + wave * (2 * ABUF);               // two buffers, used in turn
+    const int a_wr = (lane >> 2) * AROW + (lane & 3) * 16;    // + 16 * i rows
+    const int a_rd = l32 * AROW + half * 16;                  // + 32 * tm rows, + 32 bytes per step
+    for (int q = q0; q < q1; q += P) {
+#pragma unroll
+        for (int st = 0; st < P; ++st) {
+            if (q + st < q1) {                                 // the same for the whole wave
+                char* const buf = abuf + (st & 1) * ABUF;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) *(u32x4*)(buf + 16 * i * AROW + a_wr) = ra[st][i];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    const uint4 f0 = *(const uint4*)(buf + 32 * tm * AROW + a_rd);
+                    const uint4 f1 = *(const uint4*)(buf + 32 * tm * AROW + a_rd + 32);
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const u32x4 b0 = rb[st][tn][0], b1 = rb[st][tn][1];
+                        Mma<T>::run(f0, make_uint4(b0.x, b0.y, b0.z, b0.w), acc[tm][tn]);
+                        Mma<T>::run(f1, make_uint4(b1.x, b1.y, b1.z, b1.w), acc[tm][tn]);
+                    }
+                }
+            }
+            fetch_b(st, q + st + P);
+            fetch_a(st, q + st + P);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // the waves' sums meet in LDS (the operand buffers are done with) and are added in wave order
+    __syncthreads();
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = tm * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                red[(wave * BM + m) * RS + tn * 32 + l32] = acc[tm][tn][r];
+            }
+    __syncthreads();
+    const bool vec_ok = emit_vec_ok<T>(a, fused);
+    const bool to_y = fused && a.y != nullptr;
+    for (int e = tid; e < BM * (BN / N); e += 64 * W) {
+        const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
+        const int r = r0 + m, o = blockIdx.x * BN + nn;
+        if (r >= rows || o >= a.Cout) continue;
+        const long t = (long)r * a.Cout + o;
+        long pix = 0;
+        if (to_y) {
+            const int n = r / pb, p = r - n * pb;
+            const int py = p / a.bw, px = p - py * a.bw;
+            const int yy = org[2 * m] + py, xx = org[2 * m + 1] + px;
+            if (yy < 0 || yy >= a.Hout || xx < 0 || xx >= a.Wout) continue;
+            pix = (long)yy * a.Wout + xx;
+        }
+        // bias and residuals do not depend on the sums: they are fetched before the sums are read
+        const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
+        uint4 early[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+        if (early_ok) {
+            if (a.res_tiles) early[0] = *(const uint4*)((const T*)a.res_tiles + t);
+            if (a.res_full) early[1] = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+        }
+        float v[N], bv[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            v[i] = 0.0f;
+            bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
+        }
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const float4* src = (const float4*)(red + (w * BM + m) * RS + nn);
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i) {
+                const float4 q = src[i];
+                v[4 * i] += q.x; v[4 * i + 1] += q.y; v[4 * i + 2] += q.z; v[4 * i + 3] += q.w;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += bv[i];
+        emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok ? early : nullptr);
+    }
 }
 
 struct ConvPlan {
@@ -762,6 +968,46 @@ extern "C" int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout,
     return SIGE_OK;
 }
 
+// Whether a call goes to pointwise_kernel, and with how many 32-wide output-channel tiles per
+// workgroup (0 = not): a plain 1x1 (no scale, shift or activation on the way in), an even number of
+// K steps, and few enough rows that its patches do not fill the compute units more than once (then
+// the tiled kernel, which reads every weight once per 128 rows, is the better one).
+static int pointwise_tiles(const sige_geom* g, const ConvArgs& a, int ks, int nl)
+{
+    const char* force = getenv("SIGE_CONV_POINTWISE");      // tuning aid: 0 = never, 1 / 2 = that many tiles
+    if (force && atoi(force) == 0) return 0;
+    if (g->k != 1 || g->stride != 1 || g->pad != 0 || a.up != 0 || a.scale != nullptr || a.act != SIGE_ACT_NONE)
+        return 0;
+    const int kcs = a.Cin / ks;
+    if (kcs % 2 || (kcs < 20 && !force)) return 0;          // a short K is the tiled kernel's (one staged chunk)
+    const long mt = ((long)nl * g->block_h * g->block_w + 63) / 64, nt = (a.Cout + 31) / 32;
+    if (mt > 65535) return 0;
+    if (force) return atoi(force) == 2 ? 2 : 1;
+    if (mt * nt <= 256) return 1;
+    if (mt * ((nt + 1) / 2) <= 256) return 2;
+    return 0;
+}
+
+template <typename T, int W, int P, int TN>
+static int launch_pointwise_as(const ConvArgs& a, int nl, hipStream_t st)
+{
+    auto kern = pointwise_kernel<T, W, P, TN>;
+    const size_t lds = std::max((size_t)W * 64 * (32 * TN + 4) * sizeof(float), (size_t)W * 2 * 64 * 80);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_conv: cannot reserve %zu bytes of LDS: %s", lds,
+                 hipGetErrorString(e));
+    const int mt = (int)(((long)nl * a.bh * a.bw + 63) / 64);
+    hipLaunchKernelGGL(kern, dim3((a.Cout + 32 * TN - 1) / (32 * TN), mt), dim3(64 * W), lds, st, a);
+    SIGE_LAUNCH_CHECK("sige_conv");
+    return SIGE_OK;
+}
+
+template <typename T>
+static int launch_pointwise(const ConvArgs& a, int nl, int tiles, hipStream_t st)
+{
+    return tiles == 2 ? launch_pointwise_as<T, 8, 3, 2>(a, nl, st) : launch_pointwise_as<T, 8, 4, 1>(a, nl, st);
+}
+
 template <typename T>
 static int launch_reduce(const ConvArgs& a, int nl, hipStream_t st)
 {
@@ -779,6 +1025,12 @@ static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, 
                     void* stream)
 {
     const int ks = dt == SIGE_F32 ? 8 : 16;
+    a.bh = g->block_h; a.bw = g->block_w; a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
+    if (const int tiles = pointwise_tiles(g, a, ks, nl)) {
+        hipStream_t st = (hipStream_t)stream;
+        return dt == SIGE_F32 ? launch_pointwise<float>(a, nl, tiles, st)
+               : dt == SIGE_F16 ? launch_pointwise<f16>(a, nl, tiles, st) : launch_pointwise<bf16>(a, nl, tiles, st);
+    }
     ConvPlan p;
     const bool ws_ok = workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
     SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok ? workspace_bytes / sizeof(float) : 0, &p),

@@ -191,7 +191,8 @@ def random_blocks(rng, g, n):
 
 @pytest.mark.parametrize("dtype,C,H,W,b,k,s", [
     ("f32", 64, 64, 64, 6, 3, 1), ("f16", 128, 70, 90, 16, 3, 1), ("bf16", 320, 33, 31, 4, 1, 1),
-    ("f16", 64, 64, 48, 8, 3, 2), ("f32", 8, 20, 20, 6, 5, 1), ("f16", 24, 41, 29, 6, 3, 1)])
+    ("f16", 64, 64, 48, 8, 3, 2), ("f32", 8, 20, 20, 6, 5, 1), ("f16", 24, 41, 29, 6, 3, 1),
+    ("f16", 2560, 12, 10, 4, 1, 1)])     # more than 256 16-byte vectors per pixel
 def test_gather_unfused_bit_exact_and_fused(oracle, dtype, C, H, W, b, k, s):
     rng = np.random.default_rng(C + H)
     td = DT[dtype]
@@ -396,6 +397,80 @@ def test_conv_k_split_over_workgroups(oracle, dtype, Cin, Cout, res, b, k):
         assert_close(y, oracle.select_blocks(want, f64(cache), blocks, b, b), td, "k-split sparse")
         out = torch.from_numpy(outside_blocks_mask(blocks, b, b, res, res)).cuda()
         assert torch.equal(y[out], dev(cache)[out])
+
+
+@pytest.mark.parametrize("dtype,Cin,Cout,res,b,n", [
+    ("bf16", 320, 320, 22, 5, 9), ("bf16", 1280, 200, 16, 8, 4), ("f16", 512, 100, 16, 16, 1),
+    ("f32", 192, 72, 20, 6, 11), ("f16", 2560, 64, 8, 8, 1), ("bf16", 640, 36, 13, 4, 16)])
+def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
+    """1x1 convolutions on few rows with a long K take the kernel whose waves split K (no workspace,
+    no second kernel): stacked tiles and the fused call, one and two output-channel tiles per
+    workgroup, ragged rows (blocks of 25 or 36 pixels, blocks that stick out of the image), channel
+    counts that are no multiple of 8, both count paths, both residuals."""
+    rng = np.random.default_rng(Cin + Cout + res)
+    td = DT[dtype]
+    x = torch.from_numpy(rng.standard_normal((res, res, Cin)).astype(np.float32)).to(td)
+    w, bias = inputs.conv_params(rng, Cout, Cin, 1, td)
+    resid = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td)
+    cache = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td)
+    conv = SigeConv(dev(w), bias, res, res, b, 1, 0)
+    g = conv.g
+    bl = BlockList(g, "cuda", max_blocks=max(g.grid_blocks, n + 2)).all_active()
+    pick = np.sort(rng.permutation(g.grid_blocks)[:n])
+    if g.grid_blocks - 1 not in pick:
+        pick[-1] = g.grid_blocks - 1          # the bottom-right block: partly outside when b does not divide res
+    blocks = bl.indices[torch.from_numpy(pick).cuda()].clone()
+    bl.indices.fill_(0)
+    bl.indices[:n].copy_(blocks)
+    bl.count.fill_(n)
+    blocks = blocks.cpu().numpy()
+    want_full = oracle.conv2d(f64(x), f64(w), f64(bias), 1, 0)
+    want = oracle.select_blocks(round_to(want_full, td) + f64(resid), f64(cache), blocks, b, b)
+    out_mask = torch.from_numpy(outside_blocks_mask(blocks, b, b, res, res)).cuda()
+    ws = Workspace("cuda")
+    prev = os.environ.pop("SIGE_CONV_POINTWISE", None)
+    try:
+        for mode in (None, "1", "2"):
+            if mode is None:
+                os.environ.pop("SIGE_CONV_POINTWISE", None)
+            else:
+                os.environ["SIGE_CONV_POINTWISE"] = mode
+            for device_count in (False, True):
+                bl.n_host = -1 if device_count else n
+                bl.max_blocks = n + 2 if device_count else g.grid_blocks
+                y = dev(cache).clone()
+                conv.forward(dev(x), y, bl, ws, residual=dev(resid), fused=True)
+                assert_close(y, want, td, f"pointwise fused mode={mode} device_count={device_count}")
+                assert torch.equal(y[out_mask], dev(cache)[out_mask])
+            # stacked tiles (what the token-wise layers of a transformer block call), bias only
+            bl.n_host, bl.max_blocks = n, g.grid_blocks
+            tiles = torch.from_numpy(rng.standard_normal((n, b, b, Cin)).astype(np.float32)).to(td)
+            want_t = np.stack([oracle.conv2d(f64(tiles[i]), f64(w), f64(bias), 1, 0) for i in range(n)])
+            out = torch.full((n + 1, b, b, Cout), 5.0, dtype=td, device="cuda")
+            api.sige_conv(dev(tiles), g, Cin, Cout, conv.packed, conv.bias, bl.count, out, n_blocks=n, max_blocks=n)
+            assert_close(out[:n], want_t, td, f"pointwise tiles mode={mode}")
+            assert (out[n:] == 5.0).all()
+            if Cout % 8 == 0:
+                # tile residual through the fused call, against the three calls
+                y3 = dev(cache).clone()
+                conv.forward(dev(x), y3, bl, ws, residual_tiles=out[:n].contiguous(), residual=dev(resid))
+                yf = dev(cache).clone()
+                conv.forward(dev(x), yf, bl, ws, residual_tiles=out[:n].contiguous(), residual=dev(resid), fused=True)
+                assert torch.equal(y3, yf)
+    finally:
+        os.environ.pop("SIGE_CONV_POINTWISE", None)
+        if prev is not None:
+            os.environ["SIGE_CONV_POINTWISE"] = prev
+    # the tiled kernel on the same call: same values up to the order of the fp32 sums
+    os.environ["SIGE_CONV_POINTWISE"] = "0"
+    try:
+        y0 = dev(cache).clone()
+        conv.forward(dev(x), y0, bl, ws, residual=dev(resid), fused=True)
+        assert_close(y0, want, td, "tiled kernel on the same call")
+    finally:
+        os.environ.pop("SIGE_CONV_POINTWISE", None)
+        if prev is not None:
+            os.environ["SIGE_CONV_POINTWISE"] = prev
 
 
 # ------------------------------------------------------------------ the whole layer
