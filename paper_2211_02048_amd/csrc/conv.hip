@@ -117,11 +117,13 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 // included), t the element's index in the stacked output tiles, pix the pixel of y it belongs to.
 // Plain mode stores the tile elements; fused mode rounds them to the storage type as a stored
 // tile would be, adds the residuals in fp32 and stores into y.
-// early != nullptr: the two residual vectors were fetched by the caller ahead of time (early[0] the
-// tile residual, early[1] the full-tensor one), for the 16-byte path only.
+// early: the two residual vectors were fetched by the caller ahead of time (for the 16-byte path
+// only).
 template <typename T>
 __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_ok, long t, long pix, int o,
-                                         float (&v)[Vec16<T>::N], const uint4* early = nullptr)
+                                         float (&v)[Vec16<T>::N], bool early = false,
+                                         uint4 early_tiles = make_uint4(0, 0, 0, 0),
+                                         uint4 early_full = make_uint4(0, 0, 0, 0))
 {
     constexpr int N = Vec16<T>::N;
     T* __restrict__ out = (T*)a.out;
@@ -132,12 +134,12 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
                 float f[N], q[N];
                 unpack<T>(r, f);
                 if (a.res_tiles) {
-                    unpack<T>(early ? early[0] : *(const uint4*)((const T*)a.res_tiles + t), q);
+                    unpack<T>(early ? early_tiles : *(const uint4*)((const T*)a.res_tiles + t), q);
 #pragma unroll
                     for (int i = 0; i < N; ++i) f[i] += q[i];
                 }
                 if (a.res_full) {
-                    unpack<T>(early ? early[1] : *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
+                    unpack<T>(early ? early_full : *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
 #pragma unroll
                     for (int i = 0; i < N; ++i) f[i] += q[i];
                 }
@@ -148,7 +150,9 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
             *(uint4*)(out + t) = r;
         }
     } else {
-        for (int i = 0; i < N && o + i < a.Cout; ++i) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if (o + i >= a.Cout) break;
             T r = from_f32<T>(v[i]);
             if (to_y) {
                 if (a.res_tiles || a.res_full) {
@@ -420,9 +424,10 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
         for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
             // A rows run AD steps ahead of their MFMAs: one step where a step holds four MFMAs or
-            // more, two where it holds fewer and would not cover the LDS latency.  The barrier after
-            // the loads keeps them in front of this step's MFMAs (the scheduler otherwise issues them
-            // behind, and every step then waits for its own rows).
+            // more, two where it holds fewer and would not cover the LDS latency.  In the small shapes
+            // a barrier after the loads keeps them in front of this step's MFMAs (the scheduler
+            // otherwise issues them behind, and every step then waits for its own rows); the large
+            // shape is faster with the scheduler left free inside a step.
             constexpr int AD = TM * TN >= 4 ? 1 : (STEPS > 2 ? 2 : 1);
             uint4 af[AD + 1][TM];
 #pragma unroll
@@ -430,7 +435,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
 #pragma unroll
             for (int st = 0; st < STEPS; ++st) {
                 if (st + AD < STEPS) load_a(af[(st + AD) % (AD + 1)], (st + AD) / KW, (st + AD) % KW);
-                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (TM * TN < 4) __builtin_amdgcn_sched_barrier(0);
                 multiply(af[st % (AD + 1)], ring[st % D]);
                 const int nx = (st + D) % STEPS;              // the step that takes over this slot
                 fetch(ring[st % D], st + D < STEPS ? chunk : chunk + 1, nx / KW, nx % KW);
@@ -496,7 +501,9 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
 #pragma unroll
                     for (int i = 0; i < N; i += 4) *(float4*)(dst + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
                 } else {
-                    for (int i = 0; i < N && o + i < a.Cout; ++i) dst[i] = v[i];
+#pragma unroll
+                    for (int i = 0; i < N; ++i)
+                        if (o + i < a.Cout) dst[i] = v[i];
                 }
                 continue;
             }
@@ -542,10 +549,10 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     // with the shares
     const bool vec_ok = emit_vec_ok<T>(a, fused);
     const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
-    uint4 early[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    uint4 early_t = make_uint4(0, 0, 0, 0), early_f = make_uint4(0, 0, 0, 0);
     if (early_ok) {
-        if (a.res_tiles) early[0] = *(const uint4*)((const T*)a.res_tiles + t);
-        if (a.res_full) early[1] = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+        if (a.res_tiles) early_t = *(const uint4*)((const T*)a.res_tiles + t);
+        if (a.res_full) early_f = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
     }
     float v[N], bv[N];
     const bool vec4 = (a.Cout & 3) == 0 && o + N <= a.Cout;
@@ -577,12 +584,14 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     } else {
         for (int s = 0; s < a.ksplit; ++s) {
             const float* __restrict__ src = a.partial + s * a.partial_stride + t;
-            for (int i = 0; i < N && o + i < a.Cout; ++i) v[i] += src[i];
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+                if (o + i < a.Cout) v[i] += src[i];
         }
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) v[i] += bv[i];
-    emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok ? early : nullptr);
+    emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok, early_t, early_f);
 }
 
 // ---- 1x1 convolutions with few rows ------------------------------------------------------------
@@ -597,18 +606,20 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
 // covers 16 rows, one request per row).  That is not the MFMA operand layout, so each pair of steps
 // passes through a buffer in LDS that belongs to the wave alone: written as loaded, read back as
 // operands, no workgroup barrier involved.
-template <typename T, int W, int P, int TN>
+template <typename T, int W, int P, int TM, int TN>
 __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
 {
     constexpr int KS = Mma<T>::KSTEP, S = (int)sizeof(T), N = Vec16<T>::N;
-    constexpr int TM = 2, BM = 32 * TM, BN = 32 * TN, RS = BN + 4;
+    constexpr int BM = 32 * TM, BN = 32 * TN, RS = BN + 4;
+    constexpr int NI = BM / 16;                               // load instructions per pair of K steps: 16 rows each
     constexpr int AROW = 80;                                  // bytes per row in the wave's buffer: 64 + pad
-    constexpr int ABUF = BM * AROW;                           // one pair of K steps of 64 rows
+    constexpr int ABUF = BM * AROW;                           // one pair of K steps of the patch rows
     static_assert(2 * KS * S == 64, "two K steps of one row are 64 bytes");
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
     float* red = reinterpret_cast<float*>(lds4);              // [W][BM][RS], after the K loop
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: the K loop is uniform
     const int pb = a.bh * a.bw;
     const int r0 = blockIdx.y * BM;
     const bool fused = a.x != nullptr;
@@ -624,7 +635,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
         wp[tn] = (const u32x4*)a.w + (long)min((int)blockIdx.x * TN + tn, ntn_total - 1) * kcs * 64 + lane;
-    u32x4 ra[P][4], rb[P][TN][2];
+    u32x4 ra[P][NI], rb[P][TN][2];
     auto fetch_b = [&](int st, int q) {
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
@@ -636,12 +647,12 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
 #pragma unroll
     for (int st = 0; st < P; ++st) fetch_b(st, q0 + st);
 
-    // rows this lane loads from: row 16*i + lane/4 of the patch, i = 0..3, clamped to rows that exist;
+    // rows this lane loads from: row 16*i + lane/4 of the patch, i < NI, clamped to rows that exist;
     // in fused mode the block origins are fetched together with the count (row n exists for
     // n < max_blocks)
-    int oy[4], ox[4], rr[4];
+    int oy[NI], ox[NI], rr[NI];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NI; ++i) {
         rr[i] = r0 + 16 * i + (lane >> 2);
         oy[i] = ox[i] = 0;
         if (fused) {
@@ -651,24 +662,24 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         }
     }
     int n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
-    asm volatile("" : "+v"(oy[0]), "+v"(ox[0]), "+v"(oy[1]), "+v"(ox[1]), "+v"(oy[2]), "+v"(ox[2]), "+v"(oy[3]),
-                 "+v"(ox[3]), "+v"(n_eff));
+#pragma unroll
+    for (int i = 0; i < NI; ++i) asm volatile("" : "+v"(oy[i]), "+v"(ox[i]), "+v"(n_eff));
     const int rows = n_eff * pb;
     if (r0 >= rows) return;
-    // the epilogue needs the origin of every row's block again: waves 0..3 hold those of rows
-    // 16*wave + lane/4 (the i = wave entry of what they just fetched)
+    // the epilogue needs the origin of every row's block again: the first NI waves hold those of
+    // rows 16*wave + lane/4 (the i = wave entry of what they just fetched)
     __shared__ int org[2 * BM];
-    if (fused && wave < 4 && (lane & 3) == 0) {
+    if (fused && wave < NI && (lane & 3) == 0) {
         int yy = oy[0], xx = ox[0];
-        if (wave == 1) { yy = oy[1]; xx = ox[1]; }
-        if (wave == 2) { yy = oy[2]; xx = ox[2]; }
-        if (wave == 3) { yy = oy[3]; xx = ox[3]; }
+#pragma unroll
+        for (int i = 1; i < NI; ++i)
+            if (wave == i) { yy = oy[i]; xx = ox[i]; }
         org[2 * (16 * wave + (lane >> 2))] = yy;
         org[2 * (16 * wave + (lane >> 2)) + 1] = xx;
     }
-    const char* __restrict__ rp[4];
+    const char* __restrict__ rp[NI];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NI; ++i) {
         const int r = min(rr[i], rows - 1);
         long pixel = r;
         long ld = a.Cin;
@@ -685,7 +696,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
     }
     auto fetch_a = [&](int st, int q) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < NI; ++i)
             ra[st][i] = *(q < q1 ? (const u32x4*)(rp[i] + (long)q * 64) : idle);
     };
 #pragma unroll
@@ -705,10 +716,14 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
     for (int q = q0; q < q1; q += P) {
 #pragma unroll
         for (int st = 0; st < P; ++st) {
-            if (q + st < q1) {                                 // the same for the whole wave
+            {
+                // no branch in the loop body: a stage past the wave's share multiplies zero rows, and the
+                // number of loads in flight at every wait is known at compile time
+                const bool live = q + st < q1;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
                 char* const buf = abuf + (st & 1) * ABUF;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) *(u32x4*)(buf + 16 * i * AROW + a_wr) = ra[st][i];
+                for (int i = 0; i < NI; ++i) *(u32x4*)(buf + 16 * i * AROW + a_wr) = live ? ra[st][i] : zero;
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) {
@@ -757,10 +772,10 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         }
         // bias and residuals do not depend on the sums: they are fetched before the sums are read
         const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
-        uint4 early[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+        uint4 early_t = make_uint4(0, 0, 0, 0), early_f = make_uint4(0, 0, 0, 0);
         if (early_ok) {
-            if (a.res_tiles) early[0] = *(const uint4*)((const T*)a.res_tiles + t);
-            if (a.res_full) early[1] = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+            if (a.res_tiles) early_t = *(const uint4*)((const T*)a.res_tiles + t);
+            if (a.res_full) early_f = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
         }
         float v[N], bv[N];
 #pragma unroll
@@ -779,7 +794,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         }
 #pragma unroll
         for (int i = 0; i < N; ++i) v[i] += bv[i];
-        emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok ? early : nullptr);
+        emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok, early_t, early_f);
     }
 }
 
@@ -968,8 +983,9 @@ extern "C" int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout,
     return SIGE_OK;
 }
 
-// Whether a call goes to pointwise_kernel, and with how many 32-wide output-channel tiles per
-// workgroup (0 = not): a plain 1x1 (no scale, shift or activation on the way in), an even number of
+// Whether a call goes to pointwise_kernel, and with which patch per workgroup (0 = not; 1: 64 rows
+// x 32 channels, 2: 64 x 64, 3: 32 x 32 where the larger patches would leave most compute units
+// without work): a plain 1x1 (no scale, shift or activation on the way in), an even number of
 // K steps, and few enough rows that its patches do not fill the compute units more than once (then
 // the tiled kernel, which reads every weight once per 128 rows, is the better one).
 static int pointwise_tiles(const sige_geom* g, const ConvArgs& a, int ks, int nl)
@@ -980,23 +996,27 @@ static int pointwise_tiles(const sige_geom* g, const ConvArgs& a, int ks, int nl
         return 0;
     const int kcs = a.Cin / ks;
     if (kcs % 2 || (kcs < 20 && !force)) return 0;          // a short K is the tiled kernel's (one staged chunk)
-    const long mt = ((long)nl * g->block_h * g->block_w + 63) / 64, nt = (a.Cout + 31) / 32;
-    if (mt > 65535) return 0;
-    if (force) return atoi(force) == 2 ? 2 : 1;
+    const long rows = (long)nl * g->block_h * g->block_w;
+    const long mt = (rows + 63) / 64, nt = (a.Cout + 31) / 32;
+    if ((rows + 31) / 32 > 65535) return 0;
+    if (force) return std::min(std::max(atoi(force), 1), 3);
+    // the smallest patch that still fits one workgroup per compute unit
+    if ((rows + 31) / 32 * nt <= 256) return 3;
     if (mt * nt <= 256) return 1;
     if (mt * ((nt + 1) / 2) <= 256) return 2;
     return 0;
 }
 
-template <typename T, int W, int P, int TN>
+template <typename T, int W, int P, int TM, int TN>
 static int launch_pointwise_as(const ConvArgs& a, int nl, hipStream_t st)
 {
-    auto kern = pointwise_kernel<T, W, P, TN>;
-    const size_t lds = std::max((size_t)W * 64 * (32 * TN + 4) * sizeof(float), (size_t)W * 2 * 64 * 80);
+    auto kern = pointwise_kernel<T, W, P, TM, TN>;
+    constexpr int BM = 32 * TM;
+    const size_t lds = std::max((size_t)W * BM * (32 * TN + 4) * sizeof(float), (size_t)W * 2 * BM * 80);
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_conv: cannot reserve %zu bytes of LDS: %s", lds,
                  hipGetErrorString(e));
-    const int mt = (int)(((long)nl * a.bh * a.bw + 63) / 64);
+    const int mt = (int)(((long)nl * a.bh * a.bw + BM - 1) / BM);
     hipLaunchKernelGGL(kern, dim3((a.Cout + 32 * TN - 1) / (32 * TN), mt), dim3(64 * W), lds, st, a);
     SIGE_LAUNCH_CHECK("sige_conv");
     return SIGE_OK;
@@ -1005,7 +1025,8 @@ static int launch_pointwise_as(const ConvArgs& a, int nl, hipStream_t st)
 template <typename T>
 static int launch_pointwise(const ConvArgs& a, int nl, int tiles, hipStream_t st)
 {
-    return tiles == 2 ? launch_pointwise_as<T, 8, 3, 2>(a, nl, st) : launch_pointwise_as<T, 8, 4, 1>(a, nl, st);
+    if (tiles == 3) return launch_pointwise_as<T, 8, 6, 1, 1>(a, nl, st);
+    return tiles == 2 ? launch_pointwise_as<T, 8, 3, 2, 2>(a, nl, st) : launch_pointwise_as<T, 8, 4, 2, 1>(a, nl, st);
 }
 
 template <typename T>

@@ -430,7 +430,7 @@ def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
     ws = Workspace("cuda")
     prev = os.environ.pop("SIGE_CONV_POINTWISE", None)
     try:
-        for mode in (None, "1", "2"):
+        for mode in (None, "1", "2", "3"):
             if mode is None:
                 os.environ.pop("SIGE_CONV_POINTWISE", None)
             else:
