@@ -186,13 +186,29 @@ int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32
                  const void* residual_tiles, const void* residual, int32_t res_ld,
                  void* y, int32_t y_ld, void* stream);
 
+/* Sec. 3.2 "Kernel fusion", the output half: sige_conv on the stacked tiles with sige_scatter
+ * folded into its epilogue - the output tiles never touch HBM.  For layers whose input tiles
+ * already exist (the token-wise layers between Gather and Scatter of Fig. "sige-attention":
+ * the projection that leaves an attention block, keys and values on their way into the
+ * caches).  Arguments as in sige_conv and sige_scatter; the convolution result is rounded
+ * to dt before the residuals are added, as a stored tile would be.  workspace as in
+ * sige_conv.                                                                          */
+int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                      const void* packed_weight, const float* bias,
+                      const int32_t* indices, const int32_t* count, int32_t max_blocks, int32_t n_blocks,
+                      const void* residual_tiles, const void* residual, int32_t res_ld,
+                      void* y, int32_t y_ld, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Sec. 3.2 "Kernel fusion" taken to its end on this hardware: Gather (with Scale+Shift and
  * the nonlinearity), the convolution and Scatter (with the residual additions) in ONE
  * kernel.  The input tile of each active block is gathered from x straight into LDS,
  * multiplied on the matrix cores, and the result goes straight into y - the stacked tiles
- * never touch HBM.  Arguments as in sige_gather / sige_conv / sige_scatter; results are
- * bit-identical to calling those three in sequence (the convolution result is rounded to dt
- * before the residuals are added, as a stored tile would be).  Exactly one of
+ * never touch HBM.  Arguments as in sige_gather / sige_conv / sige_scatter; the convolution
+ * result is rounded to dt before the residuals are added, as a stored tile would be, and the
+ * results are bit-identical to calling those three in sequence whenever both run the same
+ * kernel shape (always, except for a 1x1 convolution with Scale+Shift or an activation, where
+ * sige_conv alone may take the few-row kernel and the fp32 sums are added in another order).
+ * Exactly one of
  *   y         - scatter into the cached output, in place (residuals allowed), or
  *   out_tiles - keep the output tiles [max_blocks][block_h][block_w][Cout] (a shortcut
  *               branch whose tiles a later call adds as residual_tiles)
@@ -247,6 +263,17 @@ int sige_token_norm(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, const
                     int32_t rows_per_count, int32_t max_rows, int32_t n_rows,
                     const float* gamma, const float* beta, float eps,
                     void* y, int32_t y_ld, void* stream);
+
+/* The gather of Fig. "sige-attention" with the token norm above folded in: tiles[n][i][j][:]
+ * = layer norm (as sige_token_norm) of pixel (y0_n + i, x0_n + j) of x, for the active blocks
+ * of a geometry whose tiles are the blocks themselves (k = 1, stride 1, no padding; other
+ * geometries -> SIGE_ERR_UNSUPPORTED).  x is [H_in][W_in][x_ld >= C]; tiles is
+ * [max_blocks][block_h][block_w][C]; a pixel outside x counts as a row of zeros, as in
+ * sige_gather.  indices / count / max_blocks / n_blocks as in sige_gather.              */
+int sige_gather_token_norm(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, const sige_geom* g,
+                           const int32_t* indices, const int32_t* count, int32_t max_blocks,
+                           int32_t n_blocks, const float* gamma, const float* beta, float eps,
+                           void* tiles, void* stream);
 int sige_geglu(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, const int32_t* count,
                int32_t rows_per_count, int32_t max_rows, int32_t n_rows,
                void* y, int32_t y_ld, void* stream);

@@ -22,8 +22,8 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
-           "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
+           "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
 
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.sige_gather_modulated.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
         L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+        L.sige_conv_scatter.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp, sz, vp]
         L.sige_conv_workspace_bytes.restype = ctypes.c_size_t
         L.sige_conv_workspace_bytes.argtypes = [i32, gp, i32, i32, i32]
         L.sige_fused_conv.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp,
@@ -99,6 +100,7 @@ def lib() -> ctypes.CDLL:
         L.sige_packed_weight_bytes.argtypes = [i32, i32, i32, i32]
         L.sige_pack_weight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.sige_token_norm.argtypes = [vp, i32, i32, i32, vp, i32, i32, i32, vp, vp, f32, vp, i32, vp]
+        L.sige_gather_token_norm.argtypes = [vp, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, f32, vp, vp]
         L.sige_geglu.argtypes = [vp, i32, i32, i32, vp, i32, i32, i32, vp, i32, vp]
         L.sige_gn_stats.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp]
         _lib = L
@@ -197,6 +199,19 @@ def sige_conv(tiles, g: Geom, Cin, Cout, packed_weight, bias, count, out_tiles, 
                            _nbytes(workspace), _stream()))
 
 
+def sige_conv_scatter(tiles, g: Geom, indices, count, Cin, Cout, packed_weight, bias, y, *, n_blocks=-1,
+                      max_blocks=None, residual_tiles=None, residual=None, res_ld=None, y_ld=None, workspace=None):
+    """conv on stacked tiles -> scatter in one call: y[block n] = conv(tiles[n]) (+ residuals), in place."""
+    y_ld = y.stride(-2) if y_ld is None else y_ld
+    if residual is not None and res_ld is None:
+        res_ld = residual.stride(-2)
+    mb = tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_conv_scatter(_ptr(tiles), _DT[tiles.dtype], ctypes.byref(g), Cin, Cout, _ptr(packed_weight),
+                                   _ptr(bias), _ptr(indices), _ptr(count), mb, n_blocks, _ptr(residual_tiles),
+                                   _ptr(residual), res_ld or 0, _ptr(y), y_ld, _ptr(workspace), _nbytes(workspace),
+                                   _stream()))
+
+
 def sige_scatter(out_tiles, g: Geom, indices, count, y, *, n_blocks=-1, residual_tiles=None, residual=None,
                  Cout=None, y_ld=None, res_ld=None, max_blocks=None):
     """y[block n] = out_tiles[n] (+ residual_tiles[n]) (+ residual[block n]); y is updated in place."""
@@ -234,6 +249,15 @@ def sige_token_norm(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_row
     _check(lib().sige_token_norm(_ptr(x), _DT[x.dtype], C, x2.stride(0) if x_ld is None else x_ld, _ptr(count),
                                  rows_per_count, mr, n_rows, _ptr(gamma), _ptr(beta), eps, _ptr(y),
                                  y2.stride(0) if y_ld is None else y_ld, _stream()))
+
+
+def sige_gather_token_norm(x, g: Geom, indices, count, tiles, C, *, n_blocks=-1, max_blocks=None, gamma=None,
+                           beta=None, eps=1e-5, x_ld=None):
+    """tiles[n] = layer_norm over the channels of every pixel of block n of x (gather and token norm in one)."""
+    mb = tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_gather_token_norm(_ptr(x), _DT[x.dtype], C, x.stride(-2) if x_ld is None else x_ld,
+                                        ctypes.byref(g), _ptr(indices), _ptr(count), mb, n_blocks, _ptr(gamma),
+                                        _ptr(beta), eps, _ptr(tiles), _stream()))
 
 
 def sige_geglu(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_rows=None, x_ld=None, y_ld=None):

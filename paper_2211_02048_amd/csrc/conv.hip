@@ -73,8 +73,9 @@ struct ConvArgs {
     int trows;  // tile rows staged: (rows-1)*stride + k
     int Cc;     // channels staged per pass (multiple of KSTEP)
     int ps;     // LDS pixel stride in bytes: Cc*size + 16 (the pad spreads pixels over banks)
-    // fused mode (x != nullptr): tiles are gathered from x on the way into LDS and the output is
-    // scattered into y (or stored as tiles when y == nullptr)
+    // gather folded in (x != nullptr): tiles are gathered from x on the way into LDS; scatter folded
+    // in (y != nullptr, indices given): the output goes to the blocks' places in y, residuals added;
+    // otherwise it is stored as tiles in out
     const void* x;
     const int32_t* indices;
     const float* scale;
@@ -171,11 +172,11 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
 
 // Whether the 16-byte paths of emit_run may be taken for this call.
 template <typename T>
-__device__ __forceinline__ bool emit_vec_ok(const ConvArgs& a, bool fused)
+__device__ __forceinline__ bool emit_vec_ok(const ConvArgs& a)
 {
     constexpr int N = Vec16<T>::N;
     return (a.Cout % N == 0) && aligned16_dev(a.out) &&
-           (!fused || a.y == nullptr ||
+           (a.y == nullptr ||
             (a.y_ld % N == 0 && aligned16_dev(a.y) && (!a.res_tiles || aligned16_dev(a.res_tiles)) &&
              (!a.res_full || (a.res_ld % N == 0 && aligned16_dev(a.res_full)))));
 }
@@ -466,8 +467,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int RS = BN + 4;                                // fp32 row stride: pad keeps 16-byte alignment
     float* red = reinterpret_cast<float*>(lds);               // [WK][BM][RS]
-    const bool vec_ok = emit_vec_ok<T>(a, fused);
-    const bool to_y = fused && a.y != nullptr;
+    const bool vec_ok = emit_vec_ok<T>(a);
+    const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
     {
         __syncthreads();
 #pragma unroll
@@ -532,8 +533,7 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     const int pb = a.bh * a.bw;
     const int n = (int)(row / pb), p = (int)(row - (long)n * pb);
     const int py = p / a.bw, px = p - py * a.bw;
-    const bool fused = a.x != nullptr;
-    const bool to_y = fused && a.y != nullptr;
+    const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
     int y0 = 0, x0 = 0, n_eff;
     if (to_y) n_eff = blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, y0, x0);
     else n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
@@ -547,7 +547,7 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     }
     // the residual vectors do not depend on the sums: fetch them first so that they travel together
     // with the shares
-    const bool vec_ok = emit_vec_ok<T>(a, fused);
+    const bool vec_ok = emit_vec_ok<T>(a);
     const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
     uint4 early_t = make_uint4(0, 0, 0, 0), early_f = make_uint4(0, 0, 0, 0);
     if (early_ok) {
@@ -622,7 +622,8 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: the K loop is uniform
     const int pb = a.bh * a.bw;
     const int r0 = blockIdx.y * BM;
-    const bool fused = a.x != nullptr;
+    const bool gathered = a.x != nullptr;                     // rows come from x at the blocks' pixels
+    const bool have_org = a.indices != nullptr;               // needed by the gather and by the scatter epilogue
     const int kcs = a.Cin / KS, np = kcs / 2;                 // K steps, pairs of K steps
     const int q0 = wave * np / W, q1 = (wave + 1) * np / W;   // this wave's pairs
     const int ntn_total = (a.Cout + 31) / 32;
@@ -655,7 +656,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
     for (int i = 0; i < NI; ++i) {
         rr[i] = r0 + 16 * i + (lane >> 2);
         oy[i] = ox[i] = 0;
-        if (fused) {
+        if (have_org) {
             const int n = min(rr[i] / pb, a.max_blocks - 1);
             oy[i] = a.indices[2 * n];
             ox[i] = a.indices[2 * n + 1];
@@ -669,7 +670,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
     // the epilogue needs the origin of every row's block again: the first NI waves hold those of
     // rows 16*wave + lane/4 (the i = wave entry of what they just fetched)
     __shared__ int org[2 * BM];
-    if (fused && wave < NI && (lane & 3) == 0) {
+    if (have_org && wave < NI && (lane & 3) == 0) {
         int yy = oy[0], xx = ox[0];
 #pragma unroll
         for (int i = 1; i < NI; ++i)
@@ -683,7 +684,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         const int r = min(rr[i], rows - 1);
         long pixel = r;
         long ld = a.Cin;
-        if (fused) {
+        if (gathered) {
             const int n = r / pb, p = r - n * pb;
             const int py = p / a.bw, px = p - py * a.bw;
             // the origin fetched above belongs to row rr; a clamped row reads the last block's
@@ -692,7 +693,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
             pixel = (long)min(y0 + py, a.Hin - 1) * a.Win + min(x0 + px, a.Win - 1);
             ld = a.x_ld;
         }
-        rp[i] = (fused ? (const char*)a.x : (const char*)a.tiles) + pixel * ld * S + (lane & 3) * 16;
+        rp[i] = (gathered ? (const char*)a.x : (const char*)a.tiles) + pixel * ld * S + (lane & 3) * 16;
     }
     auto fetch_a = [&](int st, int q) {
 #pragma unroll
@@ -755,8 +756,8 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
                 red[(wave * BM + m) * RS + tn * 32 + l32] = acc[tm][tn][r];
             }
     __syncthreads();
-    const bool vec_ok = emit_vec_ok<T>(a, fused);
-    const bool to_y = fused && a.y != nullptr;
+    const bool vec_ok = emit_vec_ok<T>(a);
+    const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
     for (int e = tid; e < BM * (BN / N); e += 64 * W) {
         const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
         const int r = r0 + m, o = blockIdx.x * BN + nn;
@@ -1040,7 +1041,7 @@ static int launch_reduce(const ConvArgs& a, int nl, hipStream_t st)
     return SIGE_OK;
 }
 
-// Shared by sige_conv and sige_fused_conv: plan, fill the arguments, launch.
+// Shared by sige_conv, sige_conv_scatter and sige_fused_conv: plan, fill the arguments, launch.
 static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, int tw, int Cin, int Cout,
                     int max_blocks, int n_blocks, int nl, ConvArgs& a, void* workspace, size_t workspace_bytes,
                     void* stream)
@@ -1112,6 +1113,35 @@ extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, i
     if (nl == 0) return SIGE_OK;
     ConvArgs a = {};
     a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
+    return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
+}
+
+extern "C" int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                                 const void* packed_weight, const float* bias, const int32_t* indices,
+                                 const int32_t* count, int32_t max_blocks, int32_t n_blocks,
+                                 const void* residual_tiles, const void* residual, int32_t res_ld, void* y,
+                                 int32_t y_ld, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    const char* who = "sige_conv_scatter";
+    int th, tw, nl;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(tiles && packed_weight && indices && y, SIGE_ERR_INVALID_ARG,
+                 "%s: tiles, packed_weight, indices and y are required", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cin > 0 && Cout > 0 && y_ld >= Cout, SIGE_ERR_INVALID_ARG, "%s: need Cin, Cout > 0 and y_ld >= Cout", who);
+    SIGE_REQUIRE(residual == nullptr || res_ld >= Cout, SIGE_ERR_INVALID_ARG, "%s: res_ld must be >= Cout", who);
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
+    SIGE_REQUIRE(aligned16(tiles) && aligned16(packed_weight), SIGE_ERR_UNSUPPORTED,
+                 "%s: tiles and packed_weight must be 16-byte aligned", who);
+    if (nl == 0) return SIGE_OK;
+    ConvArgs a = {};
+    a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.count = count; a.indices = indices;
+    a.res_tiles = residual_tiles; a.res_full = residual; a.y = y;
+    a.Hin = g->H_in; a.Win = g->W_in; a.pad = g->pad;
+    a.Hout = g->H_out; a.Wout = g->W_out; a.y_ld = y_ld; a.res_ld = res_ld;
     return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
 }
 

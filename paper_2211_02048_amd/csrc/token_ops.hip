@@ -19,6 +19,10 @@ struct RowArgs {
     int C, x_ld, y_ld;
     int rows_per_count, max_rows, n_host;
     float eps;
+    // gather mode (indices != NULL): row r is pixel r % (bh * bw) of block r / (bh * bw) of the
+    // [H][W][x_ld] tensor x; a pixel outside the tensor is a row of zeros, as in a gathered tile
+    const int32_t* indices;
+    int bh, bw, H, W;
 };
 
 __device__ __forceinline__ int effective_rows(const RowArgs& a)
@@ -45,14 +49,23 @@ __global__ __launch_bounds__(256) void token_norm_kernel(RowArgs a)
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= effective_rows(a)) return;
     const int V = a.C / N;                                  // vectors per token
-    const uint4* __restrict__ src = (const uint4*)((const T*)a.x + (long)row * a.x_ld);
+    long pixel = row;
+    bool inside = true;
+    if (a.indices != nullptr) {
+        const int pb = a.bh * a.bw, n = row / pb, p = row - n * pb;
+        const int py = p / a.bw, px = p - py * a.bw;
+        const int iy = a.indices[2 * n] + py, ix = a.indices[2 * n + 1] + px;
+        inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+        pixel = inside ? (long)iy * a.W + ix : 0;
+    }
+    const uint4* __restrict__ src = (const uint4*)((const T*)a.x + pixel * a.x_ld);
     float f[NV][N];
     float s = 0.0f;
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         const int j = lane + 64 * u;
         if (j < V) {
-            unpack<T>(src[j], f[u]);
+            unpack<T>(inside ? src[j] : make_uint4(0, 0, 0, 0), f[u]);
 #pragma unroll
             for (int i = 0; i < N; ++i) s += f[u][i];
         }
@@ -154,6 +167,38 @@ extern "C" int sige_token_norm(const void* x, sige_dtype dt, int32_t C, int32_t 
     RowArgs a;
     a.x = x; a.y = y; a.gamma = gamma; a.beta = beta; a.count = count; a.C = C; a.x_ld = x_ld; a.y_ld = y_ld;
     a.rows_per_count = rows_per_count; a.max_rows = max_rows; a.n_host = n_rows; a.eps = eps;
+    a.indices = nullptr; a.bh = a.bw = a.H = a.W = 0;
+    hipStream_t st = (hipStream_t)stream;
+    return dt == SIGE_F32 ? launch_norm<float>(a, rows, st)
+           : dt == SIGE_F16 ? launch_norm<f16>(a, rows, st) : launch_norm<bf16>(a, rows, st);
+}
+
+extern "C" int sige_gather_token_norm(const void* x, sige_dtype dt, int32_t C, int32_t x_ld, const sige_geom* g,
+                                      const int32_t* indices, const int32_t* count, int32_t max_blocks,
+                                      int32_t n_blocks, const float* gamma, const float* beta, float eps,
+                                      void* tiles, void* stream)
+{
+    clear_error();
+    const char* who = "sige_gather_token_norm";
+    int th, tw, nl;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(indices != nullptr, SIGE_ERR_INVALID_ARG, "%s: indices are required", who);
+    SIGE_REQUIRE(g->k == 1 && g->stride == 1 && g->pad == 0, SIGE_ERR_UNSUPPORTED,
+                 "%s: tokens are the pixels of the blocks themselves (k = 1, stride 1, no padding)", who);
+    const long pb = (long)g->block_h * g->block_w;
+    SIGE_REQUIRE(pb * max_blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "%s: too many tokens", who);
+    int rows;
+    if (int rc = check_rows(who, x, tiles, dt, C, x_ld, C, C, count, (int)pb, (int)(pb * max_blocks),
+                            n_blocks >= 0 ? (int)(pb * n_blocks) : -1, &rows))
+        return rc;
+    SIGE_REQUIRE(C * dtype_size(dt) / 16 <= 512, SIGE_ERR_UNSUPPORTED, "%s: at most 8 KiB per token", who);
+    if (rows == 0) return SIGE_OK;
+    RowArgs a;
+    a.x = x; a.y = tiles; a.gamma = gamma; a.beta = beta; a.count = count; a.C = C; a.x_ld = x_ld; a.y_ld = C;
+    a.rows_per_count = (int)pb; a.max_rows = (int)(pb * max_blocks); a.n_host = n_blocks >= 0 ? (int)(pb * n_blocks) : -1;
+    a.eps = eps;
+    a.indices = indices; a.bh = g->block_h; a.bw = g->block_w; a.H = g->H_in; a.W = g->W_in;
     hipStream_t st = (hipStream_t)stream;
     return dt == SIGE_F32 ? launch_norm<float>(a, rows, st)
            : dt == SIGE_F16 ? launch_norm<f16>(a, rows, st) : launch_norm<bf16>(a, rows, st);
@@ -171,6 +216,7 @@ extern "C" int sige_geglu(const void* x, sige_dtype dt, int32_t C, int32_t x_ld,
     RowArgs a;
     a.x = x; a.y = y; a.gamma = nullptr; a.beta = nullptr; a.count = count; a.C = C; a.x_ld = x_ld; a.y_ld = y_ld;
     a.rows_per_count = rows_per_count; a.max_rows = max_rows; a.n_host = n_rows; a.eps = 0.0f;
+    a.indices = nullptr; a.bh = a.bw = a.H = a.W = 0;
     const long n = (long)rows * (C * (long)dtype_size(dt) / 16);
     const long blocks = (n + 255) / 256;
     SIGE_REQUIRE(blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "%s: too many elements", who);

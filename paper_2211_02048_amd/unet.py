@@ -202,11 +202,10 @@ class SigeUNet:
                           max_blocks=nb, workspace=split)
             return out
 
-        def normed(src_full, part):
-            t = tiles("x_t", C)
-            api.sige_gather(src_full, g1, idx, cnt, t, n_blocks=nb, max_blocks=nb)
+        def normed(src_full, part):      # gather with the token norm folded in
             tn = tiles("x_n", C)
-            api.sige_token_norm(t, tn, C, n_rows=rows, gamma=L[part + ".g"], beta=L[part + ".b"], eps=1e-5)
+            api.sige_gather_token_norm(src_full, g1, idx, cnt, tn, C, n_blocks=nb, max_blocks=nb,
+                                       gamma=L[part + ".g"], beta=L[part + ".b"], eps=1e-5)
             return tn
 
         def attend(q, k, v, Tk, kv_ld):
@@ -217,8 +216,11 @@ class SigeUNet:
                                  d=d, q_ld=C, kv_ld=kv_ld, o_ld=C)
             return o
 
-        def back(out_tiles, dst, residual):
-            api.sige_scatter(out_tiles, g1, idx, cnt, dst, n_blocks=nb, residual=residual, Cout=C, max_blocks=nb)
+        def back(layer, src, dst, residual=None):      # convolution with the scatter folded in
+            nbytes = api.sige_conv_workspace_bytes(self.td, layer.g, layer.Cin, layer.Cout, nb)
+            split = ws.get("split_k", nbytes // 4, torch.float32) if nbytes else None
+            api.sige_conv_scatter(src, layer.g, idx, cnt, layer.Cin, layer.Cout, layer.packed, layer.bias, dst,
+                                  n_blocks=nb, max_blocks=nb, residual=residual, workspace=split)
 
         if dense:   # keys and values of the text embeddings do not depend on the image
             one = torch.ones(1, dtype=torch.int32, device=self.device)
@@ -229,22 +231,21 @@ class SigeUNet:
         # self-attention: only the active tokens' queries; their keys and values go into the caches first
         tn = normed(L["h0"], "ln1")
         q = conv(L["q1"], tn, "x_q")
-        kv = conv(L["kv1"], tn, "x_kv")
-        api.sige_scatter(kv, g1, idx, cnt, L["kv"], n_blocks=nb, Cout=2 * C, max_blocks=nb)
+        back(L["kv1"], tn, L["kv"])
         kvc = L["kv"].view(T, 2 * C)
         o = attend(q, kvc[:, :C], kvc[:, C:], T, 2 * C)
-        back(conv(L["o1"], o, "x_p"), L["h1"], L["h0"])
+        back(L["o1"], o, L["h1"], L["h0"])
         # cross-attention over the text embeddings
         tn = normed(L["h1"], "ln2")
         q = conv(L["q2"], tn, "x_q")
         o = attend(q, L["kc"][:, :C], L["kc"][:, C:], L["kc"].shape[0], 2 * C)
-        back(conv(L["o2"], o, "x_p"), L["h2"], L["h1"])
+        back(L["o2"], o, L["h2"], L["h1"])
         # gated-GELU feed-forward
         tn = normed(L["h2"], "ln3")
         u = conv(L["ff1"], tn, "x_u")
         gg = tiles("x_g", 4 * C)
         api.sige_geglu(u, gg, 4 * C, n_rows=rows)
-        back(conv(L["ff2"], gg, "x_p"), L["h3"], L["h2"])
+        back(L["ff2"], gg, L["h3"], L["h2"])
         L["out"].forward(L["h3"], y, bl, ws, residual=x, fused=True)
 
     def precompute(self, image):

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import assert_close, assert_mostly_close, dev, f64
+from helpers import expected_tiles, assert_close, assert_mostly_close, dev, f64
 from paper_2211_02048_amd import api, inputs
 
 pytestmark = pytest.mark.gpu
@@ -243,3 +243,40 @@ def test_token_norm_and_geglu(oracle, dtype, C, rows):
         api.sige_token_norm(x, y, C, n_rows=rows + 100, x_ld=ld)          # more rows than max_rows
     with pytest.raises(api.SigeError):
         api.sige_token_norm(x, y, C, n_rows=-1, x_ld=ld)                  # no count
+
+
+@pytest.mark.parametrize("dtype,C,res,b,n", [("bf16", 320, 22, 4, 9), ("f16", 1280, 16, 8, 3), ("f32", 64, 13, 5, 6)])
+def test_gather_token_norm(oracle, dtype, C, res, b, n):
+    """The gather with the token norm folded in: against the oracle's layer norm of the gathered
+    pixels (a pixel outside the tensor is a row of zeros), bit for bit against gather + token norm,
+    both count paths, a wider pixel stride, tiles beyond the count untouched, geometry errors."""
+    rng = np.random.default_rng(C + res)
+    td = DT[dtype]
+    ld = C + (16 if dtype == "f32" else 32)
+    buf = torch.from_numpy((rng.standard_normal((res, res, ld)) * 2.0 + 0.5).astype(np.float32)).to(td).cuda()
+    x = buf[:, :, :C]
+    g = api.geom(res, res, b, 1, 1, 0)
+    nby = -(-res // b)
+    pick = np.sort(rng.permutation(nby * nby)[:n])
+    pick[-1] = nby * nby - 1                      # the bottom-right block sticks out when b does not divide res
+    blocks = np.array([((i // nby) * b, (i % nby) * b) for i in np.unique(pick)], np.int32)
+    n = len(blocks)
+    idx = torch.from_numpy(blocks).cuda()
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    gamma = torch.from_numpy(rng.uniform(0.5, 1.5, C).astype(np.float32))
+    beta = torch.from_numpy(rng.uniform(-0.5, 0.5, C).astype(np.float32))
+    tiles = torch.full((n + 2, b, b, C), 7.0, dtype=td, device="cuda")
+    api.sige_gather_token_norm(x, g, idx, cnt, tiles, C, n_blocks=n, gamma=dev(gamma), beta=dev(beta), eps=1e-5)
+    gathered = expected_tiles(oracle, f64(x), blocks, b, b, 1, 0, None, None, 0)
+    want = oracle.layer_norm(gathered.reshape(-1, C), f64(gamma), f64(beta), 1e-5).reshape(n, b, b, C)
+    assert_close(tiles[:n], want, td, "gather + token norm")
+    assert (tiles[n:] == 7.0).all()
+    t0 = torch.full((n + 2, b, b, C), 7.0, dtype=td, device="cuda")
+    api.sige_gather(x, g, idx, cnt, t0, n_blocks=n, C=C)
+    api.sige_token_norm(t0, t0, C, n_rows=n * b * b, gamma=dev(gamma), beta=dev(beta), eps=1e-5)
+    assert torch.equal(t0, tiles), "the folded call differs from gather followed by token norm"
+    t1 = torch.full((n + 2, b, b, C), 7.0, dtype=td, device="cuda")
+    api.sige_gather_token_norm(x, g, idx, cnt, t1, C, n_blocks=-1, gamma=dev(gamma), beta=dev(beta), eps=1e-5)
+    assert torch.equal(t1, tiles)
+    with pytest.raises(api.SigeError):
+        api.sige_gather_token_norm(x, api.geom(res, res, b, 3, 1, 1), idx, cnt, tiles, C, n_blocks=n)

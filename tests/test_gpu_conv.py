@@ -473,6 +473,55 @@ def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
             os.environ["SIGE_CONV_POINTWISE"] = prev
 
 
+@pytest.mark.parametrize("dtype,Cin,Cout,res,b,k,n", [
+    ("bf16", 320, 320, 22, 5, 1, 9), ("f16", 1280, 64, 16, 8, 1, 3), ("f16", 128, 128, 40, 16, 3, 4),
+    ("f16", 512, 96, 16, 8, 3, 4), ("f32", 64, 40, 20, 6, 3, 7)])
+def test_conv_scatter(oracle, dtype, Cin, Cout, res, b, k, n):
+    """The convolution on stacked tiles with the scatter folded into its epilogue: bit for bit what
+    sige_conv followed by sige_scatter give (few-row kernel, tiled kernel, K split with a workspace),
+    residuals included, both count paths; against the oracle; y outside the blocks untouched."""
+    rng = np.random.default_rng(Cin + Cout + res + k)
+    td = DT[dtype]
+    w, bias = inputs.conv_params(rng, Cout, Cin, k, td)
+    conv = SigeConv(dev(w), bias, res, res, b, 1, k // 2)
+    g = conv.g
+    nby = -(-res // b)
+    pick = np.unique(np.append(rng.permutation(nby * nby)[:n - 1], nby * nby - 1))
+    blocks = np.array([((i // nby) * b, (i % nby) * b) for i in pick], np.int32)
+    n = len(blocks)
+    idx = torch.from_numpy(blocks).cuda()
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    tiles = torch.from_numpy(rng.standard_normal((n + 1, g.tile_h, g.tile_w, Cin)).astype(np.float32)).to(td).cuda()
+    resid = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td).cuda()
+    rtiles = torch.from_numpy(rng.standard_normal((n + 1, b, b, Cout)).astype(np.float32)).to(td).cuda()
+    cache = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td).cuda()
+    nbytes = api.sige_conv_workspace_bytes(td, g, Cin, Cout, n + 1)
+    split = torch.full((max(nbytes // 4, 1),), float("nan"), device="cuda") if nbytes else None
+    out_mask = torch.from_numpy(outside_blocks_mask(blocks, b, b, res, res)).cuda()
+    vec = Cout % (4 if dtype == "f32" else 8) == 0       # sige_scatter needs 16-byte channel runs
+    for nb, mb in ((n, n), (-1, n + 1)):
+        for rt, rf in ((None, None), (rtiles, resid)):
+            y = cache.clone()
+            api.sige_conv_scatter(tiles, g, idx, cnt, Cin, Cout, conv.packed, conv.bias, y, n_blocks=nb, max_blocks=mb,
+                                  residual_tiles=rt, residual=rf, workspace=split)
+            assert torch.equal(y[out_mask], cache[out_mask])
+            if vec:
+                o = torch.empty((n + 1, b, b, Cout), dtype=td, device="cuda")
+                api.sige_conv(tiles, g, Cin, Cout, conv.packed, conv.bias, cnt, o, n_blocks=nb, max_blocks=mb, workspace=split)
+                y2 = cache.clone()
+                api.sige_scatter(o, g, idx, cnt, y2, n_blocks=nb, residual_tiles=rt, residual=rf, max_blocks=mb)
+                assert torch.equal(y, y2), "conv + scatter folded differs from the two calls"
+            want_t = np.stack([oracle.conv2d(f64(tiles[i]), f64(w), f64(bias), 1, 0) for i in range(n)])
+            want = f64(cache)
+            for i, (y0, x0) in enumerate(blocks):
+                h, wd = min(b, res - y0), min(b, res - x0)
+                blk = round_to(want_t[i], td)[:h, :wd]
+                if rt is not None:
+                    blk = blk + f64(rtiles[i])[:h, :wd] + f64(resid)[y0:y0 + h, x0:x0 + wd]
+                want[y0:y0 + h, x0:x0 + wd] = blk
+            assert_close(y, want, td, f"conv_scatter n_blocks={nb} residuals={rt is not None}")
+
+
 # ------------------------------------------------------------------ the whole layer
 
 def sparse_layer(cfg, *, fused, shortcut=False, device_count=False, cache=None):
