@@ -868,9 +868,9 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     if (best_score < 0.0) return false;
     // K split over workgroups.  A workgroup walks through its channel chunks one after the other and
     // each costs a staging round trip (a few microseconds), so a call with at most one workgroup per
-    // compute unit and at least three full chunks is cut along K (up to four workgroups per compute
-    // unit; with fewer chunks the second kernel costs more than it saves); smaller chunks when that
-    // is what it takes to reach 256 workgroups.
+    // compute unit and at least three chunks (320 channels or more in the half types) is cut along K
+    // (up to four workgroups per compute unit; with fewer chunks the second kernel costs more than it
+    // saves); smaller chunks when that is what it takes to reach 256 workgroups.
     ConvPlan& p = *best;
     const char* force_split = getenv("SIGE_CONV_SPLIT");
     const long wgs = (long)p.groups * p.bands * p.slabs;
@@ -882,7 +882,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         if (kc == 8 && wgs * (Cin / (8 * kstep)) < 256 && 4 % WK == 0 && !force_kc) kc = 4;
         const int nch = Cin / (kc * kstep);
         int S = 1;
-        if (wgs <= 256 && Cin >= 3 * 8 * kstep) S = (int)std::min<long>(nch, (1024 + wgs - 1) / wgs);
+        if (wgs <= 256 && nch >= 3 && Cin >= 20 * kstep) S = (int)std::min<long>(nch, (1024 + wgs - 1) / wgs);
         if (force_split) S = std::min(atoi(force_split), nch);
         S = std::max(1, std::min(S, max_by_ws));
         if (S > 1) {
@@ -1004,7 +1004,7 @@ static int pointwise_tiles(const sige_geom* g, const ConvArgs& a, int ks, int nl
     // the smallest patch that still fits one workgroup per compute unit
     if ((rows + 31) / 32 * nt <= 256) return 3;
     if (mt * nt <= 256) return 1;
-    if (mt * ((nt + 1) / 2) <= 256) return 2;
+    if (mt * ((nt + 1) / 2) <= (kcs >= 64 ? 512 : 256)) return 2;   // a long K: better two rounds here than the tiled kernel's chunks
     return 0;
 }
 
