@@ -46,6 +46,18 @@ typedef enum { SIGE_F32 = 0, SIGE_F16 = 1, SIGE_BF16 = 2 } sige_dtype;
 typedef enum { SIGE_ACT_NONE = 0, SIGE_ACT_SILU = 1, SIGE_ACT_RELU = 2,
                SIGE_ACT_LEAKY_RELU = 3 /* slope 0.2 for negative inputs */ } sige_act;
 
+/* An activated copy of a layer's output (host struct, see sige_fused_conv): y is a device
+ * tensor with the pixel grid of the layer's output and pixel stride y_ld >= Cout; scale and
+ * shift are fp32 [Cout] device arrays (both NULL: 1 and 0).                              */
+typedef struct sige_act_out {
+    void* y;
+    int32_t y_ld;
+    const float* scale;
+    const float* shift;
+    sige_act act;
+} sige_act_out;
+#define SIGE_MAX_ACT_OUTS 3
+
 /* Geometry of one wrapped convolution (host struct).  The output is cut into
  * block_h x block_w blocks anchored at (0,0); edge blocks may be partial.  The
  * input tile of a block is tile = (block-1)*stride + k pixels per side and starts
@@ -215,7 +227,17 @@ int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int3
  * must be given.  x and y must not overlap (a tile's halo belongs to other blocks).
  * workspace: as for sige_conv (the reduction kernel then also adds the residuals and
  * scatters); bit-identity with the three calls holds when sige_conv gets a workspace of
- * the same size.                                                                      */
+ * the same size.
+ * act_outs (n_act_outs of them, 0..SIGE_MAX_ACT_OUTS; scatter mode only): Sec. 3.2
+ * "Pre-computing normalization parameters" makes the Scale+Shift of the NEXT layer a
+ * constant per channel, so the layer that produces a tensor can apply it, and the
+ * nonlinearity, to each value once instead of every gathering workgroup doing so again:
+ * besides y[p][o] = v, copy j receives
+ *   act_outs[j].y[p][o] = act_j(scale_j[o] * v + shift_j[o])
+ * computed in fp32 from the stored (rounded) v, i.e. bit for bit what a fused gather of y
+ * with the same scale, shift and activation would read.  A consumer then gathers the copy
+ * without Scale+Shift.  Needs Cout * size and all pixel strides to be multiples of 16 bytes
+ * (else SIGE_ERR_UNSUPPORTED).                                                        */
 int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
                     const sige_geom* g, const int32_t* indices, const int32_t* count,
                     int32_t max_blocks, int32_t n_blocks,
@@ -223,6 +245,7 @@ int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int
                     int32_t Cout, const void* packed_weight, const float* bias,
                     const void* residual_tiles, const void* residual, int32_t res_ld,
                     void* y, int32_t y_ld, void* out_tiles,
+                    const sige_act_out* act_outs, int32_t n_act_outs,
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* Fig. "sige-attention" / Sec. 3.2 "Extension to attention layers": attention for the

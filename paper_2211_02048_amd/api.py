@@ -93,7 +93,7 @@ def lib() -> ctypes.CDLL:
         L.sige_conv_workspace_bytes.restype = ctypes.c_size_t
         L.sige_conv_workspace_bytes.argtypes = [i32, gp, i32, i32, i32]
         L.sige_fused_conv.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp,
-                                      i32, vp, i32, vp, vp, sz, vp]
+                                      i32, vp, i32, vp, vp, i32, vp, sz, vp]
         L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
         L.sige_sparse_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
         L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
@@ -225,10 +225,28 @@ def sige_scatter(out_tiles, g: Geom, indices, count, y, *, n_blocks=-1, residual
                               _ptr(y), y_ld, _stream()))
 
 
+class ActOut(ctypes.Structure):
+    """Mirror of sige_act_out."""
+    _fields_ = [("y", ctypes.c_void_p), ("y_ld", ctypes.c_int32), ("scale", ctypes.c_void_p),
+                ("shift", ctypes.c_void_p), ("act", ctypes.c_int32)]
+
+
+def act_out_array(act_outs):
+    """[(y, scale, shift, act), ...] (device tensors; y a [H, W, >=Cout] view) -> a ctypes array of sige_act_out."""
+    arr = (ActOut * len(act_outs))()
+    for a, (y, scale, shift, act) in zip(arr, act_outs):
+        a.y, a.y_ld, a.scale, a.shift, a.act = _ptr(y), y.stride(-2), _ptr(scale), _ptr(shift), act
+    return arr
+
+
 def sige_fused_conv(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, *, y=None, out_tiles=None,
                     n_blocks=-1, max_blocks=None, scale=None, shift=None, act=ACT_NONE, up=0, x_ld=None,
-                    residual_tiles=None, residual=None, res_ld=None, y_ld=None, workspace=None):
-    """gather -> conv -> scatter in one kernel; y is updated in place (or out_tiles receives the tiles)."""
+                    residual_tiles=None, residual=None, res_ld=None, y_ld=None, workspace=None, act_outs=None):
+    """gather -> conv -> scatter in one kernel; y is updated in place (or out_tiles receives the tiles).
+    act_outs: [(y, scale, shift, act), ...] or a prepared act_out_array - activated copies of the output."""
+    if act_outs is not None and not isinstance(act_outs, ctypes.Array):
+        act_outs = act_out_array(act_outs)
+    n_ao = 0 if act_outs is None else len(act_outs)
     x_ld = x.stride(-2) if x_ld is None else x_ld
     if y is not None and y_ld is None:
         y_ld = y.stride(-2)
@@ -238,7 +256,8 @@ def sige_fused_conv(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, 
     _check(lib().sige_fused_conv(_ptr(x), _DT[x.dtype], Cin, x_ld, up, ctypes.byref(g), _ptr(indices), _ptr(count),
                                  mb, n_blocks, _ptr(scale), _ptr(shift), act, Cout, _ptr(packed_weight), _ptr(bias),
                                  _ptr(residual_tiles), _ptr(residual), res_ld or 0, _ptr(y), y_ld or 0,
-                                 _ptr(out_tiles), _ptr(workspace), _nbytes(workspace), _stream()))
+                                 _ptr(out_tiles), act_outs if n_ao else None, n_ao, _ptr(workspace),
+                                 _nbytes(workspace), _stream()))
 
 
 def sige_token_norm(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_rows=None, gamma=None, beta=None,

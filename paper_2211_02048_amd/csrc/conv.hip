@@ -90,6 +90,11 @@ struct ConvArgs {
     float* partial;
     long partial_stride;
     int ksplit, bands;
+    // activated copies of the output (scatter mode only): copy j receives
+    // act_j(scale_j[o] * v + shift_j[o]) of every value v stored to y, at the same pixel
+    struct ActOut { void* y; const float* scale; const float* shift; int ld, act; };
+    ActOut ao[SIGE_MAX_ACT_OUTS];
+    int n_ao;
 };
 
 // Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
@@ -147,6 +152,21 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
                 r = pack<T>(f);
             }
             *(uint4*)((T*)a.y + pix * a.y_ld + o) = r;
+            // the next layers' normalisation and nonlinearity, applied here once instead of by every
+            // workgroup that later gathers this pixel (from the stored, rounded value)
+#pragma unroll
+            for (int j = 0; j < SIGE_MAX_ACT_OUTS; ++j) {
+                if (j >= a.n_ao) break;
+                float f[N], sc[N], sh[N];
+                unpack<T>(r, f);
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    sc[i] = a.ao[j].scale ? a.ao[j].scale[o + i] : 1.0f;
+                    sh[i] = a.ao[j].scale ? a.ao[j].shift[o + i] : 0.0f;
+                }
+                scale_shift_act<N>(f, sc, sh, a.ao[j].act);
+                *(uint4*)((T*)a.ao[j].y + pix * a.ao[j].ld + o) = pack<T>(f);
+            }
         } else {
             *(uint4*)(out + t) = r;
         }
@@ -1150,8 +1170,8 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
                                int32_t max_blocks, int32_t n_blocks, const float* scale, const float* shift,
                                sige_act act, int32_t Cout, const void* packed_weight, const float* bias,
                                const void* residual_tiles, const void* residual, int32_t res_ld, void* y,
-                               int32_t y_ld, void* out_tiles, void* workspace, size_t workspace_bytes,
-                               void* stream)
+                               int32_t y_ld, void* out_tiles, const sige_act_out* act_outs, int32_t n_act_outs,
+                               void* workspace, size_t workspace_bytes, void* stream)
 {
     clear_error();
     const char* who = "sige_fused_conv";
@@ -1178,8 +1198,32 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
     SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
     SIGE_REQUIRE((x_ld * s) % 16 == 0 && aligned16(x) && aligned16(packed_weight), SIGE_ERR_UNSUPPORTED,
                  "%s: x and packed_weight must be 16-byte aligned and x_ld a multiple of %zu elements", who, 16 / s);
+    SIGE_REQUIRE(n_act_outs >= 0 && n_act_outs <= SIGE_MAX_ACT_OUTS && (n_act_outs == 0 || act_outs != nullptr),
+                 SIGE_ERR_INVALID_ARG, "%s: between 0 and %d activated copies", who, SIGE_MAX_ACT_OUTS);
+    SIGE_REQUIRE(n_act_outs == 0 || y != nullptr, SIGE_ERR_INVALID_ARG,
+                 "%s: activated copies are written beside the scatter; they need y", who);
+    if (n_act_outs > 0) {
+        // they are written from the 16-byte path of the epilogue only
+        SIGE_REQUIRE((Cout * s) % 16 == 0 && (y_ld * s) % 16 == 0 && aligned16(y) &&
+                     (residual == nullptr || ((res_ld * s) % 16 == 0 && aligned16(residual))) &&
+                     (residual_tiles == nullptr || aligned16(residual_tiles)),
+                     SIGE_ERR_UNSUPPORTED, "%s: activated copies need 16-byte channel runs in y and the residuals", who);
+        for (int j = 0; j < n_act_outs; ++j) {
+            const sige_act_out& o = act_outs[j];
+            SIGE_REQUIRE(o.y != nullptr && o.y_ld >= Cout && (o.scale == nullptr) == (o.shift == nullptr) &&
+                         act_ok((int)o.act), SIGE_ERR_INVALID_ARG, "%s: bad activated copy %d", who, j);
+            SIGE_REQUIRE((o.y_ld * s) % 16 == 0 && aligned16(o.y), SIGE_ERR_UNSUPPORTED,
+                         "%s: activated copy %d must be 16-byte aligned with a pixel stride that is a multiple of %zu elements",
+                         who, j, 16 / s);
+        }
+    }
     if (nl == 0) return SIGE_OK;
     ConvArgs a = {};
+    a.n_ao = n_act_outs;
+    for (int j = 0; j < n_act_outs; ++j) {
+        a.ao[j].y = act_outs[j].y; a.ao[j].scale = act_outs[j].scale; a.ao[j].shift = act_outs[j].shift;
+        a.ao[j].ld = act_outs[j].y_ld; a.ao[j].act = (int)act_outs[j].act;
+    }
     a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
     a.x = x; a.indices = indices; a.scale = scale; a.shift = shift;
     a.res_tiles = residual_tiles; a.res_full = residual; a.y = y;

@@ -100,9 +100,10 @@ class SigeConv:
 
     def forward(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None,
                 act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False,
-                split_k=True, mod=None):
+                split_k=True, mod=None, act_outs=None):
         """gather(x) -> conv -> scatter into y (in place), as three calls or as the one fused call
-        (a modulated gather, mod given, always runs as three calls).
+        (a modulated gather, mod given, always runs as three calls).  act_outs: activated copies of
+        the output for the layers that normalise it next (the fused call only).
         Returns the output tiles (None when the fused call scattered them directly)."""
         g, n = self.g, blocks.n_host
         cap = blocks.max_blocks if n < 0 else max(n, 1)
@@ -118,8 +119,9 @@ class SigeConv:
             api.sige_fused_conv(x, g, blocks.indices, blocks.count, self.Cin, self.Cout, self.packed, self.bias,
                                 y=y if scatter else None, out_tiles=out_tiles, n_blocks=n, max_blocks=cap,
                                 scale=scale, shift=shift, act=act, up=self.up, residual_tiles=residual_tiles,
-                                residual=residual, workspace=split)
+                                residual=residual, workspace=split, act_outs=act_outs if scatter else None)
             return out_tiles
+        assert not act_outs, "activated copies are written by the fused call only"
         tiles = ws.get("tiles", self.tiles_numel(cap), self.dtype)
         out_tiles = ws.get("out_" + tag, self.out_numel(cap), self.dtype)
         if mod is None:

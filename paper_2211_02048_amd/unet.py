@@ -31,7 +31,8 @@ def _next_pow2(n: int) -> int:
 class SigeUNet:
     def __init__(self, res=256, channels=(128, 128, 256, 256, 512, 512), attn_res=(16,), heads=4,
                  dtype="f16", seed=1003, device="cuda", block=16, groups=32, eps=1e-5, dilate=1,
-                 min_sparse_res=64, params=None, fused=True, in_ch=3, attn_kind="attn", ctx=(77, 768)):
+                 min_sparse_res=64, params=None, fused=True, in_ch=3, attn_kind="attn", ctx=(77, 768),
+                 act_copies=True):
         self.res, self.device, self.td = res, device, inputs.DTYPES[dtype]
         self.block, self.groups, self.eps, self.dilate, self.min_sparse_res = block, groups, eps, dilate, min_sparse_res
         self.bufs_shape, self.ops = inputs.unet_topology(res, in_ch, channels, attn_res, heads, attn_kind=attn_kind,
@@ -99,6 +100,58 @@ class SigeUNet:
                 L["scale"] = torch.zeros(C, device=device)
                 L["shift"] = torch.zeros(C, device=device)
             self.layers[n] = L
+        # Activated copies (Sec. 3.2 "Pre-computing normalization parameters": with cached statistics
+        # the next layer's Scale+Shift is a constant per channel): the layer that produces a tensor
+        # also writes act(scale * v + shift) for every layer that normalises it, so that those gather
+        # a plain tensor.  Needs the fused call (its epilogue writes the copies).
+        self.act_copies = bool(act_copies) and fused is True
+        self._copies_valid = False
+        if self.act_copies:
+            self._plan_act_copies()
+
+    def _plan_act_copies(self):
+        order = list(self.layers.items())
+        specs = {}
+        for i, (n, L) in enumerate(order):
+            op = L["op"]
+            if "scale" not in L:
+                continue
+            bufname, off, C = op["x"]
+            latest = [None] * C                    # the last layer before this one that writes each input channel
+            for pn, PL in order[:i]:
+                yv = PL["op"].get("y")
+                if yv is None or yv[0] != bufname:
+                    continue
+                lo, hi = max(yv[1], off), min(yv[1] + yv[2], off + C)
+                if lo >= hi:
+                    continue
+                assert (lo, hi) == (yv[1], yv[1] + yv[2]), "a producer's output lies wholly inside the normalised view"
+                latest[lo - off:hi - off] = [pn] * (hi - lo)
+            if any(p is None for p in latest):
+                continue                           # fed from outside the network: stays fused into the gather
+            H = self.bufs_shape[bufname][0]
+            L["pre"] = torch.zeros((H, H, C), dtype=self.td, device=self.device)
+            act = api.ACT_SILU if (op["kind"] == "conv" and op["act"]) else api.ACT_NONE
+            for pn in dict.fromkeys(latest):
+                yv = self.layers[pn]["op"]["y"]
+                o = yv[1] - off
+                specs.setdefault(pn, []).append((L["pre"][:, :, o:o + yv[2]], L["scale"][o:o + yv[2]],
+                                                 L["shift"][o:o + yv[2]], act))
+        for pn, spec in specs.items():
+            assert len(spec) <= 3, (pn, len(spec))
+            self.layers[pn]["act_spec"] = spec                 # keeps the views alive
+            self.layers[pn]["act_outs"] = api.act_out_array(spec)
+
+    def _fill_copy(self, L, x, scale, shift, act):
+        """Dense pass: the activated copy of a whole tensor, once its statistics are known."""
+        H, C = x.shape[0], x.shape[2]
+        b = min(self.block, H)
+        bl = self._lists(H, 1, 1, b)[0]
+        n = bl.n_host
+        t = self.ws.get("fill", n * b * b * C, self.td).view(n, b, b, C)
+        api.sige_gather(x, bl.g, bl.indices, bl.count, t, n_blocks=n, scale=scale, shift=shift, act=act, C=C,
+                        max_blocks=n)
+        api.sige_scatter(t, bl.g, bl.indices, bl.count, L["pre"], n_blocks=n, Cout=C, max_blocks=n)
 
     # ------------------------------------------------------------------ plumbing
     def _lists(self, Hin, k, stride, b):
@@ -135,46 +188,59 @@ class SigeUNet:
                 bl.max_blocks = min(bl.indices.shape[0], max(8, _next_pow2(n)))
         return counts
 
-    def _run(self, image, dense: bool):
+    def _run(self, image, dense: bool, fill_copies: bool = True):
         self.B["image"].copy_(image)
         shortcut_tiles = {}
+        use_copies = self.act_copies and self.fused is True
         for n, L in self.layers.items():
             op = L["op"]
             fused = self.fused is True or (self.fused == "lowres" and not L["sparse"])
             bl = L["list"][0 if (dense or not L["sparse"]) else 1]
             x = self.view(op["x"])
+            xn = x                  # what the normalising layer gathers: x, or its activated copy
             scale = shift = None
+            act = api.ACT_SILU if (op["kind"] == "conv" and op["act"]) else api.ACT_NONE
             if "scale" in L:
                 scale, shift = L["scale"], L["shift"]
                 if dense:   # statistics of the original activation, computed where a dense model would
                     api.sige_gn_stats(x, self.groups, L["mean"], L["var"], gamma=L["gamma"], beta=L["beta"],
                                       eps=self.eps, scale=scale, shift=shift, C=op["x"][2])
+                if "pre" in L and use_copies and (fill_copies or not dense):
+                    if dense:
+                        self._fill_copy(L, x, scale, shift, act)
+                    xn, scale, shift, act = L["pre"], None, None, api.ACT_NONE
+            # the sparse pass keeps the copies of its output up to date; the dense pass fills them where
+            # they are consumed (the statistics are not known before)
+            ao = L.get("act_outs") if (use_copies and not dense) else None
             if op["kind"] == "conv":
-                act = api.ACT_SILU if op["act"] else api.ACT_NONE
                 if not op["scatter"]:
                     shortcut_tiles[n] = L["conv"].forward(x, None, bl, self.ws, scatter=False, tag="short",
                                                           fused=fused)
                     continue
                 res_t = shortcut_tiles.get(op["shortcut"]) if op["shortcut"] else None
                 res_f = self.view(op["residual"]) if op["residual"] is not None else None
-                L["conv"].forward(x, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift, act=act,
-                                  residual_tiles=res_t, residual=res_f, tag="main", fused=fused)
+                L["conv"].forward(xn, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift, act=act,
+                                  residual_tiles=res_t, residual=res_f, tag="main", fused=fused, act_outs=ao)
             elif op["kind"] == "xfmr":
-                self._transformer(L, x, self.view(op["y"]), bl, dense, scale, shift)
+                self._transformer(L, x, xn, self.view(op["y"]), bl, dense, scale, shift, ao)
             else:
                 C, heads = op["C"], op["heads"]
                 T = x.shape[0] * x.shape[1]
-                L["qkv"].forward(x, L["qkv_buf"], bl, self.ws, scale=scale, shift=shift, tag="main",
+                L["qkv"].forward(xn, L["qkv_buf"], bl, self.ws, scale=scale, shift=shift, tag="main",
                                  fused=fused)
                 qkv = L["qkv_buf"].view(T, 3 * C)
                 api.sige_sparse_attn(qkv[:, :C], qkv[:, C:2 * C], qkv[:, 2 * C:], L["att_buf"].view(T, C),
                                      1.0 / math.sqrt(C // heads), Nq=T, workspace=L["att_ws"], heads=heads,
                                      d=C // heads, q_ld=3 * C, kv_ld=3 * C, o_ld=C)
                 L["proj"].forward(L["att_buf"], self.view(op["y"]), bl, self.ws, residual=x, tag="main",
-                                  fused=fused)
+                                  fused=fused, act_outs=ao)
+        if dense:
+            self._copies_valid = use_copies and fill_copies
+        elif not use_copies:
+            self._copies_valid = False          # a pass that does not maintain them leaves them stale
         return self.B["out"]
 
-    def _transformer(self, L, x, y, bl, dense, scale, shift):
+    def _transformer(self, L, x, xn, y, bl, dense, scale, shift, act_outs=None):
         """A transformer block on the tokens of the active blocks (Fig. "sige-attention"): gather,
         token-wise layers and 1x1 convolutions on the stacked tiles, keys and values scattered into
         their caches, attention for the gathered queries only, result scattered back with the
@@ -227,7 +293,7 @@ class SigeUNet:
             kv2 = L["kv2"]
             api.sige_conv(L["ctx"].view(1, 1, -1, kv2.Cin), kv2.g, kv2.Cin, kv2.Cout, kv2.packed, kv2.bias, one,
                           L["kc"].view(1, 1, -1, 2 * C), n_blocks=1, max_blocks=1)
-        L["in"].forward(x, L["h0"], bl, ws, scale=scale, shift=shift, fused=True)
+        L["in"].forward(xn, L["h0"], bl, ws, scale=scale, shift=shift, fused=True)
         # self-attention: only the active tokens' queries; their keys and values go into the caches first
         tn = normed(L["h0"], "ln1")
         q = conv(L["q1"], tn, "x_q")
@@ -246,15 +312,33 @@ class SigeUNet:
         gg = tiles("x_g", 4 * C)
         api.sige_geglu(u, gg, 4 * C, n_rows=rows)
         back(L["ff2"], gg, L["h3"], L["h2"])
-        L["out"].forward(L["h3"], y, bl, ws, residual=x, fused=True)
+        L["out"].forward(L["h3"], y, bl, ws, residual=x, fused=True, act_outs=act_outs)
 
-    def precompute(self, image):
-        """Dense pass on the original image: fills every cache and the normalisation statistics."""
-        return self._run(image, dense=True)
+    def precompute(self, image, fill_copies: bool = True):
+        """Dense pass on the original image: fills every cache and the normalisation statistics (and,
+        unless fill_copies is False - a plain dense model, for timing - the activated copies)."""
+        return self._run(image, dense=True, fill_copies=fill_copies)
 
     def step(self, image_edit):
         """Sparse pass on the edited image (after set_edit): updates the caches in place."""
+        assert not (self.act_copies and self.fused is True) or self._copies_valid, \
+            "the activated copies are stale: run precompute(image) first"
         return self._run(image_edit, dense=False)
+
+    def capture_dense(self, image):
+        """Captures a plain dense pass (statistics on the fly, no copies) in a HIP graph, for timing."""
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            for _ in range(2):
+                self.precompute(image, fill_copies=False)
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.precompute(image, fill_copies=False)
+        torch.cuda.synchronize()
+        return g
 
     def capture(self, image_edit):
         """Captures step(image_edit) in a HIP graph (lists sized by capacity, counts on the device)."""

@@ -72,15 +72,32 @@ def test_pointer_and_capacity_errors(L):
     assert L.sige_conv(FAKE, 0, gp, 4, 64, FAKE, None, FAKE, 8, -1, FAKE, None, 0, None) == 2
     # fused call: exactly one destination
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
-                             FAKE, 64, FAKE, None, 0, None) == 1
+                             FAKE, 64, FAKE, None, 0, None, 0, None) == 1
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
-                             None, 0, None, None, 0, None) == 1
+                             None, 0, None, None, 0, None, 0, None) == 1
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, FAKE, None, 0,
-                             None, 0, FAKE, None, 0, None) == 1       # residuals need y
+                             None, 0, FAKE, None, 0, None, 0, None) == 1       # residuals need y
     assert L.sige_fused_conv(FAKE, 1, 24, 24, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
-                             FAKE, 64, None, None, 0, None) == 2
+                             FAKE, 64, None, None, 0, None, 0, None) == 2
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, 9, None, None, 0, 64, FAKE, None, None, None, 0,
-                             FAKE, 64, None, None, 0, None) == 3
+                             FAKE, 64, None, None, 0, None, 0, None) == 3
+    # activated copies: at most SIGE_MAX_ACT_OUTS, scatter mode only, a list when the count is positive
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             FAKE, 64, None, None, 4, None, 0, None) == 1
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             FAKE, 64, None, None, 1, None, 0, None) == 1
+    ao = (api.ActOut * 1)()
+    ao[0].y, ao[0].y_ld, ao[0].act = FAKE, 64, 0
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             None, 0, FAKE, ao, 1, None, 0, None) == 1      # copies need y
+    ao[0].y_ld = 60                                                            # narrower than Cout
+    assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
+                             FAKE, 64, None, ao, 1, None, 0, None) == 1
+    # convolution with the scatter folded in, gather with the token norm folded in
+    assert L.sige_conv_scatter(FAKE, 1, gp, 64, 64, FAKE, None, None, FAKE, 8, -1, None, None, 0, FAKE, 64, None, 0, None) == 1
+    assert L.sige_conv_scatter(FAKE, 1, gp, 64, 64, FAKE, None, FAKE, FAKE, 8, -1, None, None, 0, FAKE, 32, None, 0, None) == 1
+    assert L.sige_gather_token_norm(FAKE, 1, 64, 64, gp, FAKE, FAKE, 8, -1, None, None, 1e-5, FAKE, None) == 2   # k = 3 geometry
+    assert L.sige_gather_token_norm(FAKE, 1, 64, 64, gp, None, FAKE, 8, -1, None, None, 1e-5, FAKE, None) == 1
     # scale without shift
     assert L.sige_gather(FAKE, 0, 64, 64, 0, gp, FAKE, FAKE, 8, -1, FAKE, None, 0, FAKE, None) == 1
     # unknown dtype

@@ -522,6 +522,67 @@ def test_conv_scatter(oracle, dtype, Cin, Cout, res, b, k, n):
             assert_close(y, want, td, f"conv_scatter n_blocks={nb} residuals={rt is not None}")
 
 
+@pytest.mark.parametrize("dtype,Cin,Cout,res,b,k,n", [
+    ("f16", 128, 128, 40, 16, 3, 4), ("bf16", 320, 64, 22, 5, 1, 9), ("f16", 512, 96, 16, 8, 3, 4),
+    ("f32", 64, 40, 20, 6, 3, 7)])
+def test_fused_conv_activated_copies(oracle, dtype, Cin, Cout, res, b, k, n):
+    """Activated copies of the output (the next layers' Scale+Shift and nonlinearity applied by the
+    producing layer): y is what the call gives without copies; inside the active blocks every copy is
+    bit for bit what a fused gather of y with the same scale, shift and activation reads, and within
+    tolerance of the oracle's; outside the blocks the copies are untouched.  Tiled kernel, few-row
+    kernel and K split; residual included."""
+    rng = np.random.default_rng(Cin + Cout + res + k)
+    td = DT[dtype]
+    x = torch.from_numpy(rng.standard_normal((res, res, Cin)).astype(np.float32)).to(td).cuda()
+    w, bias = inputs.conv_params(rng, Cout, Cin, k, td)
+    conv = SigeConv(dev(w), bias, res, res, b, 1, k // 2)
+    g = conv.g
+    g1 = api.geom(res, res, b, 1, 1, 0)
+    nby = -(-res // b)
+    pick = np.unique(np.append(rng.permutation(nby * nby)[:n - 1], nby * nby - 1))
+    blocks = np.array([((i // nby) * b, (i % nby) * b) for i in pick], np.int32)
+    n = len(blocks)
+    bl = BlockList(g, "cuda", max_blocks=n + 1)
+    bl.indices[:n].copy_(torch.from_numpy(blocks))
+    bl.count.fill_(n)
+    resid = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td).cuda()
+    cache = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td).cuda()
+    ws = Workspace("cuda")
+    acts = [api.ACT_SILU, api.ACT_NONE, api.ACT_RELU]
+    wide = torch.full((res, res, 2 * Cout + 16), 3.0, dtype=td, device="cuda")     # two copies share a wider buffer
+    lone = torch.full((res, res, Cout), 3.0, dtype=td, device="cuda")
+    scales = [torch.from_numpy(rng.uniform(0.5, 1.5, Cout).astype(np.float32)).cuda() for _ in acts]
+    shifts = [torch.from_numpy(rng.uniform(-0.5, 0.5, Cout).astype(np.float32)).cuda() for _ in acts]
+    copies = [wide[:, :, :Cout], wide[:, :, Cout + 16:], lone]
+    spec = [(copies[0], scales[0], shifts[0], acts[0]), (copies[1], scales[1], shifts[1], acts[1]),
+            (copies[2], None, None, acts[2])]
+    out_mask = torch.from_numpy(outside_blocks_mask(blocks, b, b, res, res)).cuda()
+    for nb in (n, -1):
+        bl.n_host = nb
+        y0 = cache.clone()
+        conv.forward(x, y0, bl, ws, residual=resid, fused=True)
+        y = cache.clone()
+        wide.fill_(3.0)
+        lone.fill_(3.0)
+        conv.forward(x, y, bl, ws, residual=resid, fused=True, act_outs=spec)
+        assert torch.equal(y, y0)
+        idx = bl.indices[:n].contiguous()
+        cnt = bl.count
+        for j, c in enumerate(copies):
+            assert (c[out_mask] == 3.0).all()
+            got = torch.empty((n, b, b, Cout), dtype=td, device="cuda")
+            api.sige_gather(c, g1, idx, cnt, got, n_blocks=n, C=Cout)
+            ref = torch.empty((n, b, b, Cout), dtype=td, device="cuda")
+            api.sige_gather(y, g1, idx, cnt, ref, n_blocks=n, C=Cout, scale=spec[j][1], shift=spec[j][2], act=acts[j])
+            # rows of blocks that stick out of the image are zero padding in both gathers
+            assert torch.equal(got, ref), f"copy {j} differs from a fused gather of y"
+            want = expected_tiles(oracle, f64(y), blocks, b, b, 1, 0,
+                                  None if spec[j][1] is None else f64(spec[j][1]),
+                                  None if spec[j][2] is None else f64(spec[j][2]), acts[j])
+            assert_close(got, want, td, f"activated copy {j}")
+        assert (wide[:, :, Cout:Cout + 16] == 3.0).all()
+
+
 # ------------------------------------------------------------------ the whole layer
 
 def sparse_layer(cfg, *, fused, shortcut=False, device_count=False, cache=None):

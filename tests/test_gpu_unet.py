@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from helpers import f64, round_to
-from paper_2211_02048_amd import inputs
+from paper_2211_02048_amd import api, inputs
 from paper_2211_02048_amd.unet import SigeUNet
 
 pytestmark = pytest.mark.gpu
@@ -88,16 +88,31 @@ def test_unet_precompute_and_sparse_step(setup):
     assert checked >= 20
     # the edit really changed the output, and only moderately many blocks were touched
     assert not torch.equal(net.B["out"], gpu_cache["out"])
-    # the three-call path (gather, conv, scatter) and the fused call give the same bits
-    three_calls = {n: b.clone() for n, b in net.B.items()}
-    net.fused = True
-    for n in gpu_cache:
+    # the three-call path (gather with Scale+Shift and SiLU, conv, scatter; no activated copies) gives
+    # the same bits as the fused calls with the copies written by the producing layers
+    fused_run = {n: b.clone() for n, b in net.B.items()}
+    net.fused = False
+    for n in gpu_cache:                      # same caches, same cached statistics
         net.B[n].copy_(gpu_cache[n])
     net.step(s["img_e"].cuda())
     torch.cuda.synchronize()
-    net.fused = False
-    for n in three_calls:
-        assert torch.equal(net.B[n], three_calls[n]), ("fused vs three calls", n)
+    net.fused = True
+    for n in fused_run:
+        assert torch.equal(net.B[n], fused_run[n]), ("fused vs three calls", n)
+    # and the copies hold exactly what a fused gather would compute from the tensors they mirror
+    net.precompute(s["img_o"].cuda())
+    net.step(s["img_e"].cuda())
+    n_copies = 0
+    for n, L in net.layers.items():
+        if "pre" not in L or L["op"]["x"] == L["op"].get("y"):
+            continue            # (an attention block overwrites its input in place: nothing left to compare with)
+        x = net.view(L["op"]["x"])
+        keep = L["pre"].clone()
+        act = api.ACT_SILU if (L["op"]["kind"] == "conv" and L["op"]["act"]) else api.ACT_NONE
+        net._fill_copy(L, x, L["scale"], L["shift"], act)
+        assert torch.equal(L["pre"], keep), ("activated copy", n)
+        n_copies += 1
+    assert n_copies >= 20
 
 
 def test_unet_zero_edit_and_graph_replay(setup):
@@ -185,6 +200,8 @@ def test_latent_unet_transformer_blocks(sd_setup):
                 mx, rms = rel_err(f64(L[part]), round_to(s["cache"][f"{n}.{part}"], td))
                 assert rms <= tol and mx <= 8 * tol, ("precompute", n, part, mx, rms)
     gpu_cache = {n: b.clone() for n, b in net.B.items()}
+    copies = {n: L["pre"].clone() for n, L in net.layers.items() if "pre" in L}   # activated copies: caches too
+    assert len(copies) >= 10
     inner = {(n, part): L[part].clone() for n, L in net.layers.items() if L["op"]["kind"] == "xfmr"
              for part in ("h0", "kv", "h1", "h2", "h3")}
     counts = net.set_edit(torch.from_numpy(s["mask"]).cuda(), exact=True)
@@ -221,6 +238,8 @@ def test_latent_unet_transformer_blocks(sd_setup):
         net.B[n].copy_(gpu_cache[n])
     for (n, part), t in inner.items():
         net.layers[n][part].copy_(t)
+    for n, t in copies.items():
+        net.layers[n]["pre"].copy_(t)
     net.set_edit(torch.zeros((SD["res"], SD["res"]), dtype=torch.uint8, device="cuda"), exact=True)
     net.step(s["img_o"].cuda())
     torch.cuda.synchronize()
