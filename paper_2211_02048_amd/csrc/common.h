@@ -147,6 +147,11 @@ __device__ __forceinline__ bool aligned16_dev(const void* p)
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
 }
 
+// Forces a kernel argument into a scalar register here.  Left alone, the compiler fetches the fields
+// of a large by-value argument struct in small groups right before their first use, each group a
+// dependent round trip to the scalar cache; pinned at the top of a kernel they arrive together.
+#define SIGE_PIN_S(x) asm volatile("" ::"s"(x))
+
 // Number of blocks a kernel may touch: the host value when given, else the device count.
 __device__ __forceinline__ int effective_blocks(const int32_t* count, int max_blocks, int n_host)
 {

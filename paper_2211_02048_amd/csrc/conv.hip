@@ -125,10 +125,27 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 // tile would be, adds the residuals in fp32 and stores into y.
 // early: the two residual vectors were fetched by the caller ahead of time (for the 16-byte path
 // only).
+// Scale and shift of the activated copies for the N channels from o on, fetched by the caller
+// ahead of the sums so that their latency does not sit behind the store of y.
+template <int N> struct ActParams { float sc[SIGE_MAX_ACT_OUTS][N], sh[SIGE_MAX_ACT_OUTS][N]; };
+template <int N>
+__device__ __forceinline__ void load_act_params(const ConvArgs& a, int o, ActParams<N>& p)
+{
+#pragma unroll
+    for (int j = 0; j < SIGE_MAX_ACT_OUTS; ++j) {
+        if (j >= a.n_ao) break;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            p.sc[j][i] = a.ao[j].scale ? a.ao[j].scale[o + i] : 1.0f;
+            p.sh[j][i] = a.ao[j].scale ? a.ao[j].shift[o + i] : 0.0f;
+        }
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_ok, long t, long pix, int o,
-                                         float (&v)[Vec16<T>::N], bool early = false,
-                                         uint4 early_tiles = make_uint4(0, 0, 0, 0),
+                                         float (&v)[Vec16<T>::N], const ActParams<Vec16<T>::N>& ap,
+                                         bool early = false, uint4 early_tiles = make_uint4(0, 0, 0, 0),
                                          uint4 early_full = make_uint4(0, 0, 0, 0))
 {
     constexpr int N = Vec16<T>::N;
@@ -157,14 +174,9 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
 #pragma unroll
             for (int j = 0; j < SIGE_MAX_ACT_OUTS; ++j) {
                 if (j >= a.n_ao) break;
-                float f[N], sc[N], sh[N];
+                float f[N];
                 unpack<T>(r, f);
-#pragma unroll
-                for (int i = 0; i < N; ++i) {
-                    sc[i] = a.ao[j].scale ? a.ao[j].scale[o + i] : 1.0f;
-                    sh[i] = a.ao[j].scale ? a.ao[j].shift[o + i] : 0.0f;
-                }
-                scale_shift_act<N>(f, sc, sh, a.ao[j].act);
+                scale_shift_act<N>(f, ap.sc[j], ap.sh[j], a.ao[j].act);
                 *(uint4*)((T*)a.ao[j].y + pix * a.ao[j].ld + o) = pack<T>(f);
             }
         } else {
@@ -218,7 +230,7 @@ constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks i
 // unrolled), 0 for any other kernel size.  Two waves per SIMD are enforced: with fewer the MFMA
 // phase has nothing to overlap its LDS and L2 latencies with.
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
-__global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
+__global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void conv_kernel(ConvArgs a)
 {
     constexpr int NT = 64 * WM * WN * WK;                     // threads per workgroup
     static_assert(NT == 256 || NT == 512, "four or eight waves per workgroup");
@@ -508,6 +520,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
             const int g = m / pb, p = m - g * pb;
             const int py = p / a.bw, px = p - py * a.bw;
             if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
+            ActParams<N> ap;
+            if (vec_ok && o + N <= a.Cout) load_act_params<N>(a, o, ap);
             float v[N];
 #pragma unroll
             for (int i = 0; i < N; ++i) {
@@ -534,7 +548,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK, 2) void conv_kernel(ConvArgs a)
                 if (oy < 0 || oy >= a.Hout || ox < 0 || ox >= a.Wout) continue;
                 pix = (long)oy * a.Wout + ox;
             }
-            emit_run<T>(a, to_y, vec_ok, t, pix, o, v);
+            emit_run<T>(a, to_y, vec_ok, t, pix, o, v, ap);
         }
     }
 }
@@ -545,6 +559,13 @@ template <typename T>
 __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_runs)
 {
     constexpr int N = Vec16<T>::N;
+    // every argument this kernel reads, fetched in one go
+    asm volatile("" ::"s"(a.Cout), "s"(a.bh), "s"(a.bw), "s"(a.y), "s"(a.count), "s"(a.max_blocks), "s"(a.n_host),
+                 "s"(a.indices), "s"(a.Hout), "s"(a.Wout), "s"(a.y_ld), "s"(a.res_tiles), "s"(a.res_full),
+                 "s"(a.res_ld), "s"(a.bias), "s"(a.partial), "s"(a.partial_stride), "s"(a.ksplit), "s"(a.out),
+                 "s"(a.n_ao), "s"(a.ao[0].y), "s"(a.ao[0].scale), "s"(a.ao[0].shift), "s"(a.ao[0].ld),
+                 "s"(a.ao[0].act), "s"(a.ao[1].y), "s"(a.ao[1].scale), "s"(a.ao[1].shift), "s"(a.ao[1].ld),
+                 "s"(a.ao[1].act));
     const long e = (long)blockIdx.x * 256 + threadIdx.x;
     if (e >= n_runs) return;
     const int runs = (a.Cout + N - 1) / N;
@@ -570,9 +591,11 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     const bool vec_ok = emit_vec_ok<T>(a);
     const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
     uint4 early_t = make_uint4(0, 0, 0, 0), early_f = make_uint4(0, 0, 0, 0);
+    ActParams<N> ap;
     if (early_ok) {
         if (a.res_tiles) early_t = *(const uint4*)((const T*)a.res_tiles + t);
         if (a.res_full) early_f = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+        load_act_params<N>(a, o, ap);
     }
     float v[N], bv[N];
     const bool vec4 = (a.Cout & 3) == 0 && o + N <= a.Cout;
@@ -611,7 +634,7 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) v[i] += bv[i];
-    emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok, early_t, early_f);
+    emit_run<T>(a, to_y, vec_ok, t, pix, o, v, ap, early_ok, early_t, early_f);
 }
 
 // ---- 1x1 convolutions with few rows ------------------------------------------------------------
@@ -794,9 +817,11 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         // bias and residuals do not depend on the sums: they are fetched before the sums are read
         const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
         uint4 early_t = make_uint4(0, 0, 0, 0), early_f = make_uint4(0, 0, 0, 0);
+        ActParams<N> ap;
         if (early_ok) {
             if (a.res_tiles) early_t = *(const uint4*)((const T*)a.res_tiles + t);
             if (a.res_full) early_f = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+            load_act_params<N>(a, o, ap);
         }
         float v[N], bv[N];
 #pragma unroll
@@ -815,7 +840,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         }
 #pragma unroll
         for (int i = 0; i < N; ++i) v[i] += bv[i];
-        emit_run<T>(a, to_y, vec_ok, t, pix, o, v, early_ok, early_t, early_f);
+        emit_run<T>(a, to_y, vec_ok, t, pix, o, v, ap, early_ok, early_t, early_f);
     }
 }
 
@@ -829,14 +854,14 @@ struct ConvPlan {
 
 // M x N per workgroup and whether the four waves split K
 struct CfgShape { int M, N, WK; };
-constexpr int kNumCfg = 4;
-static const CfgShape kCfg[kNumCfg] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}};
+constexpr int kNumCfg = 4;    // shapes that compete by score; the fifth is chosen by its own rule
+static const CfgShape kCfg[kNumCfg + 1] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}, {64, 32, 8}};
 
 // Chooses the workgroup shape and the staged channel chunk for one call, then - when the caller
 // gave a workspace (partial_elems = fp32 elements it holds) and the call has few workgroups but a
 // long K - how many workgroups share one output patch along K.
 static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, size_t s, int kstep,
-                      int nblocks, size_t partial_elems, ConvPlan* best)
+                      int nblocks, size_t partial_elems, bool staged_math, ConvPlan* best)
 {
     const char* force = getenv("SIGE_CONV_CFG");
     const char* force_kc = getenv("SIGE_CONV_KC");   // tuning aids: fix the shape / the K steps per chunk
@@ -893,6 +918,38 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     // saves); smaller chunks when that is what it takes to reach 256 workgroups.
     ConvPlan& p = *best;
     const char* force_split = getenv("SIGE_CONV_SPLIT");
+    // Few workgroups and a long K, nothing to compute while staging (no Scale+Shift, no activation):
+    // 64 x 32 patches whose EIGHT waves split K, with 256 or 512 channels staged per chunk.  One
+    // kernel, no workspace; the waves' sums meet in LDS.  (With staged arithmetic the chunk would
+    // cost every workgroup eight times the activation work of the four-wave shape's.)
+    if (g->k == 3 && !staged_math && !force && !force_kc && !force_split && g->block_w <= 64 && Cin >= 20 * kstep) {
+        ConvPlan q;
+        q.cfg = 4;
+        q.ksplit = 1;
+        const int M = 64, pbfull = g->block_h * g->block_w;
+        if (pbfull <= M) { q.G = M / pbfull; q.rows = g->block_h; }
+        else { q.G = 1; q.rows = M / g->block_w; }
+        q.bands = (g->block_h + q.rows - 1) / q.rows;
+        q.trows = (q.rows - 1) * g->stride + g->k;
+        q.slabs = (Cout + 31) / 32;
+        q.groups = (nblocks + q.G - 1) / q.G;
+        const long npix = (long)q.G * q.trows * tw;
+        q.kc = 0;
+        for (int kc : {32, 16}) {
+            if (Cin % (kc * kstep)) continue;
+            const size_t lds = lds_bytes(4, npix, kc);
+            if (lds <= 150u * 1024u) { q.kc = kc; q.lds = lds; break; }
+        }
+        const long wgs4 = (long)q.groups * q.bands * q.slabs;
+        // at most two chunks: beyond that a workgroup streams so much weight by itself that the cut
+        // over workgroups below, second kernel included, is faster
+        if (q.kc && wgs4 <= 256 && Cin / (q.kc * kstep) <= 2) {
+            q.Cc = q.kc * kstep;
+            q.ps = (int)(q.Cc * s + 16);
+            p = q;
+            return true;
+        }
+    }
     const long wgs = (long)p.groups * p.bands * p.slabs;
     const size_t per_split = (size_t)nblocks * g->block_h * g->block_w * Cout;
     const int max_by_ws = per_split ? (int)std::min<size_t>(partial_elems / per_split, 64) : 0;
@@ -938,19 +995,31 @@ template <typename T, int KC, int KK>
 static int launch_kc(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
     switch (p.cfg) {
-    case 0: return launch_cfg<T, 2, 2, 2, 2, 1, KC, KK>(a, p, st);
-    case 1: return launch_cfg<T, 2, 1, 2, 2, 1, KC, KK>(a, p, st);
-    case 2: return launch_cfg<T, 1, 1, 2, 2, 1, KC, KK>(a, p, st);
+    case 0:
+        if constexpr (KC <= 8) return launch_cfg<T, 2, 2, 2, 2, 1, KC, KK>(a, p, st);
+        break;
+    case 1:
+        if constexpr (KC <= 8) return launch_cfg<T, 2, 1, 2, 2, 1, KC, KK>(a, p, st);
+        break;
+    case 2:
+        if constexpr (KC <= 8) return launch_cfg<T, 1, 1, 2, 2, 1, KC, KK>(a, p, st);
+        break;
+    case 3:
+        if constexpr (KC % 4 == 0 && KC <= 8) return launch_cfg<T, 2, 1, 1, 1, 4, KC, KK>(a, p, st);
+        break;
     default:
-        if constexpr (KC % 4 == 0) return launch_cfg<T, 2, 1, 1, 1, 4, KC, KK>(a, p, st);
-        return fail(SIGE_ERR_UNSUPPORTED, "sige_conv: internal: K-split shape without a K-split chunk");
+        if constexpr (KC % 8 == 0 && KC >= 16 && KK == 9) return launch_cfg<T, 2, 1, 1, 1, 8, KC, KK>(a, p, st);
+        break;
     }
+    return fail(SIGE_ERR_UNSUPPORTED, "sige_conv: internal: shape %d without a matching chunk %d", p.cfg, KC);
 }
 
 template <typename T, int KK>
 static int launch_kk(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
     switch (p.kc) {
+    case 32: return launch_kc<T, 32, KK>(a, p, st);
+    case 16: return launch_kc<T, 16, KK>(a, p, st);
     case 8: return launch_kc<T, 8, KK>(a, p, st);
     case 4: return launch_kc<T, 4, KK>(a, p, st);
     default: return launch_kc<T, 1, KK>(a, p, st);
@@ -1075,7 +1144,8 @@ static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, 
     }
     ConvPlan p;
     const bool ws_ok = workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
-    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok ? workspace_bytes / sizeof(float) : 0, &p),
+    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok ? workspace_bytes / sizeof(float) : 0,
+                           a.scale != nullptr || a.act != SIGE_ACT_NONE, &p),
                  SIGE_ERR_UNSUPPORTED, "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who,
                  g->block_h, g->block_w, g->k, g->stride, Cin);
     SIGE_REQUIRE(p.groups <= 65535 && p.bands * p.ksplit <= 65535, SIGE_ERR_UNSUPPORTED,
@@ -1105,7 +1175,7 @@ extern "C" size_t sige_conv_workspace_bytes(sige_dtype dt, const sige_geom* g, i
     size_t need = 0;
     for (int nl = 1; nl <= max_blocks; ++nl) {
         ConvPlan p;
-        if (!plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, (size_t)1 << 40, &p)) return 0;
+        if (!plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, (size_t)1 << 40, true, &p)) return 0;
         if (p.ksplit > 1) need = std::max(need, (size_t)p.ksplit * nl * g->block_h * g->block_w * Cout * sizeof(float));
         else if ((long)p.groups * p.bands * p.slabs > 256) break;   // more blocks only add workgroups
     }
