@@ -240,6 +240,16 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
     constexpr int KW = KC / WK;                               // K steps per wave and tap
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
+    // the arguments, fetched in two goes instead of group by group before each first use
+    asm volatile("" ::"s"(a.indices), "s"(a.count), "s"(a.max_blocks), "s"(a.n_host), "s"(a.G), "s"(a.bands),
+                 "s"(a.rows), "s"(a.bh), "s"(a.bw), "s"(a.stride), "s"(a.trows), "s"(a.tw), "s"(a.th), "s"(a.ps),
+                 "s"(a.k), "s"(a.Cin), "s"(a.Cout), "s"(a.w), "s"(a.bias), "s"(a.partial), "s"(a.ksplit),
+                 "s"(a.x), "s"(a.tiles), "s"(a.scale), "s"(a.shift), "s"(a.act), "s"(a.x_ld), "s"(a.up),
+                 "s"(a.pad), "s"(a.Hin));
+    asm volatile("" ::"s"(a.Win), "s"(a.y), "s"(a.y_ld), "s"(a.out), "s"(a.res_tiles), "s"(a.res_full),
+                 "s"(a.res_ld), "s"(a.Hout), "s"(a.Wout), "s"(a.partial_stride), "s"(a.n_ao), "s"(a.ao[0].y),
+                 "s"(a.ao[0].scale), "s"(a.ao[0].shift), "s"(a.ao[0].ld), "s"(a.ao[0].act), "s"(a.ao[1].y),
+                 "s"(a.ao[1].scale), "s"(a.ao[1].shift), "s"(a.ao[1].ld), "s"(a.ao[1].act));
 
     // Fused mode: the origins of this workgroup's blocks go to LDS once.  Their loads and the
     // load of the count are independent and are issued together (row n exists for n < max_blocks).
@@ -661,6 +671,13 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
     float* red = reinterpret_cast<float*>(lds4);              // [W][BM][RS], after the K loop
+    // the arguments, fetched in two goes instead of group by group before each first use
+    asm volatile("" ::"s"(a.w), "s"(a.Cin), "s"(a.Cout), "s"(a.bh), "s"(a.bw), "s"(a.x), "s"(a.tiles),
+                 "s"(a.indices), "s"(a.count), "s"(a.max_blocks), "s"(a.n_host), "s"(a.Hin), "s"(a.Win),
+                 "s"(a.x_ld), "s"(a.y), "s"(a.y_ld), "s"(a.out), "s"(a.res_tiles), "s"(a.res_full), "s"(a.res_ld),
+                 "s"(a.bias), "s"(a.Hout), "s"(a.Wout), "s"(a.n_ao));
+    asm volatile("" ::"s"(a.ao[0].y), "s"(a.ao[0].scale), "s"(a.ao[0].shift), "s"(a.ao[0].ld), "s"(a.ao[0].act),
+                 "s"(a.ao[1].y), "s"(a.ao[1].scale), "s"(a.ao[1].shift), "s"(a.ao[1].ld), "s"(a.ao[1].act));
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: the K loop is uniform
     const int pb = a.bh * a.bw;
