@@ -102,7 +102,8 @@ class SigeConv:
                 act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False,
                 split_k=True, mod=None, act_outs=None):
         """gather(x) -> conv -> scatter into y (in place), as three calls or as the one fused call
-        (a modulated gather, mod given, always runs as three calls).  act_outs: activated copies of
+        (a modulated gather, mod given, stays a call of its own; fused then folds the scatter into
+        the convolution).  act_outs: activated copies of
         the output for the layers that normalise it next (the fused call only).
         Returns the output tiles (None when the fused call scattered them directly)."""
         g, n = self.g, blocks.n_host
@@ -130,6 +131,11 @@ class SigeConv:
         else:   # spatially-adaptive normalisation: per-pixel gamma | beta beside the cached statistics
             api.sige_gather_modulated(x, g, blocks.indices, blocks.count, tiles, mod, n_blocks=n, scale=scale,
                                       shift=shift, act=act, up=self.up, C=self.Cin, max_blocks=cap)
+        if scatter and fused:     # a modulated gather, then the convolution with the scatter folded in
+            api.sige_conv_scatter(tiles, g, blocks.indices, blocks.count, self.Cin, self.Cout, self.packed, self.bias,
+                                  y, n_blocks=n, max_blocks=cap, residual_tiles=residual_tiles, residual=residual,
+                                  workspace=split)
+            return None
         api.sige_conv(tiles, g, self.Cin, self.Cout, self.packed, self.bias, blocks.count, out_tiles,
                       n_blocks=n, max_blocks=cap, workspace=split)
         if scatter:
