@@ -157,12 +157,16 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
                 float f[N], q[N];
                 unpack<T>(r, f);
                 if (a.res_tiles) {
-                    unpack<T>(early ? early_tiles : *(const uint4*)((const T*)a.res_tiles + t), q);
+                    uint4 rt = early_tiles;
+                    if (!early) rt = *(const uint4*)((const T*)a.res_tiles + t);
+                    unpack<T>(rt, q);
 #pragma unroll
                     for (int i = 0; i < N; ++i) f[i] += q[i];
                 }
                 if (a.res_full) {
-                    unpack<T>(early ? early_full : *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o), q);
+                    uint4 rf = early_full;
+                    if (!early) rf = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+                    unpack<T>(rf, q);
 #pragma unroll
                     for (int i = 0; i < N; ++i) f[i] += q[i];
                 }
@@ -563,6 +567,33 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
     }
 }
 
+// v += the ksplit shares of one run of N channels, B of them in flight at a time (each batch is a
+// round trip to memory), added in the order of the split index.
+template <int B, int N>
+__device__ __forceinline__ void add_shares(const float* __restrict__ partial, long stride, int ksplit, long t,
+                                           float (&v)[N])
+{
+    for (int s0 = 0; s0 < ksplit; s0 += B) {
+        f32x4 q[B][N / 4];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const float* __restrict__ src = partial + min(s0 + j, ksplit - 1) * stride + t;
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i) q[j][i] = *(const f32x4*)(src + 4 * i);
+        }
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            if (s0 + j < ksplit) {
+#pragma unroll
+                for (int i = 0; i < N / 4; ++i) {
+                    v[4 * i] += q[j][i].x; v[4 * i + 1] += q[j][i].y;
+                    v[4 * i + 2] += q[j][i].z; v[4 * i + 3] += q[j][i].w;
+                }
+            }
+        }
+    }
+}
+
 // Second kernel of a K-split call: adds the workgroups' shares in a fixed order, then the bias, and
 // finishes every run of output channels exactly as the unsplit epilogue does.
 template <typename T>
@@ -615,25 +646,9 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
         bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
     }
     if (vec4) {
-        // four shares are in flight at a time; they are still added in the order of the split index
-        for (int s0 = 0; s0 < a.ksplit; s0 += 4) {
-            float4 q[4][N / 4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float* __restrict__ src = a.partial + min(s0 + j, a.ksplit - 1) * a.partial_stride + t;
-#pragma unroll
-                for (int i = 0; i < N / 4; ++i) q[j][i] = *(const float4*)(src + 4 * i);
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (s0 + j >= a.ksplit) break;
-#pragma unroll
-                for (int i = 0; i < N / 4; ++i) {
-                    v[4 * i] += q[j][i].x; v[4 * i + 1] += q[j][i].y;
-                    v[4 * i + 2] += q[j][i].z; v[4 * i + 3] += q[j][i].w;
-                }
-            }
-        }
+        if (a.ksplit <= 4) add_shares<4, N>(a.partial, a.partial_stride, a.ksplit, t, v);
+        else if (a.ksplit <= 8) add_shares<8, N>(a.partial, a.partial_stride, a.ksplit, t, v);
+        else add_shares<16, N>(a.partial, a.partial_stride, a.ksplit, t, v);
     } else {
         for (int s = 0; s < a.ksplit; ++s) {
             const float* __restrict__ src = a.partial + s * a.partial_stride + t;

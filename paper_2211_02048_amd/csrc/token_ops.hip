@@ -59,13 +59,50 @@ __global__ __launch_bounds__(256) void token_norm_kernel(RowArgs a)
         pixel = inside ? (long)iy * a.W + ix : 0;
     }
     const uint4* __restrict__ src = (const uint4*)((const T*)a.x + pixel * a.x_ld);
-    float f[NV][N];
+    float f[NV][N], gm[NV][N], bt[NV][N];
+    uint4 raw[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int j = lane + 64 * u;
+        raw[u] = (inside && j < V) ? src[j] : make_uint4(0, 0, 0, 0);
+    }
+    // gamma and beta do not depend on the statistics: they are fetched right behind the row, as
+    // 16-byte vectors (C is a multiple of N, the arrays come from an allocator: 16-byte aligned or
+    // the scalar path)
+    const bool gvec = aligned16_dev(a.gamma) && aligned16_dev(a.beta);
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int j = lane + 64 * u;
+#pragma unroll
+        for (int i = 0; i < N; ++i) { gm[u][i] = 1.0f; bt[u][i] = 0.0f; }
+        if (j < V) {
+            if (gvec) {
+#pragma unroll
+                for (int i = 0; i < N; i += 4) {
+                    if (a.gamma) {
+                        const float4 g4 = *(const float4*)(a.gamma + j * N + i);
+                        gm[u][i] = g4.x; gm[u][i + 1] = g4.y; gm[u][i + 2] = g4.z; gm[u][i + 3] = g4.w;
+                    }
+                    if (a.beta) {
+                        const float4 b4 = *(const float4*)(a.beta + j * N + i);
+                        bt[u][i] = b4.x; bt[u][i + 1] = b4.y; bt[u][i + 2] = b4.z; bt[u][i + 3] = b4.w;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    if (a.gamma) gm[u][i] = a.gamma[j * N + i];
+                    if (a.beta) bt[u][i] = a.beta[j * N + i];
+                }
+            }
+        }
+    }
     float s = 0.0f;
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         const int j = lane + 64 * u;
         if (j < V) {
-            unpack<T>(inside ? src[j] : make_uint4(0, 0, 0, 0), f[u]);
+            unpack<T>(raw[u], f[u]);
 #pragma unroll
             for (int i = 0; i < N; ++i) s += f[u][i];
         }
@@ -89,11 +126,7 @@ __global__ __launch_bounds__(256) void token_norm_kernel(RowArgs a)
         const int j = lane + 64 * u;
         if (j < V) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int c = j * N + i;
-                const float g = a.gamma ? a.gamma[c] : 1.0f, b = a.beta ? a.beta[c] : 0.0f;
-                f[u][i] = fmaf(f[u][i] * rstd, g, b);
-            }
+            for (int i = 0; i < N; ++i) f[u][i] = fmaf(f[u][i] * rstd, gm[u][i], bt[u][i]);
             dst[j] = pack<T>(f[u]);
         }
     }
