@@ -28,8 +28,8 @@ sys.path.insert(0, ROOT)
 
 # HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs of `bench.py --probe`: FETCH_SIZE
 # scaled by 2.0, WRITE_SIZE by 1.0, the factors a plain 128 MiB copy gives; see profiles/hbm_traffic_pmc.md)
-PMC_TRAFFIC_DIFF_MASK_CONFIG2 = 16450 * 2 * 1024 + 65 * 1024
-PMC_TRAFFIC_FUSED_CONV_CONFIG2 = 2547 * 2 * 1024 + 576 * 1024
+PMC_TRAFFIC_DIFF_MASK_CONFIG2 = 16425 * 2 * 1024 + 64 * 1024
+PMC_TRAFFIC_FUSED_CONV_CONFIG2 = 2586 * 2 * 1024 + 576 * 1024
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
 
