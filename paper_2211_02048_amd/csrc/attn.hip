@@ -18,6 +18,8 @@
 // second small kernel merges the partial (max, sum, O) triples.
 #include "common.h"
 
+#include <stdlib.h>
+
 namespace sige {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -297,14 +299,16 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
 }
 
 // Number of key splits: a workgroup walks through its key chunks one after the other and each costs
-// a staging round trip, so few queries are spread over up to four workgroups per compute unit, at
-// least 2 chunks each.
+// a staging round trip, so few queries are spread over about two workgroups per compute unit (more
+// splits cost the merge kernel more than they save: measured at 64 to 1280 queries), at least 2
+// chunks each.
 static int pick_splits(int Nq, int T, int heads, int d)
 {
     const int KCH = keys_per_chunk(d);
     const long base = (long)heads * ((Nq + 127) / 128);
     const int chunks = (T + KCH - 1) / KCH;
-    long want = (1024 + base - 1) / base;
+    const char* target = getenv("SIGE_ATTN_WGS");           // tuning aid: workgroups to aim for
+    long want = ((target ? atoi(target) : 512) + base - 1) / base;
     long cap = chunks / 2;
     if (want > cap) want = cap;
     if (want > 64) want = 64;
