@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the block-sparse layer hot path on one MI355X.
 
-A step is one pass of the whole path over BASELINE config 2 (256x256x128 fp16, ~1 % blob edit,
+A step is one pass of the whole path over benchmark configuration 2 (256x256x128 fp16, ~1 % blob edit,
 16x16 blocks): difference mask + block lists (3x3 and 1x1 geometry), then gather(GN+SiLU) ->
 conv3x3 -> scatter and gather -> conv1x1 -> scatter, inputs resident in HBM, replayed as one HIP
 graph (block counts stay on the device).  `value` is the algorithmic bytes of one step divided by
@@ -13,9 +13,9 @@ both timed live with events on the launch stream, the CPU oracle timed on the ho
 `supplement`: per-call times, gather / scatter / difference-mask bandwidth on a 1024x1024x128
 tensor with every block active (footprint far beyond the 256 MB Infinity Cache), convolution
 throughput with every block active, sparse-query attention, the synthetic DDPM-style UNet step
-(BASELINE config 3) sparse at ~1.2 % and 15.5 % edit versus dense, and the synthetic latent-diffusion
-style UNet step (BASELINE config 4) at 1 / 5 / 20 % edit versus dense, and the synthetic SPADE-style
-generator (BASELINE config 5) over ten successive ~1 % label edits versus dense.
+(benchmark configuration 3) sparse at ~1.2 % and 15.5 % edit versus dense, and the synthetic latent-diffusion
+style UNet step (benchmark configuration 4) at 1 / 5 / 20 % edit versus dense, and the synthetic SPADE-style
+generator (benchmark configuration 5) over ten successive ~1 % label edits versus dense.
 """
 import argparse
 import json
@@ -388,7 +388,7 @@ def supplement(L, with_unet):
     att["all_over_1pct_speedup"] = round(att["all_queries"]["us"] / att["1pct"]["us"], 2)
     out["sparse_attention_T4096_h8_d40_bf16"] = att
 
-    # ---- the synthetic DDPM-style UNet step (BASELINE config 3)
+    # ---- the synthetic DDPM-style UNet step (benchmark configuration 3)
     if with_unet:
         from paper_2211_02048_amd.unet import SigeUNet
         net = SigeUNet()
@@ -430,7 +430,7 @@ def supplement(L, with_unet):
         del net
         torch.cuda.empty_cache()
 
-        # ---- the synthetic latent-diffusion style UNet step (BASELINE config 4)
+        # ---- the synthetic latent-diffusion style UNet step (benchmark configuration 4)
         net = SigeUNet(64, (320, 640, 1280, 1280), (64, 32, 16), 8, dtype="bf16", seed=1004, block=8, dilate=1,
                        min_sparse_res=16, in_ch=4, attn_kind="xfmr", ctx=(77, 768))
         sd = {"config": "64x64x4 latent, channels 320/640/1280/1280, 2 ResBlocks per level each followed by a "
@@ -475,7 +475,7 @@ def supplement(L, with_unet):
         del net
         torch.cuda.empty_cache()
 
-        # ---- the synthetic SPADE-style conditional generator (BASELINE config 5): ten successive
+        # ---- the synthetic SPADE-style conditional generator (benchmark configuration 5): ten successive
         # label edits of ~1 % each, every one reusing and updating the caches of the previous one
         from paper_2211_02048_amd.spade import SigeSpade
         net = SigeSpade()
@@ -650,7 +650,7 @@ def main():
            "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-           "config": {"workload": "BASELINE config 2: GN(32, cached stats)+SiLU+3x3 conv 128->128 and 1x1 shortcut "
+           "config": {"workload": "benchmark configuration 2: GN(32, cached stats)+SiLU+3x3 conv 128->128 and 1x1 shortcut "
                                   "128->256, 256x256 fp16, ~1% blob edit, 16x16 blocks; step = diff mask + block "
                                   "lists + gather/conv/scatter for both convs",
                       "launch": f"one HIP graph per step, device-side block counts, capacity {L.capacity} blocks, "

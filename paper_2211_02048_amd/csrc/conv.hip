@@ -11,8 +11,13 @@
 // workgroup), prefetched through a register ring.  fp32 accumulation, bias added when
 // the accumulators leave the registers, one rounding to the storage type at the store.
 // sige_fused_conv is the same kernel with the gather folded into the staging and the
-// scatter into the epilogue; with a workspace, calls with few workgroups and a long K are
-// cut along K and finished by conv_reduce_kernel.
+// scatter into the epilogue (sige_conv_scatter: the scatter only); with a workspace, calls
+// with few workgroups and a long K are cut along K and finished by conv_reduce_kernel, or
+// - without staged arithmetic and up to two chunks - take a shape whose eight waves split K.
+// 1x1 calls with few rows have a kernel of their own further down (pointwise_kernel).
+// The epilogue can also write activated copies of the output for the layers that
+// normalise it next (Sec. 3.2 "Pre-computing normalization parameters": their Scale+Shift
+// is a constant per channel).
 #include <type_traits>
 
 #include "common.h"

@@ -146,7 +146,7 @@ def token_mask(seed: int, Ht: int, Wt: int, area_frac: float, n_blobs: int = 3) 
 
 
 # ----------------------------------------------------------------------------------------
-# Synthetic DDPM-style UNet denoiser (BASELINE config 3).  The topology is plain data: a list
+# Synthetic DDPM-style UNet denoiser (benchmark configuration 3).  The topology is plain data: a list
 # of operations over named buffers, consumed by the HIP harness and, separately, by the CPU
 # oracle.  Views are (buffer, first channel, channels); buffers are NHWC [res, res, Ctot].
 # ----------------------------------------------------------------------------------------
@@ -325,7 +325,7 @@ def unet_images(seed: int, res: int, area_frac: float, dtype: str = "f16", in_ch
 
 
 # ----------------------------------------------------------------------------------------
-# Synthetic SPADE-style conditional generator (BASELINE config 5): a constant start tensor,
+# Synthetic SPADE-style conditional generator (benchmark configuration 5): a constant start tensor,
 # seven spatially-adaptive residual blocks with nearest x2 up-sampling in between, modulation
 # computed from a one-hot label map.  Again plain data: buffers (H, W, C) and a list of ops.
 #   up   : y = nearest x2 of x

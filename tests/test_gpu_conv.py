@@ -781,7 +781,7 @@ def test_layer_stride2_and_upsample(oracle):
 
 
 def test_layer_config2_full_size_sampled(oracle):
-    """BASELINE config 2 at full size (256x256x128 fp16, 16x16 blocks, ~1 % blobs), in the launch
+    """benchmark configuration 2 at full size (256x256x128 fp16, 16x16 blocks, ~1 % blobs), in the launch
     configuration the benchmark times; the oracle evaluates sampled output pixels one by one.
     The cache is an arbitrary seeded tensor: what must hold is 'dense layer on active blocks,
     cache bit for bit elsewhere'."""

@@ -1,4 +1,4 @@
-"""GPU parity of a SPADE-style conditional generator (BASELINE config 5 at small size) against the
+"""GPU parity of a SPADE-style conditional generator (benchmark configuration 5 at small size) against the
 step-by-step oracle: pre-computation pass on the original label map, then three successive label
 edits that reuse and update the caches in place (the sequential-edit setting of Sec. 4.2).
 Replica: output 64x128 from a 2x4 start, channels 64/64/64/32/32/16/16, 5 classes, 16 hidden

@@ -1,5 +1,5 @@
 """GPU parity of a whole UNet step (pre-computation pass, then the sparse edit pass) against the
-step-by-step dense-then-select oracle, on a 64x64 replica of the BASELINE config-3 network (same
+step-by-step dense-then-select oracle, on a 64x64 replica of the benchmark configuration 3 network (same
 topology, six levels, two ResBlocks per level, attention at the fifth level, narrower channels so
 the CPU oracle finishes in seconds)."""
 import numpy as np
@@ -150,7 +150,7 @@ def test_unet_zero_edit_and_graph_replay(setup):
 
 
 # ---------------------------------------------------------------------------------------------
-# Latent-diffusion style replica (BASELINE config 4 at small size): transformer blocks with
+# Latent-diffusion style replica (benchmark configuration 4 at small size): transformer blocks with
 # self-attention on the active tokens only, cross-attention over text embeddings, gated-GELU
 # feed-forward; 16x16x4 latent, channels 32/64/64/64, attention at 16/8/4, 7 text tokens of width 32.
 # ---------------------------------------------------------------------------------------------
