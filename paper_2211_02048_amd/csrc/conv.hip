@@ -783,6 +783,38 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
 #pragma unroll
     for (int st = 0; st < P; ++st) fetch_a(st, q0 + st);
 
+    // What the epilogue needs for this thread's first run of output channels and does not depend on
+    // the sums - bias and residuals - is fetched now and arrives during the K loop (the origin of the
+    // run's row comes straight from the list: LDS holds it only later).
+    const bool vec_ok = emit_vec_ok<T>(a);
+    const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
+    bool pre_ok = false;
+    long pre_pix = 0;
+    uint4 pre_t = make_uint4(0, 0, 0, 0), pre_f = make_uint4(0, 0, 0, 0);
+    float pre_bv[N];
+    {
+        const int m = tid / (BN / N), nn = (tid - m * (BN / N)) * N;
+        const int r = r0 + m, o = blockIdx.x * BN + nn;
+#pragma unroll
+        for (int i = 0; i < N; ++i) pre_bv[i] = 0.0f;
+        if (tid < BM * (BN / N) && r < rows && o < a.Cout) {
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+                if (a.bias && o + i < a.Cout) pre_bv[i] = a.bias[o + i];
+            if (to_y && vec_ok && o + N <= a.Cout) {
+                const int n = r / pb, p = r - n * pb;
+                const int py = p / a.bw, px = p - py * a.bw;
+                const int yy = a.indices[2 * n] + py, xx = a.indices[2 * n + 1] + px;
+                if (yy >= 0 && yy < a.Hout && xx >= 0 && xx < a.Wout) {
+                    pre_ok = true;
+                    pre_pix = (long)yy * a.Wout + xx;
+                    if (a.res_tiles) pre_t = *(const uint4*)((const T*)a.res_tiles + (long)r * a.Cout + o);
+                    if (a.res_full) pre_f = *(const uint4*)((const T*)a.res_full + pre_pix * a.res_ld + o);
+                }
+            }
+        }
+    }
+
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
@@ -836,8 +868,6 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
                 red[(wave * BM + m) * RS + tn * 32 + l32] = acc[tm][tn][r];
             }
     __syncthreads();
-    const bool vec_ok = emit_vec_ok<T>(a);
-    const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
     for (int e = tid; e < BM * (BN / N); e += 64 * W) {
         const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
         const int r = r0 + m, o = blockIdx.x * BN + nn;
@@ -851,20 +881,28 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
             if (yy < 0 || yy >= a.Hout || xx < 0 || xx >= a.Wout) continue;
             pix = (long)yy * a.Wout + xx;
         }
-        // bias and residuals do not depend on the sums: they are fetched before the sums are read
+        // bias and residuals do not depend on the sums: the first pass has them from the top of the
+        // kernel, later passes fetch them before the sums are read
+        const bool first = e == tid;
         const bool early_ok = to_y && vec_ok && o + N <= a.Cout;
-        uint4 early_t = make_uint4(0, 0, 0, 0), early_f = make_uint4(0, 0, 0, 0);
+        uint4 early_t = pre_t, early_f = pre_f;
         ActParams<N> ap;
-        if (early_ok) {
-            if (a.res_tiles) early_t = *(const uint4*)((const T*)a.res_tiles + t);
-            if (a.res_full) early_f = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
-            load_act_params<N>(a, o, ap);
-        }
         float v[N], bv[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             v[i] = 0.0f;
-            bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
+            bv[i] = pre_bv[i];
+        }
+        if (early_ok) {
+            load_act_params<N>(a, o, ap);
+            if (!(first && pre_ok)) {
+                if (a.res_tiles) early_t = *(const uint4*)((const T*)a.res_tiles + t);
+                if (a.res_full) early_f = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+            }
+        }
+        if (!first) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
         }
 #pragma unroll
         for (int w = 0; w < W; ++w) {
