@@ -164,15 +164,18 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
         for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.0f;
+            // all K fragments of the tile first (independent LDS reads, one latency), then the MFMAs:
+            // read one by one, each in front of its MFMA, they cost a round trip to LDS per step
+            uint4 kf[DKMAX];
 #pragma unroll
             for (int s = 0; s < DKMAX; ++s) {
-                if (s < dk) {
-                    const int dd = 16 * s + 8 * half;
-                    uint4 kf = make_uint4(0, 0, 0, 0);
-                    if (dd < d) kf = *(const uint4*)(ks + (kt * 32 + l32) * k_stride + dd * 2);
-                    Mma16<T>::run(kf, qf[s], sacc[kt]);
-                }
+                const int dd = 16 * s + 8 * half;
+                kf[s] = make_uint4(0, 0, 0, 0);
+                if (s < dk && dd < d) kf[s] = *(const uint4*)(ks + (kt * 32 + l32) * k_stride + dd * 2);
             }
+#pragma unroll
+            for (int s = 0; s < DKMAX; ++s)
+                if (s < dk) Mma16<T>::run(kf[s], qf[s], sacc[kt]);
         }
         // online softmax; of tile kt this lane holds keys 8*(r/4) + 4*half + r%4 of its query
         float mx = m_run;
@@ -209,15 +212,18 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
                 union { uint4 u; T h[8]; } pf;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf.h[e] = from_f32<T>(sacc[kt][8 * s + e]);
+                uint2 lo[DT], hi[DT];                        // likewise: the V^T fragments of all tiles, then the MFMAs
 #pragma unroll
                 for (int nt = 0; nt < DT; ++nt) {
                     const int row = nt * 32 + l32;
                     const int sw = (row >> 3) & 7;
                     const int g_lo = kt * 8 + ((4 * s + half) ^ sw), g_hi = kt * 8 + ((4 * s + 2 + half) ^ sw);
-                    const uint2 lo = *(const uint2*)(vt + row * VT_STRIDE + g_lo * 8);
-                    const uint2 hi = *(const uint2*)(vt + row * VT_STRIDE + g_hi * 8);
-                    Mma16<T>::run(make_uint4(lo.x, lo.y, hi.x, hi.y), pf.u, oacc[nt]);
+                    lo[nt] = *(const uint2*)(vt + row * VT_STRIDE + g_lo * 8);
+                    hi[nt] = *(const uint2*)(vt + row * VT_STRIDE + g_hi * 8);
                 }
+#pragma unroll
+                for (int nt = 0; nt < DT; ++nt)
+                    Mma16<T>::run(make_uint4(lo[nt].x, lo[nt].y, hi[nt].x, hi[nt].y), pf.u, oacc[nt]);
             }
     }
 
