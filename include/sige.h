@@ -198,6 +198,20 @@ int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32
                  const void* residual_tiles, const void* residual, int32_t res_ld,
                  void* y, int32_t y_ld, void* stream);
 
+/* sige_conv on the stacked tiles with the gated GELU of a feed-forward layer (sige_geglu) folded into
+ * its epilogue: the convolution has 2*Cout output channels, laid out in groups of 16 = 8 value
+ * channels followed by their 8 gate channels (pack the OIHW weight with its rows in that order:
+ * rows 16j..16j+7 = value channels 8j..8j+7, rows 16j+8..16j+15 = their gates; bias likewise,
+ * fp32 [2*Cout] or NULL), and
+ *   out[n][py][px][c] = value_c * gelu(gate_c),  gelu(g) = g/2 * (1 + erf(g / sqrt 2)),
+ * computed from the fp32 sums (the 2*Cout-channel intermediate is never stored or rounded).
+ * out_tiles: [max_blocks][block_h][block_w][Cout].  Cout must be a multiple of 8.  Never splits K
+ * over workgroups (no workspace).  Other arguments as in sige_conv.                        */
+int sige_conv_geglu(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                    const void* packed_weight, const float* bias,
+                    const int32_t* count, int32_t max_blocks, int32_t n_blocks,
+                    void* out_tiles, void* stream);
+
 /* Sec. 3.2 "Kernel fusion", the output half: sige_conv on the stacked tiles with sige_scatter
  * folded into its epilogue - the output tiles never touch HBM.  For layers whose input tiles
  * already exist (the token-wise layers between Gather and Scatter of Fig. "sige-attention":

@@ -22,7 +22,7 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
         L.sige_gather_modulated.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
         L.sige_conv.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+        L.sige_conv_geglu.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, i32, i32, vp, vp]
         L.sige_conv_scatter.argtypes = [vp, i32, gp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp, sz, vp]
         L.sige_conv_workspace_bytes.restype = ctypes.c_size_t
         L.sige_conv_workspace_bytes.argtypes = [i32, gp, i32, i32, i32]
@@ -197,6 +198,22 @@ def sige_conv(tiles, g: Geom, Cin, Cout, packed_weight, bias, count, out_tiles, 
     _check(lib().sige_conv(_ptr(tiles), _DT[tiles.dtype], ctypes.byref(g), Cin, Cout, _ptr(packed_weight),
                            _ptr(bias), _ptr(count), mb, n_blocks, _ptr(out_tiles), _ptr(workspace),
                            _nbytes(workspace), _stream()))
+
+
+def geglu_rows(n_out: int) -> torch.Tensor:
+    """Row order sige_conv_geglu expects of a [2*n_out, ...] weight / bias whose first n_out rows are the
+    values and whose last n_out rows are the gates: groups of 8 values followed by their 8 gates."""
+    j = torch.arange(n_out).view(-1, 8)
+    return torch.cat([j, j + n_out], dim=1).reshape(-1)
+
+
+def sige_conv_geglu(tiles, g: Geom, Cin, Cout, packed_weight, bias, count, out_tiles, *, n_blocks=-1,
+                    max_blocks=None):
+    """out_tiles[n] = value * gelu(gate) of the 2*Cout-channel convolution of tiles[n] (weight rows in
+    geglu_rows order)."""
+    mb = tiles.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_conv_geglu(_ptr(tiles), _DT[tiles.dtype], ctypes.byref(g), Cin, Cout, _ptr(packed_weight),
+                                 _ptr(bias), _ptr(count), mb, n_blocks, _ptr(out_tiles), _stream()))
 
 
 def sige_conv_scatter(tiles, g: Geom, indices, count, Cin, Cout, packed_weight, bias, y, *, n_blocks=-1,

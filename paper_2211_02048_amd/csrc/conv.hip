@@ -100,6 +100,9 @@ struct ConvArgs {
     struct ActOut { void* y; const float* scale; const float* shift; int ld, act; };
     ActOut ao[SIGE_MAX_ACT_OUTS];
     int n_ao;
+    // gated GELU folded into the epilogue (tiles out only): the Cout convolution channels come in
+    // groups of 16 = 8 values followed by their 8 gates; out has Cout / 2 channels
+    int glu;
 };
 
 // Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
@@ -208,6 +211,26 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
                 out[t + i] = r;
             }
         }
+    }
+}
+
+// One run of a gated-GELU output: v the N values, gt their gates (bias included in both), o the
+// convolution channel of v[0] (o % 16 < 8): out[row][(o / 16) * 8 + o % 16 + i] = v[i] * gelu(gt[i]),
+// gelu(g) = g/2 * (1 + erf(g / sqrt 2)).
+template <typename T>
+__device__ __forceinline__ void emit_glu(const ConvArgs& a, long row, int o, float (&v)[Vec16<T>::N],
+                                         const float (&gt)[Vec16<T>::N])
+{
+    constexpr int N = Vec16<T>::N;
+    const int Cg = a.Cout / 2, oo = (o >> 4) * 8 + (o & 15);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] *= 0.5f * gt[i] * (1.0f + erff(gt[i] * 0.70710678118654752f));
+    T* dst = (T*)a.out + row * Cg + oo;
+    if (Cg % N == 0 && aligned16_dev(a.out)) {
+        *(uint4*)dst = pack<T>(v);
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) dst[i] = from_f32<T>(v[i]);
     }
 }
 
@@ -539,6 +562,21 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
             const int g = m / pb, p = m - g * pb;
             const int py = p / a.bw, px = p - py * a.bw;
             if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
+            if (a.glu) {          // value runs finish themselves and their gates, gate runs have nothing to do
+                if ((o & 15) >= 8) continue;
+                float v[N], gt[N];
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    v[i] = gt[i] = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < WK; ++w) {
+                        v[i] += red[(w * BM + m) * RS + nn + i];
+                        gt[i] += red[(w * BM + m) * RS + nn + 8 + i];
+                    }
+                }
+                emit_glu<T>(a, ((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px, o, v, gt);
+                continue;
+            }
             ActParams<N> ap;
             if (vec_ok && o + N <= a.Cout) load_act_params<N>(a, o, ap);
             float v[N];
@@ -872,6 +910,24 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
         const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;
         const int r = r0 + m, o = blockIdx.x * BN + nn;
         if (r >= rows || o >= a.Cout) continue;
+        if (a.glu) {              // value runs finish themselves and their gates, gate runs have nothing to do
+            if ((o & 15) >= 8) continue;
+            float v[N], gt[N];
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                v[i] = a.bias ? a.bias[o + i] : 0.0f;
+                gt[i] = a.bias ? a.bias[o + 8 + i] : 0.0f;
+            }
+#pragma unroll
+            for (int w = 0; w < W; ++w)
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    v[i] += red[(w * BM + m) * RS + nn + i];
+                    gt[i] += red[(w * BM + m) * RS + nn + 8 + i];
+                }
+            emit_glu<T>(a, r, o, v, gt);
+            continue;
+        }
         const long t = (long)r * a.Cout + o;
         long pix = 0;
         if (to_y) {
@@ -1219,7 +1275,7 @@ static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, 
     }
     ConvPlan p;
     const bool ws_ok = workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
-    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok ? workspace_bytes / sizeof(float) : 0,
+    SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok && !a.glu ? workspace_bytes / sizeof(float) : 0,
                            a.scale != nullptr || a.act != SIGE_ACT_NONE, &p),
                  SIGE_ERR_UNSUPPORTED, "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who,
                  g->block_h, g->block_w, g->k, g->stride, Cin);
@@ -1279,6 +1335,31 @@ extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, i
     ConvArgs a = {};
     a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
     return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
+}
+
+extern "C" int sige_conv_geglu(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
+                               const void* packed_weight, const float* bias, const int32_t* count,
+                               int32_t max_blocks, int32_t n_blocks, void* out_tiles, void* stream)
+{
+    clear_error();
+    const char* who = "sige_conv_geglu";
+    int th, tw, nl;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
+    SIGE_REQUIRE(tiles && packed_weight && out_tiles, SIGE_ERR_INVALID_ARG,
+                 "%s: tiles, packed_weight and out_tiles are required", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cin > 0 && Cout > 0, SIGE_ERR_INVALID_ARG, "%s: Cin and Cout must be positive", who);
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
+    SIGE_REQUIRE(Cout % 8 == 0, SIGE_ERR_UNSUPPORTED, "%s: Cout must be a multiple of 8 (values and gates come in groups of 8)", who);
+    SIGE_REQUIRE(aligned16(tiles) && aligned16(packed_weight), SIGE_ERR_UNSUPPORTED,
+                 "%s: tiles and packed_weight must be 16-byte aligned", who);
+    if (nl == 0) return SIGE_OK;
+    ConvArgs a = {};
+    a.tiles = tiles; a.w = packed_weight; a.bias = bias; a.out = out_tiles; a.count = count;
+    a.glu = 1;
+    return run_conv(who, dt, g, th, tw, Cin, 2 * Cout, max_blocks, n_blocks, nl, a, nullptr, 0, stream);
 }
 
 extern "C" int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,

@@ -64,8 +64,12 @@ class SigeUNet:
                 assert r_in % b == 0, "token blocks must tile the map exactly"
                 Cx, nc, dc = op["C"], op["n_ctx"], op["d_ctx"]
                 lin = lambda part: SigeConv(P[f"{n}.{part}.w"].to(device), P[f"{n}.{part}.b"], r_in, r_in, b, 1, 0)
-                for part in ("in", "q1", "o1", "q2", "o2", "ff1", "ff2", "out"):
+                for part in ("in", "q1", "o1", "q2", "o2", "ff2", "out"):
                     L[part] = lin(part)
+                # the first feed-forward layer carries the gated GELU in its epilogue: values and gates
+                # interleaved in groups of 8 (a row permutation of the weight, no arithmetic)
+                rows = api.geglu_rows(4 * Cx)
+                L["ff1"] = SigeConv(P[f"{n}.ff1.w"][rows].to(device), P[f"{n}.ff1.b"][rows], r_in, r_in, b, 1, 0)
                 L["kv1"] = SigeConv(torch.cat([P[f"{n}.k1.w"], P[f"{n}.v1.w"]], 0).to(device),
                                     torch.cat([P[f"{n}.k1.b"], P[f"{n}.v1.b"]], 0), r_in, r_in, b, 1, 0)
                 # keys and values of the text embeddings: a 1 x n_ctx "image", one block
@@ -308,9 +312,9 @@ class SigeUNet:
         back(L["o2"], o, L["h2"], L["h1"])
         # gated-GELU feed-forward
         tn = normed(L["h2"], "ln3")
-        u = conv(L["ff1"], tn, "x_u")
         gg = tiles("x_g", 4 * C)
-        api.sige_geglu(u, gg, 4 * C, n_rows=rows)
+        api.sige_conv_geglu(tn, L["ff1"].g, C, 4 * C, L["ff1"].packed, L["ff1"].bias, cnt, gg, n_blocks=nb,
+                            max_blocks=nb)
         back(L["ff2"], gg, L["h3"], L["h2"])
         L["out"].forward(L["h3"], y, bl, ws, residual=x, fused=True, act_outs=act_outs)
 

@@ -93,6 +93,9 @@ def test_pointer_and_capacity_errors(L):
     ao[0].y_ld = 60                                                            # narrower than Cout
     assert L.sige_fused_conv(FAKE, 1, 64, 64, 0, gp, FAKE, FAKE, 8, -1, None, None, 0, 64, FAKE, None, None, None, 0,
                              FAKE, 64, None, ao, 1, None, 0, None) == 1
+    # convolution with the gated GELU folded in: output channels in groups of 8
+    assert L.sige_conv_geglu(FAKE, 1, gp, 64, 12, FAKE, None, FAKE, 8, -1, FAKE, None) == 2
+    assert L.sige_conv_geglu(FAKE, 1, gp, 64, 16, FAKE, None, FAKE, 8, -1, None, None) == 1
     # convolution with the scatter folded in, gather with the token norm folded in
     assert L.sige_conv_scatter(FAKE, 1, gp, 64, 64, FAKE, None, None, FAKE, 8, -1, None, None, 0, FAKE, 64, None, 0, None) == 1
     assert L.sige_conv_scatter(FAKE, 1, gp, 64, 64, FAKE, None, FAKE, FAKE, 8, -1, None, None, 0, FAKE, 32, None, 0, None) == 1

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import expected_tiles, assert_close, assert_mostly_close, dev, f64
+from helpers import round_to, expected_tiles, assert_close, assert_mostly_close, dev, f64
 from paper_2211_02048_amd import api, inputs
 
 pytestmark = pytest.mark.gpu
@@ -280,3 +280,37 @@ def test_gather_token_norm(oracle, dtype, C, res, b, n):
     assert torch.equal(t1, tiles)
     with pytest.raises(api.SigeError):
         api.sige_gather_token_norm(x, api.geom(res, res, b, 3, 1, 1), idx, cnt, tiles, C, n_blocks=n)
+
+
+@pytest.mark.parametrize("dtype,Cin,Cg,b,n", [("bf16", 320, 1280, 8, 10), ("f16", 64, 24, 4, 5), ("f32", 32, 16, 3, 7),
+                                               ("bf16", 1280, 512, 8, 2), ("f16", 128, 2560, 8, 1)])
+def test_conv_geglu(oracle, dtype, Cin, Cg, b, n):
+    """The feed-forward layer with the gated GELU folded into its epilogue: against the oracle's
+    convolution (fp64, unrounded) followed by its gated GELU; tiled and few-row kernels (chosen by size);
+    both count paths; tiles beyond the count untouched."""
+    rng = np.random.default_rng(Cin + Cg + b)
+    td = DT[dtype]
+    g = api.geom(8 * b, 8 * b, b, 1, 1, 0)
+    tiles = torch.from_numpy(rng.standard_normal((n, b, b, Cin)).astype(np.float32)).to(td)
+    w, bias = inputs.conv_params(rng, 2 * Cg, Cin, 1, td)
+    u = np.stack([oracle.conv2d(f64(tiles[i]), f64(w), f64(bias), 1, 0) for i in range(n)])     # [n, b, b, 2Cg]
+    want = oracle.geglu(u.reshape(-1, 2 * Cg)).reshape(n, b, b, Cg)
+    rows = api.geglu_rows(Cg)
+    packed = api.sige_pack_weight(dev(w[rows].contiguous()))
+    cnt = torch.tensor([n], dtype=torch.int32, device="cuda")
+    for nb, mb in ((n, n), (-1, n + 1)):
+        out = torch.full((n + 1, b, b, Cg), 5.0, dtype=td, device="cuda")
+        big = torch.cat([dev(tiles), torch.zeros((1, b, b, Cin), dtype=td, device="cuda")])
+        api.sige_conv_geglu(big, g, Cin, Cg, packed, dev(bias[rows].contiguous()), cnt, out, n_blocks=nb, max_blocks=mb)
+        assert_close(out[:n], want, td, f"conv + gated GELU n_blocks={nb}")
+        assert (out[n:] == 5.0).all()
+    # the two calls it replaces: convolution (stored, rounded), then sige_geglu
+    o2 = torch.empty((n, b, b, 2 * Cg), dtype=td, device="cuda")
+    api.sige_conv(dev(tiles), g, Cin, 2 * Cg, api.sige_pack_weight(dev(w)), dev(bias), cnt, o2, n_blocks=n, max_blocks=n)
+    y2 = torch.empty((n, b, b, Cg), dtype=td, device="cuda")
+    api.sige_geglu(o2, y2, Cg, n_rows=n * b * b)
+    # (their intermediate is a stored tensor: the oracle rounds it to the storage type too)
+    want2 = oracle.geglu(round_to(u, td).reshape(-1, 2 * Cg)).reshape(n, b, b, Cg)
+    assert_mostly_close(y2, want2, td, "conv, then gated GELU")   # (a 1-ulp flip of the stored intermediate shows)
+    with pytest.raises(api.SigeError):
+        api.sige_conv_geglu(dev(tiles), g, Cin, Cg + 4, packed, None, cnt, out, n_blocks=n, max_blocks=n)
