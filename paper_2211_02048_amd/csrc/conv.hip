@@ -370,14 +370,16 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
     };
     const bool fused = a.x != nullptr;
     const bool fuse_math = fused && (a.scale != nullptr || a.act != SIGE_ACT_NONE);
-    // Staging of one channel chunk.  NT is a multiple of VPC, so a thread keeps one 16-byte channel
+    // Staging of one channel chunk.  The staging threads are a multiple of VPC (the few left over when
+    // VPC does not divide NT sit the staging out), so a thread keeps one 16-byte channel
     // group and walks over the pixels NT / VPC at a time without dividing.  Each batch of U vectors
     // is loaded before any of them is used (addresses are clamped into the source, so the loads are
     // unconditional and overlap; what lies outside becomes zero afterwards).
     constexpr int U = TM * TN >= 4 ? 6 : 8;                   // fewer where the accumulators leave fewer registers
     constexpr int PPI = NT / VPC;                             // pixels covered by one step of the walk
+    constexpr int NTS = PPI * VPC;                            // threads that stage (all of them unless VPC is 40 or 80)
     const int sv = tid % VPC;
-    int sq0 = tid / VPC, sg0, sr0, sx0;                       // first pixel of this thread: index, block, row, column
+    int sq0 = tid < NTS ? tid / VPC : npix, sg0, sr0, sx0;    // first pixel of this thread: index, block, row, column
     int step_g, step_r, step_x;                               // PPI pixels further, in the same mixed radix
     {
         const int per = a.trows * a.tw;
@@ -977,7 +979,7 @@ __global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
 
 struct ConvPlan {
     int cfg;  // index into kCfg
-    int kc;   // K steps per staged channel chunk: 8, 4 or 1
+    int kc;   // K steps per staged channel chunk: 8, 4 or 1; 16 to 40 in the shapes that stage the whole of Cin
     int G, rows, trows, Cc, ps, bands, slabs, groups;
     int ksplit;   // workgroups that share one output patch along K (1 = no split)
     size_t lds;
@@ -996,6 +998,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
 {
     const char* force = getenv("SIGE_CONV_CFG");
     const char* force_kc = getenv("SIGE_CONV_KC");   // tuning aids: fix the shape / the K steps per chunk
+    const bool force_whole = force && atoi(force) >= 3 && force_kc && atoi(force_kc) >= 16;
     double best_score = -1.0;
     auto lds_bytes = [&](int cfg, long npix, int kc) {
         size_t lds = (size_t)npix * (kc * kstep * s + 16);
@@ -1005,7 +1008,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         return lds <= (kc == 1 || (kc == 4 && kCfg[cfg].WK == 4) ? 160u : 80u) * 1024u;
     };
     for (int cfg = 0; cfg < kNumCfg; ++cfg) {
-        if (force && atoi(force) != cfg) continue;
+        if (force && !force_whole && atoi(force) != cfg) continue;
         if (g->k != 1 && g->k != 3 && cfg != 2) continue;   // only the plain 64x64 shape is built for other k
         const int M = kCfg[cfg].M, Nn = kCfg[cfg].N, WK = kCfg[cfg].WK;
         if (g->block_w > M) continue;
@@ -1023,7 +1026,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         // K steps per chunk: the largest of 8 / 4 / 1 that divides Cin and whose staged tile fits
         p.kc = 0;
         for (int kc : {8, 4, 1}) {
-            if (force_kc && atoi(force_kc) != kc) continue;
+            if (force_kc && !force_whole && atoi(force_kc) != kc) continue;
             if (kc % WK || Cin % (kc * kstep)) continue;
             if (g->k != 1 && g->k != 3 && kc != 1) continue;
             const size_t lds = lds_bytes(cfg, npix, kc);
@@ -1044,18 +1047,20 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     if (best_score < 0.0) return false;
     // K split over workgroups.  A workgroup walks through its channel chunks one after the other and
     // each costs a staging round trip (a few microseconds), so a call with at most one workgroup per
-    // compute unit and at least three chunks (320 channels or more in the half types) is cut along K
-    // (up to four workgroups per compute unit; with fewer chunks the second kernel costs more than it
-    // saves); smaller chunks when that is what it takes to reach 256 workgroups.
+    // compute unit and at least three chunks (320 channels or more in the half types) is cut along K,
+    // to about 200 workgroups in all: measured with weights that come from HBM (a network's do), more
+    // shares than that cost more in the second kernel than they save in the first.  Smaller chunks
+    // when that is what it takes to reach 256 workgroups.
     ConvPlan& p = *best;
     const char* force_split = getenv("SIGE_CONV_SPLIT");
     // Few workgroups and a long K, nothing to compute while staging (no Scale+Shift, no activation):
-    // 64 x 32 patches whose EIGHT waves split K, with 256 or 512 channels staged per chunk.  One
-    // kernel, no workspace; the waves' sums meet in LDS.  (With staged arithmetic the chunk would
-    // cost every workgroup eight times the activation work of the four-wave shape's.)
-    if (g->k == 3 && !staged_math && !force && !force_kc && !force_split && g->block_w <= 64 && Cin >= 20 * kstep) {
+    // 64 x 32 patches whose waves split K, with the whole of Cin (or half of it) staged at once -
+    // eight waves over 256, 512 or 640 channels, four over 320.  One kernel, no workspace; the waves'
+    // sums meet in LDS.  (With staged arithmetic the chunk would cost every workgroup many times the
+    // activation work of the plain four-wave shape's.)
+    if (g->k == 3 && g->block_w <= 64 &&
+        (force_whole || (!staged_math && !force && !force_kc && !force_split && Cin >= 20 * kstep))) {
         ConvPlan q;
-        q.cfg = 4;
         q.ksplit = 1;
         const int M = 64, pbfull = g->block_h * g->block_w;
         if (pbfull <= M) { q.G = M / pbfull; q.rows = g->block_h; }
@@ -1066,19 +1071,21 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         q.groups = (nblocks + q.G - 1) / q.G;
         const long npix = (long)q.G * q.trows * tw;
         q.kc = 0;
-        for (int kc : {32, 16}) {
-            if (Cin % (kc * kstep)) continue;
-            const size_t lds = lds_bytes(4, npix, kc);
-            if (lds <= 150u * 1024u) { q.kc = kc; q.lds = lds; break; }
+        static const int cand[4][2] = {{4, 40}, {4, 32}, {4, 16}, {3, 20}};   // shape, K steps per chunk
+        for (const auto& c : cand) {
+            if (force_whole && (atoi(force) != c[0] || atoi(force_kc) != c[1])) continue;
+            // at most two chunks: beyond that a workgroup streams so much weight by itself that the
+            // cut over workgroups below, second kernel included, is faster
+            if (Cin % (c[1] * kstep) || (!force_whole && Cin / (c[1] * kstep) > (c[1] == 40 ? 1 : 2))) continue;
+            const size_t lds = lds_bytes(c[0], npix, c[1]);
+            if (lds <= (c[0] == 4 ? 150u : 75u) * 1024u) { q.cfg = c[0]; q.kc = c[1]; q.lds = lds; break; }
         }
         const long wgs4 = (long)q.groups * q.bands * q.slabs;
-        // at most two chunks: beyond that a workgroup streams so much weight by itself that the cut
-        // over workgroups below, second kernel included, is faster
-        if (q.kc && wgs4 <= 256 && Cin / (q.kc * kstep) <= 2) {
+        if (q.kc && (wgs4 <= 256 || force_whole)) {
             q.Cc = q.kc * kstep;
             q.ps = (int)(q.Cc * s + 16);
             p = q;
-            return true;
+            if (!force_whole) return true;
         }
     }
     const long wgs = (long)p.groups * p.bands * p.slabs;
@@ -1090,7 +1097,9 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         if (kc == 8 && wgs * (Cin / (8 * kstep)) < 256 && 4 % WK == 0 && !force_kc) kc = 4;
         const int nch = Cin / (kc * kstep);
         int S = 1;
-        if (wgs <= 256 && nch >= 3 && Cin >= 20 * kstep) S = (int)std::min<long>(nch, (1024 + wgs - 1) / wgs);
+        const char* tw_env = getenv("SIGE_CONV_SPLIT_WGS");   // tuning aid
+        const long target = tw_env ? atol(tw_env) : 200;
+        if (wgs <= 256 && nch >= 3 && Cin >= 20 * kstep) S = (int)std::min<long>(nch, (target + wgs - 1) / wgs);
         if (force_split) S = std::min(atoi(force_split), nch);
         S = std::max(1, std::min(S, max_by_ws));
         if (S > 1) {
@@ -1136,7 +1145,7 @@ static int launch_kc(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
         if constexpr (KC <= 8) return launch_cfg<T, 1, 1, 2, 2, 1, KC, KK>(a, p, st);
         break;
     case 3:
-        if constexpr (KC % 4 == 0 && KC <= 8) return launch_cfg<T, 2, 1, 1, 1, 4, KC, KK>(a, p, st);
+        if constexpr (KC % 4 == 0 && (KC <= 8 || (KC == 20 && KK == 9))) return launch_cfg<T, 2, 1, 1, 1, 4, KC, KK>(a, p, st);
         break;
     default:
         if constexpr (KC % 8 == 0 && KC >= 16 && KK == 9) return launch_cfg<T, 2, 1, 1, 1, 8, KC, KK>(a, p, st);
@@ -1149,7 +1158,9 @@ template <typename T, int KK>
 static int launch_kk(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
 {
     switch (p.kc) {
+    case 40: return launch_kc<T, 40, KK>(a, p, st);
     case 32: return launch_kc<T, 32, KK>(a, p, st);
+    case 20: return launch_kc<T, 20, KK>(a, p, st);
     case 16: return launch_kc<T, 16, KK>(a, p, st);
     case 8: return launch_kc<T, 8, KK>(a, p, st);
     case 4: return launch_kc<T, 4, KK>(a, p, st);

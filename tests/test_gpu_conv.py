@@ -346,7 +346,10 @@ def test_conv_on_tiles(oracle, dtype, Cin, Cout, b, k, s, n):
 
 @pytest.mark.parametrize("dtype,Cin,Cout,res,b,k", [
     ("f16", 512, 96, 8, 8, 3), ("bf16", 384, 136, 16, 16, 3), ("f32", 192, 32, 8, 8, 3),
-    ("f16", 384, 64, 8, 4, 1), ("f16", 512, 33, 12, 8, 3)])
+    ("f16", 384, 64, 8, 4, 1), ("f16", 512, 33, 12, 8, 3),
+    # the whole of Cin (or half) staged at once, waves split K: 320 (four waves), 640, 2 x 640
+    ("bf16", 320, 72, 16, 8, 3), ("f16", 640, 40, 16, 8, 3), ("bf16", 1280, 64, 8, 8, 3),
+    ("f16", 320, 64, 10, 4, 3), ("f32", 160, 32, 12, 8, 3), ("f32", 320, 40, 8, 8, 3)])
 def test_conv_k_split_over_workgroups(oracle, dtype, Cin, Cout, res, b, k):
     """Few blocks, many input channels: with a workspace the call is cut along K over several
     workgroups and a second kernel adds the shares.  Against the oracle; the workspace is poisoned
