@@ -279,6 +279,22 @@ int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, const void* v, 
                      void* o, int32_t o_ld, void* workspace, size_t workspace_bytes, void* stream);
 size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_t heads, int32_t d);
 
+/* The same attention with the queries taken straight from a full-resolution tensor by
+ * block list (Fig. "sige-attention": the gather of the query tokens folded into the
+ * attention call): q is [H_in*W_in][heads][d] with row stride q_ld, one row per pixel;
+ * query i of the call is pixel i % (block_h*block_w) (row-major inside the block) of
+ * block i / (block_h*block_w), whose top-left corner is indices[2*b], indices[2*b+1];
+ * Nq = n_blocks * block_h * block_w and o is the [Nq][heads][d] stacked result, as
+ * above.  g must be the geometry of a 1x1, stride-1, unpadded layer; n_blocks is a
+ * host value >= 0 (0 enqueues nothing).  Pixels of a block that stick out of the map
+ * read the nearest pixel inside it.  Use sige_sparse_attn_workspace_bytes with that Nq.
+ * With q, k and v three channel ranges of one cached tensor, one convolution
+ * (sige_conv_scatter) can refresh all three for the active tokens.                  */
+int sige_sparse_attn_blocks(const void* q, int32_t q_ld, const sige_geom* g, const int32_t* indices,
+                            int32_t n_blocks, const void* k, const void* v, int32_t kv_ld,
+                            sige_dtype dt, int32_t T, int32_t heads, int32_t d, float scale,
+                            void* o, int32_t o_ld, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Sec. 3.2 "Extension to attention layers" (Fig. "sige-attention"): between Gather and
  * Scatter an attention block sees only the tokens of the active blocks, so its token-wise
  * layers run on the stacked tiles, one row per token: x is [n_rows][C] with row stride x_ld,

@@ -22,7 +22,7 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_sparse_attn",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_sparse_attn", "sige_sparse_attn_blocks",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -98,6 +98,7 @@ def lib() -> ctypes.CDLL:
         L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
         L.sige_sparse_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
         L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sige_sparse_attn_blocks.argtypes = [vp, i32, gp, vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
         L.sige_packed_weight_bytes.argtypes = [i32, i32, i32, i32]
         L.sige_pack_weight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.sige_token_norm.argtypes = [vp, i32, i32, i32, vp, i32, i32, i32, vp, vp, f32, vp, i32, vp]
@@ -321,6 +322,20 @@ def sige_sparse_attn(q, k, v, o, scale, *, Nq=None, workspace=None, heads=None, 
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sige_sparse_attn(_ptr(q), q_ld, _ptr(k), _ptr(v), kv_ld, _DT[q.dtype], Nq, T, heads, d,
                                   scale, _ptr(o), o_ld, _ptr(workspace), wsb, _stream()))
+
+
+def sige_sparse_attn_blocks(q_full, g: Geom, indices, n_blocks, k, v, o, scale, *, heads, d, workspace=None,
+                            q_ld=None, kv_ld=None, o_ld=None):
+    """The same with the queries read from a full tensor by block list: query i is pixel
+    i % (block_h*block_w) of block i / (block_h*block_w); o holds the stacked rows."""
+    T = k.shape[0]
+    q_ld = q_full.stride(-2) if q_ld is None else q_ld
+    kv_ld = k.stride(0) if kv_ld is None else kv_ld
+    o_ld = o.stride(0) if o_ld is None else o_ld
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sige_sparse_attn_blocks(_ptr(q_full), q_ld, ctypes.byref(g), _ptr(indices), n_blocks, _ptr(k),
+                                         _ptr(v), kv_ld, _DT[q_full.dtype], T, heads, d, scale, _ptr(o), o_ld,
+                                         _ptr(workspace), wsb, _stream()))
 
 
 def sige_packed_weight_bytes(dtype, Cout, Cin, k) -> int:

@@ -54,6 +54,10 @@ struct AttnArgs {
     int Nq, T, heads, d;
     int splits, chunks_per_split;
     float scale_log2e;
+    // queries taken from a full tensor by block list (q_blocks != NULL): query i is pixel i % q_tpb of
+    // block i / q_tpb, at row (y0 + py) * q_W + x0 + px of q (clamped into the q_H x q_W map)
+    const int32_t* q_blocks;
+    int q_tpb, q_bw, q_H, q_W;
 };
 
 // 32-key tiles per chunk, by head size (DT = 32-wide tiles over d)
@@ -89,12 +93,19 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
 
     // Q fragments (B operand of S^T = K Q^T): 8 consecutive d values of this lane's query
     uint4 qf[DKMAX];
+    long qrow = qi;
+    if (a.q_blocks != nullptr && q_ok) {
+        const int b = qi / a.q_tpb, p = qi - b * a.q_tpb;
+        const int py = p / a.q_bw, px = p - py * a.q_bw;
+        const int y0 = a.q_blocks[2 * b], x0 = a.q_blocks[2 * b + 1];
+        qrow = (long)min(max(y0 + py, 0), a.q_H - 1) * a.q_W + min(max(x0 + px, 0), a.q_W - 1);
+    }
 #pragma unroll
     for (int s = 0; s < DKMAX; ++s) {
         const int dd = 16 * s + 8 * half;
         qf[s] = make_uint4(0, 0, 0, 0);
         if (q_ok && dd < d)
-            qf[s] = *(const uint4*)((const char*)a.q + ((long)qi * a.q_ld + head * d + dd) * 2);
+            qf[s] = *(const uint4*)((const char*)a.q + (qrow * a.q_ld + head * d + dd) * 2);
     }
     // rows d .. DT*32 of V^T never receive data: zero them once
     for (int j = tid; j < (DT * 32 - d) * (VT_STRIDE / 4); j += 256)
@@ -372,13 +383,10 @@ extern "C" size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_
     return (size_t)splits * heads * Nq * (d + 2) * sizeof(float);
 }
 
-extern "C" int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, const void* v, int32_t kv_ld,
-                                sige_dtype dt, int32_t Nq, int32_t T, int32_t heads, int32_t d,
-                                float scale, void* o, int32_t o_ld, void* workspace,
-                                size_t workspace_bytes, void* stream)
+static int attn_entry(const char* who, AttnArgs& a, const void* q, int32_t q_ld, const void* k, const void* v,
+                      int32_t kv_ld, sige_dtype dt, int32_t Nq, int32_t T, int32_t heads, int32_t d, float scale,
+                      void* o, int32_t o_ld, void* workspace, size_t workspace_bytes, void* stream)
 {
-    clear_error();
-    const char* who = "sige_sparse_attn";
     SIGE_REQUIRE(Nq >= 0 && T > 0 && heads > 0 && d > 0, SIGE_ERR_INVALID_ARG,
                  "%s: need Nq >= 0, T > 0, heads > 0, d > 0", who);
     SIGE_REQUIRE(dt == SIGE_F16 || dt == SIGE_BF16, SIGE_ERR_UNSUPPORTED, "%s: dtype must be f16 or bf16", who);
@@ -392,7 +400,6 @@ extern "C" int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, cons
                  "%s: row strides must be multiples of 8 elements", who);
     SIGE_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o), SIGE_ERR_UNSUPPORTED,
                  "%s: pointers must be 16-byte aligned", who);
-    AttnArgs a;
     a.q = q; a.k = k; a.v = v; a.o = o; a.ws = (float*)workspace;
     a.q_ld = q_ld; a.kv_ld = kv_ld; a.o_ld = o_ld;
     a.Nq = Nq; a.T = T; a.heads = heads; a.d = d;
@@ -408,4 +415,43 @@ extern "C" int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, cons
     a.splits = (chunks + a.chunks_per_split - 1) / a.chunks_per_split;
     hipStream_t st = (hipStream_t)stream;
     return dt == SIGE_F16 ? launch_attn<f16>(a, st) : launch_attn<bf16>(a, st);
+}
+
+extern "C" int sige_sparse_attn(const void* q, int32_t q_ld, const void* k, const void* v, int32_t kv_ld,
+                                sige_dtype dt, int32_t Nq, int32_t T, int32_t heads, int32_t d,
+                                float scale, void* o, int32_t o_ld, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    AttnArgs a;
+    a.q_blocks = nullptr;
+    a.q_tpb = a.q_bw = a.q_H = a.q_W = 1;
+    return attn_entry("sige_sparse_attn", a, q, q_ld, k, v, kv_ld, dt, Nq, T, heads, d, scale, o, o_ld, workspace,
+                      workspace_bytes, stream);
+}
+
+extern "C" int sige_sparse_attn_blocks(const void* q, int32_t q_ld, const sige_geom* g, const int32_t* indices,
+                                       int32_t n_blocks, const void* k, const void* v, int32_t kv_ld,
+                                       sige_dtype dt, int32_t T, int32_t heads, int32_t d, float scale, void* o,
+                                       int32_t o_ld, void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    const char* who = "sige_sparse_attn_blocks";
+    SIGE_REQUIRE(g != nullptr, SIGE_ERR_INVALID_ARG, "%s: geometry is required", who);
+    SIGE_REQUIRE(g->k == 1 && g->stride == 1 && g->pad == 0 && g->block_h > 0 && g->block_w > 0 && g->H_in > 0 &&
+                     g->W_in > 0,
+                 SIGE_ERR_UNSUPPORTED, "%s: the geometry must be that of a 1x1, stride-1, unpadded layer", who);
+    SIGE_REQUIRE(n_blocks >= 0, SIGE_ERR_INVALID_ARG, "%s: n_blocks must be a host value >= 0", who);
+    SIGE_REQUIRE((long)n_blocks * g->block_h * g->block_w <= 0x7fffffffL, SIGE_ERR_UNSUPPORTED,
+                 "%s: too many query rows", who);
+    if (n_blocks == 0) return SIGE_OK;
+    SIGE_REQUIRE(indices != nullptr, SIGE_ERR_INVALID_ARG, "%s: indices are required", who);
+    AttnArgs a;
+    a.q_blocks = indices;
+    a.q_tpb = g->block_h * g->block_w;
+    a.q_bw = g->block_w;
+    a.q_H = g->H_in;
+    a.q_W = g->W_in;
+    return attn_entry(who, a, q, q_ld, k, v, kv_ld, dt, n_blocks * a.q_tpb, T, heads, d, scale, o, o_ld, workspace,
+                      workspace_bytes, stream);
 }

@@ -64,14 +64,15 @@ class SigeUNet:
                 assert r_in % b == 0, "token blocks must tile the map exactly"
                 Cx, nc, dc = op["C"], op["n_ctx"], op["d_ctx"]
                 lin = lambda part: SigeConv(P[f"{n}.{part}.w"].to(device), P[f"{n}.{part}.b"], r_in, r_in, b, 1, 0)
-                for part in ("in", "q1", "o1", "q2", "o2", "ff2", "out"):
+                for part in ("in", "o1", "q2", "o2", "ff2", "out"):
                     L[part] = lin(part)
                 # the first feed-forward layer carries the gated GELU in its epilogue: values and gates
                 # interleaved in groups of 8 (a row permutation of the weight, no arithmetic)
                 rows = api.geglu_rows(4 * Cx)
                 L["ff1"] = SigeConv(P[f"{n}.ff1.w"][rows].to(device), P[f"{n}.ff1.b"][rows], r_in, r_in, b, 1, 0)
-                L["kv1"] = SigeConv(torch.cat([P[f"{n}.k1.w"], P[f"{n}.v1.w"]], 0).to(device),
-                                    torch.cat([P[f"{n}.k1.b"], P[f"{n}.v1.b"]], 0), r_in, r_in, b, 1, 0)
+                # self-attention: queries, keys and values from one convolution, into one cached tensor
+                L["qkv1"] = SigeConv(torch.cat([P[f"{n}.{p}1.w"] for p in "qkv"], 0).to(device),
+                                     torch.cat([P[f"{n}.{p}1.b"] for p in "qkv"], 0), r_in, r_in, b, 1, 0)
                 # keys and values of the text embeddings: a 1 x n_ctx "image", one block
                 L["kv2"] = SigeConv(torch.cat([P[f"{n}.k2.w"], P[f"{n}.v2.w"]], 0).to(device),
                                     torch.cat([P[f"{n}.k2.b"], P[f"{n}.v2.b"]], 0), 1, nc, (1, nc), 1, 0)
@@ -81,7 +82,7 @@ class SigeUNet:
                     L[part + ".g"], L[part + ".b"] = f32(P[f"{n}.{part}.gamma"]), f32(P[f"{n}.{part}.beta"])
                 for name in ("h0", "h1", "h2", "h3"):
                     L[name] = torch.zeros((r_in, r_in, Cx), dtype=self.td, device=device)
-                L["kv"] = torch.zeros((r_in, r_in, 2 * Cx), dtype=self.td, device=device)
+                L["qkv"] = torch.zeros((r_in, r_in, 3 * Cx), dtype=self.td, device=device)
                 L["g1"] = L["in"].g
                 L["list"] = self._lists(r_in, 3, 1, b)
             else:
@@ -278,12 +279,16 @@ class SigeUNet:
                                        gamma=L[part + ".g"], beta=L[part + ".b"], eps=1e-5)
             return tn
 
-        def attend(q, k, v, Tk, kv_ld):
+        def attend(q, k, v, Tk, kv_ld, q_full=None):
             o = tiles("x_o", C)
             nbytes = api.sige_sparse_attn_workspace_bytes(rows, Tk, heads, d)
             aws = ws.get("attn_ws", nbytes // 4, torch.float32) if nbytes else None
-            api.sige_sparse_attn(q.view(rows, C), k, v, o.view(rows, C), sm, Nq=rows, workspace=aws, heads=heads,
-                                 d=d, q_ld=C, kv_ld=kv_ld, o_ld=C)
+            if q_full is not None:      # the queries of the active tokens, read from the cached tensor by block list
+                api.sige_sparse_attn_blocks(q_full, g1, idx, nb, k, v, o.view(rows, C), sm, heads=heads, d=d,
+                                            workspace=aws, q_ld=kv_ld, kv_ld=kv_ld, o_ld=C)
+            else:
+                api.sige_sparse_attn(q.view(rows, C), k, v, o.view(rows, C), sm, Nq=rows, workspace=aws,
+                                     heads=heads, d=d, q_ld=C, kv_ld=kv_ld, o_ld=C)
             return o
 
         def back(layer, src, dst, residual=None):      # convolution with the scatter folded in
@@ -298,12 +303,12 @@ class SigeUNet:
             api.sige_conv(L["ctx"].view(1, 1, -1, kv2.Cin), kv2.g, kv2.Cin, kv2.Cout, kv2.packed, kv2.bias, one,
                           L["kc"].view(1, 1, -1, 2 * C), n_blocks=1, max_blocks=1)
         L["in"].forward(xn, L["h0"], bl, ws, scale=scale, shift=shift, fused=True)
-        # self-attention: only the active tokens' queries; their keys and values go into the caches first
+        # self-attention: only the active tokens' queries; their queries, keys and values go into the
+        # cache first, in one convolution
         tn = normed(L["h0"], "ln1")
-        q = conv(L["q1"], tn, "x_q")
-        back(L["kv1"], tn, L["kv"])
-        kvc = L["kv"].view(T, 2 * C)
-        o = attend(q, kvc[:, :C], kvc[:, C:], T, 2 * C)
+        back(L["qkv1"], tn, L["qkv"])
+        qkv = L["qkv"].view(T, 3 * C)
+        o = attend(None, qkv[:, C:2 * C], qkv[:, 2 * C:], T, 3 * C, q_full=qkv)
         back(L["o1"], o, L["h1"], L["h0"])
         # cross-attention over the text embeddings
         tn = normed(L["h1"], "ln2")

@@ -136,6 +136,16 @@ def test_attention_and_helper_errors(L):
     assert L.sige_sparse_attn(FAKE, 100, FAKE, FAKE, 320, 2, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1
     assert L.sige_sparse_attn(None, 320, FAKE, FAKE, 320, 2, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1
     assert L.sige_sparse_attn(None, 320, None, None, 320, 2, 0, 64, 8, 40, f, None, 320, None, 0, None) == 0
+    # queries by block list: a 1x1 geometry, a host block count, indices
+    g1 = api.geom(64, 64, 8, 1, 1, 0)
+    g3 = api.geom(64, 64, 8, 3, 1, 1)
+    blk = lambda g, idx, n, d=40: L.sige_sparse_attn_blocks(FAKE, 960, ctypes.byref(g), idx, n, FAKE, FAKE, 960, 2,
+                                                            4096, 8, d, f, FAKE, 320, None, 0, None)
+    assert blk(g3, FAKE, 2) == 2 and "1x1" in err(L)
+    assert blk(g1, FAKE, -1) == 1
+    assert blk(g1, None, 2) == 1
+    assert blk(g1, FAKE, 2, 36) == 2
+    assert blk(g1, None, 0) == 0
     assert L.sige_packed_weight_bytes(1, 128, 128, 3) == 128 * 128 * 9 * 2
     assert L.sige_packed_weight_bytes(0, 3, 64, 3) == 32 * 64 * 9 * 4  # Cout padded to 32
     assert L.sige_packed_weight_bytes(1, 128, 24, 3) == 0

@@ -57,6 +57,57 @@ def test_sparse_attention_matches_oracle(oracle, T, heads, d, n_q, dtype):
         assert splits == [True, False]  # the small-query cases do exercise the split + merge path
 
 
+@pytest.mark.parametrize("dtype,res,b,heads,d,n", [("bf16", 32, 8, 8, 40, 3), ("f16", 16, 4, 4, 64, 16),
+                                                   ("bf16", 20, 8, 2, 24, 4), ("f16", 64, 8, 8, 40, 1)])
+def test_sparse_attention_queries_by_block_list(oracle, dtype, res, b, heads, d, n):
+    """Queries, keys and values are three channel ranges of one full tensor; the queries of the
+    call are the pixels of the listed blocks, taken from it by the attention kernel.  Against the
+    oracle's attention on the rows gathered by hand, and bit for bit against the call that is
+    handed those rows; a block that sticks out of the map (20 = 2.5 blocks of 8) reads the clamped
+    pixels; n_blocks == 0 enqueues nothing."""
+    td = DT[dtype]
+    C, T = heads * d, res * res
+    rng = np.random.default_rng(res + d + n)
+    qkv = torch.from_numpy(rng.standard_normal((res, res, 3 * C)).astype(np.float32)).to(td)
+    g = api.geom(res, res, b, 1, 1, 0)
+    gb_y, gb_x = -(-res // b), -(-res // b)
+    pick = np.sort(rng.permutation(gb_y * gb_x)[:n])
+    pick[-1] = gb_y * gb_x - 1                 # the bottom-right block: partly outside when b does not divide res
+    blocks = np.stack([(pick // gb_x) * b, (pick % gb_x) * b], 1).astype(np.int32)
+    ys = np.minimum(blocks[:, 0, None, None] + np.arange(b)[None, :, None], res - 1)
+    xs = np.minimum(blocks[:, 1, None, None] + np.arange(b)[None, None, :], res - 1)
+    tok = (ys * res + xs).reshape(-1)          # token of every query row, block by block, row-major inside
+    flat = qkv.view(T, 3 * C)
+    q_rows = flat[torch.from_numpy(tok)][:, :C].contiguous()
+    scale = 1.0 / math.sqrt(d)
+    want = oracle.attention(f64(q_rows).reshape(-1, heads, d), f64(flat[:, C:2 * C]).reshape(T, heads, d),
+                            f64(flat[:, 2 * C:]).reshape(T, heads, d), scale).reshape(-1, C)
+    qkv_d = dev(qkv).view(T, 3 * C)
+    idx = torch.from_numpy(blocks).cuda()
+    rows = n * b * b
+    nb = api.sige_sparse_attn_workspace_bytes(rows, T, heads, d)
+    for use_ws in (True, False):
+        ws = torch.empty(nb // 4, dtype=torch.float32, device="cuda") if (use_ws and nb) else None
+        o = torch.full((rows + 1, C), 7.0, dtype=td, device="cuda")
+        api.sige_sparse_attn_blocks(qkv_d, g, idx, n, qkv_d[:, C:2 * C], qkv_d[:, 2 * C:], o, scale, heads=heads,
+                                    d=d, workspace=ws, q_ld=3 * C, kv_ld=3 * C, o_ld=C)
+        o2 = torch.full((rows + 1, C), 7.0, dtype=td, device="cuda")
+        api.sige_sparse_attn(dev(q_rows), qkv_d[:, C:2 * C], qkv_d[:, 2 * C:], o2, scale, Nq=rows, workspace=ws,
+                             heads=heads, d=d, q_ld=C, kv_ld=3 * C, o_ld=C)
+        torch.cuda.synchronize()
+        attn_close(o[:rows], want, td, f"attention by block list, workspace={use_ws}")
+        assert torch.equal(o, o2), "queries by block list differ from the same queries handed over as rows"
+        assert (o[rows] == 7.0).all()
+    o = torch.full((rows, C), 7.0, dtype=td, device="cuda")
+    api.sige_sparse_attn_blocks(qkv_d, g, idx, 0, qkv_d[:, C:2 * C], qkv_d[:, 2 * C:], o, scale, heads=heads, d=d,
+                                q_ld=3 * C, kv_ld=3 * C, o_ld=C)
+    torch.cuda.synchronize()
+    assert (o == 7.0).all()
+    with pytest.raises(api.SigeError):        # the geometry of a 3x3 layer has tiles larger than its blocks
+        api.sige_sparse_attn_blocks(qkv_d, api.geom(res, res, b, 3, 1, 1), idx, n, qkv_d[:, C:2 * C],
+                                    qkv_d[:, 2 * C:], o, scale, heads=heads, d=d, q_ld=3 * C, kv_ld=3 * C, o_ld=C)
+
+
 def test_sparse_attention_edge_cases(oracle):
     c = inputs.attention_case(5, 300, 4, 40, 64, "bf16")
     # Nq smaller than the buffer: rows beyond Nq are untouched

@@ -176,6 +176,14 @@ def sd_setup(request):
                 net=net)
 
 
+def inner_tensor(L, part):
+    """A transformer block's cached tensor by the oracle's name: its keys and values are the last
+    two thirds of the cached queries | keys | values."""
+    if part == "kv":
+        return L["qkv"][:, :, L["op"]["C"]:]
+    return L[part]
+
+
 def test_latent_unet_transformer_blocks(sd_setup):
     """Whole pre-computation pass and sparse step against the step-by-step oracle.  Every call on
     the way is held to the per-call bar in its own test; across ~150 stored tensors the two
@@ -197,13 +205,13 @@ def test_latent_unet_transformer_blocks(sd_setup):
     for n, L in net.layers.items():
         if L["op"]["kind"] == "xfmr":
             for part in ("h0", "kv", "h1", "h2", "h3"):
-                mx, rms = rel_err(f64(L[part]), round_to(s["cache"][f"{n}.{part}"], td))
+                mx, rms = rel_err(f64(inner_tensor(L, part)), round_to(s["cache"][f"{n}.{part}"], td))
                 assert rms <= tol and mx <= 8 * tol, ("precompute", n, part, mx, rms)
     gpu_cache = {n: b.clone() for n, b in net.B.items()}
     copies = {n: L["pre"].clone() for n, L in net.layers.items() if "pre" in L}   # activated copies: caches too
     assert len(copies) >= 10
     inner = {(n, part): L[part].clone() for n, L in net.layers.items() if L["op"]["kind"] == "xfmr"
-             for part in ("h0", "kv", "h1", "h2", "h3")}
+             for part in ("h0", "qkv", "h1", "h2", "h3")}
     counts = net.set_edit(torch.from_numpy(s["mask"]).cuda(), exact=True)
     assert all(0 < c for c in counts.values())
     n_sparse_x = 0
@@ -228,9 +236,10 @@ def test_latent_unet_transformer_blocks(sd_setup):
             keep[y0:y0 + g1.block_h, x0:x0 + g1.block_w] = False
         k = torch.from_numpy(keep).cuda()
         for part in ("h0", "kv", "h1", "h2", "h3"):
-            mx, rms = rel_err(f64(L[part]), round_to(s["edit"][f"{n}.{part}"], td))
+            mx, rms = rel_err(f64(inner_tensor(L, part)), round_to(s["edit"][f"{n}.{part}"], td))
             assert rms <= tol and mx <= 8 * tol, ("edit", n, part, mx, rms)
-            # tokens outside the active blocks: the caches, bit for bit (keys and values included)
+        for part in ("h0", "qkv", "h1", "h2", "h3"):
+            # tokens outside the active blocks: the caches, bit for bit (queries, keys and values included)
             assert torch.equal(L[part][k], inner[(n, part)][k]), (n, part)
     assert not torch.equal(net.B["out"], gpu_cache["out"])
     # zero edit: nothing moves
