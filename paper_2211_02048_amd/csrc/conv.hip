@@ -987,8 +987,8 @@ struct ConvPlan {
 
 // M x N per workgroup and whether the four waves split K
 struct CfgShape { int M, N, WK; };
-constexpr int kNumCfg = 4;    // shapes that compete by score; the fifth is chosen by its own rule
-static const CfgShape kCfg[kNumCfg + 1] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}, {64, 32, 8}};
+constexpr int kNumCfg = 4;    // shapes that compete by score; the last two are chosen by a rule of their own
+static const CfgShape kCfg[kNumCfg + 2] = {{128, 128, 1}, {128, 64, 1}, {64, 64, 1}, {64, 32, 4}, {64, 32, 8}, {32, 32, 8}};
 
 // Chooses the workgroup shape and the staged channel chunk for one call, then - when the caller
 // gave a workspace (partial_elems = fp32 elements it holds) and the call has few workgroups but a
@@ -1080,7 +1080,21 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
             const size_t lds = lds_bytes(c[0], npix, c[1]);
             if (lds <= (c[0] == 4 ? 150u : 75u) * 1024u) { q.cfg = c[0]; q.kc = c[1]; q.lds = lds; break; }
         }
-        const long wgs4 = (long)q.groups * q.bands * q.slabs;
+        long wgs4 = (long)q.groups * q.bands * q.slabs;
+        // at most 64 workgroups (a 512-channel layer at 8 x 8 has 16): patches of 32 rows instead of
+        // 64, so that twice as many compute units stream the weight and share the MFMAs
+        const char* half_env = getenv("SIGE_CONV_HALF");     // tuning aid: most workgroups for which rows are halved
+        const long half_max = half_env ? atol(half_env) : 64;
+        if (q.kc && q.cfg == 4 && wgs4 <= half_max && pbfull >= 64 && g->block_w <= 32) {
+            q.cfg = 5;
+            q.G = 1;
+            q.rows = 32 / g->block_w;
+            q.bands = (g->block_h + q.rows - 1) / q.rows;
+            q.trows = (q.rows - 1) * g->stride + g->k;
+            q.groups = nblocks;
+            q.lds = lds_bytes(5, (long)q.trows * tw, q.kc);
+            wgs4 = (long)q.groups * q.bands * q.slabs;
+        }
         if (q.kc && (wgs4 <= 256 || force_whole)) {
             q.Cc = q.kc * kstep;
             q.ps = (int)(q.Cc * s + 16);
@@ -1147,8 +1161,11 @@ static int launch_kc(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
     case 3:
         if constexpr (KC % 4 == 0 && (KC <= 8 || (KC == 20 && KK == 9))) return launch_cfg<T, 2, 1, 1, 1, 4, KC, KK>(a, p, st);
         break;
-    default:
+    case 4:
         if constexpr (KC % 8 == 0 && KC >= 16 && KK == 9) return launch_cfg<T, 2, 1, 1, 1, 8, KC, KK>(a, p, st);
+        break;
+    default:
+        if constexpr (KC % 8 == 0 && KC >= 16 && KK == 9) return launch_cfg<T, 1, 1, 1, 1, 8, KC, KK>(a, p, st);
         break;
     }
     return fail(SIGE_ERR_UNSUPPORTED, "sige_conv: internal: shape %d without a matching chunk %d", p.cfg, KC);
