@@ -22,6 +22,7 @@ struct GatherArgs {
     int Hin, Win, ld_vec, V;  // V = 16-byte vectors per pixel, ld_vec = pixel stride in vectors
     int th, tw, stride, pad, up;
     int max_blocks, n_host, act, rows_per_wg;
+    int segs, seg_px;   // few blocks: a tile row is cut into segs runs of seg_px pixels, one workgroup each
 };
 
 // FIXED_CG: blockDim.x is a multiple of V, so a thread keeps one channel group and
@@ -34,7 +35,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
     int by0, bx0;
     if (n >= blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, by0, bx0)) return;
     const int iy0 = by0 * a.stride - a.pad, ix0 = bx0 * a.stride - a.pad;
-    const int r0 = blockIdx.x * a.rows_per_wg;
+    const int rg = blockIdx.x / a.segs, seg = blockIdx.x - rg * a.segs;
+    const int r0 = rg * a.rows_per_wg;
     const int r1 = min(r0 + a.rows_per_wg, a.th);
     const int row_vecs = a.tw * a.V;
     const int total = (r1 - r0) * row_vecs;
@@ -85,7 +87,19 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
         }
         dst[(r * a.tw + px) * a.V + cg] = v;
     };
-    if (FIXED_CG) {
+    if (a.segs > 1) {
+        // one run of pixels of one tile row (rows_per_wg is 1 here)
+        const int px0 = seg * a.seg_px, px1 = min(px0 + a.seg_px, a.tw);
+        if (FIXED_CG) {
+            const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
+            for (int px = px0 + threadIdx.x / a.V; px < px1; px += ppi) move(0, px, cg);
+        } else {
+            for (int j = px0 * a.V + threadIdx.x; j < px1 * a.V; j += 256) {
+                const int px = j / a.V;
+                move(0, px, j - px * a.V);
+            }
+        }
+    } else if (FIXED_CG) {
         // a thread keeps its channel group and walks over the pixels of the row group without
         // dividing: 256 / V pixels further each time
         const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
@@ -292,7 +306,20 @@ static int run_gather(const char* who, const void* x, sige_dtype dt, int32_t C, 
                      who, 16 / s);
     const bool fused = scale != nullptr || act != SIGE_ACT_NONE || mod != nullptr;
     a.rows_per_wg = pick_rows(th, (size_t)tw * C * s, nl, fused ? 40960 : 8192);
-    dim3 grid((th + a.rows_per_wg - 1) / a.rows_per_wg, nl);
+    // Few blocks: even one tile row per workgroup leaves most of the chip idle and every thread
+    // with a chain of dependent iterations.  The rows are cut into runs of pixels, down to one
+    // iteration of the 256 threads per workgroup, until about 1024 workgroups exist.
+    a.segs = 1;
+    a.seg_px = tw;
+    if (a.rows_per_wg == 1 && (long)nl * th < 1024) {
+        const int V = (int)((size_t)C * s / 16);
+        const int min_px = std::max(1, 256 / std::max(V, 1));          // pixels of one iteration
+        const int want = (int)((1024 + (long)nl * th - 1) / ((long)nl * th));
+        const int seg_px = std::max(min_px, (tw + want - 1) / want);
+        a.seg_px = seg_px;
+        a.segs = (tw + seg_px - 1) / seg_px;
+    }
+    dim3 grid(((th + a.rows_per_wg - 1) / a.rows_per_wg) * a.segs, nl);
     SIGE_REQUIRE(nl <= 65535, SIGE_ERR_UNSUPPORTED, "%s: more than 65535 blocks per launch", who);
     hipStream_t st = (hipStream_t)stream;
     if (dt == SIGE_F32) launch_gather<float>(a, grid, fused, st);

@@ -1,9 +1,13 @@
 // sige_gn_stats: group statistics of a full tensor, folded into the per-channel
 // Scale+Shift that replaces the normalisation layer once the statistics of the
 // original activation are cached (Sec. 3.2 "Pre-computing normalization parameters").
-// Used by the pre-computation pass only: the sparse pass never touches full tensors.
+// Used by the pre-computation pass, and by the sparse pass of a generator at the low resolutions
+// whose statistics are recomputed instead of cached (Sec. 4.1).
 //
-// Pass 1 streams the tensor once, fully coalesced (every lane keeps one 16-byte
+// Small tensors (the low resolutions): ONE kernel, each workgroup owns the channels of a few whole
+// groups, sums them over all pixels in a fixed order (no atomics: the result is reproducible bit for
+// bit) and writes mean, variance, scale and shift itself.
+// Large tensors: pass 1 streams the tensor once, fully coalesced (every lane keeps one 16-byte
 // channel group and walks down the pixels), reduces per-group sums of x and x^2 in
 // LDS and adds them to the fp32 accumulators; pass 2 (one workgroup) turns the sums
 // into mean / biased variance and the folded scale and shift.
@@ -143,6 +147,101 @@ __global__ __launch_bounds__(256) void gn_fold_kernel(float* mean, float* var, f
     }
 }
 
+// One workgroup = VW channel vectors (VW * N channels, a whole number of groups) x 256 / VW pixel
+// lanes.  Every lane sums its pixels, the lanes' sums meet in LDS and are added in lane order, the
+// channels of a group likewise.
+template <typename T>
+__global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__ x, int n_pix, int ld_vec, int VW,
+                                                       int cg, const float* __restrict__ gamma,
+                                                       const float* __restrict__ beta, float eps,
+                                                       float* __restrict__ mean, float* __restrict__ var,
+                                                       float* __restrict__ scale, float* __restrict__ shift)
+{
+    constexpr int N = Vec16<T>::N;
+    constexpr int U = 4;               // loads in flight per lane
+    extern __shared__ float red[];     // [2][ppl][CW] sums and sums of squares, then [2][CW] mean and variance
+    const int ppl = 256 / VW, CW = VW * N;
+    const int cv = threadIdx.x % VW, pl = threadIdx.x / VW;
+    const int v0 = blockIdx.x * VW;    // first channel vector of this workgroup
+    float* sq = red + ppl * CW;
+    float* stat = red + 2 * ppl * CW;
+    if (pl < ppl) {
+        float s[N], q[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) { s[i] = 0.0f; q[i] = 0.0f; }
+        for (int p = pl; p < n_pix; p += U * ppl) {
+            uint4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int pp = p + u * ppl;
+                v[u] = pp < n_pix ? x[(long)pp * ld_vec + v0 + cv] : make_uint4(0, 0, 0, 0);   // zeros add nothing
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float f[N];
+                unpack<T>(v[u], f);
+#pragma unroll
+                for (int i = 0; i < N; ++i) { s[i] += f[i]; q[i] = fmaf(f[i], f[i], q[i]); }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            red[pl * CW + cv * N + i] = s[i];
+            sq[pl * CW + cv * N + i] = q[i];
+        }
+    }
+    __syncthreads();
+    const int c = threadIdx.x;         // channel of the workgroup (c < CW <= 256)
+    if (c < CW) {                      // a thread reads and writes its own column only
+        float st = 0.0f, qt = 0.0f;
+        for (int l = 0; l < ppl; ++l) { st += red[l * CW + c]; qt += sq[l * CW + c]; }
+        red[c] = st;
+        sq[c] = qt;
+    }
+    __syncthreads();
+    if (c < CW / cg) {                 // group c of the workgroup
+        float st = 0.0f, qt = 0.0f;
+        for (int j = 0; j < cg; ++j) { st += red[c * cg + j]; qt += sq[c * cg + j]; }
+        const float n = (float)n_pix * (float)cg;
+        const float mu = st / n;
+        const float v = fmaxf(qt / n - mu * mu, 0.0f);
+        const int g = (v0 * N) / cg + c;
+        mean[g] = mu;
+        var[g] = v;
+        stat[c] = mu;
+        stat[CW + c] = v;
+    }
+    __syncthreads();
+    if (scale != nullptr && c < CW) {
+        const int ch = v0 * N + c, g = c / cg;
+        const float sc = (gamma ? gamma[ch] : 1.0f) * rsqrtf(stat[CW + g] + eps);
+        scale[ch] = sc;
+        shift[ch] = (beta ? beta[ch] : 0.0f) - stat[g] * sc;
+    }
+}
+
+static int gcd_int(int a, int b) { return b == 0 ? a : gcd_int(b, a % b); }
+
+// Channel vectors per workgroup for the one-kernel path (a whole number of groups), or 0 when the
+// tensor is too large for it: at most 32 pixel iterations per lane.
+static int small_path_vectors(long n_pix, int cg, int N)
+{
+    const int VW = cg / gcd_int(cg, N);      // lcm(cg, N) / N
+    if (VW > 32) return 0;
+    return n_pix <= 32L * (256 / VW) ? VW : 0;
+}
+
+template <typename T>
+static void launch_small(const void* x, int n_pix, int V, int ld_vec, int VW, int cg, const float* gamma,
+                         const float* beta, float eps, float* mean, float* var, float* scale, float* shift,
+                         hipStream_t st)
+{
+    const int ppl = 256 / VW, CW = VW * Vec16<T>::N;
+    const size_t lds = (size_t)(2 * ppl * CW + 2 * CW) * sizeof(float);
+    hipLaunchKernelGGL((gn_small_kernel<T>), dim3(V / VW), dim3(256), lds, st, (const uint4*)x, n_pix, ld_vec, VW,
+                       cg, gamma, beta, eps, mean, var, scale, shift);
+}
+
 template <typename T>
 static void launch_sum(const void* x, long n_pix, int V, int ld_vec, int cg, int groups, float* mean,
                        float* var, hipStream_t st)
@@ -178,6 +277,13 @@ extern "C" int sige_gn_stats(const void* x, sige_dtype dt, int32_t H, int32_t W,
     hipStream_t st = (hipStream_t)stream;
     const long n_pix = (long)H * W;
     const int V = (int)(C * s / 16), ld_vec = (int)(x_ld * s / 16), cg = C / groups;
+    if (const int VW = small_path_vectors(n_pix, cg, (int)(16 / s))) {
+        if (dt == SIGE_F32) launch_small<float>(x, (int)n_pix, V, ld_vec, VW, cg, gamma, beta, eps, mean, var, scale, shift, st);
+        else if (dt == SIGE_F16) launch_small<f16>(x, (int)n_pix, V, ld_vec, VW, cg, gamma, beta, eps, mean, var, scale, shift, st);
+        else launch_small<bf16>(x, (int)n_pix, V, ld_vec, VW, cg, gamma, beta, eps, mean, var, scale, shift, st);
+        SIGE_LAUNCH_CHECK("sige_gn_stats(small)");
+        return SIGE_OK;
+    }
     hipLaunchKernelGGL(gn_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, mean, var, groups);
     SIGE_LAUNCH_CHECK("sige_gn_stats(zero)");
     if (dt == SIGE_F32) launch_sum<float>(x, n_pix, V, ld_vec, cg, groups, mean, var, st);

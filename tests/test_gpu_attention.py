@@ -164,7 +164,11 @@ def test_sparse_attention_token_selection_counts(oracle):
 @pytest.mark.parametrize("dtype,H,W,C,G,ld", [("f16", 64, 64, 128, 32, 128), ("bf16", 37, 21, 320, 32, 320),
                                               ("f32", 16, 16, 64, 32, 64), ("f16", 32, 32, 64, 8, 192),
                                               ("f16", 24, 24, 24, 3, 24), ("f16", 40, 40, 384, 32, 384),
-                                              ("f16", 8, 8, 2560, 32, 2560), ("f32", 9, 9, 1024, 16, 1024)])
+                                              ("f16", 8, 8, 2560, 32, 2560), ("f32", 9, 9, 1024, 16, 1024),
+                                              # one group per channel (instance norm), small: the one-kernel path
+                                              ("f16", 16, 32, 1024, 1024, 1024), ("bf16", 5, 7, 64, 64, 64),
+                                              # too many pixels for it: the streaming pass with atomics
+                                              ("f16", 128, 96, 128, 32, 128), ("f16", 100, 100, 320, 32, 320)])
 def test_gn_stats_and_fold(oracle, dtype, H, W, C, G, ld):
     rng = np.random.default_rng(C)
     td = DT[dtype]
