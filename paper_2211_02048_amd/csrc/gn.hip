@@ -191,10 +191,24 @@ __global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__
         }
     }
     __syncthreads();
+    // Column sums in two steps, both in a fixed order: 256 / CW threads per channel each add a strip of
+    // the pixel lanes, then one thread per channel adds the strips.  (A thread writes only into its
+    // own strip's first row, which nobody else reads in that step.)
+    const int strips = 256 / CW, per = (ppl + strips - 1) / strips;
+    {
+        const int cc = threadIdx.x % CW, sidx = threadIdx.x / CW;
+        if (sidx < strips) {
+            const int l0 = sidx * per, l1 = min(l0 + per, ppl);
+            float st = 0.0f, qt = 0.0f;
+            for (int l = l0; l < l1; ++l) { st += red[l * CW + cc]; qt += sq[l * CW + cc]; }
+            if (l0 < ppl) { red[l0 * CW + cc] = st; sq[l0 * CW + cc] = qt; }
+        }
+    }
+    __syncthreads();
     const int c = threadIdx.x;         // channel of the workgroup (c < CW <= 256)
-    if (c < CW) {                      // a thread reads and writes its own column only
+    if (c < CW) {
         float st = 0.0f, qt = 0.0f;
-        for (int l = 0; l < ppl; ++l) { st += red[l * CW + c]; qt += sq[l * CW + c]; }
+        for (int l0 = 0; l0 < ppl; l0 += per) { st += red[l0 * CW + c]; qt += sq[l0 * CW + c]; }
         red[c] = st;
         sq[c] = qt;
     }
