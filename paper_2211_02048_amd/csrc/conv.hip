@@ -1023,9 +1023,10 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         p.slabs = (Cout + Nn - 1) / Nn;
         p.groups = (nblocks + p.G - 1) / p.G;
         const long npix = (long)p.G * p.trows * tw;
-        // K steps per chunk: the largest of 8 / 4 / 1 that divides Cin and whose staged tile fits
+        // K steps per chunk: the largest of 8 / 4 / 3 / 1 that divides Cin and whose staged tile fits
+        // (3: the 48 channels of a label-map convolution in one chunk)
         p.kc = 0;
-        for (int kc : {8, 4, 1}) {
+        for (int kc : {8, 4, 3, 1}) {
             if (force_kc && !force_whole && atoi(force_kc) != kc) continue;
             if (kc % WK || Cin % (kc * kstep)) continue;
             if (g->k != 1 && g->k != 3 && kc != 1) continue;
@@ -1181,6 +1182,7 @@ static int launch_kk(const ConvArgs& a, const ConvPlan& p, hipStream_t st)
     case 16: return launch_kc<T, 16, KK>(a, p, st);
     case 8: return launch_kc<T, 8, KK>(a, p, st);
     case 4: return launch_kc<T, 4, KK>(a, p, st);
+    case 3: return launch_kc<T, 3, KK>(a, p, st);
     default: return launch_kc<T, 1, KK>(a, p, st);
     }
 }

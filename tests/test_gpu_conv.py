@@ -302,7 +302,8 @@ def test_scatter_bit_exact_and_untouched_outside(oracle, dtype, C, H, W, b):
 @pytest.mark.parametrize("dtype,Cin,Cout,b,k,s,n", [
     ("f32", 64, 64, 6, 3, 1, 9), ("f16", 128, 128, 16, 3, 1, 5), ("f16", 128, 256, 16, 1, 1, 5),
     ("bf16", 320, 320, 4, 1, 1, 7), ("f16", 64, 128, 8, 3, 2, 6), ("f32", 8, 3, 6, 3, 1, 4),
-    ("bf16", 48, 40, 5, 3, 1, 11), ("f16", 16, 100, 32, 3, 1, 2), ("f16", 256, 64, 16, 3, 1, 3)])
+    ("bf16", 48, 40, 5, 3, 1, 11), ("f16", 16, 100, 32, 3, 1, 2), ("f16", 256, 64, 16, 3, 1, 3),
+    ("f16", 96, 64, 16, 3, 1, 3), ("f32", 24, 16, 8, 3, 1, 4)])      # chunks of three K steps
 def test_conv_on_tiles(oracle, dtype, Cin, Cout, b, k, s, n):
     rng = np.random.default_rng(Cin * 7 + Cout)
     td = DT[dtype]
