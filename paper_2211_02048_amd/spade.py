@@ -26,7 +26,7 @@ ACTS = {None: api.ACT_NONE, "relu": api.ACT_RELU, "leaky": api.ACT_LEAKY_RELU}
 
 class SigeSpade:
     def __init__(self, topo=None, dtype="f16", seed=1005, device="cuda", block=16, eps=1e-5, dilate=1,
-                 min_sparse=(8, 16), params=None, n_labels=35):
+                 min_sparse=(8, 16), params=None, n_labels=35, merge_label_convs=True):
         topo = topo or {}
         self.device, self.td = device, inputs.DTYPES[dtype]
         self.block, self.eps, self.dilate, self.min_sparse = block, eps, dilate, min_sparse
@@ -53,6 +53,37 @@ class SigeSpade:
             else:
                 L["g1"] = api.geom(h, w, b, 1, 1, 0)
             self.layers[n] = L
+        if merge_label_convs:
+            self._merge_label_convs(P)
+
+    def _merge_label_convs(self, P):
+        """The label-map convolutions of one residual block (one per modulated layer: two or three)
+        read the same label map through the same block list, so they run as ONE convolution whose
+        output channels are theirs side by side; each hidden tensor becomes a channel slice of the
+        joint buffer (the modulation convolutions read it through its pixel stride).  Same
+        arithmetic per output channel, fewer launches."""
+        groups = {}
+        for n, L in self.layers.items():
+            op = L["op"]
+            if op["kind"] == "conv" and n.endswith(".shared"):
+                groups.setdefault((n.split(".")[0], op["hw"]), []).append(n)
+        for (blk, (h, w)), names in groups.items():
+            if len(names) < 2:
+                continue
+            ops = [self.layers[n]["op"] for n in names]
+            hidden = [o["cout"] for o in ops]
+            joint = torch.zeros((h, w, sum(hidden)), dtype=self.td, device=self.device)
+            c0 = 0
+            for o, c in zip(ops, hidden):
+                self.B[o["y"]] = joint[:, :, c0:c0 + c]
+                c0 += c
+            first = self.layers[names[0]]
+            b = first["conv"].g.block_h
+            first["conv"] = SigeConv(torch.cat([P[n + ".w"] for n in names], 0).to(self.device),
+                                     torch.cat([P[n + ".b"] for n in names], 0), h, w, b, 1, 1)
+            first["joint"] = joint
+            for n in names[1:]:
+                self.layers[n]["merged"] = True
 
     def _lists(self, h, w, b):
         key = (h, w, b)
@@ -95,6 +126,8 @@ class SigeSpade:
         short = {}
         for n, L in self.layers.items():
             op = L["op"]
+            if L.get("merged"):       # computed by the block's joint label-map convolution
+                continue
             bl = L["list"][0 if (dense or not L["sparse"]) else 1]
             x = self.B[op["x"]]
             if op["kind"] == "up":
@@ -118,8 +151,8 @@ class SigeSpade:
                 continue
             res_t = short.get(op["shortcut"]) if op["shortcut"] else None
             res_f = self.B[op["residual"]] if op["residual"] is not None else None
-            L["conv"].forward(x, self.B[op["y"]], bl, self.ws, scale=scale, shift=shift, act=act, mod=mod,
-                              residual_tiles=res_t, residual=res_f, tag="main", fused=True)
+            L["conv"].forward(x, L.get("joint", self.B[op["y"]]), bl, self.ws, scale=scale, shift=shift, act=act,
+                              mod=mod, residual_tiles=res_t, residual=res_f, tag="main", fused=True)
         return self.B["out"]
 
     def precompute(self, seg):
