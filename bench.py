@@ -133,6 +133,12 @@ class Layer2:
 
     def layer(self):
         api = self.api
+        if self.fused:   # both convolutions read a_e and are independent: handed over together (one launch)
+            c3, _ = self.main.fused_call(self.a_e, self.y_main, self.bl3, self.ws, scale=self.scale, shift=self.shift,
+                                         act=api.ACT_SILU, tag="main")
+            c1, _ = self.short.fused_call(self.a_e, self.y_short, self.bl1, self.ws, tag="short")
+            api.sige_fused_conv_pair(c3, c1)
+            return
         self.main.forward(self.a_e, self.y_main, self.bl3, self.ws, scale=self.scale, shift=self.shift,
                           act=api.ACT_SILU, fused=self.fused)
         self.short.forward(self.a_e, self.y_short, self.bl1, self.ws, fused=self.fused)
@@ -266,13 +272,22 @@ def supplement(L, with_unet):
     full1 = BlockList(L.short.g, "cuda").all_active()
     y3, y1 = torch.empty_like(L.y_main), torch.empty_like(L.y_short)
 
+    def both(ya, yb, la, lb):
+        # the two convolutions as the step runs them: handed over together (one launch where the
+        # library can, i.e. with few active blocks)
+        if L.fused:
+            ca, _ = L.main.fused_call(L.a_e, ya, la, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, tag="main")
+            cb, _ = L.short.fused_call(L.a_e, yb, lb, ws, tag="short")
+            api.sige_fused_conv_pair(ca, cb)
+        else:
+            L.main.forward(L.a_e, ya, la, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU)
+            L.short.forward(L.a_e, yb, lb, ws)
+
     def dense():
-        L.main.forward(L.a_e, y3, full3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=L.fused)
-        L.short.forward(L.a_e, y1, full1, ws, fused=L.fused)
+        both(y3, y1, full3, full1)
 
     def sparse():
-        L.main.forward(L.a_e, L.y_main, L.bl3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=L.fused)
-        L.short.forward(L.a_e, L.y_short, L.bl1, ws, fused=L.fused)
+        both(L.y_main, L.y_short, L.bl3, L.bl1)
     dense_us = time_calls(dense, 50, 5)
     sparse_us = time_calls(sparse, 200, 5)
     nfull = g3.grid_blocks
@@ -303,8 +318,7 @@ def supplement(L, with_unet):
         k3, k1 = b3.sync_count(), b1.sync_count()
 
         def run():
-            L.main.forward(L.a_e, y3, b3, ws, scale=L.scale, shift=L.shift, act=api.ACT_SILU, fused=L.fused)
-            L.short.forward(L.a_e, y1, b1, ws, fused=L.fused)
+            both(y3, y1, b3, b1)
         us = time_graphed(run, per_graph=10, replays=10)
         sweep.append({"edited_area": frac, "active_blocks_3x3": k3, "active_blocks_1x1": k1,
                       "both_convs_us": round(us, 1)})

@@ -262,6 +262,29 @@ int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int
                     const sige_act_out* act_outs, int32_t n_act_outs,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Two independent fused calls handed over together, e.g. a ResBlock's 3x3 convolution and its 1x1
+ * shortcut, which read the same tensor through lists of the same resolution (Fig. "method"; the
+ * paper's per-layer pipeline run for two layers side by side).  Each struct holds the arguments
+ * of one sige_fused_conv call, with the same meaning and the same checks.  When the first is a
+ * 3x3 and the second a 1x1 convolution of the same dtype and both would take the few-block kernel
+ * shape without a K split over workgroups, they run as ONE kernel launch (on this part a launch
+ * of a dependent kernel costs more than the work of such a call); otherwise one after the other.
+ * The outputs are bit-identical to those of the two separate calls.  The two calls must not
+ * write what the other reads or writes.                                                      */
+typedef struct {
+    const void* x; sige_dtype dt; int32_t Cin, x_ld, up;
+    const sige_geom* g; const int32_t* indices; const int32_t* count;
+    int32_t max_blocks, n_blocks;
+    const float* scale; const float* shift; sige_act act;
+    int32_t Cout; const void* packed_weight; const float* bias;
+    const void* residual_tiles; const void* residual; int32_t res_ld;
+    void* y; int32_t y_ld; void* out_tiles;
+    const sige_act_out* act_outs; int32_t n_act_outs;
+    void* workspace; size_t workspace_bytes;
+} sige_fused_conv_call;
+int sige_fused_conv_pair(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
+                         void* stream);
+
 /* Fig. "sige-attention" / Sec. 3.2 "Extension to attention layers": attention for the
  * edited query tokens only, against all T keys and values (the caches with the
  * edited tokens already overwritten):

@@ -22,7 +22,7 @@ _DT = {torch.float32: SIGE_F32, torch.float16: SIGE_F16, torch.bfloat16: SIGE_BF
 STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3: "SIGE_ERR_CAPACITY",
           4: "SIGE_ERR_HIP"}
 
-EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_sparse_attn", "sige_sparse_attn_blocks",
+EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_fused_conv_pair", "sige_sparse_attn", "sige_sparse_attn_blocks",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
            "sige_gn_stats", "sige_last_error", "sige_version"]
 
@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.sige_conv_workspace_bytes.argtypes = [i32, gp, i32, i32, i32]
         L.sige_fused_conv.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp,
                                       i32, vp, i32, vp, vp, i32, vp, sz, vp]
+        L.sige_fused_conv_pair.argtypes = [ctypes.POINTER(FusedConvCall), ctypes.POINTER(FusedConvCall), vp]
         L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
         L.sige_sparse_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
         L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
@@ -249,6 +250,19 @@ class ActOut(ctypes.Structure):
                 ("shift", ctypes.c_void_p), ("act", ctypes.c_int32)]
 
 
+class FusedConvCall(ctypes.Structure):
+    """The arguments of one sige_fused_conv call (sige_fused_conv_call in the header)."""
+    _fields_ = [("x", ctypes.c_void_p), ("dt", ctypes.c_int32), ("Cin", ctypes.c_int32), ("x_ld", ctypes.c_int32),
+                ("up", ctypes.c_int32), ("g", ctypes.POINTER(Geom)), ("indices", ctypes.c_void_p),
+                ("count", ctypes.c_void_p), ("max_blocks", ctypes.c_int32), ("n_blocks", ctypes.c_int32),
+                ("scale", ctypes.c_void_p), ("shift", ctypes.c_void_p), ("act", ctypes.c_int32),
+                ("Cout", ctypes.c_int32), ("packed_weight", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+                ("residual_tiles", ctypes.c_void_p), ("residual", ctypes.c_void_p), ("res_ld", ctypes.c_int32),
+                ("y", ctypes.c_void_p), ("y_ld", ctypes.c_int32), ("out_tiles", ctypes.c_void_p),
+                ("act_outs", ctypes.c_void_p), ("n_act_outs", ctypes.c_int32), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t)]
+
+
 def act_out_array(act_outs):
     """[(y, scale, shift, act), ...] (device tensors; y a [H, W, >=Cout] view) -> a ctypes array of sige_act_out."""
     arr = (ActOut * len(act_outs))()
@@ -276,6 +290,34 @@ def sige_fused_conv(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, 
                                  _ptr(residual_tiles), _ptr(residual), res_ld or 0, _ptr(y), y_ld or 0,
                                  _ptr(out_tiles), act_outs if n_ao else None, n_ao, _ptr(workspace),
                                  _nbytes(workspace), _stream()))
+
+
+def fused_conv_call(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, *, y=None, out_tiles=None,
+                    n_blocks=-1, max_blocks=None, scale=None, shift=None, act=ACT_NONE, up=0, x_ld=None,
+                    residual_tiles=None, residual=None, res_ld=None, y_ld=None, workspace=None, act_outs=None):
+    """The arguments of sige_fused_conv as a FusedConvCall (keeps the tensors alive alongside)."""
+    if act_outs is not None and not isinstance(act_outs, ctypes.Array):
+        act_outs = act_out_array(act_outs)
+    n_ao = 0 if act_outs is None else len(act_outs)
+    if y is not None and y_ld is None:
+        y_ld = y.stride(-2)
+    if residual is not None and res_ld is None:
+        res_ld = residual.stride(-2)
+    p = lambda t: None if t is None else t.data_ptr()
+    c = FusedConvCall(p(x), _DT[x.dtype], Cin, x.stride(-2) if x_ld is None else x_ld, up, ctypes.pointer(g),
+                      p(indices), p(count), indices.shape[0] if max_blocks is None else max_blocks, n_blocks,
+                      p(scale), p(shift), act, Cout, p(packed_weight), p(bias), p(residual_tiles), p(residual),
+                      res_ld or 0, p(y), y_ld or 0, p(out_tiles),
+                      ctypes.cast(act_outs, ctypes.c_void_p) if n_ao else None, n_ao, p(workspace),
+                      _nbytes(workspace))
+    c._keep = (x, g, indices, count, scale, shift, packed_weight, bias, residual_tiles, residual, y, out_tiles,
+               act_outs, workspace)
+    return c
+
+
+def sige_fused_conv_pair(first: FusedConvCall, second: FusedConvCall):
+    """Two independent fused calls; one launch when both take the few-block kernel shape."""
+    _check(lib().sige_fused_conv_pair(ctypes.byref(first), ctypes.byref(second), _stream()))
 
 
 def sige_token_norm(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_rows=None, gamma=None, beta=None,

@@ -261,8 +261,10 @@ constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks i
 // K steps per staged channel chunk; KK = k*k when it is 9 or 1 (the steps of a chunk are then
 // unrolled), 0 for any other kernel size.  Two waves per SIMD are enforced: with fewer the MFMA
 // phase has nothing to overlap its LDS and L2 latencies with.
+// (The body is a device function so that two calls can share one launch, see conv_pair_kernel;
+// bx, by, bz are the workgroup's coordinates inside its own call's grid.)
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
-__global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void conv_kernel(ConvArgs a)
+__device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const int by, const int bz)
 {
     constexpr int NT = 64 * WM * WN * WK;                     // threads per workgroup
     static_assert(NT == 256 || NT == 512, "four or eight waves per workgroup");
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
     // Fused mode: the origins of this workgroup's blocks go to LDS once.  Their loads and the
     // load of the count are independent and are issued together (row n exists for n < max_blocks).
     __shared__ int org[2 * MAX_G];
-    const int g0 = blockIdx.z * a.G;
+    const int g0 = bz * a.G;
     int oy = 0, ox = 0;
     if (a.indices != nullptr && threadIdx.x < a.G) {
         const int n = min(g0 + (int)threadIdx.x, a.max_blocks - 1);
@@ -300,7 +302,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
         if (threadIdx.x < a.G) { org[2 * threadIdx.x] = oy; org[2 * threadIdx.x + 1] = ox; }
         __syncthreads();
     }
-    const int split = blockIdx.y / a.bands, band = blockIdx.y - split * a.bands;
+    const int split = by / a.bands, band = by - split * a.bands;
     const int band_row0 = band * a.rows;                      // first output row of the band
     const int band_rows = min(a.rows, a.bh - band_row0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -321,7 +323,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
         a_base[tm] = ((g * a.trows + py * a.stride) * a.tw + px * a.stride) * a.ps + half * 16 +
                      wk * KW * (KS * S);
     }
-    const int nt0 = (blockIdx.x * WN + wn) * TN;              // first 32-wide Cout tile of this wave
+    const int nt0 = (bx * WN + wn) * TN;                      // first 32-wide Cout tile of this wave
     const int kk = a.k * a.k, kcs = a.Cin / KS;
     const int ntn_total = (a.Cout + 31) / 32;
 
@@ -560,7 +562,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
         __syncthreads();
         for (int e = tid; e < BM * (BN / N); e += NT) {
             const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;   // row of the workgroup's patch
-            const int o = blockIdx.x * BN + nn;
+            const int o = bx * BN + nn;
             const int g = m / pb, p = m - g * pb;
             const int py = p / a.bw, px = p - py * a.bw;
             if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
@@ -609,6 +611,29 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
             }
             emit_run<T>(a, to_y, vec_ok, t, pix, o, v, ap);
         }
+    }
+}
+
+template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
+__global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void conv_kernel(ConvArgs a)
+{
+    conv_body<T, TM, TN, WM, WN, WK, KC, KK>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Two independent calls in ONE launch: a 3x3 convolution and a 1x1 convolution that both take the
+// 64 x 32 shape whose four waves split K (few active blocks: a ResBlock's convolution and its
+// shortcut, which read the same tensor).  Workgroups with blockIdx.z < za belong to the first call,
+// the others to the second; the grid spans the larger extent in x and y and the surplus exits.
+template <typename T, int KC>
+__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int za, int xa, int ya, int xb,
+                                                           int yb)
+{
+    if ((int)blockIdx.z < za) {
+        if ((int)blockIdx.x < xa && (int)blockIdx.y < ya)
+            conv_body<T, 2, 1, 1, 1, 4, KC, 9>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    } else {
+        if ((int)blockIdx.x < xb && (int)blockIdx.y < yb)
+            conv_body<T, 2, 1, 1, 1, 4, KC, 1>(b, blockIdx.x, blockIdx.y, blockIdx.z - za);
     }
 }
 
@@ -1291,38 +1316,54 @@ static int launch_reduce(const ConvArgs& a, int nl, hipStream_t st)
     return SIGE_OK;
 }
 
-// Shared by sige_conv, sige_conv_scatter and sige_fused_conv: plan, fill the arguments, launch.
-static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, int tw, int Cin, int Cout,
-                    int max_blocks, int n_blocks, int nl, ConvArgs& a, void* workspace, size_t workspace_bytes,
-                    void* stream)
+// Shared by sige_conv, sige_conv_scatter and sige_fused_conv: plan and fill the arguments ...
+static int prepare_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, int tw, int Cin, int Cout,
+                        int max_blocks, int n_blocks, int nl, ConvArgs& a, void* workspace, size_t workspace_bytes,
+                        ConvPlan* p, int* pointwise)
 {
     const int ks = dt == SIGE_F32 ? 8 : 16;
     a.bh = g->block_h; a.bw = g->block_w; a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
-    if (const int tiles = pointwise_tiles(g, a, ks, nl)) {
-        hipStream_t st = (hipStream_t)stream;
-        return dt == SIGE_F32 ? launch_pointwise<float>(a, nl, tiles, st)
-               : dt == SIGE_F16 ? launch_pointwise<f16>(a, nl, tiles, st) : launch_pointwise<bf16>(a, nl, tiles, st);
-    }
-    ConvPlan p;
+    *pointwise = pointwise_tiles(g, a, ks, nl);
+    if (*pointwise) return SIGE_OK;
     const bool ws_ok = workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
     SIGE_REQUIRE(plan_conv(g, th, tw, Cin, Cout, dtype_size(dt), ks, nl, ws_ok && !a.glu ? workspace_bytes / sizeof(float) : 0,
-                           a.scale != nullptr || a.act != SIGE_ACT_NONE, &p),
+                           a.scale != nullptr || a.act != SIGE_ACT_NONE, p),
                  SIGE_ERR_UNSUPPORTED, "%s: no kernel shape fits block %dx%d, k %d, stride %d, Cin %d", who,
                  g->block_h, g->block_w, g->k, g->stride, Cin);
-    SIGE_REQUIRE(p.groups <= 65535 && p.bands * p.ksplit <= 65535, SIGE_ERR_UNSUPPORTED,
+    SIGE_REQUIRE(p->groups <= 65535 && p->bands * p->ksplit <= 65535, SIGE_ERR_UNSUPPORTED,
                  "%s: too many blocks per launch", who);
     a.th = th; a.tw = tw; a.bh = g->block_h; a.bw = g->block_w; a.k = g->k; a.stride = g->stride;
     a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
-    a.G = p.G; a.rows = p.rows; a.trows = p.trows; a.Cc = p.Cc; a.ps = p.ps;
-    a.bands = p.bands; a.ksplit = p.ksplit;
-    a.partial = p.ksplit > 1 ? (float*)workspace : nullptr;
+    a.G = p->G; a.rows = p->rows; a.trows = p->trows; a.Cc = p->Cc; a.ps = p->ps;
+    a.bands = p->bands; a.ksplit = p->ksplit;
+    a.partial = p->ksplit > 1 ? (float*)workspace : nullptr;
     a.partial_stride = (long)nl * g->block_h * g->block_w * Cout;
-    hipStream_t st = (hipStream_t)stream;
+    return SIGE_OK;
+}
+
+// ... and launch.
+static int launch_prepared(sige_dtype dt, const ConvArgs& a, const ConvPlan& p, int pointwise, int nl, hipStream_t st)
+{
+    if (pointwise)
+        return dt == SIGE_F32 ? launch_pointwise<float>(a, nl, pointwise, st)
+               : dt == SIGE_F16 ? launch_pointwise<f16>(a, nl, pointwise, st) : launch_pointwise<bf16>(a, nl, pointwise, st);
     int rc = dt == SIGE_F32 ? launch_conv<float>(a, p, st)
              : dt == SIGE_F16 ? launch_conv<f16>(a, p, st) : launch_conv<bf16>(a, p, st);
     if (rc || p.ksplit == 1) return rc;
     return dt == SIGE_F32 ? launch_reduce<float>(a, nl, st)
            : dt == SIGE_F16 ? launch_reduce<f16>(a, nl, st) : launch_reduce<bf16>(a, nl, st);
+}
+
+static int run_conv(const char* who, sige_dtype dt, const sige_geom* g, int th, int tw, int Cin, int Cout,
+                    int max_blocks, int n_blocks, int nl, ConvArgs& a, void* workspace, size_t workspace_bytes,
+                    void* stream)
+{
+    ConvPlan p;
+    int pointwise = 0;
+    if (int rc = prepare_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes,
+                              &p, &pointwise))
+        return rc;
+    return launch_prepared(dt, a, p, pointwise, nl, (hipStream_t)stream);
 }
 
 extern "C" size_t sige_conv_workspace_bytes(sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
@@ -1421,17 +1462,14 @@ extern "C" int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_ge
     return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
 }
 
-extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
-                               const sige_geom* g, const int32_t* indices, const int32_t* count,
-                               int32_t max_blocks, int32_t n_blocks, const float* scale, const float* shift,
-                               sige_act act, int32_t Cout, const void* packed_weight, const float* bias,
-                               const void* residual_tiles, const void* residual, int32_t res_ld, void* y,
-                               int32_t y_ld, void* out_tiles, const sige_act_out* act_outs, int32_t n_act_outs,
-                               void* workspace, size_t workspace_bytes, void* stream)
+// Checks the arguments of a fused call and fills the kernel arguments (nl = 0: nothing to launch).
+static int fused_conv_fill(const char* who, const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
+                           const sige_geom* g, const int32_t* indices, const int32_t* count, int32_t max_blocks,
+                           int32_t n_blocks, const float* scale, const float* shift, sige_act act, int32_t Cout,
+                           const void* packed_weight, const float* bias, const void* residual_tiles,
+                           const void* residual, int32_t res_ld, void* y, int32_t y_ld, void* out_tiles,
+                           const sige_act_out* act_outs, int32_t n_act_outs, ConvArgs& a, int& th, int& tw, int& nl)
 {
-    clear_error();
-    const char* who = "sige_fused_conv";
-    int th, tw, nl;
     if (int rc = check_geom(g, who, &th, &tw)) return rc;
     if (int rc = check_blocks(count, max_blocks, n_blocks, who, &nl)) return rc;
     SIGE_REQUIRE(x && indices && packed_weight, SIGE_ERR_INVALID_ARG, "%s: x, indices and packed_weight are required", who);
@@ -1473,8 +1511,7 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
                          who, j, 16 / s);
         }
     }
-    if (nl == 0) return SIGE_OK;
-    ConvArgs a = {};
+    a = ConvArgs{};
     a.n_ao = n_act_outs;
     for (int j = 0; j < n_act_outs; ++j) {
         a.ao[j].y = act_outs[j].y; a.ao[j].scale = act_outs[j].scale; a.ao[j].shift = act_outs[j].shift;
@@ -1485,5 +1522,89 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
     a.res_tiles = residual_tiles; a.res_full = residual; a.y = y;
     a.Hin = g->H_in; a.Win = g->W_in; a.x_ld = x_ld; a.up = up; a.pad = g->pad; a.act = (int)act;
     a.Hout = g->H_out; a.Wout = g->W_out; a.y_ld = y_ld; a.res_ld = res_ld;
+    return SIGE_OK;
+}
+
+extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_t x_ld, int32_t up,
+                               const sige_geom* g, const int32_t* indices, const int32_t* count,
+                               int32_t max_blocks, int32_t n_blocks, const float* scale, const float* shift,
+                               sige_act act, int32_t Cout, const void* packed_weight, const float* bias,
+                               const void* residual_tiles, const void* residual, int32_t res_ld, void* y,
+                               int32_t y_ld, void* out_tiles, const sige_act_out* act_outs, int32_t n_act_outs,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    const char* who = "sige_fused_conv";
+    ConvArgs a;
+    int th, tw, nl;
+    if (int rc = fused_conv_fill(who, x, dt, Cin, x_ld, up, g, indices, count, max_blocks, n_blocks, scale, shift, act,
+                                 Cout, packed_weight, bias, residual_tiles, residual, res_ld, y, y_ld, out_tiles,
+                                 act_outs, n_act_outs, a, th, tw, nl))
+        return rc;
+    if (nl == 0) return SIGE_OK;
     return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
+}
+
+template <typename T>
+static int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const ConvPlan& pb, hipStream_t st)
+{
+    const size_t lds = std::max(pa.lds, pb.lds);
+    const dim3 grid(std::max(pa.slabs, pb.slabs), std::max(pa.bands, pb.bands), pa.groups + pb.groups);
+    auto launch = [&](auto kern) {
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_fused_conv_pair: cannot reserve %zu bytes of LDS: %s", lds,
+                         hipGetErrorString(e));
+        }
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, pa.groups, pa.slabs, pa.bands, pb.slabs, pb.bands);
+        SIGE_LAUNCH_CHECK("sige_fused_conv_pair");
+        return (int)SIGE_OK;
+    };
+    return pa.kc == 8 ? launch(conv_pair_kernel<T, 8>) : launch(conv_pair_kernel<T, 4>);
+}
+
+extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
+                                    void* stream)
+{
+    clear_error();
+    const char* who = "sige_fused_conv_pair";
+    SIGE_REQUIRE(first && second, SIGE_ERR_INVALID_ARG, "%s: two calls are required", who);
+    const sige_fused_conv_call* c[2] = {first, second};
+    ConvArgs a[2];
+    ConvPlan p[2];
+    int th[2], tw[2], nl[2], pw[2] = {0, 0};
+    for (int i = 0; i < 2; ++i) {
+        if (int rc = fused_conv_fill(who, c[i]->x, c[i]->dt, c[i]->Cin, c[i]->x_ld, c[i]->up, c[i]->g, c[i]->indices,
+                                     c[i]->count, c[i]->max_blocks, c[i]->n_blocks, c[i]->scale, c[i]->shift,
+                                     c[i]->act, c[i]->Cout, c[i]->packed_weight, c[i]->bias, c[i]->residual_tiles,
+                                     c[i]->residual, c[i]->res_ld, c[i]->y, c[i]->y_ld, c[i]->out_tiles,
+                                     c[i]->act_outs, c[i]->n_act_outs, a[i], th[i], tw[i], nl[i]))
+            return rc;
+        if (nl[i] == 0) continue;
+        if (int rc = prepare_conv(who, c[i]->dt, c[i]->g, th[i], tw[i], c[i]->Cin, c[i]->Cout, c[i]->max_blocks,
+                                  c[i]->n_blocks, nl[i], a[i], c[i]->workspace, c[i]->workspace_bytes, &p[i], &pw[i]))
+            return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    // one launch when both take the 64 x 32 shape whose four waves split K, unsplit over workgroups,
+    // with the same chunk: a 3x3 call first, a 1x1 call second - and few workgroups in all (with more
+    // than about three per compute unit the two calls are faster one after the other: measured
+    // 33 vs 25 us at 1440 workgroups, 15.6 vs 16.3 us at 560)
+    const long wgs_both = nl[0] > 0 && nl[1] > 0 && !pw[0] && !pw[1]
+                              ? (long)p[0].groups * p[0].bands * p[0].slabs + (long)p[1].groups * p[1].bands * p[1].slabs
+                              : 0;
+    const bool together = nl[0] > 0 && nl[1] > 0 && wgs_both <= 800 && !pw[0] && !pw[1] && c[0]->dt == c[1]->dt && a[0].k == 3 &&
+                          a[1].k == 1 && p[0].cfg == 3 && p[1].cfg == 3 && p[0].ksplit == 1 && p[1].ksplit == 1 &&
+                          p[0].kc == p[1].kc && (p[0].kc == 8 || p[0].kc == 4) &&
+                          (long)p[0].groups + p[1].groups <= 65535;
+    if (together) {
+        const sige_dtype dt = c[0]->dt;
+        return dt == SIGE_F32 ? launch_pair<float>(a[0], p[0], a[1], p[1], st)
+               : dt == SIGE_F16 ? launch_pair<f16>(a[0], p[0], a[1], p[1], st) : launch_pair<bf16>(a[0], p[0], a[1], p[1], st);
+    }
+    for (int i = 0; i < 2; ++i) {
+        if (nl[i] == 0) continue;
+        if (int rc = launch_prepared(c[i]->dt, a[i], p[i], pw[i], nl[i], st)) return rc;
+    }
+    return SIGE_OK;
 }

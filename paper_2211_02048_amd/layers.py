@@ -98,6 +98,26 @@ class SigeConv:
     def out_numel(self, n):
         return n * self.g.block_h * self.g.block_w * self.Cout
 
+    def fused_call(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None, act=api.ACT_NONE,
+                   residual_tiles=None, residual=None, scatter=True, tag="t", split_k=True, act_outs=None):
+        """The arguments of this layer's fused call as a struct for api.sige_fused_conv_pair (which runs
+        two independent layers in one launch when it can).  Returns (call, out_tiles or None)."""
+        g, n = self.g, blocks.n_host
+        cap = blocks.max_blocks if n < 0 else max(n, 1)
+        split = None
+        if split_k:
+            nb = self._split_bytes.get(cap)
+            if nb is None:
+                nb = self._split_bytes[cap] = api.sige_conv_workspace_bytes(self.dtype, g, self.Cin, self.Cout, cap)
+            if nb:
+                split = ws.get("split_k_" + tag, nb // 4, torch.float32)   # its own: the partner may run beside it
+        out_tiles = None if scatter else ws.get("out_" + tag, self.out_numel(cap), self.dtype)
+        call = api.fused_conv_call(x, g, blocks.indices, blocks.count, self.Cin, self.Cout, self.packed, self.bias,
+                                   y=y if scatter else None, out_tiles=out_tiles, n_blocks=n, max_blocks=cap,
+                                   scale=scale, shift=shift, act=act, up=self.up, residual_tiles=residual_tiles,
+                                   residual=residual, workspace=split, act_outs=act_outs if scatter else None)
+        return call, out_tiles
+
     def forward(self, x, y, blocks: BlockList, ws: Workspace, *, scale=None, shift=None,
                 act=api.ACT_NONE, residual_tiles=None, residual=None, scatter=True, tag="t", fused=False,
                 split_k=True, mod=None, act_outs=None):

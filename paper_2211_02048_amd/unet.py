@@ -197,7 +197,12 @@ class SigeUNet:
         self.B["image"].copy_(image)
         shortcut_tiles = {}
         use_copies = self.act_copies and self.fused is True
-        for n, L in self.layers.items():
+        names = list(self.layers)
+        paired = set()              # shortcut convolutions already issued together with their ResBlock's first one
+        for i, n in enumerate(names):
+            if n in paired:
+                continue
+            L = self.layers[n]
             op = L["op"]
             fused = self.fused is True or (self.fused == "lowres" and not L["sparse"])
             bl = L["list"][0 if (dense or not L["sparse"]) else 1]
@@ -224,6 +229,21 @@ class SigeUNet:
                     continue
                 res_t = shortcut_tiles.get(op["shortcut"]) if op["shortcut"] else None
                 res_f = self.view(op["residual"]) if op["residual"] is not None else None
+                nxt = self.layers[names[i + 1]] if i + 1 < len(names) else None
+                if (fused and self.fused is True and nxt is not None and nxt["op"]["kind"] == "conv" and
+                        not nxt["op"]["scatter"] and nxt["op"]["x"] == op["x"] and op["k"] == 3 and
+                        nxt["op"]["k"] == 1):
+                    # a ResBlock's first convolution and its 1x1 shortcut read the same tensor: handed
+                    # over together (one launch when both have few active blocks)
+                    ca, _ = L["conv"].fused_call(xn, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift,
+                                                 act=act, residual_tiles=res_t, residual=res_f, tag="main",
+                                                 act_outs=ao)
+                    bls = nxt["list"][0 if (dense or not nxt["sparse"]) else 1]
+                    cb, tiles = nxt["conv"].fused_call(x, None, bls, self.ws, scatter=False, tag="short")
+                    api.sige_fused_conv_pair(ca, cb)
+                    shortcut_tiles[names[i + 1]] = tiles
+                    paired.add(names[i + 1])
+                    continue
                 L["conv"].forward(xn, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift, act=act,
                                   residual_tiles=res_t, residual=res_f, tag="main", fused=fused, act_outs=ao)
             elif op["kind"] == "xfmr":

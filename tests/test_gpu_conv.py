@@ -886,3 +886,62 @@ def test_gather_modulated(oracle, dtype, C, H, W, b, up, act):
     with pytest.raises(api.SigeError):
         api.sige_gather_modulated(dev(x), g, idx, cnt, tiles, dev(modbuf[:, :, :C]).contiguous(), n_blocks=n, C=C,
                                   up=up, max_blocks=n)          # modulation tensor narrower than 2C
+
+
+@pytest.mark.parametrize("dtype,Cin,C3,C1,res,b,n", [
+    ("f16", 128, 128, 256, 64, 16, 5),      # the two convolutions of benchmark configuration 2: one launch
+    ("bf16", 64, 40, 72, 40, 8, 7),         # chunks of four K steps, output widths that are no multiples of 32
+    ("f32", 64, 64, 32, 30, 6, 9),          # fp32, ragged blocks
+    ("f16", 512, 64, 64, 16, 8, 2)])        # the 3x3 call takes another kernel shape: run one after the other
+def test_fused_conv_pair(oracle, dtype, Cin, C3, C1, res, b, n):
+    """A 3x3 convolution (fused GN+SiLU gather, residual) and a 1x1 convolution on the same input,
+    handed over together: bit for bit what the two separate fused calls write, for a host and a
+    device block count, and the 3x3 result against the oracle; an empty first list still runs the
+    second call."""
+    rng = np.random.default_rng(Cin + C3 + C1 + res)
+    td = DT[dtype]
+    x = torch.from_numpy(rng.standard_normal((res, res, Cin)).astype(np.float32)).to(td)
+    w3, b3 = inputs.conv_params(rng, C3, Cin, 3, td)
+    w1, b1 = inputs.conv_params(rng, C1, Cin, 1, td)
+    scale = torch.from_numpy(rng.uniform(0.5, 1.5, Cin).astype(np.float32))
+    shift = torch.from_numpy(rng.uniform(-0.5, 0.5, Cin).astype(np.float32))
+    resid = torch.from_numpy(rng.standard_normal((res, res, C3)).astype(np.float32)).to(td)
+    cache3 = torch.from_numpy(rng.standard_normal((res, res, C3)).astype(np.float32)).to(td)
+    cache1 = torch.from_numpy(rng.standard_normal((res, res, C1)).astype(np.float32)).to(td)
+    conv3 = SigeConv(dev(w3), b3, res, res, b, 1, 1)
+    conv1 = SigeConv(dev(w1), b1, res, res, b, 1, 0)
+    blocks = random_blocks(rng, conv3.g, n)
+    n = len(blocks)
+    bl3, bl1 = BlockList(conv3.g, "cuda", max_blocks=n + 3), BlockList(conv1.g, "cuda", max_blocks=n + 3)
+    for bl in (bl3, bl1):
+        bl.indices[:n].copy_(torch.from_numpy(blocks))
+        bl.count.fill_(n)
+    bl1.count.fill_(n - 1)                  # the lists need not be equal
+    ws = Workspace("cuda")
+    xd, sc, sh, rd = dev(x), dev(scale), dev(shift), dev(resid)
+    for device_count in (False, True):
+        bl3.n_host, bl1.n_host = (-1, -1) if device_count else (n, n - 1)
+        ya, yb = dev(cache3).clone(), dev(cache1).clone()
+        conv3.forward(xd, ya, bl3, ws, scale=sc, shift=sh, act=api.ACT_SILU, residual=rd, fused=True)
+        conv1.forward(xd, yb, bl1, ws, fused=True)
+        y3, y1 = dev(cache3).clone(), dev(cache1).clone()
+        c3, _ = conv3.fused_call(xd, y3, bl3, ws, scale=sc, shift=sh, act=api.ACT_SILU, residual=rd, tag="p3")
+        c1, _ = conv1.fused_call(xd, y1, bl1, ws, tag="p1")
+        api.sige_fused_conv_pair(c3, c1)
+        torch.cuda.synchronize()
+        assert torch.equal(y3, ya) and torch.equal(y1, yb), f"pair differs from the two calls (device_count={device_count})"
+    want = oracle.dense_layer(f64(x), f64(w3), f64(b3), 1, 1, f64(scale), f64(shift), oracle.ACT_SILU)
+    want = oracle.select_blocks(round_to(want, td) + f64(resid), f64(cache3), blocks, b, b)
+    assert_mostly_close(y3, want, td, "3x3 call of the pair")
+    # an empty first list: the second call still runs
+    bl3.count.fill_(0)
+    bl3.n_host, bl1.n_host = 0, n - 1
+    y3, y1 = dev(cache3).clone(), dev(cache1).clone()
+    c3, _ = conv3.fused_call(xd, y3, bl3, ws, scale=sc, shift=sh, act=api.ACT_SILU, residual=rd, tag="p3")
+    c1, _ = conv1.fused_call(xd, y1, bl1, ws, tag="p1")
+    api.sige_fused_conv_pair(c3, c1)
+    torch.cuda.synchronize()
+    assert torch.equal(y3, dev(cache3)) and torch.equal(y1, yb)
+    c1.Cin = Cin + 1                        # argument errors of either call are reported
+    with pytest.raises(api.SigeError):
+        api.sige_fused_conv_pair(c3, c1)
