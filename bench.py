@@ -668,7 +668,7 @@ def main():
                                   "128->256, 256x256 fp16, ~1% blob edit, 16x16 blocks; step = diff mask + block "
                                   "lists + gather/conv/scatter for both convs",
                       "launch": f"one HIP graph per step, device-side block counts, capacity {L.capacity} blocks, "
-                                + ("fused gather-conv-scatter kernel" if L.fused else "gather, conv, scatter kernels"),
+                                + ("fused gather-conv-scatter calls of both convolutions in one launch" if L.fused else "gather, conv, scatter kernels"),
                       "eager_step_ms_with_count_readback": round(eager_us / 1e3, 4),
                       "active_blocks_3x3": n3, "active_blocks_1x1": n1, "grid_blocks": L.main.g.grid_blocks,
                       "algorithmic_bytes_per_step": n_bytes, "mfma_flop_per_step": L.flops_per_step(n3, n1)},
