@@ -622,18 +622,19 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
 
 // Two independent calls in ONE launch: a 3x3 convolution and a 1x1 convolution that both take the
 // 64 x 32 shape whose four waves split K (few active blocks: a ResBlock's convolution and its
-// shortcut, which read the same tensor).  Workgroups with blockIdx.z < za belong to the first call,
-// the others to the second; the grid spans the larger extent in x and y and the surplus exits.
+// shortcut, which read the same tensor).
 template <typename T, int KC>
-__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int za, int xa, int ya, int xb,
+__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int wgs_a, int xa, int ya, int xb,
                                                            int yb)
 {
-    if ((int)blockIdx.z < za) {
-        if ((int)blockIdx.x < xa && (int)blockIdx.y < ya)
-            conv_body<T, 2, 1, 1, 1, 4, KC, 9>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    // a one-dimensional grid: the first call's workgroups, then the second's, each numbered x fastest
+    const int id = blockIdx.x;
+    if (id < wgs_a) {
+        const int zy = id / xa;
+        conv_body<T, 2, 1, 1, 1, 4, KC, 9>(a, id - zy * xa, zy % ya, zy / ya);
     } else {
-        if ((int)blockIdx.x < xb && (int)blockIdx.y < yb)
-            conv_body<T, 2, 1, 1, 1, 4, KC, 1>(b, blockIdx.x, blockIdx.y, blockIdx.z - za);
+        const int j = id - wgs_a, zy = j / xb;
+        conv_body<T, 2, 1, 1, 1, 4, KC, 1>(b, j - zy * xb, zy % yb, zy / yb);
     }
 }
 
@@ -1549,14 +1550,15 @@ template <typename T>
 static int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const ConvPlan& pb, hipStream_t st)
 {
     const size_t lds = std::max(pa.lds, pb.lds);
-    const dim3 grid(std::max(pa.slabs, pb.slabs), std::max(pa.bands, pb.bands), pa.groups + pb.groups);
+    const int wgs_a = pa.slabs * pa.bands * pa.groups, wgs_b = pb.slabs * pb.bands * pb.groups;
+    const dim3 grid(wgs_a + wgs_b);
     auto launch = [&](auto kern) {
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_fused_conv_pair: cannot reserve %zu bytes of LDS: %s", lds,
                          hipGetErrorString(e));
         }
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, pa.groups, pa.slabs, pa.bands, pb.slabs, pb.bands);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, wgs_a, pa.slabs, pa.bands, pb.slabs, pb.bands);
         SIGE_LAUNCH_CHECK("sige_fused_conv_pair");
         return (int)SIGE_OK;
     };
@@ -1587,16 +1589,16 @@ extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sig
     }
     hipStream_t st = (hipStream_t)stream;
     // one launch when both take the 64 x 32 shape whose four waves split K, unsplit over workgroups,
-    // with the same chunk: a 3x3 call first, a 1x1 call second - and few workgroups in all (with more
-    // than about three per compute unit the two calls are faster one after the other: measured
-    // 33 vs 25 us at 1440 workgroups, 15.6 vs 16.3 us at 560)
+    // with the same chunk: a 3x3 call first, a 1x1 call second (measured a gain up to the 1440
+    // workgroups at which calls still take that shape: 23.3 vs 25.2 us; 11.4 vs 16.3 us at 560)
     const long wgs_both = nl[0] > 0 && nl[1] > 0 && !pw[0] && !pw[1]
                               ? (long)p[0].groups * p[0].bands * p[0].slabs + (long)p[1].groups * p[1].bands * p[1].slabs
                               : 0;
-    const bool together = nl[0] > 0 && nl[1] > 0 && wgs_both <= 800 && !pw[0] && !pw[1] && c[0]->dt == c[1]->dt && a[0].k == 3 &&
+    const char* pair_env = getenv("SIGE_CONV_PAIR_WGS");     // tuning aid: most workgroups for which the calls share a launch
+    const long pair_max = pair_env ? atol(pair_env) : (1L << 30);
+    const bool together = nl[0] > 0 && nl[1] > 0 && wgs_both <= pair_max && !pw[0] && !pw[1] && c[0]->dt == c[1]->dt && a[0].k == 3 &&
                           a[1].k == 1 && p[0].cfg == 3 && p[1].cfg == 3 && p[0].ksplit == 1 && p[1].ksplit == 1 &&
-                          p[0].kc == p[1].kc && (p[0].kc == 8 || p[0].kc == 4) &&
-                          (long)p[0].groups + p[1].groups <= 65535;
+                          p[0].kc == p[1].kc && (p[0].kc == 8 || p[0].kc == 4);
     if (together) {
         const sige_dtype dt = c[0]->dt;
         return dt == SIGE_F32 ? launch_pair<float>(a[0], p[0], a[1], p[1], st)
