@@ -945,3 +945,68 @@ def test_fused_conv_pair(oracle, dtype, Cin, C3, C1, res, b, n):
     c1.Cin = Cin + 1                        # argument errors of either call are reported
     with pytest.raises(api.SigeError):
         api.sige_fused_conv_pair(c3, c1)
+
+
+def test_config2_full_size_step_as_benchmarked(oracle):
+    """Benchmark configuration 2 at full size exactly as the benchmark's step runs it: one
+    difference pass that fills the lists of both geometries (device-side counts, capacity 16),
+    then both convolutions handed over together (one launch).  Lists bit for bit; both outputs
+    equal to the cache outside the active blocks and to the separate fused calls everywhere;
+    sampled output pixels of both convolutions against the oracle."""
+    cfg = inputs.config2()
+    td = torch.float16
+    H = W = 256
+    C, Cs, b = cfg["Cin"], cfg["Cs"], cfg["block"]
+    a_o, a_e = dev(cfg["a_orig"]), dev(cfg["a_edit"])
+    main = SigeConv(dev(cfg["w"]), cfg["bias"], H, W, b, 1, 1)
+    short = SigeConv(dev(cfg["w_s"]), cfg["bias_s"], H, W, b, 1, 0)
+    cap = 16
+    bl3, bl1 = BlockList(main.g, "cuda", max_blocks=cap), BlockList(short.g, "cuda", max_blocks=cap)
+    mask = torch.zeros((H, W), dtype=torch.uint8, device="cuda")
+    mean, var = torch.zeros(32, device="cuda"), torch.zeros(32, device="cuda")
+    scale, shift = torch.zeros(C, device="cuda"), torch.zeros(C, device="cuda")
+    api.sige_gn_stats(a_o, 32, mean, var, gamma=dev(cfg["gamma"]), beta=dev(cfg["beta"]), eps=cfg["eps"],
+                      scale=scale, shift=shift)
+    rng = np.random.default_rng(7)
+    cache3 = torch.from_numpy(rng.standard_normal((H, W, C)).astype(np.float32)).to(td).cuda()
+    cache1 = torch.from_numpy(rng.standard_normal((H, W, Cs)).astype(np.float32)).to(td).cuda()
+    ws = Workspace("cuda")
+    BlockList.reduce_together([bl3, bl1], a_orig=a_o, a_edit=a_e, tau=cfg["tau"], mask_out=mask, dilate=cfg["dilate"])
+    y3, y1 = cache3.clone(), cache1.clone()
+    c3, _ = main.fused_call(a_e, y3, bl3, ws, scale=scale, shift=shift, act=api.ACT_SILU, tag="main")
+    c1, _ = short.fused_call(a_e, y1, bl1, ws, tag="short")
+    assert c3.n_blocks == -1 and c1.n_blocks == -1 and c3.max_blocks == cap
+    api.sige_fused_conv_pair(c3, c1)
+    torch.cuda.synchronize()
+    m = oracle.diff_mask(cfg["a_orig"].float().numpy(), cfg["a_edit"].float().numpy(), 0.0)
+    assert np.array_equal(mask.cpu().numpy(), m)
+    n3, n1 = int(bl3.count.item()), int(bl1.count.item())
+    blocks3, blocks1 = bl3.indices[:n3].cpu().numpy(), bl1.indices[:n1].cpu().numpy()
+    assert np.array_equal(blocks3, oracle.active_blocks(m, H, W, b, b, 3, 1, 1)) and n3 <= cap
+    assert np.array_equal(blocks1, oracle.active_blocks(m, H, W, b, b, 1, 1, 0)) and 0 < n1 <= n3
+    # the separate fused calls write the same bits
+    z3, z1 = cache3.clone(), cache1.clone()
+    main.forward(a_e, z3, bl3, ws, scale=scale, shift=shift, act=api.ACT_SILU, fused=True)
+    short.forward(a_e, z1, bl1, ws, fused=True)
+    assert torch.equal(y3, z3) and torch.equal(y1, z1)
+    for y, cache, blocks in ((y3, cache3, blocks3), (y1, cache1, blocks1)):
+        out = torch.from_numpy(outside_blocks_mask(blocks, b, b, H, W)).cuda()
+        assert torch.equal(y[out], cache[out])
+    om, ov = oracle.gn_stats(f64(cfg["a_orig"]), 32)
+    osc, osh = oracle.fold_gn(f64(cfg["gamma"]), f64(cfg["beta"]), om, ov, cfg["eps"])
+
+    def sample(blocks):
+        px = []
+        for (y0, x0) in blocks:
+            px += [(y0, x0), (y0 + b - 1, x0 + b - 1), (y0, x0 + b - 1), (y0 + b - 1, x0)]
+            px += [(y0 + int(rng.integers(b)), x0 + int(rng.integers(b))) for _ in range(8)]
+        return np.array(px, np.int32)
+    px = sample(blocks3)
+    got = y3[torch.from_numpy(px[:, 0]).long().cuda(), torch.from_numpy(px[:, 1]).long().cuda()]
+    want = oracle.dense_layer(f64(cfg["a_edit"]), f64(cfg["w"]), f64(cfg["bias"]), 1, 1, osc, osh, oracle.ACT_SILU,
+                              pixels=px, storage="f16")
+    assert_close(got, want, td, "3x3 convolution of the step (sampled)")
+    px = sample(blocks1)
+    got = y1[torch.from_numpy(px[:, 0]).long().cuda(), torch.from_numpy(px[:, 1]).long().cuda()]
+    want = oracle.dense_layer(f64(cfg["a_edit"]), f64(cfg["w_s"]), f64(cfg["bias_s"]), 1, 0, pixels=px)
+    assert_close(got, want, td, "1x1 shortcut of the step (sampled)")
