@@ -13,8 +13,10 @@
 // sige_fused_conv is the same kernel with the gather folded into the staging and the
 // scatter into the epilogue (sige_conv_scatter: the scatter only); with a workspace, calls
 // with few workgroups and a long K are cut along K and finished by conv_reduce_kernel, or
-// - without staged arithmetic and up to two chunks - take a shape whose eight waves split K.
-// 1x1 calls with few rows have a kernel of their own further down (pointwise_kernel).
+// - without staged arithmetic and up to two chunks - take a shape whose four or eight waves split K
+// with the whole of Cin (or half) staged at once.  1x1 calls with few rows have a kernel of their
+// own further down (pointwise_kernel); two independent fused calls can share one launch
+// (conv_pair_kernel, sige_fused_conv_pair).
 // The epilogue can also write activated copies of the output for the layers that
 // normalise it next (Sec. 3.2 "Pre-computing normalization parameters": their Scale+Shift
 // is a constant per channel).
