@@ -195,3 +195,31 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(api.SigeError):
         api.sige_version()
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors of the header's structs have the C compiler's sizes and field offsets
+    (the header is plain C: compiled here with gcc, no GPU toolchain involved)."""
+    import subprocess
+    src = tmp_path / "layout.c"
+    fields = {"sige_geom": ("Geom", ["H_in", "W_out", "block_w", "pad"]),
+              "sige_act_out": ("ActOut", ["y", "y_ld", "scale", "shift", "act"]),
+              "sige_block_list": ("BlockListDesc", ["g", "indices", "max_blocks", "count", "workspace",
+                                                    "workspace_bytes"]),
+              "sige_fused_conv_call": ("FusedConvCall", [f for f, _ in api.FusedConvCall._fields_])}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sige.h"', "int main(void) {"]
+    for cname, (_, fs) in fields.items():
+        lines.append(f'    printf("{cname} %zu\\n", sizeof({cname}));')
+        for f in fs:
+            lines.append(f'    printf("{cname}.{f} %zu\\n", offsetof({cname}, {f}));')
+    lines += ["    return 0;", "}"]
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, (pyname, fs) in fields.items():
+        cls = getattr(api, pyname)
+        assert ctypes.sizeof(cls) == int(out[cname]), cname
+        for f in fs:
+            assert getattr(cls, f).offset == int(out[f"{cname}.{f}"]), (cname, f)
