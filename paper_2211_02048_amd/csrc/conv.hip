@@ -748,7 +748,7 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
 // passes through a buffer in LDS that belongs to the wave alone: written as loaded, read back as
 // operands, no workgroup barrier involved.
 template <typename T, int W, int P, int TM, int TN>
-__global__ __launch_bounds__(64 * W, 1) void pointwise_kernel(ConvArgs a)
+__global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvArgs a)
 {
     constexpr int KS = Mma<T>::KSTEP, S = (int)sizeof(T), N = Vec16<T>::N;
     constexpr int BM = 32 * TM, BN = 32 * TN, RS = BN + 4;
@@ -1305,7 +1305,15 @@ template <typename T>
 static int launch_pointwise(const ConvArgs& a, int nl, int tiles, hipStream_t st)
 {
     if (tiles == 3) return launch_pointwise_as<T, 8, 6, 1, 1>(a, nl, st);
-    return tiles == 2 ? launch_pointwise_as<T, 8, 3, 2, 2>(a, nl, st) : launch_pointwise_as<T, 8, 4, 2, 1>(a, nl, st);
+    if (tiles == 2) {
+        // more 64 x 64 patches than compute units: four waves per workgroup, so that two workgroups
+        // share a compute unit and all of them run at once instead of in two rounds
+        const long mt = ((long)nl * a.bh * a.bw + 63) / 64, nt2 = (a.Cout + 63) / 64;
+        const char* w4 = getenv("SIGE_CONV_POINTWISE_W4");     // tuning aid: 0 = never, 1 = always
+        const bool four = w4 ? atoi(w4) != 0 : mt * nt2 > 256;
+        return four ? launch_pointwise_as<T, 4, 3, 2, 2>(a, nl, st) : launch_pointwise_as<T, 8, 3, 2, 2>(a, nl, st);
+    }
+    return launch_pointwise_as<T, 8, 4, 2, 1>(a, nl, st);
 }
 
 template <typename T>

@@ -434,11 +434,14 @@ def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
     ws = Workspace("cuda")
     prev = os.environ.pop("SIGE_CONV_POINTWISE", None)
     try:
-        for mode in (None, "1", "2", "3"):
+        for mode in (None, "1", "2", "3", "2 with four waves"):
+            os.environ.pop("SIGE_CONV_POINTWISE_W4", None)
             if mode is None:
                 os.environ.pop("SIGE_CONV_POINTWISE", None)
             else:
-                os.environ["SIGE_CONV_POINTWISE"] = mode
+                os.environ["SIGE_CONV_POINTWISE"] = mode[0]
+                if len(mode) > 1:     # the 64 x 64 shape as it runs when there are more patches than compute units
+                    os.environ["SIGE_CONV_POINTWISE_W4"] = "1"
             for device_count in (False, True):
                 bl.n_host = -1 if device_count else n
                 bl.max_blocks = n + 2 if device_count else g.grid_blocks
@@ -463,6 +466,7 @@ def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
                 assert torch.equal(y3, yf)
     finally:
         os.environ.pop("SIGE_CONV_POINTWISE", None)
+        os.environ.pop("SIGE_CONV_POINTWISE_W4", None)
         if prev is not None:
             os.environ["SIGE_CONV_POINTWISE"] = prev
     # the tiled kernel on the same call: same values up to the order of the fp32 sums
