@@ -174,4 +174,26 @@ __device__ __forceinline__ int blocks_and_origin(const int32_t* count, int max_b
     return n_eff;
 }
 
+// Division by a divisor known on the host: q = floor(x / d) for any 0 <= x < 2^32 and d >= 1 from one
+// high multiply and one correction (m = floor(2^32 / d), 0 for d == 1).  The compiler's expansion of
+// a 32-bit division is about thirty instructions, several of them quarter-rate multiplies, and the
+// prologues of the small kernels are instruction bound.
+struct FastDiv { int d; unsigned m; };
+inline FastDiv fast_div(int d)
+{
+    FastDiv f;
+    f.d = d;
+    f.m = d <= 1 ? 0u : (unsigned)((1ull << 32) / (unsigned)d);
+    return f;
+}
+__device__ __forceinline__ void divmod(int x, const FastDiv f, int& q, int& r)
+{
+    if (f.m == 0u) { q = x; r = 0; return; }     // d == 1
+    unsigned qq = __umulhi((unsigned)x, f.m);
+    unsigned rr = (unsigned)x - qq * (unsigned)f.d;
+    if (rr >= (unsigned)f.d) { ++qq; rr -= (unsigned)f.d; }
+    q = (int)qq;
+    r = (int)rr;
+}
+
 }  // namespace sige

@@ -105,6 +105,9 @@ struct ConvArgs {
     // gated GELU folded into the epilogue (tiles out only): the Cout convolution channels come in
     // groups of 16 = 8 values followed by their 8 gates; out has Cout / 2 channels
     int glu;
+    // divisors the kernels divide by, prepared on the host: rows * bw (a workgroup's rows per block),
+    // bw, trows * tw, tw, bh * bw, and the 16-byte runs per output pixel (the reduction kernel's)
+    FastDiv d_pb, d_bw, d_per, d_tw, d_pbfull, d_runs;
 };
 
 // Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
@@ -311,7 +314,6 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
     const int wk = wave % WK, wmn = wave / WK;
     const int wm = wmn / WN, wn = wmn - wm * WN;
     const int half = lane >> 5, l32 = lane & 31;
-    const int pb = a.rows * a.bw;                             // M rows one block contributes
     const int trow0 = band_row0 * a.stride;                   // first staged tile row
 
     // LDS byte offset of this lane's A row for each of its M tiles (clamped to a valid pixel)
@@ -319,8 +321,9 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int m = (wm * TM + tm) * 32 + l32;
-        int g = m / pb, p = m - g * pb;
-        int py = p / a.bw, px = p - py * a.bw;
+        int g, p, py, px;
+        divmod(m, a.d_pb, g, p);
+        divmod(p, a.d_bw, py, px);
         if (g >= a.G || py >= band_rows) { g = 0; py = 0; px = 0; }
         a_base[tm] = ((g * a.trows + py * a.stride) * a.tw + px * a.stride) * a.ps + half * 16 +
                      wk * KW * (KS * S);
@@ -386,15 +389,11 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
     int sq0 = tid < NTS ? tid / VPC : npix, sg0, sr0, sx0;    // first pixel of this thread: index, block, row, column
     int step_g, step_r, step_x;                               // PPI pixels further, in the same mixed radix
     {
-        const int per = a.trows * a.tw;
-        sg0 = sq0 / per;
-        int rem = sq0 - sg0 * per;
-        sr0 = rem / a.tw;
-        sx0 = rem - sr0 * a.tw;
-        step_g = PPI / per;
-        rem = PPI - step_g * per;
-        step_r = rem / a.tw;
-        step_x = rem - step_r * a.tw;
+        int rem;
+        divmod(sq0, a.d_per, sg0, rem);
+        divmod(rem, a.d_tw, sr0, sx0);
+        divmod(PPI, a.d_per, step_g, rem);
+        divmod(rem, a.d_tw, step_r, step_x);
     }
     const int Ws = a.Win >> a.up;
     const int rmax = a.th - 1 - trow0;                        // last staged row that exists in the tile
@@ -487,7 +486,8 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
         }
     };
     auto load_a = [&](uint4 (&af)[TM], int tp, int kc) {
-        const int ky = tp / a.k, kx = tp - ky * a.k;
+        const int kdim = KK == 9 ? 3 : (KK == 1 ? 1 : a.k);      // known at compile time for the unrolled sizes
+        const int ky = tp / kdim, kx = tp - ky * kdim;
         const int off = (ky * a.tw + kx) * a.ps + kc * (KS * S);
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) af[tm] = *(const uint4*)(lds + a_base[tm] + off);
@@ -565,8 +565,9 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
         for (int e = tid; e < BM * (BN / N); e += NT) {
             const int m = e / (BN / N), nn = (e - m * (BN / N)) * N;   // row of the workgroup's patch
             const int o = bx * BN + nn;
-            const int g = m / pb, p = m - g * pb;
-            const int py = p / a.bw, px = p - py * a.bw;
+            int g, p, py, px;
+            divmod(m, a.d_pb, g, p);
+            divmod(p, a.d_bw, py, px);
             if (g >= a.G || py >= band_rows || g0 + g >= n_eff || o >= a.Cout) continue;
             if (a.glu) {          // value runs finish themselves and their gates, gate runs have nothing to do
                 if ((o & 15) >= 8) continue;
@@ -682,18 +683,17 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
                  "s"(a.ao[1].act));
     const long e = (long)blockIdx.x * 256 + threadIdx.x;
     if (e >= n_runs) return;
-    const int runs = (a.Cout + N - 1) / N;
-    const long row = e / runs;
-    const int o = (int)(e - row * runs) * N;
-    const int pb = a.bh * a.bw;
-    const int n = (int)(row / pb), p = (int)(row - (long)n * pb);
-    const int py = p / a.bw, px = p - py * a.bw;
+    int row, run, n, p, py, px;                          // e < 2^31 (checked at the launch)
+    divmod((int)e, a.d_runs, row, run);
+    const int o = run * N;
+    divmod(row, a.d_pbfull, n, p);
+    divmod(p, a.d_bw, py, px);
     const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
     int y0 = 0, x0 = 0, n_eff;
     if (to_y) n_eff = blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, y0, x0);
     else n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
     if (n >= n_eff) return;
-    const long t = row * a.Cout + o;
+    const long t = (long)row * a.Cout + o;
     long pix = 0;
     if (to_y) {
         const int oy = y0 + py, ox = x0 + px;
@@ -805,7 +805,9 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
         rr[i] = r0 + 16 * i + (lane >> 2);
         oy[i] = ox[i] = 0;
         if (have_org) {
-            const int n = min(rr[i] / pb, a.max_blocks - 1);
+            int n, rem_;
+            divmod(rr[i], a.d_pbfull, n, rem_);
+            n = min(n, a.max_blocks - 1);
             oy[i] = a.indices[2 * n];
             ox[i] = a.indices[2 * n + 1];
         }
@@ -833,8 +835,9 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
         long pixel = r;
         long ld = a.Cin;
         if (gathered) {
-            const int n = r / pb, p = r - n * pb;
-            const int py = p / a.bw, px = p - py * a.bw;
+            int n, p, py, px;
+            divmod(r, a.d_pbfull, n, p);
+            divmod(p, a.d_bw, py, px);
             // the origin fetched above belongs to row rr; a clamped row reads the last block's
             const int y0 = r == rr[i] ? oy[i] : a.indices[2 * n];
             const int x0 = r == rr[i] ? ox[i] : a.indices[2 * n + 1];
@@ -870,8 +873,9 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
             for (int i = 0; i < N; ++i)
                 if (a.bias && o + i < a.Cout) pre_bv[i] = a.bias[o + i];
             if (to_y && vec_ok && o + N <= a.Cout) {
-                const int n = r / pb, p = r - n * pb;
-                const int py = p / a.bw, px = p - py * a.bw;
+                int n, p, py, px;
+                divmod(r, a.d_pbfull, n, p);
+                divmod(p, a.d_bw, py, px);
                 const int yy = a.indices[2 * n] + py, xx = a.indices[2 * n + 1] + px;
                 if (yy >= 0 && yy < a.Hout && xx >= 0 && xx < a.Wout) {
                     pre_ok = true;
@@ -961,8 +965,9 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
         const long t = (long)r * a.Cout + o;
         long pix = 0;
         if (to_y) {
-            const int n = r / pb, p = r - n * pb;
-            const int py = p / a.bw, px = p - py * a.bw;
+            int n, p, py, px;
+            divmod(r, a.d_pbfull, n, p);
+            divmod(p, a.d_bw, py, px);
             const int yy = org[2 * m] + py, xx = org[2 * m + 1] + px;
             if (yy < 0 || yy >= a.Hout || xx < 0 || xx >= a.Wout) continue;
             pix = (long)yy * a.Wout + xx;
@@ -1321,7 +1326,7 @@ static int launch_reduce(const ConvArgs& a, int nl, hipStream_t st)
 {
     const long n_runs = (long)nl * a.bh * a.bw * ((a.Cout + Vec16<T>::N - 1) / Vec16<T>::N);
     const long blocks = (n_runs + 255) / 256;
-    SIGE_REQUIRE(blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "sige_conv: too many output elements for the K-split reduction");
+    SIGE_REQUIRE(n_runs < (1L << 31), SIGE_ERR_UNSUPPORTED, "sige_conv: too many output elements for the K-split reduction");
     hipLaunchKernelGGL((conv_reduce_kernel<T>), dim3((int)blocks), dim3(256), 0, st, a, n_runs);
     SIGE_LAUNCH_CHECK("sige_conv(reduce)");
     return SIGE_OK;
@@ -1334,6 +1339,9 @@ static int prepare_conv(const char* who, sige_dtype dt, const sige_geom* g, int 
 {
     const int ks = dt == SIGE_F32 ? 8 : 16;
     a.bh = g->block_h; a.bw = g->block_w; a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
+    a.d_bw = fast_div(g->block_w);
+    a.d_pbfull = fast_div(g->block_h * g->block_w);
+    a.d_runs = fast_div((Cout + (int)(16 / dtype_size(dt)) - 1) / (int)(16 / dtype_size(dt)));
     *pointwise = pointwise_tiles(g, a, ks, nl);
     if (*pointwise) return SIGE_OK;
     const bool ws_ok = workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
@@ -1347,6 +1355,9 @@ static int prepare_conv(const char* who, sige_dtype dt, const sige_geom* g, int 
     a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
     a.G = p->G; a.rows = p->rows; a.trows = p->trows; a.Cc = p->Cc; a.ps = p->ps;
     a.bands = p->bands; a.ksplit = p->ksplit;
+    a.d_pb = fast_div(p->rows * g->block_w);
+    a.d_per = fast_div(p->trows * tw);
+    a.d_tw = fast_div(tw);
     a.partial = p->ksplit > 1 ? (float*)workspace : nullptr;
     a.partial_stride = (long)nl * g->block_h * g->block_w * Cout;
     return SIGE_OK;
