@@ -23,6 +23,8 @@ struct GatherArgs {
     int th, tw, stride, pad, up;
     int max_blocks, n_host, act, rows_per_wg;
     int segs, seg_px;   // few blocks: a tile row is cut into segs runs of seg_px pixels, one workgroup each
+    int lv;             // log2(V) where V divides 256 (a power of two then): divisions by V are shifts
+    FastDiv d_tw, d_segs;
 };
 
 // FIXED_CG: blockDim.x is a multiple of V, so a thread keeps one channel group and
@@ -35,7 +37,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
     int by0, bx0;
     if (n >= blocks_and_origin(a.count, a.max_blocks, a.n_host, a.indices, n, by0, bx0)) return;
     const int iy0 = by0 * a.stride - a.pad, ix0 = bx0 * a.stride - a.pad;
-    const int rg = blockIdx.x / a.segs, seg = blockIdx.x - rg * a.segs;
+    int rg, seg;
+    divmod(blockIdx.x, a.d_segs, rg, seg);
     const int r0 = rg * a.rows_per_wg;
     const int r1 = min(r0 + a.rows_per_wg, a.th);
     const int row_vecs = a.tw * a.V;
@@ -46,7 +49,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
 
     float sc[N], sh[N];
     if (FUSED && FIXED_CG) {
-        const int cg = threadIdx.x % a.V;
+        const int cg = threadIdx.x & (a.V - 1);
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             sc[i] = a.scale ? a.scale[cg * N + i] : 1.0f;
@@ -91,8 +94,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
         // one run of pixels of one tile row (rows_per_wg is 1 here)
         const int px0 = seg * a.seg_px, px1 = min(px0 + a.seg_px, a.tw);
         if (FIXED_CG) {
-            const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
-            for (int px = px0 + threadIdx.x / a.V; px < px1; px += ppi) move(0, px, cg);
+            const int ppi = 256 >> a.lv, cg = threadIdx.x & (a.V - 1);
+            for (int px = px0 + (threadIdx.x >> a.lv); px < px1; px += ppi) move(0, px, cg);
         } else {
             for (int j = px0 * a.V + threadIdx.x; j < px1 * a.V; j += 256) {
                 const int px = j / a.V;
@@ -102,10 +105,10 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
     } else if (FIXED_CG) {
         // a thread keeps its channel group and walks over the pixels of the row group without
         // dividing: 256 / V pixels further each time
-        const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
-        const int step_r = ppi / a.tw, step_x = ppi - step_r * a.tw;
-        int p = threadIdx.x / a.V;
-        int r = p / a.tw, px = p - r * a.tw;
+        const int ppi = 256 >> a.lv, cg = threadIdx.x & (a.V - 1);
+        int step_r, step_x, r, px;
+        divmod(ppi, a.d_tw, step_r, step_x);
+        divmod(threadIdx.x >> a.lv, a.d_tw, r, px);
         const int nrows = r1 - r0;
         while (r < nrows) {
             move(r, px, cg);
@@ -132,6 +135,8 @@ struct ScatterArgs {
     int Hout, Wout, V, y_ld_vec, res_ld_vec;
     int bh, bw;
     int max_blocks, n_host, rows_per_wg;
+    int lv;             // log2(V) where V divides 256
+    FastDiv d_bw;       // for blocks that are not clipped at the right edge (cols == bw)
 };
 
 template <typename T, bool ADD>
@@ -177,10 +182,16 @@ __global__ __launch_bounds__(256) void scatter_kernel(ScatterArgs a)
         // division-free walk: a thread keeps its channel group, 256 / V pixels further each time;
         // the tile vectors (and residuals) of U pixels are loaded before any is stored
         constexpr int U = 4;
-        const int ppi = 256 / a.V, cg = threadIdx.x % a.V;
-        const int step_r = ppi / cols, step_x = ppi - step_r * cols;
-        int p = threadIdx.x / a.V;
-        int r = p / cols, px = p - r * cols;
+        const int ppi = 256 >> a.lv, cg = threadIdx.x & (a.V - 1);
+        const int p = threadIdx.x >> a.lv;
+        int step_r, step_x, r, px;
+        if (cols == a.bw) {              // the usual case: divisor known on the host
+            divmod(ppi, a.d_bw, step_r, step_x);
+            divmod(p, a.d_bw, r, px);
+        } else {
+            step_r = ppi / cols; step_x = ppi - step_r * cols;
+            r = p / cols; px = p - r * cols;
+        }
         const int nrows = r1 - r0;
         while (r < nrows) {
             uint4 v[U], q1[U], q2[U];
@@ -319,6 +330,10 @@ static int run_gather(const char* who, const void* x, sige_dtype dt, int32_t C, 
         a.seg_px = seg_px;
         a.segs = (tw + seg_px - 1) / seg_px;
     }
+    a.lv = 0;
+    while ((1 << (a.lv + 1)) <= a.V && a.lv < 8) ++a.lv;      // floor(log2 V); exact where V divides 256
+    a.d_tw = fast_div(tw);
+    a.d_segs = fast_div(a.segs);
     dim3 grid(((th + a.rows_per_wg - 1) / a.rows_per_wg) * a.segs, nl);
     SIGE_REQUIRE(nl <= 65535, SIGE_ERR_UNSUPPORTED, "%s: more than 65535 blocks per launch", who);
     hipStream_t st = (hipStream_t)stream;
@@ -381,6 +396,9 @@ extern "C" int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geo
     a.bh = g->block_h; a.bw = g->block_w;
     a.max_blocks = max_blocks; a.n_host = n_blocks;
     a.rows_per_wg = pick_rows(g->block_h, (size_t)g->block_w * Cout * s, nl, 8192);
+    a.lv = 0;
+    while ((1 << (a.lv + 1)) <= a.V && a.lv < 8) ++a.lv;
+    a.d_bw = fast_div(g->block_w);
     dim3 grid((g->block_h + a.rows_per_wg - 1) / a.rows_per_wg, nl);
     hipStream_t st = (hipStream_t)stream;
     if (dt == SIGE_F32) launch_scatter<float>(a, grid, st);

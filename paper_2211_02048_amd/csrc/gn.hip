@@ -151,8 +151,12 @@ __global__ __launch_bounds__(256) void gn_fold_kernel(float* mean, float* var, f
 // lanes.  Every lane sums its pixels, the lanes' sums meet in LDS and are added in lane order, the
 // channels of a group likewise.
 template <typename T>
+// ppl = 256 / VW pixel lanes, strips = 256 / CW, per = ceil(ppl / strips), gpw = CW / cg groups per
+// workgroup and the reciprocals of VW, CW and cg come from the host.
 __global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__ x, int n_pix, int ld_vec, int VW,
-                                                       int cg, const float* __restrict__ gamma,
+                                                       int cg, int ppl, int strips, int per, int gpw,
+                                                       FastDiv d_vw, FastDiv d_cw, FastDiv d_cg,
+                                                       const float* __restrict__ gamma,
                                                        const float* __restrict__ beta, float eps,
                                                        float* __restrict__ mean, float* __restrict__ var,
                                                        float* __restrict__ scale, float* __restrict__ shift)
@@ -160,8 +164,9 @@ __global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__
     constexpr int N = Vec16<T>::N;
     constexpr int U = 4;               // loads in flight per lane
     extern __shared__ float red[];     // [2][ppl][CW] sums and sums of squares, then [2][CW] mean and variance
-    const int ppl = 256 / VW, CW = VW * N;
-    const int cv = threadIdx.x % VW, pl = threadIdx.x / VW;
+    const int CW = VW * N;
+    int cv, pl;
+    divmod(threadIdx.x, d_vw, pl, cv);
     const int v0 = blockIdx.x * VW;    // first channel vector of this workgroup
     float* sq = red + ppl * CW;
     float* stat = red + 2 * ppl * CW;
@@ -194,9 +199,9 @@ __global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__
     // Column sums in two steps, both in a fixed order: 256 / CW threads per channel each add a strip of
     // the pixel lanes, then one thread per channel adds the strips.  (A thread writes only into its
     // own strip's first row, which nobody else reads in that step.)
-    const int strips = 256 / CW, per = (ppl + strips - 1) / strips;
     {
-        const int cc = threadIdx.x % CW, sidx = threadIdx.x / CW;
+        int cc, sidx;
+        divmod(threadIdx.x, d_cw, sidx, cc);
         if (sidx < strips) {
             const int l0 = sidx * per, l1 = min(l0 + per, ppl);
             float st = 0.0f, qt = 0.0f;
@@ -213,13 +218,13 @@ __global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__
         sq[c] = qt;
     }
     __syncthreads();
-    if (c < CW / cg) {                 // group c of the workgroup
+    if (c < gpw) {                     // group c of the workgroup (gpw = CW / cg of them)
         float st = 0.0f, qt = 0.0f;
         for (int j = 0; j < cg; ++j) { st += red[c * cg + j]; qt += sq[c * cg + j]; }
         const float n = (float)n_pix * (float)cg;
         const float mu = st / n;
         const float v = fmaxf(qt / n - mu * mu, 0.0f);
-        const int g = (v0 * N) / cg + c;
+        const int g = blockIdx.x * gpw + c;
         mean[g] = mu;
         var[g] = v;
         stat[c] = mu;
@@ -227,7 +232,9 @@ __global__ __launch_bounds__(256) void gn_small_kernel(const uint4* __restrict__
     }
     __syncthreads();
     if (scale != nullptr && c < CW) {
-        const int ch = v0 * N + c, g = c / cg;
+        int g, rem_;
+        divmod(c, d_cg, g, rem_);
+        const int ch = v0 * N + c;
         const float sc = (gamma ? gamma[ch] : 1.0f) * rsqrtf(stat[CW + g] + eps);
         scale[ch] = sc;
         shift[ch] = (beta ? beta[ch] : 0.0f) - stat[g] * sc;
@@ -250,10 +257,11 @@ static void launch_small(const void* x, int n_pix, int V, int ld_vec, int VW, in
                          const float* beta, float eps, float* mean, float* var, float* scale, float* shift,
                          hipStream_t st)
 {
-    const int ppl = 256 / VW, CW = VW * Vec16<T>::N;
+    const int ppl = 256 / VW, CW = VW * Vec16<T>::N, strips = 256 / CW;
     const size_t lds = (size_t)(2 * ppl * CW + 2 * CW) * sizeof(float);
     hipLaunchKernelGGL((gn_small_kernel<T>), dim3(V / VW), dim3(256), lds, st, (const uint4*)x, n_pix, ld_vec, VW,
-                       cg, gamma, beta, eps, mean, var, scale, shift);
+                       cg, ppl, strips, (ppl + strips - 1) / strips, CW / cg, fast_div(VW), fast_div(CW), fast_div(cg), gamma,
+                       beta, eps, mean, var, scale, shift);
 }
 
 template <typename T>

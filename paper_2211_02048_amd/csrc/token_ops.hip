@@ -23,6 +23,7 @@ struct RowArgs {
     // [H][W][x_ld] tensor x; a pixel outside the tensor is a row of zeros, as in a gathered tile
     const int32_t* indices;
     int bh, bw, H, W;
+    FastDiv d_pb, d_bw;     // bh * bw and bw, prepared on the host
 };
 
 __device__ __forceinline__ int effective_rows(const RowArgs& a)
@@ -52,8 +53,9 @@ __global__ __launch_bounds__(256) void token_norm_kernel(RowArgs a)
     long pixel = row;
     bool inside = true;
     if (a.indices != nullptr) {
-        const int pb = a.bh * a.bw, n = row / pb, p = row - n * pb;
-        const int py = p / a.bw, px = p - py * a.bw;
+        int n, p, py, px;
+        divmod(row, a.d_pb, n, p);
+        divmod(p, a.d_bw, py, px);
         const int iy = a.indices[2 * n] + py, ix = a.indices[2 * n + 1] + px;
         inside = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
         pixel = inside ? (long)iy * a.W + ix : 0;
@@ -201,6 +203,7 @@ extern "C" int sige_token_norm(const void* x, sige_dtype dt, int32_t C, int32_t 
     a.x = x; a.y = y; a.gamma = gamma; a.beta = beta; a.count = count; a.C = C; a.x_ld = x_ld; a.y_ld = y_ld;
     a.rows_per_count = rows_per_count; a.max_rows = max_rows; a.n_host = n_rows; a.eps = eps;
     a.indices = nullptr; a.bh = a.bw = a.H = a.W = 0;
+    a.d_pb = a.d_bw = fast_div(1);
     hipStream_t st = (hipStream_t)stream;
     return dt == SIGE_F32 ? launch_norm<float>(a, rows, st)
            : dt == SIGE_F16 ? launch_norm<f16>(a, rows, st) : launch_norm<bf16>(a, rows, st);
@@ -232,6 +235,8 @@ extern "C" int sige_gather_token_norm(const void* x, sige_dtype dt, int32_t C, i
     a.rows_per_count = (int)pb; a.max_rows = (int)(pb * max_blocks); a.n_host = n_blocks >= 0 ? (int)(pb * n_blocks) : -1;
     a.eps = eps;
     a.indices = indices; a.bh = g->block_h; a.bw = g->block_w; a.H = g->H_in; a.W = g->W_in;
+    a.d_pb = fast_div(g->block_h * g->block_w);
+    a.d_bw = fast_div(g->block_w);
     hipStream_t st = (hipStream_t)stream;
     return dt == SIGE_F32 ? launch_norm<float>(a, rows, st)
            : dt == SIGE_F16 ? launch_norm<f16>(a, rows, st) : launch_norm<bf16>(a, rows, st);
@@ -250,6 +255,7 @@ extern "C" int sige_geglu(const void* x, sige_dtype dt, int32_t C, int32_t x_ld,
     a.x = x; a.y = y; a.gamma = nullptr; a.beta = nullptr; a.count = count; a.C = C; a.x_ld = x_ld; a.y_ld = y_ld;
     a.rows_per_count = rows_per_count; a.max_rows = max_rows; a.n_host = n_rows; a.eps = 0.0f;
     a.indices = nullptr; a.bh = a.bw = a.H = a.W = 0;
+    a.d_pb = a.d_bw = fast_div(1);
     const long n = (long)rows * (C * (long)dtype_size(dt) / 16);
     const long blocks = (n + 255) / 256;
     SIGE_REQUIRE(blocks < (1L << 31), SIGE_ERR_UNSUPPORTED, "%s: too many elements", who);
