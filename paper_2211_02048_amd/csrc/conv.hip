@@ -155,6 +155,27 @@ __device__ __forceinline__ void load_act_params(const ConvArgs& a, int o, ActPar
     }
 }
 
+// The bias of the N channels from o on: as 16-byte vectors when the run is whole and the array is
+// 16-byte aligned (o is a multiple of N), element by element otherwise; 0 where there is none.
+template <int N>
+__device__ __forceinline__ void load_bias(const ConvArgs& a, int o, float (&bv)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) bv[i] = 0.0f;
+    if (a.bias == nullptr) return;
+    if (o + N <= a.Cout && aligned16_dev(a.bias)) {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            const f32x4 q = *(const f32x4*)(a.bias + o + 4 * i);
+            bv[4 * i] = q.x; bv[4 * i + 1] = q.y; bv[4 * i + 2] = q.z; bv[4 * i + 3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            if (o + i < a.Cout) bv[i] = a.bias[o + i];
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_ok, long t, long pix, int o,
                                          float (&v)[Vec16<T>::N], const ActParams<Vec16<T>::N>& ap,
@@ -716,8 +737,8 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvArgs a, long n_run
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         v[i] = 0.0f;
-        bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
     }
+    load_bias<N>(a, o, bv);
     if (vec4) {
         if (a.ksplit <= 4) add_shares<4, N>(a.partial, a.partial_stride, a.ksplit, t, v);
         else if (a.ksplit <= 8) add_shares<8, N>(a.partial, a.partial_stride, a.ksplit, t, v);
@@ -869,9 +890,7 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
 #pragma unroll
         for (int i = 0; i < N; ++i) pre_bv[i] = 0.0f;
         if (tid < BM * (BN / N) && r < rows && o < a.Cout) {
-#pragma unroll
-            for (int i = 0; i < N; ++i)
-                if (a.bias && o + i < a.Cout) pre_bv[i] = a.bias[o + i];
+            load_bias<N>(a, o, pre_bv);
             if (to_y && vec_ok && o + N <= a.Cout) {
                 int n, p, py, px;
                 divmod(r, a.d_pbfull, n, p);
@@ -993,7 +1012,8 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
         }
         if (!first) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) bv[i] = (a.bias && o + i < a.Cout) ? a.bias[o + i] : 0.0f;
+            for (int i = 0; i < N; ++i) bv[i] = 0.0f;
+            load_bias<N>(a, o, bv);
         }
 #pragma unroll
         for (int w = 0; w < W; ++w) {
