@@ -148,9 +148,21 @@ __device__ __forceinline__ void load_act_params(const ConvArgs& a, int o, ActPar
     for (int j = 0; j < SIGE_MAX_ACT_OUTS; ++j) {
         if (j >= a.n_ao) break;
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            p.sc[j][i] = a.ao[j].scale ? a.ao[j].scale[o + i] : 1.0f;
-            p.sh[j][i] = a.ao[j].scale ? a.ao[j].shift[o + i] : 0.0f;
+        for (int i = 0; i < N; ++i) { p.sc[j][i] = 1.0f; p.sh[j][i] = 0.0f; }
+        if (a.ao[j].scale == nullptr) continue;
+        if (aligned16_dev(a.ao[j].scale) && aligned16_dev(a.ao[j].shift)) {    // o is a multiple of N: whole vectors
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i) {
+                const f32x4 c = *(const f32x4*)(a.ao[j].scale + o + 4 * i), h = *(const f32x4*)(a.ao[j].shift + o + 4 * i);
+                p.sc[j][4 * i] = c.x; p.sc[j][4 * i + 1] = c.y; p.sc[j][4 * i + 2] = c.z; p.sc[j][4 * i + 3] = c.w;
+                p.sh[j][4 * i] = h.x; p.sh[j][4 * i + 1] = h.y; p.sh[j][4 * i + 2] = h.z; p.sh[j][4 * i + 3] = h.w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                p.sc[j][i] = a.ao[j].scale[o + i];
+                p.sh[j][i] = a.ao[j].shift[o + i];
+            }
         }
     }
 }
@@ -427,11 +439,21 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
         if (chunk != ch0) __syncthreads();
         float sc[N], sh[N];
         if (FUSED && fuse_math) {
-            const int cbase = c0 + sv * N;
+            const int cbase = c0 + sv * N;                     // a multiple of N: whole 16-byte vectors
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                sc[i] = a.scale ? a.scale[cbase + i] : 1.0f;
-                sh[i] = a.scale ? a.shift[cbase + i] : 0.0f;
+            for (int i = 0; i < N; ++i) { sc[i] = 1.0f; sh[i] = 0.0f; }
+            if (a.scale != nullptr) {
+                if (aligned16_dev(a.scale) && aligned16_dev(a.shift)) {
+#pragma unroll
+                    for (int i = 0; i < N / 4; ++i) {
+                        const f32x4 c = *(const f32x4*)(a.scale + cbase + 4 * i), h = *(const f32x4*)(a.shift + cbase + 4 * i);
+                        sc[4 * i] = c.x; sc[4 * i + 1] = c.y; sc[4 * i + 2] = c.z; sc[4 * i + 3] = c.w;
+                        sh[4 * i] = h.x; sh[4 * i + 1] = h.y; sh[4 * i + 2] = h.z; sh[4 * i + 3] = h.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < N; ++i) { sc[i] = a.scale[cbase + i]; sh[i] = a.shift[cbase + i]; }
+                }
             }
         }
         // this thread's 16 bytes of pixel 0 of the source; pixels are then a 32-bit index away
