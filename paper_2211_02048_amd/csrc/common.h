@@ -174,6 +174,24 @@ __device__ __forceinline__ int blocks_and_origin(const int32_t* count, int max_b
     return n_eff;
 }
 
+// N consecutive fp32 parameters starting at p + off (off a multiple of N): as 16-byte vectors when p
+// is 16-byte aligned, element by element otherwise.
+template <int N>
+__device__ __forceinline__ void load_f32_run(const float* p, int off, float (&out)[N])
+{
+    typedef float vec4 __attribute__((ext_vector_type(4)));
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            const vec4 q = *(const vec4*)(p + off + 4 * i);
+            out[4 * i] = q.x; out[4 * i + 1] = q.y; out[4 * i + 2] = q.z; out[4 * i + 3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) out[i] = p[off + i];
+    }
+}
+
 // Division by a divisor known on the host: q = floor(x / d) for any 0 <= x < 2^32 and d >= 1 from one
 // high multiply and one correction (m = floor(2^32 / d), 0 for d == 1).  The compiler's expansion of
 // a 32-bit division is about thirty instructions, several of them quarter-rate multiplies, and the

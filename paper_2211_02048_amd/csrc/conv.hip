@@ -989,9 +989,10 @@ __global__ __launch_bounds__(64 * W, W == 4 ? 2 : 1) void pointwise_kernel(ConvA
             if ((o & 15) >= 8) continue;
             float v[N], gt[N];
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                v[i] = a.bias ? a.bias[o + i] : 0.0f;
-                gt[i] = a.bias ? a.bias[o + 8 + i] : 0.0f;
+            for (int i = 0; i < N; ++i) { v[i] = 0.0f; gt[i] = 0.0f; }
+            if (a.bias != nullptr) {      // whole runs: the channel count is a multiple of 16 here
+                load_f32_run<N>(a.bias, o, v);
+                load_f32_run<N>(a.bias, o + 8, gt);
             }
 #pragma unroll
             for (int w = 0; w < W; ++w)

@@ -51,9 +51,10 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
     if (FUSED && FIXED_CG) {
         const int cg = threadIdx.x & (a.V - 1);
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            sc[i] = a.scale ? a.scale[cg * N + i] : 1.0f;
-            sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
+        for (int i = 0; i < N; ++i) { sc[i] = 1.0f; sh[i] = 0.0f; }
+        if (a.scale != nullptr) {
+            load_f32_run<N>(a.scale, cg * N, sc);
+            load_f32_run<N>(a.shift, cg * N, sh);
         }
     }
     auto move = [&](int r, int px, int cg) {
@@ -66,9 +67,10 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
                 unpack<T>(v, f);
                 if (!FIXED_CG) {
 #pragma unroll
-                    for (int i = 0; i < N; ++i) {
-                        sc[i] = a.scale ? a.scale[cg * N + i] : 1.0f;
-                        sh[i] = a.scale ? a.shift[cg * N + i] : 0.0f;
+                    for (int i = 0; i < N; ++i) { sc[i] = 1.0f; sh[i] = 0.0f; }
+                    if (a.scale != nullptr) {
+                        load_f32_run<N>(a.scale, cg * N, sc);
+                        load_f32_run<N>(a.shift, cg * N, sh);
                     }
                 }
                 if (a.mod == nullptr) {
