@@ -35,10 +35,12 @@ def instance_stats(x, eps: float):
 
 
 def spade_pass(bufs, ops, P, seg, *, storage: str, eps: float = 1e-5, block: int = 16, cache=None, stats=None,
-               mask=None, dilate: int = 1, min_sparse=(8, 16)):
+               mask=None, dilate: int = 1, min_sparse=(8, 16), trace=None):
     """seg: {(h, w): one-hot label map [h, w, label_pad]} for every resolution.  cache None: the
     pass on the original label map, returns (buffers, stats); otherwise the edit pass over copies
-    of the cached buffers, returns (buffers, blocks per op)."""
+    of the cached buffers, returns (buffers, blocks per op).  trace (a list, optional) receives one
+    (op name, {"y": copy of the buffer the operation wrote} or {"short": a shortcut branch's full
+    output, "t": the modulated and activated input}) entry per operation, in order."""
     rnd = lambda a: so.round_storage(a, storage)
     dense = cache is None
     B = {n: np.zeros(s) for n, s in bufs.items()} if dense else {n: a.copy() for n, a in cache.items()}
@@ -63,6 +65,8 @@ def spade_pass(bufs, ops, P, seg, *, storage: str, eps: float = 1e-5, block: int
         if op["kind"] == "up":
             y = x.repeat(2, axis=0).repeat(2, axis=1)
             B[op["y"]] = so.select_blocks(y, B[op["y"]], blocks, b, b)
+            if trace is not None:
+                trace.append((n, {"y": B[op["y"]].copy()}))
             continue
         act = ACTS[op["act"]]
         if op["spade"] is not None:
@@ -78,10 +82,14 @@ def spade_pass(bufs, ops, P, seg, *, storage: str, eps: float = 1e-5, block: int
         y = rnd(so.conv2d(t, _p64(P, n + ".w"), _p64(P, n + ".b"), 1, k // 2))
         if not op["scatter"]:
             short[n] = y
+            if trace is not None:
+                trace.append((n, {"short": y.copy()}))
             continue
         if op["shortcut"] is not None:
             y = rnd(y + short[op["shortcut"]])
         if op["residual"] is not None:
             y = rnd(y + B[op["residual"]])
         B[op["y"]] = so.select_blocks(y, B[op["y"]], blocks, b, b)
+        if trace is not None:
+            trace.append((n, {"y": B[op["y"]].copy()}))
     return (B, stats_out) if dense else (B, used)

@@ -38,15 +38,18 @@ def all_blocks(Hout, Wout, b):
 
 
 def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate, block, min_sparse_res,
-                       groups, eps):
+                       groups, eps, rec=None):
     """A latent-diffusion style transformer block under the method (Sec. 3.2 "Extension to attention
     layers", Fig. "sige-attention"), written densely: every stage is computed for all tokens from the
     current tensors and kept only on the tokens of the active blocks; the self-attention keys and
     values are caches whose active tokens are overwritten before the attention runs.  Stages: group
     norm (cached statistics) + 1x1 in; layer norm + self-attention + residual; layer norm +
     cross-attention over the text embeddings + residual; layer norm + gated-GELU feed-forward +
-    residual; 1x1 out + the block's input.  Every stored tensor is rounded once to the storage type."""
+    residual; 1x1 out + the block's input.  Every stored tensor is rounded once to the storage type.
+    rec (a dict, optional) receives a copy of every stored tensor of the block, whole, under the
+    names used below."""
     n, C, heads = op["name"], op["C"], op["heads"]
+    note = (lambda name, a: rec.__setitem__(name, np.array(a, copy=True))) if rec is not None else (lambda name, a: None)
     d = C // heads
     r = x.shape[0]
     T = r * r
@@ -70,41 +73,59 @@ def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate
     x_in = x.copy()
     keep(rnd(lin(rnd(so.scale_shift_act(x, scale, shift, so.ACT_NONE)), "in")), f"{n}.h0")
     h0 = B[f"{n}.h0"]
+    note("h0", h0)
     # self-attention
     tn = rnd(ln(h0, "ln1"))
+    note("tn1", tn)
     q = rnd(lin(tn, "q1"))
+    note("q1", q)
     kv = np.concatenate([rnd(lin(tn, "k1")), rnd(lin(tn, "v1"))], axis=2)
     keep(kv, f"{n}.kv")
     kv = B[f"{n}.kv"]
+    note("kv", kv)
     a = rnd(so.attention(q.reshape(T, heads, d), kv[:, :, :C].reshape(T, heads, d),
                          kv[:, :, C:].reshape(T, heads, d), 1.0 / np.sqrt(d))).reshape(r, r, C)
+    note("a1", a)
     keep(rnd(rnd(lin(a, "o1")) + h0), f"{n}.h1")
     h1 = B[f"{n}.h1"]
+    note("h1", h1)
     # cross-attention over the text embeddings
     ctx = _p64(P, "ctx")[None]                       # [1, n_ctx, d_ctx] as a one-row image
     kc, vc = rnd(lin(ctx, "k2"))[0], rnd(lin(ctx, "v2"))[0]
+    note("kc", np.concatenate([kc, vc], axis=1))
     tn = rnd(ln(h1, "ln2"))
+    note("tn2", tn)
     q = rnd(lin(tn, "q2"))
+    note("q2", q)
     nc = kc.shape[0]
     a = rnd(so.attention(q.reshape(T, heads, d), kc.reshape(nc, heads, d), vc.reshape(nc, heads, d),
                          1.0 / np.sqrt(d))).reshape(r, r, C)
+    note("a2", a)
     keep(rnd(rnd(lin(a, "o2")) + h1), f"{n}.h2")
     h2 = B[f"{n}.h2"]
+    note("h2", h2)
     # gated-GELU feed-forward
     tn = rnd(ln(h2, "ln3"))
+    note("tn3", tn)
     u = rnd(lin(tn, "ff1"))
     gg = rnd(so.geglu(u))
+    note("gg", gg)
     keep(rnd(rnd(lin(gg, "ff2")) + h2), f"{n}.h3")
     h3 = B[f"{n}.h3"]
+    note("h3", h3)
     y = rnd(rnd(lin(h3, "out")) + x_in)
     yv = _view(B, op["y"])
     yv[...] = so.select_blocks(y, yv, blocks, b, b)
+    note("y", B[op["y"][0]])
 
 
 def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float = 1e-5, block: int = 16,
-              cache=None, stats=None, mask=None, dilate: int = 1, min_sparse_res: int = 64):
+              cache=None, stats=None, mask=None, dilate: int = 1, min_sparse_res: int = 64, trace=None):
     """One forward pass.  cache is None: dense pass on the original image, returns (buffers, stats).
-    Otherwise: the edit pass over copies of the cached buffers, returns (buffers, blocks_per_op)."""
+    Otherwise: the edit pass over copies of the cached buffers, returns (buffers, blocks_per_op).
+    trace (a list, optional) receives one (op name, {tensor name: copy}) entry per operation, in order:
+    "y" = the whole buffer the operation wrote, as it stands right after it ("short" = the full output
+    of a shortcut branch, which is kept in no buffer), plus the inner tensors of an attention block."""
     rnd = lambda a: so.round_storage(a, storage)
     dense = cache is None
     B = {n: np.zeros(s) for n, s in bufs.items()} if dense else {n: a.copy() for n, a in cache.items()}
@@ -134,6 +155,8 @@ def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float
                                    storage=storage))
             if not op["scatter"]:
                 short[n] = y          # shortcut branch: added by the consumer on its blocks
+                if trace is not None:
+                    trace.append((n, {"short": y.copy()}))
                 continue
             if op["shortcut"] is not None:
                 y = rnd(y + short[op["shortcut"]])
@@ -149,9 +172,14 @@ def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float
                                       1 if k == 1 else pad)
             used_blocks[n] = blocks
             yv[...] = so.select_blocks(y, yv, blocks, b, b)
+            if trace is not None:
+                trace.append((n, {"y": B[op["y"][0]].copy()}))
         elif op["kind"] == "xfmr":
+            rec = {} if trace is not None else None
             _transformer_block(op, B, P, x, rnd, dense, stats_out, used_blocks, mask, dilate, block,
-                               min_sparse_res, groups, eps)
+                               min_sparse_res, groups, eps, rec)
+            if trace is not None:
+                trace.append((n, rec))
         else:  # self-attention block: GN -> q, k, v (1x1) -> attention -> proj (1x1) -> + x
             C, heads = op["C"], op["heads"]
             d = C // heads
@@ -168,4 +196,7 @@ def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float
             y = rnd(y + x)
             assert dense or r_in < min_sparse_res, "attention is only wrapped at all-active resolutions here"
             _view(B, op["y"])[...] = y
+            used_blocks[n] = all_blocks(r_in, r_in, min(block, r_in))
+            if trace is not None:
+                trace.append((n, {"qkv": np.concatenate([q, kk, v], axis=2), "a": a.copy(), "y": B[op["y"][0]].copy()}))
     return (B, stats_out) if dense else (B, used_blocks)
