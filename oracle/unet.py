@@ -107,8 +107,8 @@ def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate
     # gated-GELU feed-forward
     tn = rnd(ln(h2, "ln3"))
     note("tn3", tn)
-    u = rnd(lin(tn, "ff1"))
-    gg = rnd(so.geglu(u))
+    # the first feed-forward layer and its gated GELU are one layer with one stored tensor
+    gg = rnd(so.geglu(lin(tn, "ff1")))
     note("gg", gg)
     keep(rnd(rnd(lin(gg, "ff2")) + h2), f"{n}.h3")
     h3 = B[f"{n}.h3"]
