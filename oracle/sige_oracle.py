@@ -291,11 +291,13 @@ def layer_norm(x, gamma=None, beta=None, eps: float = 1e-5) -> np.ndarray:
 def geglu(x) -> np.ndarray:
     """Gated GELU of a feed-forward layer: x[..., :C] * gelu(x[..., C:]) with the exact
     gelu(g) = g/2 * (1 + erf(g / sqrt 2))."""
-    from math import erf, sqrt
+    from math import sqrt
+
+    from scipy.special import erf          # the library's double-precision error function, element-wise
     x = _f64(x)
     C = x.shape[-1] // 2
     g = x[..., C:]
-    phi = 0.5 * (1.0 + np.vectorize(erf)(g / sqrt(2.0)))
+    phi = 0.5 * (1.0 + erf(g / sqrt(2.0)))
     return x[..., :C] * g * phi
 
 
