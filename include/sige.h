@@ -11,7 +11,8 @@
  *    and base pointers 16-byte aligned unless a function says otherwise.
  *  - ALL pointers are DEVICE pointers owned by the caller, except `sige_geom*`
  *    (host) and where marked host.  The library allocates nothing, keeps no
- *    state between calls and only enqueues work on the HIP stream passed as
+ *    state between calls (but for the overrides of sige_set_knob, which tests and tuning
+ *    runs use) and only enqueues work on the HIP stream passed as
  *    `void* stream` (a hipStream_t; NULL = the default stream).  No call
  *    synchronises.
  *  - Return value: SIGE_OK or an error code; argument errors are detected on the
@@ -185,6 +186,24 @@ int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin,
 size_t sige_conv_workspace_bytes(sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
                                  int32_t max_blocks);
 
+/* Which kernel a convolution call would run (host only, nothing is enqueued): for tests that must
+ * know which code path they cover and for tuning.  n_blocks = the number of blocks the launch is
+ * sized for; staged_math != 0 when Scale+Shift or an activation is applied on the way into LDS;
+ * up as in sige_fused_conv; workspace_bytes as the call would get (0 = none).
+ *   kernel             0 = tiled implicit GEMM, 1 = the 1x1 kernel for few rows
+ *   shape              tiled: 0 = 128x128, 1 = 128x64, 2 = 64x64, 3 = 64x32 with four waves splitting K,
+ *                      4 = 64x32 and 5 = 32x32 with eight waves splitting K; few rows: 1 = 64x32, 2 = 64x64,
+ *                      3 = 32x32
+ *   patch_m, patch_n   output rows (pixels) x channels per workgroup
+ *   k_steps_per_chunk  MFMA K steps per staged channel chunk (tiled kernel)
+ *   ksplit             workgroups sharing one output patch along K (> 1: a second kernel adds them)
+ *   workgroups, threads, lds_bytes (dynamic + static) of the launch                              */
+typedef struct {
+    int32_t kernel, shape, patch_m, patch_n, k_steps_per_chunk, ksplit, workgroups, threads, lds_bytes;
+} sige_conv_plan_info;
+int sige_conv_plan(sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout, int32_t n_blocks,
+                   int32_t staged_math, int32_t up, size_t workspace_bytes, sige_conv_plan_info* info);
+
 /* Fig. "pipeline" (b) Scatter: y holds the cached F_l(A_orig) on entry and is updated
  * in place; for every active block and every in-image pixel of it
  *   y[y0+i][x0+j][o] = out_tiles[n][i][j][o] (+ residual_tiles[n][i][j][o])
@@ -204,7 +223,8 @@ int sige_scatter(const void* out_tiles, sige_dtype dt, const sige_geom* g, int32
  * rows 16j..16j+7 = value channels 8j..8j+7, rows 16j+8..16j+15 = their gates; bias likewise,
  * fp32 [2*Cout] or NULL), and
  *   out[n][py][px][c] = value_c * gelu(gate_c),  gelu(g) = g/2 * (1 + erf(g / sqrt 2)),
- * computed from the fp32 sums (the 2*Cout-channel intermediate is never stored or rounded).
+ * computed from the fp32 sums: the layer has ONE stored tensor, this product, rounded once (the
+ * 2*Cout-channel intermediate is never stored or rounded).
  * out_tiles: [max_blocks][block_h][block_w][Cout].  Cout must be a multiple of 8.  Never splits K
  * over workgroups (no workspace).  Other arguments as in sige_conv.                        */
 int sige_conv_geglu(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
@@ -291,8 +311,11 @@ int sige_fused_conv_pair(const sige_fused_conv_call* first, const sige_fused_con
  *   o[i][h][:] = sum_t softmax_t(scale * q[i][h][:] . k[t][h][:]) * v[t][h][:].
  * q, o: [Nq][heads][d] with row strides q_ld / o_ld elements; k, v: [T][heads][d]
  * with row stride kv_ld (a row = one token, heads*d contiguous elements inside it).
- * dt is f16 or bf16; d % 8 == 0, d <= 256; strides multiples of 8 elements.
- * Streaming (online) softmax in fp32 on the matrix cores.  Nq is a host value;
+ * Any dt; d * size and the strides * size multiples of 16 bytes, d <= 256.
+ * Streaming (online) softmax in fp32 on the matrix cores.  fp16 feeds the probabilities
+ * to the second product rounded to fp16, bf16 as the sum of two bf16 numbers (16 bits), and
+ * both normalise by the sum of exactly those values; single precision (the precision of
+ * the paper's experiments, Sec. 4.1) rounds nothing in between.  Nq is a host value;
  * Nq == 0 enqueues nothing.
  * workspace: optional device scratch for splitting the keys over several workgroups
  * when Nq is small; sige_sparse_attn_workspace_bytes gives the size that allows it.
@@ -375,6 +398,30 @@ int sige_gn_stats(const void* x, sige_dtype dt, int32_t H, int32_t W, int32_t C,
 
 const char* sige_last_error(void);
 int sige_version(void);
+
+/* Overrides of the launch heuristics, for tests that must reach a given kernel shape and for
+ * tuning runs.  This is the only state the library keeps: process-wide, read on the host when a
+ * call is planned; set them while no other thread is inside a call.  value < 0 restores the
+ * automatic choice (the default of every knob).  An override that a call cannot honour (a shape
+ * that does not fit the layer) is ignored or ends in SIGE_ERR_UNSUPPORTED, never in a wrong
+ * result.
+ *   CONV_CFG           workgroup shape of the tiled convolution: 0 = 128x128, 1 = 128x64, 2 = 64x64,
+ *                      3 = 64x32 with four waves splitting K; with CONV_KC >= 16 also 4 (eight waves)
+ *   CONV_KC            K steps per staged channel chunk (1, 3, 4, 8; 16, 20, 32, 40 = whole-Cin shapes)
+ *   CONV_SPLIT         number of workgroups that share an output patch along K (needs a workspace)
+ *   CONV_HALF          most workgroups up to which the eight-wave shape takes 32-row patches
+ *   CONV_SPLIT_WGS     workgroups a K split over workgroups aims for
+ *   CONV_POINTWISE     the few-row 1x1 kernel: 0 = never, 1 = 64x32, 2 = 64x64, 3 = 32x32 patches
+ *   CONV_POINTWISE_W4  its four-wave variant for 64x64 patches: 0 = never, 1 = always
+ *   CONV_PAIR_WGS      most workgroups up to which sige_fused_conv_pair shares one launch
+ *   ATTN_WGS           workgroups the key split of sige_sparse_attn aims for                    */
+typedef enum {
+    SIGE_KNOB_CONV_CFG = 0, SIGE_KNOB_CONV_KC = 1, SIGE_KNOB_CONV_SPLIT = 2, SIGE_KNOB_CONV_HALF = 3,
+    SIGE_KNOB_CONV_SPLIT_WGS = 4, SIGE_KNOB_CONV_POINTWISE = 5, SIGE_KNOB_CONV_POINTWISE_W4 = 6,
+    SIGE_KNOB_CONV_PAIR_WGS = 7, SIGE_KNOB_ATTN_WGS = 8, SIGE_KNOB_COUNT = 9
+} sige_knob;
+int sige_set_knob(sige_knob knob, int32_t value);
+int32_t sige_get_knob(sige_knob knob);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,11 @@ STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3:
 
 EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_fused_conv_pair", "sige_sparse_attn", "sige_sparse_attn_blocks",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
-           "sige_gn_stats", "sige_last_error", "sige_version"]
+           "sige_gn_stats", "sige_last_error", "sige_version", "sige_set_knob", "sige_get_knob", "sige_conv_plan"]
+
+# sige_knob of the header
+KNOBS = {"CONV_CFG": 0, "CONV_KC": 1, "CONV_SPLIT": 2, "CONV_HALF": 3, "CONV_SPLIT_WGS": 4, "CONV_POINTWISE": 5,
+         "CONV_POINTWISE_W4": 6, "CONV_PAIR_WGS": 7, "ATTN_WGS": 8}
 
 
 class SigeError(RuntimeError):
@@ -55,6 +59,18 @@ class BlockListDesc(ctypes.Structure):
     """Mirror of sige_block_list."""
     _fields_ = [("g", Geom), ("indices", ctypes.c_void_p), ("max_blocks", ctypes.c_int32),
                 ("count", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class ConvPlanInfo(ctypes.Structure):
+    """Mirror of sige_conv_plan_info."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("kernel", "shape", "patch_m", "patch_n", "k_steps_per_chunk", "ksplit", "workgroups", "threads",
+                 "lds_bytes")]
+
+    def __repr__(self):
+        kind = "few-row 1x1" if self.kernel else "tiled"
+        return (f"{kind} kernel, shape {self.shape} ({self.patch_m}x{self.patch_n}), {self.k_steps_per_chunk} K steps "
+                f"per chunk, ksplit {self.ksplit}, {self.workgroups} workgroups of {self.threads}, {self.lds_bytes} B LDS")
 
 
 def geom(H_in, W_in, block, k=3, stride=1, pad=None) -> Geom:
@@ -106,6 +122,10 @@ def lib() -> ctypes.CDLL:
         L.sige_gather_token_norm.argtypes = [vp, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, f32, vp, vp]
         L.sige_geglu.argtypes = [vp, i32, i32, i32, vp, i32, i32, i32, vp, i32, vp]
         L.sige_gn_stats.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp]
+        L.sige_conv_plan.argtypes = [i32, gp, i32, i32, i32, i32, i32, sz, ctypes.POINTER(ConvPlanInfo)]
+        L.sige_set_knob.argtypes = [i32, i32]
+        L.sige_get_knob.argtypes = [i32]
+        L.sige_get_knob.restype = i32
         _lib = L
     return _lib
 
@@ -191,6 +211,14 @@ def _nbytes(t):
 
 def sige_conv_workspace_bytes(dtype, g: Geom, Cin, Cout, max_blocks) -> int:
     return int(lib().sige_conv_workspace_bytes(_DT[dtype], ctypes.byref(g), Cin, Cout, max_blocks))
+
+
+def sige_conv_plan(dtype, g: Geom, Cin, Cout, n_blocks, *, staged_math=False, up=0, workspace_bytes=0) -> ConvPlanInfo:
+    """Which kernel and launch shape a convolution call with these arguments would take (host only)."""
+    info = ConvPlanInfo()
+    _check(lib().sige_conv_plan(_DT[dtype], ctypes.byref(g), Cin, Cout, n_blocks, int(bool(staged_math)), up,
+                                workspace_bytes, ctypes.byref(info)))
+    return info
 
 
 def sige_conv(tiles, g: Geom, Cin, Cout, packed_weight, bias, count, out_tiles, *, n_blocks=-1,
@@ -408,3 +436,30 @@ def sige_gn_stats(x, groups, mean, var, *, gamma=None, beta=None, eps=1e-5, scal
 
 def sige_version() -> int:
     return int(lib().sige_version())
+
+
+def sige_set_knob(name: str, value: int) -> None:
+    """Overrides one launch heuristic (value < 0: automatic again); see sige_knob in the header."""
+    _check(lib().sige_set_knob(KNOBS[name], value))
+
+
+def sige_get_knob(name: str) -> int:
+    return int(lib().sige_get_knob(KNOBS[name]))
+
+
+class knobs:
+    """with api.knobs(CONV_CFG=3, CONV_KC=16): ... - overrides for the duration of the block."""
+
+    def __init__(self, **kv):
+        self.kv = kv
+
+    def __enter__(self):
+        self.prev = {k: sige_get_knob(k) for k in self.kv}
+        for k, v in self.kv.items():
+            sige_set_knob(k, -1 if v is None else int(v))
+        return self
+
+    def __exit__(self, *exc):
+        for k, v in self.prev.items():
+            sige_set_knob(k, v)
+        return False

@@ -4,6 +4,8 @@
 namespace sige {
 
 static thread_local char g_err[512] = "";
+int g_knobs[SIGE_KNOB_COUNT] = {-1, -1, -1, -1, -1, -1, -1, -1, -1};
+static_assert(SIGE_KNOB_COUNT == 9, "one initialiser per knob");
 
 int fail(int code, const char* fmt, ...)
 {
@@ -55,4 +57,17 @@ int check_blocks(const int32_t* count, int32_t max_blocks, int32_t n_blocks, con
 }  // namespace sige
 
 extern "C" const char* sige_last_error(void) { return sige::g_err; }
-extern "C" int sige_version(void) { return 1; }
+extern "C" int sige_version(void) { return 2; }
+
+extern "C" int sige_set_knob(sige_knob k, int32_t value)
+{
+    sige::clear_error();
+    SIGE_REQUIRE((int)k >= 0 && (int)k < SIGE_KNOB_COUNT, SIGE_ERR_INVALID_ARG, "sige_set_knob: unknown knob %d", (int)k);
+    sige::g_knobs[k] = value < 0 ? -1 : value;
+    return SIGE_OK;
+}
+
+extern "C" int32_t sige_get_knob(sige_knob k)
+{
+    return ((int)k >= 0 && (int)k < SIGE_KNOB_COUNT) ? sige::g_knobs[k] : -1;
+}

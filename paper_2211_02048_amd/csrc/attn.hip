@@ -15,10 +15,12 @@
 // staged in LDS once per workgroup (4 waves = 128 queries); V is transposed on the
 // way in, with an XOR swizzle on 4-key groups to keep the 2-byte stores off the same
 // banks.  When few queries are active the key range is split over workgroups and a
-// second small kernel merges the partial (max, sum, O) triples.
+// second small kernel merges the partial (max, sum, O) triples.  Single precision has a kernel of
+// its own further down (attn_f32_kernel).
 #include "common.h"
 
-#include <stdlib.h>
+#include <algorithm>
+#include <type_traits>
 
 namespace sige {
 
@@ -62,7 +64,7 @@ struct AttnArgs {
 
 // 32-key tiles per chunk, by head size (DT = 32-wide tiles over d)
 constexpr int key_tiles(int DT) { return DT <= 3 ? 2 : 1; }
-static int keys_per_chunk(int d) { return 32 * key_tiles((d + 31) / 32); }
+static int keys_per_chunk(int d, sige_dtype dt) { return dt == SIGE_F32 ? 32 : 32 * key_tiles((d + 31) / 32); }
 
 template <typename T, int DT>
 __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
@@ -200,29 +202,42 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float alpha = exp2f(m_run - mx);  // first chunk: exp2(-inf) = 0
-        float lsum = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sacc[kt][r] = exp2f(sacc[kt][r] - mx);
-                lsum += sacc[kt][r];
-            }
-        l_run = l_run * alpha + lsum;
+            for (int r = 0; r < 16; ++r) sacc[kt][r] = exp2f(sacc[kt][r] - mx);
         m_run = mx;
 #pragma unroll
         for (int nt = 0; nt < DT; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[nt][r] *= alpha;
 
-        // O^T += V^T P^T, two steps of 16 keys per tile; step s uses registers 8s..8s+7
+        // O^T += V^T P^T, two steps of 16 keys per tile; step s uses registers 8s..8s+7.
+        // The probabilities enter this product in the storage type, and the row's denominator sums
+        // those same rounded values, so that numerator and denominator carry the same rounding (a row
+        // dominated by one key returns that key's value row exactly).  fp16 keeps 11 bits of a
+        // probability; bf16 keeps 8, too few for the stated tolerance on rows spread over many keys,
+        // so there a probability goes in as the sum of two bf16 numbers (the rounded value and the
+        // rounded remainder, 16 bits together) and the same V^T fragments are multiplied twice.
+        constexpr bool TWO = std::is_same<T, bf16>::value;
+        float lsum = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                union { uint4 u; T h[8]; } pf;
+                union { uint4 u; T h[8]; } pf, pr;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf.h[e] = from_f32<T>(sacc[kt][8 * s + e]);
+                for (int e = 0; e < 8; ++e) {
+                    const float p = sacc[kt][8 * s + e];
+                    pf.h[e] = from_f32<T>(p);
+                    const float ph = to_f32(pf.h[e]);
+                    if constexpr (TWO) {
+                        pr.h[e] = from_f32<T>(p - ph);
+                        lsum += ph + to_f32(pr.h[e]);
+                    } else {
+                        lsum += ph;
+                    }
+                }
                 uint2 lo[DT], hi[DT];                        // likewise: the V^T fragments of all tiles, then the MFMAs
 #pragma unroll
                 for (int nt = 0; nt < DT; ++nt) {
@@ -233,9 +248,13 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
                     hi[nt] = *(const uint2*)(vt + row * VT_STRIDE + g_hi * 8);
                 }
 #pragma unroll
-                for (int nt = 0; nt < DT; ++nt)
-                    Mma16<T>::run(make_uint4(lo[nt].x, lo[nt].y, hi[nt].x, hi[nt].y), pf.u, oacc[nt]);
+                for (int nt = 0; nt < DT; ++nt) {
+                    const uint4 vf = make_uint4(lo[nt].x, lo[nt].y, hi[nt].x, hi[nt].y);
+                    Mma16<T>::run(vf, pf.u, oacc[nt]);
+                    if constexpr (TWO) Mma16<T>::run(vf, pr.u, oacc[nt]);
+                }
             }
+        l_run = l_run * alpha + lsum;
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -253,6 +272,181 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
                     for (int e = 0; e < 4; ++e) x.h[e] = from_f32<T>(oacc[nt][4 * rq + e] * inv);
                     *(uint2*)((char*)a.o + ((long)qi * a.o_ld + head * d + dd) * 2) = x.u;
                 }
+            }
+    } else {
+        float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 2);
+        if (half == 0) { w[d] = m_run; w[d + 1] = l_tot; }
+#pragma unroll
+        for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dd = nt * 32 + 8 * rq + 4 * half;
+                if (dd < d) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[dd + e] = oacc[nt][4 * rq + e];
+                }
+            }
+    }
+}
+
+// Single precision (the precision the paper's experiments run in, Sec. 4.1 "Implementation details"):
+// the same transposed products on v_mfma_f32_32x32x2_f32, whose operands are one value per lane, so
+// nothing is rounded between the two products and V needs no transpose (a lane picks V[key][d]
+// itself).  A workgroup of NW waves holds its 32 * NW query rows in LDS (row stride d + 1 words, so
+// that the lanes of a half fall on different banks) and stages 32 keys per chunk.
+template <int DT, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_f32_kernel(AttnArgs a)
+{
+    constexpr int NT = 64 * NW;
+    constexpr int KCH = 32;
+    constexpr int VS = DT * 32 + 4;                // words per staged V row (columns d .. DT*32 stay zero)
+    constexpr int NV = (8 * DT * 32 + NT - 1) / NT; // 16-byte vectors of K (and of V) a thread stages per chunk, at most
+    extern __shared__ uint4 lds4[];
+    float* lds = reinterpret_cast<float*>(lds4);
+    const int d = a.d;
+    const int rs = d + 1;                          // words per staged Q or K row
+    float* qsm = lds;                              // [NW*32][rs]
+    float* ksm = qsm + NW * 32 * rs;               // [KCH][rs]
+    float* vsm = ksm + KCH * rs;                   // [KCH][VS]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int head = blockIdx.y;
+    const int q0 = blockIdx.x * (NW * 32);
+    const int qi = q0 + wave * 32 + l32;
+    const bool q_ok = qi < a.Nq;
+    const int dvec = d / 4;
+
+    const int chunks_total = (a.T + KCH - 1) / KCH;
+    const int c_begin = blockIdx.z * a.chunks_per_split;
+    const int c_end = min(c_begin + a.chunks_per_split, chunks_total);
+
+    // the workgroup's query rows (rows past Nq are zero)
+    for (int j = tid; j < NW * 32 * dvec; j += NT) {
+        const int row = j / dvec, dv = j - row * dvec;
+        const int qq = q0 + row;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (qq < a.Nq) {
+            long qrow = qq;
+            if (a.q_blocks != nullptr) {
+                const int b = qq / a.q_tpb, p = qq - b * a.q_tpb;
+                const int py = p / a.q_bw, px = p - py * a.q_bw;
+                const int y0 = a.q_blocks[2 * b], x0 = a.q_blocks[2 * b + 1];
+                qrow = (long)min(max(y0 + py, 0), a.q_H - 1) * a.q_W + min(max(x0 + px, 0), a.q_W - 1);
+            }
+            v = *(const float4*)((const float*)a.q + qrow * a.q_ld + head * d + dv * 4);
+        }
+        float* dst = qsm + row * rs + dv * 4;
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+    for (int j = tid; j < KCH * (VS - d); j += NT) {
+        const int key = j / (VS - d), c = j - key * (VS - d);
+        vsm[key * VS + d + c] = 0.0f;
+    }
+
+    int skey[NV], sdv[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int j = tid + u * NT;
+        skey[u] = j < KCH * dvec ? j / dvec : -1;
+        sdv[u] = j < KCH * dvec ? j - skey[u] * dvec : 0;
+    }
+    float4 kreg[NV], vreg[NV];
+    auto fetch = [&](int c) {
+        const int t0 = c * KCH;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            if (skey[u] < 0) continue;
+            const long off = (long)min(t0 + skey[u], a.T - 1) * a.kv_ld + head * d + sdv[u] * 4;
+            kreg[u] = *(const float4*)((const float*)a.k + off);
+            vreg[u] = *(const float4*)((const float*)a.v + off);
+        }
+    };
+    auto commit = [&](int c) {
+        const int t0 = c * KCH;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            if (skey[u] < 0) continue;
+            const bool in = t0 + skey[u] < a.T;
+            const float4 kv = in ? kreg[u] : make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 vv = in ? vreg[u] : make_float4(0.f, 0.f, 0.f, 0.f);
+            float* kd = ksm + skey[u] * rs + sdv[u] * 4;
+            kd[0] = kv.x; kd[1] = kv.y; kd[2] = kv.z; kd[3] = kv.w;
+            *(float4*)(vsm + skey[u] * VS + sdv[u] * 4) = vv;
+        }
+    };
+
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[nt][r] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+    const float* qrow_s = qsm + (wave * 32 + l32) * rs + half;
+    const float* krow_s = ksm + l32 * rs + half;
+
+    if (c_begin < c_end) fetch(c_begin);
+    for (int c = c_begin; c < c_end; ++c) {
+        const int t0 = c * KCH;
+        __syncthreads();  // previous chunk fully consumed (and, the first time, the query rows written)
+        commit(c);
+        __syncthreads();
+        if (c + 1 < c_end) fetch(c + 1);
+
+        // S^T tile: rows = the chunk's 32 keys, cols = this wave's 32 queries; two values of d per MFMA
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
+        for (int j = 0; j < d; j += 4) {              // d is a multiple of 4
+            const float k0 = krow_s[j], q0v = qrow_s[j], k1 = krow_s[j + 2], q1v = qrow_s[j + 2];
+            sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(k0, q0v, sacc, 0, 0, 0);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(k1, q1v, sacc, 0, 0, 0);
+        }
+        // online softmax; this lane holds keys 8*(r/4) + 4*half + r%4 of its query
+        float mx = m_run;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = t0 + 8 * (r >> 2) + 4 * half + (r & 3);
+            sacc[r] = key < a.T ? sacc[r] * a.scale_log2e : -INFINITY;
+            mx = fmaxf(mx, sacc[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float alpha = exp2f(m_run - mx);
+        float lsum = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            sacc[r] = exp2f(sacc[r] - mx);
+            lsum += sacc[r];
+        }
+        l_run = l_run * alpha + lsum;
+        m_run = mx;
+#pragma unroll
+        for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[nt][r] *= alpha;
+        // O^T += V^T P^T: register r of the two lane halves is one pair of keys
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float* vrow = vsm + (8 * (r >> 2) + 4 * half + (r & 3)) * VS + l32;
+#pragma unroll
+            for (int nt = 0; nt < DT; ++nt)
+                oacc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[nt * 32], sacc[r], oacc[nt], 0, 0, 0);
+        }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (!q_ok) return;
+    if (a.splits == 1) {
+        const float inv = 1.0f / l_tot;
+#pragma unroll
+        for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dd = nt * 32 + 8 * rq + 4 * half;
+                if (dd < d)
+                    *(float4*)((float*)a.o + (long)qi * a.o_ld + head * d + dd) =
+                        make_float4(oacc[nt][4 * rq] * inv, oacc[nt][4 * rq + 1] * inv, oacc[nt][4 * rq + 2] * inv,
+                                    oacc[nt][4 * rq + 3] * inv);
             }
     } else {
         float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 2);
@@ -319,13 +513,13 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
 // a staging round trip, so few queries are spread over about two workgroups per compute unit (more
 // splits cost the merge kernel more than they save: measured at 64 to 1280 queries), at least 2
 // chunks each.
-static int pick_splits(int Nq, int T, int heads, int d)
+static int pick_splits(int Nq, int T, int heads, int d, sige_dtype dt)
 {
-    const int KCH = keys_per_chunk(d);
+    const int KCH = keys_per_chunk(d, dt);
     const long base = (long)heads * ((Nq + 127) / 128);
     const int chunks = (T + KCH - 1) / KCH;
-    const char* target = getenv("SIGE_ATTN_WGS");           // tuning aid: workgroups to aim for
-    long want = ((target ? atoi(target) : 512) + base - 1) / base;
+    const int target = knob(SIGE_KNOB_ATTN_WGS);            // workgroups to aim for
+    long want = ((target >= 0 ? target : 512) + base - 1) / base;
     long cap = chunks / 2;
     if (want > cap) want = cap;
     if (want > 64) want = 64;
@@ -371,6 +565,42 @@ static int launch_attn(const AttnArgs& a, hipStream_t st)
     }
 }
 
+template <int DT, int NW>
+static int launch_attn_f32_as(const AttnArgs& a, hipStream_t st)
+{
+    const size_t lds = ((size_t)(NW * 32 + 32) * (a.d + 1) + 32 * (DT * 32 + 4)) * sizeof(float);
+    dim3 grid((a.Nq + NW * 32 - 1) / (NW * 32), a.heads, a.splits);
+    auto kern = attn_f32_kernel<DT, NW>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_sparse_attn: cannot reserve %zu bytes of LDS: %s", lds,
+                     hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, st, a);
+    SIGE_LAUNCH_CHECK("sige_sparse_attn");
+    if (a.splits > 1) {
+        const long n = (long)a.Nq * a.heads * a.d;
+        hipLaunchKernelGGL((attn_merge_kernel<float>), dim3((int)((n + 255) / 256)), dim3(256), 0, st, a);
+        SIGE_LAUNCH_CHECK("sige_sparse_attn(merge)");
+    }
+    return SIGE_OK;
+}
+
+// Four waves (128 queries) per workgroup while their rows, the key chunk and the value chunk fit
+// the LDS of a compute unit, two beyond (heads wider than 128).
+static int launch_attn_f32(const AttnArgs& a, hipStream_t st)
+{
+    switch ((a.d + 31) / 32) {
+    case 1: return launch_attn_f32_as<1, 4>(a, st);
+    case 2: return launch_attn_f32_as<2, 4>(a, st);
+    case 3: return launch_attn_f32_as<3, 4>(a, st);
+    case 4: return launch_attn_f32_as<4, 4>(a, st);
+    case 5: return launch_attn_f32_as<5, 2>(a, st);
+    case 6: return launch_attn_f32_as<6, 2>(a, st);
+    default: return launch_attn_f32_as<8, 2>(a, st);
+    }
+}
+
 }  // namespace sige
 
 using namespace sige;
@@ -378,7 +608,8 @@ using namespace sige;
 extern "C" size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_t heads, int32_t d)
 {
     if (Nq <= 0 || T <= 0 || heads <= 0 || d <= 0) return 0;
-    const int splits = pick_splits(Nq, T, heads, d);
+    // the larger of what the half-precision and the single-precision kernels would use
+    const int splits = std::max(pick_splits(Nq, T, heads, d, SIGE_F16), pick_splits(Nq, T, heads, d, SIGE_F32));
     if (splits <= 1) return 0;
     return (size_t)splits * heads * Nq * (d + 2) * sizeof(float);
 }
@@ -389,24 +620,25 @@ static int attn_entry(const char* who, AttnArgs& a, const void* q, int32_t q_ld,
 {
     SIGE_REQUIRE(Nq >= 0 && T > 0 && heads > 0 && d > 0, SIGE_ERR_INVALID_ARG,
                  "%s: need Nq >= 0, T > 0, heads > 0, d > 0", who);
-    SIGE_REQUIRE(dt == SIGE_F16 || dt == SIGE_BF16, SIGE_ERR_UNSUPPORTED, "%s: dtype must be f16 or bf16", who);
-    SIGE_REQUIRE(d % 8 == 0 && d <= 256, SIGE_ERR_UNSUPPORTED, "%s: d must be a multiple of 8 and <= 256", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    const int vw = dt == SIGE_F32 ? 4 : 8;                  // elements per 16-byte vector
+    SIGE_REQUIRE(d % vw == 0 && d <= 256, SIGE_ERR_UNSUPPORTED, "%s: d must be a multiple of %d and <= 256", who, vw);
     SIGE_REQUIRE(heads <= 65535, SIGE_ERR_UNSUPPORTED, "%s: too many heads", who);
     if (Nq == 0) return SIGE_OK;
     SIGE_REQUIRE(q && k && v && o, SIGE_ERR_INVALID_ARG, "%s: q, k, v and o are required", who);
     SIGE_REQUIRE(q_ld >= heads * d && kv_ld >= heads * d && o_ld >= heads * d, SIGE_ERR_INVALID_ARG,
                  "%s: row strides must be >= heads*d", who);
-    SIGE_REQUIRE(q_ld % 8 == 0 && kv_ld % 8 == 0 && o_ld % 8 == 0, SIGE_ERR_UNSUPPORTED,
-                 "%s: row strides must be multiples of 8 elements", who);
+    SIGE_REQUIRE(q_ld % vw == 0 && kv_ld % vw == 0 && o_ld % vw == 0, SIGE_ERR_UNSUPPORTED,
+                 "%s: row strides must be multiples of %d elements", who, vw);
     SIGE_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(o), SIGE_ERR_UNSUPPORTED,
                  "%s: pointers must be 16-byte aligned", who);
     a.q = q; a.k = k; a.v = v; a.o = o; a.ws = (float*)workspace;
     a.q_ld = q_ld; a.kv_ld = kv_ld; a.o_ld = o_ld;
     a.Nq = Nq; a.T = T; a.heads = heads; a.d = d;
     a.scale_log2e = scale * 1.4426950408889634f;
-    const int KCH = keys_per_chunk(d);
+    const int KCH = keys_per_chunk(d, dt);
     const int chunks = (T + KCH - 1) / KCH;
-    int splits = pick_splits(Nq, T, heads, d);
+    int splits = pick_splits(Nq, T, heads, d, dt);
     if (splits > 1 && (workspace == nullptr ||
                        workspace_bytes < (size_t)splits * heads * Nq * (d + 2) * sizeof(float) ||
                        (reinterpret_cast<uintptr_t>(workspace) & 3u)))
@@ -414,6 +646,7 @@ static int attn_entry(const char* who, AttnArgs& a, const void* q, int32_t q_ld,
     a.chunks_per_split = (chunks + splits - 1) / splits;
     a.splits = (chunks + a.chunks_per_split - 1) / a.chunks_per_split;
     hipStream_t st = (hipStream_t)stream;
+    if (dt == SIGE_F32) return launch_attn_f32(a, st);
     return dt == SIGE_F16 ? launch_attn<f16>(a, st) : launch_attn<bf16>(a, st);
 }
 

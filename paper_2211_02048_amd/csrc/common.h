@@ -29,6 +29,11 @@ void clear_error();
             return sige::fail(SIGE_ERR_HIP, "%s: launch failed: %s", name, hipGetErrorString(e_)); \
     } while (0)
 
+// Overrides of the launch heuristics set through sige_set_knob (-1 = automatic); process-wide,
+// read on the host when a call is planned.
+extern int g_knobs[SIGE_KNOB_COUNT];
+inline int knob(sige_knob k) { return g_knobs[k]; }
+
 inline size_t dtype_size(sige_dtype dt) { return dt == SIGE_F32 ? 4 : 2; }
 inline bool dtype_ok(sige_dtype dt) { return dt == SIGE_F32 || dt == SIGE_F16 || dt == SIGE_BF16; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -24,8 +24,6 @@
 
 #include "common.h"
 
-#include <stdlib.h>
-
 #include <algorithm>
 
 namespace sige {
@@ -254,7 +252,8 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
 
 // One run of a gated-GELU output: v the N values, gt their gates (bias included in both), o the
 // convolution channel of v[0] (o % 16 < 8): out[row][(o / 16) * 8 + o % 16 + i] = v[i] * gelu(gt[i]),
-// gelu(g) = g/2 * (1 + erf(g / sqrt 2)).
+// gelu(g) = g/2 * (1 + erf(g / sqrt 2)), from the fp32 sums: the layer's one stored tensor is this
+// product, rounded once.
 template <typename T>
 __device__ __forceinline__ void emit_glu(const ConvArgs& a, long row, int o, float (&v)[Vec16<T>::N],
                                          const float (&gt)[Vec16<T>::N])
@@ -1072,19 +1071,23 @@ static const CfgShape kCfg[kNumCfg + 2] = {{128, 128, 1}, {128, 64, 1}, {64, 64,
 static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, size_t s, int kstep,
                       int nblocks, size_t partial_elems, bool staged_math, ConvPlan* best)
 {
-    const char* force = getenv("SIGE_CONV_CFG");
-    const char* force_kc = getenv("SIGE_CONV_KC");   // tuning aids: fix the shape / the K steps per chunk
-    const bool force_whole = force && atoi(force) >= 3 && force_kc && atoi(force_kc) >= 16;
+    // overrides for tests and tuning runs (sige_set_knob; -1 = automatic): the shape / the K steps per chunk
+    const int force_cfg = knob(SIGE_KNOB_CONV_CFG), force_kc_v = knob(SIGE_KNOB_CONV_KC);
+    const bool force = force_cfg >= 0, force_kc = force_kc_v >= 0;
+    const bool force_whole = force && force_cfg >= 3 && force_kc && force_kc_v >= 16;
     double best_score = -1.0;
     auto lds_bytes = [&](int cfg, long npix, int kc) {
         size_t lds = (size_t)npix * (kc * kstep * s + 16);
         return std::max(lds, (size_t)kCfg[cfg].WK * kCfg[cfg].M * (kCfg[cfg].N + 4) * sizeof(float));   // the epilogue's staging
     };
+    // a compute unit has 160 KiB of LDS: one workgroup where a single chunk is all there is to overlap,
+    // two otherwise; the kernel's own static array (the block origins) counts too
+    constexpr size_t kStaticLds = 2 * MAX_G * sizeof(int);
     auto lds_fits = [&](int cfg, size_t lds, int kc) {
-        return lds <= (kc == 1 || (kc == 4 && kCfg[cfg].WK == 4) ? 160u : 80u) * 1024u;
+        return lds + kStaticLds <= (kc == 1 || (kc == 4 && kCfg[cfg].WK == 4) ? 160u : 80u) * 1024u;
     };
     for (int cfg = 0; cfg < kNumCfg; ++cfg) {
-        if (force && !force_whole && atoi(force) != cfg) continue;
+        if (force && !force_whole && force_cfg != cfg) continue;
         if (g->k != 1 && g->k != 3 && cfg != 2) continue;   // only the plain 64x64 shape is built for other k
         const int M = kCfg[cfg].M, Nn = kCfg[cfg].N, WK = kCfg[cfg].WK;
         if (g->block_w > M) continue;
@@ -1103,7 +1106,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         // (3: the 48 channels of a label-map convolution in one chunk)
         p.kc = 0;
         for (int kc : {8, 4, 3, 1}) {
-            if (force_kc && !force_whole && atoi(force_kc) != kc) continue;
+            if (force_kc && !force_whole && force_kc_v != kc) continue;
             if (kc % WK || Cin % (kc * kstep)) continue;
             if (g->k != 1 && g->k != 3 && kc != 1) continue;
             const size_t lds = lds_bytes(cfg, npix, kc);
@@ -1129,7 +1132,8 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
     // shares than that cost more in the second kernel than they save in the first.  Smaller chunks
     // when that is what it takes to reach 256 workgroups.
     ConvPlan& p = *best;
-    const char* force_split = getenv("SIGE_CONV_SPLIT");
+    const int force_split_v = knob(SIGE_KNOB_CONV_SPLIT);
+    const bool force_split = force_split_v >= 0;
     // Few workgroups and a long K, nothing to compute while staging (no Scale+Shift, no activation):
     // 64 x 32 patches whose waves split K, with the whole of Cin (or half of it) staged at once -
     // eight waves over 256, 512 or 640 channels, four over 320.  One kernel, no workspace; the waves'
@@ -1150,7 +1154,7 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         q.kc = 0;
         static const int cand[4][2] = {{4, 40}, {4, 32}, {4, 16}, {3, 20}};   // shape, K steps per chunk
         for (const auto& c : cand) {
-            if (force_whole && (atoi(force) != c[0] || atoi(force_kc) != c[1])) continue;
+            if (force_whole && (force_cfg != c[0] || force_kc_v != c[1])) continue;
             // at most two chunks: beyond that a workgroup streams so much weight by itself that the
             // cut over workgroups below, second kernel included, is faster
             if (Cin % (c[1] * kstep) || (!force_whole && Cin / (c[1] * kstep) > (c[1] == 40 ? 1 : 2))) continue;
@@ -1160,8 +1164,8 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         long wgs4 = (long)q.groups * q.bands * q.slabs;
         // at most 64 workgroups (a 512-channel layer at 8 x 8 has 16): patches of 32 rows instead of
         // 64, so that twice as many compute units stream the weight and share the MFMAs
-        const char* half_env = getenv("SIGE_CONV_HALF");     // tuning aid: most workgroups for which rows are halved
-        const long half_max = half_env ? atol(half_env) : 64;
+        const int half_knob = knob(SIGE_KNOB_CONV_HALF);     // most workgroups for which rows are halved
+        const long half_max = half_knob >= 0 ? half_knob : 64;
         if (q.kc && q.cfg == 4 && wgs4 <= half_max && pbfull >= 64 && g->block_w <= 32) {
             q.cfg = 5;
             q.G = 1;
@@ -1188,10 +1192,10 @@ static bool plan_conv(const sige_geom* g, int th, int tw, int Cin, int Cout, siz
         if (kc == 8 && wgs * (Cin / (8 * kstep)) < 256 && 4 % WK == 0 && !force_kc) kc = 4;
         const int nch = Cin / (kc * kstep);
         int S = 1;
-        const char* tw_env = getenv("SIGE_CONV_SPLIT_WGS");   // tuning aid
-        const long target = tw_env ? atol(tw_env) : 200;
+        const int tw_knob = knob(SIGE_KNOB_CONV_SPLIT_WGS);
+        const long target = tw_knob >= 0 ? tw_knob : 200;
         if (wgs <= 256 && nch >= 3 && Cin >= 20 * kstep) S = (int)std::min<long>(nch, (target + wgs - 1) / wgs);
-        if (force_split) S = std::min(atoi(force_split), nch);
+        if (force_split) S = std::min(force_split_v, nch);
         S = std::max(1, std::min(S, max_by_ws));
         if (S > 1) {
             if (kc != p.kc) {
@@ -1317,8 +1321,9 @@ extern "C" int sige_pack_weight(const void* w_oihw, sige_dtype dt, int32_t Cout,
 // the tiled kernel, which reads every weight once per 128 rows, is the better one).
 static int pointwise_tiles(const sige_geom* g, const ConvArgs& a, int ks, int nl)
 {
-    const char* force = getenv("SIGE_CONV_POINTWISE");      // tuning aid: 0 = never, 1 / 2 = that many tiles
-    if (force && atoi(force) == 0) return 0;
+    const int force_v = knob(SIGE_KNOB_CONV_POINTWISE);     // 0 = never, 1 / 2 / 3 = that patch
+    const bool force = force_v >= 0;
+    if (force && force_v == 0) return 0;
     if (g->k != 1 || g->stride != 1 || g->pad != 0 || a.up != 0 || a.scale != nullptr || a.act != SIGE_ACT_NONE)
         return 0;
     const int kcs = a.Cin / ks;
@@ -1326,7 +1331,7 @@ static int pointwise_tiles(const sige_geom* g, const ConvArgs& a, int ks, int nl
     const long rows = (long)nl * g->block_h * g->block_w;
     const long mt = (rows + 63) / 64, nt = (a.Cout + 31) / 32;
     if ((rows + 31) / 32 > 65535) return 0;
-    if (force) return std::min(std::max(atoi(force), 1), 3);
+    if (force) return std::min(std::max(force_v, 1), 3);
     // the smallest patch that still fits one workgroup per compute unit
     if ((rows + 31) / 32 * nt <= 256) return 3;
     if (mt * nt <= 256) return 1;
@@ -1357,8 +1362,8 @@ static int launch_pointwise(const ConvArgs& a, int nl, int tiles, hipStream_t st
         // more 64 x 64 patches than compute units: four waves per workgroup, so that two workgroups
         // share a compute unit and all of them run at once instead of in two rounds
         const long mt = ((long)nl * a.bh * a.bw + 63) / 64, nt2 = (a.Cout + 63) / 64;
-        const char* w4 = getenv("SIGE_CONV_POINTWISE_W4");     // tuning aid: 0 = never, 1 = always
-        const bool four = w4 ? atoi(w4) != 0 : mt * nt2 > 256;
+        const int w4 = knob(SIGE_KNOB_CONV_POINTWISE_W4);      // 0 = never, 1 = always
+        const bool four = w4 >= 0 ? w4 != 0 : mt * nt2 > 256;
         return four ? launch_pointwise_as<T, 4, 3, 2, 2>(a, nl, st) : launch_pointwise_as<T, 8, 3, 2, 2>(a, nl, st);
     }
     return launch_pointwise_as<T, 8, 4, 2, 1>(a, nl, st);
@@ -1447,6 +1452,55 @@ extern "C" size_t sige_conv_workspace_bytes(sige_dtype dt, const sige_geom* g, i
         else if ((long)p.groups * p.bands * p.slabs > 256) break;   // more blocks only add workgroups
     }
     return need;
+}
+
+extern "C" int sige_conv_plan(sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout, int32_t n_blocks,
+                              int32_t staged_math, int32_t up, size_t workspace_bytes, sige_conv_plan_info* info)
+{
+    clear_error();
+    const char* who = "sige_conv_plan";
+    int th, tw;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    SIGE_REQUIRE(info != nullptr, SIGE_ERR_INVALID_ARG, "%s: info is required", who);
+    SIGE_REQUIRE(dtype_ok(dt), SIGE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, (int)dt);
+    SIGE_REQUIRE(Cin > 0 && Cout > 0 && n_blocks > 0, SIGE_ERR_INVALID_ARG, "%s: Cin, Cout and n_blocks must be positive", who);
+    const int ks = dt == SIGE_F32 ? 8 : 16;
+    SIGE_REQUIRE(Cin % ks == 0, SIGE_ERR_UNSUPPORTED, "%s: Cin must be a multiple of %d for this dtype", who, ks);
+    ConvArgs a = {};
+    a.up = up;
+    a.act = staged_math ? SIGE_ACT_SILU : SIGE_ACT_NONE;
+    ConvPlan p;
+    int pointwise = 0;
+    // any 16-byte aligned non-null address stands for the workspace: nothing is dereferenced here
+    void* ws = workspace_bytes ? reinterpret_cast<void*>(uintptr_t(16)) : nullptr;
+    if (int rc = prepare_conv(who, dt, g, th, tw, Cin, Cout, n_blocks, n_blocks, n_blocks, a, ws, workspace_bytes, &p, &pointwise))
+        return rc;
+    *info = sige_conv_plan_info{};
+    if (pointwise) {
+        const long rows = (long)n_blocks * g->block_h * g->block_w;
+        const int BM = pointwise == 3 ? 32 : 64, BN = pointwise == 2 ? 64 : 32;
+        const long mt = (rows + BM - 1) / BM, nt = (Cout + BN - 1) / BN;
+        const bool four = pointwise == 2 && (knob(SIGE_KNOB_CONV_POINTWISE_W4) >= 0 ? knob(SIGE_KNOB_CONV_POINTWISE_W4) != 0
+                                                                                    : mt * nt > 256);
+        const int W = four ? 4 : 8;
+        info->kernel = 1;
+        info->shape = pointwise;
+        info->patch_m = BM; info->patch_n = BN;
+        info->threads = 64 * W;
+        info->ksplit = 1;
+        info->workgroups = (int32_t)(mt * nt);
+        info->lds_bytes = (int32_t)(std::max((size_t)W * BM * (BN + 4) * sizeof(float), (size_t)W * 2 * BM * 80) + 2 * BM * sizeof(int));
+        return SIGE_OK;
+    }
+    info->kernel = 0;
+    info->shape = p.cfg;
+    info->patch_m = kCfg[p.cfg].M; info->patch_n = kCfg[p.cfg].N;
+    info->k_steps_per_chunk = p.kc;
+    info->threads = kCfg[p.cfg].WK == 8 ? 512 : 256;
+    info->ksplit = p.ksplit;
+    info->workgroups = (int32_t)((long)p.slabs * p.bands * p.ksplit * p.groups);
+    info->lds_bytes = (int32_t)(p.lds + 2 * MAX_G * sizeof(int));
+    return SIGE_OK;
 }
 
 extern "C" int sige_conv(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
@@ -1658,8 +1712,8 @@ extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sig
     const long wgs_both = nl[0] > 0 && nl[1] > 0 && !pw[0] && !pw[1]
                               ? (long)p[0].groups * p[0].bands * p[0].slabs + (long)p[1].groups * p[1].bands * p[1].slabs
                               : 0;
-    const char* pair_env = getenv("SIGE_CONV_PAIR_WGS");     // tuning aid: most workgroups for which the calls share a launch
-    const long pair_max = pair_env ? atol(pair_env) : (1L << 30);
+    const int pair_knob = knob(SIGE_KNOB_CONV_PAIR_WGS);     // most workgroups for which the calls share a launch
+    const long pair_max = pair_knob >= 0 ? pair_knob : (1L << 30);
     const bool together = nl[0] > 0 && nl[1] > 0 && wgs_both <= pair_max && !pw[0] && !pw[1] && c[0]->dt == c[1]->dt && a[0].k == 3 &&
                           a[1].k == 1 && p[0].cfg == 3 && p[1].cfg == 3 && p[0].ksplit == 1 && p[1].ksplit == 1 &&
                           p[0].kc == p[1].kc && (p[0].kc == 8 || p[0].kc == 4);

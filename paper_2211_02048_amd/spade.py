@@ -40,6 +40,9 @@ class SigeSpade:
         self.ws = Workspace(device)
         self.lists, self.layers = {}, {}
         self.mask = torch.zeros(self.out_hw, dtype=torch.uint8, device=device)
+        # Optional observer for tests: hook(when, name, layer, tensors), when = "pre" before an operation's
+        # calls are issued and "post" after them; it may read and overwrite buffers (after synchronising).
+        self.hook = None
         for op in self.ops:
             n, (h, w) = op["name"], op["hw"]
             b = min(block, h)
@@ -130,6 +133,8 @@ class SigeSpade:
                 continue
             bl = L["list"][0 if (dense or not L["sparse"]) else 1]
             x = self.B[op["x"]]
+            if self.hook:
+                self.hook("pre", n, L, dict(dense=dense, blocks=bl))
             if op["kind"] == "up":
                 g1 = L["g1"]
                 nb, cap = bl.n_host, (bl.max_blocks if bl.n_host < 0 else max(bl.n_host, 1))
@@ -137,6 +142,8 @@ class SigeSpade:
                 api.sige_gather(x, g1, bl.indices, bl.count, t, n_blocks=nb, up=1, C=op["cin"], max_blocks=cap)
                 api.sige_scatter(t, g1, bl.indices, bl.count, self.B[op["y"]], n_blocks=nb, Cout=op["cin"],
                                  max_blocks=cap)
+                if self.hook:
+                    self.hook("post", n, L, dict(dense=dense, blocks=bl))
                 continue
             scale = shift = mod = None
             if op["spade"] is not None:
@@ -148,11 +155,15 @@ class SigeSpade:
             if not op["scatter"]:
                 short[n] = L["conv"].forward(x, None, bl, self.ws, scale=scale, shift=shift, act=act, mod=mod,
                                              scatter=False, tag="short")
+                if self.hook:
+                    self.hook("post", n, L, dict(dense=dense, blocks=bl, tiles=short[n]))
                 continue
             res_t = short.get(op["shortcut"]) if op["shortcut"] else None
             res_f = self.B[op["residual"]] if op["residual"] is not None else None
             L["conv"].forward(x, L.get("joint", self.B[op["y"]]), bl, self.ws, scale=scale, shift=shift, act=act,
                               mod=mod, residual_tiles=res_t, residual=res_f, tag="main", fused=True)
+            if self.hook:
+                self.hook("post", n, L, dict(dense=dense, blocks=bl))
         return self.B["out"]
 
     def precompute(self, seg):

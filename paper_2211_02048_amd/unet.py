@@ -43,6 +43,11 @@ class SigeUNet:
         self.lists = {}        # (H_in, k, stride) -> [all-active list, sparse list]
         self.layers = {}
         self.graph = None
+        # Optional observer for tests: hook(when, name, layer, tensors) is called with when = "pre" before
+        # an operation's calls are issued, "stage" after each call inside an attention block (tensors
+        # names what that call just wrote) and "post" after the operation's last call.  It may read and
+        # overwrite buffers (after synchronising); the orchestration itself never looks at what it does.
+        self.hook = None
         # True: one fused gather-conv-scatter call per convolution instead of three; "lowres": only
         # for the layers below min_sparse_res (all blocks active, few of them, many channels)
         self.fused = fused
@@ -206,6 +211,8 @@ class SigeUNet:
             op = L["op"]
             fused = self.fused is True or (self.fused == "lowres" and not L["sparse"])
             bl = L["list"][0 if (dense or not L["sparse"]) else 1]
+            if self.hook:
+                self.hook("pre", n, L, dict(dense=dense, blocks=bl))
             x = self.view(op["x"])
             xn = x                  # what the normalising layer gathers: x, or its activated copy
             scale = shift = None
@@ -226,6 +233,8 @@ class SigeUNet:
                 if not op["scatter"]:
                     shortcut_tiles[n] = L["conv"].forward(x, None, bl, self.ws, scatter=False, tag="short",
                                                           fused=fused)
+                    if self.hook:
+                        self.hook("post", n, L, dict(dense=dense, blocks=bl, tiles=shortcut_tiles[n]))
                     continue
                 res_t = shortcut_tiles.get(op["shortcut"]) if op["shortcut"] else None
                 res_f = self.view(op["residual"]) if op["residual"] is not None else None
@@ -243,29 +252,38 @@ class SigeUNet:
                     api.sige_fused_conv_pair(ca, cb)
                     shortcut_tiles[names[i + 1]] = tiles
                     paired.add(names[i + 1])
+                    if self.hook:
+                        self.hook("post", n, L, dict(dense=dense, blocks=bl))
+                        self.hook("post", names[i + 1], nxt, dict(dense=dense, blocks=bls, tiles=tiles))
                     continue
                 L["conv"].forward(xn, self.view(op["y"]), bl, self.ws, scale=scale, shift=shift, act=act,
                                   residual_tiles=res_t, residual=res_f, tag="main", fused=fused, act_outs=ao)
             elif op["kind"] == "xfmr":
-                self._transformer(L, x, xn, self.view(op["y"]), bl, dense, scale, shift, ao)
+                self._transformer(L, x, xn, self.view(op["y"]), bl, dense, scale, shift, ao, name=n)
             else:
                 C, heads = op["C"], op["heads"]
                 T = x.shape[0] * x.shape[1]
                 L["qkv"].forward(xn, L["qkv_buf"], bl, self.ws, scale=scale, shift=shift, tag="main",
                                  fused=fused)
+                if self.hook:
+                    self.hook("stage", n, L, dict(dense=dense, blocks=bl, qkv=L["qkv_buf"]))
                 qkv = L["qkv_buf"].view(T, 3 * C)
                 api.sige_sparse_attn(qkv[:, :C], qkv[:, C:2 * C], qkv[:, 2 * C:], L["att_buf"].view(T, C),
                                      1.0 / math.sqrt(C // heads), Nq=T, workspace=L["att_ws"], heads=heads,
                                      d=C // heads, q_ld=3 * C, kv_ld=3 * C, o_ld=C)
+                if self.hook:
+                    self.hook("stage", n, L, dict(dense=dense, blocks=bl, a=L["att_buf"]))
                 L["proj"].forward(L["att_buf"], self.view(op["y"]), bl, self.ws, residual=x, tag="main",
                                   fused=fused, act_outs=ao)
+            if self.hook:
+                self.hook("post", n, L, dict(dense=dense, blocks=bl))
         if dense:
             self._copies_valid = use_copies and fill_copies
         elif not use_copies:
             self._copies_valid = False          # a pass that does not maintain them leaves them stale
         return self.B["out"]
 
-    def _transformer(self, L, x, xn, y, bl, dense, scale, shift, act_outs=None):
+    def _transformer(self, L, x, xn, y, bl, dense, scale, shift, act_outs=None, name=None):
         """A transformer block on the tokens of the active blocks (Fig. "sige-attention"): gather,
         token-wise layers and 1x1 convolutions on the stacked tiles, keys and values scattered into
         their caches, attention for the gathered queries only, result scattered back with the
@@ -317,30 +335,47 @@ class SigeUNet:
             api.sige_conv_scatter(src, layer.g, idx, cnt, layer.Cin, layer.Cout, layer.packed, layer.bias, dst,
                                   n_blocks=nb, max_blocks=nb, residual=residual, workspace=split)
 
+        def seen(**tensors):      # a call has just written these (tiles: stacked rows of the active blocks)
+            if self.hook:
+                self.hook("stage", name, L, dict(dense=dense, blocks=bl, **tensors))
+
         if dense:   # keys and values of the text embeddings do not depend on the image
             one = torch.ones(1, dtype=torch.int32, device=self.device)
             kv2 = L["kv2"]
             api.sige_conv(L["ctx"].view(1, 1, -1, kv2.Cin), kv2.g, kv2.Cin, kv2.Cout, kv2.packed, kv2.bias, one,
                           L["kc"].view(1, 1, -1, 2 * C), n_blocks=1, max_blocks=1)
+            seen(kc=L["kc"])
         L["in"].forward(xn, L["h0"], bl, ws, scale=scale, shift=shift, fused=True)
+        seen(h0=L["h0"])
         # self-attention: only the active tokens' queries; their queries, keys and values go into the
         # cache first, in one convolution
         tn = normed(L["h0"], "ln1")
+        seen(tn1=tn)
         back(L["qkv1"], tn, L["qkv"])
+        seen(qkv=L["qkv"])
         qkv = L["qkv"].view(T, 3 * C)
         o = attend(None, qkv[:, C:2 * C], qkv[:, 2 * C:], T, 3 * C, q_full=qkv)
+        seen(a1=o)
         back(L["o1"], o, L["h1"], L["h0"])
+        seen(h1=L["h1"])
         # cross-attention over the text embeddings
         tn = normed(L["h1"], "ln2")
+        seen(tn2=tn)
         q = conv(L["q2"], tn, "x_q")
+        seen(q2=q)
         o = attend(q, L["kc"][:, :C], L["kc"][:, C:], L["kc"].shape[0], 2 * C)
+        seen(a2=o)
         back(L["o2"], o, L["h2"], L["h1"])
+        seen(h2=L["h2"])
         # gated-GELU feed-forward
         tn = normed(L["h2"], "ln3")
+        seen(tn3=tn)
         gg = tiles("x_g", 4 * C)
         api.sige_conv_geglu(tn, L["ff1"].g, C, 4 * C, L["ff1"].packed, L["ff1"].bias, cnt, gg, n_blocks=nb,
                             max_blocks=nb)
+        seen(gg=gg)
         back(L["ff2"], gg, L["h3"], L["h2"])
+        seen(h3=L["h3"])
         L["out"].forward(L["h3"], y, bl, ws, residual=x, fused=True, act_outs=act_outs)
 
     def precompute(self, image, fill_copies: bool = True):

@@ -131,7 +131,9 @@ def test_reduce_mask_errors(L):
 
 def test_attention_and_helper_errors(L):
     f = ctypes.c_float(0.1)
-    assert L.sige_sparse_attn(FAKE, 320, FAKE, FAKE, 320, 0, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 2
+    assert L.sige_sparse_attn(FAKE, 320, FAKE, FAKE, 320, 0, 16, 64, 8, 38, f, FAKE, 320, None, 0, None) == 2   # fp32: d % 4
+    assert L.sige_sparse_attn(FAKE, 322, FAKE, FAKE, 320, 0, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 2   # fp32: stride % 4
+    assert L.sige_sparse_attn(FAKE, 320, FAKE, FAKE, 320, 5, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1   # unknown dtype
     assert L.sige_sparse_attn(FAKE, 320, FAKE, FAKE, 320, 2, 16, 64, 8, 36, f, FAKE, 320, None, 0, None) == 2
     assert L.sige_sparse_attn(FAKE, 100, FAKE, FAKE, 320, 2, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1
     assert L.sige_sparse_attn(None, 320, FAKE, FAKE, 320, 2, 16, 64, 8, 40, f, FAKE, 320, None, 0, None) == 1
@@ -190,6 +192,73 @@ def test_token_layer_modulated_gather_and_list_errors(L):
     assert L.sige_conv_workspace_bytes(1, ctypes.byref(small), 512, 512, 1) > 0
 
 
+def test_knobs_are_explicit_state(L):
+    """The launch-heuristic overrides are set and read through the ABI (no environment variables),
+    default to automatic, and an unknown knob is refused."""
+    for name, k in api.KNOBS.items():
+        assert L.sige_get_knob(k) == -1, name
+    assert L.sige_set_knob(api.KNOBS["CONV_CFG"], 3) == 0 and L.sige_get_knob(api.KNOBS["CONV_CFG"]) == 3
+    assert L.sige_set_knob(api.KNOBS["CONV_CFG"], -5) == 0 and L.sige_get_knob(api.KNOBS["CONV_CFG"]) == -1
+    assert L.sige_set_knob(len(api.KNOBS), 1) == 1 and "knob" in err(L)
+    assert L.sige_get_knob(99) == -1
+    with api.knobs(ATTN_WGS=64, CONV_KC=4):
+        assert api.sige_get_knob("ATTN_WGS") == 64 and api.sige_get_knob("CONV_KC") == 4
+        # fewer workgroups to aim for -> fewer key splits -> a smaller workspace
+        small = L.sige_sparse_attn_workspace_bytes(64, 4096, 8, 40)
+    assert api.sige_get_knob("ATTN_WGS") == -1 and api.sige_get_knob("CONV_KC") == -1
+    assert 0 < small < L.sige_sparse_attn_workspace_bytes(64, 4096, 8, 40)
+    hdr = open(os.path.join(ROOT, "include", "sige.h")).read()
+    for name, k in api.KNOBS.items():
+        assert re.search(rf"SIGE_KNOB_{name}\s*=\s*{k}\b", hdr), name
+    for src in os.listdir(os.path.join(ROOT, "paper_2211_02048_amd", "csrc")):
+        if src.endswith((".hip", ".h")):
+            assert "getenv" not in open(os.path.join(ROOT, "paper_2211_02048_amd", "csrc", src)).read(), src
+
+
+def test_conv_plans_respect_the_lds_of_a_compute_unit(L):
+    """Every plan, whatever the block size and channel count, fits the 160 KiB of LDS of a compute
+    unit INCLUDING the kernel's static LDS (the block origins), and the shapes that promise two
+    resident workgroups fit twice; a layer no shape covers is refused cleanly.  Also: what the plan
+    query reports for the layers of the benchmark configurations."""
+    import torch
+    n_plans = 0
+    for dtype in (torch.float16, torch.float32):
+        for k in (1, 3):
+            for b in (4, 6, 8, 16, 22, 32, 48, 64, 96, 128):
+                for cin in (16, 48, 64, 128, 320, 512, 640, 1024, 1280):
+                    for nb in (1, 9, 300):
+                        g = api.geom(256, 256, b, k, 1, k // 2)
+                        for staged in (False, True):
+                            try:
+                                p = api.sige_conv_plan(dtype, g, cin, 128, nb, staged_math=staged, workspace_bytes=1 << 30)
+                            except api.SigeError as e:
+                                assert e.code == 2
+                                continue
+                            n_plans += 1
+                            assert p.lds_bytes <= 160 * 1024, (dtype, k, b, cin, nb, p)
+                            if p.kernel == 0 and p.shape <= 3 and p.k_steps_per_chunk == 8:
+                                assert 2 * p.lds_bytes <= 160 * 1024, (dtype, k, b, cin, nb, p)   # two per compute unit
+                            assert p.workgroups >= 1 and p.threads in (256, 512)
+    assert n_plans > 1000
+    f16 = torch.float16
+    # benchmark configuration 2: both convolutions with few blocks take the 64x32 four-wave K-split shape
+    g3, g1 = api.geom(256, 256, 16, 3, 1, 1), api.geom(256, 256, 16, 1, 1, 0)
+    p3, p1 = api.sige_conv_plan(f16, g3, 128, 128, 16, staged_math=True), api.sige_conv_plan(f16, g1, 128, 256, 16)
+    assert (p3.kernel, p3.shape, p3.patch_m, p3.patch_n) == (0, 3, 64, 32) and (p1.kernel, p1.shape) == (0, 3)
+    # every block active: the 128x128 shape
+    pa = api.sige_conv_plan(f16, g3, 128, 128, 256, staged_math=True)
+    assert (pa.kernel, pa.shape, pa.k_steps_per_chunk) == (0, 0, 8)
+    # a transformer block's feed-forward layers on 640 tokens of the latent-diffusion step: the few-row kernel
+    gt = api.geom(64, 64, 8, 1, 1, 0)
+    assert api.sige_conv_plan(torch.bfloat16, gt, 1280, 320, 10).kernel == 1
+    with api.knobs(CONV_POINTWISE=0):
+        assert api.sige_conv_plan(torch.bfloat16, gt, 1280, 320, 10).kernel == 0
+    with pytest.raises(api.SigeError):
+        api.sige_conv_plan(f16, g3, 24, 128, 4)            # Cin not a multiple of the K step
+    with pytest.raises(api.SigeError):
+        api.sige_conv_plan(f16, g3, 128, 128, 0)
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(api, "_lib", None)
     monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "missing.so"))
@@ -203,6 +272,7 @@ def test_struct_layouts_match_the_header(tmp_path):
     import subprocess
     src = tmp_path / "layout.c"
     fields = {"sige_geom": ("Geom", ["H_in", "W_out", "block_w", "pad"]),
+              "sige_conv_plan_info": ("ConvPlanInfo", [f for f, _ in api.ConvPlanInfo._fields_]),
               "sige_act_out": ("ActOut", ["y", "y_ld", "scale", "shift", "act"]),
               "sige_block_list": ("BlockListDesc", ["g", "indices", "max_blocks", "count", "workspace",
                                                     "workspace_bytes"]),

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import round_to, expected_tiles, assert_close, assert_mostly_close, dev, f64
+from helpers import round_to, expected_tiles, assert_close, dev, f64
 from paper_2211_02048_amd import api, inputs
 
 pytestmark = pytest.mark.gpu
@@ -13,10 +13,8 @@ DT = inputs.DTYPES
 
 
 def attn_close(got, want64, dtype, what):
-    """The kernel feeds the probabilities to the second matrix product in the storage type (the V
-    operand's), which the oracle does not model: at least 99.9 % of the elements within the stated
-    tolerance (1e-2 of max(|ref|, rms)) and every element within twice that."""
-    assert_mostly_close(got, want64, dtype, what, frac=0.999, loose=2.0)
+    """Element-wise at the stated tolerance: 1e-2 (fp16, bf16) or 1e-4 (fp32) of max(|ref|, rms(ref))."""
+    assert_close(got, want64, dtype, what)
 
 
 def run_attn(c, use_ws=True, n_q=None):
@@ -44,6 +42,9 @@ def run_attn(c, use_ws=True, n_q=None):
     (31, 1, 8, 5, "f16"),           # fewer keys than one chunk, smallest head
     (512, 3, 256, 70, "bf16"),      # largest head dimension
     (2048, 4, 96, 200, "f16"),
+    # single precision (the precision of the paper's experiments): its own kernel, 1e-4
+    (4096, 8, 40, 96, "f32"), (1024, 8, 80, 50, "f32"), (256, 8, 160, 256, "f32"), (77, 8, 40, 130, "f32"),
+    (31, 1, 4, 5, "f32"), (512, 3, 256, 70, "f32"), (300, 2, 100, 129, "f32"), (100, 2, 64, 1, "f32"),
 ])
 def test_sparse_attention_matches_oracle(oracle, T, heads, d, n_q, dtype):
     c = inputs.attention_case(100 + T + d, T, heads, d, n_q, dtype)
@@ -58,7 +59,8 @@ def test_sparse_attention_matches_oracle(oracle, T, heads, d, n_q, dtype):
 
 
 @pytest.mark.parametrize("dtype,res,b,heads,d,n", [("bf16", 32, 8, 8, 40, 3), ("f16", 16, 4, 4, 64, 16),
-                                                   ("bf16", 20, 8, 2, 24, 4), ("f16", 64, 8, 8, 40, 1)])
+                                                   ("bf16", 20, 8, 2, 24, 4), ("f16", 64, 8, 8, 40, 1),
+                                                   ("f32", 20, 8, 2, 24, 4), ("f32", 32, 8, 8, 40, 3)])
 def test_sparse_attention_queries_by_block_list(oracle, dtype, res, b, heads, d, n):
     """Queries, keys and values are three channel ranges of one full tensor; the queries of the
     call are the pixels of the listed blocks, taken from it by the attention kernel.  Against the
@@ -143,6 +145,22 @@ def test_sparse_attention_edge_cases(oracle):
                             f64(v).reshape(T, heads, d), 0.2)
     attn_close(o.reshape(nq, heads, d), want, torch.float16, "attention strided")
     assert (ob[:, :heads * d] == 0).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_sparse_attention_peaked_rows(oracle, dtype):
+    """Rows whose softmax is dominated by one or two keys (large logits): the probabilities that enter
+    the second product are rounded to the storage type, and the row is normalised by the sum of those
+    same rounded values, so a dominated row returns (a mix of) the value rows at the stated tolerance."""
+    T, heads, d, nq = 640, 4, 40, 200
+    c = inputs.attention_case(77, T, heads, d, nq, dtype)
+    rng = np.random.default_rng(3)
+    q = c["q"].float().numpy() * rng.uniform(1.0, 6.0, (nq, heads, 1)).astype(np.float32)   # temperature per row
+    c["q"] = torch.from_numpy(q).to(DT[dtype])
+    want = oracle.attention(f64(c["q"]), f64(c["k"]), f64(c["v"]), c["scale"])
+    for use_ws in (True, False):
+        o, _ = run_attn(c, use_ws)
+        attn_close(o, want, DT[dtype], f"peaked rows {dtype} workspace={use_ws}")
 
 
 def test_sparse_attention_token_selection_counts(oracle):
@@ -247,8 +265,26 @@ def test_sige_attention_layer_sparse_queries(oracle):
         act[y0:y0 + 4, x0:x0 + 4] = True
     a_t = torch.from_numpy(act).cuda()
     assert torch.equal(oc[~a_t], dev(out_cache)[~a_t])      # unedited tokens keep the cached output
-    # stored intermediates (q, k, v, attended values) are rounded to bf16 on the way: 2e-2 on the chain
-    assert_close(oc[a_t], want[act], td, "SIGE attention layer (active tokens)", tol=2e-2)
+    # call by call at the stated tolerance, each against the oracle's result from the oracle's own
+    # (rounded) inputs: queries, attended values, output projection
+    xe64 = f64(x_e)
+    q64 = round_to(oracle.conv2d(xe64, w64[0], b64[0]), td)
+    tok = oracle.block_pixels(blocks, 4, 4, H, W)
+    q_rows = np.stack([q64[y, x] for y, x in tok])
+    assert_close(q_tiles.view(nq, C), q_rows, td, "queries of the active tokens")
+    k_full, v_full = f64(kc), f64(vc)               # the caches as the library left them (checked below)
+    a_want = oracle.attention(f64(q_tiles).reshape(nq, heads, d), k_full.reshape(H * W, heads, d),
+                              v_full.reshape(H * W, heads, d), scale)
+    assert_close(att, a_want, td, "attention of the active tokens")
+    o_rows = oracle.conv2d(f64(att).reshape(nq, 1, C), w64[3], b64[3])[:, 0]
+    o_want = np.zeros((H, W, C))
+    for i, (y, x) in enumerate(tok):                # token order of the call -> the tokens' places in the map
+        o_want[y, x] = o_rows[i]
+    assert_close(oc[a_t], o_want[act], td, "output projection scattered into the cache")
+    # and the whole layer against the oracle's dense statement of it (no intermediate forced): the
+    # layer's three stored intermediates each add a rounding, so this second check is a drift bound
+    drift = np.abs(f64(oc[a_t]) - round_to(want[act], td)).max() / np.sqrt(np.mean(want[act] ** 2))
+    assert drift < 4e-2, f"whole layer drifted {drift:.3e} of the rms from the oracle's layer"
     # K/V caches: edited tokens overwritten, the rest bit-identical
     assert torch.equal(kc[~a_t], dev(k_cache)[~a_t]) and torch.equal(vc[~a_t], dev(v_cache)[~a_t])
     assert_close(kc[a_t], oracle.conv2d(f64(x_e), w64[1], b64[1])[act], td, "K overwrite")
@@ -340,9 +376,10 @@ def test_gather_token_norm(oracle, dtype, C, res, b, n):
 @pytest.mark.parametrize("dtype,Cin,Cg,b,n", [("bf16", 320, 1280, 8, 10), ("f16", 64, 24, 4, 5), ("f32", 32, 16, 3, 7),
                                                ("bf16", 1280, 512, 8, 2), ("f16", 128, 2560, 8, 1)])
 def test_conv_geglu(oracle, dtype, Cin, Cg, b, n):
-    """The feed-forward layer with the gated GELU folded into its epilogue: against the oracle's
-    convolution (fp64, unrounded) followed by its gated GELU; tiled and few-row kernels (chosen by size);
-    both count paths; tiles beyond the count untouched."""
+    """The feed-forward layer with the gated GELU folded into its epilogue (one layer, one stored
+    tensor): against the oracle's convolution (fp64, unrounded) followed by its gated GELU; tiled and
+    few-row kernels (chosen by size); both count paths; tiles beyond the count untouched.  The two
+    calls it replaces are each held to the same bar on their own inputs."""
     rng = np.random.default_rng(Cin + Cg + b)
     td = DT[dtype]
     g = api.geom(8 * b, 8 * b, b, 1, 1, 0)
@@ -364,8 +401,8 @@ def test_conv_geglu(oracle, dtype, Cin, Cg, b, n):
     api.sige_conv(dev(tiles), g, Cin, 2 * Cg, api.sige_pack_weight(dev(w)), dev(bias), cnt, o2, n_blocks=n, max_blocks=n)
     y2 = torch.empty((n, b, b, Cg), dtype=td, device="cuda")
     api.sige_geglu(o2, y2, Cg, n_rows=n * b * b)
-    # (their intermediate is a stored tensor: the oracle rounds it to the storage type too)
-    want2 = oracle.geglu(round_to(u, td).reshape(-1, 2 * Cg)).reshape(n, b, b, Cg)
-    assert_mostly_close(y2, want2, td, "conv, then gated GELU")   # (a 1-ulp flip of the stored intermediate shows)
+    # each call against the oracle on that call's own input (the intermediate is a stored tensor)
+    assert_close(o2, u, td, "the convolution alone")
+    assert_close(y2, oracle.geglu(f64(o2).reshape(-1, 2 * Cg)).reshape(n, b, b, Cg), td, "sige_geglu of the stored intermediate")
     with pytest.raises(api.SigeError):
         api.sige_conv_geglu(dev(tiles), g, Cin, Cg + 4, packed, None, cnt, out, n_blocks=n, max_blocks=n)

@@ -25,6 +25,60 @@ def rel_err(got, want):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_spade_every_layer_teacher_forced(dtype):
+    """The per-layer bar inside the generator: 1e-2 (fp16) / 1e-4 (fp32), element-wise, for every stored
+    tensor of the pre-computation pass and of a sparse step (modulated gathers, label-map and modulation
+    convolutions, up-samplings, shortcut tiles), each computed by the GPU from the oracle's own inputs
+    (see teacher.py)."""
+    from oracle import spade as osp
+    from teacher import SpadeTeacher
+    td = inputs.DTYPES[dtype]
+    bufs, ops = inputs.spade_topology(**TOPO)
+    P = inputs.spade_params(1005, bufs, ops, dtype, n_labels=5)
+    lab0 = inputs.label_map(1005, 64, 128, 5, 12)
+    lab1 = inputs.relabel(1006, lab0, 0.02, 5)
+    seg0, seg1 = (inputs.one_hot_pyramid(l, SIZES, 5, 16, dtype) for l in (lab0, lab1))
+    seg64 = lambda s: {k: v.double().numpy() for k, v in s.items()}
+    trace_d, trace_e = [], []
+    cache, stats = osp.spade_pass(bufs, ops, P, seg64(seg0), storage=dtype, block=BLOCK, min_sparse=MIN_SPARSE,
+                                  trace=trace_d)
+    mask = (lab1 != lab0).astype(np.uint8)
+    want, blocks = osp.spade_pass(bufs, ops, P, seg64(seg1), storage=dtype, block=BLOCK, cache=cache, stats=stats,
+                                  mask=mask, dilate=1, min_sparse=MIN_SPARSE, trace=trace_e)
+    net = SigeSpade(TOPO, dtype=dtype, block=BLOCK, min_sparse=MIN_SPARSE, params=P, n_labels=5)
+    start = {n: np.zeros(shape) for n, shape in bufs.items()}
+    start["z"] = f64(P["z"])
+    for (h, w), t in seg0.items():
+        if f"seg{h}" in start:
+            start[f"seg{h}"] = f64(t)
+    t_d = SpadeTeacher(net, td, trace_d, start)
+    net.hook = t_d
+    try:
+        net.precompute({k: v.cuda() for k, v in seg0.items()})
+        torch.cuda.synchronize()
+        net.hook = None
+        start = {n: a.copy() for n, a in cache.items()}
+        t_e = SpadeTeacher(net, td, trace_e, start, stats=stats)
+        t_e._force_buffers()                  # the GPU's caches = the oracle's, so that the edit's mask is the same
+        net.set_edit({k: v.cuda() for k, v in seg1.items()}, exact=True)
+        for (h, w), t in seg1.items():
+            if f"seg{h}" in t_e.state:
+                t_e.state[f"seg{h}"] = f64(t)
+                t_e.dirty.add(f"seg{h}")
+        net.hook = t_e
+        net.step()
+        torch.cuda.synchronize()
+    finally:
+        net.hook = None
+    t_d.rep.assert_clean(min_checked=50)
+    t_e.rep.assert_clean(min_checked=50)
+    for n, L in net.layers.items():
+        if L["sparse"]:
+            bl = L["list"][1]
+            assert np.array_equal(bl.indices[:bl.n_host].cpu().numpy(), blocks[n]), n
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_spade_generator_sequential_edits(dtype):
     from oracle import spade as osp
     td = inputs.DTYPES[dtype]
@@ -35,6 +89,7 @@ def test_spade_generator_sequential_edits(dtype):
         labels.append(inputs.relabel(1006 + i, labels[-1], frac, 5))
     segs = [inputs.one_hot_pyramid(l, SIZES, 5, 16, dtype) for l in labels]
     seg64 = lambda s: {k: v.double().numpy() for k, v in s.items()}
+    # SECOND check, on the free-running chain (the per-layer bar is held by the teacher-forced test above):
     # chain of ~110 stored tensors: unit roundoff u of the storage type, drift asserted at 10 u rms / 80 u max
     u = {"f16": 2.0 ** -11, "f32": 2.0 ** -24}[dtype]
     tol = max(10.0 * u, 1e-5)
