@@ -79,16 +79,20 @@ def spade_pass(bufs, ops, P, seg, *, storage: str, eps: float = 1e-5, block: int
         else:
             t = rnd(so.activation(x, act))
         k = op["k"]
-        y = rnd(so.conv2d(t, _p64(P, n + ".w"), _p64(P, n + ".b"), 1, k // 2))
+        # a layer's stored output is the convolution plus its residuals (Scatter with Block Residual,
+        # App. A.2), rounded once; a shortcut branch's output is a stored tensor itself
+        y = so.conv2d(t, _p64(P, n + ".w"), _p64(P, n + ".b"), 1, k // 2)
         if not op["scatter"]:
+            y = rnd(y)
             short[n] = y
             if trace is not None:
                 trace.append((n, {"short": y.copy()}))
             continue
         if op["shortcut"] is not None:
-            y = rnd(y + short[op["shortcut"]])
+            y = y + short[op["shortcut"]]
         if op["residual"] is not None:
-            y = rnd(y + B[op["residual"]])
+            y = y + B[op["residual"]]
+        y = rnd(y)
         B[op["y"]] = so.select_blocks(y, B[op["y"]], blocks, b, b)
         if trace is not None:
             trace.append((n, {"y": B[op["y"]].copy()}))

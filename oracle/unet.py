@@ -10,8 +10,8 @@ the sparse resolutions run with every block active (Sec. 4.1 "Implementation det
 
 The network itself is data (a list of operations over named buffers, see the workload
 generator); this module only interprets it with the oracle's dense primitives.  Every
-stored tensor (gathered activation, convolution output, layer output) is rounded once to
-the storage type.
+stored tensor (gathered activation, shortcut tiles, layer output = convolution plus its
+residuals) is rounded once to the storage type.
 """
 from __future__ import annotations
 
@@ -86,7 +86,7 @@ def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate
     a = rnd(so.attention(q.reshape(T, heads, d), kv[:, :, :C].reshape(T, heads, d),
                          kv[:, :, C:].reshape(T, heads, d), 1.0 / np.sqrt(d))).reshape(r, r, C)
     note("a1", a)
-    keep(rnd(rnd(lin(a, "o1")) + h0), f"{n}.h1")
+    keep(rnd(lin(a, "o1") + h0), f"{n}.h1")
     h1 = B[f"{n}.h1"]
     note("h1", h1)
     # cross-attention over the text embeddings
@@ -101,7 +101,7 @@ def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate
     a = rnd(so.attention(q.reshape(T, heads, d), kc.reshape(nc, heads, d), vc.reshape(nc, heads, d),
                          1.0 / np.sqrt(d))).reshape(r, r, C)
     note("a2", a)
-    keep(rnd(rnd(lin(a, "o2")) + h1), f"{n}.h2")
+    keep(rnd(lin(a, "o2") + h1), f"{n}.h2")
     h2 = B[f"{n}.h2"]
     note("h2", h2)
     # gated-GELU feed-forward
@@ -110,10 +110,10 @@ def _transformer_block(op, B, P, x, rnd, dense, stats, used_blocks, mask, dilate
     # the first feed-forward layer and its gated GELU are one layer with one stored tensor
     gg = rnd(so.geglu(lin(tn, "ff1")))
     note("gg", gg)
-    keep(rnd(rnd(lin(gg, "ff2")) + h2), f"{n}.h3")
+    keep(rnd(lin(gg, "ff2") + h2), f"{n}.h3")
     h3 = B[f"{n}.h3"]
     note("h3", h3)
-    y = rnd(rnd(lin(h3, "out")) + x_in)
+    y = rnd(lin(h3, "out") + x_in)
     yv = _view(B, op["y"])
     yv[...] = so.select_blocks(y, yv, blocks, b, b)
     note("y", B[op["y"][0]])
@@ -151,17 +151,21 @@ def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float
                     stats_out[n] = so.fold_gn(_p64(P, n + ".gamma"), _p64(P, n + ".beta"), mean, var, eps)
                 scale, shift = stats_out[n]
             act = so.ACT_SILU if op["act"] else so.ACT_NONE
-            y = rnd(so.dense_layer(xin, _p64(P, n + ".w"), _p64(P, n + ".b"), s, pad, scale, shift, act,
-                                   storage=storage))
+            # a layer's stored output is the convolution plus its residuals (Scatter with Block
+            # Residual, App. A.2), rounded once; a shortcut branch's output is a stored tensor itself
+            y = so.dense_layer(xin, _p64(P, n + ".w"), _p64(P, n + ".b"), s, pad, scale, shift, act,
+                               storage=storage)
             if not op["scatter"]:
+                y = rnd(y)
                 short[n] = y          # shortcut branch: added by the consumer on its blocks
                 if trace is not None:
                     trace.append((n, {"short": y.copy()}))
                 continue
             if op["shortcut"] is not None:
-                y = rnd(y + short[op["shortcut"]])
+                y = y + short[op["shortcut"]]
             if op["residual"] is not None:
-                y = rnd(y + _view(B, op["residual"]))
+                y = y + _view(B, op["residual"])
+            y = rnd(y)
             yv = _view(B, op["y"])
             if dense or r_in < min_sparse_res:
                 blocks = all_blocks(Hout, Hout, b)
@@ -192,8 +196,7 @@ def unet_pass(bufs, ops, P, image, *, storage: str, groups: int = 32, eps: float
             q, kk, v = [rnd(so.conv2d(z, _p64(P, f"{n}.{p}.w"), _p64(P, f"{n}.{p}.b"))) for p in "qkv"]
             a = rnd(so.attention(q.reshape(T, heads, d), kk.reshape(T, heads, d), v.reshape(T, heads, d),
                                  1.0 / np.sqrt(d))).reshape(r_in, r_in, C)
-            y = rnd(so.conv2d(a, _p64(P, n + ".o.w"), _p64(P, n + ".o.b")))
-            y = rnd(y + x)
+            y = rnd(so.conv2d(a, _p64(P, n + ".o.w"), _p64(P, n + ".o.b")) + x)
             assert dense or r_in < min_sparse_res, "attention is only wrapped at all-active resolutions here"
             _view(B, op["y"])[...] = y
             used_blocks[n] = all_blocks(r_in, r_in, min(block, r_in))
