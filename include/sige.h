@@ -236,9 +236,9 @@ int sige_conv_geglu(const void* tiles, sige_dtype dt, const sige_geom* g, int32_
  * folded into its epilogue - the output tiles never touch HBM.  For layers whose input tiles
  * already exist (the token-wise layers between Gather and Scatter of Fig. "sige-attention":
  * the projection that leaves an attention block, keys and values on their way into the
- * caches).  Arguments as in sige_conv and sige_scatter; the convolution result is rounded
- * to dt before the residuals are added, as a stored tile would be.  workspace as in
- * sige_conv.                                                                          */
+ * caches).  Arguments as in sige_conv and sige_scatter; the residuals are added to the fp32
+ * sums and the result is rounded to dt once (Scatter with Block Residual, App. A.2: the
+ * layer's stored output is the convolution plus its residuals).  workspace as in sige_conv. */
 int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int32_t Cin, int32_t Cout,
                       const void* packed_weight, const float* bias,
                       const int32_t* indices, const int32_t* count, int32_t max_blocks, int32_t n_blocks,
@@ -249,10 +249,13 @@ int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int3
  * the nonlinearity), the convolution and Scatter (with the residual additions) in ONE
  * kernel.  The input tile of each active block is gathered from x straight into LDS,
  * multiplied on the matrix cores, and the result goes straight into y - the stacked tiles
- * never touch HBM.  Arguments as in sige_gather / sige_conv / sige_scatter; the convolution
- * result is rounded to dt before the residuals are added, as a stored tile would be, and the
- * results are bit-identical to calling those three in sequence whenever both run the same
- * kernel shape (always, except for a 1x1 convolution with Scale+Shift or an activation, where
+ * never touch HBM.  Arguments as in sige_gather / sige_conv / sige_scatter.  Residuals are
+ * added to the fp32 sums and the result is rounded to dt once (Scatter with Block Residual,
+ * App. A.2: the layer's stored output is the convolution plus its residuals; the three calls
+ * round the stored output tiles first and once more after the addition, so with residuals
+ * the fused result may differ from theirs in the last place).  Without residuals the results
+ * are bit-identical to calling those three in sequence whenever both run the same kernel
+ * shape (always, except for a 1x1 convolution with Scale+Shift or an activation, where
  * sige_conv alone may take the few-row kernel and the fp32 sums are added in another order).
  * Exactly one of
  *   y         - scatter into the cached output, in place (residuals allowed), or
@@ -260,8 +263,8 @@ int sige_conv_scatter(const void* tiles, sige_dtype dt, const sige_geom* g, int3
  *               branch whose tiles a later call adds as residual_tiles)
  * must be given.  x and y must not overlap (a tile's halo belongs to other blocks).
  * workspace: as for sige_conv (the reduction kernel then also adds the residuals and
- * scatters); bit-identity with the three calls holds when sige_conv gets a workspace of
- * the same size.
+ * scatters); bit-identity with the three calls (no residuals) holds when sige_conv gets a
+ * workspace of the same size.
  * act_outs (n_act_outs of them, 0..SIGE_MAX_ACT_OUTS; scatter mode only): Sec. 3.2
  * "Pre-computing normalization parameters" makes the Scale+Shift of the NEXT layer a
  * constant per channel, so the layer that produces a tensor can apply it, and the

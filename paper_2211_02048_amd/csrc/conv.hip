@@ -132,8 +132,9 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T* __restrict__ 
 
 // Finishes one run of N consecutive output channels starting at o: v holds the fp32 sums (bias
 // included), t the element's index in the stacked output tiles, pix the pixel of y it belongs to.
-// Plain mode stores the tile elements; fused mode rounds them to the storage type as a stored
-// tile would be, adds the residuals in fp32 and stores into y.
+// Plain mode stores the tile elements; fused mode adds the residuals to the fp32 sums and rounds
+// once into y (Scatter with Block Residual, App. A.2: the layer's stored output is the convolution
+// plus its residuals; no tile is stored on the way, so none is rounded).
 // early: the two residual vectors were fetched by the caller ahead of time (for the 16-byte path
 // only).
 // Scale and shift of the activated copies for the N channels from o on, fetched by the caller
@@ -195,27 +196,26 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
     constexpr int N = Vec16<T>::N;
     T* __restrict__ out = (T*)a.out;
     if (vec_ok && o + N <= a.Cout) {
-        uint4 r = pack<T>(v);
-        if (to_y) {
-            if (a.res_tiles || a.res_full) {
-                float f[N], q[N];
-                unpack<T>(r, f);
-                if (a.res_tiles) {
-                    uint4 rt = early_tiles;
-                    if (!early) rt = *(const uint4*)((const T*)a.res_tiles + t);
-                    unpack<T>(rt, q);
+        uint4 r;
+        if (to_y && (a.res_tiles || a.res_full)) {
+            float q[N];
+            if (a.res_tiles) {
+                uint4 rt = early_tiles;
+                if (!early) rt = *(const uint4*)((const T*)a.res_tiles + t);
+                unpack<T>(rt, q);
 #pragma unroll
-                    for (int i = 0; i < N; ++i) f[i] += q[i];
-                }
-                if (a.res_full) {
-                    uint4 rf = early_full;
-                    if (!early) rf = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
-                    unpack<T>(rf, q);
-#pragma unroll
-                    for (int i = 0; i < N; ++i) f[i] += q[i];
-                }
-                r = pack<T>(f);
+                for (int i = 0; i < N; ++i) v[i] += q[i];
             }
+            if (a.res_full) {
+                uint4 rf = early_full;
+                if (!early) rf = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+                unpack<T>(rf, q);
+#pragma unroll
+                for (int i = 0; i < N; ++i) v[i] += q[i];
+            }
+        }
+        r = pack<T>(v);
+        if (to_y) {
             *(uint4*)((T*)a.y + pix * a.y_ld + o) = r;
             // the next layers' normalisation and nonlinearity, applied here once instead of by every
             // workgroup that later gathers this pixel (from the stored, rounded value)
@@ -234,14 +234,13 @@ __device__ __forceinline__ void emit_run(const ConvArgs& a, bool to_y, bool vec_
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             if (o + i >= a.Cout) break;
-            T r = from_f32<T>(v[i]);
+            float f = v[i];
             if (to_y) {
-                if (a.res_tiles || a.res_full) {
-                    float f = to_f32(r);
-                    if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t + i]);
-                    if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o + i]);
-                    r = from_f32<T>(f);
-                }
+                if (a.res_tiles) f += to_f32(((const T*)a.res_tiles)[t + i]);
+                if (a.res_full) f += to_f32(((const T*)a.res_full)[pix * a.res_ld + o + i]);
+            }
+            const T r = from_f32<T>(f);
+            if (to_y) {
                 ((T*)a.y)[pix * a.y_ld + o + i] = r;
             } else {
                 out[t + i] = r;

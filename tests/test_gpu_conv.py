@@ -365,11 +365,18 @@ def test_conv_k_split_over_workgroups(oracle, dtype, Cin, Cout, res, b, k):
         y_f = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
         conv.forward(dev(x), y_f, bl, ws, residual=dev(resid), fused=True)
         if three_calls:
+            # the three calls store the output tiles (rounded once) before the scatter adds the residual ...
             y = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
             conv.forward(dev(x), y, bl, ws, residual=dev(resid))
-            assert torch.equal(y, y_f), "fused call differs from gather + conv + scatter under a K split"
-        # the convolution result is a stored tensor (rounded once) before the residual is added
-        assert_close(y_f, round_to(want, td) + f64(resid), td, "k-split + residual")
+            assert_close(y, round_to(want, td) + f64(resid), td, "gather + conv + scatter under a K split, residual")
+            # ... and without a residual they and the fused call write the same bits
+            y0 = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+            conv.forward(dev(x), y0, bl, ws)
+            y0f = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+            conv.forward(dev(x), y0f, bl, ws, fused=True)
+            assert torch.equal(y0, y0f), "fused call differs from gather + conv + scatter under a K split"
+        # the fused call adds the residual to the fp32 sums and rounds once
+        assert_close(y_f, want + f64(resid), td, "k-split + residual")
     # without a workspace: the unsplit kernel; same values up to the rounding order of the fp32 sum
     y_n = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
     conv.forward(dev(x), y_n, bl, ws, split_k=False, fused=True)
@@ -420,7 +427,7 @@ def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
     bl.count.fill_(n)
     blocks = blocks.cpu().numpy()
     want_full = oracle.conv2d(f64(x), f64(w), f64(bias), 1, 0)
-    want = oracle.select_blocks(round_to(want_full, td) + f64(resid), f64(cache), blocks, b, b)
+    want = oracle.select_blocks(want_full + f64(resid), f64(cache), blocks, b, b)
     out_mask = torch.from_numpy(outside_blocks_mask(blocks, b, b, res, res)).cuda()
     ws = Workspace("cuda")
     for mode in (None, "1", "2", "3", "2 with four waves"):
@@ -444,12 +451,21 @@ def test_conv_pointwise_few_rows(oracle, dtype, Cin, Cout, res, b, n):
             assert_close(out[:n], want_t, td, f"pointwise tiles mode={mode}")
             assert (out[n:] == 5.0).all()
             if Cout % 8 == 0:
-                # tile residual through the fused call, against the three calls
+                # tile residual through the fused call (one rounding of convolution + residuals) and through
+                # the three calls (the output tiles are stored, hence rounded, before the scatter adds)
+                rt = out[:n].contiguous()
+                rt_full = np.zeros((res, res, Cout))
+                for i, (y0, x0) in enumerate(blocks):
+                    h, wd = min(b, res - y0), min(b, res - x0)
+                    rt_full[y0:y0 + h, x0:x0 + wd] = f64(rt[i])[:h, :wd]
                 y3 = dev(cache).clone()
-                conv.forward(dev(x), y3, bl, ws, residual_tiles=out[:n].contiguous(), residual=dev(resid))
+                conv.forward(dev(x), y3, bl, ws, residual_tiles=rt, residual=dev(resid))
                 yf = dev(cache).clone()
-                conv.forward(dev(x), yf, bl, ws, residual_tiles=out[:n].contiguous(), residual=dev(resid), fused=True)
-                assert torch.equal(y3, yf)
+                conv.forward(dev(x), yf, bl, ws, residual_tiles=rt, residual=dev(resid), fused=True)
+                assert_close(yf, oracle.select_blocks(want_full + rt_full + f64(resid), f64(cache), blocks, b, b), td,
+                             f"fused, both residuals mode={mode}")
+                assert_close(y3, oracle.select_blocks(round_to(want_full, td) + rt_full + f64(resid), f64(cache), blocks,
+                                                      b, b), td, f"three calls, both residuals mode={mode}")
     # the tiled kernel on the same call: same values up to the order of the fp32 sums
     with api.knobs(CONV_POINTWISE=0):
         y0 = dev(cache).clone()
@@ -494,12 +510,13 @@ def test_conv_scatter(oracle, dtype, Cin, Cout, res, b, k, n):
                 api.sige_conv(tiles, g, Cin, Cout, conv.packed, conv.bias, cnt, o, n_blocks=nb, max_blocks=mb, workspace=split)
                 y2 = cache.clone()
                 api.sige_scatter(o, g, idx, cnt, y2, n_blocks=nb, residual_tiles=rt, residual=rf, max_blocks=mb)
-                assert torch.equal(y, y2), "conv + scatter folded differs from the two calls"
+                if rt is None:
+                    assert torch.equal(y, y2), "conv + scatter folded differs from the two calls"
             want_t = np.stack([oracle.conv2d(f64(tiles[i]), f64(w), f64(bias), 1, 0) for i in range(n)])
             want = f64(cache)
             for i, (y0, x0) in enumerate(blocks):
                 h, wd = min(b, res - y0), min(b, res - x0)
-                blk = round_to(want_t[i], td)[:h, :wd]
+                blk = want_t[i][:h, :wd]              # convolution plus residuals, rounded once
                 if rt is not None:
                     blk = blk + f64(rtiles[i])[:h, :wd] + f64(resid)[y0:y0 + h, x0:x0 + wd]
                 want[y0:y0 + h, x0:x0 + wd] = blk
@@ -692,12 +709,22 @@ def test_layer_config2_shortcut_and_residual(oracle):
     assert torch.equal(res_f, res_tiles)
     full_res = dev(cfg["a_orig"])[:, :, :64].contiguous()
     main.forward(dev(cfg["a_edit"]), y_f, bl3, wsp, residual_tiles=res_f, tag="mf", fused=True)
-    assert torch.equal(y_f, y)
-    # both residual kinds at once, three calls vs fused
+    # the fused call adds the shortcut tiles to the fp32 sums and rounds once; the three calls round the
+    # stored output tiles first: each against the oracle's statement of what it computes
+    short_rounded = round_to(oracle.conv2d(a_e, ws_, bs_, 1, 0), td)            # the shortcut tiles are a stored tensor
+    main_e = oracle.conv2d(a_e, w, b, 1, 1)
+    assert_close(y_f, oracle.select_blocks(main_e + short_rounded, f64(cache_sum), blocks3, 16, 16), td,
+                 "fused main + shortcut tiles")
+    assert_close(y, oracle.select_blocks(round_to(main_e, td) + short_rounded, f64(cache_sum), blocks3, 16, 16), td,
+                 "three calls, main + shortcut tiles")
+    # both residual kinds at once, three calls and fused
     y1, y2 = dev(cache_sum).clone(), dev(cache_sum).clone()
     main.forward(dev(cfg["a_edit"]), y1, bl3, wsp, residual_tiles=res_tiles, residual=full_res, tag="m")
     main.forward(dev(cfg["a_edit"]), y2, bl3, wsp, residual_tiles=res_f, residual=full_res, tag="mf", fused=True)
-    assert torch.equal(y1, y2)
+    both = short_rounded + f64(full_res)
+    assert_close(y2, oracle.select_blocks(main_e + both, f64(cache_sum), blocks3, 16, 16), td, "fused, both residuals")
+    assert_close(y1, oracle.select_blocks(round_to(main_e, td) + both, f64(cache_sum), blocks3, 16, 16), td,
+                 "three calls, both residuals")
 
 
 def test_layer_all_active_equals_dense_and_zero_blocks(oracle):
@@ -915,9 +942,9 @@ def test_fused_conv_pair(oracle, dtype, Cin, C3, C1, res, b, n):
         api.sige_fused_conv_pair(c3, c1)
         torch.cuda.synchronize()
         assert torch.equal(y3, ya) and torch.equal(y1, yb), f"pair differs from the two calls (device_count={device_count})"
-    want = oracle.dense_layer(f64(x), f64(w3), f64(b3), 1, 1, f64(scale), f64(shift), oracle.ACT_SILU)
-    want = oracle.select_blocks(round_to(want, td) + f64(resid), f64(cache3), blocks, b, b)
-    assert_mostly_close(y3, want, td, "3x3 call of the pair")
+    want = oracle.dense_layer(f64(x), f64(w3), f64(b3), 1, 1, f64(scale), f64(shift), oracle.ACT_SILU, storage=dtype)
+    want = oracle.select_blocks(want + f64(resid), f64(cache3), blocks, b, b)
+    assert_close(y3, want, td, "3x3 call of the pair")
     # an empty first list: the second call still runs
     bl3.count.fill_(0)
     bl3.n_host, bl1.n_host = 0, n - 1
