@@ -104,6 +104,24 @@ int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt,
                      void* workspace, size_t workspace_bytes, void* stream);
 size_t sige_reduce_mask_workspace_bytes(const sige_geom* g);
 
+/* sige_reduce_mask for callers that cannot allocate device memory: code that runs under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * and the same kernels as sige_reduce_mask called with a workspace (one list); the per-block flags
+ * live in a scratch array built into the library (SIGE_NOALLOC_MAX_BLOCKS bytes of device memory
+ * per GPU the library runs on, held until the process ends) instead of a caller workspace, and the
+ * call neither allocates nor frees anything.  A block grid of more than SIGE_NOALLOC_MAX_BLOCKS
+ * blocks is refused with SIGE_ERR_CAPACITY; indices and count are required (use sige_reduce_mask
+ * for the mask alone).  The first call on a device resolves the array's address and clears it
+ * with a small kernel on `stream`: make that call outside a stream capture.  Every call leaves
+ * the flags it used zero again.  All calls on one GPU share the array: calls that overlap on one
+ * GPU (different streams, different host threads) race and must be ordered by the caller.     */
+#define SIGE_NOALLOC_MAX_BLOCKS 65536
+int sige_reduce_mask_noalloc(const void* a_orig, const void* a_edit, sige_dtype dt,
+                             int32_t Hm, int32_t Wm, int32_t C, float tau,
+                             const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
+                             const sige_geom* g, uint8_t* mask_out,
+                             int32_t* indices, int32_t max_blocks, int32_t* count, void* stream);
+
 /* One list of sige_reduce_mask_lists: a layer geometry, where its list goes, and its own
  * flag workspace (required here; zeroed once by the caller, left zero by every call). */
 typedef struct {

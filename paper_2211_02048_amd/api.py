@@ -24,7 +24,7 @@ STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3:
 
 EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_fused_conv_pair", "sige_sparse_attn", "sige_sparse_attn_blocks",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
-           "sige_gn_stats", "sige_last_error", "sige_version", "sige_set_knob", "sige_get_knob", "sige_conv_plan"]
+           "sige_gn_stats", "sige_last_error", "sige_version", "sige_set_knob", "sige_get_knob", "sige_conv_plan", "sige_reduce_mask_noalloc"]
 
 # sige_knob of the header
 KNOBS = {"CONV_CFG": 0, "CONV_KC": 1, "CONV_SPLIT": 2, "CONV_HALF": 3, "CONV_SPLIT_WGS": 4, "CONV_POINTWISE": 5,
@@ -98,6 +98,7 @@ def lib() -> ctypes.CDLL:
         gp = ctypes.POINTER(Geom)
         L.sige_reduce_mask.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp, sz,
                                        vp]
+        L.sige_reduce_mask_noalloc.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp]
         L.sige_reduce_mask_lists.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32,
                                              ctypes.POINTER(BlockListDesc), i32, vp, vp]
         L.sige_reduce_mask_workspace_bytes.restype = ctypes.c_size_t
@@ -161,6 +162,24 @@ def sige_reduce_mask(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0
                                   dilate, ctypes.byref(g), _ptr(mask_out), _ptr(indices), mb, _ptr(count),
                                   _ptr(workspace), 0 if workspace is None else workspace.numel() *
                                   workspace.element_size(), _stream()))
+
+
+NOALLOC_MAX_BLOCKS = 65536
+
+
+def sige_reduce_mask_noalloc(g: Geom, indices, count, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None,
+                             mask_out=None, pool_log2=0, dilate=0, max_blocks=None):
+    """sige_reduce_mask with the block flags in the library's built-in scratch: allocates nothing."""
+    if a_orig is not None:
+        Hm, Wm, C = a_orig.shape
+        dt = _DT[a_orig.dtype]
+    else:
+        Hm, Wm = mask_in.shape
+        C, dt = 0, SIGE_F32
+    mb = indices.shape[0] if max_blocks is None else max_blocks
+    _check(lib().sige_reduce_mask_noalloc(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2,
+                                          dilate, ctypes.byref(g), _ptr(mask_out), _ptr(indices), mb, _ptr(count),
+                                          _stream()))
 
 
 def sige_reduce_mask_lists(lists, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None, mask_out=None,

@@ -14,6 +14,8 @@
 // mask (flags in LDS) and compacts.
 #include "common.h"
 
+#include <mutex>
+
 namespace sige {
 
 template <typename T>
@@ -444,6 +446,82 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
     sige_block_list L;
     L.g = *g; L.indices = indices; L.max_blocks = max_blocks; L.count = count;
     L.workspace = workspace; L.workspace_bytes = workspace_bytes;
+    return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, &L, 1, nullptr,
+                        mask_out, stream);
+}
+
+// ---- the same reduction for callers that cannot allocate ------------------------------------------
+// The block flags live in a file-scope device array instead of a caller workspace.  In host code the
+// array's name is only a stand-in for the symbol: the address the kernels get is resolved once per
+// device with hipGetSymbolAddress (each GPU holds its own copy at its own address) and kept.
+static __device__ __align__(256) unsigned char scratch[SIGE_NOALLOC_MAX_BLOCKS];
+
+namespace sige {
+
+__global__ __launch_bounds__(256) void clear_scratch_kernel(uint4* p, int n_vec)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n_vec) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];      // per device, nullptr until resolved
+static std::mutex g_scratch_mutex;
+
+// The device address of `scratch` on the current device; the first time on a device the whole
+// array is cleared by a small kernel on `st` (the reduction's kernels follow on the same stream).
+static int scratch_address(const char* who, hipStream_t st, void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "%s: hipGetDevice: %s", who, hipGetErrorString(e));
+    SIGE_REQUIRE(dev >= 0 && dev < kMaxDevices, SIGE_ERR_UNSUPPORTED, "%s: device ordinal %d beyond %d", who, dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        SIGE_REQUIRE(e == hipSuccess && ptr != nullptr, SIGE_ERR_HIP, "%s: hipGetSymbolAddress: %s", who,
+                     hipGetErrorString(e));
+        hipLaunchKernelGGL(clear_scratch_kernel, dim3(SIGE_NOALLOC_MAX_BLOCKS / 16 / 256), dim3(256), 0, st,
+                           (uint4*)ptr, SIGE_NOALLOC_MAX_BLOCKS / 16);
+        SIGE_LAUNCH_CHECK(who);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SIGE_OK;
+}
+
+}  // namespace sige
+
+extern "C" int sige_reduce_mask_noalloc(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
+                                        int32_t Wm, int32_t C, float tau, const uint8_t* mask_in,
+                                        int32_t pool_log2, int32_t dilate, const sige_geom* g,
+                                        uint8_t* mask_out, int32_t* indices, int32_t max_blocks,
+                                        int32_t* count, void* stream)
+{
+    clear_error();
+    const char* who = "sige_reduce_mask_noalloc";
+    SIGE_REQUIRE(g != nullptr, SIGE_ERR_INVALID_ARG, "%s: geometry is NULL", who);
+    int th, tw;
+    if (int rc = check_geom(g, who, &th, &tw)) return rc;
+    SIGE_REQUIRE(indices != nullptr && count != nullptr, SIGE_ERR_INVALID_ARG, "%s: indices and count are required", who);
+    const size_t need = sige_reduce_mask_workspace_bytes(g);
+    SIGE_REQUIRE(need <= (size_t)SIGE_NOALLOC_MAX_BLOCKS, SIGE_ERR_CAPACITY,
+                 "%s: the block grid has %zu blocks, the built-in scratch holds %d", who,
+                 (size_t)((g->H_out + g->block_h - 1) / g->block_h) * ((g->W_out + g->block_w - 1) / g->block_w),
+                 SIGE_NOALLOC_MAX_BLOCKS);
+    // every other argument error is found before the device is touched
+    const bool diff_mode = a_orig != nullptr || a_edit != nullptr;
+    SIGE_REQUIRE(diff_mode != (mask_in != nullptr), SIGE_ERR_INVALID_ARG,
+                 "%s: give either (a_orig, a_edit) or mask_in, not both and not neither", who);
+    SIGE_REQUIRE(!diff_mode || (a_orig && a_edit && mask_out), SIGE_ERR_INVALID_ARG,
+                 "%s: a_orig, a_edit and mask_out are required when the mask is computed from activations", who);
+    SIGE_REQUIRE(max_blocks >= 0, SIGE_ERR_INVALID_ARG, "%s: max_blocks is negative", who);
+    void* ptr = nullptr;
+    if (int rc = scratch_address(who, (hipStream_t)stream, &ptr)) return rc;
+    sige_block_list L;
+    L.g = *g; L.indices = indices; L.max_blocks = max_blocks; L.count = count;
+    L.workspace = ptr; L.workspace_bytes = need;
     return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, &L, 1, nullptr,
                         mask_out, stream);
 }
