@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libsige_hip.so")
-SOURCES = ["api.hip", "reduce_mask.hip", "gather_scatter.hip", "conv.hip", "attn.hip", "gn.hip", "token_ops.hip"]
+SOURCES = ["conv_f16.hip", "conv_bf16.hip", "conv_f32.hip", "conv.hip", "attn.hip", "api.hip", "reduce_mask.hip", "gather_scatter.hip", "gn.hip", "token_ops.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-fno-gpu-rdc", "-Wall", "-Wno-unused-function"]
@@ -31,7 +31,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
     if verbose:

@@ -1,0 +1,7 @@
+// The convolution kernels for storage type bf16: this translation unit instantiates them (one per type, so
+// that the three compile side by side).
+#include "conv_kernels.h"
+
+namespace sige {
+SIGE_CONV_LAUNCHERS(, bf16)
+}  // namespace sige
