@@ -435,11 +435,16 @@ int sige_version(void);
  *   CONV_POINTWISE     the few-row 1x1 kernel: 0 = never, 1 = 64x32, 2 = 64x64, 3 = 32x32 patches
  *   CONV_POINTWISE_W4  its four-wave variant for 64x64 patches: 0 = never, 1 = always
  *   CONV_PAIR_WGS      most workgroups up to which sige_fused_conv_pair shares one launch
- *   ATTN_WGS           workgroups the key split of sige_sparse_attn aims for                    */
+ *   ATTN_WGS           workgroups the key split of sige_sparse_attn aims for
+ *   DIFF_LOADS         16-byte loads per lane and tensor in flight in the difference kernel (1, 2, 4, 8)
+ *   DIFF_WGS           most workgroups of the difference kernel
+ *   CONV_DIRECT        0: the shapes whose waves do not split K send their accumulators through LDS
+ *                      instead of straight from the registers                                    */
 typedef enum {
     SIGE_KNOB_CONV_CFG = 0, SIGE_KNOB_CONV_KC = 1, SIGE_KNOB_CONV_SPLIT = 2, SIGE_KNOB_CONV_HALF = 3,
     SIGE_KNOB_CONV_SPLIT_WGS = 4, SIGE_KNOB_CONV_POINTWISE = 5, SIGE_KNOB_CONV_POINTWISE_W4 = 6,
-    SIGE_KNOB_CONV_PAIR_WGS = 7, SIGE_KNOB_ATTN_WGS = 8, SIGE_KNOB_COUNT = 9
+    SIGE_KNOB_CONV_PAIR_WGS = 7, SIGE_KNOB_ATTN_WGS = 8, SIGE_KNOB_DIFF_LOADS = 9, SIGE_KNOB_DIFF_WGS = 10,
+    SIGE_KNOB_CONV_DIRECT = 11, SIGE_KNOB_COUNT = 12
 } sige_knob;
 int sige_set_knob(sige_knob knob, int32_t value);
 int32_t sige_get_knob(sige_knob knob);

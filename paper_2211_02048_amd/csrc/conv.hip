@@ -258,6 +258,7 @@ static int prepare_conv(const char* who, sige_dtype dt, const sige_geom* g, int 
     a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
     a.G = p->G; a.rows = p->rows; a.trows = p->trows; a.Cc = p->Cc; a.ps = p->ps;
     a.bands = p->bands; a.ksplit = p->ksplit;
+    a.direct = knob(SIGE_KNOB_CONV_DIRECT) != 0;
     a.d_pb = fast_div(p->rows * g->block_w);
     a.d_per = fast_div(p->trows * tw);
     a.d_tw = fast_div(tw);

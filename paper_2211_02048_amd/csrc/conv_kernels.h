@@ -85,6 +85,7 @@ struct ConvArgs {
     // gated GELU folded into the epilogue (tiles out only): the Cout convolution channels come in
     // groups of 16 = 8 values followed by their 8 gates; out has Cout / 2 channels
     int glu;
+    int direct;   // shapes with swapped operands: accumulators leave straight from the registers (else through LDS)
     // divisors the kernels divide by, prepared on the host: rows * bw (a workgroup's rows per block),
     // bw, trows * tw, tw, bh * bw, and the 16-byte runs per output pixel (the reduction kernel's)
     FastDiv d_pb, d_bw, d_per, d_tw, d_pbfull, d_runs;
@@ -347,16 +348,31 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
 
     // The bias is fetched now and added when the accumulators leave the registers, so that its
     // load latency hides behind the whole K loop instead of delaying the first MFMA.
+    // Shapes whose waves do not split K multiply with the operands swapped (weights as the first,
+    // pixels as the second): a lane then owns ONE pixel of a 32 x 32 tile and registers 4g .. 4g+3 hold
+    // its channels 8g + 4*half .. + 3, so the accumulators can leave straight from the registers in
+    // 16-byte channel runs (no trip through LDS, no barrier).  Their bias is folded into the start value
+    // of the accumulators; the other shapes add it when the waves' sums meet in LDS.
+    constexpr bool SWAP = WK == 1;
     f32x16 acc[TM][TN];
     float bias_v[TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int o = (nt0 + tn) * 32 + l32;
-        bias_v[tn] = (a.bias && o < a.Cout && wk == 0 && a.partial == nullptr) ? a.bias[o] : 0.0f;
+        bias_v[tn] = (!SWAP && a.bias && o < a.Cout && wk == 0 && a.partial == nullptr) ? a.bias[o] : 0.0f;
+        f32x16 init;
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+        for (int r = 0; r < 16; ++r) init[r] = 0.0f;
+        if (SWAP && a.bias != nullptr && a.partial == nullptr) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.0f;
+            for (int g = 0; g < 4; ++g) {
+                const int ob = (nt0 + tn) * 32 + 8 * g + 4 * half;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) init[4 * g + i] = ob + i < a.Cout ? a.bias[ob + i] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = init;
     }
 
     // weight fragment pointers of this wave's Cout tiles (at tap 0, this wave's first K step)
@@ -519,7 +535,10 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) Mma<T>::run(af[tm], b[tn], acc[tm][tn]);
+            for (int tn = 0; tn < TN; ++tn) {
+                if constexpr (SWAP) Mma<T>::run(b[tn], af[tm], acc[tm][tn]);
+                else Mma<T>::run(af[tm], b[tn], acc[tm][tn]);
+            }
     };
 
     if constexpr (KK > 0) {
@@ -563,15 +582,79 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
         }
     }
 
-    // ---- epilogue.  The accumulators go through LDS (the staged tile is no longer needed) so that
-    // every thread then owns 8 consecutive output channels of one pixel: residual reads and output
-    // writes are 16-byte vectors and a pixel's channels leave in one coalesced run.
+    // ---- epilogue.  Shapes with swapped operands send whole 16-byte channel runs straight from the
+    // registers (a lane owns a pixel).  Otherwise - waves that split K, a gated GELU, partial sums of a K
+    // split over workgroups, ragged channel counts - the accumulators go through LDS (the staged tile is
+    // no longer needed) so that every thread then owns 8 consecutive output channels of one pixel.
     constexpr int N = Vec16<T>::N;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int RS = BN + 4;                                // fp32 row stride: pad keeps 16-byte alignment
     float* red = reinterpret_cast<float*>(lds);               // [WK][BM][RS]
     const bool vec_ok = emit_vec_ok<T>(a);
     const bool to_y = a.y != nullptr;                    // scatter epilogue (block origins given)
+    if constexpr (SWAP) {
+        // Straight from the registers: whole 16-byte runs, no gated GELU, no K split over workgroups
+        // (everything else takes the path through LDS below).
+        if (vec_ok && !a.glu && a.partial == nullptr && a.direct) {
+            constexpr int RL = N == 8 ? 2 : 4;            // runs of N channels this lane emits per 32 x 32 tile
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int m = (wm * TM + tm) * 32 + l32;
+                int g, p, py, px;
+                divmod(m, a.d_pb, g, p);
+                divmod(p, a.d_bw, py, px);
+                bool valid = g < a.G && py < band_rows && g0 + g < n_eff;
+                long pix = 0;
+                if (to_y && valid) {
+                    const int oy = org[2 * g] + band_row0 + py, ox = org[2 * g + 1] + px;
+                    valid = oy >= 0 && oy < a.Hout && ox >= 0 && ox < a.Wout;
+                    pix = (long)oy * a.Wout + ox;
+                }
+                const long trow = (((long)(g0 + g) * a.bh + band_row0 + py) * a.bw + px) * a.Cout;
+                const bool res = to_y && valid && (a.res_tiles != nullptr || a.res_full != nullptr);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    // the residual vectors of this tile's runs do not depend on the sums: fetched together first
+                    uint4 et[RL], ef[RL];
+#pragma unroll
+                    for (int j = 0; j < RL; ++j) {
+                        const int o = (nt0 + tn) * 32 + (N == 8 ? 16 * j + 8 * half : 8 * j + 4 * half);
+                        et[j] = ef[j] = make_uint4(0, 0, 0, 0);
+                        if (res && o < a.Cout) {
+                            if (a.res_tiles) et[j] = *(const uint4*)((const T*)a.res_tiles + trow + o);
+                            if (a.res_full) ef[j] = *(const uint4*)((const T*)a.res_full + pix * a.res_ld + o);
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < RL; ++j) {
+                        float v[N];
+                        int o;
+                        if constexpr (N == 8) {
+                            // groups 2j (channels 16j .. 16j+7 split over the lane halves) and 2j+1: the lower
+                            // half of the wave takes the first run and hands over its share of the second
+                            o = (nt0 + tn) * 32 + 16 * j + 8 * half;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float first = acc[tm][tn][8 * j + i], second = acc[tm][tn][8 * j + 4 + i];
+                                const float got = __shfl_xor(half ? first : second, 32);       // the partner's share of my run
+                                v[i] = half ? got : first;
+                                v[4 + i] = half ? second : got;
+                            }
+                        } else {
+                            o = (nt0 + tn) * 32 + 8 * j + 4 * half;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) v[i] = acc[tm][tn][4 * j + i];
+                        }
+                        if (!valid || o >= a.Cout) continue;
+                        ActParams<N> ap;
+                        load_act_params<N>(a, o, ap);
+                        emit_run<T>(a, to_y, true, trow + o, pix, o, v, ap, true, et[j], ef[j]);
+                    }
+                }
+            }
+            return;
+        }
+    }
     {
         __syncthreads();
 #pragma unroll
@@ -580,8 +663,10 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int m = (wm * TM + tm) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const int nn = (wn * TN + tn) * 32 + l32;
+                    // (swapped operands: the lane is the pixel and the registers are the channels)
+                    const int rr = 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int m = (wm * TM + tm) * 32 + (SWAP ? l32 : rr);
+                    const int nn = (wn * TN + tn) * 32 + (SWAP ? rr : l32);
                     red[(wk * BM + m) * RS + nn] = acc[tm][tn][r] + bias_v[tn];
                 }
         __syncthreads();

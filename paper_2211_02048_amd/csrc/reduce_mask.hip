@@ -288,13 +288,21 @@ static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, i
         if (V <= 64 && (V & (V - 1)) == 0) {
             int log2v = 0;
             while ((1 << log2v) < V) ++log2v;
-            // two 16-byte loads per tensor and lane in flight, up to 8192 workgroups: the finer grain
-            // measured fastest both at 32 MB and at 512 MB per call
-            constexpr int U = 2;
+            // two 16-byte loads per tensor and lane in flight, one step per workgroup up to 32768 workgroups
+            // (measured: 7.3 - 7.5 us at 32 MB whatever the grain between 1024 and 8192 workgroups and 1 - 2
+            // loads, 8.3 us with 4 loads, 11.7 us with 8; at 512 MB 77 us with 32768 workgroups, 81 us with 8192)
+            const int U = knob(SIGE_KNOB_DIFF_LOADS) > 0 ? knob(SIGE_KNOB_DIFF_LOADS) : 2;
+            const long max_wgs = knob(SIGE_KNOB_DIFF_WGS) > 0 ? knob(SIGE_KNOB_DIFF_WGS) : 32768;
             long steps = (n_vec + 256L * U - 1) / (256L * U);
-            int grid = (int)(steps < 8192 ? steps : 8192);
-            hipLaunchKernelGGL((diff_mask_pow2<T, U>), dim3(grid), dim3(256), 0, st,
-                               (const uint4*)a_orig, (const uint4*)a_edit, n_vec, log2v, tau, n_pix, mask, mk);
+            int grid = (int)(steps < max_wgs ? steps : max_wgs);
+            auto launch = [&](auto kern) {
+                hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint4*)a_orig, (const uint4*)a_edit, n_vec,
+                                   log2v, tau, n_pix, mask, mk);
+            };
+            if (U == 1) launch(diff_mask_pow2<T, 1>);
+            else if (U == 4) launch(diff_mask_pow2<T, 4>);
+            else if (U == 8) launch(diff_mask_pow2<T, 8>);
+            else launch(diff_mask_pow2<T, 2>);
             *marked = mk.n != 0;
         } else {
             long blocks = (n_pix + 3) / 4;

@@ -336,6 +336,49 @@ def test_conv_on_tiles(oracle, dtype, Cin, Cout, b, k, s, n):
     assert api.sige_get_knob("CONV_CFG") == -1
 
 
+@pytest.mark.parametrize("dtype,Cin,Cout,b,k", [("f16", 128, 128, 16, 3), ("bf16", 64, 72, 8, 1), ("f32", 32, 40, 6, 3)])
+def test_conv_epilogue_from_registers_equals_the_one_through_lds(oracle, dtype, Cin, Cout, b, k):
+    """The shapes whose waves do not split K send whole channel runs straight from the accumulator
+    registers (a lane owns a pixel); forced through LDS instead (the path ragged channel counts, the
+    gated GELU and K splits over workgroups take) they write the same bits: tiles, scatter with both
+    residuals, activated copies; and both match the oracle."""
+    rng = np.random.default_rng(Cin + Cout + b)
+    td = DT[dtype]
+    res = 5 * b - 2                               # ragged edge blocks
+    x = torch.from_numpy(rng.standard_normal((res, res, Cin)).astype(np.float32)).to(td).cuda()
+    w, bias = inputs.conv_params(rng, Cout, Cin, k, td)
+    conv = SigeConv(dev(w), bias, res, res, b, 1, k // 2)
+    bl = BlockList(conv.g, "cuda").all_active()
+    n = bl.n_host
+    resid = torch.from_numpy(rng.standard_normal((res, res, Cout)).astype(np.float32)).to(td).cuda()
+    rt = torch.from_numpy(rng.standard_normal((n, b, b, Cout)).astype(np.float32)).to(td).cuda()
+    sc = torch.from_numpy(rng.uniform(0.5, 1.5, Cout).astype(np.float32)).cuda()
+    sh = torch.from_numpy(rng.uniform(-0.5, 0.5, Cout).astype(np.float32)).cuda()
+    ws = Workspace("cuda")
+    want = oracle.conv2d(f64(x), f64(w), f64(bias), 1, k // 2)
+    rt_full = np.zeros((res, res, Cout))
+    for i, (y0, x0) in enumerate(bl.indices[:n].cpu().numpy()):
+        h, wd = min(b, res - y0), min(b, res - x0)
+        rt_full[y0:y0 + h, x0:x0 + wd] = f64(rt[i])[:h, :wd]
+    for cfg in (0, 1, 2):
+        if b * b > (128 if cfg < 2 else 64) and b > (128 if cfg < 2 else 64):
+            continue
+        outs = []
+        for direct in (None, 0):
+            with api.knobs(CONV_CFG=cfg, CONV_DIRECT=direct):
+                y = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+                copy = torch.full((res, res, Cout), float("nan"), dtype=td, device="cuda")
+                conv.forward(x, y, bl, ws, residual_tiles=rt, residual=resid, fused=True,
+                             act_outs=[(copy, sc, sh, api.ACT_SILU)])
+                tiles = conv.forward(x, None, bl, ws, scatter=False, fused=True).clone()
+                outs.append((y, copy, tiles))
+        for a_, b_ in zip(*outs):
+            assert torch.equal(a_, b_), f"shape {cfg}: registers and LDS epilogues differ"
+        assert_close(outs[0][0], want + rt_full + f64(resid), td, f"shape {cfg}: convolution + both residuals")
+        z = oracle.scale_shift_act(f64(outs[0][0]), f64(sc), f64(sh), oracle.ACT_SILU)
+        assert_close(outs[0][1], z, td, f"shape {cfg}: activated copy")
+
+
 @pytest.mark.parametrize("dtype,Cin,Cout,res,b,k", [
     ("f16", 512, 96, 8, 8, 3), ("bf16", 384, 136, 16, 16, 3), ("f32", 192, 32, 8, 8, 3),
     ("f16", 384, 64, 8, 4, 1), ("f16", 512, 33, 12, 8, 3),
