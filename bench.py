@@ -131,13 +131,23 @@ class Layer2:
         BlockList.reduce_together([self.bl3, self.bl1], a_orig=self.a_o, a_edit=self.a_e, tau=c["tau"],
                                   mask_out=self.mask, dilate=c["dilate"])
 
-    def layer(self):
+    def mark(self):
+        # the marking half of the reduction: the layer's launch builds the lists from the flags
+        from paper_2211_02048_amd.layers import BlockList
+        c = self.cfg
+        BlockList.mark_together([self.bl3, self.bl1], a_orig=self.a_o, a_edit=self.a_e, tau=c["tau"],
+                                mask_out=self.mask, dilate=c["dilate"])
+
+    def layer(self, marked=False):
         api = self.api
         if self.fused:   # both convolutions read a_e and are independent: handed over together (one launch)
             c3, _ = self.main.fused_call(self.a_e, self.y_main, self.bl3, self.ws, scale=self.scale, shift=self.shift,
                                          act=api.ACT_SILU, tag="main")
             c1, _ = self.short.fused_call(self.a_e, self.y_short, self.bl1, self.ws, tag="short")
-            api.sige_fused_conv_pair(c3, c1)
+            if marked:
+                api.sige_fused_conv_pair_marked(c3, c1, [self.bl3.desc(), self.bl1.desc()])
+            else:
+                api.sige_fused_conv_pair(c3, c1)
             return
         self.main.forward(self.a_e, self.y_main, self.bl3, self.ws, scale=self.scale, shift=self.shift,
                           act=api.ACT_SILU, fused=self.fused)
@@ -161,8 +171,12 @@ class Layer2:
         self.bl1 = BlockList(self.short.g, self.a_o.device, max_blocks=cap)
 
         def body():
-            self.reduce()
-            self.layer()   # n_host = -1: counts are read on the device
+            if self.fused:     # two launches: difference + block flags, then lists + both convolutions
+                self.mark()
+                self.layer(marked=True)
+            else:
+                self.reduce()
+                self.layer()   # n_host = -1: counts are read on the device
         s = torch.cuda.Stream()
         s.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(s):

@@ -92,8 +92,9 @@ typedef struct {
  * blocks, even when it exceeds max_blocks.  The block grid may hold at most
  * 131072 blocks (SIGE_ERR_CAPACITY beyond).
  * workspace: optional device scratch of sige_reduce_mask_workspace_bytes(g) bytes,
- * 16-byte aligned, which the caller zeroes ONCE before the first use (every call leaves
- * it zero again); with it the marked pixels set per-block flags in parallel.  Calls that
+ * 16-byte aligned, which the caller zeroes ONCE before the first use and whose contents belong
+ * to the library from then on (per-block flags, which every call leaves cleared for the next,
+ * and two bookkeeping words); with it the marked pixels set per-block flags in parallel.  Calls that
  * share a workspace must not overlap.  NULL (or too small): one workgroup tests every
  * block - same results, slower on large grids.                                     */
 int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dtype dt,
@@ -123,7 +124,7 @@ int sige_reduce_mask_noalloc(const void* a_orig, const void* a_edit, sige_dtype 
                              int32_t* indices, int32_t max_blocks, int32_t* count, void* stream);
 
 /* One list of sige_reduce_mask_lists: a layer geometry, where its list goes, and its own
- * flag workspace (required here; zeroed once by the caller, left zero by every call). */
+ * flag workspace (required here; 16-byte aligned, zeroed once by the caller, left zero by every call). */
 typedef struct {
     sige_geom g;
     int32_t*  indices;          /* device [max_blocks][2]                          */
@@ -145,6 +146,21 @@ int sige_reduce_mask_lists(const void* a_orig, const void* a_edit, sige_dtype dt
                            const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
                            const sige_block_list* lists, int32_t n_lists,
                            uint8_t* mask_out, void* stream);
+
+/* The first half of sige_reduce_mask_lists (Sec. 3.1 difference mask; Sec. 3.2 pooling, dilation and
+ * the block test): the mask is written and every list's per-block flags are set in its workspace,
+ * but the ordered lists are NOT built (indices and count are not touched).  The second half -
+ * flags to row-major list, flags cleared - is done by the consumer: sige_fused_conv_pair_marked.
+ * On this part a dependent kernel launch costs more than the compaction's work, so a step that
+ * consists of one reduction and one layer saves a launch this way.  Every call must be followed by
+ * exactly one consumer of the same lists before the workspaces are used again (a second marking
+ * pass in between would add its flags to the first's).  Arguments and errors as for
+ * sige_reduce_mask_lists; every list needs its workspace.                                   */
+int sige_mark_blocks(const void* a_orig, const void* a_edit, sige_dtype dt,
+                     int32_t Hm, int32_t Wm, int32_t C, float tau,
+                     const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
+                     const sige_block_list* lists, int32_t n_lists,
+                     uint8_t* mask_out, void* stream);
 
 /* Fig. "method" Gather, with Sec. 3.2 "Pre-computing normalization parameters" and
  * "Kernel fusion" folded in:
@@ -325,6 +341,19 @@ typedef struct {
 } sige_fused_conv_call;
 int sige_fused_conv_pair(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
                          void* stream);
+
+/* sige_fused_conv_pair on lists that sige_mark_blocks left marked: marked is a HOST array of two
+ * entries, marked[i] the list of call i (same geometry; call i's indices, count and max_blocks must be
+ * marked[i]'s; n_blocks must be -1, the count is not known to the host).  Same results as the
+ * compaction of sige_reduce_mask_lists followed by sige_fused_conv_pair: the ordered lists and
+ * their counts are stored in marked[i].indices / count as there, the workspaces are ready for the
+ * next reduction or marking pass on return, the outputs are bit-identical.  When the two calls share a launch and each block grid
+ * has at most 1024 blocks, the workgroups build the lists themselves from the flags (no
+ * compaction launch; the workspace's second half and its phase words let the flags of this step
+ * stay in place while the half for the next step is cleared); otherwise the compaction pass
+ * runs first.                                                                              */
+int sige_fused_conv_pair_marked(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
+                                const sige_block_list* marked, void* stream);
 
 /* Fig. "sige-attention" / Sec. 3.2 "Extension to attention layers": attention for the
  * edited query tokens only, against all T keys and values (the caches with the

@@ -24,7 +24,8 @@ STATUS = {0: "SIGE_OK", 1: "SIGE_ERR_INVALID_ARG", 2: "SIGE_ERR_UNSUPPORTED", 3:
 
 EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_mask_lists", "sige_gather", "sige_gather_modulated", "sige_conv", "sige_conv_workspace_bytes", "sige_conv_geglu", "sige_conv_scatter", "sige_scatter", "sige_fused_conv", "sige_fused_conv_pair", "sige_sparse_attn", "sige_sparse_attn_blocks",
            "sige_sparse_attn_workspace_bytes", "sige_token_norm", "sige_gather_token_norm", "sige_geglu", "sige_packed_weight_bytes", "sige_pack_weight",
-           "sige_gn_stats", "sige_last_error", "sige_version", "sige_set_knob", "sige_get_knob", "sige_conv_plan", "sige_reduce_mask_noalloc"]
+           "sige_gn_stats", "sige_last_error", "sige_version", "sige_set_knob", "sige_get_knob", "sige_conv_plan", "sige_reduce_mask_noalloc", "sige_mark_blocks",
+           "sige_fused_conv_pair_marked"]
 
 # sige_knob of the header
 KNOBS = {"CONV_CFG": 0, "CONV_KC": 1, "CONV_SPLIT": 2, "CONV_HALF": 3, "CONV_SPLIT_WGS": 4, "CONV_POINTWISE": 5,
@@ -102,6 +103,7 @@ def lib() -> ctypes.CDLL:
         L.sige_reduce_mask_noalloc.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32, gp, vp, vp, i32, vp, vp]
         L.sige_reduce_mask_lists.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, i32, i32,
                                              ctypes.POINTER(BlockListDesc), i32, vp, vp]
+        L.sige_mark_blocks.argtypes = L.sige_reduce_mask_lists.argtypes
         L.sige_reduce_mask_workspace_bytes.restype = ctypes.c_size_t
         L.sige_reduce_mask_workspace_bytes.argtypes = [gp]
         L.sige_gather.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, vp, vp]
@@ -114,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.sige_fused_conv.argtypes = [vp, i32, i32, i32, i32, gp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp,
                                       i32, vp, i32, vp, vp, i32, vp, sz, vp]
         L.sige_fused_conv_pair.argtypes = [ctypes.POINTER(FusedConvCall), ctypes.POINTER(FusedConvCall), vp]
+        L.sige_fused_conv_pair_marked.argtypes = [ctypes.POINTER(FusedConvCall), ctypes.POINTER(FusedConvCall),
+                                                  ctypes.POINTER(BlockListDesc), vp]
         L.sige_scatter.argtypes = [vp, i32, gp, i32, vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
         L.sige_sparse_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, vp, sz, vp]
         L.sige_sparse_attn_workspace_bytes.argtypes = [i32, i32, i32, i32]
@@ -184,7 +188,7 @@ def sige_reduce_mask_noalloc(g: Geom, indices, count, *, a_orig=None, a_edit=Non
 
 
 def sige_reduce_mask_lists(lists, *, a_orig=None, a_edit=None, tau=0.0, mask_in=None, mask_out=None,
-                           pool_log2=0, dilate=0):
+                           pool_log2=0, dilate=0, mark_only=False):
     """One mask, several layer geometries: lists = [(g, indices, count, max_blocks, workspace), ...]."""
     if a_orig is not None:
         Hm, Wm, C = a_orig.shape
@@ -192,6 +196,20 @@ def sige_reduce_mask_lists(lists, *, a_orig=None, a_edit=None, tau=0.0, mask_in=
     else:
         Hm, Wm = mask_in.shape
         C, dt = 0, SIGE_F32
+    arr = block_list_array(lists)
+    fn = lib().sige_mark_blocks if mark_only else lib().sige_reduce_mask_lists
+    _check(fn(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2, dilate, arr, len(lists),
+              _ptr(mask_out), _stream()))
+
+
+def sige_mark_blocks(lists, **kw):
+    """The first half of sige_reduce_mask_lists: mask and per-block flags, no lists (sige_fused_conv_pair_marked
+    builds them)."""
+    sige_reduce_mask_lists(lists, mark_only=True, **kw)
+
+
+def block_list_array(lists):
+    """[(g, indices, count, max_blocks, workspace), ...] as a host array of sige_block_list."""
     arr = (BlockListDesc * max(len(lists), 1))()
     for d, (g, indices, count, mb, ws) in zip(arr, lists):
         d.g = g
@@ -199,8 +217,8 @@ def sige_reduce_mask_lists(lists, *, a_orig=None, a_edit=None, tau=0.0, mask_in=
         d.max_blocks = indices.shape[0] if mb is None else mb
         d.workspace = None if ws is None else ws.data_ptr()
         d.workspace_bytes = 0 if ws is None else ws.numel() * ws.element_size()
-    _check(lib().sige_reduce_mask_lists(_ptr(a_orig), _ptr(a_edit), dt, Hm, Wm, C, tau, _ptr(mask_in), pool_log2,
-                                        dilate, arr, len(lists), _ptr(mask_out), _stream()))
+    arr._keep = lists
+    return arr
 
 
 def sige_gather(x, g: Geom, indices, count, tiles, *, n_blocks=-1, scale=None, shift=None, act=ACT_NONE,
@@ -366,6 +384,13 @@ def fused_conv_call(x, g: Geom, indices, count, Cin, Cout, packed_weight, bias, 
 def sige_fused_conv_pair(first: FusedConvCall, second: FusedConvCall):
     """Two independent fused calls; one launch when both take the few-block kernel shape."""
     _check(lib().sige_fused_conv_pair(ctypes.byref(first), ctypes.byref(second), _stream()))
+
+
+def sige_fused_conv_pair_marked(first: FusedConvCall, second: FusedConvCall, marked):
+    """sige_fused_conv_pair on lists that sige_mark_blocks left marked (marked: the two lists as for
+    sige_reduce_mask_lists); the launch builds the ordered lists itself when it can."""
+    arr = marked if isinstance(marked, ctypes.Array) else block_list_array(marked)
+    _check(lib().sige_fused_conv_pair_marked(ctypes.byref(first), ctypes.byref(second), arr, _stream()))
 
 
 def sige_token_norm(x, y, C, *, n_rows=-1, count=None, rows_per_count=0, max_rows=None, gamma=None, beta=None,

@@ -6,6 +6,7 @@
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <string.h>
 
 #include "sige.h"
 
@@ -33,6 +34,10 @@ void clear_error();
 // read on the host when a call is planned.
 extern int g_knobs[SIGE_KNOB_COUNT];
 inline int knob(sige_knob k) { return g_knobs[k]; }
+
+// reduce_mask.hip: the compaction pass over lists that sige_mark_blocks left marked (flags -> ordered
+// lists, flags cleared), for consumers of marked lists that cannot build the lists themselves
+int compact_marked_lists(const char* who, const sige_block_list* lists, int n, hipStream_t st);
 
 inline size_t dtype_size(sige_dtype dt) { return dt == SIGE_F32 ? 4 : 2; }
 inline bool dtype_ok(sige_dtype dt) { return dt == SIGE_F32 || dt == SIGE_F16 || dt == SIGE_BF16; }

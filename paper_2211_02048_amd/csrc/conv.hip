@@ -520,16 +520,33 @@ extern "C" int sige_fused_conv(const void* x, sige_dtype dt, int32_t Cin, int32_
     return run_conv(who, dt, g, th, tw, Cin, Cout, max_blocks, n_blocks, nl, a, workspace, workspace_bytes, stream);
 }
 
-extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
-                                    void* stream)
+// Both pair entry points.  marks == nullptr: the calls bring their lists.  Otherwise marks[i] is the list
+// of call i as the marking pass left it (flags set, list not built).
+static int fused_pair(const char* who, const sige_fused_conv_call* first, const sige_fused_conv_call* second,
+                      const sige_block_list* marks, void* stream)
 {
-    clear_error();
-    const char* who = "sige_fused_conv_pair";
     SIGE_REQUIRE(first && second, SIGE_ERR_INVALID_ARG, "%s: two calls are required", who);
     const sige_fused_conv_call* c[2] = {first, second};
     ConvArgs a[2];
     ConvPlan p[2];
     int th[2], tw[2], nl[2], pw[2] = {0, 0};
+    long nb[2] = {0, 0};
+    if (marks != nullptr) {
+        for (int i = 0; i < 2; ++i) {
+            const sige_block_list& L = marks[i];
+            SIGE_REQUIRE(c[i]->g != nullptr && memcmp(c[i]->g, &L.g, sizeof(sige_geom)) == 0, SIGE_ERR_INVALID_ARG,
+                         "%s: call %d and its marked list differ in geometry", who, i);
+            SIGE_REQUIRE(L.indices != nullptr && L.count != nullptr && c[i]->indices == L.indices &&
+                             c[i]->count == L.count && c[i]->max_blocks == L.max_blocks,
+                         SIGE_ERR_INVALID_ARG, "%s: call %d must read the list that its marked list describes", who, i);
+            SIGE_REQUIRE(c[i]->n_blocks < 0, SIGE_ERR_INVALID_ARG,
+                         "%s: the block count of call %d is not known to the host yet (n_blocks must be -1)", who, i);
+            SIGE_REQUIRE(L.workspace != nullptr && L.workspace_bytes >= sige_reduce_mask_workspace_bytes(&L.g) &&
+                             (reinterpret_cast<uintptr_t>(L.workspace) & 15u) == 0,
+                         SIGE_ERR_INVALID_ARG, "%s: list %d needs its 16-byte aligned flag workspace", who, i);
+        }
+        SIGE_REQUIRE(marks[0].workspace != marks[1].workspace, SIGE_ERR_INVALID_ARG, "%s: the lists share a workspace", who);
+    }
     for (int i = 0; i < 2; ++i) {
         if (int rc = fused_conv_fill(who, c[i]->x, c[i]->dt, c[i]->Cin, c[i]->x_ld, c[i]->up, c[i]->g, c[i]->indices,
                                      c[i]->count, c[i]->max_blocks, c[i]->n_blocks, c[i]->scale, c[i]->shift,
@@ -554,10 +571,31 @@ extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sig
     const bool together = nl[0] > 0 && nl[1] > 0 && wgs_both <= pair_max && !pw[0] && !pw[1] && c[0]->dt == c[1]->dt && a[0].k == 3 &&
                           a[1].k == 1 && p[0].cfg == 3 && p[1].cfg == 3 && p[0].ksplit == 1 && p[1].ksplit == 1 &&
                           p[0].kc == p[1].kc && (p[0].kc == 8 || p[0].kc == 4);
+    bool scan = false;
+    if (marks != nullptr) {
+        // the one-launch kernel builds the lists itself when a workgroup can scan a whole block grid
+        // (1024 flags); otherwise the compaction pass runs first and the calls read its lists
+        scan = together;
+        for (int i = 0; i < 2; ++i) {
+            const sige_geom& g = marks[i].g;
+            const long nbx = (g.W_out + g.block_w - 1) / g.block_w, nby = (g.H_out + g.block_h - 1) / g.block_h;
+            nb[i] = nbx * nby;
+            scan = scan && nb[i] <= 1024;
+            a[i].mk_flags = (uint8_t*)marks[i].workspace;
+            a[i].mk_half = (int)((nb[i] + 15) & ~15L);
+            a[i].mk_indices = marks[i].indices;
+            a[i].mk_count = marks[i].count;
+            a[i].mk_nb = (int)nb[i];
+            a[i].mk_nbx = (int)nbx;
+        }
+        if (!scan)
+            if (int rc = compact_marked_lists(who, marks, 2, st)) return rc;
+    }
     if (together) {
         const sige_dtype dt = c[0]->dt;
-        return dt == SIGE_F32 ? launch_pair<float>(a[0], p[0], a[1], p[1], st)
-               : dt == SIGE_F16 ? launch_pair<f16>(a[0], p[0], a[1], p[1], st) : launch_pair<bf16>(a[0], p[0], a[1], p[1], st);
+        return dt == SIGE_F32 ? launch_pair<float>(a[0], p[0], a[1], p[1], scan, st)
+               : dt == SIGE_F16 ? launch_pair<f16>(a[0], p[0], a[1], p[1], scan, st)
+                                : launch_pair<bf16>(a[0], p[0], a[1], p[1], scan, st);
     }
     for (int i = 0; i < 2; ++i) {
         if (nl[i] == 0) continue;
@@ -566,3 +604,18 @@ extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sig
     return SIGE_OK;
 }
 
+extern "C" int sige_fused_conv_pair(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
+                                    void* stream)
+{
+    clear_error();
+    return fused_pair("sige_fused_conv_pair", first, second, nullptr, stream);
+}
+
+extern "C" int sige_fused_conv_pair_marked(const sige_fused_conv_call* first, const sige_fused_conv_call* second,
+                                           const sige_block_list* marked, void* stream)
+{
+    clear_error();
+    const char* who = "sige_fused_conv_pair_marked";
+    SIGE_REQUIRE(marked != nullptr, SIGE_ERR_INVALID_ARG, "%s: the two marked lists are required", who);
+    return fused_pair(who, first, second, marked, stream);
+}

@@ -86,6 +86,15 @@ struct ConvArgs {
     // groups of 16 = 8 values followed by their 8 gates; out has Cout / 2 channels
     int glu;
     int direct;   // shapes with swapped operands: accumulators leave straight from the registers (else through LDS)
+    // Marked mode (conv_pair_kernel only): the block list is not given but built by every workgroup
+    // from the per-block flags that the marking pass left (mk_nb of them, mk_nbx per block row); the
+    // call's first workgroup also stores the ordered list and its length where a compaction pass
+    // would have.  `indices` is then non-null but not read.  mk_flags is the list's flag workspace:
+    // two halves of mk_half bytes, then the phase words (see reduce_mask.hip).
+    uint8_t* mk_flags;
+    int32_t* mk_indices;
+    int32_t* mk_count;
+    int mk_nb, mk_nbx, mk_half;
     // divisors the kernels divide by, prepared on the host: rows * bw (a workgroup's rows per block),
     // bw, trows * tw, tw, bh * bw, and the 16-byte runs per output pixel (the reduction kernel's)
     FastDiv d_pb, d_bw, d_per, d_tw, d_pbfull, d_runs;
@@ -282,7 +291,7 @@ constexpr int MAX_G = 256;   // most blocks one workgroup can hold (1x1 blocks i
 // phase has nothing to overlap its LDS and L2 latencies with.
 // (The body is a device function so that two calls can share one launch, see conv_pair_kernel;
 // bx, by, bz are the workgroup's coordinates inside its own call's grid.)
-template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
+template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK, bool MARKED = false>
 __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const int by, const int bz)
 {
     constexpr int NT = 64 * WM * WN * WK;                     // threads per workgroup
@@ -308,18 +317,78 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
     // load of the count are independent and are issued together (row n exists for n < max_blocks).
     __shared__ int org[2 * MAX_G];
     const int g0 = bz * a.G;
-    int oy = 0, ox = 0;
-    if (a.indices != nullptr && threadIdx.x < a.G) {
-        const int n = min(g0 + (int)threadIdx.x, a.max_blocks - 1);
-        oy = a.indices[2 * n];
-        ox = a.indices[2 * n + 1];
-    }
-    int n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
-    asm volatile("" : "+v"(oy), "+v"(ox), "+v"(n_eff));
-    if (g0 >= n_eff) return;
-    if (a.indices != nullptr) {
-        if (threadIdx.x < a.G) { org[2 * threadIdx.x] = oy; org[2 * threadIdx.x + 1] = ox; }
+    int n_eff;
+    if constexpr (MARKED) {
+        // Marked mode: the ordered list is the row-major sequence of the set flags (Sec. 3.2, the block
+        // reduction).  A lane takes four flags (one 32-bit word: the workspace is 16-byte aligned and
+        // padded), the lanes before it are counted with ballots of the bits of its own count, the waves
+        // before it through LDS.  The workgroup keeps the origins of its own G slots; the first one of
+        // the call stores the whole list and the count.
+        // The flags of this step are in the half that the marking pass used (it left the phase it
+        // read in the second phase word; both halves are fetched together with it, one round trip).
+        // Nobody touches the other half during this step, so the call's first workgroup clears it
+        // and advances the first phase word: the next marking pass finds a clean half without any
+        // workgroup having to wait for the others to finish reading this one.
+        static_assert(NT == 256, "marked mode is built for the four-wave shape");
+        __shared__ int wtot[4];
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+        const uint32_t* words = reinterpret_cast<const uint32_t*>(a.mk_flags);
+        const int hw = a.mk_half >> 2;
+        uint32_t w0 = 0u, w1 = 0u;
+        if (4 * tid < a.mk_nb) { w0 = words[tid]; w1 = words[hw + tid]; }
+        const uint32_t phase = words[2 * hw + 1];
+        const uint32_t w = (phase & 1u) ? w1 : w0;
+        const bool writer = bx == 0 && by == 0 && bz == 0;
+        if (writer) {
+            uint4* other = reinterpret_cast<uint4*>(a.mk_flags + ((phase & 1u) ? 0 : a.mk_half));
+            for (int i = tid; i < (a.mk_half >> 4); i += NT) other[i] = make_uint4(0, 0, 0, 0);
+            if (tid == 0) reinterpret_cast<uint32_t*>(a.mk_flags)[2 * hw] = phase + 1u;
+        }
+        int f[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = ((w >> (8 * j)) & 0xffu) != 0u && 4 * tid + j < a.mk_nb;
+        const int c = f[0] + f[1] + f[2] + f[3];
+        const unsigned long long b0 = __ballot(c & 1), b1 = __ballot(c & 2), b2 = __ballot(c & 4);
+        const unsigned long long lt = (1ull << lane) - 1ull;
+        const int pre = __popcll(b0 & lt) + 2 * __popcll(b1 & lt) + 4 * __popcll(b2 & lt);
+        if (lane == 0) wtot[wave] = __popcll(b0) + 2 * __popcll(b1) + 4 * __popcll(b2);
         __syncthreads();
+        int off = 0, total = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = wtot[i];
+            if (i < wave) off += t;
+            total += t;
+        }
+        int slot = off + pre;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (f[j]) {
+                const int blk = 4 * tid + j, byy = blk / a.mk_nbx;
+                const int oy = byy * a.bh, ox = (blk - byy * a.mk_nbx) * a.bw;
+                if (slot >= g0 && slot < g0 + a.G) { org[2 * (slot - g0)] = oy; org[2 * (slot - g0) + 1] = ox; }
+                if (writer && slot < a.max_blocks) { a.mk_indices[2 * slot] = oy; a.mk_indices[2 * slot + 1] = ox; }
+                ++slot;
+            }
+        }
+        if (writer && tid == 0) *a.mk_count = total;
+        n_eff = min(total, a.max_blocks);
+        __syncthreads();
+        if (g0 >= n_eff) return;
+    } else {
+        int oy = 0, ox = 0;
+        if (a.indices != nullptr && threadIdx.x < a.G) {
+            const int n = min(g0 + (int)threadIdx.x, a.max_blocks - 1);
+            oy = a.indices[2 * n];
+            ox = a.indices[2 * n + 1];
+        }
+        n_eff = effective_blocks(a.count, a.max_blocks, a.n_host);
+        asm volatile("" : "+v"(oy), "+v"(ox), "+v"(n_eff));
+        if (g0 >= n_eff) return;
+        if (a.indices != nullptr) {
+            if (threadIdx.x < a.G) { org[2 * threadIdx.x] = oy; org[2 * threadIdx.x + 1] = ox; }
+            __syncthreads();
+        }
     }
     const int split = by / a.bands, band = by - split * a.bands;
     const int band_row0 = band * a.rows;                      // first output row of the band
@@ -734,7 +803,10 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
 // Two independent calls in ONE launch: a 3x3 convolution and a 1x1 convolution that both take the
 // 64 x 32 shape whose four waves split K (few active blocks: a ResBlock's convolution and its
 // shortcut, which read the same tensor).
-template <typename T, int KC>
+// MARKED: the launch follows the marking pass directly, without the compaction pass in between (on
+// this part a dependent launch costs more than the compaction's work): every workgroup derives its
+// blocks from the flags (see conv_body).
+template <typename T, int KC, bool MARKED>
 __global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int wgs_a, int xa, int ya, int xb,
                                                            int yb)
 {
@@ -742,10 +814,10 @@ __global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs 
     const int id = blockIdx.x;
     if (id < wgs_a) {
         const int zy = id / xa;
-        conv_body<T, 2, 1, 1, 1, 4, KC, 9>(a, id - zy * xa, zy % ya, zy / ya);
+        conv_body<T, 2, 1, 1, 1, 4, KC, 9, MARKED>(a, id - zy * xa, zy % ya, zy / ya);
     } else {
         const int j = id - wgs_a, zy = j / xb;
-        conv_body<T, 2, 1, 1, 1, 4, KC, 1>(b, j - zy * xb, zy % yb, zy / yb);
+        conv_body<T, 2, 1, 1, 1, 4, KC, 1, MARKED>(b, j - zy * xb, zy % yb, zy / yb);
     }
 }
 
@@ -1240,7 +1312,8 @@ int launch_reduce(const ConvArgs& a, int nl, hipStream_t st)
 }
 
 template <typename T>
-int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const ConvPlan& pb, hipStream_t st)
+int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const ConvPlan& pb, bool marked,
+                hipStream_t st)
 {
     const size_t lds = std::max(pa.lds, pb.lds);
     const int wgs_a = pa.slabs * pa.bands * pa.groups, wgs_b = pb.slabs * pb.bands * pb.groups;
@@ -1255,7 +1328,8 @@ int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const 
         SIGE_LAUNCH_CHECK("sige_fused_conv_pair");
         return (int)SIGE_OK;
     };
-    return pa.kc == 8 ? launch(conv_pair_kernel<T, 8>) : launch(conv_pair_kernel<T, 4>);
+    if (marked) return pa.kc == 8 ? launch(conv_pair_kernel<T, 8, true>) : launch(conv_pair_kernel<T, 4, true>);
+    return pa.kc == 8 ? launch(conv_pair_kernel<T, 8, false>) : launch(conv_pair_kernel<T, 4, false>);
 }
 
 // Re-lays an OIHW weight into the fragment order the kernels read.
@@ -1273,7 +1347,8 @@ int launch_pack(const void* w_oihw, int Cout, int Cin, int k, long n, void* pack
     KW template int launch_conv<T>(const ConvArgs&, const ConvPlan&, hipStream_t);                              \
     KW template int launch_pointwise<T>(const ConvArgs&, int, int, hipStream_t);                                \
     KW template int launch_reduce<T>(const ConvArgs&, int, hipStream_t);                                        \
-    KW template int launch_pair<T>(const ConvArgs&, const ConvPlan&, const ConvArgs&, const ConvPlan&, hipStream_t); \
+    KW template int launch_pair<T>(const ConvArgs&, const ConvPlan&, const ConvArgs&, const ConvPlan&, bool, \
+                                   hipStream_t);                                                            \
     KW template int launch_pack<T>(const void*, int, int, int, long, void*, hipStream_t);
 
 }  // namespace sige

@@ -10,6 +10,13 @@
 // dilated tile contains it - done by the difference kernel itself, or by a vectorised
 // scan of a ready mask - and one small workgroup compacts the flags into the row-major
 // list with an ordered ballot/popcount prefix sum and clears them for the next call.
+// The flag workspace has two halves and two phase words behind them.  The marking pass writes into
+// the half that the first phase word selects and copies that word into the second; the compaction
+// reads and clears the same half.  A consumer that builds the list itself (conv_pair_kernel in
+// marked mode, which follows the marking pass without a compaction launch) cannot clear the half its
+// workgroups are still reading: it clears the OTHER half and advances the first phase word instead,
+// so that the next marking pass finds a clean half.  Each phase word is written only by a kernel
+// none of whose workgroups reads it.
 // Without a workspace a single workgroup tests every block against the pooled, dilated
 // mask (flags in LDS) and compacts.
 #include "common.h"
@@ -31,7 +38,9 @@ __device__ __forceinline__ bool vec_differs(const uint4& o, const uint4& e, floa
 }
 
 struct MarkArgs {
-    uint8_t* flags;  // one byte per block of the grid, all zero on entry; NULL = do not mark
+    uint8_t* flags;  // the flag workspace: two halves of `half` bytes (one byte per block of the grid, padded to
+                     // 16; the half in use is all zero on entry), then the two phase words; NULL = do not mark
+    int half;
     int Wm, pool_log2, dilate;
     int sy, sx;      // block pitch in input pixels: block * stride
     int th, tw, pad, nby, nbx;
@@ -43,6 +52,20 @@ struct MarkSet {
     int n;           // 0 = do not mark
     MarkArgs m[MAX_LISTS];
 };
+
+__device__ __forceinline__ uint32_t phase_of(const uint8_t* flags, int half)
+{
+    return *reinterpret_cast<const uint32_t*>(flags + 2 * half);
+}
+
+// The first thread of a marking launch leaves the phase it marks in where consumers look for it.
+__device__ __forceinline__ void publish_phase(const MarkSet& mk)
+{
+    for (int i = 0; i < mk.n; ++i) {
+        uint32_t* p = reinterpret_cast<uint32_t*>(mk.m[i].flags + 2 * mk.m[i].half);
+        p[1] = p[0];
+    }
+}
 
 // Sets the flag of every block whose input tile, grown by the dilation radius, contains the
 // pooled position of the marked source pixel `pix`.  In input coordinates block b covers
@@ -60,8 +83,9 @@ __device__ __forceinline__ void mark_blocks(const MarkArgs& m, int py, int px)
     bx0 = max(bx0, 0);
     // Plain stores (the race is benign: every writer stores 1).  Looking at the flag first would
     // save stores but puts a dependent global load on the path of every marking lane.
+    uint8_t* flags = m.flags + (phase_of(m.flags, m.half) & 1u) * m.half;
     for (int by = by0; by <= by1; ++by)
-        for (int bx = bx0; bx <= bx1; ++bx) m.flags[by * m.nbx + bx] = 1;
+        for (int bx = bx0; bx <= bx1; ++bx) flags[by * m.nbx + bx] = 1;
 }
 
 // V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
@@ -77,6 +101,7 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
     const int V = 1 << log2v;
     const int ppw = 64 >> log2v;  // pixels per wave step
     const unsigned long long gmask = V == 64 ? ~0ull : ((1ull << V) - 1ull);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish_phase(mk);
     for (long base = wave * (64L * U); base < n_vec; base += n_waves * (64L * U)) {
         uint4 o[U], e[U];
 #pragma unroll
@@ -225,6 +250,7 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
                                                              int words_per_row, int aligned, MarkSet mk)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) publish_phase(mk);
     if (t >= Hm * words_per_row) return;
     const int Wm = mk.m[0].Wm;
     const int y = t / words_per_row, x0 = (t - y * words_per_row) * 4;
@@ -245,7 +271,8 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
 
 struct ListSet {
     ListArgs a[MAX_LISTS];
-    uint8_t* flags[MAX_LISTS];
+    uint8_t* flags[MAX_LISTS];   // the flag workspaces (two halves, phase words)
+    int half[MAX_LISTS];
 };
 
 // Flags (global) -> ordered list, one workgroup per list; the flags are cleared again for the
@@ -254,7 +281,8 @@ __global__ __launch_bounds__(1024) void compact_ws_kernel(ListSet s)
 {
     __shared__ int wave_tot[16];
     const ListArgs& a = s.a[blockIdx.x];
-    uint8_t* flags = s.flags[blockIdx.x];
+    const int half = s.half[blockIdx.x];
+    uint8_t* flags = s.flags[blockIdx.x] + (phase_of(s.flags[blockIdx.x], half) & 1u) * half;
     const int nb = a.nby * a.nbx;
     compact_flags<1024>(a, flags, nb, wave_tot);
     for (int i = threadIdx.x; i < nb; i += 1024) flags[i] = 0;
@@ -320,6 +348,27 @@ static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, i
     return SIGE_OK;
 }
 
+// The second half of a reduction whose first half was sige_mark_blocks: flags -> ordered lists, flags cleared.
+int compact_marked_lists(const char* who, const sige_block_list* lists, int n, hipStream_t st)
+{
+    SIGE_REQUIRE(n >= 1 && n <= MAX_LISTS, SIGE_ERR_INVALID_ARG, "%s: between 1 and %d lists", who, MAX_LISTS);
+    ListSet ls;
+    for (int i = 0; i < n; ++i) {
+        const sige_geom* g = &lists[i].g;
+        ListArgs& a = ls.a[i];
+        a = ListArgs{};
+        a.bh = g->block_h; a.bw = g->block_w;
+        a.nby = (g->H_out + g->block_h - 1) / g->block_h;
+        a.nbx = (g->W_out + g->block_w - 1) / g->block_w;
+        a.indices = lists[i].indices; a.max_blocks = lists[i].max_blocks; a.count = lists[i].count;
+        ls.flags[i] = (uint8_t*)lists[i].workspace;
+        ls.half[i] = (a.nby * a.nbx + 15) & ~15;
+    }
+    hipLaunchKernelGGL(compact_ws_kernel, dim3(n), dim3(1024), 0, st, ls);
+    SIGE_LAUNCH_CHECK(who);
+    return SIGE_OK;
+}
+
 }  // namespace sige
 
 using namespace sige;
@@ -328,7 +377,8 @@ extern "C" size_t sige_reduce_mask_workspace_bytes(const sige_geom* g)
 {
     if (g == nullptr || g->block_h <= 0 || g->block_w <= 0 || g->H_out <= 0 || g->W_out <= 0) return 0;
     const size_t nb = (size_t)((g->H_out + g->block_h - 1) / g->block_h) * ((g->W_out + g->block_w - 1) / g->block_w);
-    return (nb + 15) & ~(size_t)15;
+    // two halves of one flag per block, then the phase words
+    return 2 * ((nb + 15) & ~(size_t)15) + 16;
 }
 
 // Shared by both entry points: n lists (n >= 1; n == 0 only for the mask-only mode) built from one
@@ -336,7 +386,7 @@ extern "C" size_t sige_reduce_mask_workspace_bytes(const sige_geom* g)
 static int reduce_lists(const char* who, const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm,
                         int32_t Wm, int32_t C, float tau, const uint8_t* mask_in, int32_t pool_log2,
                         int32_t dilate, const sige_block_list* lists, int n, const sige_geom* g_mask_only,
-                        uint8_t* mask_out, void* stream)
+                        uint8_t* mask_out, void* stream, bool mark_only = false)
 {
     const bool diff_mode = a_orig != nullptr || a_edit != nullptr;
     SIGE_REQUIRE(diff_mode != (mask_in != nullptr), SIGE_ERR_INVALID_ARG,
@@ -373,6 +423,7 @@ static int reduce_lists(const char* who, const void* a_orig, const void* a_edit,
                          "%s: lists %d and %d share a workspace", who, j, i);
         MarkArgs& m = mk.m[i];
         m.flags = (uint8_t*)L.workspace;
+        m.half = (int)((nby * nbx + 15) & ~15L);
         m.Wm = Wm; m.pool_log2 = pool_log2; m.dilate = dilate;
         m.sy = g->block_h * g->stride; m.sx = g->block_w * g->stride;
         m.th = th; m.tw = tw; m.pad = g->pad; m.nby = (int)nby; m.nbx = (int)nbx;
@@ -383,6 +434,7 @@ static int reduce_lists(const char* who, const void* a_orig, const void* a_edit,
         a.nby = (int)nby; a.nbx = (int)nbx;
         a.indices = L.indices; a.max_blocks = L.max_blocks; a.count = L.count;
         ls.flags[i] = (uint8_t*)L.workspace;
+        ls.half[i] = m.half;
     }
     SIGE_REQUIRE(n <= 1 || all_ws, SIGE_ERR_INVALID_ARG,
                  "%s: every list needs its own zeroed, 16-byte aligned workspace of "
@@ -421,10 +473,12 @@ static int reduce_lists(const char* who, const void* a_orig, const void* a_edit,
                                Hm, wpr, aligned, mk);
             SIGE_LAUNCH_CHECK("sige_reduce_mask(mark)");
         }
+        if (mark_only) return SIGE_OK;     // the consumer of the marked lists compacts
         hipLaunchKernelGGL(compact_ws_kernel, dim3(n), dim3(1024), 0, st, ls);
         SIGE_LAUNCH_CHECK("sige_reduce_mask(compact)");
         return SIGE_OK;
     }
+    SIGE_REQUIRE(!mark_only, SIGE_ERR_INVALID_ARG, "%s: every list needs its flag workspace", who);
     const ListArgs& a = ls.a[0];
     const size_t lds = ((size_t)(a.nby * a.nbx) + 15) & ~(size_t)15;
     if (lds > 48 * 1024) {
@@ -462,7 +516,7 @@ extern "C" int sige_reduce_mask(const void* a_orig, const void* a_edit, sige_dty
 // The block flags live in a file-scope device array instead of a caller workspace.  In host code the
 // array's name is only a stand-in for the symbol: the address the kernels get is resolved once per
 // device with hipGetSymbolAddress (each GPU holds its own copy at its own address) and kept.
-static __device__ __align__(256) unsigned char scratch[SIGE_NOALLOC_MAX_BLOCKS];
+static __device__ __align__(256) unsigned char scratch[2 * SIGE_NOALLOC_MAX_BLOCKS + 16];
 
 namespace sige {
 
@@ -490,8 +544,8 @@ static int scratch_address(const char* who, hipStream_t st, void** out)
         e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
         SIGE_REQUIRE(e == hipSuccess && ptr != nullptr, SIGE_ERR_HIP, "%s: hipGetSymbolAddress: %s", who,
                      hipGetErrorString(e));
-        hipLaunchKernelGGL(clear_scratch_kernel, dim3(SIGE_NOALLOC_MAX_BLOCKS / 16 / 256), dim3(256), 0, st,
-                           (uint4*)ptr, SIGE_NOALLOC_MAX_BLOCKS / 16);
+        constexpr int n_vec = (2 * SIGE_NOALLOC_MAX_BLOCKS + 16) / 16;
+        hipLaunchKernelGGL(clear_scratch_kernel, dim3((n_vec + 255) / 256), dim3(256), 0, st, (uint4*)ptr, n_vec);
         SIGE_LAUNCH_CHECK(who);
         g_scratch_ptr[dev] = ptr;
     }
@@ -514,7 +568,7 @@ extern "C" int sige_reduce_mask_noalloc(const void* a_orig, const void* a_edit, 
     if (int rc = check_geom(g, who, &th, &tw)) return rc;
     SIGE_REQUIRE(indices != nullptr && count != nullptr, SIGE_ERR_INVALID_ARG, "%s: indices and count are required", who);
     const size_t need = sige_reduce_mask_workspace_bytes(g);
-    SIGE_REQUIRE(need <= (size_t)SIGE_NOALLOC_MAX_BLOCKS, SIGE_ERR_CAPACITY,
+    SIGE_REQUIRE(need <= 2 * (size_t)SIGE_NOALLOC_MAX_BLOCKS + 16, SIGE_ERR_CAPACITY,
                  "%s: the block grid has %zu blocks, the built-in scratch holds %d", who,
                  (size_t)((g->H_out + g->block_h - 1) / g->block_h) * ((g->W_out + g->block_w - 1) / g->block_w),
                  SIGE_NOALLOC_MAX_BLOCKS);
@@ -547,4 +601,18 @@ extern "C" int sige_reduce_mask_lists(const void* a_orig, const void* a_edit, si
         SIGE_REQUIRE(lists[i].workspace != nullptr, SIGE_ERR_INVALID_ARG, "%s: list %d has no workspace", who, i);
     return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, lists, n_lists,
                         nullptr, mask_out, stream);
+}
+
+extern "C" int sige_mark_blocks(const void* a_orig, const void* a_edit, sige_dtype dt, int32_t Hm, int32_t Wm,
+                                int32_t C, float tau, const uint8_t* mask_in, int32_t pool_log2, int32_t dilate,
+                                const sige_block_list* lists, int32_t n_lists, uint8_t* mask_out, void* stream)
+{
+    clear_error();
+    const char* who = "sige_mark_blocks";
+    SIGE_REQUIRE(lists != nullptr && n_lists >= 1 && n_lists <= MAX_LISTS, SIGE_ERR_INVALID_ARG,
+                 "%s: between 1 and %d lists per call", who, MAX_LISTS);
+    for (int i = 0; i < n_lists; ++i)
+        SIGE_REQUIRE(lists[i].workspace != nullptr, SIGE_ERR_INVALID_ARG, "%s: list %d has no workspace", who, i);
+    return reduce_lists(who, a_orig, a_edit, dt, Hm, Wm, C, tau, mask_in, pool_log2, dilate, lists, n_lists,
+                        nullptr, mask_out, stream, true);
 }

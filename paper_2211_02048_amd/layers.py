@@ -56,6 +56,16 @@ class BlockList:
         for b in lists:
             b.n_host = -1
 
+    @staticmethod
+    def mark_together(lists, **kw):
+        """The marking half of reduce_together: the lists stay marked for api.sige_fused_conv_pair_marked."""
+        api.sige_mark_blocks([b.desc() for b in lists], **kw)
+        for b in lists:
+            b.n_host = -1
+
+    def desc(self):
+        return (self.g, self.indices, self.count, self.max_blocks, self.scratch)
+
     def all_active(self):
         """Every block of the grid, row-major: the dense / pre-computation pass."""
         g = self.g

@@ -126,7 +126,7 @@ def test_reduce_mask_errors(L):
     big = api.geom(2048, 2048, 4, 1, 1, 0)
     assert L.sige_reduce_mask(None, None, 0, 2048, 2048, 0, f, FAKE, 0, 0, ctypes.byref(big), None, FAKE, 8,
                               FAKE, None, 0, None) == 3
-    assert L.sige_reduce_mask_workspace_bytes(gp) == 128  # 121 block flags rounded up to 16
+    assert L.sige_reduce_mask_workspace_bytes(gp) == 2 * 128 + 16  # two halves of 121 block flags rounded up to 16, then the phase words
 
 
 def test_attention_and_helper_errors(L):
@@ -178,7 +178,7 @@ def test_token_layer_modulated_gather_and_list_errors(L):
     for d in lst:
         d.g = g
         d.indices, d.count, d.max_blocks = 0x10000, 0x10000, 121
-        d.workspace, d.workspace_bytes = 0x20000, 128
+        d.workspace, d.workspace_bytes = 0x20000, 2 * 128 + 16
     fz = ctypes.c_float(0.0)
     assert L.sige_reduce_mask_lists(None, None, 0, 64, 64, 0, fz, FAKE, 0, 0, lst, 5, None, None) == 1
     assert L.sige_reduce_mask_lists(None, None, 0, 64, 64, 0, fz, FAKE, 0, 0, lst, 0, None, None) == 1

@@ -1002,6 +1002,111 @@ def test_fused_conv_pair(oracle, dtype, Cin, C3, C1, res, b, n):
         api.sige_fused_conv_pair(c3, c1)
 
 
+@pytest.mark.parametrize("dtype,Cin,C3,C1,res,b,frac", [
+    ("f16", 128, 128, 256, 256, 16, 0.01),   # benchmark configuration 2: the launch builds the lists itself
+    ("bf16", 64, 40, 72, 100, 8, 0.03),      # 169 blocks of 8x8 on a ragged grid
+    ("f32", 64, 64, 32, 62, 6, 0.10),        # fp32, 11 x 11 ragged blocks, lists longer than their capacity
+    ("f16", 64, 64, 64, 300, 8, 0.01),       # 1444 blocks: beyond what a workgroup scans, the compaction pass runs
+    ("f16", 512, 64, 64, 32, 8, 0.05)])      # the 3x3 call takes another kernel shape: compaction pass, two launches
+def test_fused_conv_pair_on_marked_lists(oracle, dtype, Cin, C3, C1, res, b, frac):
+    """Marking pass + the pair call that builds the lists from the flags, against the reduction with its
+    compaction pass + the plain pair call: lists and counts bit for bit, outputs bit for bit, flags and
+    ticket counter zero afterwards - over successive edits through the same workspaces (a growing, a
+    shrinking and an empty one), and once more replayed from a HIP graph."""
+    rng = np.random.default_rng(Cin + C3 + res)
+    td = DT[dtype]
+    x = torch.from_numpy(rng.standard_normal((res, res, Cin)).astype(np.float32)).to(td)
+    w3, b3 = inputs.conv_params(rng, C3, Cin, 3, td)
+    w1, b1 = inputs.conv_params(rng, C1, Cin, 1, td)
+    conv3 = SigeConv(dev(w3), b3, res, res, b, 1, 1)
+    conv1 = SigeConv(dev(w1), b1, res, res, b, 1, 0)
+    cap = 8 if dtype == "f32" else 64
+    ws = Workspace("cuda")
+    xd = dev(x)
+    cache3 = torch.from_numpy(rng.standard_normal((res, res, C3)).astype(np.float32)).to(td).cuda()
+    cache1 = torch.from_numpy(rng.standard_normal((res, res, C1)).astype(np.float32)).to(td).cuda()
+    ref = [BlockList(conv3.g, "cuda", max_blocks=cap), BlockList(conv1.g, "cuda", max_blocks=cap)]
+    got = [BlockList(conv3.g, "cuda", max_blocks=cap), BlockList(conv1.g, "cuda", max_blocks=cap)]
+    ya, yb = cache3.clone(), cache1.clone()
+    y3, y1 = cache3.clone(), cache1.clone()
+    mask_d = torch.zeros((res, res), dtype=torch.uint8, device="cuda")
+
+    def reference():
+        BlockList.reduce_together(ref, mask_in=mask_d, dilate=1)
+        ca, _ = conv3.fused_call(xd, ya, ref[0], ws, act=api.ACT_SILU, tag="r3")
+        cb, _ = conv1.fused_call(xd, yb, ref[1], ws, tag="r1")
+        api.sige_fused_conv_pair(ca, cb)
+
+    def marked():
+        BlockList.mark_together(got, mask_in=mask_d, dilate=1)
+        c3, _ = conv3.fused_call(xd, y3, got[0], ws, act=api.ACT_SILU, tag="p3")
+        c1, _ = conv1.fused_call(xd, y1, got[1], ws, tag="p1")
+        api.sige_fused_conv_pair_marked(c3, c1, [bl.desc() for bl in got])
+
+    def check(what):
+        torch.cuda.synchronize()
+        for r, g_ in zip(ref, got):
+            n = int(r.count.item())
+            assert int(g_.count.item()) == n, what
+            assert torch.equal(g_.indices[:min(n, cap)], r.indices[:min(n, cap)]), what
+            ws_ = g_.scratch
+            half = (ws_.numel() - 16) // 2
+            ph = int(ws_[2 * half:2 * half + 4].view(torch.int32).item())
+            clean = ws_[(ph & 1) * half:(ph & 1) * half + half]       # the half the next marking pass uses
+            assert int(clean.sum().item()) == 0, f"{what}: flags left set for the next pass"
+        assert torch.equal(y3, ya) and torch.equal(y1, yb), what
+        return int(ref[0].count.item())
+
+    counts = []
+    for i, f in enumerate((frac, 2 * frac, 0.5 * frac, 0.0)):
+        m = np.zeros((res, res), dtype=np.uint8)
+        if f > 0:
+            m = inputs.blob_mask(np.random.Generator(np.random.PCG64(900 + i)), res, res, max(1, int(f * res * res)), 2,
+                                 (3.0, 8.0), tol=0.5)
+        mask_d.copy_(torch.from_numpy(m))
+        for y in (ya, y3):
+            y.copy_(cache3)
+        for y in (yb, y1):
+            y.copy_(cache1)
+        reference()
+        marked()
+        counts.append(check(f"edit {i}"))
+    assert counts[0] > 0 and counts[3] == 0
+    if dtype == "f32":
+        assert max(counts) > cap, "a list longer than its capacity is part of this case"
+    # replayed from a graph: three replays on changing masks, eager work and synchronisation in between
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        marked()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        marked()
+    for i in range(3):
+        m = inputs.blob_mask(np.random.Generator(np.random.PCG64(950 + i)), res, res, max(1, int(frac * res * res)), 1,
+                             (3.0, 8.0), tol=0.5)
+        mask_d.copy_(torch.from_numpy(m))
+        for y in (ya, y3):
+            y.copy_(cache3)
+        for y in (yb, y1):
+            y.copy_(cache1)
+        reference()
+        g.replay()
+        check(f"replay {i}")
+    # argument errors: the call must read the list its marked list describes; the count is not a host value
+    c3, _ = conv3.fused_call(xd, y3, got[0], ws, act=api.ACT_SILU, tag="p3")
+    c1, _ = conv1.fused_call(xd, y1, got[1], ws, tag="p1")
+    with pytest.raises(api.SigeError):
+        api.sige_fused_conv_pair_marked(c3, c1, [got[1].desc(), got[0].desc()])
+    got[0].n_host = 3
+    c3h, _ = conv3.fused_call(xd, y3, got[0], ws, act=api.ACT_SILU, tag="p3")
+    got[0].n_host = -1
+    with pytest.raises(api.SigeError):
+        api.sige_fused_conv_pair_marked(c3h, c1, [bl.desc() for bl in got])
+
+
 def test_config2_full_size_step_as_benchmarked(oracle):
     """Benchmark configuration 2 at full size exactly as the benchmark's step runs it: one
     difference pass that fills the lists of both geometries (device-side counts, capacity 16),
