@@ -807,18 +807,23 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
 // this part a dependent launch costs more than the compaction's work): every workgroup derives its
 // blocks from the flags (see conv_body).
 template <typename T, int KC, bool MARKED>
-__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int wgs_a, int xa, int ya, int xb,
-                                                           int yb)
+__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int wgs_a, int xa, int ya, int ta,
+                                                           int xb, int yb, int tb)
 {
-    // a one-dimensional grid: the first call's workgroups, then the second's, each numbered x fastest
-    const int id = blockIdx.x;
-    if (id < wgs_a) {
-        const int zy = id / xa;
-        conv_body<T, 2, 1, 1, 1, 4, KC, 9, MARKED>(a, id - zy * xa, zy % ya, zy / ya);
-    } else {
-        const int j = id - wgs_a, zy = j / xb;
-        conv_body<T, 2, 1, 1, 1, 4, KC, 1, MARKED>(b, j - zy * xb, zy % yb, zy / yb);
-    }
+    // A one-dimensional grid: the first call's workgroups, then the second's.  Consecutive workgroups
+    // go to the eight XCDs in turn and each XCD has its own L2, so the workgroups that read the same
+    // input tile (one per 32-wide slab of output channels) are numbered eight apart: they land on one
+    // XCD and the tile leaves HBM once instead of once per slab.  (ta, tb: tiles = bands * groups.)
+    int id = blockIdx.x;
+    const bool first = id < wgs_a;
+    if (!first) id -= wgs_a;
+    const int nx = first ? xa : xb, ny = first ? ya : yb, nt = first ? ta : tb;
+    const int j = id >> 3, jt = j / nx;
+    const int tile = jt * 8 + (id & 7), bx = j - jt * nx;
+    if (tile >= nt) return;
+    const int bz = tile / ny, by = tile - bz * ny;
+    if (first) conv_body<T, 2, 1, 1, 1, 4, KC, 9, MARKED>(a, bx, by, bz);
+    else conv_body<T, 2, 1, 1, 1, 4, KC, 1, MARKED>(b, bx, by, bz);
 }
 
 // v += the ksplit shares of one run of N channels, B of them in flight at a time (each batch is a
@@ -1316,7 +1321,9 @@ int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const 
                 hipStream_t st)
 {
     const size_t lds = std::max(pa.lds, pb.lds);
-    const int wgs_a = pa.slabs * pa.bands * pa.groups, wgs_b = pb.slabs * pb.bands * pb.groups;
+    // tiles in groups of eight (one per XCD), every group times the slabs
+    const int ta = pa.bands * pa.groups, tb = pb.bands * pb.groups;
+    const int wgs_a = (ta + 7) / 8 * 8 * pa.slabs, wgs_b = (tb + 7) / 8 * 8 * pb.slabs;
     const dim3 grid(wgs_a + wgs_b);
     auto launch = [&](auto kern) {
         if (lds > 48 * 1024) {
@@ -1324,7 +1331,7 @@ int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const 
             SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_fused_conv_pair: cannot reserve %zu bytes of LDS: %s", lds,
                          hipGetErrorString(e));
         }
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, wgs_a, pa.slabs, pa.bands, pb.slabs, pb.bands);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, wgs_a, pa.slabs, pa.bands, ta, pb.slabs, pb.bands, tb);
         SIGE_LAUNCH_CHECK("sige_fused_conv_pair");
         return (int)SIGE_OK;
     };

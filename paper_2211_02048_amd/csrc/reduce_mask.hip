@@ -70,7 +70,7 @@ __device__ __forceinline__ void publish_phase(const MarkSet& mk)
 // Sets the flag of every block whose input tile, grown by the dilation radius, contains the
 // pooled position of the marked source pixel `pix`.  In input coordinates block b covers
 // [b*s - pad - r, b*s - pad + tile + r); clipping to the image never excludes an in-image pixel.
-__device__ __forceinline__ void mark_blocks(const MarkArgs& m, int py, int px)
+__device__ __forceinline__ void mark_blocks(const MarkArgs& m, uint32_t phase, int py, int px)
 {
     const int y = py >> m.pool_log2, x = px >> m.pool_log2;
     const int ylo = y - m.dilate - m.th + m.pad, xlo = x - m.dilate - m.tw + m.pad;
@@ -83,7 +83,7 @@ __device__ __forceinline__ void mark_blocks(const MarkArgs& m, int py, int px)
     bx0 = max(bx0, 0);
     // Plain stores (the race is benign: every writer stores 1).  Looking at the flag first would
     // save stores but puts a dependent global load on the path of every marking lane.
-    uint8_t* flags = m.flags + (phase_of(m.flags, m.half) & 1u) * m.half;
+    uint8_t* flags = m.flags + (phase & 1u) * m.half;
     for (int by = by0; by <= by1; ++by)
         for (int bx = bx0; bx <= bx1; ++bx) flags[by * m.nbx + bx] = 1;
 }
@@ -125,7 +125,11 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
                 if (marked && mk.n) {
                     const int py = (int)pix / mk.m[0].Wm;     // the host checked that pixels fit 31 bits
                     const int px = (int)pix - py * mk.m[0].Wm;
-                    for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], py, px);
+                    // (the phase word is fetched here, by the few lanes that mark.  Fetched up front by every
+                    // wave it is one address asked for by 10^5 waves: measured +2 us for the kernel as a
+                    // per-lane load, +1 us as a wave-uniform load of a read-only argument)
+                    for (int i = 0; i < mk.n; ++i)
+                        mark_blocks(mk.m[i], phase_of(mk.m[i].flags, mk.m[i].half), py, px);
                 }
             }
         }
@@ -261,11 +265,11 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if ((w >> (8 * j)) & 0xffu)
-                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], y, x0 + j);
+                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], phase_of(mk.m[i].flags, mk.m[i].half), y, x0 + j);
     } else {
         for (int x = x0; x < min(x0 + 4, Wm); ++x)
             if (row[x])
-                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], y, x);
+                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], phase_of(mk.m[i].flags, mk.m[i].half), y, x);
     }
 }
 
