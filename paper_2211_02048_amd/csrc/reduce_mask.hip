@@ -44,7 +44,15 @@ struct MarkArgs {
     int Wm, pool_log2, dilate;
     int sy, sx;      // block pitch in input pixels: block * stride
     int th, tw, pad, nby, nbx;
+    FastDiv dsy, dsx, dWm;   // division by sy, sx and Wm
 };
+
+__device__ __forceinline__ int fdiv(int x, const FastDiv& f)
+{
+    int q, r;
+    divmod(x, f, q, r);
+    return q;
+}
 
 // The lists one call builds from the same pooled mask (one per layer geometry at that resolution).
 constexpr int MAX_LISTS = 4;
@@ -74,11 +82,14 @@ __device__ __forceinline__ void mark_blocks(const MarkArgs& m, uint32_t phase, i
 {
     const int y = py >> m.pool_log2, x = px >> m.pool_log2;
     const int ylo = y - m.dilate - m.th + m.pad, xlo = x - m.dilate - m.tw + m.pad;
-    // first block with b*s > lo  (floor division that is correct for negative lo)
-    int by0 = (ylo >= 0 ? ylo / m.sy : -((-ylo + m.sy - 1) / m.sy)) + 1;
-    int bx0 = (xlo >= 0 ? xlo / m.sx : -((-xlo + m.sx - 1) / m.sx)) + 1;
-    const int by1 = min((y + m.dilate + m.pad) / m.sy, m.nby - 1);
-    const int bx1 = min((x + m.dilate + m.pad) / m.sx, m.nbx - 1);
+    // first block with b*s > lo  (floor division that is correct for negative lo).  The divisors are
+    // prepared on the host: a wave that marks is the slowest wave of a kernel that lasts a few
+    // microseconds, and the thirty-odd dependent instructions of each of the compiler's divisions
+    // were most of its extra time (measured: about 1 us per list).
+    int by0 = (ylo >= 0 ? fdiv(ylo, m.dsy) : -fdiv(-ylo + m.sy - 1, m.dsy)) + 1;
+    int bx0 = (xlo >= 0 ? fdiv(xlo, m.dsx) : -fdiv(-xlo + m.sx - 1, m.dsx)) + 1;
+    const int by1 = min(fdiv(y + m.dilate + m.pad, m.dsy), m.nby - 1);
+    const int bx1 = min(fdiv(x + m.dilate + m.pad, m.dsx), m.nbx - 1);
     by0 = max(by0, 0);
     bx0 = max(bx0, 0);
     // Plain stores (the race is benign: every writer stores 1).  Looking at the flag first would
@@ -123,8 +134,8 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
                 const bool marked = ((b >> (lane << log2v)) & gmask) != 0ull;
                 mask[pix] = marked ? 1 : 0;
                 if (marked && mk.n) {
-                    const int py = (int)pix / mk.m[0].Wm;     // the host checked that pixels fit 31 bits
-                    const int px = (int)pix - py * mk.m[0].Wm;
+                    int py, px;                               // the host checked that pixels fit 31 bits
+                    divmod((int)pix, mk.m[0].dWm, py, px);
                     // (the phase word is fetched here, by the few lanes that mark.  Fetched up front by every
                     // wave it is one address asked for by 10^5 waves: measured +2 us for the kernel as a
                     // per-lane load, +1 us as a wave-uniform load of a read-only argument)
@@ -431,6 +442,7 @@ static int reduce_lists(const char* who, const void* a_orig, const void* a_edit,
         m.Wm = Wm; m.pool_log2 = pool_log2; m.dilate = dilate;
         m.sy = g->block_h * g->stride; m.sx = g->block_w * g->stride;
         m.th = th; m.tw = tw; m.pad = g->pad; m.nby = (int)nby; m.nbx = (int)nbx;
+        m.dsy = fast_div(m.sy); m.dsx = fast_div(m.sx); m.dWm = fast_div(Wm);
         ListArgs& a = ls.a[i];
         a.Hm = Hm; a.Wm = Wm; a.pool_log2 = pool_log2; a.dilate = dilate;
         a.Hin = g->H_in; a.Win = g->W_in; a.bh = g->block_h; a.bw = g->block_w;
