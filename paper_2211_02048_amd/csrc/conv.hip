@@ -258,6 +258,7 @@ static int prepare_conv(const char* who, sige_dtype dt, const sige_geom* g, int 
     a.Cin = Cin; a.Cout = Cout; a.max_blocks = max_blocks; a.n_host = n_blocks;
     a.G = p->G; a.rows = p->rows; a.trows = p->trows; a.Cc = p->Cc; a.ps = p->ps;
     a.bands = p->bands; a.ksplit = p->ksplit;
+    a.d_bands = fast_div(p->bands); a.d_ksplit = fast_div(p->ksplit); a.d_mk_nbx = fast_div(1);
     a.direct = knob(SIGE_KNOB_CONV_DIRECT) != 0;
     a.d_pb = fast_div(p->rows * g->block_w);
     a.d_per = fast_div(p->trows * tw);
@@ -587,6 +588,7 @@ static int fused_pair(const char* who, const sige_fused_conv_call* first, const 
             a[i].mk_count = marks[i].count;
             a[i].mk_nb = (int)nb[i];
             a[i].mk_nbx = (int)nbx;
+            a[i].d_mk_nbx = fast_div((int)nbx);
         }
         if (!scan)
             if (int rc = compact_marked_lists(who, marks, 2, st)) return rc;

@@ -98,6 +98,7 @@ struct ConvArgs {
     // divisors the kernels divide by, prepared on the host: rows * bw (a workgroup's rows per block),
     // bw, trows * tw, tw, bh * bw, and the 16-byte runs per output pixel (the reduction kernel's)
     FastDiv d_pb, d_bw, d_per, d_tw, d_pbfull, d_runs;
+    FastDiv d_bands, d_ksplit, d_mk_nbx;   // bands, ksplit and (marked mode) blocks per block row
 };
 
 // Packed weight: [Cout_pad/32][k*k][Cin/KSTEP][64 lanes][16 bytes]; lane l of a fragment
@@ -364,8 +365,10 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (f[j]) {
-                const int blk = 4 * tid + j, byy = blk / a.mk_nbx;
-                const int oy = byy * a.bh, ox = (blk - byy * a.mk_nbx) * a.bw;
+                const int blk = 4 * tid + j;
+                int byy, bxx;
+                divmod(blk, a.d_mk_nbx, byy, bxx);
+                const int oy = byy * a.bh, ox = bxx * a.bw;
                 if (slot >= g0 && slot < g0 + a.G) { org[2 * (slot - g0)] = oy; org[2 * (slot - g0) + 1] = ox; }
                 if (writer && slot < a.max_blocks) { a.mk_indices[2 * slot] = oy; a.mk_indices[2 * slot + 1] = ox; }
                 ++slot;
@@ -390,7 +393,9 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
             __syncthreads();
         }
     }
-    const int split = by / a.bands, band = by - split * a.bands;
+    // (a compiler-made division is some forty dependent instructions, 0.15 us on the path of every workgroup)
+    int split, band;
+    divmod(by, a.d_bands, split, band);
     const int band_row0 = band * a.rows;                      // first output row of the band
     const int band_rows = min(a.rows, a.bh - band_row0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -465,7 +470,11 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
     constexpr int STEPS = KK > 0 ? KK * KW : 1;
     constexpr int D = KK == 0 ? 1 : ring_depth(STEPS, TN == 1 ? 18 : 8);
     const int nch = a.Cin / (KC * KS);
-    const int ch0 = split * nch / a.ksplit, ch1 = (split + 1) * nch / a.ksplit;   // this workgroup's chunks
+    int ch0 = 0, ch1 = nch, rem_unused;                       // this workgroup's chunks
+    if (a.ksplit > 1) {
+        divmod(split * nch, a.d_ksplit, ch0, rem_unused);
+        divmod((split + 1) * nch, a.d_ksplit, ch1, rem_unused);
+    }
     const int ntaps = KK ? KK : kk;
     uint4 ring[D][TN];
     auto fetch = [&](uint4 (&slot)[TN], int chunk, int tp, int kc) {
@@ -807,8 +816,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void
 // this part a dependent launch costs more than the compaction's work): every workgroup derives its
 // blocks from the flags (see conv_body).
 template <typename T, int KC, bool MARKED>
-__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int wgs_a, int xa, int ya, int ta,
-                                                           int xb, int yb, int tb)
+__global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs b, int wgs_a, FastDiv xa, FastDiv ya,
+                                                           int ta, FastDiv xb, FastDiv yb, int tb)
 {
     // A one-dimensional grid: the first call's workgroups, then the second's.  Consecutive workgroups
     // go to the eight XCDs in turn and each XCD has its own L2, so the workgroups that read the same
@@ -817,11 +826,13 @@ __global__ __launch_bounds__(256, 2) void conv_pair_kernel(ConvArgs a, ConvArgs 
     int id = blockIdx.x;
     const bool first = id < wgs_a;
     if (!first) id -= wgs_a;
-    const int nx = first ? xa : xb, ny = first ? ya : yb, nt = first ? ta : tb;
-    const int j = id >> 3, jt = j / nx;
-    const int tile = jt * 8 + (id & 7), bx = j - jt * nx;
+    const FastDiv nx = first ? xa : xb, ny = first ? ya : yb;
+    const int nt = first ? ta : tb;
+    int jt, bx, bz, by;
+    divmod(id >> 3, nx, jt, bx);
+    const int tile = jt * 8 + (id & 7);
     if (tile >= nt) return;
-    const int bz = tile / ny, by = tile - bz * ny;
+    divmod(tile, ny, bz, by);
     if (first) conv_body<T, 2, 1, 1, 1, 4, KC, 9, MARKED>(a, bx, by, bz);
     else conv_body<T, 2, 1, 1, 1, 4, KC, 1, MARKED>(b, bx, by, bz);
 }
@@ -1331,7 +1342,8 @@ int launch_pair(const ConvArgs& a, const ConvPlan& pa, const ConvArgs& b, const 
             SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_fused_conv_pair: cannot reserve %zu bytes of LDS: %s", lds,
                          hipGetErrorString(e));
         }
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, wgs_a, pa.slabs, pa.bands, ta, pb.slabs, pb.bands, tb);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, b, wgs_a, fast_div(pa.slabs), fast_div(pa.bands), ta,
+                           fast_div(pb.slabs), fast_div(pb.bands), tb);
         SIGE_LAUNCH_CHECK("sige_fused_conv_pair");
         return (int)SIGE_OK;
     };
