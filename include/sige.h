@@ -465,8 +465,8 @@ int sige_version(void);
  *   CONV_POINTWISE_W4  its four-wave variant for 64x64 patches: 0 = never, 1 = always
  *   CONV_PAIR_WGS      most workgroups up to which sige_fused_conv_pair shares one launch
  *   ATTN_WGS           workgroups the key split of sige_sparse_attn aims for
- *   DIFF_LOADS         16-byte loads per lane and tensor in flight in the difference kernel (1, 2, 4, 8)
- *   DIFF_WGS           most workgroups of the difference kernel
+ *   DIFF_LOADS         16-byte loads per lane and tensor in flight in the difference kernel (1, 2, 4)
+ *   DIFF_WGS           accepted and ignored (the difference kernel runs one step per wave)
  *   CONV_DIRECT        0: the shapes whose waves do not split K send their accumulators through LDS
  *                      instead of straight from the registers                                    */
 typedef enum {

@@ -22,6 +22,7 @@
 #include "common.h"
 
 #include <mutex>
+#include <type_traits>
 
 namespace sige {
 
@@ -39,12 +40,15 @@ __device__ __forceinline__ bool vec_differs(const uint4& o, const uint4& e, floa
 
 struct MarkArgs {
     uint8_t* flags;  // the flag workspace: two halves of `half` bytes (one byte per block of the grid, padded to
-                     // 16; the half in use is all zero on entry), then the two phase words; NULL = do not mark
+                     // 16; the half in use is all zero on entry), then the two phase words
     int half;
-    int Wm, pool_log2, dilate;
+    int pool_log2;
+    int oy, ox;      // dilate + tile - pad: a pixel at pooled position p touches the blocks b with b*s > p - o ...
+    int hi;          // dilate + pad:        ... and b*s <= p + hi
     int sy, sx;      // block pitch in input pixels: block * stride
-    int th, tw, pad, nby, nbx;
-    FastDiv dsy, dsx, dWm;   // division by sy, sx and Wm
+    int nby, nbx;
+    int ly, lx;      // base-2 logarithms of sy and sx where they are powers of two, else -1
+    FastDiv dsy, dsx;   // division by sy and sx
 };
 
 __device__ __forceinline__ int fdiv(int x, const FastDiv& f)
@@ -56,10 +60,14 @@ __device__ __forceinline__ int fdiv(int x, const FastDiv& f)
 
 // The lists one call builds from the same pooled mask (one per layer geometry at that resolution).
 constexpr int MAX_LISTS = 4;
-struct MarkSet {
-    int n;           // 0 = do not mark
-    MarkArgs m[MAX_LISTS];
+template <int NL>
+struct MarkSetN {
+    int n;           // lists in use (<= NL); 0 = do not mark
+    int Wm, lW;      // source pixels per row; its base-2 logarithm if it is a power of two, else -1
+    FastDiv dWm;
+    MarkArgs m[NL > 0 ? NL : 1];
 };
+typedef MarkSetN<MAX_LISTS> MarkSet;
 
 __device__ __forceinline__ uint32_t phase_of(const uint8_t* flags, int half)
 {
@@ -67,65 +75,136 @@ __device__ __forceinline__ uint32_t phase_of(const uint8_t* flags, int half)
 }
 
 // The first thread of a marking launch leaves the phase it marks in where consumers look for it.
-__device__ __forceinline__ void publish_phase(const MarkSet& mk)
+template <int NL>
+__device__ __forceinline__ void publish_phase(const MarkSetN<NL>& mk)
 {
-    for (int i = 0; i < mk.n; ++i) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        if (i >= mk.n) break;
         uint32_t* p = reinterpret_cast<uint32_t*>(mk.m[i].flags + 2 * mk.m[i].half);
         p[1] = p[0];
     }
 }
 
 // Sets the flag of every block whose input tile, grown by the dilation radius, contains the
-// pooled position of the marked source pixel `pix`.  In input coordinates block b covers
+// pooled position of the marked source pixel (py, px).  In input coordinates block b covers
 // [b*s - pad - r, b*s - pad + tile + r); clipping to the image never excludes an in-image pixel.
+// A wave that marks is the slowest wave of a kernel that lasts a few microseconds, and what it
+// executes here is one dependent chain (measured: 1.6 us for two lists with general divisions): block
+// pitches that are powers of two - the usual case - take shifts, the others divisors prepared on the
+// host, and the usual one or two blocks per axis are stored without a loop.
 __device__ __forceinline__ void mark_blocks(const MarkArgs& m, uint32_t phase, int py, int px)
 {
     const int y = py >> m.pool_log2, x = px >> m.pool_log2;
-    const int ylo = y - m.dilate - m.th + m.pad, xlo = x - m.dilate - m.tw + m.pad;
-    // first block with b*s > lo  (floor division that is correct for negative lo).  The divisors are
-    // prepared on the host: a wave that marks is the slowest wave of a kernel that lasts a few
-    // microseconds, and the thirty-odd dependent instructions of each of the compiler's divisions
-    // were most of its extra time (measured: about 1 us per list).
-    int by0 = (ylo >= 0 ? fdiv(ylo, m.dsy) : -fdiv(-ylo + m.sy - 1, m.dsy)) + 1;
-    int bx0 = (xlo >= 0 ? fdiv(xlo, m.dsx) : -fdiv(-xlo + m.sx - 1, m.dsx)) + 1;
-    const int by1 = min(fdiv(y + m.dilate + m.pad, m.dsy), m.nby - 1);
-    const int bx1 = min(fdiv(x + m.dilate + m.pad, m.dsx), m.nbx - 1);
+    const int ylo = y - m.oy, xlo = x - m.ox, yhi = y + m.hi, xhi = x + m.hi;
+    int by0, bx0, by1, bx1;
+    // first block with b*s > lo (a floor division that is also right for negative lo), last with b*s <= hi
+    if (m.ly >= 0) {
+        by0 = (ylo >> m.ly) + 1;
+        by1 = yhi >> m.ly;
+    } else {
+        by0 = (ylo >= 0 ? fdiv(ylo, m.dsy) : -fdiv(-ylo + m.sy - 1, m.dsy)) + 1;
+        by1 = fdiv(yhi, m.dsy);
+    }
+    if (m.lx >= 0) {
+        bx0 = (xlo >> m.lx) + 1;
+        bx1 = xhi >> m.lx;
+    } else {
+        bx0 = (xlo >= 0 ? fdiv(xlo, m.dsx) : -fdiv(-xlo + m.sx - 1, m.dsx)) + 1;
+        bx1 = fdiv(xhi, m.dsx);
+    }
     by0 = max(by0, 0);
     bx0 = max(bx0, 0);
+    by1 = min(by1, m.nby - 1);
+    bx1 = min(bx1, m.nbx - 1);
+    if (by1 < by0 || bx1 < bx0) return;
     // Plain stores (the race is benign: every writer stores 1).  Looking at the flag first would
     // save stores but puts a dependent global load on the path of every marking lane.
     uint8_t* flags = m.flags + (phase & 1u) * m.half;
+    uint8_t* f = flags + by0 * m.nbx + bx0;
+    if (by1 - by0 <= 1 && bx1 - bx0 <= 1) {
+        f[0] = 1;
+        if (bx1 > bx0) f[1] = 1;
+        if (by1 > by0) {
+            f[m.nbx] = 1;
+            if (bx1 > bx0) f[m.nbx + 1] = 1;
+        }
+        return;
+    }
     for (int by = by0; by <= by1; ++by)
         for (int bx = bx0; bx <= bx1; ++bx) flags[by * m.nbx + bx] = 1;
 }
 
-// V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
-template <typename T, int U>
-__global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ a_o,
-                                                      const uint4* __restrict__ a_e, long n_vec,
-                                                      int log2v, float tau, long n_pix,
-                                                      uint8_t* __restrict__ mask, MarkSet mk)
+// Row and column of source pixel `pix` (rows of Wm pixels; a shift when Wm is a power of two).
+template <int NL>
+__device__ __forceinline__ void pixel_rc(const MarkSetN<NL>& mk, int pix, int& py, int& px)
 {
+    if (mk.lW >= 0) {
+        py = pix >> mk.lW;
+        px = pix & (mk.Wm - 1);
+    } else {
+        divmod(pix, mk.dWm, py, px);
+    }
+}
+
+// All lists' phase words in one round trip, then the marks.
+template <int NL>
+__device__ __forceinline__ void mark_pixel(const MarkSetN<NL>& mk, int py, int px)
+{
+    uint32_t ph[NL > 0 ? NL : 1];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) ph[i] = i < mk.n ? phase_of(mk.m[i].flags, mk.m[i].half) : 0u;
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+        if (i < mk.n) mark_blocks(mk.m[i], ph[i], py, px);
+}
+
+// The fields of one list as scalar-register inputs of an empty statement: the compiler then fetches
+// them in one batch at the top of the kernel instead of group by group before each first use.
+#define SIGE_PIN_MARK(L_)                                                                                          \
+    asm volatile("" ::"s"((L_).flags), "s"((L_).half), "s"((L_).pool_log2), "s"((L_).oy), "s"((L_).ox), "s"((L_).hi), \
+                 "s"((L_).sy), "s"((L_).sx), "s"((L_).nby), "s"((L_).nbx), "s"((L_).ly), "s"((L_).lx),                  \
+                 "s"((L_).dsy.d), "s"((L_).dsy.m), "s"((L_).dsx.d), "s"((L_).dsx.m))
+
+// V = vectors per pixel = 1 << log2v, V <= 64.  One wave covers 64/V pixels per step.
+// NL = lists the launch can mark for (0: mask only; the kernel then carries no marking code and no list
+// arguments).  Every wave of this kernel lives for one round trip to memory, so what it does before its
+// first load counts: the list arguments are fetched in one batch (left to itself the compiler fetches them
+// in five or six dependent groups at the top of EVERY wave: +0.7 us for the kernel), and eight waves per
+// SIMD are required of the compiler: the launch is sized so that the whole tensor is in flight in one
+// round of workgroups, and at seven waves the last eighth runs as a second round (8.1 instead of 6.3 us
+// at 33 MB).
+template <typename T, int U, int NL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void diff_mask_pow2(const uint4* __restrict__ a_o, const uint4* __restrict__ a_e, long n_vec, int log2v, float tau,
+                    long n_pix, uint8_t* __restrict__ mask, MarkSetN<NL> mk)
+{
+    // what every wave needs, fetched in one batch
+    asm volatile("" ::"s"(a_o), "s"(a_e), "s"(n_vec), "s"(log2v), "s"(tau), "s"(n_pix), "s"(mask));
     const int lane = threadIdx.x & 63;
     const long wave = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const long n_waves = (long)gridDim.x * (blockDim.x >> 6);
     const int V = 1 << log2v;
     const int ppw = 64 >> log2v;  // pixels per wave step
     const unsigned long long gmask = V == 64 ? ~0ull : ((1ull << V) - 1ull);
-    if (blockIdx.x == 0 && threadIdx.x == 0) publish_phase(mk);
-    for (long base = wave * (64L * U); base < n_vec; base += n_waves * (64L * U)) {
+    // (one step per wave and no loop around it: the compiler moves whatever a loop leaves unchanged to
+    // the front of it, and here that is the marking path's arithmetic, run by every wave for nothing)
+    const long base = wave * (64L * U);
+    if (base < n_vec) {
+        // Unconditional loads at clamped indices, so that all 2U of them are in flight before the first is
+        // looked at (with a bounds test around each pair the compiler finishes one pair before it issues the
+        // next: U round trips to memory instead of one).  A clamped vector belongs to a pixel >= n_pix,
+        // which is not stored below.
         uint4 o[U], e[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            long idx = base + u * 64 + lane;
-            if (idx < n_vec) {
-                o[u] = load_stream(a_o + idx);
-                e[u] = load_stream(a_e + idx);
-            } else {
-                o[u] = make_uint4(0, 0, 0, 0);
-                e[u] = o[u];
-            }
+            const long idx = min(base + u * 64 + lane, n_vec - 1);
+            o[u] = load_stream(a_o + idx);
+            e[u] = load_stream(a_e + idx);
         }
+        // (neither the optimiser nor the instruction scheduler may move a load below this point or a use
+        // of a loaded value above it)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             unsigned long long b = __ballot(vec_differs<T>(o[u], e[u], tau));
@@ -133,18 +212,22 @@ __global__ __launch_bounds__(256) void diff_mask_pow2(const uint4* __restrict__ 
             if (lane < ppw && pix < n_pix) {
                 const bool marked = ((b >> (lane << log2v)) & gmask) != 0ull;
                 mask[pix] = marked ? 1 : 0;
-                if (marked && mk.n) {
-                    int py, px;                               // the host checked that pixels fit 31 bits
-                    divmod((int)pix, mk.m[0].dWm, py, px);
-                    // (the phase word is fetched here, by the few lanes that mark.  Fetched up front by every
-                    // wave it is one address asked for by 10^5 waves: measured +2 us for the kernel as a
-                    // per-lane load, +1 us as a wave-uniform load of a read-only argument)
-                    for (int i = 0; i < mk.n; ++i)
-                        mark_blocks(mk.m[i], phase_of(mk.m[i].flags, mk.m[i].half), py, px);
+                if constexpr (NL > 0) {
+                    if (marked && mk.n) {
+                        int py, px;                               // the host checked that pixels fit 31 bits
+                        pixel_rc(mk, (int)pix, py, px);
+                        // (the phase words are fetched here, by the few lanes that mark.  Fetched up front by
+                        // every wave they are one address asked for by 10^5 waves: measured +2 us for the
+                        // kernel as a per-lane load, +1 us as a wave-uniform load of a read-only argument)
+                        mark_pixel(mk, py, px);
+                    }
                 }
             }
         }
     }
+    // (last, so that nothing of it sits in front of the first wave's loads)
+    if constexpr (NL > 0)
+        if (blockIdx.x == 0 && threadIdx.x == 0) publish_phase(mk);
 }
 
 // Any number of vectors per pixel: one wave per pixel.
@@ -267,7 +350,7 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) publish_phase(mk);
     if (t >= Hm * words_per_row) return;
-    const int Wm = mk.m[0].Wm;
+    const int Wm = mk.Wm;
     const int y = t / words_per_row, x0 = (t - y * words_per_row) * 4;
     const uint8_t* row = mask + (long)y * Wm;
     if (aligned && x0 + 4 <= Wm) {
@@ -276,11 +359,11 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if ((w >> (8 * j)) & 0xffu)
-                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], phase_of(mk.m[i].flags, mk.m[i].half), y, x0 + j);
+                mark_pixel(mk, y, x0 + j);
     } else {
         for (int x = x0; x < min(x0 + 4, Wm); ++x)
             if (row[x])
-                for (int i = 0; i < mk.n; ++i) mark_blocks(mk.m[i], phase_of(mk.m[i].flags, mk.m[i].half), y, x);
+                mark_pixel(mk, y, x);
     }
 }
 
@@ -335,17 +418,27 @@ static int launch_diff(const void* a_orig, const void* a_edit, int Hm, int Wm, i
             // (measured: 7.3 - 7.5 us at 32 MB whatever the grain between 1024 and 8192 workgroups and 1 - 2
             // loads, 8.3 us with 4 loads, 11.7 us with 8; at 512 MB 77 us with 32768 workgroups, 81 us with 8192)
             const int U = knob(SIGE_KNOB_DIFF_LOADS) > 0 ? knob(SIGE_KNOB_DIFF_LOADS) : 2;
-            const long max_wgs = knob(SIGE_KNOB_DIFF_WGS) > 0 ? knob(SIGE_KNOB_DIFF_WGS) : 32768;
-            long steps = (n_vec + 256L * U - 1) / (256L * U);
-            int grid = (int)(steps < max_wgs ? steps : max_wgs);
-            auto launch = [&](auto kern) {
-                hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint4*)a_orig, (const uint4*)a_edit, n_vec,
-                                   log2v, tau, n_pix, mask, mk);
+            const long steps = (n_vec + 256L * U - 1) / (256L * U);     // one step per wave
+            SIGE_REQUIRE(steps < (1L << 24), SIGE_ERR_UNSUPPORTED, "sige_reduce_mask: more than 2^32 threads");
+            const int grid = (int)steps;
+            // the kernel instance that carries just as many lists as the call has (0, 1, 2 or up to MAX_LISTS)
+            auto launch_n = [&](auto nl_c) {
+                constexpr int NL = decltype(nl_c)::value;
+                MarkSetN<NL> mn;
+                mn.n = mk.n; mn.Wm = mk.Wm; mn.lW = mk.lW; mn.dWm = mk.dWm;
+                for (int i = 0; i < NL && i < mk.n; ++i) mn.m[i] = mk.m[i];
+                auto launch = [&](auto kern) {
+                    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, st, (const uint4*)a_orig, (const uint4*)a_edit,
+                                       n_vec, log2v, tau, n_pix, mask, mn);
+                };
+                if (U == 1) launch(diff_mask_pow2<T, 1, NL>);
+                else if (U == 4) launch(diff_mask_pow2<T, 4, NL>);
+                else launch(diff_mask_pow2<T, 2, NL>);
             };
-            if (U == 1) launch(diff_mask_pow2<T, 1>);
-            else if (U == 4) launch(diff_mask_pow2<T, 4>);
-            else if (U == 8) launch(diff_mask_pow2<T, 8>);
-            else launch(diff_mask_pow2<T, 2>);
+            if (mk.n == 0) launch_n(std::integral_constant<int, 0>{});
+            else if (mk.n == 1) launch_n(std::integral_constant<int, 1>{});
+            else if (mk.n == 2) launch_n(std::integral_constant<int, 2>{});
+            else launch_n(std::integral_constant<int, MAX_LISTS>{});
             *marked = mk.n != 0;
         } else {
             long blocks = (n_pix + 3) / 4;
@@ -413,8 +506,10 @@ static int reduce_lists(const char* who, const void* a_orig, const void* a_edit,
     const int ps = 1 << pool_log2;
     const int Hp = (Hm + ps - 1) / ps, Wp = (Wm + ps - 1) / ps;
     hipStream_t st = (hipStream_t)stream;
+    auto log2_or = [](int v) { int l = 0; while ((1 << l) < v) ++l; return (1 << l) == v ? l : -1; };
     MarkSet mk;
     mk.n = 0;
+    mk.Wm = Wm; mk.lW = log2_or(Wm); mk.dWm = fast_div(Wm);
     ListSet ls;
     bool all_ws = n > 0;
     for (int i = 0; i < n; ++i) {
@@ -439,10 +534,12 @@ static int reduce_lists(const char* who, const void* a_orig, const void* a_edit,
         MarkArgs& m = mk.m[i];
         m.flags = (uint8_t*)L.workspace;
         m.half = (int)((nby * nbx + 15) & ~15L);
-        m.Wm = Wm; m.pool_log2 = pool_log2; m.dilate = dilate;
+        m.pool_log2 = pool_log2;
+        m.oy = dilate + th - g->pad; m.ox = dilate + tw - g->pad; m.hi = dilate + g->pad;
         m.sy = g->block_h * g->stride; m.sx = g->block_w * g->stride;
-        m.th = th; m.tw = tw; m.pad = g->pad; m.nby = (int)nby; m.nbx = (int)nbx;
-        m.dsy = fast_div(m.sy); m.dsx = fast_div(m.sx); m.dWm = fast_div(Wm);
+        m.nby = (int)nby; m.nbx = (int)nbx;
+        m.dsy = fast_div(m.sy); m.dsx = fast_div(m.sx);
+        m.ly = log2_or(m.sy); m.lx = log2_or(m.sx);
         ListArgs& a = ls.a[i];
         a.Hm = Hm; a.Wm = Wm; a.pool_log2 = pool_log2; a.dilate = dilate;
         a.Hin = g->H_in; a.Win = g->W_in; a.bh = g->block_h; a.bw = g->block_w;
