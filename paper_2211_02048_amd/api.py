@@ -88,6 +88,8 @@ _lib = None
 def lib() -> ctypes.CDLL:
     """Loads the HIP library; raises if it has not been built (no CPU fallback)."""
     global _lib
+    if _recording is not None:
+        return _recording
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise SigeError(-1, f"{LIB_PATH} is missing: run `python -m paper_2211_02048_amd.build` "
@@ -134,6 +136,68 @@ def lib() -> ctypes.CDLL:
         L.sige_get_knob.restype = i32
         _lib = L
     return _lib
+
+
+# ---- prepared calls ---------------------------------------------------------------------------------
+# A step that is a few kernels of a few microseconds each is bound by what the host does per launch.
+# `record()` runs a piece of code once and keeps every library call it made together with its marshalled
+# arguments; `CallList.run()` then repeats exactly those calls (same pointers, same sizes, same stream)
+# without building the arguments again.  Marshalling only: each run still goes through the C entry
+# points, which validate, plan and launch as always.
+_QUERIES = ("sige_last_error", "sige_packed_weight_bytes", "sige_sparse_attn_workspace_bytes",
+            "sige_reduce_mask_workspace_bytes", "sige_conv_workspace_bytes", "sige_conv_plan", "sige_set_knob",
+            "sige_get_knob")
+
+
+class CallList:
+    """Library calls recorded by `record()`.  The tensors they name must outlive the list; the calls run
+    on the stream that was current while they were recorded."""
+
+    def __init__(self):
+        self.calls = []
+
+    def run(self):
+        for fn, args in self.calls:
+            rc = fn(*args)
+            if rc != 0:
+                _check(rc)
+
+    def __len__(self):
+        return len(self.calls)
+
+
+class _RecordingLib:
+    def __init__(self, real, calls):
+        self._real, self._calls = real, calls
+
+    def __getattr__(self, name):
+        fn = getattr(self._real, name)
+        if not name.startswith("sige_") or name in _QUERIES:
+            return fn
+
+        def call(*args):
+            self._calls.append((fn, args))
+            return fn(*args)
+        return call
+
+
+_recording = None
+
+
+class record:
+    """with api.record() as calls: ...   (the calls are made as usual and kept in `calls`)"""
+
+    def __enter__(self):
+        global _recording
+        assert _recording is None, "api.record() does not nest"
+        self.list = CallList()
+        _recording = _RecordingLib(lib(), self.list.calls)
+        return self.list
+
+    def __exit__(self, *exc):
+        global _recording
+        _recording = None
+        return False
 
 
 def _ptr(t):

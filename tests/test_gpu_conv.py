@@ -1170,3 +1170,48 @@ def test_config2_full_size_step_as_benchmarked(oracle):
     got = y1[torch.from_numpy(px[:, 0]).long().cuda(), torch.from_numpy(px[:, 1]).long().cuda()]
     want = oracle.dense_layer(f64(cfg["a_edit"]), f64(cfg["w_s"]), f64(cfg["bias_s"]), 1, 0, pixels=px)
     assert_close(got, want, td, "1x1 shortcut of the step (all active pixels)")
+
+
+@pytest.mark.gpu
+def test_recorded_calls_repeat_the_step():
+    """api.record keeps the marshalled arguments of the calls made under it; run() repeats them on the
+    tensors' current contents: same lists and outputs as fresh calls, bit for bit, also after the input
+    has changed, and an error of a repeated call is raised like a fresh call's."""
+    res, C, Co, cap = 64, 32, 32, 16
+    td = torch.float16
+    rng = np.random.Generator(np.random.PCG64(77))
+    conv = SigeConv(torch.from_numpy(rng.standard_normal((Co, C, 3, 3)).astype(np.float32) * 0.1).to(td).cuda(),
+                    torch.from_numpy(rng.standard_normal(Co).astype(np.float32)), res, res, 16, 1, 1)
+    ws = Workspace("cuda")
+    a_o = torch.from_numpy(rng.standard_normal((res, res, C)).astype(np.float32)).to(td).cuda()
+    a_e = a_o.clone()
+    cache = torch.from_numpy(rng.standard_normal((res, res, Co)).astype(np.float32)).to(td).cuda()
+    y_rec, y_new = cache.clone(), cache.clone()
+    bl_rec, bl_new = BlockList(conv.g, "cuda", max_blocks=cap), BlockList(conv.g, "cuda", max_blocks=cap)
+    mask = torch.zeros((res, res), dtype=torch.uint8, device="cuda")
+
+    def step(bl, y):
+        BlockList.reduce_together([bl], a_orig=a_o, a_edit=a_e, tau=0.0, mask_out=mask, dilate=1)
+        conv.forward(a_e, y, bl, ws, act=api.ACT_SILU, fused=True)
+
+    a_e[5:9, 40:44] += 1.0
+    with api.record() as calls:
+        step(bl_rec, y_rec)
+    assert len(calls) >= 2
+    for edit in range(3):
+        a_e.copy_(a_o)
+        if edit < 2:
+            a_e[20 * edit + 3:20 * edit + 9, 10:30] += 1.0
+        y_rec.copy_(cache)
+        y_new.copy_(cache)
+        calls.run()
+        step(bl_new, y_new)
+        torch.cuda.synchronize()
+        n = int(bl_new.count.item())
+        assert int(bl_rec.count.item()) == n and (n > 0) == (edit < 2)
+        assert torch.equal(bl_rec.indices[:n], bl_new.indices[:n])
+        assert torch.equal(y_rec, y_new)
+    fn, args = calls.calls[0]
+    calls.calls[0] = (fn, args[:2] + (99,) + args[3:])          # an unknown dtype
+    with pytest.raises(api.SigeError):
+        calls.run()
