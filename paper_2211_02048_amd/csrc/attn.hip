@@ -46,6 +46,25 @@ template <> struct Mma16<bf16> {
     }
 };
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Two floats rounded to nearest even into one 32-bit pair of T (a in the low half).
+template <typename T> __device__ __forceinline__ uint32_t pack2_rne(float a, float b);
+template <> __device__ __forceinline__ uint32_t pack2_rne<f16>(float a, float b)
+{
+    union { f16x2 v; uint32_t u; } r;
+    r.v = __builtin_convertvector((f32x2){a, b}, f16x2);
+    return r.u;
+}
+template <> __device__ __forceinline__ uint32_t pack2_rne<bf16>(float a, float b)
+{
+    union { bf16x2 v; uint32_t u; } r;
+    r.v = __builtin_convertvector((f32x2){a, b}, bf16x2);
+    return r.u;
+}
+
 struct AttnArgs {
     const void* q;
     const void* k;
@@ -66,13 +85,22 @@ struct AttnArgs {
 constexpr int key_tiles(int DT) { return DT <= 3 ? 2 : 1; }
 static int keys_per_chunk(int d, sige_dtype dt) { return dt == SIGE_F32 ? 32 : 32 * key_tiles((d + 31) / 32); }
 
-template <typename T, int DT>
+// DT = 32-wide tiles over d; ODD: d takes an odd number of 16-wide steps (d % 32 is 8 or 16), so the
+// last tile of V^T has spare rows.  One of them is then a row of ones: the second product sums the
+// probabilities of a query - exactly the rounded values that it multiplies V with - into that row of
+// O^T, the running rescale included, and the softmax spends no vector instruction on the denominator.
+// The softmax is what bounds this kernel (for d = 40 its vector instructions outweigh the matrix
+// instructions), so it is kept to a maximum, one fused multiply-add, one exponential and the rounding
+// per logit: logits are compared raw and scaled inside the exponent, keys past T are masked only in
+// the chunk that holds them, and the accumulators are rescaled only when some query's maximum moved.
+template <typename T, int DT, int ODD>
 __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
 {
     constexpr int KT = key_tiles(DT);
     constexpr int KCH = 32 * KT;                   // keys per chunk
     constexpr int VT_STRIDE = KCH * 2 + 8;         // bytes per row of the transposed V chunk (pad 8)
-    constexpr int DKMAX = 2 * DT;                  // 16-wide steps over d for S^T
+    constexpr int DKMAX = 2 * DT;                  // 16-wide steps over d for S^T, at most
+    constexpr int DK = 2 * DT - ODD;               // ... and exactly
     constexpr int NV = (KT * DT + 1) / 2;          // K (and V) vectors a thread stages per chunk, at most
     extern __shared__ uint4 lds4[];
     char* lds = reinterpret_cast<char*>(lds4);
@@ -86,7 +114,6 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
     const int head = blockIdx.y;
     const int qi = (blockIdx.x * 4 + wave) * 32 + l32;
     const bool q_ok = qi < a.Nq;
-    const int dk = (d + 15) / 16;
     const int dvec = d / 8;                        // 16-byte vectors per row
 
     const int chunks_total = (a.T + KCH - 1) / KCH;
@@ -109,9 +136,13 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
         if (q_ok && dd < d)
             qf[s] = *(const uint4*)((const char*)a.q + (qrow * a.q_ld + head * d + dd) * 2);
     }
-    // rows d .. DT*32 of V^T never receive data: zero them once
+    // rows d .. DT*32 of V^T never receive data: zero them once (row d: ones, see above); likewise the
+    // 16 bytes behind the d values of every staged K row, which the last 16-wide step reads when d is
+    // not a multiple of 16
+    constexpr uint32_t ONE2 = std::is_same<T, bf16>::value ? 0x3f803f80u : 0x3c003c00u;
     for (int j = tid; j < (DT * 32 - d) * (VT_STRIDE / 4); j += 256)
-        *(uint32_t*)(vt + d * VT_STRIDE + j * 4) = 0u;
+        *(uint32_t*)(vt + d * VT_STRIDE + j * 4) = (ODD && j < KCH / 2) ? ONE2 : 0u;
+    for (int j = tid; j < KCH; j += 256) *(uint4*)(ks + j * k_stride + d * 2) = make_uint4(0, 0, 0, 0);
 
     // The vectors of a chunk this thread stages: (key, 16-byte group of d), the same for every chunk.
     int skey[NV], sdv[NV];
@@ -179,65 +210,81 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
             for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.0f;
             // all K fragments of the tile first (independent LDS reads, one latency), then the MFMAs:
             // read one by one, each in front of its MFMA, they cost a round trip to LDS per step
-            uint4 kf[DKMAX];
+            uint4 kf[DK];
 #pragma unroll
-            for (int s = 0; s < DKMAX; ++s) {
-                const int dd = 16 * s + 8 * half;
-                kf[s] = make_uint4(0, 0, 0, 0);
-                if (s < dk && dd < d) kf[s] = *(const uint4*)(ks + (kt * 32 + l32) * k_stride + dd * 2);
-            }
+            for (int s = 0; s < DK; ++s)
+                kf[s] = *(const uint4*)(ks + (kt * 32 + l32) * k_stride + (16 * s + 8 * half) * 2);
 #pragma unroll
-            for (int s = 0; s < DKMAX; ++s)
-                if (s < dk) Mma16<T>::run(kf[s], qf[s], sacc[kt]);
+            for (int s = 0; s < DK; ++s) Mma16<T>::run(kf[s], qf[s], sacc[kt]);
         }
         // online softmax; of tile kt this lane holds keys 8*(r/4) + 4*half + r%4 of its query
-        float mx = m_run;
+        if (t0 + KCH > a.T) {                      // the chunk that holds the end of the keys
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = t0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (key >= a.T) sacc[kt][r] = -INFINITY;
+                }
+        }
+        float mr = sacc[0][0];                     // raw logits: the scale (>= 0) goes into the exponent
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = t0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                sacc[kt][r] = key < a.T ? sacc[kt][r] * a.scale_log2e : -INFINITY;
-                mx = fmaxf(mx, sacc[kt][r]);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float alpha = exp2f(m_run - mx);  // first chunk: exp2(-inf) = 0
+            for (int r = 0; r < 16; ++r) mr = fmaxf(mr, sacc[kt][r]);
+        mr = fmaxf(mr, __shfl_xor(mr, 32));
+        const float mx = fmaxf(m_run, mr * a.scale_log2e);
+        if (__builtin_amdgcn_ballot_w64(mx != m_run) != 0ull) {     // some query's maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m_run - mx);  // first chunk: exp2(-inf) = 0
+            m_run = mx;
+            l_run *= alpha;
+#pragma unroll
+            for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[nt][r] *= alpha;
+        }
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kt][r] = exp2f(sacc[kt][r] - mx);
-        m_run = mx;
-#pragma unroll
-        for (int nt = 0; nt < DT; ++nt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[nt][r] *= alpha;
+            for (int r = 0; r < 16; ++r)
+                sacc[kt][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt][r], a.scale_log2e, -m_run));
 
         // O^T += V^T P^T, two steps of 16 keys per tile; step s uses registers 8s..8s+7.
-        // The probabilities enter this product in the storage type, and the row's denominator sums
-        // those same rounded values, so that numerator and denominator carry the same rounding (a row
-        // dominated by one key returns that key's value row exactly).  fp16 keeps 11 bits of a
+        // The probabilities enter this product in the storage type.  fp16 keeps 11 bits of a
         // probability; bf16 keeps 8, too few for the stated tolerance on rows spread over many keys,
         // so there a probability goes in as the sum of two bf16 numbers (the rounded value and the
         // rounded remainder, 16 bits together) and the same V^T fragments are multiplied twice.
+        // The row's denominator sums what the product multiplies with: through the row of ones (ODD),
+        // else here - the rounded fp16 values, or for bf16 the unrounded ones (which the two terms
+        // match to 2^-16) - so that numerator and denominator carry the same rounding and a row
+        // dominated by one key returns that key's value row.  With the row of ones fp16 may even
+        // truncate (one instruction per pair): the truncation is in both.
         constexpr bool TWO = std::is_same<T, bf16>::value;
         float lsum = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                union { uint4 u; T h[8]; } pf, pr;
+                uint32_t ph[4], pl[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float p = sacc[kt][8 * s + e];
-                    pf.h[e] = from_f32<T>(p);
-                    const float ph = to_f32(pf.h[e]);
+                for (int j = 0; j < 4; ++j) {
+                    const float p0 = sacc[kt][8 * s + 2 * j], p1 = sacc[kt][8 * s + 2 * j + 1];
                     if constexpr (TWO) {
-                        pr.h[e] = from_f32<T>(p - ph);
-                        lsum += ph + to_f32(pr.h[e]);
+                        ph[j] = pack2_rne<T>(p0, p1);
+                        const float h0 = __uint_as_float(ph[j] << 16), h1 = __uint_as_float(ph[j] & 0xffff0000u);
+                        pl[j] = pack2_rne<T>(p0 - h0, p1 - h1);
+                        if constexpr (!ODD) lsum += p0 + p1;
+                    } else if constexpr (ODD) {
+                        union { decltype(__builtin_amdgcn_cvt_pkrtz(0.f, 0.f)) v; uint32_t u; } r;
+                        r.v = __builtin_amdgcn_cvt_pkrtz(p0, p1);
+                        ph[j] = r.u;
                     } else {
-                        lsum += ph;
+                        union { f16x2 v; uint32_t u; } r;
+                        r.u = ph[j] = pack2_rne<T>(p0, p1);
+                        lsum += (float)r.v.x + (float)r.v.y;
                     }
                 }
+                const uint4 pf = make_uint4(ph[0], ph[1], ph[2], ph[3]);
                 uint2 lo[DT], hi[DT];                        // likewise: the V^T fragments of all tiles, then the MFMAs
 #pragma unroll
                 for (int nt = 0; nt < DT; ++nt) {
@@ -250,14 +297,21 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
 #pragma unroll
                 for (int nt = 0; nt < DT; ++nt) {
                     const uint4 vf = make_uint4(lo[nt].x, lo[nt].y, hi[nt].x, hi[nt].y);
-                    Mma16<T>::run(vf, pf.u, oacc[nt]);
-                    if constexpr (TWO) Mma16<T>::run(vf, pr.u, oacc[nt]);
+                    Mma16<T>::run(vf, pf, oacc[nt]);
+                    if constexpr (TWO) Mma16<T>::run(vf, make_uint4(pl[0], pl[1], pl[2], pl[3]), oacc[nt]);
                 }
             }
-        l_run = l_run * alpha + lsum;
+        l_run += lsum;
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    float l_tot;
+    if constexpr (ODD) {
+        // row d of O^T (in the last tile: row 8 or 16, held by the lower half of the wave in register 4 or 8)
+        const float ones = (d & 31) == 8 ? oacc[DT - 1][4] : oacc[DT - 1][8];
+        l_tot = __shfl(ones, l32);
+    } else {
+        l_tot = l_run + __shfl_xor(l_run, 32);
+    }
     if (!q_ok) return;
     if (a.splits == 1) {
         const float inv = 1.0f / l_tot;
@@ -534,7 +588,8 @@ static int launch_attn_dt(const AttnArgs& a, hipStream_t st)
     constexpr int KCH = 32 * key_tiles(DT);
     const size_t lds = (size_t)KCH * (a.d * 2 + 16) + (size_t)DT * 32 * (KCH * 2 + 8);
     dim3 grid((a.Nq + 127) / 128, a.heads, a.splits);
-    auto kern = attn_kernel<T, DT>;
+    const bool odd = ((a.d + 15) / 16) & 1;        // d % 32 is 8 or 16
+    auto kern = odd ? attn_kernel<T, DT, 1> : attn_kernel<T, DT, 0>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         SIGE_REQUIRE(e == hipSuccess, SIGE_ERR_HIP, "sige_sparse_attn: cannot reserve %zu bytes of LDS: %s", lds,
@@ -635,6 +690,7 @@ static int attn_entry(const char* who, AttnArgs& a, const void* q, int32_t q_ld,
     a.q = q; a.k = k; a.v = v; a.o = o; a.ws = (float*)workspace;
     a.q_ld = q_ld; a.kv_ld = kv_ld; a.o_ld = o_ld;
     a.Nq = Nq; a.T = T; a.heads = heads; a.d = d;
+    SIGE_REQUIRE(scale >= 0.0f, SIGE_ERR_UNSUPPORTED, "%s: the scale must not be negative", who);
     a.scale_log2e = scale * 1.4426950408889634f;
     const int KCH = keys_per_chunk(d, dt);
     const int chunks = (T + KCH - 1) / KCH;
