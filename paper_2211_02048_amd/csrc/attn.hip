@@ -70,7 +70,8 @@ struct AttnArgs {
     const void* k;
     const void* v;
     void* o;
-    float* ws;       // partials [split][head][Nq][d + 2] when splits > 1
+    float* ws;       // partials [split][head][Nq][d + 4] when splits > 1: the d sums, the maximum, the denominator, 2 unused
+                     // (rows of whole 16-byte vectors; d is a multiple of 4)
     int q_ld, kv_ld, o_ld;
     int Nq, T, heads, d;
     int splits, chunks_per_split;
@@ -166,15 +167,14 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
         }
     };
     // registers -> LDS: K rows as they are, V transposed
-    auto commit = [&](int c) {
-        const int t0 = c * KCH;
+    auto commit = [&]() {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
             if (skey[u] < 0) continue;
             const int key = skey[u], dv = sdv[u];
-            const bool in = t0 + key < a.T;
-            const uint4 kv = in ? kreg[u] : make_uint4(0, 0, 0, 0);
-            const uint4 vv = in ? vreg[u] : make_uint4(0, 0, 0, 0);
+            // (keys past the end hold a copy of the last key's rows: their logits are masked, so their
+            // probabilities are exactly zero)
+            const uint4 kv = kreg[u], vv = vreg[u];
             *(uint4*)(ks + key * k_stride + dv * 16) = kv;
             // element e of this vector is row dv*8+e of V^T; the index of the 4-key group is swizzled
             // by dv in its low three bits
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
     for (int c = c_begin; c < c_end; ++c) {
         const int t0 = c * KCH;
         __syncthreads();  // previous chunk fully consumed
-        commit(c);
+        commit();
         __syncthreads();
         if (c + 1 < c_end) fetch(c + 1);          // in flight while this chunk is multiplied
         __builtin_amdgcn_sched_barrier(0);        // (kept above the MFMAs: the scheduler would sink the loads)
@@ -328,17 +328,16 @@ __global__ __launch_bounds__(256, DT <= 3 ? 2 : 1) void attn_kernel(AttnArgs a)
                 }
             }
     } else {
-        float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 2);
-        if (half == 0) { w[d] = m_run; w[d + 1] = l_tot; }
+        float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 4);
+        if (half == 0) *(float2*)(w + d) = make_float2(m_run, l_tot);
 #pragma unroll
         for (int nt = 0; nt < DT; ++nt)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int dd = nt * 32 + 8 * rq + 4 * half;
-                if (dd < d) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) w[dd + e] = oacc[nt][4 * rq + e];
-                }
+                if (dd < d)
+                    *(float4*)(w + dd) = make_float4(oacc[nt][4 * rq], oacc[nt][4 * rq + 1], oacc[nt][4 * rq + 2],
+                                                     oacc[nt][4 * rq + 3]);
             }
     }
 }
@@ -503,64 +502,100 @@ __global__ __launch_bounds__(64 * NW) void attn_f32_kernel(AttnArgs a)
                                     oacc[nt][4 * rq + 3] * inv);
             }
     } else {
-        float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 2);
-        if (half == 0) { w[d] = m_run; w[d + 1] = l_tot; }
+        float* w = a.ws + (((long)blockIdx.z * a.heads + head) * a.Nq + qi) * (d + 4);
+        if (half == 0) *(float2*)(w + d) = make_float2(m_run, l_tot);
 #pragma unroll
         for (int nt = 0; nt < DT; ++nt)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int dd = nt * 32 + 8 * rq + 4 * half;
-                if (dd < d) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) w[dd + e] = oacc[nt][4 * rq + e];
-                }
+                if (dd < d)
+                    *(float4*)(w + dd) = make_float4(oacc[nt][4 * rq], oacc[nt][4 * rq + 1], oacc[nt][4 * rq + 2],
+                                                     oacc[nt][4 * rq + 3]);
             }
     }
 }
 
-// Merge of the per-split partials: one thread per (query, head, d element).
-template <typename T>
+// Merge of the per-split partials.  P neighbouring lanes share one (query, head, four consecutive d
+// elements): lane p takes splits p, p + P, p + 2P, p + 3P - all of its loads are in flight together, one
+// round trip to memory however many splits there are - and the P partial (maximum, denominator, sums)
+// triples are combined with a butterfly of lane exchanges, each step rescaling to the common maximum as
+// the attention kernel does.  The order of the sums is fixed by (P, splits): results are reproducible.
+template <typename T, int P>
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
 {
+    constexpr int B = 4;                           // splits per lane, at most (the host picks P accordingly)
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int d = a.d;
-    if (i >= (long)a.Nq * a.heads * d) return;
-    const int dd = (int)(i % d);
-    const int head = (int)((i / d) % a.heads);
-    const int qi = (int)(i / ((long)d * a.heads));
-    // One pass, sixteen splits fetched at a time (their loads are independent): the running maximum
-    // rescales what has been summed so far, as inside the attention kernel; the order of the sums is
-    // that of the split index.
-    constexpr int B = 16;
-    const long sstride = (long)a.heads * a.Nq * (d + 2);
-    const float* w0 = a.ws + ((long)head * a.Nq + qi) * (d + 2);
-    float m = -INFINITY, num = 0.0f, den = 0.0f;
-    for (int s0 = 0; s0 < a.splits; s0 += B) {
-        float mx[B], val[B], dn[B];
+    const int d = a.d, dq = d >> 2;
+    const long grp = i / P;
+    const int sub = (int)(i % P);
+    const bool live = grp < (long)a.Nq * a.heads * dq;      // (whole groups: P divides the workgroup size)
+    const long g = live ? grp : 0;
+    const int dd = (int)(g % dq) * 4;
+    const int head = (int)((g / dq) % a.heads);
+    const int qi = (int)(g / ((long)dq * a.heads));
+    const long sstride = (long)a.heads * a.Nq * (d + 4);
+    const float* w0 = a.ws + ((long)head * a.Nq + qi) * (d + 4);
+    float2 ml[B];
+    float4 val[B];
 #pragma unroll
-        for (int j = 0; j < B; ++j) {
-            const float* w = w0 + min(s0 + j, a.splits - 1) * sstride;
-            mx[j] = w[d];
-            val[j] = w[dd];
-            dn[j] = w[d + 1];
-        }
-        float mb = m;
-#pragma unroll
-        for (int j = 0; j < B; ++j)
-            if (s0 + j < a.splits) mb = fmaxf(mb, mx[j]);
-        const float r = exp2f(m - mb);       // 0 on the first batch (m = -inf), when nothing is summed yet
-        num *= r;
-        den *= r;
-        m = mb;
-#pragma unroll
-        for (int j = 0; j < B; ++j) {
-            if (s0 + j >= a.splits) break;
-            const float f = exp2f(mx[j] - m);
-            num += val[j] * f;
-            den += dn[j] * f;
-        }
+    for (int j = 0; j < B; ++j) {
+        const float* w = w0 + min(sub + j * P, a.splits - 1) * sstride;
+        ml[j] = *(const float2*)(w + d);
+        val[j] = *(const float4*)(w + dd);
     }
-    ((T*)a.o)[(long)qi * a.o_ld + head * d + dd] = from_f32<T>(num / den);
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < B; ++j)
+        if (sub + j * P < a.splits) m = fmaxf(m, ml[j].x);
+    float den = 0.0f, num[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int j = 0; j < B; ++j) {
+        const float f = sub + j * P < a.splits ? exp2f(ml[j].x - m) : 0.0f;
+        num[0] += val[j].x * f; num[1] += val[j].y * f; num[2] += val[j].z * f; num[3] += val[j].w * f;
+        den += ml[j].y * f;
+    }
+#pragma unroll
+    for (int x = 1; x < P; x <<= 1) {
+        const float m2 = __shfl_xor(m, x), den2 = __shfl_xor(den, x);
+        float n2[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) n2[e] = __shfl_xor(num[e], x);
+        const float mm = fmaxf(m, m2);
+        // a lane without splits carries (-inf, 0, 0): its weight is 0, not exp2(-inf + inf)
+        const float f1 = m == -INFINITY ? 0.0f : exp2f(m - mm), f2 = m2 == -INFINITY ? 0.0f : exp2f(m2 - mm);
+        // both partners add in the same order (lower lane's share first), so they hold the same bits
+        const bool low = (sub & x) == 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) num[e] = low ? num[e] * f1 + n2[e] * f2 : n2[e] * f2 + num[e] * f1;
+        den = low ? den * f1 + den2 * f2 : den2 * f2 + den * f1;
+        m = mm;
+    }
+    if (!live || sub != 0) return;
+    T* o = (T*)a.o + (long)qi * a.o_ld + head * d + dd;
+    const float inv = 1.0f / den;
+    if constexpr (sizeof(T) == 4) {
+        *(float4*)o = make_float4(num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv);
+    } else {
+        union { uint2 u; T h[4]; } x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x.h[e] = from_f32<T>(num[e] * inv);
+        *(uint2*)o = x.u;
+    }
+}
+
+template <typename T>
+static int launch_merge(const AttnArgs& a, hipStream_t st)
+{
+    const long groups = (long)a.Nq * a.heads * (a.d / 4);
+    auto go = [&](auto kern, int P) {
+        hipLaunchKernelGGL(kern, dim3((int)((groups * P + 255) / 256)), dim3(256), 0, st, a);
+    };
+    if (a.splits <= 4) go(attn_merge_kernel<T, 1>, 1);
+    else if (a.splits <= 16) go(attn_merge_kernel<T, 4>, 4);
+    else go(attn_merge_kernel<T, 16>, 16);          // at most 64 splits
+    SIGE_LAUNCH_CHECK("sige_sparse_attn(merge)");
+    return SIGE_OK;
 }
 
 // Number of key splits: a workgroup walks through its key chunks one after the other and each costs
@@ -597,11 +632,7 @@ static int launch_attn_dt(const AttnArgs& a, hipStream_t st)
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
     SIGE_LAUNCH_CHECK("sige_sparse_attn");
-    if (a.splits > 1) {
-        const long n = (long)a.Nq * a.heads * a.d;
-        hipLaunchKernelGGL((attn_merge_kernel<T>), dim3((int)((n + 255) / 256)), dim3(256), 0, st, a);
-        SIGE_LAUNCH_CHECK("sige_sparse_attn(merge)");
-    }
+    if (a.splits > 1) return launch_merge<T>(a, st);
     return SIGE_OK;
 }
 
@@ -633,11 +664,7 @@ static int launch_attn_f32_as(const AttnArgs& a, hipStream_t st)
     }
     hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds, st, a);
     SIGE_LAUNCH_CHECK("sige_sparse_attn");
-    if (a.splits > 1) {
-        const long n = (long)a.Nq * a.heads * a.d;
-        hipLaunchKernelGGL((attn_merge_kernel<float>), dim3((int)((n + 255) / 256)), dim3(256), 0, st, a);
-        SIGE_LAUNCH_CHECK("sige_sparse_attn(merge)");
-    }
+    if (a.splits > 1) return launch_merge<float>(a, st);
     return SIGE_OK;
 }
 
@@ -666,7 +693,7 @@ extern "C" size_t sige_sparse_attn_workspace_bytes(int32_t Nq, int32_t T, int32_
     // the larger of what the half-precision and the single-precision kernels would use
     const int splits = std::max(pick_splits(Nq, T, heads, d, SIGE_F16), pick_splits(Nq, T, heads, d, SIGE_F32));
     if (splits <= 1) return 0;
-    return (size_t)splits * heads * Nq * (d + 2) * sizeof(float);
+    return (size_t)splits * heads * Nq * (d + 4) * sizeof(float);
 }
 
 static int attn_entry(const char* who, AttnArgs& a, const void* q, int32_t q_ld, const void* k, const void* v,
@@ -696,8 +723,8 @@ static int attn_entry(const char* who, AttnArgs& a, const void* q, int32_t q_ld,
     const int chunks = (T + KCH - 1) / KCH;
     int splits = pick_splits(Nq, T, heads, d, dt);
     if (splits > 1 && (workspace == nullptr ||
-                       workspace_bytes < (size_t)splits * heads * Nq * (d + 2) * sizeof(float) ||
-                       (reinterpret_cast<uintptr_t>(workspace) & 3u)))
+                       workspace_bytes < (size_t)splits * heads * Nq * (d + 4) * sizeof(float) ||
+                       (reinterpret_cast<uintptr_t>(workspace) & 15u)))
         splits = 1;
     a.chunks_per_split = (chunks + splits - 1) / splits;
     a.splits = (chunks + a.chunks_per_split - 1) / a.chunks_per_split;
