@@ -468,12 +468,13 @@ int sige_version(void);
  *   DIFF_LOADS         16-byte loads per lane and tensor in flight in the difference kernel (1, 2, 4)
  *   DIFF_WGS           accepted and ignored (the difference kernel runs one step per wave)
  *   CONV_DIRECT        0: the shapes whose waves do not split K send their accumulators through LDS
- *                      instead of straight from the registers                                    */
+ *                      instead of straight from the registers
+ *   CONV_LDS_PAD       bytes between the staged pixels' channel runs in LDS (a multiple of 16)        */
 typedef enum {
     SIGE_KNOB_CONV_CFG = 0, SIGE_KNOB_CONV_KC = 1, SIGE_KNOB_CONV_SPLIT = 2, SIGE_KNOB_CONV_HALF = 3,
     SIGE_KNOB_CONV_SPLIT_WGS = 4, SIGE_KNOB_CONV_POINTWISE = 5, SIGE_KNOB_CONV_POINTWISE_W4 = 6,
     SIGE_KNOB_CONV_PAIR_WGS = 7, SIGE_KNOB_ATTN_WGS = 8, SIGE_KNOB_DIFF_LOADS = 9, SIGE_KNOB_DIFF_WGS = 10,
-    SIGE_KNOB_CONV_DIRECT = 11, SIGE_KNOB_COUNT = 12
+    SIGE_KNOB_CONV_DIRECT = 11, SIGE_KNOB_CONV_LDS_PAD = 12, SIGE_KNOB_COUNT = 13
 } sige_knob;
 int sige_set_knob(sige_knob knob, int32_t value);
 int32_t sige_get_knob(sige_knob knob);

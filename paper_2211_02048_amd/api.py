@@ -29,7 +29,7 @@ EXPORTS = ["sige_reduce_mask", "sige_reduce_mask_workspace_bytes", "sige_reduce_
 
 # sige_knob of the header
 KNOBS = {"CONV_CFG": 0, "CONV_KC": 1, "CONV_SPLIT": 2, "CONV_HALF": 3, "CONV_SPLIT_WGS": 4, "CONV_POINTWISE": 5,
-         "CONV_POINTWISE_W4": 6, "CONV_PAIR_WGS": 7, "ATTN_WGS": 8, "DIFF_LOADS": 9, "DIFF_WGS": 10,
+         "CONV_POINTWISE_W4": 6, "CONV_PAIR_WGS": 7, "ATTN_WGS": 8, "DIFF_LOADS": 9, "DIFF_WGS": 10, "CONV_LDS_PAD": 12,
          "CONV_DIRECT": 11}
 
 

@@ -4,8 +4,8 @@
 namespace sige {
 
 static thread_local char g_err[512] = "";
-int g_knobs[SIGE_KNOB_COUNT] = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
-static_assert(SIGE_KNOB_COUNT == 12, "one initialiser per knob");
+int g_knobs[SIGE_KNOB_COUNT] = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
+static_assert(SIGE_KNOB_COUNT == 13, "one initialiser per knob");
 
 int fail(int code, const char* fmt, ...)
 {
