@@ -147,13 +147,27 @@ __device__ __forceinline__ void pixel_rc(const MarkSetN<NL>& mk, int pix, int& p
     }
 }
 
-// All lists' phase words in one round trip, then the marks.
+// All lists' phase words (one round trip; lists beyond mk.n read the first list's word and are not used).
 template <int NL>
-__device__ __forceinline__ void mark_pixel(const MarkSetN<NL>& mk, int py, int px)
+__device__ __forceinline__ void load_phases(const MarkSetN<NL>& mk, uint32_t (&ph)[NL > 0 ? NL : 1])
 {
-    uint32_t ph[NL > 0 ? NL : 1];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) ph[i] = i < mk.n ? phase_of(mk.m[i].flags, mk.m[i].half) : 0u;
+    for (int i = 0; i < NL; ++i) {
+        const bool used = i < mk.n;
+        // (the address goes through a vector register that the compiler cannot see into: knowing it uniform,
+        // it would move the word into a scalar register at once and wait for it in front of everything else)
+        unsigned long long pv = reinterpret_cast<unsigned long long>((used ? mk.m[i].flags : mk.m[0].flags) +
+                                                                     2 * (used ? mk.m[i].half : mk.m[0].half));
+        asm volatile("" : "+v"(pv));
+        // (as a pointer into global memory: a generic one would make this a flat load, which also counts as
+        // an LDS access and would be waited for with the kernel arguments)
+        ph[i] = *(const __attribute__((address_space(1))) uint32_t*)pv;
+    }
+}
+
+template <int NL>
+__device__ __forceinline__ void mark_pixel(const MarkSetN<NL>& mk, const uint32_t (&ph)[NL > 0 ? NL : 1], int py, int px)
+{
 #pragma unroll
     for (int i = 0; i < NL; ++i)
         if (i < mk.n) mark_blocks(mk.m[i], ph[i], py, px);
@@ -189,6 +203,11 @@ void diff_mask_pow2(const uint4* __restrict__ a_o, const uint4* __restrict__ a_e
     // (one step per wave and no loop around it: the compiler moves whatever a loop leaves unchanged to
     // the front of it, and here that is the marking path's arithmetic, run by every wave for nothing)
     const long base = wave * (64L * U);
+    // The phase words of the lists are asked for FIRST, by every wave: loads return in the order they were
+    // issued and these hit the cache (one address per list for the whole launch), so they are there before the
+    // streamed data and the few lanes that mark do not wait for a second round trip behind it.
+    uint32_t ph[NL > 0 ? NL : 1] = {};
+    if constexpr (NL > 0) load_phases(mk, ph);       // (an instance with lists is launched only with mk.n >= 1)
     if (base < n_vec) {
         // Unconditional loads at clamped indices, so that all 2U of them are in flight before the first is
         // looked at (with a bounds test around each pair the compiler finishes one pair before it issues the
@@ -216,10 +235,7 @@ void diff_mask_pow2(const uint4* __restrict__ a_o, const uint4* __restrict__ a_e
                     if (marked && mk.n) {
                         int py, px;                               // the host checked that pixels fit 31 bits
                         pixel_rc(mk, (int)pix, py, px);
-                        // (the phase words are fetched here, by the few lanes that mark.  Fetched up front by
-                        // every wave they are one address asked for by 10^5 waves: measured +2 us for the
-                        // kernel as a per-lane load, +1 us as a wave-uniform load of a read-only argument)
-                        mark_pixel(mk, py, px);
+                        mark_pixel(mk, ph, py, px);
                     }
                 }
             }
@@ -350,6 +366,8 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) publish_phase(mk);
     if (t >= Hm * words_per_row) return;
+    uint32_t ph[MAX_LISTS];
+    load_phases(mk, ph);
     const int Wm = mk.Wm;
     const int y = t / words_per_row, x0 = (t - y * words_per_row) * 4;
     const uint8_t* row = mask + (long)y * Wm;
@@ -359,11 +377,11 @@ __global__ __launch_bounds__(256) void mark_from_mask_kernel(const uint8_t* __re
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if ((w >> (8 * j)) & 0xffu)
-                mark_pixel(mk, y, x0 + j);
+                mark_pixel(mk, ph, y, x0 + j);
     } else {
         for (int x = x0; x < min(x0 + 4, Wm); ++x)
             if (row[x])
-                mark_pixel(mk, y, x);
+                mark_pixel(mk, ph, y, x);
     }
 }
 
