@@ -80,6 +80,58 @@ def test_unet_every_layer_teacher_forced(setup):
     rep_e.assert_clean(min_checked=70)
 
 
+def test_unet_full_size_every_layer_teacher_forced():
+    """Benchmark configuration 3 at FULL size (256x256 image, channels 128/128/256/256/512/512, two
+    ResBlocks per level, attention at 16x16, fp16, 16x16 blocks, ~1.2 % blob edit, sparse layers at
+    resolution >= 64): both passes under teacher forcing, every stored tensor of every layer compared
+    element by element at 1e-2 with the oracle, which computes each layer densely on the whole map.
+    This reaches the kernel selections of the real step (the launch shared by a ResBlock's first
+    convolution and its shortcut, the eight-wave whole-Cin shapes of the 512-channel layers, the K split
+    over workgroups with its second kernel, the few-row 1x1 kernel, attention at T = 256), which the
+    64x64 replica does not.  Block lists bit for bit."""
+    from oracle import unet as ounet
+    dtype, res, ch, block = "f16", 256, (128, 128, 256, 256, 512, 512), 16
+    bufs, ops = inputs.unet_topology(res, 3, ch, (16,), 4)
+    P = inputs.unet_params(1003, ops, dtype)
+    img_o, img_e, mask = inputs.unet_images(1003, res, 0.012, dtype)
+    trace_d, trace_e = [], []
+    print("oracle: dense pass on the original image", flush=True)
+    cache, stats = ounet.unet_pass(bufs, ops, P, f64(img_o), storage=dtype, block=block, trace=trace_d)
+    print("oracle: edit pass", flush=True)
+    edit, blocks = ounet.unet_pass(bufs, ops, P, f64(img_e), storage=dtype, block=block, cache=cache, stats=stats,
+                                   mask=mask, dilate=1, min_sparse_res=64, trace=trace_e)
+    net = SigeUNet(res, ch, (16,), 4, dtype=dtype, block=block, dilate=1, min_sparse_res=64, params=P)
+    s = dict(dtype=dtype, bufs=bufs, ops=ops, img_o=img_o, img_e=img_e, mask=mask, cache=cache, edit=edit,
+             blocks=blocks, net=net, stats=stats, trace_d=trace_d, trace_e=trace_e)
+    print("GPU: both passes under teacher forcing", flush=True)
+    rep_d, rep_e = teacher_forced(s)
+    n_sparse = 0
+    for n, L in net.layers.items():
+        if L["sparse"] and L["op"]["kind"] == "conv" and L["op"]["scatter"]:
+            bl = L["list"][1]
+            assert np.array_equal(bl.indices[:bl.n_host].cpu().numpy(), blocks[n]), n
+            assert 0 < bl.n_host < bl.g.grid_blocks
+            n_sparse += 1
+    assert n_sparse >= 20
+    # which kernels the sparse step selected, by layer sizes
+    td, seen = inputs.DTYPES[dtype], set()
+    for n, L in net.layers.items():
+        if "conv" not in L:
+            continue
+        c, bl = L["conv"], L["list"][1 if L["sparse"] else 0]
+        key = (c.g.H_in, c.g.k, c.g.stride, c.Cin, c.Cout)
+        if key in seen:
+            continue
+        seen.add(key)
+        nb = max(bl.n_host, 1)
+        nbytes = api.sige_conv_workspace_bytes(td, c.g, c.Cin, c.Cout, nb)
+        print(f"{c.g.H_in}x{c.g.W_in} {c.g.k}x{c.g.k}/{c.g.stride} {c.Cin}->{c.Cout}, {nb} blocks: "
+              f"{api.sige_conv_plan(td, c.g, c.Cin, c.Cout, nb, workspace_bytes=nbytes)!r}")
+    print(f"worst error / bound: pre-computation pass {rep_d.worst:.3f}, sparse step {rep_e.worst:.3f}")
+    rep_d.assert_clean(min_checked=80)
+    rep_e.assert_clean(min_checked=80)
+
+
 def test_unet_precompute_and_sparse_step(setup):
     s = setup
     net, td = s["net"], inputs.DTYPES[s["dtype"]]
