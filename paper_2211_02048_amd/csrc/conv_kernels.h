@@ -85,6 +85,7 @@ struct ConvArgs {
     // gated GELU folded into the epilogue (tiles out only): the Cout convolution channels come in
     // groups of 16 = 8 values followed by their 8 gates; out has Cout / 2 channels
     int glu;
+    int stagger;  // 128 x 128 shape, many rounds of workgroups: every other workgroup of the first round starts late (units of sleep)
     int direct;   // shapes with swapped operands: accumulators leave straight from the registers (else through LDS)
     // Marked mode (conv_pair_kernel only): the block list is not given but built by every workgroup
     // from the per-block flags that the marking pass left (mk_nb of them, mk_nbx per block row); the
@@ -807,6 +808,17 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
 template <typename T, int TM, int TN, int WM, int WN, int WK, int KC, int KK>
 __global__ __launch_bounds__(64 * WM * WN * WK, (WM * WN * WK > 4 ? 1 : 2)) void conv_kernel(ConvArgs a)
 {
+    if constexpr (WK == 1 && TM * TN >= 4) {
+        // A workgroup's life is staging, then MFMA, then the epilogue; the two workgroups that share a
+        // compute unit start together and would go through these phases in step for the whole launch
+        // (memory, matrix pipes and memory again taking turns).  Half of the first round starts late,
+        // which puts the co-resident workgroups out of phase; later rounds inherit the offset.
+        if (a.stagger > 0) {
+            const unsigned id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+            if (id < 512u && (id & 1u))
+                for (int i = 0; i < a.stagger; ++i) __builtin_amdgcn_s_sleep(127);
+        }
+    }
     conv_body<T, TM, TN, WM, WN, WK, KC, KK>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
