@@ -429,26 +429,40 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
     // 16-byte channel runs (no trip through LDS, no barrier).  Their bias is folded into the start value
     // of the accumulators; the other shapes add it when the waves' sums meet in LDS.
     constexpr bool SWAP = WK == 1;
+    // The start values are only requested here (four-float vectors where the run is whole) and go into
+    // the accumulators after the first chunk is staged: taken at once they would make every workgroup
+    // wait for a round trip to memory before it has asked for its weights and its tile.
     f32x16 acc[TM][TN];
+    f32x16 acc_init[TN];
     float bias_v[TN];
+    const bool bias4 = aligned16_dev(a.bias);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int o = (nt0 + tn) * 32 + l32;
         bias_v[tn] = (!SWAP && a.bias && o < a.Cout && wk == 0 && a.partial == nullptr) ? a.bias[o] : 0.0f;
-        f32x16 init;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) init[r] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc_init[tn][r] = 0.0f;
         if (SWAP && a.bias != nullptr && a.partial == nullptr) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int ob = (nt0 + tn) * 32 + 8 * g + 4 * half;
+                if (bias4 && ob + 4 <= a.Cout) {
+                    const f32x4 q = *(const f32x4*)(a.bias + ob);
+                    acc_init[tn][4 * g] = q.x; acc_init[tn][4 * g + 1] = q.y;
+                    acc_init[tn][4 * g + 2] = q.z; acc_init[tn][4 * g + 3] = q.w;
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) init[4 * g + i] = ob + i < a.Cout ? a.bias[ob + i] : 0.0f;
+                    for (int i = 0; i < 4; ++i) acc_init[tn][4 * g + i] = ob + i < a.Cout ? a.bias[ob + i] : 0.0f;
+                }
             }
         }
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = init;
     }
+    auto start_accumulators = [&]() {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = acc_init[tn];
+    };
 
     // weight fragment pointers of this wave's Cout tiles (at tap 0, this wave's first K step)
     const uint4* __restrict__ wp[TN];
@@ -624,8 +638,13 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
     if constexpr (KK > 0) {
 #pragma unroll
         for (int d = 0; d < D; ++d) fetch(ring[d], ch0, d / KW, d % KW);
+        // (shapes with start values from memory stage the first chunk ahead of the loop, so that those values
+        // are dead before the loop begins; the others keep the one staging site - their kernels start cold in a
+        // network step and every kilobyte of code is fetched first)
+        if constexpr (SWAP) stage(ch0);
+        start_accumulators();
         for (int chunk = ch0; chunk < ch1; ++chunk) {
-            stage(chunk);
+            if (!SWAP || chunk != ch0) stage(chunk);
             // A rows run AD steps ahead of their MFMAs: one step where a step holds four MFMAs or
             // more, two where it holds fewer and would not cover the LDS latency.  In the small shapes
             // a barrier after the loads keeps them in front of this step's MFMAs (the scheduler
@@ -648,6 +667,7 @@ __device__ __forceinline__ void conv_body(const ConvArgs& a, const int bx, const
             }
         }
     } else {
+        start_accumulators();
         for (int chunk = ch0; chunk < ch1; ++chunk) {
             stage(chunk);
 #pragma nounroll
