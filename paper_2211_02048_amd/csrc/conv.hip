@@ -269,8 +269,9 @@ static int prepare_conv(const char* who, sige_dtype dt, const sige_geom* g, int 
     a.direct = knob(SIGE_KNOB_CONV_DIRECT) != 0;
     // 128 x 128 shape with at least two rounds of workgroups: every other workgroup of the first round starts one
     // sleep unit (3 us) late, so that the two workgroups of a compute unit do not stage, multiply and store in
-    // step (measured + 2 - 4 % at 512 x 512 and 1024 x 1024 with 128 channels; with a single round it only costs)
-    a.stagger = (p->cfg == 0 && (long)p->groups * p->bands * p->slabs * p->ksplit >= 1024) ? 1 : 0;
+    // step (measured + 2 - 4 % at 512 x 512 and 1024 x 1024 with 128 channels; with a single round it only costs,
+    // and so it does on a 1x1 call, whose two rounds are memory traffic from start to end: 30 -> 32.5 us)
+    a.stagger = (p->cfg == 0 && g->k >= 3 && (long)p->groups * p->bands * p->slabs * p->ksplit >= 1024) ? 1 : 0;
     a.d_pb = fast_div(p->rows * g->block_w);
     a.d_per = fast_div(p->trows * tw);
     a.d_tw = fast_div(tw);
