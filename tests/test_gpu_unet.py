@@ -422,3 +422,43 @@ def test_latent_unet_full_size_level_teacher_forced(res, C, area):
     print(f"attention: T={res * res}, {heads} heads of {C // heads}, active tokens {sorted(set(n_tok.values()))}")
     rep_d.assert_clean(min_checked=70)
     rep_e.assert_clean(min_checked=70)
+
+
+def test_latent_unet_full_size_whole_step_teacher_forced():
+    """Benchmark configuration 4 at FULL size and as a whole: latent 64x64x4, channels 320/640/1280/1280, two
+    ResBlocks per level each followed by a transformer block (8 heads of 40/80/160, T = 4096/1024/256,
+    cross-attention over 77x768 text embeddings, gated-GELU feed-forward) at 64/32/16, bf16, 8x8 blocks, ~1 %
+    edit.  Both passes under teacher forcing: every stored tensor of every library call - convolutions, token
+    norms, projections, both attentions, feed-forward layers, residual scatters, inside all twelve transformer
+    blocks - compared element by element at 1e-2 with the oracle, which computes each layer on the whole map
+    (about a minute of CPU time per pass).  Block lists bit for bit."""
+    from oracle import unet as ounet
+    dtype, res, ch, att, heads, block, ctx = "bf16", 64, (320, 640, 1280, 1280), (64, 32, 16), 8, 8, (77, 768)
+    bufs, ops = inputs.unet_topology(res, 4, ch, att, heads, attn_kind="xfmr", ctx=ctx)
+    P = inputs.unet_params(1004, ops, dtype, in_ch=4)
+    img_o, img_e, mask = inputs.unet_images(1004, res, 0.01, dtype, in_ch=4)
+    trace_d, trace_e = [], []
+    print("oracle: dense pass on the original latent", flush=True)
+    cache, stats = ounet.unet_pass(bufs, ops, P, f64(img_o), storage=dtype, block=block, trace=trace_d)
+    print("oracle: edit pass", flush=True)
+    edit, blocks = ounet.unet_pass(bufs, ops, P, f64(img_e), storage=dtype, block=block, cache=cache, stats=stats,
+                                   mask=mask, dilate=1, min_sparse_res=16, trace=trace_e)
+    net = SigeUNet(res, ch, att, heads, dtype=dtype, block=block, dilate=1, min_sparse_res=16, params=P, in_ch=4,
+                   attn_kind="xfmr", ctx=ctx)
+    s = dict(dtype=dtype, bufs=bufs, ops=ops, img_o=img_o, img_e=img_e, mask=mask, cache=cache, edit=edit,
+             blocks=blocks, net=net, stats=stats, trace_d=trace_d, trace_e=trace_e)
+    print("GPU: both passes under teacher forcing", flush=True)
+    rep_d, rep_e = teacher_forced(s, inner=True)
+    n_x = 0
+    for n, L in net.layers.items():
+        if L["sparse"] and n in blocks:
+            bl = L["list"][1]
+            assert np.array_equal(bl.indices[:bl.n_host].cpu().numpy(), blocks[n]), n
+            if L["op"]["kind"] == "xfmr":
+                assert 0 < bl.n_host < bl.g.grid_blocks
+                n_x += 1
+    assert n_x == 12
+    print(f"worst error / bound: pre-computation pass {rep_d.worst:.3f}, sparse step {rep_e.worst:.3f}; "
+          f"{rep_d.n_checked} + {rep_e.n_checked} tensors compared")
+    rep_d.assert_clean(min_checked=220)
+    rep_e.assert_clean(min_checked=220)
