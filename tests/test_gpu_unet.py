@@ -424,8 +424,9 @@ def test_latent_unet_full_size_level_teacher_forced(res, C, area):
     rep_e.assert_clean(min_checked=70)
 
 
-def test_latent_unet_full_size_whole_step_teacher_forced():
-    """Benchmark configuration 4 at FULL size and as a whole: latent 64x64x4, channels 320/640/1280/1280, two
+@pytest.mark.parametrize("area", [0.01, 0.2])
+def test_latent_unet_full_size_whole_step_teacher_forced(area):
+    """Benchmark configuration 4 at FULL size and as a whole (the ends of its edit sweep, 1 % and 20 %): latent 64x64x4, channels 320/640/1280/1280, two
     ResBlocks per level each followed by a transformer block (8 heads of 40/80/160, T = 4096/1024/256,
     cross-attention over 77x768 text embeddings, gated-GELU feed-forward) at 64/32/16, bf16, 8x8 blocks, ~1 %
     edit.  Both passes under teacher forcing: every stored tensor of every library call - convolutions, token
@@ -436,7 +437,7 @@ def test_latent_unet_full_size_whole_step_teacher_forced():
     dtype, res, ch, att, heads, block, ctx = "bf16", 64, (320, 640, 1280, 1280), (64, 32, 16), 8, 8, (77, 768)
     bufs, ops = inputs.unet_topology(res, 4, ch, att, heads, attn_kind="xfmr", ctx=ctx)
     P = inputs.unet_params(1004, ops, dtype, in_ch=4)
-    img_o, img_e, mask = inputs.unet_images(1004, res, 0.01, dtype, in_ch=4)
+    img_o, img_e, mask = inputs.unet_images(1004, res, area, dtype, in_ch=4)
     trace_d, trace_e = [], []
     print("oracle: dense pass on the original latent", flush=True)
     cache, stats = ounet.unet_pass(bufs, ops, P, f64(img_o), storage=dtype, block=block, trace=trace_d)
@@ -455,7 +456,7 @@ def test_latent_unet_full_size_whole_step_teacher_forced():
             bl = L["list"][1]
             assert np.array_equal(bl.indices[:bl.n_host].cpu().numpy(), blocks[n]), n
             if L["op"]["kind"] == "xfmr":
-                assert 0 < bl.n_host < bl.g.grid_blocks
+                assert 0 < bl.n_host <= bl.g.grid_blocks
                 n_x += 1
     assert n_x == 12
     print(f"worst error / bound: pre-computation pass {rep_d.worst:.3f}, sparse step {rep_e.worst:.3f}; "
