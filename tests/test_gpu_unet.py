@@ -80,9 +80,11 @@ def test_unet_every_layer_teacher_forced(setup):
     rep_e.assert_clean(min_checked=70)
 
 
-def test_unet_full_size_every_layer_teacher_forced():
+@pytest.mark.parametrize("area", [0.012, 0.155])
+def test_unet_full_size_every_layer_teacher_forced(area):
     """Benchmark configuration 3 at FULL size (256x256 image, channels 128/128/256/256/512/512, two
-    ResBlocks per level, attention at 16x16, fp16, 16x16 blocks, ~1.2 % blob edit, sparse layers at
+    ResBlocks per level, attention at 16x16, fp16, 16x16 blocks, blob edits of ~1.2 % and 15.5 % - the two
+    edited areas of the paper's showcased DDPM example, Tab. 2 - sparse layers at
     resolution >= 64): both passes under teacher forcing, every stored tensor of every layer compared
     element by element at 1e-2 with the oracle, which computes each layer densely on the whole map.
     This reaches the kernel selections of the real step (the launch shared by a ResBlock's first
@@ -93,7 +95,7 @@ def test_unet_full_size_every_layer_teacher_forced():
     dtype, res, ch, block = "f16", 256, (128, 128, 256, 256, 512, 512), 16
     bufs, ops = inputs.unet_topology(res, 3, ch, (16,), 4)
     P = inputs.unet_params(1003, ops, dtype)
-    img_o, img_e, mask = inputs.unet_images(1003, res, 0.012, dtype)
+    img_o, img_e, mask = inputs.unet_images(1003, res, area, dtype)
     trace_d, trace_e = [], []
     print("oracle: dense pass on the original image", flush=True)
     cache, stats = ounet.unet_pass(bufs, ops, P, f64(img_o), storage=dtype, block=block, trace=trace_d)
