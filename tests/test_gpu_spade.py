@@ -37,7 +37,8 @@ CASES = {
 @pytest.mark.parametrize("case,dtype", [("replica", "f16"), ("replica", "f32"), ("full", "f16")])
 def test_spade_every_layer_teacher_forced(case, dtype):
     """The per-layer bar inside the generator: 1e-2 (fp16) / 1e-4 (fp32), element-wise, for every stored
-    tensor of the pre-computation pass and of a sparse step (modulated gathers, label-map and modulation
+    tensor of the pre-computation pass and of two successive sparse steps - the second edit relabels the already
+    edited map and runs on the caches the first one left - (modulated gathers, label-map and modulation
     convolutions, up-samplings, shortcut tiles), each computed by the GPU from the oracle's own inputs
     (see teacher.py).  The full-size case runs the kernel shapes the benchmarked step selects (1024-channel
     layers at 8x16 to 32x64, the few-block layers at 256x512); the oracle computes every layer densely
@@ -50,18 +51,16 @@ def test_spade_every_layer_teacher_forced(case, dtype):
     P = inputs.spade_params(1005, bufs, ops, dtype, n_labels=n_labels)
     out_h, out_w = sizes[-1]
     lab0 = inputs.label_map(1005, out_h, out_w, n_labels, regions)
-    lab1 = inputs.relabel(1006, lab0, area, n_labels)
-    seg0, seg1 = (inputs.one_hot_pyramid(l, sizes, n_labels, label_pad, dtype) for l in (lab0, lab1))
+    labs = [lab0, inputs.relabel(1006, lab0, area, n_labels)]
+    labs.append(inputs.relabel(1007, labs[1], area, n_labels))       # a second edit, of the edited map
+    segs = [inputs.one_hot_pyramid(l, sizes, n_labels, label_pad, dtype) for l in labs]
+    seg0 = segs[0]
     seg64 = lambda s: {k: v.double().numpy() for k, v in s.items()}
-    trace_d, trace_e = [], []
+    trace_d = []
     print(f"{case}: oracle, pass on the original label map", flush=True)
     cache, stats = osp.spade_pass(bufs, ops, P, seg64(seg0), storage=dtype, block=block, min_sparse=min_sparse,
                                   trace=trace_d)
-    mask = (lab1 != lab0).astype(np.uint8)
-    print(f"{case}: oracle, edit pass", flush=True)
-    want, blocks = osp.spade_pass(bufs, ops, P, seg64(seg1), storage=dtype, block=block, cache=cache, stats=stats,
-                                  mask=mask, dilate=1, min_sparse=min_sparse, trace=trace_e)
-    print(f"{case}: GPU, both passes under teacher forcing", flush=True)
+    print(f"{case}: GPU, pre-computation pass under teacher forcing", flush=True)
     net = SigeSpade(topo, dtype=dtype, block=block, min_sparse=min_sparse, params=P, n_labels=n_labels)
     start = {n: np.zeros(shape) for n, shape in bufs.items()}
     start["z"] = f64(P["z"])
@@ -73,30 +72,42 @@ def test_spade_every_layer_teacher_forced(case, dtype):
     try:
         net.precompute({k: v.cuda() for k, v in seg0.items()})
         torch.cuda.synchronize()
+    finally:
         net.hook = None
+    print(f"{case}: worst error / bound, pre-computation pass: {t_d.rep.worst:.3f}")
+    t_d.rep.assert_clean(min_checked=50)
+    # two successive edits, each against the current map and on the caches the one before left (Sec. 4.2)
+    for e in (1, 2):
+        trace_e = []
+        mask = (labs[e] != labs[e - 1]).astype(np.uint8)
+        print(f"{case}: oracle, edit {e}", flush=True)
+        want, blocks = osp.spade_pass(bufs, ops, P, seg64(segs[e]), storage=dtype, block=block, cache=cache,
+                                      stats=stats, mask=mask, dilate=1, min_sparse=min_sparse, trace=trace_e)
+        print(f"{case}: GPU, edit {e} under teacher forcing", flush=True)
         start = {n: a.copy() for n, a in cache.items()}
         t_e = SpadeTeacher(net, td, trace_e, start, stats=stats)
         t_e._force_buffers()                  # the GPU's caches = the oracle's, so that the edit's mask is the same
-        net.set_edit({k: v.cuda() for k, v in seg1.items()}, exact=True)
-        for (h, w), t in seg1.items():
+        net.set_edit({k: v.cuda() for k, v in segs[e].items()}, exact=True)
+        for (h, w), t in segs[e].items():
             if f"seg{h}" in t_e.state:
                 t_e.state[f"seg{h}"] = f64(t)
                 t_e.dirty.add(f"seg{h}")
         net.hook = t_e
-        net.step()
-        torch.cuda.synchronize()
-    finally:
-        net.hook = None
-    print(f"{case}: worst error / bound: pre-computation pass {t_d.rep.worst:.3f}, sparse step {t_e.rep.worst:.3f}")
-    t_d.rep.assert_clean(min_checked=50)
-    t_e.rep.assert_clean(min_checked=50)
-    n_few = 0
-    for n, L in net.layers.items():
-        if L["sparse"]:
-            bl = L["list"][1]
-            assert np.array_equal(bl.indices[:bl.n_host].cpu().numpy(), blocks[n]), n
-            n_few += 0 < bl.n_host < bl.g.grid_blocks
-    assert n_few >= (10 if case == "full" else 1)
+        try:
+            net.step()
+            torch.cuda.synchronize()
+        finally:
+            net.hook = None
+        print(f"{case}: worst error / bound, edit {e}: {t_e.rep.worst:.3f}")
+        t_e.rep.assert_clean(min_checked=50)
+        n_few = 0
+        for n, L in net.layers.items():
+            if L["sparse"]:
+                bl = L["list"][1]
+                assert np.array_equal(bl.indices[:bl.n_host].cpu().numpy(), blocks[n]), (e, n)
+                n_few += 0 < bl.n_host < bl.g.grid_blocks
+        assert n_few >= (10 if case == "full" else 1)
+        cache = want                          # the next edit starts from what this one left
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
